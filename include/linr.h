@@ -1,0 +1,187 @@
+/*
+ * linr.h -- C ABI of the MI355X-native exhaustive filtered top-k retrieval path
+ * (LiNR, arXiv 2407.13218: Sec. 3.1 "Exhaustive Search with Attribute-Based
+ * Matching").
+ *
+ * The library keeps an item index resident in GPU memory (Sec. 4.2: the corpus
+ * and its filter attributes live wholly on the device) and answers batches of
+ * queries: every item is scored against every query (Sec. 3.1.1), an item may
+ * enter a query's result only if it satisfies all of that query's clauses
+ * (Sec. 3.1.1 feasibility rule, applied as a pre-filter in the sense of
+ * Sec. 3.1.2), and the exact top-k of the feasible items is returned.
+ *
+ * Conventions for every entry point
+ *   - returns LINR_OK (0) or a negative LINR_E_* code; never aborts or throws;
+ *   - arguments are validated on the host before any device work is enqueued;
+ *     on error no output buffer has been touched;
+ *   - "device" pointers are HIP device memory of the index's GPU, "host"
+ *     pointers are ordinary process memory;
+ *   - linr_search_filtered only enqueues work on the caller's stream; results are
+ *     valid once that stream has been synchronised.  It allocates nothing.
+ */
+#ifndef LINR_H
+#define LINR_H
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct linr_index linr_index;       /* opaque; created/destroyed by the library */
+
+enum { LINR_F32 = 0, LINR_BF16 = 1, LINR_I8 = 2 };          /* element type of the index */
+
+enum {
+    LINR_OK = 0,
+    LINR_E_NULL = -1,        /* a required pointer is NULL                                 */
+    LINR_E_SHAPE = -2,       /* d / m / B / alignment not supported                        */
+    LINR_E_DTYPE = -3,       /* loader or query type does not match the index type         */
+    LINR_E_K = -4,           /* k == 0 or k > LINR_MAX_K                                   */
+    LINR_E_CAPACITY = -5,    /* n exceeds the capacity given at creation, or id space      */
+    LINR_E_NOT_LOADED = -6,  /* search on an index that holds no items yet                 */
+    LINR_E_WORKSPACE = -7,   /* workspace NULL, misaligned or smaller than required        */
+    LINR_E_HIP = -8,         /* a HIP runtime call failed (see linr_last_hip_error)        */
+    LINR_E_FILTER = -9       /* malformed filter (host filters only are checked)           */
+};
+
+/* where the loader's source arrays live and who owns the resident copy */
+enum {
+    LINR_SRC_HOST = 0,           /* host arrays, copied into library-owned device memory   */
+    LINR_SRC_DEVICE_COPY = 1,    /* device arrays, copied into library-owned device memory */
+    LINR_SRC_DEVICE_BORROW = 2   /* device arrays used in place; the caller keeps them
+                                    alive and unchanged for the life of the index          */
+};
+
+/* flags of linr_search_filtered */
+enum {
+    LINR_FILTERS_ON_DEVICE = 0,  /* default: `filters` is a device pointer                 */
+    LINR_FILTERS_ON_HOST = 1     /* `filters` is a host pointer: validated, then copied    */
+};
+
+#define LINR_MAX_ANY 4
+#define LINR_MAX_K   2048
+#define LINR_MAX_M   8
+#define LINR_NO_ID   0xFFFFFFFFu
+
+/*
+ * One query's predicate over an item's 32-bit attribute mask and optional
+ * 32-bit timestamp (40 bytes, plain data).  Sec. 3.1.1: an item is feasible iff
+ * every clause holds; a clause with several attributes holds if at least one of
+ * them is present; a reverse clause holds on mismatch.
+ *   all_bits  : union of the single-attribute clauses -- each bit must be set;
+ *   none_bits : reverse clauses -- none of these bits may be set;
+ *   any_bits[g], g < n_any : a multi-attribute clause -- at least one bit set;
+ *   ts_min..ts_max : inclusive unsigned window on the item timestamp, evaluated
+ *                    only when the index has a timestamp column.
+ * The all-zero filter with ts window (0, 0xFFFFFFFF) passes every item.
+ */
+typedef struct {
+    uint32_t all_bits;
+    uint32_t none_bits;
+    uint32_t any_bits[LINR_MAX_ANY];
+    uint32_t n_any;
+    uint32_t ts_min, ts_max;
+    uint32_t _pad;
+} linr_filter;
+
+/*
+ * Create an empty index for up to `capacity` items of `d` dimensions on HIP
+ * device `device`.  d * sizeof(element) must be a multiple of 16 and at most 512
+ * bytes.  capacity <= 2^32 - 2 (item ids are uint32 row numbers).
+ * The handle is owned by the library until linr_index_destroy.
+ */
+int linr_index_create(linr_index** out, uint64_t capacity, uint32_t d, int dtype, int device);
+
+/*
+ * Make `n` items resident (Sec. 4.2: embeddings plus filter attributes form the
+ * served model).  Row i of `emb` ([n][d], row-major, 16-byte aligned) becomes
+ * item id i.  `mask` is [n]; `ts` is [n] or NULL (no timestamp column).
+ * A later load replaces the previous contents.  `src` is a LINR_SRC_* value.
+ * bf16 values are passed as their 16-bit patterns.
+ * int8: symmetric codes with one positive fp32 scale per row; row_scale == NULL
+ * selects raw ranking (see linr_search_filtered).  This quantised layout is this
+ * library's memory-saving representation (the paper's own is the 1-bit code of
+ * Sec. 3.2); it keeps a 1e9 x 64 index at 72 GB.
+ */
+int linr_index_load_fp32(linr_index*, const float* emb, const uint32_t* mask, const uint32_t* ts,
+                         uint64_t n, int src);
+int linr_index_load_bf16(linr_index*, const uint16_t* emb, const uint32_t* mask, const uint32_t* ts,
+                         uint64_t n, int src);
+int linr_index_load_int8(linr_index*, const int8_t* emb, const float* row_scale, const uint32_t* mask,
+                         const uint32_t* ts, uint64_t n, int src);
+
+/* Bytes of device workspace linr_search_filtered needs for (B, m, k) on this index. */
+int linr_search_workspace_bytes(const linr_index*, uint32_t B, uint32_t m, uint32_t k, uint64_t* bytes);
+
+/*
+ * Exhaustive filtered top-k (Sec. 3.1.1 scoring, Sec. 3.1.2 pre-filter semantics,
+ * Sec. 5.3.2: each query of the batch has its own filter).
+ *
+ *   Q        device [B][m][d] of the index element type; m embeddings per query,
+ *            an item's score for the query is the maximum over the m dot products;
+ *   q_scale  device [B] or NULL (= 1.0f); int8 only;
+ *   filters  [B] linr_filter, device or host per `flags`;
+ *   out_ids  device [B][k]; out_scores device [B][k]; out_raw device [B][k] or NULL
+ *            (int8 only: the int32 dot product); out_counts device [B];
+ *   workspace  device, 256-byte aligned, >= linr_search_workspace_bytes; contents
+ *            need not be initialised and are garbage afterwards.  Two searches
+ *            that may overlap in time need separate workspaces;
+ *   hip_stream  a hipStream_t (NULL = the default stream).
+ *
+ * Ranking value of item i for query b:
+ *   fp32/bf16 : max_e <Q[b][e], emb[i]> accumulated in fp32;
+ *   int8, row_scale given : (float)raw * row_scale[i], raw = max_e int32 dot, one
+ *               round-to-nearest fp32 product; out_scores = that * q_scale[b];
+ *   int8, no row_scale    : raw itself; out_scores = (float)raw * q_scale[b].
+ * Row b of the outputs holds counts[b] = min(k, #feasible items) entries sorted by
+ * (ranking value descending, item id ascending); the tail is padded with
+ * LINR_NO_ID, -INFINITY and INT32_MIN.  Inputs must be finite.
+ * B == 0 is a no-op.  Errors: LINR_E_K, LINR_E_SHAPE (m == 0 or m > LINR_MAX_M),
+ * LINR_E_NOT_LOADED, LINR_E_WORKSPACE, LINR_E_NULL, LINR_E_FILTER (host filters:
+ * n_any > LINR_MAX_ANY, ts_min > ts_max), LINR_E_HIP.
+ */
+int linr_search_filtered(const linr_index*, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                         const linr_filter* filters, uint32_t k,
+                         uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
+                         void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags);
+
+int linr_index_destroy(linr_index*);
+
+/* number of items currently resident / element type / dimensions */
+int linr_index_info(const linr_index*, uint64_t* n, uint32_t* d, int* dtype, int* has_ts, int* has_row_scale);
+
+const char* linr_strerror(int code);
+/* hipError_t value of the last failing HIP call on this thread (0 if none) */
+int linr_last_hip_error(void);
+
+/*
+ * Launch-shape knobs for tests and tuning (process-wide; 0 = library default).
+ *   sample_ratio   : factor between the item counts of successive threshold-seeding
+ *                    sweeps (power of two >= 2);
+ *   min_sample     : smallest first sweep, in items;
+ *   blocks_per_cu  : persistent workgroups per compute unit for the scan;
+ *   max_levels     : upper bound on the number of sweeps (1 = single full sweep);
+ *   force_generic  : 1 = always use the kernel that streams queries from LDS.
+ */
+typedef struct {
+    uint32_t sample_ratio, min_sample, blocks_per_cu, max_levels, force_generic, _r0, _r1, _r2;
+} linr_tuning;
+int linr_set_tuning(const linr_tuning*);
+
+/*
+ * Per-stage timing of a search, for benchmarks.  When `events` is non-NULL the
+ * caller provides 2 * LINR_MAX_STAGES hipEvent_t created by the caller; stage s of
+ * the next search records events[2s] / events[2s+1] around its launch on the
+ * search stream.  *n_stages receives the number of stages, kinds[s] a LINR_STAGE_*.
+ */
+#define LINR_MAX_STAGES 24
+enum { LINR_STAGE_INIT = 0, LINR_STAGE_SCAN = 1, LINR_STAGE_MERGE = 2 };
+int linr_search_filtered_timed(const linr_index*, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                         const linr_filter* filters, uint32_t k,
+                         uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
+                         void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags,
+                         void** events, uint32_t* n_stages, uint32_t* kinds, uint64_t* stage_items);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

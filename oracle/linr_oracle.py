@@ -1,0 +1,123 @@
+"""ctypes loader for oracle/linr_oracle.c (plain C, built with gcc).
+
+TEST INFRASTRUCTURE: the product path never calls into this module.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+import numpy as np
+
+F32, BF16, I8 = 0, 1, 2
+NO_ID = 0xFFFFFFFF
+
+#: the oracle's own statement of the 40-byte filter record read by linr_oracle.c
+FILTER_DTYPE = np.dtype([
+    ("all_bits", "<u4"), ("none_bits", "<u4"), ("any_bits", "<u4", (4,)),
+    ("n_any", "<u4"), ("ts_min", "<u4"), ("ts_max", "<u4"), ("_pad", "<u4"),
+])
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "linr_oracle.c")
+_LIB = os.path.join(_HERE, "liblinr_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+                               "-o", tmp, _SRC, "-lpthread", "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = C.CDLL(_LIB)
+        vp, u64, u32, i32 = C.c_void_p, C.c_uint64, C.c_uint32, C.c_int
+        lib.linr_oracle_search.restype = i32
+        lib.linr_oracle_search.argtypes = [i32, vp, vp, vp, vp, u64, u32, u64, vp, vp, u32, u32, vp, u32,
+                                           vp, vp, vp, vp, i32]
+        lib.linr_oracle_pairs.restype = i32
+        lib.linr_oracle_pairs.argtypes = [i32, vp, vp, vp, vp, u32, vp, u32, vp, u64, vp, vp, vp, vp, vp]
+        lib.linr_oracle_dot_f64.restype = C.c_double
+        lib.linr_oracle_dot_f64.argtypes = [i32, vp, vp, u32]
+        lib.linr_oracle_pass.restype = i32
+        lib.linr_oracle_pass.argtypes = [vp, u32, i32, u32]
+        _lib = lib
+    return _lib
+
+
+_ELT = {F32: np.float32, BF16: np.uint16, I8: np.int8}
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _c(a, dt):
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a)
+    if a.dtype != dt:
+        raise TypeError(f"expected {dt}, got {a.dtype}")
+    return a
+
+
+def search(dtype, emb, mask, Q, filters, k, row_scale=None, ts=None, q_scale=None, id_base=0, nthreads=1):
+    """Exhaustive filtered top-k on the CPU.  emb [n,d]; Q [B,m,d] (or [B,d]); filters [B] records.
+    Returns ids [B,k] u32, scores [B,k] f32, raw [B,k] i32, counts [B] u32."""
+    lib = _load()
+    emb = _c(emb, _ELT[dtype]); Q = _c(Q, _ELT[dtype])
+    if Q.ndim == 2:
+        Q = Q[:, None, :]
+    n, d = emb.shape
+    B, m, d2 = Q.shape
+    assert d2 == d
+    mask = _c(mask, np.uint32); ts = _c(ts, np.uint32)
+    row_scale = _c(row_scale, np.float32); q_scale = _c(q_scale, np.float32)
+    filters = _c(filters, FILTER_DTYPE)
+    assert mask.shape == (n,) and filters.shape == (B,)
+    ids = np.empty((B, k), np.uint32); sc = np.empty((B, k), np.float32)
+    raw = np.empty((B, k), np.int32); cnt = np.empty(B, np.uint32)
+    rc = lib.linr_oracle_search(dtype, _ptr(emb), _ptr(row_scale), _ptr(mask), _ptr(ts), n, d, id_base,
+                                _ptr(Q), _ptr(q_scale), B, m, _ptr(filters), k,
+                                _ptr(ids), _ptr(sc), _ptr(raw), _ptr(cnt), nthreads)
+    if rc != 0:
+        raise RuntimeError(f"linr_oracle_search failed ({rc})")
+    return ids, sc, raw, cnt
+
+
+def pairs(dtype, emb, mask, Q, filters, pb, pi, row_scale=None, ts=None):
+    """Ranking value / raw dot / feasibility of listed (query, item) pairs."""
+    lib = _load()
+    emb = _c(emb, _ELT[dtype]); Q = _c(Q, _ELT[dtype])
+    if Q.ndim == 2:
+        Q = Q[:, None, :]
+    n, d = emb.shape
+    B, m, _ = Q.shape
+    mask = _c(mask, np.uint32); ts = _c(ts, np.uint32); row_scale = _c(row_scale, np.float32)
+    filters = _c(filters, FILTER_DTYPE)
+    pb = np.ascontiguousarray(pb, np.uint32); pi = np.ascontiguousarray(pi, np.uint64)
+    npairs = pb.shape[0]
+    rank = np.empty(npairs, np.float64); raw = np.empty(npairs, np.int32); feas = np.empty(npairs, np.uint8)
+    lib.linr_oracle_pairs(dtype, _ptr(emb), _ptr(row_scale), _ptr(mask), _ptr(ts), d, _ptr(Q), m, _ptr(filters),
+                          npairs, _ptr(pb), _ptr(pi), _ptr(rank), _ptr(raw), _ptr(feas))
+    return rank, raw, feas.astype(bool)
+
+
+def dot_f64(dtype, q, x):
+    lib = _load()
+    q = _c(q, _ELT[dtype]); x = _c(x, _ELT[dtype])
+    return lib.linr_oracle_dot_f64(dtype, _ptr(q), _ptr(x), q.shape[0])
+
+
+def passes(filt_record, mask, ts=None):
+    lib = _load()
+    f = np.ascontiguousarray(np.asarray(filt_record, dtype=FILTER_DTYPE).reshape(1))
+    return bool(lib.linr_oracle_pass(_ptr(f), int(mask), 0 if ts is None else 1, 0 if ts is None else int(ts)))
