@@ -168,10 +168,13 @@ typedef struct {
 int linr_set_tuning(const linr_tuning*);
 
 /*
- * Per-stage timing of a search, for benchmarks.  When `events` is non-NULL the
- * caller provides 2 * LINR_MAX_STAGES hipEvent_t created by the caller; stage s of
- * the next search records events[2s] / events[2s+1] around its launch on the
- * search stream.  *n_stages receives the number of stages, kinds[s] a LINR_STAGE_*.
+ * Per-stage timing of a search, for benchmarks (Sec. 5.3 reports latency per batch;
+ * this breaks one batch down by launch).  `events` holds 2 * LINR_MAX_STAGES
+ * hipEvent_t made by linr_events_create; stage s of this search records
+ * events[2s] / events[2s+1] around its launch on the search stream.  Nothing is
+ * synchronised: read the times with linr_events_elapsed_ms after the stream has
+ * finished.  *n_stages receives the number of stages, kinds[s] a LINR_STAGE_* value
+ * and stage_items[s] the number of items a scan stage visits.
  */
 #define LINR_MAX_STAGES 24
 enum { LINR_STAGE_INIT = 0, LINR_STAGE_SCAN = 1, LINR_STAGE_MERGE = 2 };
@@ -180,6 +183,11 @@ int linr_search_filtered_timed(const linr_index*, const void* Q, const float* q_
                          uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
                          void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags,
                          void** events, uint32_t* n_stages, uint32_t* kinds, uint64_t* stage_items);
+/* hipEvent_t helpers for callers without direct access to the HIP runtime (host arrays) */
+int linr_events_create(void** events, uint32_t n);
+int linr_events_destroy(void** events, uint32_t n);
+/* ms[i] = time from events[2i] to events[2i+1], i < n_pairs; the events must have completed */
+int linr_events_elapsed_ms(void** events, uint32_t n_pairs, float* ms);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,274 @@
+"""ctypes binding of include/linr.h -- argument marshalling only.
+
+The functions carry the names of the C entry points (without the `linr_` prefix) and
+take torch tensors (device memory) or numpy arrays (host memory); `Index` is a small
+convenience wrapper that allocates outputs and workspace with torch.  If the HIP
+library has not been built, loading fails loudly: nothing here computes on the CPU.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import numpy as np
+
+F32, BF16, I8 = 0, 1, 2
+NO_ID = 0xFFFFFFFF
+MAX_K = 2048
+MAX_M = 8
+SRC_HOST, SRC_DEVICE_COPY, SRC_DEVICE_BORROW = 0, 1, 2
+FILTERS_ON_DEVICE, FILTERS_ON_HOST = 0, 1
+MAX_STAGES = 24
+STAGE_NAMES = {0: "init", 1: "scan", 2: "merge"}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblinr.so")
+_lib = None
+
+#: every symbol include/linr.h declares
+EXPORTS = [
+    "linr_index_create", "linr_index_load_fp32", "linr_index_load_bf16", "linr_index_load_int8",
+    "linr_search_workspace_bytes", "linr_search_filtered", "linr_index_destroy", "linr_index_info",
+    "linr_strerror", "linr_last_hip_error", "linr_set_tuning", "linr_search_filtered_timed",
+    "linr_events_create", "linr_events_destroy", "linr_events_elapsed_ms",
+]
+
+
+class LinrError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = strerror(code)
+        if code == -8:
+            msg += f" (hipError_t {load_library().linr_last_hip_error()})"
+        super().__init__(f"{where}: {msg} [{code}]")
+
+
+class Tuning(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in ("sample_ratio", "min_sample", "blocks_per_cu", "max_levels",
+                                          "force_generic", "_r0", "_r1", "_r2")]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """dlopen the in-tree HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it first (python paper_2407_13218_amd/build.py "
+                          "or __graft_entry__.build()); there is no fallback path")
+    lib = C.CDLL(_LIB_PATH)
+    vp, u64, u32, i32 = C.c_void_p, C.c_uint64, C.c_uint32, C.c_int
+    lib.linr_index_create.restype = i32
+    lib.linr_index_create.argtypes = [C.POINTER(vp), u64, u32, i32, i32]
+    for name in ("linr_index_load_fp32", "linr_index_load_bf16"):
+        f = getattr(lib, name); f.restype = i32; f.argtypes = [vp, vp, vp, vp, u64, i32]
+    lib.linr_index_load_int8.restype = i32
+    lib.linr_index_load_int8.argtypes = [vp, vp, vp, vp, vp, u64, i32]
+    lib.linr_search_workspace_bytes.restype = i32
+    lib.linr_search_workspace_bytes.argtypes = [vp, u32, u32, u32, C.POINTER(u64)]
+    sargs = [vp, vp, vp, u32, u32, vp, u32, vp, vp, vp, vp, vp, u64, vp, u32]
+    lib.linr_search_filtered.restype = i32
+    lib.linr_search_filtered.argtypes = sargs
+    lib.linr_search_filtered_timed.restype = i32
+    lib.linr_search_filtered_timed.argtypes = sargs + [vp, C.POINTER(u32), vp, vp]
+    lib.linr_index_destroy.restype = i32
+    lib.linr_index_destroy.argtypes = [vp]
+    lib.linr_index_info.restype = i32
+    lib.linr_index_info.argtypes = [vp, C.POINTER(u64), C.POINTER(u32), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
+    lib.linr_strerror.restype = C.c_char_p
+    lib.linr_strerror.argtypes = [i32]
+    lib.linr_last_hip_error.restype = i32
+    lib.linr_last_hip_error.argtypes = []
+    lib.linr_set_tuning.restype = i32
+    lib.linr_set_tuning.argtypes = [vp]
+    lib.linr_events_create.restype = i32
+    lib.linr_events_create.argtypes = [vp, u32]
+    lib.linr_events_destroy.restype = i32
+    lib.linr_events_destroy.argtypes = [vp, u32]
+    lib.linr_events_elapsed_ms.restype = i32
+    lib.linr_events_elapsed_ms.argtypes = [vp, u32, vp]
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load_library().linr_strerror(code).decode()
+
+
+def _ptr(x):
+    """address of a torch tensor (device or host), a numpy array, or None"""
+    if x is None:
+        return None
+    if isinstance(x, np.ndarray):
+        if not x.flags["C_CONTIGUOUS"]:
+            raise ValueError("numpy argument must be C-contiguous")
+        return x.ctypes.data
+    if hasattr(x, "data_ptr"):
+        if not x.is_contiguous():
+            raise ValueError("tensor argument must be contiguous")
+        return x.data_ptr()
+    if isinstance(x, int):
+        return x
+    raise TypeError(type(x))
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise LinrError(rc, where)
+
+
+def index_create(capacity: int, d: int, dtype: int, device: int = 0) -> int:
+    h = C.c_void_p()
+    _check(load_library().linr_index_create(C.byref(h), capacity, d, dtype, device), "linr_index_create")
+    return h.value
+
+
+def index_load_fp32(ix, emb, mask, ts, n, src):
+    _check(load_library().linr_index_load_fp32(ix, _ptr(emb), _ptr(mask), _ptr(ts), n, src), "linr_index_load_fp32")
+
+
+def index_load_bf16(ix, emb, mask, ts, n, src):
+    _check(load_library().linr_index_load_bf16(ix, _ptr(emb), _ptr(mask), _ptr(ts), n, src), "linr_index_load_bf16")
+
+
+def index_load_int8(ix, emb, row_scale, mask, ts, n, src):
+    _check(load_library().linr_index_load_int8(ix, _ptr(emb), _ptr(row_scale), _ptr(mask), _ptr(ts), n, src),
+           "linr_index_load_int8")
+
+
+def index_info(ix):
+    n, d = C.c_uint64(), C.c_uint32()
+    dt, hts, hrs = C.c_int(), C.c_int(), C.c_int()
+    _check(load_library().linr_index_info(ix, C.byref(n), C.byref(d), C.byref(dt), C.byref(hts), C.byref(hrs)), "linr_index_info")
+    return dict(n=n.value, d=d.value, dtype=dt.value, has_ts=bool(hts.value), has_row_scale=bool(hrs.value))
+
+
+def index_destroy(ix):
+    _check(load_library().linr_index_destroy(ix), "linr_index_destroy")
+
+
+def search_workspace_bytes(ix, B, m, k) -> int:
+    out = C.c_uint64()
+    _check(load_library().linr_search_workspace_bytes(ix, B, m, k, C.byref(out)), "linr_search_workspace_bytes")
+    return out.value
+
+
+def search_filtered(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_raw, out_counts,
+                    workspace, workspace_bytes, stream=0, flags=FILTERS_ON_DEVICE):
+    _check(load_library().linr_search_filtered(ix, _ptr(Q), _ptr(q_scale), B, m, _ptr(filters), k, _ptr(out_ids),
+                                               _ptr(out_scores), _ptr(out_raw), _ptr(out_counts), _ptr(workspace),
+                                               workspace_bytes, stream, flags), "linr_search_filtered")
+
+
+def search_filtered_timed(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_raw, out_counts,
+                          workspace, workspace_bytes, stream, flags, events):
+    """`events`: ctypes array of 2*MAX_STAGES hipEvent_t.  Returns (kinds, items) per stage."""
+    ns = C.c_uint32()
+    kinds = (C.c_uint32 * MAX_STAGES)()
+    items = (C.c_uint64 * MAX_STAGES)()
+    _check(load_library().linr_search_filtered_timed(ix, _ptr(Q), _ptr(q_scale), B, m, _ptr(filters), k, _ptr(out_ids),
+                                                     _ptr(out_scores), _ptr(out_raw), _ptr(out_counts), _ptr(workspace),
+                                                     workspace_bytes, stream, flags, C.addressof(events), C.byref(ns),
+                                                     C.addressof(kinds), C.addressof(items)),
+           "linr_search_filtered_timed")
+    return [kinds[i] for i in range(ns.value)], [items[i] for i in range(ns.value)]
+
+
+def events_create(n: int):
+    """ctypes array of n hipEvent_t"""
+    ev = (C.c_void_p * n)()
+    _check(load_library().linr_events_create(C.addressof(ev), n), "linr_events_create")
+    return ev
+
+
+def events_destroy(ev):
+    _check(load_library().linr_events_destroy(C.addressof(ev), len(ev)), "linr_events_destroy")
+
+
+def events_elapsed_ms(ev, n_pairs: int):
+    ms = (C.c_float * n_pairs)()
+    _check(load_library().linr_events_elapsed_ms(C.addressof(ev), n_pairs, C.addressof(ms)), "linr_events_elapsed_ms")
+    return [ms[i] for i in range(n_pairs)]
+
+
+def set_tuning(**kw):
+    """set_tuning() restores the defaults."""
+    lib = load_library()
+    if not kw:
+        _check(lib.linr_set_tuning(None), "linr_set_tuning")
+        return
+    t = Tuning()
+    for key, v in kw.items():
+        setattr(t, key, int(v))
+    _check(lib.linr_set_tuning(C.addressof(t)), "linr_set_tuning")
+
+
+class Index:
+    """Owns a linr_index handle; torch provides device memory and the stream."""
+
+    def __init__(self, capacity: int, d: int, dtype: int, device: int = 0):
+        self.handle = index_create(capacity, d, dtype, device)
+        self.dtype, self.d, self.device = dtype, d, device
+        self._keep = None
+
+    def load(self, emb, mask, ts=None, row_scale=None, src=None):
+        host = isinstance(emb, np.ndarray)
+        if src is None:
+            src = SRC_HOST if host else SRC_DEVICE_BORROW
+        n = emb.shape[0]
+        if self.dtype == F32:
+            index_load_fp32(self.handle, emb, mask, ts, n, src)
+        elif self.dtype == BF16:
+            index_load_bf16(self.handle, emb, mask, ts, n, src)
+        else:
+            index_load_int8(self.handle, emb, row_scale, mask, ts, n, src)
+        self._keep = (emb, mask, ts, row_scale) if src == SRC_DEVICE_BORROW else None
+        self.n = n
+        return self
+
+    def workspace_bytes(self, B, m, k):
+        return search_workspace_bytes(self.handle, B, m, k)
+
+    def search(self, Q, filters, k, q_scale=None, workspace=None, want_raw=True):
+        """Q: device tensor [B, m, d] (or [B, d]); filters: numpy records (host) or a device uint8/int32
+        tensor of B*40 bytes.  Returns device tensors ids (int32 bits of uint32), scores, raw, counts."""
+        import torch
+        if Q.dim() == 2:
+            Q = Q.unsqueeze(1)
+        Q = Q.contiguous()
+        B, m, d = Q.shape
+        assert d == self.d
+        dev = Q.device
+        ids = torch.empty((B, k), dtype=torch.int32, device=dev)
+        scores = torch.empty((B, k), dtype=torch.float32, device=dev)
+        raw = torch.empty((B, k), dtype=torch.int32, device=dev) if (want_raw and self.dtype == I8) else None
+        counts = torch.empty((B,), dtype=torch.int32, device=dev)
+        if B == 0:
+            return ids, scores, raw, counts
+        nbytes = self.workspace_bytes(B, m, k)
+        if workspace is None or workspace.numel() < nbytes:
+            workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        if isinstance(filters, np.ndarray):
+            flags, f = FILTERS_ON_HOST, np.ascontiguousarray(filters)
+        else:
+            flags, f = FILTERS_ON_DEVICE, filters
+        stream = torch.cuda.current_stream(dev).cuda_stream
+        search_filtered(self.handle, Q, q_scale, B, m, f, k, ids, scores, raw, counts, workspace, workspace.numel(),
+                        stream, flags)
+        self._last_workspace = workspace
+        return ids, scores, raw, counts
+
+    def close(self):
+        if self.handle:
+            index_destroy(self.handle)
+            self.handle = None
+            self._keep = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,405 @@
+// Host side of the C ABI declared in include/linr.h: index object, argument
+// validation, launch planning and the enqueue sequence of one search.
+// (LiNR, arXiv 2407.13218: Sec. 4.2 -- the served model is the item embeddings plus
+// their filter attributes resident in GPU memory; Sec. 3.1 -- the search itself.)
+#include "linr_internal.h"
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+static thread_local int g_last_hip = 0;
+static linr_tuning g_tuning = {0, 0, 0, 0, 0, 0, 0, 0};
+
+#define HIP_TRY(expr)                                   \
+    do {                                                \
+        hipError_t e__ = (expr);                        \
+        if (e__ != hipSuccess) { g_last_hip = (int)e__; return LINR_E_HIP; } \
+    } while (0)
+
+extern "C" const char* linr_strerror(int code)
+{
+    switch (code) {
+    case LINR_OK: return "ok";
+    case LINR_E_NULL: return "required pointer is NULL";
+    case LINR_E_SHAPE: return "unsupported shape (d, m, B or alignment)";
+    case LINR_E_DTYPE: return "element type mismatch";
+    case LINR_E_K: return "k out of range";
+    case LINR_E_CAPACITY: return "item count exceeds capacity";
+    case LINR_E_NOT_LOADED: return "index holds no items";
+    case LINR_E_WORKSPACE: return "workspace missing, misaligned or too small";
+    case LINR_E_HIP: return "HIP runtime error";
+    case LINR_E_FILTER: return "malformed filter";
+    default: return "unknown error";
+    }
+}
+extern "C" int linr_last_hip_error(void) { return g_last_hip; }
+
+extern "C" int linr_set_tuning(const linr_tuning* t)
+{
+    if (!t) { memset(&g_tuning, 0, sizeof(g_tuning)); return LINR_OK; }
+    if (t->sample_ratio && (t->sample_ratio < 2 || (t->sample_ratio & (t->sample_ratio - 1)))) return LINR_E_SHAPE;
+    g_tuning = *t;
+    return LINR_OK;
+}
+
+static uint32_t elt_bytes(int dtype) { return dtype == LINR_F32 ? 4u : dtype == LINR_BF16 ? 2u : 1u; }
+
+extern "C" int linr_index_create(linr_index** out, uint64_t capacity, uint32_t d, int dtype, int device)
+{
+    if (!out) return LINR_E_NULL;
+    *out = nullptr;
+    if (dtype != LINR_F32 && dtype != LINR_BF16 && dtype != LINR_I8) return LINR_E_DTYPE;
+    if (d == 0) return LINR_E_SHAPE;
+    uint64_t rb = (uint64_t)d * elt_bytes(dtype);
+    if (rb % 16 != 0 || rb > 512) return LINR_E_SHAPE;
+    if (capacity == 0 || capacity > 0xFFFFFFFEull) return LINR_E_CAPACITY;
+    int ndev = 0;
+    HIP_TRY(hipGetDeviceCount(&ndev));
+    if (device < 0 || device >= ndev) return LINR_E_SHAPE;
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, device));
+    linr_index* ix = new (std::nothrow) linr_index();
+    if (!ix) return LINR_E_HIP;
+    memset(ix, 0, sizeof(*ix));
+    ix->device = device; ix->dtype = dtype; ix->d = d; ix->row_bytes = (uint32_t)rb;
+    ix->capacity = capacity; ix->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+    *out = ix;
+    return LINR_OK;
+}
+
+static void release_columns(linr_index* ix)
+{
+    if (ix->owned) {
+        if (ix->emb) (void)hipFree((void*)ix->emb);
+        if (ix->row_scale) (void)hipFree((void*)ix->row_scale);
+        if (ix->mask) (void)hipFree((void*)ix->mask);
+        if (ix->ts) (void)hipFree((void*)ix->ts);
+    }
+    ix->emb = nullptr; ix->row_scale = nullptr; ix->mask = nullptr; ix->ts = nullptr;
+    ix->owned = 0; ix->n = 0;
+}
+
+extern "C" int linr_index_destroy(linr_index* ix)
+{
+    if (!ix) return LINR_E_NULL;
+    int dev = 0;
+    bool have = hipGetDevice(&dev) == hipSuccess;
+    if (have) (void)hipSetDevice(ix->device);
+    release_columns(ix);
+    if (have) (void)hipSetDevice(dev);
+    delete ix;
+    return LINR_OK;
+}
+
+extern "C" int linr_index_info(const linr_index* ix, uint64_t* n, uint32_t* d, int* dtype, int* has_ts, int* has_row_scale)
+{
+    if (!ix) return LINR_E_NULL;
+    if (n) *n = ix->n;
+    if (d) *d = ix->d;
+    if (dtype) *dtype = ix->dtype;
+    if (has_ts) *has_ts = ix->ts != nullptr;
+    if (has_row_scale) *has_row_scale = ix->row_scale != nullptr;
+    return LINR_OK;
+}
+
+static int copy_column(const void** dst, const void* src, uint64_t bytes, int from_host)
+{
+    void* p = nullptr;
+    HIP_TRY(hipMalloc(&p, bytes ? bytes : 16));
+    hipError_t e = hipMemcpy(p, src, bytes, from_host ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice);
+    if (e != hipSuccess) { (void)hipFree(p); g_last_hip = (int)e; return LINR_E_HIP; }
+    *dst = p;
+    return LINR_OK;
+}
+
+static int load_common(linr_index* ix, int dtype, const void* emb, const float* row_scale, const uint32_t* mask,
+                       const uint32_t* ts, uint64_t n, int src)
+{
+    if (!ix) return LINR_E_NULL;
+    if (ix->dtype != dtype) return LINR_E_DTYPE;
+    if (!emb || !mask) return LINR_E_NULL;
+    if (n == 0 || n > ix->capacity) return LINR_E_CAPACITY;
+    if (src != LINR_SRC_HOST && src != LINR_SRC_DEVICE_COPY && src != LINR_SRC_DEVICE_BORROW) return LINR_E_SHAPE;
+    if (src == LINR_SRC_DEVICE_BORROW) {
+        if (((uintptr_t)emb | (uintptr_t)mask | (uintptr_t)ts | (uintptr_t)row_scale) & 15u) return LINR_E_SHAPE;
+    }
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipSetDevice(ix->device));
+    release_columns(ix);
+    int rc = LINR_OK;
+    if (src == LINR_SRC_DEVICE_BORROW) {
+        ix->emb = emb; ix->row_scale = row_scale; ix->mask = mask; ix->ts = ts; ix->owned = 0;
+    } else {
+        int fh = src == LINR_SRC_HOST;
+        ix->owned = 1;
+        rc = copy_column(&ix->emb, emb, n * ix->row_bytes, fh);
+        if (rc == LINR_OK) rc = copy_column((const void**)&ix->mask, mask, n * 4, fh);
+        if (rc == LINR_OK && ts) rc = copy_column((const void**)&ix->ts, ts, n * 4, fh);
+        if (rc == LINR_OK && row_scale) rc = copy_column((const void**)&ix->row_scale, row_scale, n * 4, fh);
+        if (rc != LINR_OK) release_columns(ix);
+    }
+    if (rc == LINR_OK) ix->n = n;
+    (void)hipSetDevice(dev);
+    return rc;
+}
+
+extern "C" int linr_index_load_fp32(linr_index* ix, const float* emb, const uint32_t* mask, const uint32_t* ts, uint64_t n, int src)
+{
+    return load_common(ix, LINR_F32, emb, nullptr, mask, ts, n, src);
+}
+extern "C" int linr_index_load_bf16(linr_index* ix, const uint16_t* emb, const uint32_t* mask, const uint32_t* ts, uint64_t n, int src)
+{
+    return load_common(ix, LINR_BF16, emb, nullptr, mask, ts, n, src);
+}
+extern "C" int linr_index_load_int8(linr_index* ix, const int8_t* emb, const float* row_scale, const uint32_t* mask,
+                                    const uint32_t* ts, uint64_t n, int src)
+{
+    return load_common(ix, LINR_I8, emb, row_scale, mask, ts, n, src);
+}
+
+// ---------------------------------------------------------------------------
+// planning
+// ---------------------------------------------------------------------------
+static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+// Choose kernel shape, grid and the sequence of threshold-seeding sweeps for a pass of
+// at most B queries.  Returns LINR_OK or LINR_E_SHAPE.
+static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, linr_plan* p)
+{
+    memset(p, 0, sizeof(*p));
+    if (m == 0 || m > LINR_MAX_M) return LINR_E_SHAPE;
+    p->vk = ix->dtype == LINR_I8 ? (ix->row_scale ? LINR_VK_I8_SCALED : LINR_VK_I8_RAW) : LINR_VK_FLOAT;
+    uint32_t ks = (ix->row_bytes + 63) / 64;
+    p->ks = ks <= 1 ? 1 : ks <= 2 ? 2 : ks <= 4 ? 4 : 8;
+    p->tpc = 8 / p->ks;
+    p->chunk_items = 16 * p->tpc;
+    const uint32_t nsg = (B + 15) / 16;
+    // smallest group count covering the batch for which a register-resident kernel exists,
+    // else the largest existing one (the batch is then split over several waves per chunk)
+    uint32_t qg = 0;
+    if (!g_tuning.force_generic)
+        for (uint32_t c = 1; c <= 16; c <<= 1) {
+            if (!linr_fast_variant_exists(ix->dtype, p->vk, p->ks, m, c)) continue;
+            qg = c;
+            if (c >= nsg) break;
+        }
+    uint32_t Bp;
+    if (qg) {
+        p->qg = qg;
+        p->generic = 0;
+        p->max_batch = LINR_MAX_NSPLIT * qg * 16;
+        Bp = B < p->max_batch ? B : p->max_batch;
+        p->nsplit = ((Bp + 15) / 16 + qg - 1) / qg;
+    } else {                                            // queries streamed from LDS
+        uint32_t groups = LINR_LDS_SCAN_MAX_FRAGS / (m * p->ks);
+        if (groups < 1) return LINR_E_SHAPE;
+        p->generic = 1;
+        p->max_batch = groups * 16;
+        Bp = B < p->max_batch ? B : p->max_batch;
+        p->qg = (Bp + 15) / 16;
+        p->nsplit = 1;
+    }
+    if (p->nsplit < 1) p->nsplit = 1;
+    uint32_t bpc = g_tuning.blocks_per_cu ? g_tuning.blocks_per_cu : 4;
+    if (bpc > 4) bpc = 4;                               // 4 x 38 KB of LDS per compute unit
+    if (p->generic) bpc = 1;                            // its query fragments take most of the LDS
+    p->n_chunks = (ix->n + p->chunk_items - 1) / p->chunk_items;
+    uint64_t waves_wanted = p->n_chunks * p->nsplit;
+    uint64_t grid = (uint64_t)ix->num_cu * bpc;
+    uint64_t grid_needed = (waves_wanted + LINR_WAVES_PER_BLOCK - 1) / LINR_WAVES_PER_BLOCK;
+    if (grid > grid_needed) grid = grid_needed;
+    if (grid < 1) grid = 1;
+    uint64_t nslots = grid * LINR_WAVES_PER_BLOCK / p->nsplit;
+    if (nslots < 1) {                                   // fewer waves than splits: one slot
+        grid = (p->nsplit + LINR_WAVES_PER_BLOCK - 1) / LINR_WAVES_PER_BLOCK;
+        nslots = 1;
+    }
+    if (nslots > LINR_MAX_SLOTS) nslots = LINR_MAX_SLOTS;
+    p->grid = (uint32_t)grid;
+    p->nslots = (uint32_t)nslots;
+    p->cap = (uint32_t)align_up((uint64_t)k + p->chunk_items, 64);
+
+    // sweeps: the last visits every chunk; each earlier one a 1/ratio subsample of the next
+    uint32_t ratio = g_tuning.sample_ratio ? g_tuning.sample_ratio : 32;
+    uint64_t min_sample = g_tuning.min_sample ? g_tuning.min_sample : (uint64_t)4 * k;
+    uint32_t max_levels = g_tuning.max_levels ? g_tuning.max_levels : LINR_MAX_LEVELS;
+    if (max_levels > LINR_MAX_LEVELS) max_levels = LINR_MAX_LEVELS;
+    uint32_t strides[LINR_MAX_LEVELS];
+    uint32_t nl = 0;
+    uint64_t s = 1;
+    strides[nl++] = 1;
+    while (nl < max_levels) {
+        uint64_t s2 = s * ratio;
+        uint64_t items = (p->n_chunks / s2) * p->chunk_items;
+        if (s2 > 0x40000000ull || items < min_sample) break;
+        strides[nl++] = (uint32_t)s2;
+        s = s2;
+    }
+    p->nlevels = nl;
+    for (uint32_t l = 0; l < nl; ++l) p->stride[l] = strides[nl - 1 - l];
+
+    uint64_t off = 0;
+    p->off_tau = off;      off = align_up(off + (uint64_t)Bp * 8, 256);
+    p->off_cnt = off;      off = align_up(off + (uint64_t)Bp * p->nslots * 4, 256);
+    p->off_filters = off;  off = align_up(off + (uint64_t)Bp * sizeof(linr_filter), 256);
+    p->off_seg = off;      off = align_up(off + (uint64_t)p->nslots * Bp * p->cap * 8, 256);
+    p->total_bytes = off;
+    return LINR_OK;
+}
+
+extern "C" int linr_search_workspace_bytes(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, uint64_t* bytes)
+{
+    if (!ix || !bytes) return LINR_E_NULL;
+    if (k == 0 || k > LINR_MAX_K) return LINR_E_K;
+    if (ix->n == 0) return LINR_E_NOT_LOADED;
+    if (B == 0) { *bytes = 256; return LINR_OK; }
+    linr_plan p;
+    int rc = make_plan(ix, B, m, k, &p);
+    if (rc != LINR_OK) return rc;
+    *bytes = p.total_bytes;
+    return LINR_OK;
+}
+
+// ---------------------------------------------------------------------------
+// search
+// ---------------------------------------------------------------------------
+static int search_impl(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                       const linr_filter* filters, uint32_t k, uint32_t* out_ids, float* out_scores, int32_t* out_raw,
+                       uint32_t* out_counts, void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags,
+                       void** events, uint32_t* n_stages, uint32_t* kinds, uint64_t* stage_items)
+{
+    if (n_stages) *n_stages = 0;
+    if (!ix) return LINR_E_NULL;
+    if (k == 0 || k > LINR_MAX_K) return LINR_E_K;
+    if (m == 0 || m > LINR_MAX_M) return LINR_E_SHAPE;
+    if (ix->n == 0 || !ix->emb) return LINR_E_NOT_LOADED;
+    if (B == 0) return LINR_OK;
+    if (!Q || !filters || !out_ids || !out_scores || !out_counts) return LINR_E_NULL;
+    if (((uintptr_t)Q) & 15u) return LINR_E_SHAPE;
+    linr_plan p;
+    int rc = make_plan(ix, B, m, k, &p);
+    if (rc != LINR_OK) return rc;
+    if (!workspace || (((uintptr_t)workspace) & 255u) || workspace_bytes < p.total_bytes) return LINR_E_WORKSPACE;
+    if (flags & LINR_FILTERS_ON_HOST) {
+        for (uint32_t b = 0; b < B; ++b) {
+            if (filters[b].n_any > LINR_MAX_ANY) return LINR_E_FILTER;
+            if (filters[b].ts_min > filters[b].ts_max) return LINR_E_FILTER;
+        }
+    }
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+    uint32_t stage = 0;
+    auto ev = [&](int which, int kind, uint64_t items) -> hipError_t {
+        if (!events || stage >= LINR_MAX_STAGES) return hipSuccess;
+        hipError_t e = hipEventRecord((hipEvent_t)events[2 * stage + which], st);
+        if (which == 1) {
+            if (kinds) kinds[stage] = (uint32_t)kind;
+            if (stage_items) stage_items[stage] = items;
+            ++stage;
+        }
+        return e;
+    };
+
+    for (uint32_t b0 = 0; b0 < B; b0 += p.max_batch) {
+        const uint32_t Bp = (B - b0) < p.max_batch ? (B - b0) : p.max_batch;
+        linr_plan pp = p;
+        if (Bp != (B < p.max_batch ? B : p.max_batch)) {      // ragged last pass: replan for its size
+            rc = make_plan(ix, Bp, m, k, &pp);
+            if (rc != LINR_OK) return rc;
+            if (pp.total_bytes > workspace_bytes) return LINR_E_WORKSPACE;
+        }
+        unsigned long long* tau = (unsigned long long*)(ws + pp.off_tau);
+        uint32_t* cnt = (uint32_t*)(ws + pp.off_cnt);
+        linr_filter* dfilt = (linr_filter*)(ws + pp.off_filters);
+        unsigned long long* seg = (unsigned long long*)(ws + pp.off_seg);
+        const linr_filter* use_filt = filters + b0;
+        if (flags & LINR_FILTERS_ON_HOST) {
+            HIP_TRY(hipMemcpyAsync(dfilt, filters + b0, (size_t)Bp * sizeof(linr_filter), hipMemcpyHostToDevice, st));
+            use_filt = dfilt;
+        }
+        HIP_TRY(ev(0, LINR_STAGE_INIT, 0));
+        HIP_TRY(linr_launch_init(tau, cnt, (uint64_t)Bp * pp.nslots, Bp, st));
+        HIP_TRY(ev(1, LINR_STAGE_INIT, 0));
+
+        linr_scan_args sa;
+        memset(&sa, 0, sizeof(sa));
+        sa.emb = ix->emb; sa.row_scale = ix->row_scale; sa.mask = ix->mask; sa.ts = ix->ts;
+        sa.n = ix->n; sa.row_bytes = ix->row_bytes;
+        sa.Q = (const char*)Q + (uint64_t)b0 * m * ix->row_bytes; sa.B = Bp; sa.m = m;
+        sa.filters = use_filt; sa.tau = tau; sa.cnt = cnt; sa.seg = seg;
+        sa.nslots = pp.nslots; sa.cap = pp.cap; sa.nsplit = pp.nsplit; sa.k = k;
+
+        linr_merge_args ma;
+        memset(&ma, 0, sizeof(ma));
+        ma.tau = tau; ma.cnt = cnt; ma.seg = seg; ma.nslots = pp.nslots; ma.cap = pp.cap; ma.B = Bp; ma.k = k;
+        ma.dtype = ix->dtype; ma.vk = pp.vk; ma.emb = ix->emb; ma.row_scale = ix->row_scale;
+        ma.row_bytes = ix->row_bytes; ma.d = ix->d; ma.Q = sa.Q; ma.q_scale = q_scale ? q_scale + b0 : nullptr; ma.m = m;
+        ma.out_ids = out_ids + (uint64_t)b0 * k; ma.out_scores = out_scores + (uint64_t)b0 * k;
+        ma.out_raw = out_raw ? out_raw + (uint64_t)b0 * k : nullptr; ma.out_counts = out_counts + b0;
+
+        for (uint32_t l = 0; l < pp.nlevels; ++l) {
+            sa.stride = pp.stride[l];
+            sa.n_level_chunks = (pp.n_chunks + sa.stride - 1) / sa.stride;
+            uint64_t items = sa.n_level_chunks * pp.chunk_items;
+            if (items > ix->n) items = ix->n;
+            HIP_TRY(ev(0, LINR_STAGE_SCAN, items));
+            HIP_TRY(linr_launch_scan(pp, ix->dtype, sa, st));
+            HIP_TRY(ev(1, LINR_STAGE_SCAN, items));
+            ma.final_level = (l + 1 == pp.nlevels);
+            HIP_TRY(ev(0, LINR_STAGE_MERGE, 0));
+            HIP_TRY(linr_launch_merge(ma, st));
+            HIP_TRY(ev(1, LINR_STAGE_MERGE, 0));
+        }
+    }
+    if (n_stages) *n_stages = stage;
+    return LINR_OK;
+}
+
+extern "C" int linr_search_filtered(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                                    const linr_filter* filters, uint32_t k, uint32_t* out_ids, float* out_scores,
+                                    int32_t* out_raw, uint32_t* out_counts, void* workspace, uint64_t workspace_bytes,
+                                    void* hip_stream, uint32_t flags)
+{
+    return search_impl(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_raw, out_counts, workspace,
+                       workspace_bytes, hip_stream, flags, nullptr, nullptr, nullptr, nullptr);
+}
+
+extern "C" int linr_search_filtered_timed(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                                          const linr_filter* filters, uint32_t k, uint32_t* out_ids, float* out_scores,
+                                          int32_t* out_raw, uint32_t* out_counts, void* workspace, uint64_t workspace_bytes,
+                                          void* hip_stream, uint32_t flags, void** events, uint32_t* n_stages,
+                                          uint32_t* kinds, uint64_t* stage_items)
+{
+    return search_impl(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_raw, out_counts, workspace,
+                       workspace_bytes, hip_stream, flags, events, n_stages, kinds, stage_items);
+}
+
+extern "C" int linr_events_create(void** events, uint32_t n)
+{
+    if (!events) return LINR_E_NULL;
+    for (uint32_t i = 0; i < n; ++i) events[i] = nullptr;
+    for (uint32_t i = 0; i < n; ++i) {
+        hipEvent_t e;
+        hipError_t rc = hipEventCreate(&e);
+        if (rc != hipSuccess) { g_last_hip = (int)rc; return LINR_E_HIP; }
+        events[i] = (void*)e;
+    }
+    return LINR_OK;
+}
+
+extern "C" int linr_events_destroy(void** events, uint32_t n)
+{
+    if (!events) return LINR_E_NULL;
+    for (uint32_t i = 0; i < n; ++i)
+        if (events[i]) { (void)hipEventDestroy((hipEvent_t)events[i]); events[i] = nullptr; }
+    return LINR_OK;
+}
+
+extern "C" int linr_events_elapsed_ms(void** events, uint32_t n_pairs, float* ms)
+{
+    if (!events || !ms) return LINR_E_NULL;
+    for (uint32_t i = 0; i < n_pairs; ++i)
+        HIP_TRY(hipEventElapsedTime(&ms[i], (hipEvent_t)events[2 * i], (hipEvent_t)events[2 * i + 1]));
+    return LINR_OK;
+}

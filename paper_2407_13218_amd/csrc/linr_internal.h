@@ -1,0 +1,84 @@
+// Internal declarations shared by the host-side C ABI (linr_api.cpp) and the HIP
+// kernels (linr_kernels.hip).  Not installed; the public interface is include/linr.h.
+#pragma once
+#include <stdint.h>
+#include <hip/hip_runtime.h>
+#include "linr.h"
+
+#define LINR_WAVES_PER_BLOCK 4
+#define LINR_MAX_LEVELS 8
+#define LINR_MAX_SLOTS 4096          // merge kernel keeps one prefix entry per slot in LDS
+#define LINR_MAX_NSPLIT 16
+
+// how the ranking value is held in the scan's accumulators
+enum { LINR_VK_FLOAT = 0,       // fp32 / bf16: fp32 accumulator is the ranking value
+       LINR_VK_I8_SCALED = 1,   // int8: (float)int32 * row_scale
+       LINR_VK_I8_RAW = 2 };    // int8: the int32 itself
+
+struct linr_index {
+    int device;
+    int dtype;
+    uint32_t d;
+    uint32_t row_bytes;
+    uint64_t capacity;
+    uint64_t n;
+    const void* emb;
+    const float* row_scale;
+    const uint32_t* mask;
+    const uint32_t* ts;
+    int owned;                  // library allocated the four columns
+    int num_cu;
+};
+
+// Launch plan of one search pass (at most max_batch queries).
+struct linr_plan {
+    int vk;                     // LINR_VK_*
+    uint32_t ks;                // 64-byte K-steps per row (1, 2, 4 or 8)
+    uint32_t tpc;               // 16-item tiles per chunk (8 / ks)
+    uint32_t chunk_items;       // 16 * tpc
+    uint32_t qg;                // 16-query groups held per wave
+    uint32_t nsplit;            // waves that share a chunk and split the query groups
+    uint32_t generic;           // 1 = queries streamed from LDS
+    uint32_t grid;              // workgroups of LINR_WAVES_PER_BLOCK waves
+    uint32_t nslots;            // chunk-slots = waves / nsplit
+    uint32_t cap;               // entries per (slot, query) candidate segment
+    uint32_t max_batch;         // queries per pass
+    uint32_t nlevels;
+    uint32_t stride[LINR_MAX_LEVELS];   // level l visits chunks c with c % stride[l] == 0; last is 1
+    uint64_t n_chunks;
+    // workspace layout (byte offsets)
+    uint64_t off_tau, off_cnt, off_filters, off_seg, total_bytes;
+};
+
+struct linr_scan_args {
+    const void* emb; const float* row_scale; const uint32_t* mask; const uint32_t* ts;
+    uint64_t n; uint32_t row_bytes;
+    const void* Q; uint32_t B; uint32_t m;
+    const linr_filter* filters;
+    unsigned long long* tau;     // [B] best-known lower bound of each query's k-th key (0 = none)
+    uint32_t* cnt;              // [B][nslots]
+    unsigned long long* seg;     // [nslots][B][cap]
+    uint32_t nslots, cap, nsplit, k;
+    uint64_t n_level_chunks; uint32_t stride;
+};
+
+struct linr_merge_args {
+    unsigned long long* tau; uint32_t* cnt; const unsigned long long* seg;
+    uint32_t nslots, cap, B, k;
+    int final_level;
+    // finalisation (final level only)
+    int dtype, vk;
+    const void* emb; const float* row_scale; uint32_t row_bytes, d;
+    const void* Q; const float* q_scale; uint32_t m;
+    uint32_t* out_ids; float* out_scores; int32_t* out_raw; uint32_t* out_counts;
+};
+
+// kernels' host launchers (linr_kernels.hip)
+hipError_t linr_launch_init(unsigned long long* tau, uint32_t* cnt, uint64_t n_cnt, uint32_t B, hipStream_t s);
+hipError_t linr_launch_scan(const linr_plan& p, int dtype, const linr_scan_args& a, hipStream_t s);
+hipError_t linr_launch_merge(const linr_merge_args& a, hipStream_t s);
+// 1 if a register-resident-query scan kernel exists for this shape
+int linr_fast_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg);
+// dynamic LDS bytes of the LDS-streamed scan kernel for a pass of B queries
+uint32_t linr_lds_scan_dynamic_bytes(uint32_t B, uint32_t m, uint32_t ks);
+#define LINR_LDS_SCAN_MAX_FRAGS 96   // 1 KB each, next to 38 KB of per-wave staging
