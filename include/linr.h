@@ -160,10 +160,12 @@ int linr_last_hip_error(void);
  *   min_sample     : smallest first sweep, in items;
  *   blocks_per_cu  : persistent workgroups per compute unit for the scan;
  *   max_levels     : upper bound on the number of sweeps (1 = single full sweep);
- *   force_generic  : 1 = always use the kernel that streams queries from LDS.
+ *   force_generic  : 1 = always use the kernel that streams queries from LDS;
+ *   max_qg         : cap on the 16-query groups one wave keeps in registers (larger
+ *                    batches are then split over several waves per chunk).
  */
 typedef struct {
-    uint32_t sample_ratio, min_sample, blocks_per_cu, max_levels, force_generic, _r0, _r1, _r2;
+    uint32_t sample_ratio, min_sample, blocks_per_cu, max_levels, force_generic, max_qg, _r1, _r2;
 } linr_tuning;
 int linr_set_tuning(const linr_tuning*);
 

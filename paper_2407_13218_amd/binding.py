@@ -44,7 +44,7 @@ class LinrError(RuntimeError):
 
 class Tuning(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in ("sample_ratio", "min_sample", "blocks_per_cu", "max_levels",
-                                          "force_generic", "_r0", "_r1", "_r2")]
+                                          "force_generic", "max_qg", "_r1", "_r2")]
 
 
 def lib_path() -> str:

@@ -21,6 +21,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-I" + os.path.join(ROOT, "include"),
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-mllvm", "-amdgpu-mfma-vgpr-form",     # matrix results straight into VGPRs (no AGPR copies)
            "-o", tmp] + SOURCES
     if verbose:
         cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")

@@ -179,7 +179,7 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
     // else the largest existing one (the batch is then split over several waves per chunk)
     uint32_t qg = 0;
     if (!g_tuning.force_generic)
-        for (uint32_t c = 1; c <= 16; c <<= 1) {
+        for (uint32_t c = 1; c <= (g_tuning.max_qg ? g_tuning.max_qg : 16u); c <<= 1) {
             if (!linr_fast_variant_exists(ix->dtype, p->vk, p->ks, m, c)) continue;
             qg = c;
             if (c >= nsg) break;
@@ -192,7 +192,9 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
         Bp = B < p->max_batch ? B : p->max_batch;
         p->nsplit = ((Bp + 15) / 16 + qg - 1) / qg;
     } else {                                            // queries streamed from LDS
-        uint32_t groups = LINR_LDS_SCAN_MAX_FRAGS / (m * p->ks);
+        // LDS of that kernel: 38 KB of chunk staging + per 16-query group m*ks KB of fragments
+        // and 704 bytes of bounds, compact filters and counters; 160 KB per workgroup
+        uint32_t groups = LINR_LDS_SCAN_BUDGET / (m * p->ks * 1024u + 704u);
         if (groups < 1) return LINR_E_SHAPE;
         p->generic = 1;
         p->max_batch = groups * 16;

@@ -81,4 +81,4 @@ hipError_t linr_launch_merge(const linr_merge_args& a, hipStream_t s);
 int linr_fast_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg);
 // dynamic LDS bytes of the LDS-streamed scan kernel for a pass of B queries
 uint32_t linr_lds_scan_dynamic_bytes(uint32_t B, uint32_t m, uint32_t ks);
-#define LINR_LDS_SCAN_MAX_FRAGS 96   // 1 KB each, next to 38 KB of per-wave staging
+#define LINR_LDS_SCAN_BUDGET 120000u  // bytes of dynamic LDS next to 38 KB of per-wave chunk staging

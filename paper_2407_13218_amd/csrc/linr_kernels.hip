@@ -185,11 +185,15 @@ __device__ __forceinline__ void wave_compact_segment(u64* base, uint32_t* cnt_p,
 // ---------------------------------------------------------------------------
 template <int VK, int KS>
 struct ChunkRegs {
-    v4i ra[8];
-    v4u rsc, rmk, rts;
+    v4i ra[8];                 // 8 KB of rows in MFMA operand layout
+    uint32_t rsc[2], rmk[2], rts[2];   // side columns of items lane and lane + 64 of the chunk
 };
 
 // Issue the loads of level chunk `lc` (8 KB of rows + side columns) into registers.
+// Fast path (whole chunk inside the index, rows exactly KS*64 bytes): one uniform base plus a
+// per-lane 32-bit offset.  General path: rows and side entries past the end of the index are read
+// from the last item instead (their candidates are discarded later by the `item < n` test) and
+// 16-byte pieces past the end of a short row read as zero.
 template <int VK, int KS>
 __device__ __forceinline__ void issue_chunk(ChunkRegs<VK, KS>& R, const linr_scan_args& A, u64 lc, int lane, bool has_ts)
 {
@@ -199,117 +203,214 @@ __device__ __forceinline__ void issue_chunk(ChunkRegs<VK, KS>& R, const linr_sca
     const char* embp = (const char*)A.emb;
     const uint32_t rb = A.row_bytes;
     const u64 item0 = lc * A.stride * CH;
-    if (item0 + CH <= A.n) {
+    if (item0 + CH <= A.n && rb == (uint32_t)KS * 64u) {
+        const char* cb = embp + item0 * (u64)(KS * 64);
+        const uint32_t lane_off = (uint32_t)row * (KS * 64) + (uint32_t)g4 * 16;
 #pragma unroll
         for (int t = 0; t < TPC; ++t)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                uint32_t off = ks * 64 + g4 * 16;
-                v4i z = {0, 0, 0, 0};
-                if (off < rb) z = __builtin_nontemporal_load((const v4i*)(embp + (item0 + t * 16 + row) * rb + off));
-                R.ra[t * KS + ks] = z;
+            for (int ks = 0; ks < KS; ++ks)
+                R.ra[t * KS + ks] = __builtin_nontemporal_load((const v4i*)(cb + (lane_off + (uint32_t)(t * 16 * KS * 64 + ks * 64))));
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            if (h * 64 < CH && lane < CH - h * 64) {
+                const u64 it = item0 + h * 64 + lane;
+                if (VK == LINR_VK_I8_SCALED) R.rsc[h] = __builtin_nontemporal_load((const uint32_t*)A.row_scale + it);
+                R.rmk[h] = __builtin_nontemporal_load(A.mask + it);
+                if (has_ts) R.rts[h] = __builtin_nontemporal_load(A.ts + it);
             }
-        if (lane < CH / 4) {
-            if (VK == LINR_VK_I8_SCALED) R.rsc = __builtin_nontemporal_load((const v4u*)(A.row_scale + item0 + 4 * lane));
-            R.rmk = __builtin_nontemporal_load((const v4u*)(A.mask + item0 + 4 * lane));
-            if (has_ts) R.rts = __builtin_nontemporal_load((const v4u*)(A.ts + item0 + 4 * lane));
         }
-    } else {                                     // ragged last chunk: rows past the end read as zero
+        return;
+    }
+    const u64 last = A.n - 1;
 #pragma unroll
-        for (int t = 0; t < TPC; ++t)
+    for (int t = 0; t < TPC; ++t) {
+        u64 it = item0 + t * 16 + row;
+        it = it < last ? it : last;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                uint32_t off = ks * 64 + g4 * 16;
-                u64 it = item0 + t * 16 + row;
-                v4i z = {0, 0, 0, 0};
-                if (off < rb && it < A.n) z = *(const v4i*)(embp + it * rb + off);
-                R.ra[t * KS + ks] = z;
-            }
-        if (lane < CH / 4) {
+        for (int ks = 0; ks < KS; ++ks) {
+            uint32_t off = ks * 64 + g4 * 16;
+            v4i z = {0, 0, 0, 0};
+            if (off < rb) z = *(const v4i*)(embp + it * rb + off);
+            R.ra[t * KS + ks] = z;
+        }
+    }
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                u64 it = item0 + 4 * lane + r;
-                bool in = it < A.n;
-                R.rsc[r] = (VK == LINR_VK_I8_SCALED && in) ? __float_as_uint(A.row_scale[it]) : 0u;
-                R.rmk[r] = in ? A.mask[it] : 0u;
-                R.rts[r] = (has_ts && in) ? A.ts[it] : 0u;
-            }
+    for (int h = 0; h < 2; ++h) {
+        if (h * 64 < CH && lane < CH - h * 64) {
+            u64 it = item0 + h * 64 + lane;
+            it = it < last ? it : last;
+            if (VK == LINR_VK_I8_SCALED) R.rsc[h] = ((const uint32_t*)A.row_scale)[it];
+            R.rmk[h] = A.mask[it];
+            if (has_ts) R.rts[h] = A.ts[it];
         }
     }
 }
 
-// registers -> this wave's LDS area; returns 0.999 / max(row scale of the chunk) for the scaled int8 path
-template <int VK, int KS>
+// registers -> this wave's LDS area; returns max(row scale of the chunk) when asked for
+template <int VK, int KS, bool WANT_SMAX>
 __device__ __forceinline__ float stage_chunk(const ChunkRegs<VK, KS>& R, WaveLds& L, int lane, bool has_ts)
 {
     constexpr int CH = 16 * (8 / KS);
-    float rinv = 0.0f;
-    if constexpr (VK == LINR_VK_I8_SCALED) {
-        float smax = 0.0f;
-        if (lane < CH / 4)
-            smax = fmaxf(fmaxf(__uint_as_float(R.rsc[0]), __uint_as_float(R.rsc[1])),
-                         fmaxf(__uint_as_float(R.rsc[2]), __uint_as_float(R.rsc[3])));
+    float smax = 0.0f;
+    if constexpr (WANT_SMAX) {
+        if (lane < CH) smax = __uint_as_float(R.rsc[0]);
+        if (CH > 64 && lane < CH - 64) smax = fmaxf(smax, __uint_as_float(R.rsc[1]));
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) smax = fmaxf(smax, __shfl_xor(smax, o));
-        rinv = 0.999f / smax;
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) L.a[j][lane] = R.ra[j];
-    if (lane < CH / 4) {
-        if (VK == LINR_VK_I8_SCALED) *(v4u*)&L.sc[4 * lane] = R.rsc;
-        *(v4u*)&L.mk[4 * lane] = R.rmk;
-        if (has_ts) *(v4u*)&L.ts[4 * lane] = R.rts;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        if (h * 64 < CH && lane < CH - h * 64) {
+            if (VK == LINR_VK_I8_SCALED) L.sc[h * 64 + lane] = __uint_as_float(R.rsc[h]);
+            L.mk[h * 64 + lane] = R.rmk[h];
+            if (has_ts) L.ts[h * 64 + lane] = R.rts[h];
+        }
     }
     wave_sync();
-    return rinv;
+    return smax;
 }
 
 // conservative integer form of "raw * row_scale >= thr" for a whole chunk (thr > 0 only)
-__device__ __forceinline__ int int_bound(float thr, float rinv)
+__device__ __forceinline__ int int_bound(float thr, float smax)
 {
-    float x = thr * rinv;
+    float x = thr * __builtin_amdgcn_rcpf(smax) * 0.999f;
     return (thr > 0.0f) ? ((x >= 2.0e9f) ? INT_MAX : (int)x) : INT_MIN;
 }
 
-// Stages A-C for the four items x one query a lane holds after the matrix product.
-//   A: cheap test on the maximum of the four accumulators (exact for float / raw int,
-//      conservative through `tint` for scaled int8);  B: exact ranking values against
-//      the query's bound;  C: attribute predicate of the survivors, key append.
-template <int VK, int CH, typename acc_t>
-__device__ __forceinline__ void tile_epilogue(const acc_t& acc, float thr_f, int thr_int, uint32_t qi, int ib, u64 item0,
-                                              const WaveLds& L, const linr_scan_args& A, uint32_t slot, bool has_ts,
-                                              bool& need_compact)
+// Scaled int8 rows of at most 256 dimensions: the accumulator starts at the bit pattern of
+// 1.5 * 2^23, so that (bits of accumulator) read as fp32 equal 12582912 + raw exactly
+// (|raw| < 2^22).  One fused multiply-add, fma(acc_as_float, scale, -(12582912 - 2) * scale), then
+// gives raw * scale + 2 * scale to within 0.75 * scale: never below the exact product for a
+// positive scale, and tight enough for the cheap first test (the bound it is compared with is
+// additionally lowered by 2^-14 relative).  The exact value is recomputed for survivors.
+#define LINR_MAGIC_BITS 0x4B400000
+#define LINR_MAGIC_F 12582912.0f
+#define LINR_MAGIC_U (12582912.0f - 2.0f)
+
+__device__ __forceinline__ float lowered(float thr)          // thr - 2^-14 |thr| (infinities unchanged)
 {
-    bool hot;
+    return (fabsf(thr) < 3.0e38f) ? thr - fabsf(thr) * 6.1035156e-5f : thr;
+}
+
+// Query-side state in LDS (pointers to arrays indexed by the wave-local query number).
+struct QSide {
+    uint32_t* cnt;          // entries appended so far to this wave's segment of the query (wave private)
+    float* thr_f;           // lower bound of the ranking value (float kinds)
+    int* thr_i;             // same for raw int8 ranking
+    const uint32_t* fall;   // filter: bits that must be set            } an item passes both iff
+    const uint32_t* fnone;  // filter: all_bits | none_bits (care mask)  } (mask & care) == must
+    const uint32_t* tsmin;  // filter: ts window
+    const uint32_t* tsmax;
+    const uint32_t* fflag;  // bit 0: the filter has any-of clauses (read the full record from global)
+};
+
+__device__ __forceinline__ void load_query_side(const QSide& qs, uint32_t ql, uint32_t qi, const linr_scan_args& A,
+                                                bool with_filter)
+{
+    float tf; int ti;
+    if (qi < A.B) {
+        u64 t = aload64(A.tau + qi);
+        uint32_t hi = (uint32_t)(t >> 32);
+        tf = t ? unord_f32(hi) : -INFINITY;
+        ti = t ? unord_i32(hi) : INT_MIN;
+    } else {
+        tf = INFINITY;
+        ti = INT_MAX;
+    }
+    qs.thr_f[ql] = tf;
+    qs.thr_i[ql] = ti;
+    if (with_filter) {
+        linr_filter F;
+        if (qi < A.B) F = A.filters[qi];
+        else { F.all_bits = 0xFFFFFFFFu; F.none_bits = 0xFFFFFFFFu; F.n_any = 0; F.ts_min = 1; F.ts_max = 0; }
+        const bool impossible = (F.all_bits & F.none_bits) != 0u;       // a bit both required and forbidden
+        ((uint32_t*)qs.fall)[ql] = impossible ? 0xFFFFFFFFu : F.all_bits;
+        ((uint32_t*)qs.fnone)[ql] = impossible ? 0u : (F.all_bits | F.none_bits);
+        ((uint32_t*)qs.tsmin)[ql] = F.ts_min;
+        ((uint32_t*)qs.tsmax)[ql] = F.ts_max;
+        ((uint32_t*)qs.fflag)[ql] = F.n_any ? 1u : 0u;
+    }
+}
+
+// Stage A for the four items x one query a lane holds after the matrix product: can any of
+// them still matter?  Exact for float / raw int.  Scaled int8: with MAGIC accumulators
+// fma(acc_as_float, scale, -MAGIC*scale) against a bound lowered by the rounding slack,
+// otherwise the conservative per-chunk integer bound.
+template <int VK, bool MAGIC, typename acc_t>
+__device__ __forceinline__ bool tile_hot(const acc_t& acc, float thr_f, int thr_int, const v4f& sc4, const v4f& u4)
+{
     if constexpr (VK == LINR_VK_FLOAT) {
         float mx = fmaxf(fmaxf(acc[0], acc[1]), fmaxf(acc[2], acc[3]));
-        hot = mx >= thr_f;
+        return mx >= thr_f;
+    } else if constexpr (VK == LINR_VK_I8_SCALED && MAGIC) {
+        float s0 = __builtin_fmaf(__int_as_float(acc[0]), sc4[0], -u4[0]);
+        float s1 = __builtin_fmaf(__int_as_float(acc[1]), sc4[1], -u4[1]);
+        float s2 = __builtin_fmaf(__int_as_float(acc[2]), sc4[2], -u4[2]);
+        float s3 = __builtin_fmaf(__int_as_float(acc[3]), sc4[3], -u4[3]);
+        float mx = fmaxf(fmaxf(s0, s1), fmaxf(s2, s3));
+        return mx >= thr_f;
     } else {
         int mx = max(max(acc[0], acc[1]), max(acc[2], acc[3]));
-        hot = mx >= thr_int;
+        return mx >= thr_int;
     }
-    if (!wave_any(hot)) return;
+}
 
+// Stage A with the bitmask / timestamp part of the predicate folded in (used when a wave holds few
+// query groups and the pass is HBM-bound, so the vector ALU has time for it): an item only counts
+// if it can pass its query's all/none bits and ts window.  Any-of clauses are left to stage C.
+template <int VK, bool MAGIC, bool TS, typename acc_t>
+__device__ __forceinline__ bool tile_hot_pred(const acc_t& acc, float thr_f, int thr_int, const v4f& sc4, const v4f& u4,
+                                              const v4u& mk4, const v4u& ts4, uint32_t fa, uint32_t fn, uint32_t t0, uint32_t t1)
+{
+    bool hot = false;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        bool feas = (mk4[r] & fn) == fa;
+        if constexpr (TS) feas = feas && (ts4[r] - t0) <= t1;          // t1 holds ts_max - ts_min here
+        bool above;
+        if constexpr (VK == LINR_VK_FLOAT) above = acc[r] >= thr_f;
+        else if constexpr (VK == LINR_VK_I8_SCALED && MAGIC)
+            above = __builtin_fmaf(__int_as_float(acc[r]), sc4[r], -u4[r]) >= thr_f;
+        else above = acc[r] >= thr_int;
+        hot = hot || (feas && above);
+    }
+    return hot;
+}
+
+// Stages B and C (rare): exact ranking values against the query's bound, then the attribute
+// predicate for the survivors and the key append to the wave's segment of that query.
+template <int VK, bool MAGIC, int CH, typename acc_t>
+__device__ __forceinline__ void tile_survivors(const acc_t& acc, const QSide& qs, uint32_t ql, uint32_t qi, int ib, u64 item0,
+                                               const WaveLds& L, const linr_scan_args& A, uint32_t slot, bool has_ts,
+                                               bool& need_compact)
+{
     uint32_t surv = 0;
     uint32_t hi[4];
     if constexpr (VK == LINR_VK_I8_SCALED) {
+        const float tf = qs.thr_f[ql];
         v4f sc4 = *(const v4f*)&L.sc[ib];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            float s = (float)acc[r] * sc4[r];
-            if (s >= thr_f) surv |= 1u << r;
+            int raw = MAGIC ? acc[r] - LINR_MAGIC_BITS : acc[r];
+            float s = (float)raw * sc4[r];
+            if (s >= tf) surv |= 1u << r;
             hi[r] = ord_f32(s);
         }
     } else if constexpr (VK == LINR_VK_FLOAT) {
+        const float tf = qs.thr_f[ql];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            if (acc[r] >= thr_f) surv |= 1u << r;
+            if (acc[r] >= tf) surv |= 1u << r;
             hi[r] = ord_f32(acc[r]);
         }
     } else {
+        const int ti = qs.thr_i[ql];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            if (acc[r] >= thr_int) surv |= 1u << r;
+            if (acc[r] >= ti) surv |= 1u << r;
             hi[r] = ord_i32(acc[r]);
         }
     }
@@ -320,15 +421,20 @@ __device__ __forceinline__ void tile_epilogue(const acc_t& acc, float thr_f, int
     v4u ts4 = {0, 0, 0, 0};
     if (has_ts) ts4 = *(const v4u*)&L.ts[ib];
     if (surv) {
-        const linr_filter F = A.filters[qi];
-        uint32_t* cnt_p = A.cnt + (u64)qi * A.nslots + slot;
+        const uint32_t fa = qs.fall[ql], fn = qs.fnone[ql];
+        const bool complex = (qs.fflag[ql] & 1u) != 0u;
+        uint32_t t0 = 0u, t1 = 0xFFFFFFFFu;
+        if (has_ts) { t0 = qs.tsmin[ql]; t1 = qs.tsmax[ql]; }
         u64* seg_p = A.seg + ((u64)slot * A.B + qi) * A.cap;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            u64 item = item0 + ib + r;
-            if (((surv >> r) & 1u) && item < A.n && filter_pass(F, mk4[r], has_ts, ts4[r])) {
+            const u64 item = item0 + ib + r;
+            const uint32_t mk = mk4[r];
+            bool ok = ((surv >> r) & 1u) && item < A.n && ((mk & fn) == fa) && (ts4[r] >= t0) && (ts4[r] <= t1);
+            if (ok && complex) ok = filter_pass(A.filters[qi], mk, has_ts, ts4[r]);
+            if (ok) {
                 u64 key = ((u64)hi[r] << 32) | (u64)(uint32_t)~(uint32_t)item;
-                uint32_t pos = atomicAdd(cnt_p, 1u);
+                uint32_t pos = atomicAdd(&qs.cnt[ql], 1u);
                 if (pos < A.cap) seg_p[pos] = key;
                 if (pos + 1 + CH > A.cap) need_compact = true;
             }
@@ -336,39 +442,26 @@ __device__ __forceinline__ void tile_epilogue(const acc_t& acc, float thr_f, int
     }
 }
 
-// Rare: some segment of this wave (queries q_first .. q_first+nq) is nearly full.
+// Rare: some segment of this wave (wave-local queries 0 .. nq) is nearly full.
 template <int CH>
-__device__ __forceinline__ void compact_full_segments(const linr_scan_args& A, uint32_t slot, uint32_t q_first, uint32_t nq,
-                                                   uint32_t* hist, int lane)
+__device__ __forceinline__ void compact_full_segments(const linr_scan_args& A, const QSide& qs, uint32_t slot, uint32_t q_first,
+                                                      uint32_t nq, uint32_t* hist, int lane)
 {
     __threadfence();
     for (uint32_t q0 = 0; q0 < nq; q0 += 64) {
-        uint32_t qi = q_first + q0 + lane;
+        uint32_t ql = q0 + lane;
         uint32_t c = 0;
-        if (q0 + lane < nq && qi < A.B) c = aload32(A.cnt + (u64)qi * A.nslots + slot);
+        if (ql < nq && q_first + ql < A.B) c = qs.cnt[ql];
         u64 todo = __ballot(c + CH > A.cap);
         while (todo) {
             int src = __ffsll((long long)todo) - 1;
             todo &= todo - 1;
-            uint32_t qsel = q_first + q0 + src;
+            uint32_t lsel = q0 + src;
+            uint32_t qsel = q_first + lsel;
             uint32_t csel = __shfl(c, src);
             if (csel > A.cap) csel = A.cap;
-            wave_compact_segment(A.seg + ((u64)slot * A.B + qsel) * A.cap, A.cnt + (u64)qsel * A.nslots + slot,
-                                 A.tau + qsel, csel, A.k, hist, lane);
+            wave_compact_segment(A.seg + ((u64)slot * A.B + qsel) * A.cap, &qs.cnt[lsel], A.tau + qsel, csel, A.k, hist, lane);
         }
-    }
-}
-
-__device__ __forceinline__ void bound_of(const u64* tau, uint32_t qi, uint32_t B, float& tf, int& ti)
-{
-    if (qi < B) {
-        u64 t = aload64(tau + qi);
-        uint32_t hi = (uint32_t)(t >> 32);
-        tf = t ? unord_f32(hi) : -INFINITY;
-        ti = t ? unord_i32(hi) : INT_MIN;
-    } else {
-        tf = INFINITY;
-        ti = INT_MAX;
     }
 }
 
@@ -380,21 +473,37 @@ __device__ __forceinline__ void bound_of(const u64* tau, uint32_t qi, uint32_t B
 // [split*QG, split*QG+QG); slot s visits level chunks s, s+nslots, ...  No block
 // barrier is used, so waves are fully independent.
 // ---------------------------------------------------------------------------
-template <int DT, int VK, int KS, int M, int QG>
-__global__ void __launch_bounds__(64 * WPB) scan_kernel(linr_scan_args A)
+template <int QG>
+struct WaveQ {
+    uint32_t cnt[QG * 16];
+    float thr_f[QG * 16];
+    int thr_i[QG * 16];
+    uint32_t fall[QG * 16], fnone[QG * 16], tsmin[QG * 16], tsmax[QG * 16], fflag[QG * 16];
+};
+
+template <int DT, int VK, int KS, int M, int QG, bool TS>
+__global__ void __launch_bounds__(64 * WPB, (QG * M * KS <= 1 ? 4 : QG * M * KS <= 4 ? 3 : QG * M * KS <= 8 ? 2 : 1))
+scan_kernel(linr_scan_args A)
 {
     constexpr int TPC = 8 / KS;
     constexpr int CH = 16 * TPC;
+    constexpr int NQ = QG * 16;
+    constexpr bool MAGIC = (VK == LINR_VK_I8_SCALED) && (KS * 64 <= 256);
+    constexpr bool PRED_A = QG <= 2;           // evaluate all/none bits + ts window already in stage A
     using acc_t = typename AccOf<DT>::type;
 
     __shared__ WaveLds lds_all[WPB];
+    __shared__ WaveQ<QG> wq_all[WPB];
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
     WaveLds& L = lds_all[wib];
+    WaveQ<QG>& W = wq_all[wib];
+    const QSide qs = {W.cnt, W.thr_f, W.thr_i, W.fall, W.fnone, W.tsmin, W.tsmax, W.fflag};
     const int row = lane & 15, g4 = lane >> 4;
     const uint32_t gw = blockIdx.x * WPB + wib;
     const uint32_t split = gw % A.nsplit, slot = gw / A.nsplit;
     if (slot >= A.nslots) return;
     const uint32_t sg0 = split * QG;
+    const uint32_t q_first = sg0 * 16;
     const bool has_ts = A.ts != nullptr;
     const uint32_t rb = A.row_bytes;
 
@@ -415,25 +524,45 @@ __global__ void __launch_bounds__(64 * WPB) scan_kernel(linr_scan_args A)
             }
     }
 
-    // ---- per-query lower bounds (lane l tracks query row l%16 of each group)
-    float thr_f[QG];
+    // ---- query-side state: segment counters, bounds, compact filters
+    for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) {
+        W.cnt[ql] = 0;
+        load_query_side(qs, ql, q_first + ql, A, true);
+    }
+    wave_sync();
+    float thr_f[QG], thr_lo[QG];          // lane l tracks query row l%16 of each group
     int thr_i[QG];
 #pragma unroll
-    for (int i = 0; i < QG; ++i) bound_of(A.tau, (sg0 + i) * 16 + row, A.B, thr_f[i], thr_i[i]);
+    for (int i = 0; i < QG; ++i) {
+        thr_f[i] = W.thr_f[i * 16 + row]; thr_i[i] = W.thr_i[i * 16 + row]; thr_lo[i] = lowered(thr_f[i]);
+    }
+    uint32_t f_all[QG], f_none[QG], f_t0[QG], f_t1[QG];
+#pragma unroll
+    for (int i = 0; i < QG; ++i) {
+        f_all[i] = W.fall[i * 16 + row]; f_none[i] = W.fnone[i * 16 + row];
+        f_t0[i] = W.tsmin[i * 16 + row]; f_t1[i] = W.tsmax[i * 16 + row] - f_t0[i];     // window as (start, length)
+        if (W.tsmax[i * 16 + row] < W.tsmin[i * 16 + row]) { f_all[i] = 0xFFFFFFFFu; f_none[i] = 0u; }   // empty window
+    }
 
     ChunkRegs<VK, KS> R;
-    R.rsc = (v4u){0, 0, 0, 0}; R.rmk = (v4u){0, 0, 0, 0}; R.rts = (v4u){0, 0, 0, 0};
+    R.rsc[0] = R.rsc[1] = R.rmk[0] = R.rmk[1] = R.rts[0] = R.rts[1] = 0u;
     bool need_compact = false;
     uint32_t since_refresh = 0;
     u64 lc = slot;
     if (lc < A.n_level_chunks) issue_chunk<VK, KS>(R, A, lc, lane, has_ts);
+    const acc_t acc0 = MAGIC ? (acc_t){LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS} : (acc_t){0, 0, 0, 0};
 
     while (lc < A.n_level_chunks) {
         const u64 item0 = lc * A.stride * CH;
-        const float rinv = stage_chunk<VK, KS>(R, L, lane, has_ts);
-        int tcmp[QG];
+        const float smax = stage_chunk<VK, KS, (VK == LINR_VK_I8_SCALED && !MAGIC)>(R, L, lane, has_ts);
+        // bounds in the form stage A compares against
+        float tcf[QG];
+        int tci[QG];
 #pragma unroll
-        for (int i = 0; i < QG; ++i) tcmp[i] = (VK == LINR_VK_I8_SCALED) ? int_bound(thr_f[i], rinv) : thr_i[i];
+        for (int i = 0; i < QG; ++i) {
+            tcf[i] = (VK == LINR_VK_I8_SCALED && MAGIC) ? thr_lo[i] : thr_f[i];
+            tci[i] = (VK == LINR_VK_I8_SCALED && !MAGIC) ? int_bound(thr_f[i], smax) : thr_i[i];
+        }
 
         const u64 nlc = lc + A.nslots;
         if (nlc < A.n_level_chunks) issue_chunk<VK, KS>(R, A, nlc, lane, has_ts);     // in flight while scoring
@@ -444,49 +573,89 @@ __global__ void __launch_bounds__(64 * WPB) scan_kernel(linr_scan_args A)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) a[ks] = L.a[t * KS + ks][lane];
             const int ib = t * 16 + 4 * g4;              // first of this lane's four items in the chunk
+            v4f sc4 = {0, 0, 0, 0}, u4 = {0, 0, 0, 0};
+            if constexpr (MAGIC) {
+                sc4 = *(const v4f*)&L.sc[ib];
+                u4 = sc4 * LINR_MAGIC_U;
+            }
+            v4u mk4 = {0, 0, 0, 0}, ts4 = {0, 0, 0, 0};
+            if constexpr (PRED_A) {
+                mk4 = *(const v4u*)&L.mk[ib];
+                if constexpr (TS) ts4 = *(const v4u*)&L.ts[ib];
+            }
+            // all matrix products of the tile first, then one branch-free pass of stage A over the groups
+            acc_t acc[QG];
 #pragma unroll
             for (int i = 0; i < QG; ++i) {
-                acc_t acc;
 #pragma unroll
                 for (int e = 0; e < M; ++e) {
-                    acc_t tmp = {0, 0, 0, 0};
+                    acc_t tmp = acc0;
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) tmp = mfma_kstep<DT>(a[ks], q[i][e][ks], tmp);
-                    if (e == 0) acc = tmp;
+                    if (e == 0) acc[i] = tmp;
                     else {
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) acc[r] = acc[r] > tmp[r] ? acc[r] : tmp[r];
+                        for (int r = 0; r < 4; ++r) acc[i][r] = acc[i][r] > tmp[r] ? acc[i][r] : tmp[r];
                     }
                 }
-                tile_epilogue<VK, CH>(acc, thr_f[i], tcmp[i], (sg0 + i) * 16 + row, ib, item0, L, A, slot, has_ts, need_compact);
+            }
+            u64 hot[QG];
+            u64 any_hot = 0;
+#pragma unroll
+            for (int i = 0; i < QG; ++i) {
+                if constexpr (PRED_A)
+                    hot[i] = __ballot(tile_hot_pred<VK, MAGIC, TS>(acc[i], tcf[i], tci[i], sc4, u4, mk4, ts4, f_all[i], f_none[i],
+                                                                   f_t0[i], f_t1[i]));
+                else
+                    hot[i] = __ballot(tile_hot<VK, MAGIC>(acc[i], tcf[i], tci[i], sc4, u4));
+                any_hot |= hot[i];
+            }
+            if (any_hot) {
+#pragma unroll
+                for (int i = 0; i < QG; ++i)
+                    if (hot[i])
+                        tile_survivors<VK, MAGIC, CH>(acc[i], qs, i * 16 + row, q_first + i * 16 + row, ib, item0, L, A, slot,
+                                                      has_ts, need_compact);
             }
         }
         wave_sync();
 
+        bool refresh = ++since_refresh >= 16;
         if (wave_any(need_compact)) {
-            compact_full_segments<CH>(A, slot, sg0 * 16, QG * 16, (uint32_t*)&L.a[0][0], lane);
+            compact_full_segments<CH>(A, qs, slot, q_first, NQ, (uint32_t*)&L.a[0][0], lane);
             need_compact = false;
-            since_refresh = 16;
+            refresh = true;
         }
-        if (++since_refresh >= 16) {
+        if (refresh) {
+            for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) load_query_side(qs, ql, q_first + ql, A, false);
+            wave_sync();
 #pragma unroll
-            for (int i = 0; i < QG; ++i) bound_of(A.tau, (sg0 + i) * 16 + row, A.B, thr_f[i], thr_i[i]);
+            for (int i = 0; i < QG; ++i) {
+                thr_f[i] = W.thr_f[i * 16 + row]; thr_i[i] = W.thr_i[i * 16 + row]; thr_lo[i] = lowered(thr_f[i]);
+            }
             since_refresh = 0;
         }
         lc = nlc;
     }
+    // publish this wave's segment sizes
+    for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) {
+        uint32_t qi = q_first + ql;
+        if (qi < A.B) A.cnt[(u64)qi * A.nslots + slot] = W.cnt[ql];
+    }
 }
 
 // ---------------------------------------------------------------------------
-// scan kernel, query fragments and bounds streamed from LDS: any m, any number of
-// query groups (up to the LDS budget the host plans for); one chunk-slot per wave.
-// Dynamic LDS: [n_frag][64] v4i fragments, then [nsg*16] float and int bounds.
+// scan kernel, query fragments and query-side state streamed from LDS: any m, any
+// number of query groups (up to the LDS budget the host plans for); one chunk-slot per
+// wave.  Dynamic LDS: [n_frag][64] v4i fragments, 7 workgroup-shared arrays of nq16
+// words (bounds, compact filters), then one counter array of nq16 words per wave.
 // ---------------------------------------------------------------------------
 template <int DT, int VK, int KS>
 __global__ void __launch_bounds__(64 * WPB) scan_kernel_lds(linr_scan_args A)
 {
     constexpr int TPC = 8 / KS;
     constexpr int CH = 16 * TPC;
+    constexpr bool MAGIC = (VK == LINR_VK_I8_SCALED) && (KS * 64 <= 256);
     using acc_t = typename AccOf<DT>::type;
 
     __shared__ WaveLds lds_all[WPB];
@@ -497,11 +666,12 @@ __global__ void __launch_bounds__(64 * WPB) scan_kernel_lds(linr_scan_args A)
     const uint32_t slot = blockIdx.x * WPB + wib;
     const bool has_ts = A.ts != nullptr;
     const uint32_t rb = A.row_bytes;
-    const uint32_t nsg = (A.B + 15) / 16, m = A.m;
+    const uint32_t nsg = (A.B + 15) / 16, m = A.m, nq16 = nsg * 16;
     const uint32_t nfrag = nsg * m * KS;
     v4i* qf = dyn_lds;
-    float* bf = (float*)(dyn_lds + (size_t)nfrag * 64);
-    int* bi = (int*)(bf + nsg * 16);
+    uint32_t* words = (uint32_t*)(dyn_lds + (size_t)nfrag * 64);
+    const QSide qs = {words + 7 * nq16 + wib * nq16, (float*)words, (int*)(words + nq16), words + 2 * nq16, words + 3 * nq16,
+                      words + 4 * nq16, words + 5 * nq16, words + 6 * nq16};
 
     for (uint32_t f = wib; f < nfrag; f += WPB) {
         uint32_t ks = f % KS, e = (f / KS) % m, sg = f / (KS * m);
@@ -510,19 +680,21 @@ __global__ void __launch_bounds__(64 * WPB) scan_kernel_lds(linr_scan_args A)
         if (qi < A.B && off < rb) z = *(const v4i*)((const char*)A.Q + ((u64)qi * m + e) * rb + off);
         qf[(size_t)f * 64 + lane] = z;
     }
-    for (uint32_t qi = threadIdx.x; qi < nsg * 16; qi += 64 * WPB) bound_of(A.tau, qi, A.B, bf[qi], bi[qi]);
+    for (uint32_t ql = threadIdx.x; ql < nq16; ql += 64 * WPB) load_query_side(qs, ql, ql, A, true);
+    for (uint32_t ql = lane; ql < nq16; ql += 64) qs.cnt[ql] = 0;
     __syncthreads();
     if (slot >= A.nslots) return;
 
     ChunkRegs<VK, KS> R;
-    R.rsc = (v4u){0, 0, 0, 0}; R.rmk = (v4u){0, 0, 0, 0}; R.rts = (v4u){0, 0, 0, 0};
+    R.rsc[0] = R.rsc[1] = R.rmk[0] = R.rmk[1] = R.rts[0] = R.rts[1] = 0u;
     bool need_compact = false;
     u64 lc = slot;
     if (lc < A.n_level_chunks) issue_chunk<VK, KS>(R, A, lc, lane, has_ts);
+    const acc_t acc0 = MAGIC ? (acc_t){LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS} : (acc_t){0, 0, 0, 0};
 
     while (lc < A.n_level_chunks) {
         const u64 item0 = lc * A.stride * CH;
-        const float rinv = stage_chunk<VK, KS>(R, L, lane, has_ts);
+        const float smax = stage_chunk<VK, KS, (VK == LINR_VK_I8_SCALED && !MAGIC)>(R, L, lane, has_ts);
         const u64 nlc = lc + A.nslots;
         if (nlc < A.n_level_chunks) issue_chunk<VK, KS>(R, A, nlc, lane, has_ts);
 
@@ -532,12 +704,17 @@ __global__ void __launch_bounds__(64 * WPB) scan_kernel_lds(linr_scan_args A)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) a[ks] = L.a[t * KS + ks][lane];
             const int ib = t * 16 + 4 * g4;
+            v4f sc4 = {0, 0, 0, 0}, u4 = {0, 0, 0, 0};
+            if constexpr (MAGIC) {
+                sc4 = *(const v4f*)&L.sc[ib];
+                u4 = sc4 * LINR_MAGIC_U;
+            }
 #pragma unroll 1
             for (uint32_t sg = 0; sg < nsg; ++sg) {
                 acc_t acc;
 #pragma unroll 1
                 for (uint32_t e = 0; e < m; ++e) {
-                    acc_t tmp = {0, 0, 0, 0};
+                    acc_t tmp = acc0;
                     const v4i* qp = qf + ((size_t)(sg * m + e) * KS) * 64 + lane;
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) tmp = mfma_kstep<DT>(a[ks], qp[ks * 64], tmp);
@@ -548,22 +725,29 @@ __global__ void __launch_bounds__(64 * WPB) scan_kernel_lds(linr_scan_args A)
                     }
                 }
                 const uint32_t qi = sg * 16 + row;
-                const float tf = bf[qi];
-                const int tc = (VK == LINR_VK_I8_SCALED) ? int_bound(tf, rinv) : bi[qi];
-                tile_epilogue<VK, CH>(acc, tf, tc, qi, ib, item0, L, A, slot, has_ts, need_compact);
+                float tf = qs.thr_f[qi];
+                int tc = qs.thr_i[qi];
+                if constexpr (VK == LINR_VK_I8_SCALED) {
+                    if constexpr (MAGIC) tf = lowered(tf);
+                    else tc = int_bound(tf, smax);
+                }
+                if (wave_any(tile_hot<VK, MAGIC>(acc, tf, tc, sc4, u4)))
+                    tile_survivors<VK, MAGIC, CH>(acc, qs, qi, qi, ib, item0, L, A, slot, has_ts, need_compact);
             }
         }
         wave_sync();
 
         if (wave_any(need_compact)) {
-            compact_full_segments<CH>(A, slot, 0, nsg * 16, (uint32_t*)&L.a[0][0], lane);
+            compact_full_segments<CH>(A, qs, slot, 0, nq16, (uint32_t*)&L.a[0][0], lane);
             need_compact = false;
             // publish the raised bounds to the workgroup (monotone, so a racing reader is only conservative)
-            for (uint32_t qi = lane; qi < nsg * 16; qi += 64) bound_of(A.tau, qi, A.B, bf[qi], bi[qi]);
+            for (uint32_t ql = lane; ql < nq16; ql += 64) load_query_side(qs, ql, ql, A, false);
             wave_sync();
         }
         lc = nlc;
     }
+    for (uint32_t ql = lane; ql < nq16; ql += 64)
+        if (ql < A.B) A.cnt[(u64)ql * A.nslots + slot] = qs.cnt[ql];
 }
 
 // ---------------------------------------------------------------------------
@@ -767,7 +951,10 @@ hipError_t linr_launch_merge(const linr_merge_args& a, hipStream_t s)
 #define SCAN_CASE(DT, VK, KS_, M_, QG_)                                                           \
     if (dtype == DT && p.vk == VK && p.ks == KS_ && a.m == M_ && p.qg == QG_) {                   \
         if (!launch) return hipSuccess;                                                           \
-        hipLaunchKernelGGL((scan_kernel<DT, VK, KS_, M_, QG_>), dim3(p.grid), dim3(64 * WPB), 0, s, a); \
+        if (QG_ <= 2 && a.ts != nullptr)                                                          \
+            hipLaunchKernelGGL((scan_kernel<DT, VK, KS_, M_, QG_, (QG_ <= 2)>), dim3(p.grid), dim3(64 * WPB), 0, s, a); \
+        else                                                                                      \
+            hipLaunchKernelGGL((scan_kernel<DT, VK, KS_, M_, QG_, false>), dim3(p.grid), dim3(64 * WPB), 0, s, a); \
         return hipGetLastError();                                                                 \
     }
 
@@ -802,7 +989,7 @@ int linr_fast_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_
 uint32_t linr_lds_scan_dynamic_bytes(uint32_t B, uint32_t m, uint32_t ks)
 {
     uint32_t nsg = (B + 15) / 16;
-    return nsg * m * ks * 1024u + nsg * 16u * 8u;
+    return nsg * m * ks * 1024u + nsg * 16u * 4u * (7u + WPB);
 }
 
 #define LDS_CASE(DT, VK, KS_)                                                                      \
