@@ -162,10 +162,12 @@ int linr_last_hip_error(void);
  *   max_levels     : upper bound on the number of sweeps (1 = single full sweep);
  *   force_generic  : 1 = always use the kernel that streams queries from LDS;
  *   max_qg         : cap on the 16-query groups one wave keeps in registers (larger
- *                    batches are then split over several waves per chunk).
+ *                    batches are then split over several waves per chunk);
+ *   no_coop        : 1 = never use the workgroup-cooperative scan kernel;
+ *   coop_min_groups: use that kernel for batches of more than this many 16-query groups.
  */
 typedef struct {
-    uint32_t sample_ratio, min_sample, blocks_per_cu, max_levels, force_generic, max_qg, _r1, _r2;
+    uint32_t sample_ratio, min_sample, blocks_per_cu, max_levels, force_generic, max_qg, no_coop, coop_min_groups;
 } linr_tuning;
 int linr_set_tuning(const linr_tuning*);
 
@@ -178,7 +180,7 @@ int linr_set_tuning(const linr_tuning*);
  * finished.  *n_stages receives the number of stages, kinds[s] a LINR_STAGE_* value
  * and stage_items[s] the number of items a scan stage visits.
  */
-#define LINR_MAX_STAGES 24
+#define LINR_MAX_STAGES 64
 enum { LINR_STAGE_INIT = 0, LINR_STAGE_SCAN = 1, LINR_STAGE_MERGE = 2 };
 int linr_search_filtered_timed(const linr_index*, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
                          const linr_filter* filters, uint32_t k,

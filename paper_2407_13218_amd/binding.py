@@ -17,7 +17,7 @@ MAX_K = 2048
 MAX_M = 8
 SRC_HOST, SRC_DEVICE_COPY, SRC_DEVICE_BORROW = 0, 1, 2
 FILTERS_ON_DEVICE, FILTERS_ON_HOST = 0, 1
-MAX_STAGES = 24
+MAX_STAGES = 64
 STAGE_NAMES = {0: "init", 1: "scan", 2: "merge"}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -44,7 +44,7 @@ class LinrError(RuntimeError):
 
 class Tuning(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in ("sample_ratio", "min_sample", "blocks_per_cu", "max_levels",
-                                          "force_generic", "max_qg", "_r1", "_r2")]
+                                          "force_generic", "max_qg", "no_coop", "coop_min_groups")]
 
 
 def lib_path() -> str:

@@ -163,6 +163,22 @@ extern "C" int linr_index_load_int8(linr_index* ix, const int8_t* emb, const flo
 // ---------------------------------------------------------------------------
 static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
+// occupancy of each kernel variant, asked from the runtime once per process
+static int cached_blocks_per_cu(const linr_index* ix, const linr_plan& p, uint32_t Bp, uint32_t m)
+{
+    static int cache[3][3][2][2][9][17][9][2];       // dtype, vk, generic, coop, ks, qg, m, ts  (0 = unknown)
+    static int cache_dyn = 0;                          // the LDS-streamed kernel depends on (B, m): not cached
+    (void)cache_dyn;
+    const int ts = ix->ts != nullptr;
+    if (p.generic) return linr_scan_blocks_per_cu(p, ix->dtype, Bp, m, ts);
+    int& slot = cache[ix->dtype][p.vk][0][p.coop ? 1 : 0][p.ks][p.qg][m][ts];
+    if (slot == 0) {
+        int v = linr_scan_blocks_per_cu(p, ix->dtype, Bp, m, ts);
+        slot = v > 0 ? v : -1;
+    }
+    return slot > 0 ? slot : 0;
+}
+
 // Choose kernel shape, grid and the sequence of threshold-seeding sweeps for a pass of
 // at most B queries.  Returns LINR_OK or LINR_E_SHAPE.
 static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, linr_plan* p)
@@ -184,8 +200,23 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
             qg = c;
             if (c >= nsg) break;
         }
+    // batches of more than two groups: workgroup-cooperative kernel, 4 waves x cq groups each
+    uint32_t cq = 0;
+    if (!g_tuning.force_generic && !g_tuning.no_coop && nsg > (g_tuning.coop_min_groups ? g_tuning.coop_min_groups : 8u))
+        for (uint32_t c = 1; c <= 4; c <<= 1) {
+            if (!linr_coop_variant_exists(ix->dtype, p->vk, p->ks, m, c)) continue;
+            cq = c;
+            if (c * LINR_WAVES_PER_BLOCK >= nsg) break;
+        }
     uint32_t Bp;
-    if (qg) {
+    if (cq) {
+        p->qg = cq;
+        p->coop = 1;
+        p->generic = 0;
+        p->max_batch = LINR_WAVES_PER_BLOCK * cq * 16;
+        Bp = B < p->max_batch ? B : p->max_batch;
+        p->nsplit = LINR_WAVES_PER_BLOCK;              // one chunk-slot per workgroup
+    } else if (qg) {
         p->qg = qg;
         p->generic = 0;
         p->max_batch = LINR_MAX_NSPLIT * qg * 16;
@@ -203,9 +234,14 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
         p->nsplit = 1;
     }
     if (p->nsplit < 1) p->nsplit = 1;
-    uint32_t bpc = g_tuning.blocks_per_cu ? g_tuning.blocks_per_cu : 4;
-    if (bpc > 4) bpc = 4;                               // 4 x 38 KB of LDS per compute unit
-    if (p->generic) bpc = 1;                            // its query fragments take most of the LDS
+    // persistent grid: exactly the workgroups that are resident at once (a larger grid would leave
+    // a tail of workgroups running on a mostly idle chip, since chunks are assigned statically)
+    uint32_t bpc = g_tuning.blocks_per_cu;
+    if (!bpc) {
+        int occ = cached_blocks_per_cu(ix, *p, Bp, m);
+        bpc = occ > 0 ? (uint32_t)occ : 2u;
+        if (bpc > 8) bpc = 8;
+    }
     p->n_chunks = (ix->n + p->chunk_items - 1) / p->chunk_items;
     uint64_t waves_wanted = p->n_chunks * p->nsplit;
     uint64_t grid = (uint64_t)ix->num_cu * bpc;

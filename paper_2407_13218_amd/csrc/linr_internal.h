@@ -39,6 +39,7 @@ struct linr_plan {
     uint32_t qg;                // 16-query groups held per wave
     uint32_t nsplit;            // waves that share a chunk and split the query groups
     uint32_t generic;           // 1 = queries streamed from LDS
+    uint32_t coop;              // 1 = the four waves of a workgroup share each chunk and split the query groups
     uint32_t grid;              // workgroups of LINR_WAVES_PER_BLOCK waves
     uint32_t nslots;            // chunk-slots = waves / nsplit
     uint32_t cap;               // entries per (slot, query) candidate segment
@@ -79,6 +80,9 @@ hipError_t linr_launch_scan(const linr_plan& p, int dtype, const linr_scan_args&
 hipError_t linr_launch_merge(const linr_merge_args& a, hipStream_t s);
 // 1 if a register-resident-query scan kernel exists for this shape
 int linr_fast_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg);
+int linr_coop_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg);
+// workgroups of the planned scan kernel resident per compute unit (0 if unknown)
+int linr_scan_blocks_per_cu(const linr_plan& p, int dtype, uint32_t B, uint32_t m, int has_ts);
 // dynamic LDS bytes of the LDS-streamed scan kernel for a pass of B queries
 uint32_t linr_lds_scan_dynamic_bytes(uint32_t B, uint32_t m, uint32_t ks);
 #define LINR_LDS_SCAN_BUDGET 120000u  // bytes of dynamic LDS next to 38 KB of per-wave chunk staging

@@ -33,7 +33,8 @@ __device__ __forceinline__ void wave_sync()
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
-__device__ __forceinline__ bool wave_any(bool p) { return __ballot(p) != 0ull; }
+__device__ __forceinline__ u64 wave_ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+__device__ __forceinline__ bool wave_any(bool p) { return wave_ballot(p) != 0ull; }
 
 // monotone map fp32 -> uint32 (−0.0 is first folded into +0.0 so that both compare equal)
 __device__ __forceinline__ uint32_t ord_f32(float s)
@@ -365,17 +366,17 @@ template <int VK, bool MAGIC, bool TS, typename acc_t>
 __device__ __forceinline__ bool tile_hot_pred(const acc_t& acc, float thr_f, int thr_int, const v4f& sc4, const v4f& u4,
                                               const v4u& mk4, const v4u& ts4, uint32_t fa, uint32_t fn, uint32_t t0, uint32_t t1)
 {
-    bool hot = false;
+    bool hot = false;                         // bitwise, not short-circuit: no divergent branches
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         bool feas = (mk4[r] & fn) == fa;
-        if constexpr (TS) feas = feas && (ts4[r] - t0) <= t1;          // t1 holds ts_max - ts_min here
+        if constexpr (TS) feas = feas & ((ts4[r] - t0) <= t1);          // t1 holds ts_max - ts_min here
         bool above;
         if constexpr (VK == LINR_VK_FLOAT) above = acc[r] >= thr_f;
         else if constexpr (VK == LINR_VK_I8_SCALED && MAGIC)
             above = __builtin_fmaf(__int_as_float(acc[r]), sc4[r], -u4[r]) >= thr_f;
         else above = acc[r] >= thr_int;
-        hot = hot || (feas && above);
+        hot = hot | (feas & above);
     }
     return hot;
 }
@@ -384,14 +385,14 @@ __device__ __forceinline__ bool tile_hot_pred(const acc_t& acc, float thr_f, int
 // predicate for the survivors and the key append to the wave's segment of that query.
 template <int VK, bool MAGIC, int CH, typename acc_t>
 __device__ __forceinline__ void tile_survivors(const acc_t& acc, const QSide& qs, uint32_t ql, uint32_t qi, int ib, u64 item0,
-                                               const WaveLds& L, const linr_scan_args& A, uint32_t slot, bool has_ts,
-                                               bool& need_compact)
+                                               const float* l_sc, const uint32_t* l_mk, const uint32_t* l_ts,
+                                               const linr_scan_args& A, uint32_t slot, bool has_ts, bool& need_compact)
 {
     uint32_t surv = 0;
     uint32_t hi[4];
     if constexpr (VK == LINR_VK_I8_SCALED) {
         const float tf = qs.thr_f[ql];
-        v4f sc4 = *(const v4f*)&L.sc[ib];
+        v4f sc4 = *(const v4f*)&l_sc[ib];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             int raw = MAGIC ? acc[r] - LINR_MAGIC_BITS : acc[r];
@@ -417,9 +418,9 @@ __device__ __forceinline__ void tile_survivors(const acc_t& acc, const QSide& qs
     if (qi >= A.B) surv = 0;
     if (!wave_any(surv != 0)) return;
 
-    v4u mk4 = *(const v4u*)&L.mk[ib];
+    v4u mk4 = *(const v4u*)&l_mk[ib];
     v4u ts4 = {0, 0, 0, 0};
-    if (has_ts) ts4 = *(const v4u*)&L.ts[ib];
+    if (has_ts) ts4 = *(const v4u*)&l_ts[ib];
     if (surv) {
         const uint32_t fa = qs.fall[ql], fn = qs.fnone[ql];
         const bool complex = (qs.fflag[ql] & 1u) != 0u;
@@ -604,18 +605,18 @@ scan_kernel(linr_scan_args A)
 #pragma unroll
             for (int i = 0; i < QG; ++i) {
                 if constexpr (PRED_A)
-                    hot[i] = __ballot(tile_hot_pred<VK, MAGIC, TS>(acc[i], tcf[i], tci[i], sc4, u4, mk4, ts4, f_all[i], f_none[i],
+                    hot[i] = wave_ballot(tile_hot_pred<VK, MAGIC, TS>(acc[i], tcf[i], tci[i], sc4, u4, mk4, ts4, f_all[i], f_none[i],
                                                                    f_t0[i], f_t1[i]));
                 else
-                    hot[i] = __ballot(tile_hot<VK, MAGIC>(acc[i], tcf[i], tci[i], sc4, u4));
+                    hot[i] = wave_ballot(tile_hot<VK, MAGIC>(acc[i], tcf[i], tci[i], sc4, u4));
                 any_hot |= hot[i];
             }
             if (any_hot) {
 #pragma unroll
                 for (int i = 0; i < QG; ++i)
                     if (hot[i])
-                        tile_survivors<VK, MAGIC, CH>(acc[i], qs, i * 16 + row, q_first + i * 16 + row, ib, item0, L, A, slot,
-                                                      has_ts, need_compact);
+                        tile_survivors<VK, MAGIC, CH>(acc[i], qs, i * 16 + row, q_first + i * 16 + row, ib, item0, L.sc, L.mk, L.ts,
+                                                      A, slot, has_ts, need_compact);
             }
         }
         wave_sync();
@@ -642,6 +643,216 @@ scan_kernel(linr_scan_args A)
         uint32_t qi = q_first + ql;
         if (qi < A.B) A.cnt[(u64)qi * A.nslots + slot] = W.cnt[ql];
     }
+}
+
+// ---------------------------------------------------------------------------
+// scan kernel, workgroup-cooperative: the four waves of a workgroup form ONE chunk-slot.  Each
+// wave loads a quarter of every chunk into a shared, double-buffered LDS area (one barrier per
+// chunk) and scores the whole chunk against its own QG query groups (wave w owns groups
+// [w*QG, w*QG+QG)), so 4*QG*16 queries are answered per pass while every wave keeps only QG
+// groups of fragments and accumulators in registers -- several waves per SIMD stay resident and
+// the matrix pipe of one wave overlaps the vector work of another.
+// ---------------------------------------------------------------------------
+struct ChunkLds {
+    v4i a[8][64];
+    float sc[128];
+    uint32_t mk[128];
+    uint32_t ts[128];
+};
+
+template <int VK, int KS>
+struct CoopRegs {
+    v4i ra[2];
+    uint32_t rsc, rmk, rts;
+};
+
+template <int VK, int KS>
+__device__ __forceinline__ void issue_coop(CoopRegs<VK, KS>& R, const linr_scan_args& A, u64 lc, int lane, int wib, bool has_ts)
+{
+    constexpr int TPC = 8 / KS;
+    constexpr int CH = 16 * TPC;
+    const int row = lane & 15, g4 = lane >> 4;
+    const char* embp = (const char*)A.emb;
+    const uint32_t rb = A.row_bytes;
+    const u64 item0 = lc * A.stride * CH;
+    const u64 last = A.n - 1;
+    const bool fast = item0 + CH <= A.n && rb == (uint32_t)KS * 64u;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int f = wib * 2 + j, t = f / KS, ks = f % KS;
+        if (fast) {
+            R.ra[j] = __builtin_nontemporal_load((const v4i*)(embp + item0 * (u64)(KS * 64) +
+                                                            ((uint32_t)(t * 16 + row) * (KS * 64) + (uint32_t)(ks * 64 + g4 * 16))));
+        } else {
+            u64 it = item0 + t * 16 + row;
+            it = it < last ? it : last;
+            uint32_t off = ks * 64 + g4 * 16;
+            v4i z = {0, 0, 0, 0};
+            if (off < rb) z = *(const v4i*)(embp + it * rb + off);
+            R.ra[j] = z;
+        }
+    }
+    const int idx = wib * 32 + lane;
+    if (lane < 32 && idx < CH) {
+        u64 it = item0 + idx;
+        it = it < last ? it : last;
+        if (VK == LINR_VK_I8_SCALED) R.rsc = __builtin_nontemporal_load((const uint32_t*)A.row_scale + it);
+        R.rmk = __builtin_nontemporal_load(A.mask + it);
+        if (has_ts) R.rts = __builtin_nontemporal_load(A.ts + it);
+    }
+}
+
+template <int VK, int KS>
+__device__ __forceinline__ void stage_coop(const CoopRegs<VK, KS>& R, ChunkLds& C, int lane, int wib, bool has_ts)
+{
+    constexpr int CH = 16 * (8 / KS);
+    C.a[wib * 2][lane] = R.ra[0];
+    C.a[wib * 2 + 1][lane] = R.ra[1];
+    const int idx = wib * 32 + lane;
+    if (lane < 32 && idx < CH) {
+        if (VK == LINR_VK_I8_SCALED) C.sc[idx] = __uint_as_float(R.rsc);
+        C.mk[idx] = R.rmk;
+        if (has_ts) C.ts[idx] = R.rts;
+    }
+}
+
+template <int DT, int VK, int KS, int M, int QG>
+__global__ void __launch_bounds__(64 * WPB, (QG * M * KS <= 2 ? 4 : QG * M * KS <= 8 ? 3 : 2)) scan_kernel_coop(linr_scan_args A)
+{
+    constexpr int TPC = 8 / KS;
+    constexpr int CH = 16 * TPC;
+    constexpr int NQ = QG * 16;
+    constexpr bool MAGIC = (VK == LINR_VK_I8_SCALED);
+    static_assert(VK != LINR_VK_I8_SCALED || KS * 64 <= 256, "scaled int8 rows longer than 256 use another kernel");
+    using acc_t = typename AccOf<DT>::type;
+
+    __shared__ ChunkLds chunk[2];
+    __shared__ WaveQ<QG> wq_all[WPB];
+    __shared__ uint32_t hist_all[WPB][256];
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    WaveQ<QG>& W = wq_all[wib];
+    const QSide qs = {W.cnt, W.thr_f, W.thr_i, W.fall, W.fnone, W.tsmin, W.tsmax, W.fflag};
+    const int row = lane & 15, g4 = lane >> 4;
+    const uint32_t slot = blockIdx.x;
+    if (slot >= A.nslots) return;                       // uniform for the workgroup
+    const uint32_t sg0 = wib * QG;
+    const uint32_t q_first = sg0 * 16;
+    const bool active = q_first < A.B;                  // waves past the batch still load and synchronise
+    const bool has_ts = A.ts != nullptr;
+    const uint32_t rb = A.row_bytes;
+
+    v4i q[QG][M][KS];
+#pragma unroll
+    for (int i = 0; i < QG; ++i) {
+        uint32_t qi = (sg0 + i) * 16 + row;
+#pragma unroll
+        for (int e = 0; e < M; ++e)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                uint32_t off = ks * 64 + g4 * 16;
+                v4i z = {0, 0, 0, 0};
+                if (qi < A.B && off < rb)
+                    z = *(const v4i*)((const char*)A.Q + ((u64)qi * M + e) * rb + off);
+                q[i][e][ks] = z;
+            }
+    }
+    for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) {
+        W.cnt[ql] = 0;
+        load_query_side(qs, ql, q_first + ql, A, true);
+    }
+    wave_sync();
+    float tcf[QG];            // lane l tracks query row l%16 of each group; already in stage A's form
+    int tci[QG];
+#pragma unroll
+    for (int i = 0; i < QG; ++i) {
+        tcf[i] = MAGIC ? lowered(W.thr_f[i * 16 + row]) : W.thr_f[i * 16 + row];
+        tci[i] = W.thr_i[i * 16 + row];
+    }
+
+    CoopRegs<VK, KS> R;
+    R.rsc = R.rmk = R.rts = 0u;
+    bool need_compact = false;
+    uint32_t since_refresh = 0;
+    const acc_t acc0 = MAGIC ? (acc_t){LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS} : (acc_t){0, 0, 0, 0};
+    u64 lc = slot;
+    if (lc < A.n_level_chunks) issue_coop<VK, KS>(R, A, lc, lane, wib, has_ts);
+    int buf = 0;
+
+    while (lc < A.n_level_chunks) {
+        const u64 item0 = lc * A.stride * CH;
+        ChunkLds& C = chunk[buf];
+        stage_coop<VK, KS>(R, C, lane, wib, has_ts);
+        __syncthreads();
+        const u64 nlc = lc + A.nslots;
+        if (nlc < A.n_level_chunks) issue_coop<VK, KS>(R, A, nlc, lane, wib, has_ts);
+
+        if (active) {
+#pragma unroll 1
+            for (int t = 0; t < TPC; ++t) {
+                v4i a[KS];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) a[ks] = C.a[t * KS + ks][lane];
+                const int ib = t * 16 + 4 * g4;
+                v4f sc4 = {0, 0, 0, 0}, u4 = {0, 0, 0, 0};
+                if constexpr (MAGIC) {
+                    sc4 = *(const v4f*)&C.sc[ib];
+                    u4 = sc4 * LINR_MAGIC_U;
+                }
+                acc_t acc[QG];
+#pragma unroll
+                for (int i = 0; i < QG; ++i) {
+#pragma unroll
+                    for (int e = 0; e < M; ++e) {
+                        acc_t tmp = acc0;
+#pragma unroll
+                        for (int ks = 0; ks < KS; ++ks) tmp = mfma_kstep<DT>(a[ks], q[i][e][ks], tmp);
+                        if (e == 0) acc[i] = tmp;
+                        else {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) acc[i][r] = acc[i][r] > tmp[r] ? acc[i][r] : tmp[r];
+                        }
+                    }
+                }
+                u64 hot[QG];
+                u64 any_hot = 0;
+#pragma unroll
+                for (int i = 0; i < QG; ++i) {
+                    hot[i] = wave_ballot(tile_hot<VK, MAGIC>(acc[i], tcf[i], tci[i], sc4, u4));
+                    any_hot |= hot[i];
+                }
+                if (any_hot) {
+#pragma unroll
+                    for (int i = 0; i < QG; ++i)
+                        if (hot[i])
+                            tile_survivors<VK, MAGIC, CH>(acc[i], qs, i * 16 + row, q_first + i * 16 + row, ib, item0, C.sc, C.mk,
+                                                          C.ts, A, slot, has_ts, need_compact);
+                }
+            }
+            bool refresh = ++since_refresh >= 16;
+            if (wave_any(need_compact)) {
+                compact_full_segments<CH>(A, qs, slot, q_first, NQ, hist_all[wib], lane);
+                need_compact = false;
+                refresh = true;
+            }
+            if (refresh) {
+                for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) load_query_side(qs, ql, q_first + ql, A, false);
+                wave_sync();
+#pragma unroll
+                for (int i = 0; i < QG; ++i) {
+                    tcf[i] = MAGIC ? lowered(W.thr_f[i * 16 + row]) : W.thr_f[i * 16 + row];
+                    tci[i] = W.thr_i[i * 16 + row];
+                }
+                since_refresh = 0;
+            }
+        }
+        lc = nlc;
+        buf ^= 1;
+    }
+    if (active)
+        for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) {
+            uint32_t qi = q_first + ql;
+            if (qi < A.B) A.cnt[(u64)qi * A.nslots + slot] = W.cnt[ql];
+        }
 }
 
 // ---------------------------------------------------------------------------
@@ -732,7 +943,7 @@ __global__ void __launch_bounds__(64 * WPB) scan_kernel_lds(linr_scan_args A)
                     else tc = int_bound(tf, smax);
                 }
                 if (wave_any(tile_hot<VK, MAGIC>(acc, tf, tc, sc4, u4)))
-                    tile_survivors<VK, MAGIC, CH>(acc, qs, qi, qi, ib, item0, L, A, slot, has_ts, need_compact);
+                    tile_survivors<VK, MAGIC, CH>(acc, qs, qi, qi, ib, item0, L.sc, L.mk, L.ts, A, slot, has_ts, need_compact);
             }
         }
         wave_sync();
@@ -948,17 +1159,43 @@ hipError_t linr_launch_merge(const linr_merge_args& a, hipStream_t s)
     return hipGetLastError();
 }
 
+// One dispatcher for three questions about a scan kernel variant: does it exist, how many
+// workgroups of it fit a compute unit, launch it.
+enum { ACT_EXISTS = 0, ACT_OCCUPANCY = 1, ACT_LAUNCH = 2 };
+struct ScanAct {
+    int what;
+    uint32_t grid;
+    uint32_t dyn;
+    hipStream_t s;
+    const linr_scan_args* a;
+    int blocks_per_cu;       // out (ACT_OCCUPANCY)
+};
+
+template <typename K>
+static hipError_t scan_act(K kern, ScanAct& act)
+{
+    if (act.what == ACT_EXISTS) return hipSuccess;
+    if (act.dyn > 0) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)act.dyn);
+        if (e != hipSuccess) return e;
+    }
+    if (act.what == ACT_OCCUPANCY) {
+        int nb = 0;
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, 64 * WPB, act.dyn);
+        act.blocks_per_cu = nb;
+        return e;
+    }
+    hipLaunchKernelGGL(kern, dim3(act.grid), dim3(64 * WPB), act.dyn, act.s, *act.a);
+    return hipGetLastError();
+}
+
 #define SCAN_CASE(DT, VK, KS_, M_, QG_)                                                           \
-    if (dtype == DT && p.vk == VK && p.ks == KS_ && a.m == M_ && p.qg == QG_) {                   \
-        if (!launch) return hipSuccess;                                                           \
-        if (QG_ <= 2 && a.ts != nullptr)                                                          \
-            hipLaunchKernelGGL((scan_kernel<DT, VK, KS_, M_, QG_, (QG_ <= 2)>), dim3(p.grid), dim3(64 * WPB), 0, s, a); \
-        else                                                                                      \
-            hipLaunchKernelGGL((scan_kernel<DT, VK, KS_, M_, QG_, false>), dim3(p.grid), dim3(64 * WPB), 0, s, a); \
-        return hipGetLastError();                                                                 \
+    if (dtype == DT && vk == VK && ks == KS_ && m == M_ && qg == QG_) {                           \
+        if (QG_ <= 2 && ts) return scan_act(scan_kernel<DT, VK, KS_, M_, QG_, (QG_ <= 2)>, act);  \
+        return scan_act(scan_kernel<DT, VK, KS_, M_, QG_, false>, act);                           \
     }
 
-static hipError_t scan_dispatch(const linr_plan& p, int dtype, const linr_scan_args& a, hipStream_t s, bool launch)
+static hipError_t scan_dispatch(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg, bool ts, ScanAct& act)
 {
     // int8 d<=64 (one K-step), scaled and raw
     SCAN_CASE(LINR_I8, LINR_VK_I8_SCALED, 1, 1, 1)  SCAN_CASE(LINR_I8, LINR_VK_I8_SCALED, 1, 1, 2)
@@ -979,31 +1216,31 @@ static hipError_t scan_dispatch(const linr_plan& p, int dtype, const linr_scan_a
     return hipErrorInvalidDeviceFunction;
 }
 
-int linr_fast_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg)
-{
-    linr_plan p{}; p.vk = vk; p.ks = ks; p.qg = qg;
-    linr_scan_args a{}; a.m = m;
-    return scan_dispatch(p, dtype, a, nullptr, false) == hipSuccess;
-}
+#define COOP_CASE(DT, VK, KS_, M_, QG_)                                                           \
+    if (dtype == DT && vk == VK && ks == KS_ && m == M_ && qg == QG_)                             \
+        return scan_act(scan_kernel_coop<DT, VK, KS_, M_, QG_>, act);
 
-uint32_t linr_lds_scan_dynamic_bytes(uint32_t B, uint32_t m, uint32_t ks)
+static hipError_t coop_dispatch(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg, ScanAct& act)
 {
-    uint32_t nsg = (B + 15) / 16;
-    return nsg * m * ks * 1024u + nsg * 16u * 4u * (7u + WPB);
+    COOP_CASE(LINR_I8, LINR_VK_I8_SCALED, 1, 1, 1) COOP_CASE(LINR_I8, LINR_VK_I8_SCALED, 1, 1, 2)
+    COOP_CASE(LINR_I8, LINR_VK_I8_SCALED, 1, 1, 4)
+    COOP_CASE(LINR_I8, LINR_VK_I8_RAW, 1, 1, 1)    COOP_CASE(LINR_I8, LINR_VK_I8_RAW, 1, 1, 2)
+    COOP_CASE(LINR_I8, LINR_VK_I8_RAW, 1, 1, 4)
+    COOP_CASE(LINR_BF16, LINR_VK_FLOAT, 4, 1, 1)   COOP_CASE(LINR_BF16, LINR_VK_FLOAT, 4, 1, 2)
+    COOP_CASE(LINR_BF16, LINR_VK_FLOAT, 4, 1, 4)
+    COOP_CASE(LINR_BF16, LINR_VK_FLOAT, 2, 1, 1)   COOP_CASE(LINR_BF16, LINR_VK_FLOAT, 2, 1, 2)
+    COOP_CASE(LINR_BF16, LINR_VK_FLOAT, 2, 1, 4)
+    COOP_CASE(LINR_BF16, LINR_VK_FLOAT, 2, 8, 1)   COOP_CASE(LINR_BF16, LINR_VK_FLOAT, 2, 8, 2)
+    COOP_CASE(LINR_F32, LINR_VK_FLOAT, 4, 1, 1)    COOP_CASE(LINR_F32, LINR_VK_FLOAT, 4, 1, 2)
+    COOP_CASE(LINR_F32, LINR_VK_FLOAT, 4, 1, 4)
+    return hipErrorInvalidDeviceFunction;
 }
 
 #define LDS_CASE(DT, VK, KS_)                                                                      \
-    if (dtype == DT && p.vk == VK && p.ks == KS_) {                                                \
-        auto kern = scan_kernel_lds<DT, VK, KS_>;                                                  \
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn); \
-        if (e != hipSuccess) return e;                                                             \
-        hipLaunchKernelGGL(kern, dim3(p.grid), dim3(64 * WPB), dyn, s, a);                         \
-        return hipGetLastError();                                                                  \
-    }
+    if (dtype == DT && vk == VK && ks == KS_) return scan_act(scan_kernel_lds<DT, VK, KS_>, act);
 
-static hipError_t lds_dispatch(const linr_plan& p, int dtype, const linr_scan_args& a, hipStream_t s)
+static hipError_t lds_dispatch(int dtype, int vk, uint32_t ks, ScanAct& act)
 {
-    const uint32_t dyn = linr_lds_scan_dynamic_bytes(a.B, a.m, p.ks);
     LDS_CASE(LINR_I8, LINR_VK_I8_SCALED, 1) LDS_CASE(LINR_I8, LINR_VK_I8_SCALED, 2)
     LDS_CASE(LINR_I8, LINR_VK_I8_SCALED, 4) LDS_CASE(LINR_I8, LINR_VK_I8_SCALED, 8)
     LDS_CASE(LINR_I8, LINR_VK_I8_RAW, 1)    LDS_CASE(LINR_I8, LINR_VK_I8_RAW, 2)
@@ -1015,8 +1252,45 @@ static hipError_t lds_dispatch(const linr_plan& p, int dtype, const linr_scan_ar
     return hipErrorInvalidDeviceFunction;
 }
 
+int linr_fast_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg)
+{
+    ScanAct act{}; act.what = ACT_EXISTS;
+    return scan_dispatch(dtype, vk, ks, m, qg, false, act) == hipSuccess;
+}
+
+int linr_coop_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg)
+{
+    ScanAct act{}; act.what = ACT_EXISTS;
+    return coop_dispatch(dtype, vk, ks, m, qg, act) == hipSuccess;
+}
+
+uint32_t linr_lds_scan_dynamic_bytes(uint32_t B, uint32_t m, uint32_t ks)
+{
+    uint32_t nsg = (B + 15) / 16;
+    return nsg * m * ks * 1024u + nsg * 16u * 4u * (7u + WPB);
+}
+
+static hipError_t plan_dispatch(const linr_plan& p, int dtype, uint32_t B, uint32_t m, bool ts, ScanAct& act)
+{
+    if (p.generic) {
+        act.dyn = linr_lds_scan_dynamic_bytes(B, m, p.ks);
+        return lds_dispatch(dtype, p.vk, p.ks, act);
+    }
+    act.dyn = 0;
+    if (p.coop) return coop_dispatch(dtype, p.vk, p.ks, m, p.qg, act);
+    return scan_dispatch(dtype, p.vk, p.ks, m, p.qg, ts, act);
+}
+
+// workgroups of the planned scan kernel that are resident per compute unit (0 on error)
+int linr_scan_blocks_per_cu(const linr_plan& p, int dtype, uint32_t B, uint32_t m, int has_ts)
+{
+    ScanAct act{}; act.what = ACT_OCCUPANCY;
+    if (plan_dispatch(p, dtype, B, m, has_ts != 0, act) != hipSuccess) return 0;
+    return act.blocks_per_cu;
+}
+
 hipError_t linr_launch_scan(const linr_plan& p, int dtype, const linr_scan_args& a, hipStream_t s)
 {
-    if (p.generic) return lds_dispatch(p, dtype, a, s);
-    return scan_dispatch(p, dtype, a, s, true);
+    ScanAct act{}; act.what = ACT_LAUNCH; act.grid = p.grid; act.s = s; act.a = &a;
+    return plan_dispatch(p, dtype, a.B, a.m, a.ts != nullptr, act);
 }

@@ -206,6 +206,26 @@ def test_float_shapes_served_by_the_lds_kernel(oracle_mod, dtype, d, m):
     assert_float_rule(oracle_mod, w, gpu, k, label=f"lds float d={d} m={m}")
 
 
+@pytest.mark.parametrize("tuning", [dict(coop_min_groups=2), dict(no_coop=1, max_qg=4), dict(no_coop=1, max_qg=16)])
+def test_kernel_families_agree_on_a_large_batch(oracle_mod, tuning):
+    """the same 200-query batch through the workgroup-cooperative kernel, split over several waves per
+    chunk, and with 16 query groups in one wave"""
+    say(f"kernel families {tuning}")
+    w = rand_int8_workload(55, 60_000, 64, 200, scaled=True, with_ts=True)
+    gpu = run_gpu(to_cuda(w), k=300, tuning=tuning)
+    assert_exact(gpu, run_oracle(oracle_mod, w, 300), f"family {tuning}")
+
+
+def test_coop_kernel_bf16_and_multi_embedding(oracle_mod):
+    say("coop kernel: bf16 d=128 B=150; bf16 d=64 m=8 B=40")
+    w = S.config2(n=60_000, B=150, k=200, p=0.5, chunk=60_000)
+    gpu = run_gpu(to_cuda(w), tuning=dict(coop_min_groups=2))
+    assert_float_rule(oracle_mod, w, gpu, w["k"], label="coop bf16")
+    w = S.config4(n=40_000, B=40, k=100, chunk=40_000)
+    gpu = run_gpu(to_cuda(w), tuning=dict(coop_min_groups=2))
+    assert_float_rule(oracle_mod, w, gpu, w["k"], label="coop bf16 m=8")
+
+
 def test_batch_larger_than_one_pass(oracle_mod):
     say("B = 4200 (more than one pass of the register kernel)")
     w = rand_int8_workload(41, 3_000, 64, 4200, scaled=True)
