@@ -26,6 +26,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 INT8_PEAK_TOPS = 5000.0        # MI355X dense int8 MFMA
 BYTES_PER_ITEM = 64 + 4 + 4    # codes + mask + row scale: the algorithmic HBM bytes of one item
+# HBM bytes of one full-sweep launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same
+# counter reads for a 4 GiB device copy (profiles/scan_kernel_cfg5_B32_pass5.md); keyed by (N, B, pass rate, k)
+MEASURED_TRAFFIC_BYTES = {(1_000_000_000, 32, "5%", 1000): 72.04e9}
 
 
 def log(msg):
@@ -71,6 +74,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--sweep-steps", type=int, default=5)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 4 GiB device copy (known traffic) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
+                         "readings of the scan kernel can be scaled against it")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (an item-range shard per GPU is design-only); "
@@ -87,6 +93,15 @@ def main():
     torch.cuda.set_device(0)
     dev = "cuda"
     N, k = args.n_items, args.k
+
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 32, dtype=torch.int8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)                                # reads 4 GiB, writes 4 GiB
+        torch.cuda.synchronize()
+        del src, dst
+        log("calibration copy done: 3 launches, 4 GiB read + 4 GiB written each")
 
     log(f"generating {N:,} x d64 int8 clustered items on the GPU ...")
     t0 = time.time()
@@ -170,7 +185,7 @@ def main():
                                f"B={args.batch}, pass rate {args.selectivity}, k={k}", "N": N, "d": 64, "B": args.batch,
                    "k": k, "selectivity": args.selectivity, "levels": head["levels"], "workspace_GB": head["workspace_GB"]},
         "roofline": {"bound": "hbm", "achieved": head["hbm_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": head["hbm_frac"], "traffic": None,
+                     "frac": head["hbm_frac"], "traffic": MEASURED_TRAFFIC_BYTES.get((N, args.batch, args.selectivity, k)),
                      "kernel": "scan_kernel (full sweep)", "kernel_ms": head["full_sweep_launch_ms"],
                      "algorithmic_bytes_per_launch": N * BYTES_PER_ITEM},
         "cpu_baseline": cpu,
