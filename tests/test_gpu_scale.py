@@ -1,0 +1,92 @@
+"""Parity at the full benchmark size (config 5: 1e9 x d64 int8 resident in HBM, the launch configuration bench.py
+times).  The CPU oracle cannot hold 72 GB at once, so
+  (a) every returned (query, id) pair of the whole batch is re-scored by the oracle one by one (rows gathered on the
+      GPU, copied to the host): raw int32 dot, fp32 score bits, feasibility, ordering, uniqueness, counts;
+  (b) for a few queries the oracle scans the entire index, streamed device->host in 16 M-item pieces; the per-piece
+      oracle top-k lists are merged by (score desc, id asc) -- top-k of a union is the top-k of the pieces' top-k, the
+      split-and-merge property pinned in the CPU tests -- and must equal the GPU rows exactly."""
+import os
+import time
+import numpy as np
+import pytest
+
+import synth_inputs as S
+
+pytestmark = pytest.mark.gpu
+
+N_FULL = int(os.environ.get("LINR_SCALE_N", 1_000_000_000))
+PIECE = 16_000_000
+
+
+def say(msg):
+    print(f"[{time.strftime('%H:%M:%S')}] {msg}", flush=True)
+
+
+def test_config5_full_size_matches_oracle(oracle_mod):
+    import torch
+    import paper_2407_13218_amd as L
+
+    free, _ = torch.cuda.mem_get_info()
+    if free < N_FULL * 80:
+        pytest.skip("not enough free HBM for the full-size index")
+    k, B = 1000, 32
+    say(f"generating {N_FULL:,} items on the GPU")
+    base = S.config5(device="cuda", n=N_FULL, B=B, k=k, selectivity="5%")
+    cols = (base["emb"], base["scale"], base["mask"])
+    ix = L.Index(N_FULL, 64, S.I8, 0)
+    ix.load(base["emb"], base["mask"], row_scale=base["scale"])
+    runs = {}
+    for sel in ("5%", "0.1%"):
+        w = S.config5(device="cuda", n=N_FULL, B=B, k=k, selectivity=sel, index=cols)
+        ids, sc, raw, cnt = ix.search(w["Q"], w["filters"], k, q_scale=w["q_scale"])
+        torch.cuda.synchronize()
+        runs[sel] = (w, ids.cpu().numpy().view(np.uint32), sc.cpu().numpy(), raw.cpu().numpy(), cnt.cpu().numpy().view(np.uint32))
+        say(f"GPU search done for pass rate {sel}")
+
+    # (a) every returned pair, one by one
+    for sel, (w, ids, sc, raw, cnt) in runs.items():
+        assert np.all(cnt == k), f"{sel}: counts {cnt}"
+        flat = torch.from_numpy(ids.astype(np.int64).reshape(-1)).cuda()
+        rows = base["emb"].index_select(0, flat).cpu().numpy()
+        rs = base["scale"].index_select(0, flat).cpu().numpy()
+        mk = base["mask"].index_select(0, flat).cpu().numpy().view(np.uint32)
+        Qh = w["Q"].cpu().numpy(); qs = w["q_scale"].cpu().numpy()
+        pb = np.repeat(np.arange(B, dtype=np.uint32), k)
+        rank, oraw, feas = oracle_mod.pairs(S.I8, rows, mk, Qh, w["filters"], pb, np.arange(B * k, dtype=np.uint64), row_scale=rs)
+        assert feas.all(), f"{sel}: infeasible ids returned"
+        assert np.array_equal(oraw.reshape(B, k), raw), f"{sel}: raw int32 scores differ"
+        exp = (rank.astype(np.float32).reshape(B, k) * qs[:, None]).astype(np.float32)
+        assert exp.tobytes() == sc.tobytes(), f"{sel}: fp32 score bits differ"
+        r2 = rank.reshape(B, k)
+        assert np.all(np.diff(r2, axis=1) <= 0), f"{sel}: ranking values increase"
+        same = np.diff(r2, axis=1) == 0
+        assert np.all(np.diff(ids.astype(np.int64), axis=1)[same] > 0), f"{sel}: equal ranks not in ascending id"
+        assert all(len(set(ids[b].tolist())) == k for b in range(B)), f"{sel}: duplicate ids"
+        say(f"{sel}: all {B * k} returned pairs re-scored by the oracle: exact")
+
+    # (b) full oracle scan for two queries of each batch, streamed
+    picks = [("5%", 0), ("5%", 17), ("0.1%", 3), ("0.1%", 30)]
+    Qs = np.stack([runs[s][0]["Q"][b].cpu().numpy() for s, b in picks])                  # [4, 1, 64]
+    qsc = np.array([runs[s][0]["q_scale"][b].item() for s, b in picks], np.float32)
+    filt = np.stack([runs[s][0]["filters"][b] for s, b in picks]).astype(S.FILTER_DTYPE)
+    best = [dict(ids=np.zeros(0, np.uint32), sc=np.zeros(0, np.float32), raw=np.zeros(0, np.int32)) for _ in picks]
+    threads = max(1, min(16, os.cpu_count() or 1))
+    for p0 in range(0, N_FULL, PIECE):
+        p1 = min(N_FULL, p0 + PIECE)
+        emb_h = base["emb"][p0:p1].cpu().numpy(); rs_h = base["scale"][p0:p1].cpu().numpy()
+        mk_h = base["mask"][p0:p1].cpu().numpy().view(np.uint32)
+        oi, os_, orw, oc = oracle_mod.search(S.I8, emb_h, mk_h, Qs, filt, k, row_scale=rs_h, q_scale=qsc, id_base=p0, nthreads=threads)
+        for j in range(len(picks)):
+            c = int(oc[j])
+            ids_j = np.concatenate([best[j]["ids"], oi[j, :c]]); sc_j = np.concatenate([best[j]["sc"], os_[j, :c]])
+            raw_j = np.concatenate([best[j]["raw"], orw[j, :c]])
+            order = np.lexsort((ids_j, -sc_j.astype(np.float64)))[:k]     # q_scale > 0: score order == rank order
+            best[j] = dict(ids=ids_j[order], sc=sc_j[order], raw=raw_j[order])
+        if (p0 // PIECE) % 8 == 0:
+            say(f"oracle streamed {p1:,} / {N_FULL:,} items")
+    for j, (sel, b) in enumerate(picks):
+        _, ids, sc, raw, _ = runs[sel]
+        assert np.array_equal(best[j]["ids"], ids[b]), f"query {b} @ {sel}: id list differs from the full oracle scan"
+        assert np.array_equal(best[j]["raw"], raw[b]) and best[j]["sc"].tobytes() == sc[b].tobytes()
+        say(f"query {b} @ {sel}: top-{k} of {N_FULL:,} items identical to the oracle's")
+    ix.close()
