@@ -295,6 +295,13 @@ __device__ __forceinline__ float lowered(float thr)          // thr - 2^-14 |thr
 {
     return (fabsf(thr) < 3.0e38f) ? thr - fabsf(thr) * 6.1035156e-5f : thr;
 }
+__device__ __forceinline__ float lowered_pos(float thr)      // same, and "no usable bound" for thr <= 0
+{
+    return thr > 0.0f ? lowered(thr) : -INFINITY;
+}
+// keep a loop-invariant value in its registers instead of re-materialising it every iteration
+__device__ __forceinline__ void pin(v4i& x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ void pin(v4f& x) { asm volatile("" : "+v"(x)); }
 
 // Query-side state in LDS (pointers to arrays indexed by the wave-local query number).
 struct QSide {
@@ -341,18 +348,16 @@ __device__ __forceinline__ void load_query_side(const QSide& qs, uint32_t ql, ui
 // fma(acc_as_float, scale, -MAGIC*scale) against a bound lowered by the rounding slack,
 // otherwise the conservative per-chunk integer bound.
 template <int VK, bool MAGIC, typename acc_t>
-__device__ __forceinline__ bool tile_hot(const acc_t& acc, float thr_f, int thr_int, const v4f& sc4, const v4f& u4)
+__device__ __forceinline__ bool tile_hot(const acc_t& acc, float thr_f, int thr_int, float smax4, float umax4)
 {
     if constexpr (VK == LINR_VK_FLOAT) {
         float mx = fmaxf(fmaxf(acc[0], acc[1]), fmaxf(acc[2], acc[3]));
         return mx >= thr_f;
     } else if constexpr (VK == LINR_VK_I8_SCALED && MAGIC) {
-        float s0 = __builtin_fmaf(__int_as_float(acc[0]), sc4[0], -u4[0]);
-        float s1 = __builtin_fmaf(__int_as_float(acc[1]), sc4[1], -u4[1]);
-        float s2 = __builtin_fmaf(__int_as_float(acc[2]), sc4[2], -u4[2]);
-        float s3 = __builtin_fmaf(__int_as_float(acc[3]), sc4[3], -u4[3]);
-        float mx = fmaxf(fmaxf(s0, s1), fmaxf(s2, s3));
-        return mx >= thr_f;
+        // max_r(raw_r * scale_r) <= max_r(raw_r) * max_r(scale_r) whenever that maximum is >= 0; bounds <= 0 are
+        // passed in as -inf by the caller, so a negative maximum is (correctly) never hot against a positive bound
+        int mx = max(max(acc[0], acc[1]), max(acc[2], acc[3]));
+        return __builtin_fmaf(__int_as_float(mx), smax4, -umax4) >= thr_f;
     } else {
         int mx = max(max(acc[0], acc[1]), max(acc[2], acc[3]));
         return mx >= thr_int;
@@ -381,13 +386,32 @@ __device__ __forceinline__ bool tile_hot_pred(const acc_t& acc, float thr_f, int
     return hot;
 }
 
-// Stages B and C (rare): exact ranking values against the query's bound, then the attribute
-// predicate for the survivors and the key append to the wave's segment of that query.
+// Stages B and C (rare), entered by the whole wave when some lane's stage A fired:
+//   B1  the cheap part of the predicate (care-mask compare, ts window) for the lane's four items, only in
+//       lanes whose own stage A fired -- at low pass rates most hot tiles end here;
+//   B2  exact ranking values of the remaining items against the query's bound;
+//   C   any-of clauses (full filter record), key append to the wave's segment of that query.
 template <int VK, bool MAGIC, int CH, typename acc_t>
-__device__ __forceinline__ void tile_survivors(const acc_t& acc, const QSide& qs, uint32_t ql, uint32_t qi, int ib, u64 item0,
-                                               const float* l_sc, const uint32_t* l_mk, const uint32_t* l_ts,
-                                               const linr_scan_args& A, uint32_t slot, bool has_ts, bool& need_compact)
+__device__ __forceinline__ void tile_survivors(const acc_t& acc, bool lane_hot, const v4u& mk4, uint32_t fa, uint32_t fn,
+                                               const QSide& qs, uint32_t ql, uint32_t qi, int ib,
+                                               u64 item0, const float* l_sc, const uint32_t* l_ts,
+                                               const linr_scan_args& A, uint32_t slot, bool has_ts, uint32_t& need_compact)
 {
+    uint32_t cand = 0;
+    v4u ts4 = {0, 0, 0, 0};
+    if (lane_hot && qi < A.B) {
+        cand = ((mk4[0] & fn) == fa ? 1u : 0u) | ((mk4[1] & fn) == fa ? 2u : 0u) | ((mk4[2] & fn) == fa ? 4u : 0u) |
+               ((mk4[3] & fn) == fa ? 8u : 0u);
+        if (has_ts) {
+            ts4 = *(const v4u*)&l_ts[ib];
+            const uint32_t t0 = qs.tsmin[ql], t1 = qs.tsmax[ql];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (!(ts4[r] >= t0 && ts4[r] <= t1)) cand &= ~(1u << r);
+        }
+    }
+    if (!wave_any(cand != 0u)) return;
+
     uint32_t surv = 0;
     uint32_t hi[4];
     if constexpr (VK == LINR_VK_I8_SCALED) {
@@ -415,29 +439,22 @@ __device__ __forceinline__ void tile_survivors(const acc_t& acc, const QSide& qs
             hi[r] = ord_i32(acc[r]);
         }
     }
-    if (qi >= A.B) surv = 0;
-    if (!wave_any(surv != 0)) return;
+    surv &= cand;
+    if (!wave_any(surv != 0u)) return;
 
-    v4u mk4 = *(const v4u*)&l_mk[ib];
-    v4u ts4 = {0, 0, 0, 0};
-    if (has_ts) ts4 = *(const v4u*)&l_ts[ib];
     if (surv) {
-        const uint32_t fa = qs.fall[ql], fn = qs.fnone[ql];
         const bool complex = (qs.fflag[ql] & 1u) != 0u;
-        uint32_t t0 = 0u, t1 = 0xFFFFFFFFu;
-        if (has_ts) { t0 = qs.tsmin[ql]; t1 = qs.tsmax[ql]; }
         u64* seg_p = A.seg + ((u64)slot * A.B + qi) * A.cap;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const u64 item = item0 + ib + r;
-            const uint32_t mk = mk4[r];
-            bool ok = ((surv >> r) & 1u) && item < A.n && ((mk & fn) == fa) && (ts4[r] >= t0) && (ts4[r] <= t1);
-            if (ok && complex) ok = filter_pass(A.filters[qi], mk, has_ts, ts4[r]);
+            bool ok = ((surv >> r) & 1u) && item < A.n;
+            if (ok && complex) ok = filter_pass(A.filters[qi], mk4[r], has_ts, ts4[r]);
             if (ok) {
                 u64 key = ((u64)hi[r] << 32) | (u64)(uint32_t)~(uint32_t)item;
                 uint32_t pos = atomicAdd(&qs.cnt[ql], 1u);
                 if (pos < A.cap) seg_p[pos] = key;
-                if (pos + 1 + CH > A.cap) need_compact = true;
+                if (pos + 1 + CH > A.cap) need_compact = 1u;
             }
         }
     }
@@ -535,7 +552,8 @@ scan_kernel(linr_scan_args A)
     int thr_i[QG];
 #pragma unroll
     for (int i = 0; i < QG; ++i) {
-        thr_f[i] = W.thr_f[i * 16 + row]; thr_i[i] = W.thr_i[i * 16 + row]; thr_lo[i] = lowered(thr_f[i]);
+        thr_f[i] = W.thr_f[i * 16 + row]; thr_i[i] = W.thr_i[i * 16 + row];
+        thr_lo[i] = PRED_A ? lowered(thr_f[i]) : lowered_pos(thr_f[i]);
     }
     uint32_t f_all[QG], f_none[QG], f_t0[QG], f_t1[QG];
 #pragma unroll
@@ -547,11 +565,12 @@ scan_kernel(linr_scan_args A)
 
     ChunkRegs<VK, KS> R;
     R.rsc[0] = R.rsc[1] = R.rmk[0] = R.rmk[1] = R.rts[0] = R.rts[1] = 0u;
-    bool need_compact = false;
+    uint32_t need_compact = 0u;
     uint32_t since_refresh = 0;
     u64 lc = slot;
     if (lc < A.n_level_chunks) issue_chunk<VK, KS>(R, A, lc, lane, has_ts);
-    const acc_t acc0 = MAGIC ? (acc_t){LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS} : (acc_t){0, 0, 0, 0};
+    acc_t acc0 = MAGIC ? (acc_t){LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS} : (acc_t){0, 0, 0, 0};
+    pin(acc0);
 
     while (lc < A.n_level_chunks) {
         const u64 item0 = lc * A.stride * CH;
@@ -561,7 +580,7 @@ scan_kernel(linr_scan_args A)
         int tci[QG];
 #pragma unroll
         for (int i = 0; i < QG; ++i) {
-            tcf[i] = (VK == LINR_VK_I8_SCALED && MAGIC) ? thr_lo[i] : thr_f[i];
+            tcf[i] = (VK == LINR_VK_I8_SCALED && MAGIC) ? thr_lo[i] : thr_f[i];      // thr_lo: see below
             tci[i] = (VK == LINR_VK_I8_SCALED && !MAGIC) ? int_bound(thr_f[i], smax) : thr_i[i];
         }
 
@@ -575,15 +594,15 @@ scan_kernel(linr_scan_args A)
             for (int ks = 0; ks < KS; ++ks) a[ks] = L.a[t * KS + ks][lane];
             const int ib = t * 16 + 4 * g4;              // first of this lane's four items in the chunk
             v4f sc4 = {0, 0, 0, 0}, u4 = {0, 0, 0, 0};
+            float smax4 = 0.0f, umax4 = 0.0f;
             if constexpr (MAGIC) {
                 sc4 = *(const v4f*)&L.sc[ib];
-                u4 = sc4 * LINR_MAGIC_U;
+                if constexpr (PRED_A) u4 = sc4 * LINR_MAGIC_U;
+                else { smax4 = fmaxf(fmaxf(sc4[0], sc4[1]), fmaxf(sc4[2], sc4[3])); umax4 = smax4 * LINR_MAGIC_U; }
             }
-            v4u mk4 = {0, 0, 0, 0}, ts4 = {0, 0, 0, 0};
-            if constexpr (PRED_A) {
-                mk4 = *(const v4u*)&L.mk[ib];
-                if constexpr (TS) ts4 = *(const v4u*)&L.ts[ib];
-            }
+            const v4u mk4 = *(const v4u*)&L.mk[ib];
+            v4u ts4 = {0, 0, 0, 0};
+            if constexpr (PRED_A && TS) ts4 = *(const v4u*)&L.ts[ib];
             // all matrix products of the tile first, then one branch-free pass of stage A over the groups
             acc_t acc[QG];
 #pragma unroll
@@ -608,23 +627,23 @@ scan_kernel(linr_scan_args A)
                     hot[i] = wave_ballot(tile_hot_pred<VK, MAGIC, TS>(acc[i], tcf[i], tci[i], sc4, u4, mk4, ts4, f_all[i], f_none[i],
                                                                    f_t0[i], f_t1[i]));
                 else
-                    hot[i] = wave_ballot(tile_hot<VK, MAGIC>(acc[i], tcf[i], tci[i], sc4, u4));
+                    hot[i] = wave_ballot(tile_hot<VK, MAGIC>(acc[i], tcf[i], tci[i], smax4, umax4));
                 any_hot |= hot[i];
             }
             if (any_hot) {
 #pragma unroll
                 for (int i = 0; i < QG; ++i)
                     if (hot[i])
-                        tile_survivors<VK, MAGIC, CH>(acc[i], qs, i * 16 + row, q_first + i * 16 + row, ib, item0, L.sc, L.mk, L.ts,
-                                                      A, slot, has_ts, need_compact);
+                        tile_survivors<VK, MAGIC, CH>(acc[i], (hot[i] >> lane) & 1ull, mk4, f_all[i], f_none[i], qs, i * 16 + row,
+                                                      q_first + i * 16 + row, ib, item0, L.sc, L.ts, A, slot, has_ts, need_compact);
             }
         }
         wave_sync();
 
         bool refresh = ++since_refresh >= 16;
-        if (wave_any(need_compact)) {
+        if (wave_any(need_compact != 0u)) {
             compact_full_segments<CH>(A, qs, slot, q_first, NQ, (uint32_t*)&L.a[0][0], lane);
-            need_compact = false;
+            need_compact = 0u;
             refresh = true;
         }
         if (refresh) {
@@ -632,7 +651,8 @@ scan_kernel(linr_scan_args A)
             wave_sync();
 #pragma unroll
             for (int i = 0; i < QG; ++i) {
-                thr_f[i] = W.thr_f[i * 16 + row]; thr_i[i] = W.thr_i[i * 16 + row]; thr_lo[i] = lowered(thr_f[i]);
+                thr_f[i] = W.thr_f[i * 16 + row]; thr_i[i] = W.thr_i[i * 16 + row];
+                thr_lo[i] = PRED_A ? lowered(thr_f[i]) : lowered_pos(thr_f[i]);
             }
             since_refresh = 0;
         }
@@ -763,17 +783,20 @@ __global__ void __launch_bounds__(64 * WPB, (QG * M * KS <= 2 ? 4 : QG * M * KS 
     wave_sync();
     float tcf[QG];            // lane l tracks query row l%16 of each group; already in stage A's form
     int tci[QG];
+    uint32_t f_all[QG], f_none[QG];
 #pragma unroll
     for (int i = 0; i < QG; ++i) {
-        tcf[i] = MAGIC ? lowered(W.thr_f[i * 16 + row]) : W.thr_f[i * 16 + row];
+        tcf[i] = MAGIC ? lowered_pos(W.thr_f[i * 16 + row]) : W.thr_f[i * 16 + row];
         tci[i] = W.thr_i[i * 16 + row];
+        f_all[i] = W.fall[i * 16 + row]; f_none[i] = W.fnone[i * 16 + row];
     }
 
     CoopRegs<VK, KS> R;
     R.rsc = R.rmk = R.rts = 0u;
-    bool need_compact = false;
+    uint32_t need_compact = 0u;
     uint32_t since_refresh = 0;
-    const acc_t acc0 = MAGIC ? (acc_t){LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS} : (acc_t){0, 0, 0, 0};
+    acc_t acc0 = MAGIC ? (acc_t){LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS} : (acc_t){0, 0, 0, 0};
+    pin(acc0);
     u64 lc = slot;
     if (lc < A.n_level_chunks) issue_coop<VK, KS>(R, A, lc, lane, wib, has_ts);
     int buf = 0;
@@ -793,11 +816,13 @@ __global__ void __launch_bounds__(64 * WPB, (QG * M * KS <= 2 ? 4 : QG * M * KS 
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) a[ks] = C.a[t * KS + ks][lane];
                 const int ib = t * 16 + 4 * g4;
-                v4f sc4 = {0, 0, 0, 0}, u4 = {0, 0, 0, 0};
+                float smax4 = 0.0f, umax4 = 0.0f;
                 if constexpr (MAGIC) {
-                    sc4 = *(const v4f*)&C.sc[ib];
-                    u4 = sc4 * LINR_MAGIC_U;
+                    v4f sc4 = *(const v4f*)&C.sc[ib];
+                    smax4 = fmaxf(fmaxf(sc4[0], sc4[1]), fmaxf(sc4[2], sc4[3]));
+                    umax4 = smax4 * LINR_MAGIC_U;
                 }
+                const v4u mk4 = *(const v4u*)&C.mk[ib];
                 acc_t acc[QG];
 #pragma unroll
                 for (int i = 0; i < QG; ++i) {
@@ -817,21 +842,21 @@ __global__ void __launch_bounds__(64 * WPB, (QG * M * KS <= 2 ? 4 : QG * M * KS 
                 u64 any_hot = 0;
 #pragma unroll
                 for (int i = 0; i < QG; ++i) {
-                    hot[i] = wave_ballot(tile_hot<VK, MAGIC>(acc[i], tcf[i], tci[i], sc4, u4));
+                    hot[i] = wave_ballot(tile_hot<VK, MAGIC>(acc[i], tcf[i], tci[i], smax4, umax4));
                     any_hot |= hot[i];
                 }
                 if (any_hot) {
 #pragma unroll
                     for (int i = 0; i < QG; ++i)
                         if (hot[i])
-                            tile_survivors<VK, MAGIC, CH>(acc[i], qs, i * 16 + row, q_first + i * 16 + row, ib, item0, C.sc, C.mk,
-                                                          C.ts, A, slot, has_ts, need_compact);
+                            tile_survivors<VK, MAGIC, CH>(acc[i], (hot[i] >> lane) & 1ull, mk4, f_all[i], f_none[i], qs, i * 16 + row,
+                                                          q_first + i * 16 + row, ib, item0, C.sc, C.ts, A, slot, has_ts, need_compact);
                 }
             }
             bool refresh = ++since_refresh >= 16;
-            if (wave_any(need_compact)) {
+            if (wave_any(need_compact != 0u)) {
                 compact_full_segments<CH>(A, qs, slot, q_first, NQ, hist_all[wib], lane);
-                need_compact = false;
+                need_compact = 0u;
                 refresh = true;
             }
             if (refresh) {
@@ -839,7 +864,7 @@ __global__ void __launch_bounds__(64 * WPB, (QG * M * KS <= 2 ? 4 : QG * M * KS 
                 wave_sync();
 #pragma unroll
                 for (int i = 0; i < QG; ++i) {
-                    tcf[i] = MAGIC ? lowered(W.thr_f[i * 16 + row]) : W.thr_f[i * 16 + row];
+                    tcf[i] = MAGIC ? lowered_pos(W.thr_f[i * 16 + row]) : W.thr_f[i * 16 + row];
                     tci[i] = W.thr_i[i * 16 + row];
                 }
                 since_refresh = 0;
@@ -898,10 +923,11 @@ __global__ void __launch_bounds__(64 * WPB) scan_kernel_lds(linr_scan_args A)
 
     ChunkRegs<VK, KS> R;
     R.rsc[0] = R.rsc[1] = R.rmk[0] = R.rmk[1] = R.rts[0] = R.rts[1] = 0u;
-    bool need_compact = false;
+    uint32_t need_compact = 0u;
     u64 lc = slot;
     if (lc < A.n_level_chunks) issue_chunk<VK, KS>(R, A, lc, lane, has_ts);
-    const acc_t acc0 = MAGIC ? (acc_t){LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS} : (acc_t){0, 0, 0, 0};
+    acc_t acc0 = MAGIC ? (acc_t){LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS} : (acc_t){0, 0, 0, 0};
+    pin(acc0);
 
     while (lc < A.n_level_chunks) {
         const u64 item0 = lc * A.stride * CH;
@@ -915,11 +941,13 @@ __global__ void __launch_bounds__(64 * WPB) scan_kernel_lds(linr_scan_args A)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) a[ks] = L.a[t * KS + ks][lane];
             const int ib = t * 16 + 4 * g4;
-            v4f sc4 = {0, 0, 0, 0}, u4 = {0, 0, 0, 0};
+            float smax4 = 0.0f, umax4 = 0.0f;
             if constexpr (MAGIC) {
-                sc4 = *(const v4f*)&L.sc[ib];
-                u4 = sc4 * LINR_MAGIC_U;
+                v4f sc4 = *(const v4f*)&L.sc[ib];
+                smax4 = fmaxf(fmaxf(sc4[0], sc4[1]), fmaxf(sc4[2], sc4[3]));
+                umax4 = smax4 * LINR_MAGIC_U;
             }
+            const v4u mk4 = *(const v4u*)&L.mk[ib];
 #pragma unroll 1
             for (uint32_t sg = 0; sg < nsg; ++sg) {
                 acc_t acc;
@@ -939,18 +967,20 @@ __global__ void __launch_bounds__(64 * WPB) scan_kernel_lds(linr_scan_args A)
                 float tf = qs.thr_f[qi];
                 int tc = qs.thr_i[qi];
                 if constexpr (VK == LINR_VK_I8_SCALED) {
-                    if constexpr (MAGIC) tf = lowered(tf);
+                    if constexpr (MAGIC) tf = lowered_pos(tf);
                     else tc = int_bound(tf, smax);
                 }
-                if (wave_any(tile_hot<VK, MAGIC>(acc, tf, tc, sc4, u4)))
-                    tile_survivors<VK, MAGIC, CH>(acc, qs, qi, qi, ib, item0, L.sc, L.mk, L.ts, A, slot, has_ts, need_compact);
+                const bool lane_hot = tile_hot<VK, MAGIC>(acc, tf, tc, smax4, umax4);
+                if (wave_any(lane_hot))
+                    tile_survivors<VK, MAGIC, CH>(acc, lane_hot, mk4, qs.fall[qi], qs.fnone[qi], qs, qi, qi, ib, item0, L.sc, L.ts, A,
+                                                  slot, has_ts, need_compact);
             }
         }
         wave_sync();
 
-        if (wave_any(need_compact)) {
+        if (wave_any(need_compact != 0u)) {
             compact_full_segments<CH>(A, qs, slot, 0, nq16, (uint32_t*)&L.a[0][0], lane);
-            need_compact = false;
+            need_compact = 0u;
             // publish the raised bounds to the workgroup (monotone, so a racing reader is only conservative)
             for (uint32_t ql = lane; ql < nq16; ql += 64) load_query_side(qs, ql, ql, A, false);
             wave_sync();
