@@ -155,7 +155,7 @@ int linr_last_hip_error(void);
 
 /*
  * Launch-shape knobs for tests and tuning (process-wide; 0 = library default).
- *   sample_ratio   : factor between the item counts of successive threshold-seeding
+ *   sample_ratio   : factor between the item counts covered after successive early
  *                    sweeps (power of two >= 2);
  *   min_sample     : smallest first sweep, in items;
  *   blocks_per_cu  : persistent workgroups per compute unit for the scan;
@@ -164,10 +164,12 @@ int linr_last_hip_error(void);
  *   max_qg         : cap on the 16-query groups one wave keeps in registers (larger
  *                    batches are then split over several waves per chunk);
  *   no_coop        : 1 = never use the workgroup-cooperative scan kernel;
- *   coop_min_groups: use that kernel for batches of more than this many 16-query groups.
+ *   coop_min_groups: use that kernel for batches of more than this many 16-query groups;
+ *   no_top_split   : 1 = do not split the last sweep into the finer 1/8, 3/8, 1/2 sweeps.
  */
 typedef struct {
     uint32_t sample_ratio, min_sample, blocks_per_cu, max_levels, force_generic, max_qg, no_coop, coop_min_groups;
+    uint32_t no_top_split, _r1, _r2, _r3;
 } linr_tuning;
 int linr_set_tuning(const linr_tuning*);
 

@@ -8,7 +8,7 @@
 #include <new>
 
 static thread_local int g_last_hip = 0;
-static linr_tuning g_tuning = {0, 0, 0, 0, 0, 0, 0, 0};
+static linr_tuning g_tuning = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
 #define HIP_TRY(expr)                                   \
     do {                                                \
@@ -253,22 +253,30 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
         grid = (p->nsplit + LINR_WAVES_PER_BLOCK - 1) / LINR_WAVES_PER_BLOCK;
         nslots = 1;
     }
-    if (nslots > LINR_MAX_SLOTS) nslots = LINR_MAX_SLOTS;
+    if (nslots > LINR_MAX_SLOTS - 1) nslots = LINR_MAX_SLOTS - 1;     // one more segment per query carries keys between sweeps
     p->grid = (uint32_t)grid;
     p->nslots = (uint32_t)nslots;
     p->cap = (uint32_t)align_up((uint64_t)k + p->chunk_items, 64);
 
-    // sweeps: the last visits every chunk; each earlier one a 1/ratio subsample of the next
+    // Sweeps, coarse to fine.  Sweep l visits the chunks whose index is a multiple of stride[l] but not of
+    // stride[l-1] (those were visited before), so every chunk is scored exactly once per search; the k best keys
+    // found so far are carried from merge to merge and the k-th of them bounds the next sweep.  A sweep that
+    // multiplies the number of visited items by r lets about k * (r - 1) / pass_rate items per query through
+    // its score test, so the last, largest sweeps use small factors (2, 4, 4) and the early, tiny ones a big one.
     uint32_t ratio = g_tuning.sample_ratio ? g_tuning.sample_ratio : 32;
     uint64_t min_sample = g_tuning.min_sample ? g_tuning.min_sample : (uint64_t)4 * k;
     uint32_t max_levels = g_tuning.max_levels ? g_tuning.max_levels : LINR_MAX_LEVELS;
     if (max_levels > LINR_MAX_LEVELS) max_levels = LINR_MAX_LEVELS;
+    // (kernels that already fold the predicate into their first test gain nothing from the finer split)
+    const bool top_split = !g_tuning.no_top_split && p->n_chunks >= 65536 && (p->coop || p->generic || p->qg > 2);
+    static const uint32_t top_ratios[3] = {2, 4, 4};
     uint32_t strides[LINR_MAX_LEVELS];
     uint32_t nl = 0;
     uint64_t s = 1;
     strides[nl++] = 1;
     while (nl < max_levels) {
-        uint64_t s2 = s * ratio;
+        uint32_t r = (top_split && nl - 1 < 3) ? top_ratios[nl - 1] : ratio;
+        uint64_t s2 = s * r;
         uint64_t items = (p->n_chunks / s2) * p->chunk_items;
         if (s2 > 0x40000000ull || items < min_sample) break;
         strides[nl++] = (uint32_t)s2;
@@ -276,12 +284,13 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
     }
     p->nlevels = nl;
     for (uint32_t l = 0; l < nl; ++l) p->stride[l] = strides[nl - 1 - l];
+    for (uint32_t l = 0; l < nl; ++l) p->skip_mod[l] = l == 0 ? 0u : p->stride[l - 1] / p->stride[l];
 
     uint64_t off = 0;
     p->off_tau = off;      off = align_up(off + (uint64_t)Bp * 8, 256);
-    p->off_cnt = off;      off = align_up(off + (uint64_t)Bp * p->nslots * 4, 256);
+    p->off_cnt = off;      off = align_up(off + (uint64_t)Bp * (p->nslots + 1) * 4, 256);
     p->off_filters = off;  off = align_up(off + (uint64_t)Bp * sizeof(linr_filter), 256);
-    p->off_seg = off;      off = align_up(off + (uint64_t)p->nslots * Bp * p->cap * 8, 256);
+    p->off_seg = off;      off = align_up(off + (uint64_t)(p->nslots + 1) * Bp * p->cap * 8, 256);
     p->total_bytes = off;
     return LINR_OK;
 }
@@ -357,7 +366,7 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
             use_filt = dfilt;
         }
         HIP_TRY(ev(0, LINR_STAGE_INIT, 0));
-        HIP_TRY(linr_launch_init(tau, cnt, (uint64_t)Bp * pp.nslots, Bp, st));
+        HIP_TRY(linr_launch_init(tau, cnt, (uint64_t)Bp * (pp.nslots + 1), Bp, st));
         HIP_TRY(ev(1, LINR_STAGE_INIT, 0));
 
         linr_scan_args sa;
@@ -366,11 +375,11 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
         sa.n = ix->n; sa.row_bytes = ix->row_bytes;
         sa.Q = (const char*)Q + (uint64_t)b0 * m * ix->row_bytes; sa.B = Bp; sa.m = m;
         sa.filters = use_filt; sa.tau = tau; sa.cnt = cnt; sa.seg = seg;
-        sa.nslots = pp.nslots; sa.cap = pp.cap; sa.nsplit = pp.nsplit; sa.k = k;
+        sa.nslots = pp.nslots; sa.cap = pp.cap; sa.nsplit = pp.nsplit; sa.k = k; sa.cnt_stride = pp.nslots + 1;
 
         linr_merge_args ma;
         memset(&ma, 0, sizeof(ma));
-        ma.tau = tau; ma.cnt = cnt; ma.seg = seg; ma.nslots = pp.nslots; ma.cap = pp.cap; ma.B = Bp; ma.k = k;
+        ma.tau = tau; ma.cnt = cnt; ma.seg = seg; ma.nslots = pp.nslots + 1; ma.cap = pp.cap; ma.B = Bp; ma.k = k;
         ma.dtype = ix->dtype; ma.vk = pp.vk; ma.emb = ix->emb; ma.row_scale = ix->row_scale;
         ma.row_bytes = ix->row_bytes; ma.d = ix->d; ma.Q = sa.Q; ma.q_scale = q_scale ? q_scale + b0 : nullptr; ma.m = m;
         ma.out_ids = out_ids + (uint64_t)b0 * k; ma.out_scores = out_scores + (uint64_t)b0 * k;
@@ -378,8 +387,10 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
 
         for (uint32_t l = 0; l < pp.nlevels; ++l) {
             sa.stride = pp.stride[l];
-            sa.n_level_chunks = (pp.n_chunks + sa.stride - 1) / sa.stride;
-            uint64_t items = sa.n_level_chunks * pp.chunk_items;
+            sa.skip_mod = pp.skip_mod[l];
+            const uint64_t n_lc = (pp.n_chunks + sa.stride - 1) / sa.stride;
+            sa.n_dense = sa.skip_mod ? n_lc - (n_lc + sa.skip_mod - 1) / sa.skip_mod : n_lc;
+            uint64_t items = sa.n_dense * pp.chunk_items;
             if (items > ix->n) items = ix->n;
             HIP_TRY(ev(0, LINR_STAGE_SCAN, items));
             HIP_TRY(linr_launch_scan(pp, ix->dtype, sa, st));

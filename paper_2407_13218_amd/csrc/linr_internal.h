@@ -45,7 +45,8 @@ struct linr_plan {
     uint32_t cap;               // entries per (slot, query) candidate segment
     uint32_t max_batch;         // queries per pass
     uint32_t nlevels;
-    uint32_t stride[LINR_MAX_LEVELS];   // level l visits chunks c with c % stride[l] == 0; last is 1
+    uint32_t stride[LINR_MAX_LEVELS];   // sweep l visits chunks c = lc * stride[l]; the last stride is 1
+    uint32_t skip_mod[LINR_MAX_LEVELS]; // ... except level indices lc that are multiples of this (0: visit all)
     uint64_t n_chunks;
     // workspace layout (byte offsets)
     uint64_t off_tau, off_cnt, off_filters, off_seg, total_bytes;
@@ -57,15 +58,19 @@ struct linr_scan_args {
     const void* Q; uint32_t B; uint32_t m;
     const linr_filter* filters;
     unsigned long long* tau;     // [B] best-known lower bound of each query's k-th key (0 = none)
-    uint32_t* cnt;              // [B][nslots]
-    unsigned long long* seg;     // [nslots][B][cap]
+    uint32_t* cnt;              // [B][nslots + 1]
+    unsigned long long* seg;     // [nslots + 1][B][cap]; segment nslots carries the best keys of earlier sweeps
     uint32_t nslots, cap, nsplit, k;
-    uint64_t n_level_chunks; uint32_t stride;
+    uint64_t n_dense;           // chunks this sweep visits
+    uint32_t stride;            // chunk stride of this sweep
+    uint32_t skip_mod;          // level indices that are multiples of this were visited by earlier sweeps (0: none)
+    uint32_t cnt_stride;        // row length of cnt (nslots + 1: the last entry counts the carried keys)
 };
 
 struct linr_merge_args {
-    unsigned long long* tau; uint32_t* cnt; const unsigned long long* seg;
-    uint32_t nslots, cap, B, k;
+    unsigned long long* tau; uint32_t* cnt; unsigned long long* seg;
+    uint32_t nslots;            // segments per query INCLUDING the carry segment (the last one)
+    uint32_t cap, B, k;
     int final_level;
     // finalisation (final level only)
     int dtype, vk;

@@ -184,6 +184,28 @@ __device__ __forceinline__ void wave_compact_segment(u64* base, uint32_t* cnt_p,
 // Scan building blocks shared by the register-resident-query kernel and the kernel
 // that streams query fragments from LDS.
 // ---------------------------------------------------------------------------
+// Position of one chunk-slot inside a sweep.  A sweep with chunk stride S visits the chunks
+// c = lc * S whose level index lc is NOT a multiple of skip_mod (those belonged to earlier, coarser
+// sweeps; skip_mod == 0: visit every lc).  `di` enumerates the visited chunks densely; slot s takes
+// di = s, s + nslots, ...  The (q, r) pair tracks di / (skip_mod-1), di % (skip_mod-1) incrementally.
+struct SweepWalk {
+    uint32_t di, n_dense, step, mod, m1, q, r, step_q, step_r;
+    __device__ __forceinline__ void init(uint32_t slot, const linr_scan_args& A)
+    {
+        di = slot; n_dense = (uint32_t)A.n_dense; step = A.nslots; mod = A.skip_mod;
+        m1 = mod ? mod - 1 : 1; q = r = step_q = step_r = 0;
+        if (mod) { q = di / m1; r = di % m1; step_q = step / m1; step_r = step % m1; }
+    }
+    __device__ __forceinline__ bool valid() const { return di < n_dense; }
+    __device__ __forceinline__ u64 lc() const { return mod ? (u64)q * mod + r + 1 : (u64)di; }
+    __device__ __forceinline__ void advance()
+    {
+        di = (di + step < di) ? 0xFFFFFFFFu : di + step;      // saturate instead of wrapping
+        q += step_q; r += step_r;
+        if (r >= m1) { r -= m1; ++q; }
+    }
+};
+
 template <int VK, int KS>
 struct ChunkRegs {
     v4i ra[8];                 // 8 KB of rows in MFMA operand layout
@@ -567,12 +589,14 @@ scan_kernel(linr_scan_args A)
     R.rsc[0] = R.rsc[1] = R.rmk[0] = R.rmk[1] = R.rts[0] = R.rts[1] = 0u;
     uint32_t need_compact = 0u;
     uint32_t since_refresh = 0;
-    u64 lc = slot;
-    if (lc < A.n_level_chunks) issue_chunk<VK, KS>(R, A, lc, lane, has_ts);
+    SweepWalk walk;
+    walk.init(slot, A);
+    u64 lc = walk.lc();
+    if (walk.valid()) issue_chunk<VK, KS>(R, A, lc, lane, has_ts);
     acc_t acc0 = MAGIC ? (acc_t){LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS} : (acc_t){0, 0, 0, 0};
     pin(acc0);
 
-    while (lc < A.n_level_chunks) {
+    while (walk.valid()) {
         const u64 item0 = lc * A.stride * CH;
         const float smax = stage_chunk<VK, KS, (VK == LINR_VK_I8_SCALED && !MAGIC)>(R, L, lane, has_ts);
         // bounds in the form stage A compares against
@@ -584,8 +608,9 @@ scan_kernel(linr_scan_args A)
             tci[i] = (VK == LINR_VK_I8_SCALED && !MAGIC) ? int_bound(thr_f[i], smax) : thr_i[i];
         }
 
-        const u64 nlc = lc + A.nslots;
-        if (nlc < A.n_level_chunks) issue_chunk<VK, KS>(R, A, nlc, lane, has_ts);     // in flight while scoring
+        walk.advance();
+        const u64 nlc = walk.lc();
+        if (walk.valid()) issue_chunk<VK, KS>(R, A, nlc, lane, has_ts);               // in flight while scoring
 
 #pragma unroll 1
         for (int t = 0; t < TPC; ++t) {
@@ -661,7 +686,7 @@ scan_kernel(linr_scan_args A)
     // publish this wave's segment sizes
     for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) {
         uint32_t qi = q_first + ql;
-        if (qi < A.B) A.cnt[(u64)qi * A.nslots + slot] = W.cnt[ql];
+        if (qi < A.B) A.cnt[(u64)qi * A.cnt_stride + slot] = W.cnt[ql];
     }
 }
 
@@ -797,17 +822,20 @@ __global__ void __launch_bounds__(64 * WPB, (QG * M * KS <= 2 ? 4 : QG * M * KS 
     uint32_t since_refresh = 0;
     acc_t acc0 = MAGIC ? (acc_t){LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS} : (acc_t){0, 0, 0, 0};
     pin(acc0);
-    u64 lc = slot;
-    if (lc < A.n_level_chunks) issue_coop<VK, KS>(R, A, lc, lane, wib, has_ts);
+    SweepWalk walk;
+    walk.init(slot, A);
+    u64 lc = walk.lc();
+    if (walk.valid()) issue_coop<VK, KS>(R, A, lc, lane, wib, has_ts);
     int buf = 0;
 
-    while (lc < A.n_level_chunks) {
+    while (walk.valid()) {
         const u64 item0 = lc * A.stride * CH;
         ChunkLds& C = chunk[buf];
         stage_coop<VK, KS>(R, C, lane, wib, has_ts);
         __syncthreads();
-        const u64 nlc = lc + A.nslots;
-        if (nlc < A.n_level_chunks) issue_coop<VK, KS>(R, A, nlc, lane, wib, has_ts);
+        walk.advance();
+        const u64 nlc = walk.lc();
+        if (walk.valid()) issue_coop<VK, KS>(R, A, nlc, lane, wib, has_ts);
 
         if (active) {
 #pragma unroll 1
@@ -876,7 +904,7 @@ __global__ void __launch_bounds__(64 * WPB, (QG * M * KS <= 2 ? 4 : QG * M * KS 
     if (active)
         for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) {
             uint32_t qi = q_first + ql;
-            if (qi < A.B) A.cnt[(u64)qi * A.nslots + slot] = W.cnt[ql];
+            if (qi < A.B) A.cnt[(u64)qi * A.cnt_stride + slot] = W.cnt[ql];
         }
 }
 
@@ -924,16 +952,19 @@ __global__ void __launch_bounds__(64 * WPB) scan_kernel_lds(linr_scan_args A)
     ChunkRegs<VK, KS> R;
     R.rsc[0] = R.rsc[1] = R.rmk[0] = R.rmk[1] = R.rts[0] = R.rts[1] = 0u;
     uint32_t need_compact = 0u;
-    u64 lc = slot;
-    if (lc < A.n_level_chunks) issue_chunk<VK, KS>(R, A, lc, lane, has_ts);
+    SweepWalk walk;
+    walk.init(slot, A);
+    u64 lc = walk.lc();
+    if (walk.valid()) issue_chunk<VK, KS>(R, A, lc, lane, has_ts);
     acc_t acc0 = MAGIC ? (acc_t){LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS, LINR_MAGIC_BITS} : (acc_t){0, 0, 0, 0};
     pin(acc0);
 
-    while (lc < A.n_level_chunks) {
+    while (walk.valid()) {
         const u64 item0 = lc * A.stride * CH;
         const float smax = stage_chunk<VK, KS, (VK == LINR_VK_I8_SCALED && !MAGIC)>(R, L, lane, has_ts);
-        const u64 nlc = lc + A.nslots;
-        if (nlc < A.n_level_chunks) issue_chunk<VK, KS>(R, A, nlc, lane, has_ts);
+        walk.advance();
+        const u64 nlc = walk.lc();
+        if (walk.valid()) issue_chunk<VK, KS>(R, A, nlc, lane, has_ts);
 
 #pragma unroll 1
         for (int t = 0; t < TPC; ++t) {
@@ -988,7 +1019,7 @@ __global__ void __launch_bounds__(64 * WPB) scan_kernel_lds(linr_scan_args A)
         lc = nlc;
     }
     for (uint32_t ql = lane; ql < nq16; ql += 64)
-        if (ql < A.B) A.cnt[(u64)ql * A.nslots + slot] = qs.cnt[ql];
+        if (ql < A.B) A.cnt[(u64)ql * A.cnt_stride + slot] = qs.cnt[ql];
 }
 
 // ---------------------------------------------------------------------------
@@ -1103,24 +1134,30 @@ __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
         kth = prefix;
     }
 
+    if (!A.final_level && tid == 0 && Mtot >= A.k) {
+        u64 cur = A.tau[b];
+        if (kth > cur) A.tau[b] = kth;
+    }
+
+    // 3. gather the winners (all candidates when there are fewer than k)
+    if (tid == 0) S.nwin = 0;
+    __syncthreads();
+    for (uint32_t f = tid; f < Mtot; f += MT) {
+        u64 key = merge_fetch(A, S, b, f);
+        if (key >= kth) {
+            uint32_t p = atomicAdd(&S.nwin, 1u);
+            if (p < LINR_MAX_K) S.win[p] = key;
+        }
+    }
+    __syncthreads();
+    const uint32_t nwin = S.nwin < A.k ? S.nwin : A.k;
+
     if (!A.final_level) {
-        if (tid == 0 && Mtot >= A.k) {
-            u64 cur = A.tau[b];
-            if (kth > cur) A.tau[b] = kth;
-        }
+        // carry them into the next sweep's merge: segment ns-1 of this query
+        u64* carry = A.seg + ((u64)(ns - 1) * A.B + b) * A.cap;
+        for (uint32_t j = tid; j < nwin; j += MT) carry[j] = S.win[j];
     } else {
-        // 3. gather the winners, sort them, write the outputs
-        if (tid == 0) S.nwin = 0;
-        __syncthreads();
-        for (uint32_t f = tid; f < Mtot; f += MT) {
-            u64 key = merge_fetch(A, S, b, f);
-            if (key >= kth) {
-                uint32_t p = atomicAdd(&S.nwin, 1u);
-                if (p < LINR_MAX_K) S.win[p] = key;
-            }
-        }
-        __syncthreads();
-        uint32_t nwin = S.nwin < A.k ? S.nwin : A.k;
+        // sort them, write the outputs
         uint32_t P = 1;
         while (P < nwin) P <<= 1;
         for (uint32_t j = nwin + tid; j < P; j += MT) S.win[j] = 0ull;
@@ -1167,8 +1204,8 @@ __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
         if (tid == 0) A.out_counts[b] = nwin;
     }
     __syncthreads();
-    // 4. leave the segments empty for the next sweep
-    for (uint32_t s = tid; s < ns; s += MT) cnt[s] = 0;
+    // 4. leave the scan segments empty for the next sweep; the carry segment holds the winners
+    for (uint32_t s = tid; s < ns; s += MT) cnt[s] = (s == ns - 1 && !A.final_level) ? nwin : 0u;
 }
 
 // ---------------------------------------------------------------------------
