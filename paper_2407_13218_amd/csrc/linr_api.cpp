@@ -253,7 +253,7 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
         grid = (p->nsplit + LINR_WAVES_PER_BLOCK - 1) / LINR_WAVES_PER_BLOCK;
         nslots = 1;
     }
-    if (nslots > LINR_MAX_SLOTS - 1) nslots = LINR_MAX_SLOTS - 1;     // one more segment per query carries keys between sweeps
+    if (nslots > LINR_MAX_SLOTS) nslots = LINR_MAX_SLOTS;
     p->grid = (uint32_t)grid;
     p->nslots = (uint32_t)nslots;
     p->cap = (uint32_t)align_up((uint64_t)k + p->chunk_items, 64);
@@ -263,7 +263,7 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
     // found so far are carried from merge to merge and the k-th of them bounds the next sweep.  A sweep that
     // multiplies the number of visited items by r lets about k * (r - 1) / pass_rate items per query through
     // its score test, so the last, largest sweeps use small factors (2, 4, 4) and the early, tiny ones a big one.
-    uint32_t ratio = g_tuning.sample_ratio ? g_tuning.sample_ratio : 32;
+    uint32_t ratio = g_tuning.sample_ratio ? g_tuning.sample_ratio : 8;
     uint64_t min_sample = g_tuning.min_sample ? g_tuning.min_sample : (uint64_t)4 * k;
     uint32_t max_levels = g_tuning.max_levels ? g_tuning.max_levels : LINR_MAX_LEVELS;
     if (max_levels > LINR_MAX_LEVELS) max_levels = LINR_MAX_LEVELS;
@@ -286,11 +286,21 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
     for (uint32_t l = 0; l < nl; ++l) p->stride[l] = strides[nl - 1 - l];
     for (uint32_t l = 0; l < nl; ++l) p->skip_mod[l] = l == 0 ? 0u : p->stride[l - 1] / p->stride[l];
 
+    // flat candidate array per query: the carried k keys plus what one sweep appends (about k * (factor - 1)
+    // per query when the bound is good), with room to spare; anything beyond it stays in the per-slot segments
+    uint64_t fc = (uint64_t)4 * ratio * k;
+    if (fc < 4096) fc = 4096;
+    p->flat_cap = (uint32_t)align_up(fc, LINR_FLAT_REGIONS);
     uint64_t off = 0;
     p->off_tau = off;      off = align_up(off + (uint64_t)Bp * 8, 256);
-    p->off_cnt = off;      off = align_up(off + (uint64_t)Bp * (p->nslots + 1) * 4, 256);
+    p->off_ccnt = off;     off = align_up(off + (uint64_t)Bp * 4, 256);
+    p->off_carry = off;    off = align_up(off + (uint64_t)Bp * k * 8, 256);
+    p->off_gcnt = off;     off = align_up(off + (uint64_t)Bp * LINR_FLAT_REGIONS * LINR_COUNTER_STRIDE * 4, 256);
+    p->off_fvalid = off;   off = align_up(off + (uint64_t)Bp * LINR_FLAT_REGIONS * LINR_COUNTER_STRIDE * 4, 256);
+    p->off_cnt = off;      off = align_up(off + (uint64_t)Bp * p->nslots * 4, 256);
     p->off_filters = off;  off = align_up(off + (uint64_t)Bp * sizeof(linr_filter), 256);
-    p->off_seg = off;      off = align_up(off + (uint64_t)(p->nslots + 1) * Bp * p->cap * 8, 256);
+    p->off_flat = off;     off = align_up(off + (uint64_t)Bp * p->flat_cap * 8, 256);
+    p->off_seg = off;      off = align_up(off + (uint64_t)p->nslots * Bp * p->cap * 8, 256);
     p->total_bytes = off;
     return LINR_OK;
 }
@@ -358,6 +368,11 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
         }
         unsigned long long* tau = (unsigned long long*)(ws + pp.off_tau);
         uint32_t* cnt = (uint32_t*)(ws + pp.off_cnt);
+        uint32_t* gcnt = (uint32_t*)(ws + pp.off_gcnt);
+        uint32_t* fvalid = (uint32_t*)(ws + pp.off_fvalid);
+        unsigned long long* flat = (unsigned long long*)(ws + pp.off_flat);
+        unsigned long long* carry = (unsigned long long*)(ws + pp.off_carry);
+        uint32_t* ccnt = (uint32_t*)(ws + pp.off_ccnt);
         linr_filter* dfilt = (linr_filter*)(ws + pp.off_filters);
         unsigned long long* seg = (unsigned long long*)(ws + pp.off_seg);
         const linr_filter* use_filt = filters + b0;
@@ -366,7 +381,7 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
             use_filt = dfilt;
         }
         HIP_TRY(ev(0, LINR_STAGE_INIT, 0));
-        HIP_TRY(linr_launch_init(tau, cnt, (uint64_t)Bp * (pp.nslots + 1), Bp, st));
+        HIP_TRY(linr_launch_init(tau, ccnt, gcnt, fvalid, cnt, (uint64_t)Bp * pp.nslots, Bp, st));
         HIP_TRY(ev(1, LINR_STAGE_INIT, 0));
 
         linr_scan_args sa;
@@ -375,11 +390,13 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
         sa.n = ix->n; sa.row_bytes = ix->row_bytes;
         sa.Q = (const char*)Q + (uint64_t)b0 * m * ix->row_bytes; sa.B = Bp; sa.m = m;
         sa.filters = use_filt; sa.tau = tau; sa.cnt = cnt; sa.seg = seg;
-        sa.nslots = pp.nslots; sa.cap = pp.cap; sa.nsplit = pp.nsplit; sa.k = k; sa.cnt_stride = pp.nslots + 1;
+        sa.nslots = pp.nslots; sa.cap = pp.cap; sa.nsplit = pp.nsplit; sa.k = k;
+        sa.gcnt = gcnt; sa.fvalid = fvalid; sa.flat = flat; sa.flat_cap = pp.flat_cap;
 
         linr_merge_args ma;
         memset(&ma, 0, sizeof(ma));
-        ma.tau = tau; ma.cnt = cnt; ma.seg = seg; ma.nslots = pp.nslots + 1; ma.cap = pp.cap; ma.B = Bp; ma.k = k;
+        ma.tau = tau; ma.cnt = cnt; ma.seg = seg; ma.nslots = pp.nslots; ma.cap = pp.cap; ma.B = Bp; ma.k = k;
+        ma.gcnt = gcnt; ma.fvalid = fvalid; ma.flat = flat; ma.flat_cap = pp.flat_cap; ma.carry = carry; ma.ccnt = ccnt;
         ma.dtype = ix->dtype; ma.vk = pp.vk; ma.emb = ix->emb; ma.row_scale = ix->row_scale;
         ma.row_bytes = ix->row_bytes; ma.d = ix->d; ma.Q = sa.Q; ma.q_scale = q_scale ? q_scale + b0 : nullptr; ma.m = m;
         ma.out_ids = out_ids + (uint64_t)b0 * k; ma.out_scores = out_scores + (uint64_t)b0 * k;

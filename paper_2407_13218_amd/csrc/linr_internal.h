@@ -6,9 +6,11 @@
 #include "linr.h"
 
 #define LINR_WAVES_PER_BLOCK 4
-#define LINR_MAX_LEVELS 8
+#define LINR_MAX_LEVELS 12
 #define LINR_MAX_SLOTS 4096          // merge kernel keeps one prefix entry per slot in LDS
 #define LINR_MAX_NSPLIT 16
+#define LINR_FLAT_REGIONS 64          // independently counted regions of a query's flat candidate array
+#define LINR_COUNTER_STRIDE 16        // words between two region counters (one 64-byte line each)
 
 // how the ranking value is held in the scan's accumulators
 enum { LINR_VK_FLOAT = 0,       // fp32 / bf16: fp32 accumulator is the ranking value
@@ -49,7 +51,8 @@ struct linr_plan {
     uint32_t skip_mod[LINR_MAX_LEVELS]; // ... except level indices lc that are multiples of this (0: visit all)
     uint64_t n_chunks;
     // workspace layout (byte offsets)
-    uint64_t off_tau, off_cnt, off_filters, off_seg, total_bytes;
+    uint32_t flat_cap;          // keys per query in the flat candidate array
+    uint64_t off_tau, off_ccnt, off_carry, off_gcnt, off_fvalid, off_cnt, off_filters, off_flat, off_seg, total_bytes;
 };
 
 struct linr_scan_args {
@@ -58,19 +61,24 @@ struct linr_scan_args {
     const void* Q; uint32_t B; uint32_t m;
     const linr_filter* filters;
     unsigned long long* tau;     // [B] best-known lower bound of each query's k-th key (0 = none)
-    uint32_t* cnt;              // [B][nslots + 1]
-    unsigned long long* seg;     // [nslots + 1][B][cap]; segment nslots carries the best keys of earlier sweeps
+    uint32_t* cnt;              // [B][nslots]: sizes of per-slot segments that could not be flushed
+    uint32_t* gcnt;             // [B][REGIONS] (strided) keys flushed into each region of the query's flat array
+    uint32_t* fvalid;           // [B][REGIONS] (strided) end of the valid part of a region if a wave could not flush, else ~0
+    unsigned long long* flat;   // [B][REGIONS][flat_cap / REGIONS]
+    uint32_t flat_cap;
+    unsigned long long* seg;     // [nslots][B][cap] per-(slot, query) candidate segments
     uint32_t nslots, cap, nsplit, k;
     uint64_t n_dense;           // chunks this sweep visits
     uint32_t stride;            // chunk stride of this sweep
     uint32_t skip_mod;          // level indices that are multiples of this were visited by earlier sweeps (0: none)
-    uint32_t cnt_stride;        // row length of cnt (nslots + 1: the last entry counts the carried keys)
 };
 
 struct linr_merge_args {
     unsigned long long* tau; uint32_t* cnt; unsigned long long* seg;
-    uint32_t nslots;            // segments per query INCLUDING the carry segment (the last one)
-    uint32_t cap, B, k;
+    uint32_t* gcnt; uint32_t* fvalid; unsigned long long* flat; uint32_t flat_cap;
+    unsigned long long* carry;  // [B][k] best keys of the sweeps so far
+    uint32_t* ccnt;             // [B] how many of them
+    uint32_t nslots, cap, B, k;
     int final_level;
     // finalisation (final level only)
     int dtype, vk;
@@ -80,7 +88,8 @@ struct linr_merge_args {
 };
 
 // kernels' host launchers (linr_kernels.hip)
-hipError_t linr_launch_init(unsigned long long* tau, uint32_t* cnt, uint64_t n_cnt, uint32_t B, hipStream_t s);
+hipError_t linr_launch_init(unsigned long long* tau, uint32_t* ccnt, uint32_t* gcnt, uint32_t* fvalid, uint32_t* cnt,
+                            uint64_t n_cnt, uint32_t B, hipStream_t s);
 hipError_t linr_launch_scan(const linr_plan& p, int dtype, const linr_scan_args& a, hipStream_t s);
 hipError_t linr_launch_merge(const linr_merge_args& a, hipStream_t s);
 // 1 if a register-resident-query scan kernel exists for this shape

@@ -55,6 +55,16 @@ __device__ __forceinline__ u64 aload64(const u64* p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// read back what this wave itself stored earlier (same compute unit, same L2: no device-wide flush needed)
+__device__ __forceinline__ u64 own_load64(const u64* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ void own_stores_done()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
 __device__ __forceinline__ uint32_t aload32(const uint32_t* p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -505,6 +515,58 @@ __device__ __forceinline__ void compact_full_segments(const linr_scan_args& A, c
     }
 }
 
+// End of a scan wave: move what it collected for each of its queries into the query's shared flat
+// array.  One atomic per non-empty segment reserves the range; the copy itself is done by the whole wave
+// over the concatenation of its segments (a prefix over the segment sizes in `scratch`, 2*nq+1 words of
+// LDS, tells each lane which segment its element belongs to), so all loads are independent.  If a range
+// does not fit, the wave records where the valid part of the flat array ends (fvalid) and leaves those
+// keys in the per-slot segment, whose count it publishes for the merge to pick up.
+__device__ __forceinline__ void flush_segments(const linr_scan_args& A, const QSide& qs, uint32_t slot, uint32_t q_first,
+                                               uint32_t nq, int lane, uint32_t* scratch)
+{
+    uint32_t* pre = scratch;               // [nq + 1] exclusive prefix of the sizes to copy
+    uint32_t* dstb = scratch + nq + 1;     // [nq] start of the reserved range in the flat array
+    uint32_t running = 0;
+    for (uint32_t q0 = 0; q0 < nq; q0 += 64) {
+        const uint32_t ql = q0 + lane, qi = q_first + ql;
+        uint32_t c = (ql < nq && qi < A.B) ? qs.cnt[ql] : 0u;
+        uint32_t base = 0;
+        if (c) {
+            // the flat array of a query is split into LINR_FLAT_REGIONS regions with one counter each (in its own
+            // 64-byte line), so that the waves of a sweep do not all hit one address
+            const uint32_t reg = slot % LINR_FLAT_REGIONS;
+            const u64 ci = ((u64)qi * LINR_FLAT_REGIONS + reg) * LINR_COUNTER_STRIDE;
+            base = atomicAdd(A.gcnt + ci, c);
+            if (base + c > A.flat_cap / LINR_FLAT_REGIONS) {
+                atomicMin(A.fvalid + ci, base);
+                A.cnt[(u64)qi * A.nslots + slot] = c;
+                c = 0;
+            }
+            base += reg * (A.flat_cap / LINR_FLAT_REGIONS);
+        }
+        uint32_t incl = c;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            uint32_t v = __shfl_up(incl, o);
+            if (lane >= o) incl += v;
+        }
+        if (ql < nq) { pre[ql] = running + incl - c; dstb[ql] = base; }
+        running += __shfl(incl, 63);
+    }
+    if (lane == 0) pre[nq] = running;
+    wave_sync();
+    for (uint32_t t = lane; t < running; t += 64) {
+        uint32_t lo = 0, hi = nq;
+        while (hi - lo > 1) {
+            uint32_t mid = (lo + hi) >> 1;
+            if (pre[mid] <= t) lo = mid; else hi = mid;
+        }
+        const uint32_t j = t - pre[lo], qi = q_first + lo;
+        const u64 key = own_load64(A.seg + ((u64)slot * A.B + qi) * A.cap + j);
+        A.flat[(u64)qi * A.flat_cap + dstb[lo] + j] = key;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // scan kernel, queries register resident
 //   DT element type, VK ranking-value kind, KS 64-byte K-steps per row,
@@ -683,11 +745,8 @@ scan_kernel(linr_scan_args A)
         }
         lc = nlc;
     }
-    // publish this wave's segment sizes
-    for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) {
-        uint32_t qi = q_first + ql;
-        if (qi < A.B) A.cnt[(u64)qi * A.cnt_stride + slot] = W.cnt[ql];
-    }
+    own_stores_done();
+    flush_segments(A, qs, slot, q_first, NQ, lane, (uint32_t*)&L);       // the chunk staging area is free now
 }
 
 // ---------------------------------------------------------------------------
@@ -901,11 +960,10 @@ __global__ void __launch_bounds__(64 * WPB, (QG * M * KS <= 2 ? 4 : QG * M * KS 
         lc = nlc;
         buf ^= 1;
     }
-    if (active)
-        for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) {
-            uint32_t qi = q_first + ql;
-            if (qi < A.B) A.cnt[(u64)qi * A.cnt_stride + slot] = W.cnt[ql];
-        }
+    if (active) {
+        own_stores_done();
+        flush_segments(A, qs, slot, q_first, NQ, lane, hist_all[wib]);   // 2 * NQ + 1 <= 256 words
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -1018,42 +1076,82 @@ __global__ void __launch_bounds__(64 * WPB) scan_kernel_lds(linr_scan_args A)
         }
         lc = nlc;
     }
-    for (uint32_t ql = lane; ql < nq16; ql += 64)
-        if (ql < A.B) A.cnt[(u64)ql * A.cnt_stride + slot] = qs.cnt[ql];
+    own_stores_done();
+    flush_segments(A, qs, slot, 0, nq16, lane, (uint32_t*)&L);           // 2 * nq16 + 1 words <= the staging area
 }
 
 // ---------------------------------------------------------------------------
-// init: no bound yet, all segments empty
+// init: no bound yet, nothing carried, all segments empty
 // ---------------------------------------------------------------------------
-__global__ void init_kernel(u64* tau, uint32_t* cnt, u64 n_cnt, uint32_t B)
+__global__ void init_kernel(u64* tau, uint32_t* ccnt, uint32_t* gcnt, uint32_t* fvalid, uint32_t* cnt, u64 n_cnt, uint32_t B)
 {
     u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
     u64 stride = (u64)gridDim.x * blockDim.x;
     for (u64 j = i; j < n_cnt; j += stride) cnt[j] = 0;
-    for (u64 j = i; j < B; j += stride) tau[j] = 0;
+    for (u64 j = i; j < B; j += stride) { tau[j] = 0; ccnt[j] = 0; }
+    const u64 nreg = (u64)B * LINR_FLAT_REGIONS;
+    for (u64 j = i; j < nreg; j += stride) { gcnt[j * LINR_COUNTER_STRIDE] = 0; fvalid[j * LINR_COUNTER_STRIDE] = 0xFFFFFFFFu; }
 }
 
 // ---------------------------------------------------------------------------
-// merge kernel: one workgroup of 1024 lanes per query
+// merge kernel: one workgroup of 1024 lanes per query.
+// Candidates of query b: the keys carried from the previous merge (carry[b][0 .. ccnt[b])), the regions of
+// its flat array that the scan waves flushed into, and -- only if some wave could not flush (a region's
+// fvalid was lowered) -- the per-slot segments.  Exact selection of the k best: 8-bit radix select (keys are
+// distinct), then either carry them to the next sweep (and publish the k-th as its bound) or sort and write
+// the result.
 // ---------------------------------------------------------------------------
 #define MT 1024
+#define MERGE_LDS_KEYS 8192
+#define NPIECE (LINR_FLAT_REGIONS + 1)
 struct MergeLds {
-    uint32_t pre[LINR_MAX_SLOTS + 1];     // exclusive prefix of segment counts
+    union {
+        u64 keys[MERGE_LDS_KEYS];                 // all candidates, when they fit and nothing was spilled
+        uint32_t pre[LINR_MAX_SLOTS + 1];         // exclusive prefix of segment counts (spilled case)
+    } u;
+    u64 win[LINR_MAX_K];
     uint32_t part[MT];
     uint32_t hist[256];
-    u64 win[LINR_MAX_K];
-    uint32_t nwin, bsel, above, done;
+    uint32_t ppre[NPIECE + 1];                    // exclusive prefix over carry + flat regions
+    uint32_t nwin, bsel, above, done, spilled;
 };
 
-__device__ __forceinline__ u64 merge_fetch(const linr_merge_args& A, const MergeLds& S, uint32_t b, uint32_t f)
+enum { MERGE_FROM_LDS = 0, MERGE_FROM_FLAT = 1, MERGE_FROM_ALL = 2 };
+
+// start of piece p of query b (piece 0: carried keys, piece r + 1: region r of the flat array)
+__device__ __forceinline__ const u64* piece_ptr(const linr_merge_args& A, uint32_t b, uint32_t p)
 {
-    // segment s with pre[s] <= f < pre[s+1]
-    uint32_t lo = 0, hi = A.nslots;
-    while (hi - lo > 1) {
-        uint32_t mid = (lo + hi) >> 1;
-        if (S.pre[mid] <= f) lo = mid; else hi = mid;
+    if (p == 0) return A.carry + (u64)b * A.k;
+    return A.flat + (u64)b * A.flat_cap + (u64)(p - 1) * (A.flat_cap / LINR_FLAT_REGIONS);
+}
+
+// Calls f(key) once for every candidate of the query, by the whole workgroup.  From LDS when they were
+// staged there; else wave w walks pieces w, w + 16, ... with consecutive lanes on consecutive keys; the
+// per-slot segments (spilled case only) are located through the prefix array.
+template <typename F>
+__device__ __forceinline__ void for_each_candidate(const linr_merge_args& A, const MergeLds& S, int mode, uint32_t m_flat,
+                                                   uint32_t Mtot, uint32_t b, uint32_t tid, F f)
+{
+    if (mode == MERGE_FROM_LDS) {
+        for (uint32_t i = tid; i < m_flat; i += MT) f(S.u.keys[i]);
+        return;
     }
-    return A.seg[((u64)lo * A.B + b) * A.cap + (f - S.pre[lo])];
+    const uint32_t wave = tid >> 6, lane = tid & 63;
+    for (uint32_t p = wave; p < NPIECE; p += MT / 64) {
+        const uint32_t c = S.ppre[p + 1] - S.ppre[p];
+        const u64* src = piece_ptr(A, b, p);
+        for (uint32_t j = lane; j < c; j += 64) f(src[j]);
+    }
+    if (mode == MERGE_FROM_ALL) {
+        for (uint32_t g = tid; g < Mtot - m_flat; g += MT) {
+            uint32_t lo = 0, hi = A.nslots;
+            while (hi - lo > 1) {
+                uint32_t mid = (lo + hi) >> 1;
+                if (S.u.pre[mid] <= g) lo = mid; else hi = mid;
+            }
+            f(A.seg[((u64)lo * A.B + b) * A.cap + (g - S.u.pre[lo])]);
+        }
+    }
 }
 
 __device__ __forceinline__ int dot_i8_row(const int8_t* q, const int8_t* x, uint32_t d)
@@ -1070,33 +1168,75 @@ __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
     const uint32_t ns = A.nslots;
     uint32_t* cnt = A.cnt + (u64)b * ns;
 
-    // 1. segment counts -> exclusive prefix
-    const uint32_t per = (ns + MT - 1) / MT;
-    uint32_t local = 0;
-    for (uint32_t j = 0; j < per; ++j) {
-        uint32_t s = tid * per + j;
-        if (s < ns) { uint32_t c = cnt[s]; local += c < A.cap ? c : A.cap; }
-    }
-    S.part[tid] = local;
+    // 1. where the candidates are
+    if (tid == 0) S.spilled = 0;
     __syncthreads();
-    for (uint32_t o = 1; o < MT; o <<= 1) {
-        uint32_t v = tid >= o ? S.part[tid - o] : 0;
-        __syncthreads();
-        S.part[tid] += v;
-        __syncthreads();
+    if (tid < 64) {                                    // NPIECE = 65 pieces: lane 0 also takes the carry
+        const uint32_t rcap = A.flat_cap / LINR_FLAT_REGIONS;
+        const u64 ci = ((u64)b * LINR_FLAT_REGIONS + tid) * LINR_COUNTER_STRIDE;
+        uint32_t m = A.gcnt[ci];
+        const uint32_t fv = A.fvalid[ci];
+        if (fv != 0xFFFFFFFFu) S.spilled = 1;
+        if (m > fv) m = fv;
+        if (m > rcap) m = rcap;
+        uint32_t incl = m;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            uint32_t v = __shfl_up(incl, o);
+            if ((int)tid >= o) incl += v;
+        }
+        uint32_t cc = A.ccnt[b];
+        if (cc > A.k) cc = A.k;
+        S.ppre[tid + 1] = cc + incl - m;              // region tid is piece tid + 1
+        if (tid == 0) S.ppre[0] = 0;
+        if (tid == 63) S.ppre[NPIECE] = cc + incl;
     }
-    uint32_t run = S.part[tid] - local;
-    for (uint32_t j = 0; j < per; ++j) {
-        uint32_t s = tid * per + j;
-        if (s < ns) { S.pre[s] = run; uint32_t c = cnt[s]; run += c < A.cap ? c : A.cap; }
-    }
-    if (tid == MT - 1) S.pre[ns] = S.part[MT - 1];
     __syncthreads();
-    const uint32_t Mtot = S.pre[ns];
+    const uint32_t m_flat = S.ppre[NPIECE];
+    const bool spilled = S.spilled != 0;
+    uint32_t Mtot = m_flat;
+    int mode;
+    if (spilled) {
+        mode = MERGE_FROM_ALL;
+        const uint32_t per = (ns + MT - 1) / MT;
+        uint32_t local = 0;
+        for (uint32_t j = 0; j < per; ++j) {
+            uint32_t s = tid * per + j;
+            if (s < ns) { uint32_t c = cnt[s]; local += c < A.cap ? c : A.cap; }
+        }
+        S.part[tid] = local;
+        __syncthreads();
+        for (uint32_t o = 1; o < MT; o <<= 1) {
+            uint32_t v = tid >= o ? S.part[tid - o] : 0;
+            __syncthreads();
+            S.part[tid] += v;
+            __syncthreads();
+        }
+        uint32_t run = S.part[tid] - local;
+        for (uint32_t j = 0; j < per; ++j) {
+            uint32_t s = tid * per + j;
+            if (s < ns) { S.u.pre[s] = run; uint32_t c = cnt[s]; run += c < A.cap ? c : A.cap; }
+        }
+        if (tid == MT - 1) S.u.pre[ns] = S.part[MT - 1];
+        __syncthreads();
+        Mtot += S.u.pre[ns];
+    } else if (m_flat <= MERGE_LDS_KEYS) {
+        // stage everything in LDS: wave w copies pieces w, w + 16, ...
+        const uint32_t wave = tid >> 6, lane = tid & 63;
+        for (uint32_t p = wave; p < NPIECE; p += MT / 64) {
+            const uint32_t o = S.ppre[p], c = S.ppre[p + 1] - o;
+            const u64* src = piece_ptr(A, b, p);
+            for (uint32_t j = lane; j < c; j += 64) S.u.keys[o + j] = src[j];
+        }
+        mode = MERGE_FROM_LDS;
+        __syncthreads();
+    } else {
+        mode = MERGE_FROM_FLAT;
+    }
 
-    // 2. k-th largest key (all keys distinct).  Once the remaining bucket is taken whole the
-    //    low bits of the bound may stay zero: the selected set is already fixed.  A bound that
-    //    seeds the next sweep is resolved down to the full score word first.
+    // 2. k-th largest key.  Once the remaining bucket is taken whole the low bits of the bound may stay zero:
+    //    the selected set is already fixed.  A bound that seeds the next sweep is resolved down to the full
+    //    score word first.
     u64 kth = 0;
     if (Mtot >= A.k) {
         u64 prefix = 0;
@@ -1104,20 +1244,11 @@ __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
         for (int shift = 56; shift >= 0; shift -= 8) {
             if (tid < 256) S.hist[tid] = 0;
             __syncthreads();
-            for (uint32_t f0 = tid; f0 < Mtot; f0 += 4 * MT) {
-                u64 key[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    uint32_t f = f0 + u * MT;
-                    key[u] = f < Mtot ? merge_fetch(A, S, b, f) : 0ull;
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    uint32_t f = f0 + u * MT;
-                    bool match = f < Mtot && ((shift == 56) || ((key[u] >> (shift + 8)) == (prefix >> (shift + 8))));
-                    if (match) atomicAdd(&S.hist[(uint32_t)(key[u] >> shift) & 255u], 1u);
-                }
-            }
+            const u64 want = shift == 56 ? 0ull : (prefix >> (shift + 8));
+            for_each_candidate(A, S, mode, m_flat, Mtot, b, tid, [&](u64 key) {
+                const bool match = (shift == 56) || ((key >> (shift + 8)) == want);
+                if (match) atomicAdd(&S.hist[(uint32_t)(key >> shift) & 255u], 1u);
+            });
             __syncthreads();
             if (tid < 64) {
                 uint32_t bsel, above, inb;
@@ -1133,7 +1264,6 @@ __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
         }
         kth = prefix;
     }
-
     if (!A.final_level && tid == 0 && Mtot >= A.k) {
         u64 cur = A.tau[b];
         if (kth > cur) A.tau[b] = kth;
@@ -1142,20 +1272,23 @@ __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
     // 3. gather the winners (all candidates when there are fewer than k)
     if (tid == 0) S.nwin = 0;
     __syncthreads();
-    for (uint32_t f = tid; f < Mtot; f += MT) {
-        u64 key = merge_fetch(A, S, b, f);
+    for_each_candidate(A, S, mode, m_flat, Mtot, b, tid, [&](u64 key) {
         if (key >= kth) {
             uint32_t p = atomicAdd(&S.nwin, 1u);
             if (p < LINR_MAX_K) S.win[p] = key;
         }
-    }
+    });
     __syncthreads();
     const uint32_t nwin = S.nwin < A.k ? S.nwin : A.k;
 
     if (!A.final_level) {
-        // carry them into the next sweep's merge: segment ns-1 of this query
-        u64* carry = A.seg + ((u64)(ns - 1) * A.B + b) * A.cap;
-        for (uint32_t j = tid; j < nwin; j += MT) carry[j] = S.win[j];
+        // carry them into the next sweep's merge and empty the flat regions
+        for (uint32_t j = tid; j < nwin; j += MT) A.carry[(u64)b * A.k + j] = S.win[j];
+        if (tid == 0) A.ccnt[b] = nwin;
+        if (tid < LINR_FLAT_REGIONS) {
+            const u64 ci = ((u64)b * LINR_FLAT_REGIONS + tid) * LINR_COUNTER_STRIDE;
+            A.gcnt[ci] = 0; A.fvalid[ci] = 0xFFFFFFFFu;
+        }
     } else {
         // sort them, write the outputs
         uint32_t P = 1;
@@ -1203,19 +1336,22 @@ __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
         }
         if (tid == 0) A.out_counts[b] = nwin;
     }
-    __syncthreads();
-    // 4. leave the scan segments empty for the next sweep; the carry segment holds the winners
-    for (uint32_t s = tid; s < ns; s += MT) cnt[s] = (s == ns - 1 && !A.final_level) ? nwin : 0u;
+    // 4. leave the per-slot segments empty for the next sweep (they were only used if a wave spilled)
+    if (spilled) {
+        __syncthreads();
+        for (uint32_t s = tid; s < ns; s += MT) cnt[s] = 0u;
+    }
 }
 
 // ---------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------
-hipError_t linr_launch_init(unsigned long long* tau, uint32_t* cnt, uint64_t n_cnt, uint32_t B, hipStream_t s)
+hipError_t linr_launch_init(unsigned long long* tau, uint32_t* ccnt, uint32_t* gcnt, uint32_t* fvalid, uint32_t* cnt,
+                            uint64_t n_cnt, uint32_t B, hipStream_t s)
 {
     uint64_t want = (n_cnt + 255) / 256;
     uint32_t grid = (uint32_t)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
-    hipLaunchKernelGGL(init_kernel, dim3(grid), dim3(256), 0, s, (u64*)tau, cnt, (u64)n_cnt, B);
+    hipLaunchKernelGGL(init_kernel, dim3(grid), dim3(256), 0, s, (u64*)tau, ccnt, gcnt, fvalid, cnt, (u64)n_cnt, B);
     return hipGetLastError();
 }
 
