@@ -42,6 +42,7 @@ extern "C" int linr_set_tuning(const linr_tuning* t)
     return LINR_OK;
 }
 
+static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 static uint32_t elt_bytes(int dtype) { return dtype == LINR_F32 ? 4u : dtype == LINR_BF16 ? 2u : 1u; }
 
 extern "C" int linr_index_create(linr_index** out, uint64_t capacity, uint32_t d, int dtype, int device)
@@ -75,6 +76,9 @@ static void release_columns(linr_index* ix)
         if (ix->mask) (void)hipFree((void*)ix->mask);
         if (ix->ts) (void)hipFree((void*)ix->ts);
     }
+    if (ix->scale_stats) (void)hipFree(ix->scale_stats);
+    if (ix->scale_code) (void)hipFree(ix->scale_code);
+    ix->scale_stats = nullptr; ix->scale_code = nullptr;
     ix->emb = nullptr; ix->row_scale = nullptr; ix->mask = nullptr; ix->ts = nullptr;
     ix->owned = 0; ix->n = 0;
 }
@@ -139,6 +143,17 @@ static int load_common(linr_index* ix, int dtype, const void* emb, const float* 
         if (rc == LINR_OK && row_scale) rc = copy_column((const void**)&ix->row_scale, row_scale, n * 4, fh);
         if (rc != LINR_OK) release_columns(ix);
     }
+    if (rc == LINR_OK && dtype == LINR_I8 && ix->row_scale) {
+        // statistics of the row scales for the large-batch kernel's first test (Sec. 5.1: a quantised index
+        // carries its scales); 4 floats of results followed by the reduction's scratch
+        const uint64_t n_pad = align_up(n, 256);
+        hipError_t e = hipMalloc((void**)&ix->scale_stats, (4 + 3 * LINR_SCALE_STAT_BLOCKS) * sizeof(float));
+        if (e == hipSuccess) e = hipMalloc((void**)&ix->scale_code, n_pad);
+        if (e == hipSuccess)
+            e = linr_launch_scale_stats(ix->row_scale, n, n_pad, ix->scale_stats + 4, ix->scale_stats, ix->scale_code, nullptr);
+        if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+        if (e != hipSuccess) { g_last_hip = (int)e; rc = LINR_E_HIP; release_columns(ix); }
+    }
     if (rc == LINR_OK) ix->n = n;
     (void)hipSetDevice(dev);
     return rc;
@@ -161,17 +176,16 @@ extern "C" int linr_index_load_int8(linr_index* ix, const int8_t* emb, const flo
 // ---------------------------------------------------------------------------
 // planning
 // ---------------------------------------------------------------------------
-static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
 // occupancy of each kernel variant, asked from the runtime once per process
 static int cached_blocks_per_cu(const linr_index* ix, const linr_plan& p, uint32_t Bp, uint32_t m)
 {
-    static int cache[3][3][2][2][9][17][9][2];       // dtype, vk, generic, coop, ks, qg, m, ts  (0 = unknown)
+    static int cache[3][3][2][3][9][17][9][2];       // dtype, vk, generic, coop / wide, ks, qg, m, ts  (0 = unknown)
     static int cache_dyn = 0;                          // the LDS-streamed kernel depends on (B, m): not cached
     (void)cache_dyn;
     const int ts = ix->ts != nullptr;
     if (p.generic) return linr_scan_blocks_per_cu(p, ix->dtype, Bp, m, ts);
-    int& slot = cache[ix->dtype][p.vk][0][p.coop ? 1 : 0][p.ks][p.qg][m][ts];
+    int& slot = cache[ix->dtype][p.vk][0][p.wide ? 2 : p.coop ? 1 : 0][p.ks][p.qg][m][ts];
     if (slot == 0) {
         int v = linr_scan_blocks_per_cu(p, ix->dtype, Bp, m, ts);
         slot = v > 0 ? v : -1;
@@ -208,8 +222,28 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
             cq = c;
             if (c * LINR_WAVES_PER_BLOCK >= nsg) break;
         }
+    // opt-in (tuning.wide_min_batch): cooperative kernel with 32x32 tiles for int8 rows of exactly 64, 128 or 256
+    // bytes, 4 waves x qw groups of 32 queries.  Not the default: on the measured configurations it only matches
+    // the 16x16-tile kernels (its loop is bound by instruction issue, not by the matrix pipe).
+    uint32_t qw = 0;
+    if (!g_tuning.force_generic && !g_tuning.no_coop && g_tuning.wide_min_batch && B >= g_tuning.wide_min_batch &&
+        ix->row_bytes == p->ks * 64u)
+        for (uint32_t c = 1; c <= 4; c <<= 1) {
+            if (!linr_wide_variant_exists(ix->dtype, p->vk, p->ks, m, c)) continue;
+            qw = c;
+            if (c * LINR_WAVES_PER_BLOCK * 32 >= B) break;
+        }
     uint32_t Bp;
-    if (cq) {
+    if (qw) {
+        p->qg = qw;
+        p->coop = 1;
+        p->wide = 1;
+        p->chunk_items = 256 / p->ks;                   // this kernel stages 16 KB of rows per step
+        p->generic = 0;
+        p->max_batch = LINR_WAVES_PER_BLOCK * qw * 32;
+        Bp = B < p->max_batch ? B : p->max_batch;
+        p->nsplit = LINR_WAVES_PER_BLOCK;
+    } else if (cq) {
         p->qg = cq;
         p->coop = 1;
         p->generic = 0;
@@ -256,7 +290,8 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
     if (nslots > LINR_MAX_SLOTS) nslots = LINR_MAX_SLOTS;
     p->grid = (uint32_t)grid;
     p->nslots = (uint32_t)nslots;
-    p->cap = (uint32_t)align_up((uint64_t)k + p->chunk_items, 64);
+    // a segment must take what one append round can add on top of the k keys a compaction leaves
+    p->cap = (uint32_t)align_up((uint64_t)k + (p->wide ? (uint32_t)LINR_WIDE_QCAP : p->chunk_items), 64);
 
     // Sweeps, coarse to fine.  Sweep l visits the chunks whose index is a multiple of stride[l] but not of
     // stride[l-1] (those were visited before), so every chunk is scored exactly once per search; the k best keys
@@ -386,7 +421,7 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
 
         linr_scan_args sa;
         memset(&sa, 0, sizeof(sa));
-        sa.emb = ix->emb; sa.row_scale = ix->row_scale; sa.mask = ix->mask; sa.ts = ix->ts;
+        sa.emb = ix->emb; sa.row_scale = ix->row_scale; sa.mask = ix->mask; sa.ts = ix->ts; sa.scale_stats = ix->scale_stats; sa.scale_code = ix->scale_code;
         sa.n = ix->n; sa.row_bytes = ix->row_bytes;
         sa.Q = (const char*)Q + (uint64_t)b0 * m * ix->row_bytes; sa.B = Bp; sa.m = m;
         sa.filters = use_filt; sa.tau = tau; sa.cnt = cnt; sa.seg = seg;

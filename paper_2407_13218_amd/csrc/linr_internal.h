@@ -9,6 +9,7 @@
 #define LINR_MAX_LEVELS 12
 #define LINR_MAX_SLOTS 4096          // merge kernel keeps one prefix entry per slot in LDS
 #define LINR_MAX_NSPLIT 16
+#define LINR_WIDE_QCAP 320            // keys a wave of the 32x32-tile kernel queues in LDS before writing them out
 #define LINR_FLAT_REGIONS 64          // independently counted regions of a query's flat candidate array
 #define LINR_COUNTER_STRIDE 16        // words between two region counters (one 64-byte line each)
 
@@ -29,6 +30,8 @@ struct linr_index {
     const uint32_t* mask;
     const uint32_t* ts;
     int owned;                  // library allocated the four columns
+    float* scale_stats;         // scaled int8: min of 1/scale, 127/span, span/127 (+ reduction scratch); always owned
+    uint8_t* scale_code;        // scaled int8: E_i of every item, padded to a multiple of 256 items; always owned
     int num_cu;
 };
 
@@ -42,6 +45,7 @@ struct linr_plan {
     uint32_t nsplit;            // waves that share a chunk and split the query groups
     uint32_t generic;           // 1 = queries streamed from LDS
     uint32_t coop;              // 1 = the four waves of a workgroup share each chunk and split the query groups
+    uint32_t wide;              // 1 = coop with 32x32 tiles; qg then counts 32-query groups per wave
     uint32_t grid;              // workgroups of LINR_WAVES_PER_BLOCK waves
     uint32_t nslots;            // chunk-slots = waves / nsplit
     uint32_t cap;               // entries per (slot, query) candidate segment
@@ -57,6 +61,8 @@ struct linr_plan {
 
 struct linr_scan_args {
     const void* emb; const float* row_scale; const uint32_t* mask; const uint32_t* ts;
+    const float* scale_stats;   // see linr_index (read by the 32x32-tile kernel only)
+    const uint8_t* scale_code;
     uint64_t n; uint32_t row_bytes;
     const void* Q; uint32_t B; uint32_t m;
     const linr_filter* filters;
@@ -95,6 +101,12 @@ hipError_t linr_launch_merge(const linr_merge_args& a, hipStream_t s);
 // 1 if a register-resident-query scan kernel exists for this shape
 int linr_fast_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg);
 int linr_coop_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg);
+int linr_wide_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qw);
+// statistics of 1/row_scale of a scaled int8 index (out[3]; part: 3 * LINR_SCALE_STAT_BLOCKS floats of scratch) and the
+// per-item codes derived from them (codes: n_pad bytes)
+#define LINR_SCALE_STAT_BLOCKS 1024
+hipError_t linr_launch_scale_stats(const float* row_scale, uint64_t n, uint64_t n_pad, float* part, float* out, uint8_t* codes,
+                                   hipStream_t s);
 // workgroups of the planned scan kernel resident per compute unit (0 if unknown)
 int linr_scan_blocks_per_cu(const linr_plan& p, int dtype, uint32_t B, uint32_t m, int has_ts);
 // dynamic LDS bytes of the LDS-streamed scan kernel for a pass of B queries

@@ -24,6 +24,22 @@ typedef unsigned long long u64;
 
 #define WPB LINR_WAVES_PER_BLOCK
 
+// Event counters for kernel studies; compiled in only with -DLINR_STATS (the shipped library has none).
+#ifdef LINR_STATS
+__device__ unsigned long long linr_stats[16];
+#define STAT_ADD(i, v) do { if ((threadIdx.x & 63) == 0) atomicAdd(&linr_stats[i], (unsigned long long)(v)); } while (0)
+#define STAT_CLOCK() clock64()
+extern "C" int linr_debug_stats(unsigned long long* out, int reset)
+{
+    if (out && hipMemcpyFromSymbol(out, HIP_SYMBOL(linr_stats), sizeof(unsigned long long) * 16) != hipSuccess) return -1;
+    if (reset) { unsigned long long z[16] = {0}; if (hipMemcpyToSymbol(HIP_SYMBOL(linr_stats), z, sizeof(z)) != hipSuccess) return -1; }
+    return 0;
+}
+#else
+#define STAT_ADD(i, v) do { } while (0)
+#define STAT_CLOCK() 0ll
+#endif
+
 // ---------------------------------------------------------------------------
 // small helpers
 // ---------------------------------------------------------------------------
@@ -423,11 +439,15 @@ __device__ __forceinline__ bool tile_hot_pred(const acc_t& acc, float thr_f, int
 //       lanes whose own stage A fired -- at low pass rates most hot tiles end here;
 //   B2  exact ranking values of the remaining items against the query's bound;
 //   C   any-of clauses (full filter record), key append to the wave's segment of that query.
-template <int VK, bool MAGIC, int CH, typename acc_t>
+// QUEUED: the keys go to a wave-private queue in LDS instead (qcount, qkey, qql: count, keys, wave-local query
+// numbers; the caller guarantees room for the 256 keys one call can produce) and no global store is made here.
+// load_sc / load_ts: callables that return the row scales / timestamps of the lane's four items (v4f / v4u).
+template <int VK, bool MAGIC, int CH, bool QUEUED = false, typename acc_t, typename FSc, typename FTs>
 __device__ __forceinline__ void tile_survivors(const acc_t& acc, bool lane_hot, const v4u& mk4, uint32_t fa, uint32_t fn,
                                                const QSide& qs, uint32_t ql, uint32_t qi, int ib,
-                                               u64 item0, const float* l_sc, const uint32_t* l_ts,
-                                               const linr_scan_args& A, uint32_t slot, bool has_ts, uint32_t& need_compact)
+                                               u64 item0, FSc load_sc, FTs load_ts,
+                                               const linr_scan_args& A, uint32_t slot, bool has_ts, uint32_t& need_compact,
+                                               uint32_t* qcount = nullptr, u64* qkey = nullptr, uint8_t* qql = nullptr)
 {
     uint32_t cand = 0;
     v4u ts4 = {0, 0, 0, 0};
@@ -435,7 +455,7 @@ __device__ __forceinline__ void tile_survivors(const acc_t& acc, bool lane_hot, 
         cand = ((mk4[0] & fn) == fa ? 1u : 0u) | ((mk4[1] & fn) == fa ? 2u : 0u) | ((mk4[2] & fn) == fa ? 4u : 0u) |
                ((mk4[3] & fn) == fa ? 8u : 0u);
         if (has_ts) {
-            ts4 = *(const v4u*)&l_ts[ib];
+            ts4 = load_ts();
             const uint32_t t0 = qs.tsmin[ql], t1 = qs.tsmax[ql];
 #pragma unroll
             for (int r = 0; r < 4; ++r)
@@ -448,7 +468,7 @@ __device__ __forceinline__ void tile_survivors(const acc_t& acc, bool lane_hot, 
     uint32_t hi[4];
     if constexpr (VK == LINR_VK_I8_SCALED) {
         const float tf = qs.thr_f[ql];
-        v4f sc4 = *(const v4f*)&l_sc[ib];
+        const v4f sc4 = load_sc();
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             int raw = MAGIC ? acc[r] - LINR_MAGIC_BITS : acc[r];
@@ -484,9 +504,15 @@ __device__ __forceinline__ void tile_survivors(const acc_t& acc, bool lane_hot, 
             if (ok && complex) ok = filter_pass(A.filters[qi], mk4[r], has_ts, ts4[r]);
             if (ok) {
                 u64 key = ((u64)hi[r] << 32) | (u64)(uint32_t)~(uint32_t)item;
-                uint32_t pos = atomicAdd(&qs.cnt[ql], 1u);
-                if (pos < A.cap) seg_p[pos] = key;
-                if (pos + 1 + CH > A.cap) need_compact = 1u;
+                if constexpr (QUEUED) {
+                    const uint32_t pos = atomicAdd(qcount, 1u);
+                    qkey[pos] = key;
+                    qql[pos] = (uint8_t)ql;
+                } else {
+                    uint32_t pos = atomicAdd(&qs.cnt[ql], 1u);
+                    if (pos < A.cap) seg_p[pos] = key;
+                    if (pos + 1 + CH > A.cap) need_compact = 1u;
+                }
             }
         }
     }
@@ -722,7 +748,8 @@ scan_kernel(linr_scan_args A)
                 for (int i = 0; i < QG; ++i)
                     if (hot[i])
                         tile_survivors<VK, MAGIC, CH>(acc[i], (hot[i] >> lane) & 1ull, mk4, f_all[i], f_none[i], qs, i * 16 + row,
-                                                      q_first + i * 16 + row, ib, item0, L.sc, L.ts, A, slot, has_ts, need_compact);
+                                                      q_first + i * 16 + row, ib, item0, [&] { return *(const v4f*)&L.sc[ib]; },
+                                                      [&] { return *(const v4u*)&L.ts[ib]; }, A, slot, has_ts, need_compact);
             }
         }
         wave_sync();
@@ -937,7 +964,8 @@ __global__ void __launch_bounds__(64 * WPB, (QG * M * KS <= 2 ? 4 : QG * M * KS 
                     for (int i = 0; i < QG; ++i)
                         if (hot[i])
                             tile_survivors<VK, MAGIC, CH>(acc[i], (hot[i] >> lane) & 1ull, mk4, f_all[i], f_none[i], qs, i * 16 + row,
-                                                          q_first + i * 16 + row, ib, item0, C.sc, C.ts, A, slot, has_ts, need_compact);
+                                                          q_first + i * 16 + row, ib, item0, [&] { return *(const v4f*)&C.sc[ib]; },
+                                                          [&] { return *(const v4u*)&C.ts[ib]; }, A, slot, has_ts, need_compact);
                 }
             }
             bool refresh = ++since_refresh >= 16;
@@ -963,6 +991,509 @@ __global__ void __launch_bounds__(64 * WPB, (QG * M * KS <= 2 ? 4 : QG * M * KS 
     if (active) {
         own_stores_done();
         flush_segments(A, qs, slot, q_first, NQ, lane, hist_all[wib]);   // 2 * NQ + 1 <= 256 words
+    }
+}
+
+// ---------------------------------------------------------------------------
+// scan kernel for large int8 batches (m = 1): 32-item x 32-query tiles, K = 32 per step
+// (v_mfma_i32_32x32x32_i8).  Same workgroup-cooperative staging as above; wave w owns QW
+// groups of 32 queries, so a workgroup answers 128 * QW queries per pass; a chunk is 256 / KS items
+// (16 KB of rows), twice that of the other kernels, to halve the per-chunk bookkeeping.  After the
+// product a lane holds 16 items of ONE query, so the first test is a 16-way integer
+// maximum against one bound per query: 9 vector instructions per 32x32 block instead of
+// 16 with 16x16 tiles -- the vector ALU, not the matrix pipe, limits this loop.
+//
+// Scaled int8 (ranking value raw * scale_i): an item matters iff raw >= thr / scale_i, a
+// bound that differs from item to item.  With r_i = 1 / scale_i, rmin = min r_i and
+// E_i = floor(127 (r_i - rmin) / (rmax - rmin)) in [0, 127],
+//     thr * r_i >= thr * rmin + E_i * G,      G = floor(thr * (rmax - rmin) / 127),
+// so "raw - E_i * G >= floor(thr * rmin)" never misses such an item, and its right side
+// depends on the query only.  The subtraction is one more K step of the same matrix
+// instruction: the item side carries E_i in all 32 slots, the query side the digits of -G
+// (slot s holds -clamp(G - 127 s, 0, 127)).  One extra product per block buys a test that
+// is tight to under 1 % of the bound whatever the spread of the row scales inside a tile.
+// A (tile, group) that fires is narrowed to runs of 4 consecutive items per lane, the raw
+// values are restored (+ E_i * G) and handed to the same survivor path as in the 16x16
+// kernels.  Two to four waves per SIMD overlap one wave's tests with another's products.
+//   lane l of a product: query column l%32, item rows 8*(r/4) + 4*(l/32) + r%4, r<16.
+// ---------------------------------------------------------------------------
+typedef int v16i __attribute__((ext_vector_type(16)));
+#define LINR_WIDE_GMAX (32 * 127)
+
+__device__ __forceinline__ int max16(const v16i& a)
+{
+    int m = max(max(a[0], a[1]), a[2]);
+    m = max(max(m, a[3]), a[4]);
+    m = max(max(m, a[5]), a[6]);
+    m = max(max(m, a[7]), a[8]);
+    m = max(max(m, a[9]), a[10]);
+    m = max(max(m, a[11]), a[12]);
+    m = max(max(m, a[13]), a[14]);
+    return max(m, a[15]);
+}
+
+// floor(x) clamped to the int range (x may be +-inf)
+__device__ __forceinline__ int floor_to_int(float x)
+{
+    return (int)fminf(fmaxf(floorf(x), -2147483520.0f), 2147483520.0f);
+}
+
+// reciprocal of a row scale, rounded down by more than the error of the hardware reciprocal
+__device__ __forceinline__ float rcp_down(float scale)
+{
+    return __builtin_amdgcn_rcpf(scale) * 0.999999f;
+}
+
+// One stage of the chunk ring in LDS, filled by direct global -> LDS loads (no registers in between, so
+// several chunks can be in flight per workgroup).  Such a load writes the 64 lanes' data to consecutive
+// LDS addresses, so block f of `a` (1 KB) holds a 16-row x 64-byte piece of the chunk as
+// [16-byte column g][row], exactly as the lanes fetched it (lane: row l%16, column l/16).
+struct WideStage {
+    v4i a[1024];               // 16 KB of rows: a chunk of this kernel is 256 / KS items
+    uint32_t mk[256];
+    float sc[256];
+    uint32_t ts[256];
+    uint32_t ec[64];           // scaled int8: E_i, one byte per item
+};
+
+#define LINR_WIDE_DMA_PER_WAVE 8   // direct loads every wave issues per chunk (always this many)
+
+// The stages are read with hand-placed LDS instructions: for a read the compiler can see, it waits until every
+// outstanding direct load has landed (it cannot know which stage a load fills), which would empty the ring at
+// every step.  Each helper issues its reads and waits for them itself; that a stage's loads have landed is
+// established by the step protocol of the kernel (counted wait + workgroup barrier).
+__device__ __forceinline__ uint32_t lds_addr(const void* p)
+{
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
+template <int NK>
+__device__ __forceinline__ void lds_read_tile(uint32_t addr_a, uint32_t addr_e, v4i (&a)[NK], uint32_t& e)
+{
+    static_assert(NK == 2 || NK == 4 || NK == 8, "K = 32 steps per row");
+    if constexpr (NK == 2)
+        asm volatile("ds_read_b128 %0, %3\n\tds_read_b128 %1, %3 offset:512\n\tds_read_u8 %2, %4\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&v"(a[0]), "=&v"(a[1]), "=&v"(e) : "v"(addr_a), "v"(addr_e) : "memory");
+    else if constexpr (NK == 4)
+        asm volatile("ds_read_b128 %0, %5\n\tds_read_b128 %1, %5 offset:512\n\tds_read_b128 %2, %5 offset:1024\n\t"
+                     "ds_read_b128 %3, %5 offset:1536\n\tds_read_u8 %4, %6\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&v"(a[0]), "=&v"(a[1]), "=&v"(a[2]), "=&v"(a[3]), "=&v"(e) : "v"(addr_a), "v"(addr_e) : "memory");
+    else
+        asm volatile("ds_read_b128 %0, %9\n\tds_read_b128 %1, %9 offset:512\n\tds_read_b128 %2, %9 offset:1024\n\t"
+                     "ds_read_b128 %3, %9 offset:1536\n\tds_read_b128 %4, %9 offset:2048\n\tds_read_b128 %5, %9 offset:2560\n\t"
+                     "ds_read_b128 %6, %9 offset:3072\n\tds_read_b128 %7, %9 offset:3584\n\tds_read_u8 %8, %10\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&v"(a[0]), "=&v"(a[1]), "=&v"(a[2]), "=&v"(a[3]), "=&v"(a[4]), "=&v"(a[5]), "=&v"(a[6]), "=&v"(a[7]), "=&v"(e)
+                     : "v"(addr_a), "v"(addr_e) : "memory");
+}
+// side columns of four consecutive items (mask, scale, timestamp: 16 bytes each; codes: 4 bytes)
+__device__ __forceinline__ void lds_read_side(uint32_t addr_mk, uint32_t addr_sc, uint32_t addr_ts, uint32_t addr_ec, v4u& mk4, v4f& sc4,
+                                              v4u& ts4, uint32_t& e4)
+{
+    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\tds_read_b128 %2, %6\n\tds_read_b32 %3, %7\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(mk4), "=&v"(sc4), "=&v"(ts4), "=&v"(e4) : "v"(addr_mk), "v"(addr_sc), "v"(addr_ts), "v"(addr_ec) : "memory");
+}
+
+// s_waitcnt immediate that waits for the vector-memory counter only (gfx9 encoding)
+#define LINR_WAIT_VM(n) (((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+
+// Byte offsets of what a lane fetches, relative to the start of a chunk's rows / side columns; they do not change
+// from chunk to chunk, so a full chunk costs no per-lane address arithmetic (uniform base + 32-bit lane offset).
+struct WideLaneOff {
+    uint32_t emb[4];
+    uint32_t side;
+    uint32_t ec;
+};
+
+template <int KS>
+__device__ __forceinline__ WideLaneOff wide_lane_offsets(int lane, int wib)
+{
+    constexpr int CH = 256 / KS;
+    const int row = lane & 15, g4 = lane >> 4;
+    WideLaneOff o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int f = wib * 4 + j, t16 = f / KS, ks = f % KS;
+        o.emb[j] = (uint32_t)((t16 * 16 + row) * (KS * 64) + ks * 64 + g4 * 16);
+    }
+    o.side = ((uint32_t)(wib * 64 + lane) % (uint32_t)CH) * 4u;
+    o.ec = ((uint32_t)lane % (uint32_t)(CH / 4)) * 4u;
+    return o;
+}
+
+// Every wave issues the same eight loads per chunk: four 1 KB blocks of rows, its 64 items' worth of each side
+// column (repeating items when the chunk has fewer than 256) and the codes; what a short chunk or a missing
+// column leaves over is loaded from a valid address anyway and never read.
+template <int VK, int KS>
+__device__ __forceinline__ void issue_wide(WideStage& S, const linr_scan_args& A, u64 item0, int lane, int wib, bool has_ts,
+                                           const WideLaneOff& off)
+{
+    typedef const __attribute__((address_space(1))) void* gptr;
+    typedef __attribute__((address_space(3))) void* lptr;
+    constexpr int CH = 256 / KS;
+    constexpr uint32_t RB = KS * 64;
+    const char* p_emb[4];
+    const char *p_mk, *p_ts, *p_sc, *p_ec;
+    if (item0 + CH <= A.n) {                            // uniform; all chunks but possibly the last one
+        const char* eb = (const char*)A.emb + item0 * RB;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) p_emb[j] = eb + off.emb[j];
+        p_mk = (const char*)A.mask + item0 * 4 + off.side;
+        p_ts = (const char*)(has_ts ? A.ts : A.mask) + item0 * 4 + off.side;
+        p_sc = (const char*)(VK == LINR_VK_I8_SCALED ? (const void*)A.row_scale : (const void*)A.mask) + item0 * 4 + off.side;
+    } else {                                            // ragged end: items past the last one repeat it
+        const u64 last = A.n - 1;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            u64 it = item0 + off.emb[j] / RB;
+            it = it < last ? it : last;
+            p_emb[j] = (const char*)A.emb + it * RB + off.emb[j] % RB;
+        }
+        u64 it = item0 + off.side / 4;
+        it = it < last ? it : last;
+        p_mk = (const char*)A.mask + it * 4;
+        p_ts = (const char*)(has_ts ? A.ts : A.mask) + it * 4;
+        p_sc = (const char*)(VK == LINR_VK_I8_SCALED ? (const void*)A.row_scale : (const void*)A.mask) + it * 4;
+    }
+    // CH bytes of codes = CH/4 words; the column is padded so that a whole chunk can always be read
+    p_ec = VK == LINR_VK_I8_SCALED ? (const char*)A.scale_code + item0 + off.ec : p_mk;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) __builtin_amdgcn_global_load_lds((gptr)p_emb[j], (lptr)&S.a[(wib * 4 + j) * 64], 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((gptr)p_mk, (lptr)&S.mk[wib * 64], 4, 0, 0);
+    __builtin_amdgcn_global_load_lds((gptr)p_ts, (lptr)&S.ts[wib * 64], 4, 0, 0);
+    __builtin_amdgcn_global_load_lds((gptr)p_sc, (lptr)&S.sc[wib * 64], 4, 0, 0);
+    __builtin_amdgcn_global_load_lds((gptr)p_ec, (lptr)&S.ec[0], 4, 0, 0);
+}
+
+// Query side of the scale correction for the query this lane tracks (column l%32): the bound of the
+// corrected value, G, and the 16 digit bytes of -G this lane supplies (slots 16 (l/32) .. +15).
+__device__ __forceinline__ void wide_query_bound(float thr, float rmin, float r_per_e, int h2, int& base, int& G, v4i& digits)
+{
+    const float tl = lowered_pos(thr);                                  // -inf: no usable bound yet
+    base = floor_to_int(tl * rmin);
+    int g = floor_to_int(fmaxf(tl, 0.0f) * r_per_e);                    // +inf (unused query slot) clamps below
+    g = g < 0 ? 0 : (g > LINR_WIDE_GMAX ? LINR_WIDE_GMAX : g);
+    G = g;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int byte = 0; byte < 4; ++byte) {
+            const int slot = 16 * h2 + 4 * w + byte;
+            int dgt = g - 127 * slot;
+            dgt = dgt < 0 ? 0 : (dgt > 127 ? 127 : dgt);
+            word |= ((uint32_t)(-dgt) & 0xFFu) << (8 * byte);
+        }
+        digits[w] = (int)word;
+    }
+}
+
+template <int VK, int KS, int QW>
+__global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A)
+{
+    constexpr int CH = 256 / KS;
+    constexpr int TW = CH / 32;
+    constexpr int NK = 2 * KS;
+    constexpr int NQ = QW * 32;
+    constexpr int NST = 3;                               // ring stages: NST - 1 chunks (16 KB each) are in flight per workgroup
+    constexpr bool SCALED = (VK == LINR_VK_I8_SCALED);
+    static_assert(KS == 1 || KS == 2 || KS == 4, "rows of 64, 128 or 256 bytes");
+
+    constexpr int QCAP = LINR_WIDE_QCAP;
+    constexpr int SCRATCH_WORDS = 2 * QCAP + QCAP / 4 + 4;   // keys, query numbers, count (last word)
+    static_assert(SCRATCH_WORDS - 4 >= 2 * NQ + 1 && SCRATCH_WORDS - 4 >= 256, "scratch is shared with compaction and the final flush");
+
+    __shared__ WideStage ring[NST];
+    __shared__ WaveQ<QW * 2> wq_all[WPB];
+    __shared__ __attribute__((aligned(8))) uint32_t scratch_all[WPB][SCRATCH_WORDS];
+    const int lane = threadIdx.x & 63, wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    u64* const qkey = (u64*)&scratch_all[wib][0];
+    uint8_t* const qql = (uint8_t*)&scratch_all[wib][2 * QCAP];
+    uint32_t* const qcount = &scratch_all[wib][SCRATCH_WORDS - 1];
+    WaveQ<QW * 2>& W = wq_all[wib];
+    const QSide qs = {W.cnt, W.thr_f, W.thr_i, W.fall, W.fnone, W.tsmin, W.tsmax, W.fflag};
+    const int col = lane & 31, h2 = lane >> 5;
+    const uint32_t slot = blockIdx.x;
+    if (slot >= A.nslots) return;                       // uniform for the workgroup
+    const uint32_t q_first = wib * NQ;
+    const bool active = q_first < A.B;                  // waves past the batch still load and synchronise
+    const bool has_ts = A.ts != nullptr;
+    float rmin = 0.0f, r_per_e = 0.0f;                  // index-wide statistics of 1 / row scale
+    if constexpr (SCALED) { rmin = A.scale_stats[0]; r_per_e = A.scale_stats[2]; }
+
+    v4i q[QW][NK];
+#pragma unroll
+    for (int i = 0; i < QW; ++i) {
+        const uint32_t qi = q_first + i * 32 + col;
+#pragma unroll
+        for (int s = 0; s < NK; ++s) {
+            v4i z = {0, 0, 0, 0};
+            if (qi < A.B) z = *(const v4i*)((const char*)A.Q + (u64)qi * (KS * 64) + (s * 32 + h2 * 16));
+            q[i][s] = z;
+        }
+    }
+    for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) {
+        W.cnt[ql] = 0;
+        load_query_side(qs, ql, q_first + ql, A, true);
+    }
+    if (lane == 0) *qcount = 0;
+    wave_sync();
+    int bound[QW];            // lane l tracks query column l%32 of each group
+    v4i qe[QW];               // digits of -G (scaled int8)
+    auto refresh_bounds = [&]() {
+#pragma unroll
+        for (int i = 0; i < QW; ++i) {
+            if constexpr (SCALED) {
+                int G;
+                wide_query_bound(W.thr_f[i * 32 + col], rmin, r_per_e, h2, bound[i], G, qe[i]);
+                if (h2 == 0) W.thr_i[i * 32 + col] = G;  // (thr_i is not used otherwise for this ranking kind)
+            } else {
+                bound[i] = W.thr_i[i * 32 + col];
+                qe[i] = (v4i){0, 0, 0, 0};
+            }
+        }
+        wave_sync();
+    };
+    refresh_bounds();
+
+    // Fragment (T, s) of a stage: lane l needs bytes [32 s + 16 (l/32), +16) of item row 32 T + l%32.  That is
+    // 16-byte column 2 s + l/32 of the row, which sits in block (2 T + (l%32)/16) * KS + (2 s + l/32) / 4 at
+    // [column % 4][row % 16]: byte offset frag0 + 2048 KS T + 512 s.
+    const uint32_t frag0 = (uint32_t)(((col >> 4) * KS * 64 + h2 * 16 + (col & 15)) * 16);
+
+    uint32_t need_compact = 0u;
+    uint32_t since_refresh = 0;
+    // Candidate keys wait in the wave's LDS queue and are written out in bulk.  Loads and stores may complete out
+    // of order with respect to each other, which would spoil the counting of outstanding direct loads, so every
+    // path that stores to global memory ends by waiting for all of the wave's memory operations.
+    auto flush_queue = [&]() {
+        wave_sync();
+        const uint32_t nqd = *qcount;
+        STAT_ADD(4, 1);
+        STAT_ADD(5, nqd);
+        for (uint32_t t = lane; t < nqd; t += 64) {
+            const u64 key = qkey[t];
+            const uint32_t ql = qql[t];
+            const uint32_t pos = atomicAdd(&W.cnt[ql], 1u);
+            if (pos < A.cap) A.seg[((u64)slot * A.B + q_first + ql) * A.cap + pos] = key;
+            if (pos + 1 + QCAP > A.cap) need_compact = 1u;
+        }
+        wave_sync();
+        if (lane == 0) *qcount = 0;
+        wave_sync();
+        __builtin_amdgcn_s_waitcnt(LINR_WAIT_VM(0));
+    };
+    const v16i zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    const WideLaneOff lane_off = wide_lane_offsets<KS>(lane, wib);
+    // One walker runs NST - 1 chunks ahead of the consumer and hands it the first item of each chunk through a
+    // small queue indexed by ring stage; `n_mine` chunks belong to this workgroup.
+    SweepWalk ahead;
+    ahead.init(slot, A);
+    const uint32_t n_dense32 = (uint32_t)A.n_dense;
+    const uint32_t n_mine = slot < n_dense32 ? (n_dense32 - slot + A.nslots - 1) / A.nslots : 0u;
+    u64 item0_q[NST];
+    u64 item0_last = 0;
+
+    // Every wave always issues the same number of direct loads per step (past the end of the sweep it reloads
+    // the last valid chunk), so "at most (NST-2) * LINR_WIDE_DMA_PER_WAVE loads outstanding" means: the chunk
+    // about to be consumed has landed.
+    auto issue_next = [&](int rf) {
+        if (ahead.valid()) item0_last = ahead.lc() * A.stride * CH;
+#pragma unroll
+        for (int t = 0; t < NST; ++t)
+            if (t == rf) item0_q[t] = item0_last;
+        issue_wide<VK, KS>(ring[rf], A, item0_last, lane, wib, has_ts, lane_off);
+        ahead.advance();
+    };
+
+    auto consume = [&](int st) {
+        WideStage& C = ring[st];
+        u64 item0 = item0_q[0];
+#pragma unroll
+        for (int t = 1; t < NST; ++t)
+            if (t == st) item0 = item0_q[t];
+        const uint32_t base_a = lds_addr(&C.a[0]) + frag0, base_e = lds_addr(&C.ec[0]) + col;
+        const uint32_t base_mk = lds_addr(&C.mk[0]), base_sc = lds_addr(&C.sc[0]), base_ts = lds_addr(&C.ts[0]);
+#pragma unroll 1
+        for (int T = 0; T < TW; ++T) {
+            v16i acc[QW];
+            {
+                v4i a[NK];
+                uint32_t ecode;
+                lds_read_tile<NK>(base_a + T * (2048 * KS), base_e + T * 32, a, ecode);
+#pragma unroll
+                for (int s = 0; s < NK; ++s)
+#pragma unroll
+                    for (int i = 0; i < QW; ++i)
+                        acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[s], q[i][s], s == 0 ? zero16 : acc[i], 0, 0, 0);
+                if constexpr (SCALED) {
+                    const int rep = (int)(ecode * 0x01010101u);
+                    const v4i ae = {rep, rep, rep, rep};
+#pragma unroll
+                    for (int i = 0; i < QW; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ae, qe[i], acc[i], 0, 0, 0);
+                }
+            }
+            uint32_t pend = 0;                       // groups of this tile whose test fired (uniform)
+#pragma unroll
+            for (int i = 0; i < QW; ++i) pend |= wave_any(max16(acc[i]) >= bound[i]) ? (1u << i) : 0u;
+#ifdef LINR_EXP_NOSLOW
+            pend &= (uint32_t)(A.k >> 20);                  // (never fires in the experiment: k < 2^20)
+#endif
+            STAT_ADD(0, QW);
+            const long long t_slow = pend ? STAT_CLOCK() : 0ll;
+            (void)t_slow;
+            if (pend) STAT_ADD(1, __popc(pend));
+            const uint32_t pend_any = pend;
+#ifdef LINR_EXP_NOSLOW
+            if (pend && lane == 0) atomicAdd(A.cnt, pend);   // keeps the products alive without the survivor path
+            pend = 0;
+#endif
+            while (pend) {
+                const int i = __ffs((int)pend) - 1;
+                pend &= pend - 1;
+                v16i hv = acc[0];
+#pragma unroll
+                for (int c = 1; c < QW; ++c)
+                    if (i == c) hv = acc[c];
+                const uint32_t ql = i * 32 + col;
+                int bi, G = 0;
+                if constexpr (SCALED) {
+                    G = W.thr_i[ql];
+                    bi = floor_to_int(lowered_pos(W.thr_f[ql]) * rmin);
+                } else {
+                    bi = W.thr_i[ql];
+                }
+                const uint32_t fa = W.fall[ql], fn = W.fnone[ql];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int ib = T * 32 + 8 * j + 4 * h2;
+                    v4i acc4 = {hv[4 * j], hv[4 * j + 1], hv[4 * j + 2], hv[4 * j + 3]};
+                    const bool lane_hot = max(max(acc4[0], acc4[1]), max(acc4[2], acc4[3])) >= bi;
+                    if (!wave_any(lane_hot)) continue;
+                    STAT_ADD(2, 1);
+                    STAT_ADD(3, __popcll(wave_ballot(lane_hot)));
+                    v4u mk4, ts4;
+                    v4f sc4;
+                    uint32_t e4;
+                    lds_read_side(base_mk + ib * 4, base_sc + ib * 4, base_ts + ib * 4, base_e - col + ib, mk4, sc4, ts4, e4);
+                    if constexpr (SCALED) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc4[r] += (int)((e4 >> (8 * r)) & 0xFFu) * G;
+                    }
+                    if (*qcount + 256u > (uint32_t)QCAP) {             // uniform: one call appends at most 4 keys per lane
+                        flush_queue();
+                        if (wave_any(need_compact != 0u)) {
+                            compact_full_segments<QCAP>(A, qs, slot, q_first, NQ, scratch_all[wib], lane);
+                            __builtin_amdgcn_s_waitcnt(LINR_WAIT_VM(0));
+                            need_compact = 0u;
+                            since_refresh = 64;                       // bounds moved: reload them after this chunk
+                        }
+                    }
+                    tile_survivors<VK, false, CH, true>(acc4, lane_hot, mk4, fa, fn, qs, ql, q_first + ql, ib, item0,
+                                                        [&] { return sc4; }, [&] { return ts4; }, A, slot, has_ts, need_compact,
+                                                        qcount, qkey, qql);
+                }
+            }
+            if (pend_any) STAT_ADD(6, STAT_CLOCK() - t_slow);
+            (void)pend_any;
+        }
+        // (an ordinary load returns after all direct loads issued before it, so each refresh empties the ring: keep it rare)
+        const bool refresh = ++since_refresh >= 64;
+        if (refresh) {
+            for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) load_query_side(qs, ql, q_first + ql, A, false);
+            wave_sync();
+            refresh_bounds();
+            since_refresh = 0;
+        }
+    };
+
+    // One step: wait until the chunk in stage `cur` has landed for every wave, refill the stage consumed one
+    // step ago with the chunk NST - 1 steps ahead, then consume `cur`.
+    const long long t_begin = STAT_CLOCK();
+    (void)t_begin;
+    if (n_mine) {
+        // prologue: NST - 1 chunks in flight
+        for (int st = 0; st < NST - 1; ++st) issue_next(st);
+        int st = 0;                                      // stage that holds the chunk to consume
+        // One step: wait until the chunk in stage `st` has landed for every wave, refill the stage consumed one
+        // step ago with the chunk NST - 1 steps ahead, then consume `st`.
+        for (uint32_t c = 0; c < n_mine; ++c) {
+            __builtin_amdgcn_s_waitcnt(LINR_WAIT_VM((NST - 2) * LINR_WIDE_DMA_PER_WAVE));
+            __builtin_amdgcn_s_barrier();
+            issue_next(st == 0 ? NST - 1 : st - 1);
+            if (active) consume(st);
+            st = st + 1 == NST ? 0 : st + 1;
+        }
+        // nothing of this workgroup may still be on its way to LDS when its waves end
+        __builtin_amdgcn_s_waitcnt(LINR_WAIT_VM(0));
+    }
+    STAT_ADD(7, STAT_CLOCK() - t_begin);
+    STAT_ADD(8, 1);
+    if (active) {
+        flush_queue();
+        own_stores_done();
+        flush_segments(A, qs, slot, q_first, NQ, lane, scratch_all[wib]);
+    }
+}
+
+// Index-wide statistics of r = 1 / row scale for the kernel above and the per-item codes E_i.
+// out[0] = min r; out[1] = 127 / span and out[2] = span / 127, both rounded down, where span =
+// min(max r - min r, 2 (mean r - min r)) so that a few extreme rows do not cost the bulk its resolution
+// (rows beyond the span get E = 127, a valid if loose correction).  All zero if the scales are unusable.
+// Three launches: per-block partials, one block reduces them, then the codes.
+__device__ __forceinline__ float block_reduce(float v, float* sh, int op)    // op 0 min, 1 max, 2 sum
+{
+    sh[threadIdx.x] = v;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) {
+            const float x = sh[threadIdx.x], y = sh[threadIdx.x + o];
+            sh[threadIdx.x] = op == 0 ? fminf(x, y) : op == 1 ? fmaxf(x, y) : x + y;
+        }
+        __syncthreads();
+    }
+    const float r = sh[0];
+    __syncthreads();
+    return r;
+}
+
+__global__ void __launch_bounds__(256) scale_stats_partial(const float* row_scale, u64 n, float* part)
+{
+    __shared__ float sh[256];
+    float mn = INFINITY, mx = 0.0f, sum = 0.0f;
+    for (u64 i = (u64)blockIdx.x * 256 + threadIdx.x; i < n; i += (u64)gridDim.x * 256) {
+        const float r = rcp_down(row_scale[i]);
+        if (r == r) { mn = fminf(mn, r); mx = fmaxf(mx, r); sum += fminf(r, 3.0e30f); }
+    }
+    mn = block_reduce(mn, sh, 0); mx = block_reduce(mx, sh, 1); sum = block_reduce(sum, sh, 2);
+    if (threadIdx.x == 0) { part[3 * blockIdx.x] = mn; part[3 * blockIdx.x + 1] = mx; part[3 * blockIdx.x + 2] = sum; }
+}
+
+__global__ void __launch_bounds__(256) scale_stats_final(const float* part, uint32_t nparts, u64 n, float* out)
+{
+    __shared__ float sh[256];
+    float mn = INFINITY, mx = 0.0f, sum = 0.0f;
+    for (uint32_t i = threadIdx.x; i < nparts; i += 256) {
+        mn = fminf(mn, part[3 * i]); mx = fmaxf(mx, part[3 * i + 1]); sum += part[3 * i + 2];
+    }
+    mn = block_reduce(mn, sh, 0); mx = block_reduce(mx, sh, 1); sum = block_reduce(sum, sh, 2);
+    if (threadIdx.x == 0) {
+        const float mean = sum / (float)n;
+        float span = fminf(mx - mn, 2.0f * (mean - mn));
+        const bool ok = mn > 0.0f && mn < 3.0e38f;
+        const bool usable = ok && span > 0.0f && span < 3.0e38f;
+        out[0] = ok ? mn : 0.0f;                               // 0: the bound degenerates to "everything may matter"
+        out[1] = usable ? (127.0f / span) * 0.99999f : 0.0f;
+        out[2] = usable ? (span / 127.0f) * 0.99999f : 0.0f;
+    }
+}
+
+__global__ void __launch_bounds__(256) scale_code_kernel(const float* row_scale, u64 n, u64 n_pad, const float* stats, uint8_t* out)
+{
+    const float rmin = stats[0], e_per_r = stats[1];
+    for (u64 i = (u64)blockIdx.x * 256 + threadIdx.x; i < n_pad; i += (u64)gridDim.x * 256) {
+        float ef = 0.0f;
+        if (i < n) ef = fminf(fmaxf((rcp_down(row_scale[i]) - rmin) * e_per_r, 0.0f), 127.0f);    // NaN -> 0
+        out[i] = (uint8_t)ef;
     }
 }
 
@@ -1061,7 +1592,8 @@ __global__ void __launch_bounds__(64 * WPB) scan_kernel_lds(linr_scan_args A)
                 }
                 const bool lane_hot = tile_hot<VK, MAGIC>(acc, tf, tc, smax4, umax4);
                 if (wave_any(lane_hot))
-                    tile_survivors<VK, MAGIC, CH>(acc, lane_hot, mk4, qs.fall[qi], qs.fnone[qi], qs, qi, qi, ib, item0, L.sc, L.ts, A,
+                    tile_survivors<VK, MAGIC, CH>(acc, lane_hot, mk4, qs.fall[qi], qs.fnone[qi], qs, qi, qi, ib, item0,
+                                                  [&] { return *(const v4f*)&L.sc[ib]; }, [&] { return *(const v4u*)&L.ts[ib]; }, A,
                                                   slot, has_ts, need_compact);
             }
         }
@@ -1439,6 +1971,21 @@ static hipError_t coop_dispatch(int dtype, int vk, uint32_t ks, uint32_t m, uint
     return hipErrorInvalidDeviceFunction;
 }
 
+#define WIDE_CASE(VK, KS_, QW_)                                                                   \
+    if (dtype == LINR_I8 && vk == VK && ks == KS_ && m == 1 && qw == QW_)                         \
+        return scan_act(scan_kernel_wide<VK, KS_, QW_>, act);
+
+static hipError_t wide_dispatch(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qw, ScanAct& act)
+{
+    WIDE_CASE(LINR_VK_I8_SCALED, 1, 1) WIDE_CASE(LINR_VK_I8_SCALED, 1, 2)
+    WIDE_CASE(LINR_VK_I8_RAW, 1, 1)    WIDE_CASE(LINR_VK_I8_RAW, 1, 2)
+    WIDE_CASE(LINR_VK_I8_SCALED, 2, 1) WIDE_CASE(LINR_VK_I8_SCALED, 2, 2)
+    WIDE_CASE(LINR_VK_I8_RAW, 2, 1)    WIDE_CASE(LINR_VK_I8_RAW, 2, 2)
+    WIDE_CASE(LINR_VK_I8_SCALED, 4, 1) WIDE_CASE(LINR_VK_I8_SCALED, 4, 2)
+    WIDE_CASE(LINR_VK_I8_RAW, 4, 1)    WIDE_CASE(LINR_VK_I8_RAW, 4, 2)
+    return hipErrorInvalidDeviceFunction;
+}
+
 #define LDS_CASE(DT, VK, KS_)                                                                      \
     if (dtype == DT && vk == VK && ks == KS_) return scan_act(scan_kernel_lds<DT, VK, KS_>, act);
 
@@ -1467,6 +2014,25 @@ int linr_coop_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_
     return coop_dispatch(dtype, vk, ks, m, qg, act) == hipSuccess;
 }
 
+int linr_wide_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qw)
+{
+    ScanAct act{}; act.what = ACT_EXISTS;
+    return wide_dispatch(dtype, vk, ks, m, qw, act) == hipSuccess;
+}
+
+hipError_t linr_launch_scale_stats(const float* row_scale, uint64_t n, uint64_t n_pad, float* part, float* out, uint8_t* codes,
+                                   hipStream_t s)
+{
+    hipLaunchKernelGGL(scale_stats_partial, dim3(LINR_SCALE_STAT_BLOCKS), dim3(256), 0, s, row_scale, (u64)n, part);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(scale_stats_final, dim3(1), dim3(256), 0, s, (const float*)part, (uint32_t)LINR_SCALE_STAT_BLOCKS, (u64)n, out);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(scale_code_kernel, dim3(4096), dim3(256), 0, s, row_scale, (u64)n, (u64)n_pad, (const float*)out, codes);
+    return hipGetLastError();
+}
+
 uint32_t linr_lds_scan_dynamic_bytes(uint32_t B, uint32_t m, uint32_t ks)
 {
     uint32_t nsg = (B + 15) / 16;
@@ -1480,6 +2046,7 @@ static hipError_t plan_dispatch(const linr_plan& p, int dtype, uint32_t B, uint3
         return lds_dispatch(dtype, p.vk, p.ks, act);
     }
     act.dyn = 0;
+    if (p.wide) return wide_dispatch(dtype, p.vk, p.ks, m, p.qg, act);
     if (p.coop) return coop_dispatch(dtype, p.vk, p.ks, m, p.qg, act);
     return scan_dispatch(dtype, p.vk, p.ks, m, p.qg, ts, act);
 }

@@ -206,14 +206,46 @@ def test_float_shapes_served_by_the_lds_kernel(oracle_mod, dtype, d, m):
     assert_float_rule(oracle_mod, w, gpu, k, label=f"lds float d={d} m={m}")
 
 
-@pytest.mark.parametrize("tuning", [dict(coop_min_groups=2), dict(no_coop=1, max_qg=4), dict(no_coop=1, max_qg=16)])
+@pytest.mark.parametrize("tuning", [dict(wide_min_batch=65), dict(coop_min_groups=2), dict(no_coop=1, max_qg=4), dict(no_coop=1, max_qg=16)])
 def test_kernel_families_agree_on_a_large_batch(oracle_mod, tuning):
-    """the same 200-query batch through the workgroup-cooperative kernel, split over several waves per
-    chunk, and with 16 query groups in one wave"""
+    """the same 200-query batch through the 32x32-tile kernel, the 16x16-tile workgroup-cooperative kernel, split
+    over several waves per chunk, and with 16 query groups in one wave"""
     say(f"kernel families {tuning}")
     w = rand_int8_workload(55, 60_000, 64, 200, scaled=True, with_ts=True)
     gpu = run_gpu(to_cuda(w), k=300, tuning=tuning)
     assert_exact(gpu, run_oracle(oracle_mod, w, 300), f"family {tuning}")
+
+
+@pytest.mark.parametrize("n,d,B,k,scaled,with_ts", [(60_000, 64, 65, 100, False, False), (33_333, 128, 300, 200, True, False),
+                                                    (20_001, 256, 130, 64, False, True), (40_000, 64, 600, 50, True, True),
+                                                    (25_000, 128, 512, 100, True, False), (31, 64, 100, 40, True, False)])
+def test_wide_tile_kernel_shapes(oracle_mod, n, d, B, k, scaled, with_ts):
+    """32x32-tile kernel: one, two and four K-steps of 64 bytes, short rows, 1 / 2 / 4 query groups per wave, several
+    passes, ragged item and query counts"""
+    say(f"wide kernel n={n} d={d} B={B} k={k} scaled={scaled} ts={with_ts}")
+    w = rand_int8_workload(n + B, n, d, B, scaled=scaled, with_ts=with_ts)
+    gpu = run_gpu(to_cuda(w), k=k, tuning=dict(wide_min_batch=1))
+    assert_exact(gpu, run_oracle(oracle_mod, w, k), f"wide n={n} d={d} B={B}")
+
+
+def test_wide_tile_kernel_small_batch_and_compaction(oracle_mod):
+    """forced for a 5-query batch; then ascending scores in one full sweep so that segments fill and are compacted"""
+    import torch
+    say("wide kernel forced, B=5; adversarial ascending order B=70")
+    w = rand_int8_workload(77, 50_000, 64, 5, scaled=True)
+    gpu = run_gpu(to_cuda(w), k=500, tuning=dict(wide_min_batch=1))
+    assert_exact(gpu, run_oracle(oracle_mod, w, 500), "wide B=5")
+    n, d, B, k = 300_000, 64, 70, 100
+    rng = np.random.default_rng(6)
+    level = (np.arange(n) * 120 // n).astype(np.int8)[:, None]
+    emb = torch.from_numpy((level + rng.integers(0, 2, (n, d), dtype=np.int8)).astype(np.int8))
+    Q = torch.from_numpy(np.ones((B, 1, d), np.int8))
+    mask = torch.from_numpy(rng.integers(0, 2 ** 32, n, dtype=np.uint64).astype(np.uint32).view(np.int32))
+    f = S.make_filters(B); f["all_bits"][1] = 1; f["all_bits"][2] = 3; f["none_bits"][3] = 4
+    scale = torch.from_numpy(rng.uniform(0.9, 1.1, n).astype(np.float32))
+    w = dict(dtype=S.I8, d=d, m=1, k=k, emb=emb, scale=scale, mask=mask, ts=None, Q=Q, q_scale=None, filters=f)
+    gpu = run_gpu(to_cuda(w), k=k, tuning=dict(max_levels=1, blocks_per_cu=1, wide_min_batch=1))
+    assert_exact(gpu, run_oracle(oracle_mod, w, k), "wide adversarial scaled")
 
 
 def test_coop_kernel_bf16_and_multi_embedding(oracle_mod):
