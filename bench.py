@@ -26,9 +26,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 INT8_PEAK_TOPS = 5000.0        # MI355X dense int8 MFMA
 BYTES_PER_ITEM = 64 + 4 + 4    # codes + mask + row scale: the algorithmic HBM bytes of one item
-# HBM bytes of one full-sweep launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same
-# counter reads for a 4 GiB device copy (profiles/scan_kernel_cfg5_B32_pass5.md); keyed by (N, B, pass rate, k)
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes of the largest sweep's launch (7/8 of the items) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
+# scaled by what the same counter reads for a 4 GiB device copy (profiles/scan_kernel_cfg5_B32_pass5.md); keyed by
+# (N, B, pass rate, k).  30,767,340 KiB fetched x 2.000 + 10,461 KiB written x 1.000.
+MEASURED_TRAFFIC_BYTES = {(1_000_000_000, 32, "5%", 1000): 63_022_224_384}
 
 
 def log(msg):
