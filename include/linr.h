@@ -100,7 +100,10 @@ int linr_index_create(linr_index** out, uint64_t capacity, uint32_t d, int dtype
  * int8: symmetric codes with one positive fp32 scale per row; row_scale == NULL
  * selects raw ranking (see linr_search_filtered).  This quantised layout is this
  * library's memory-saving representation (the paper's own is the 1-bit code of
- * Sec. 3.2); it keeps a 1e9 x 64 index at 72 GB.
+ * Sec. 3.2); it keeps a 1e9 x 64 index at 72 GB.  With row scales the index also
+ * owns one code byte per item derived from them (library-allocated at load, in every
+ * LINR_SRC_* mode; used by the 32x32-tile kernel).  The loaders allocate device
+ * memory and synchronise; the search never does.
  */
 int linr_index_load_fp32(linr_index*, const float* emb, const uint32_t* mask, const uint32_t* ts,
                          uint64_t n, int src);
