@@ -1044,6 +1044,27 @@ __device__ __forceinline__ float rcp_down(float scale)
     return __builtin_amdgcn_rcpf(scale) * 0.999999f;
 }
 
+// One K = 32-byte step of a 32x32 product block.  The accumulators are kept as 32-bit patterns for both element
+// types: float products are only ever compared, and for a positive bound "some value >= bound" is the same
+// statement about the bit patterns read as signed integers (negative floats are negative integers).
+typedef float v16f __attribute__((ext_vector_type(16)));
+template <int DT>
+__device__ __forceinline__ v16i wide_mfma(const v4i& a, const v4i& b, const v16i& c)
+{
+    if constexpr (DT == LINR_I8) {
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+    } else {
+        const v16f r = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b),
+                                                                __builtin_bit_cast(v16f, c), 0, 0, 0);
+        return __builtin_bit_cast(v16i, r);
+    }
+}
+// bound of the bit patterns for a float threshold (no usable bound unless it is positive)
+__device__ __forceinline__ int float_bound_bits(float thr)
+{
+    return thr > 0.0f ? __float_as_int(thr) : INT_MIN;
+}
+
 // One stage of the chunk ring in LDS, filled by direct global -> LDS loads (no registers in between, so
 // several chunks can be in flight per workgroup).  Such a load writes the 64 lanes' data to consecutive
 // LDS addresses, so block f of `a` (1 KB) holds a 16-row x 64-byte piece of the chunk as
@@ -1187,7 +1208,7 @@ __device__ __forceinline__ void wide_query_bound(float thr, float rmin, float r_
     }
 }
 
-template <int VK, int KS, int QW>
+template <int DT, int VK, int KS, int QW>
 __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A)
 {
     constexpr int CH = 256 / KS;
@@ -1196,7 +1217,9 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A
     constexpr int NQ = QW * 32;
     constexpr int NST = 3;                               // ring stages: NST - 1 chunks (16 KB each) are in flight per workgroup
     constexpr bool SCALED = (VK == LINR_VK_I8_SCALED);
+    constexpr bool FLOATS = (VK == LINR_VK_FLOAT);
     static_assert(KS == 1 || KS == 2 || KS == 4, "rows of 64, 128 or 256 bytes");
+    static_assert((DT == LINR_I8 && !FLOATS) || (DT == LINR_BF16 && FLOATS), "int8 and bf16 only");
 
     constexpr int QCAP = LINR_WIDE_QCAP;
     constexpr int SCRATCH_WORDS = 2 * QCAP + QCAP / 4 + 4;   // keys, query numbers, count (last word)
@@ -1247,7 +1270,7 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A
                 wide_query_bound(W.thr_f[i * 32 + col], rmin, r_per_e, h2, bound[i], G, qe[i]);
                 if (h2 == 0) W.thr_i[i * 32 + col] = G;  // (thr_i is not used otherwise for this ranking kind)
             } else {
-                bound[i] = W.thr_i[i * 32 + col];
+                bound[i] = FLOATS ? float_bound_bits(W.thr_f[i * 32 + col]) : W.thr_i[i * 32 + col];
                 qe[i] = (v4i){0, 0, 0, 0};
             }
         }
@@ -1324,7 +1347,7 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A
                 for (int s = 0; s < NK; ++s)
 #pragma unroll
                     for (int i = 0; i < QW; ++i)
-                        acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[s], q[i][s], s == 0 ? zero16 : acc[i], 0, 0, 0);
+                        acc[i] = wide_mfma<DT>(a[s], q[i][s], s == 0 ? zero16 : acc[i]);
                 if constexpr (SCALED) {
                     const int rep = (int)(ecode * 0x01010101u);
                     const v4i ae = {rep, rep, rep, rep};
@@ -1335,18 +1358,11 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A
             uint32_t pend = 0;                       // groups of this tile whose test fired (uniform)
 #pragma unroll
             for (int i = 0; i < QW; ++i) pend |= wave_any(max16(acc[i]) >= bound[i]) ? (1u << i) : 0u;
-#ifdef LINR_EXP_NOSLOW
-            pend &= (uint32_t)(A.k >> 20);                  // (never fires in the experiment: k < 2^20)
-#endif
             STAT_ADD(0, QW);
             const long long t_slow = pend ? STAT_CLOCK() : 0ll;
             (void)t_slow;
             if (pend) STAT_ADD(1, __popc(pend));
             const uint32_t pend_any = pend;
-#ifdef LINR_EXP_NOSLOW
-            if (pend && lane == 0) atomicAdd(A.cnt, pend);   // keeps the products alive without the survivor path
-            pend = 0;
-#endif
             while (pend) {
                 const int i = __ffs((int)pend) - 1;
                 pend &= pend - 1;
@@ -1360,7 +1376,7 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A
                     G = W.thr_i[ql];
                     bi = floor_to_int(lowered_pos(W.thr_f[ql]) * rmin);
                 } else {
-                    bi = W.thr_i[ql];
+                    bi = FLOATS ? float_bound_bits(W.thr_f[ql]) : W.thr_i[ql];
                 }
                 const uint32_t fa = W.fall[ql], fn = W.fnone[ql];
 #pragma unroll
@@ -1388,9 +1404,17 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A
                             since_refresh = 64;                       // bounds moved: reload them after this chunk
                         }
                     }
-                    tile_survivors<VK, false, CH, true>(acc4, lane_hot, mk4, fa, fn, qs, ql, q_first + ql, ib, item0,
-                                                        [&] { return sc4; }, [&] { return ts4; }, A, slot, has_ts, need_compact,
-                                                        qcount, qkey, qql);
+                    if constexpr (FLOATS) {
+                        const v4f accf = {__int_as_float(acc4[0]), __int_as_float(acc4[1]), __int_as_float(acc4[2]),
+                                          __int_as_float(acc4[3])};
+                        tile_survivors<VK, false, CH, true>(accf, lane_hot, mk4, fa, fn, qs, ql, q_first + ql, ib, item0,
+                                                            [&] { return sc4; }, [&] { return ts4; }, A, slot, has_ts,
+                                                            need_compact, qcount, qkey, qql);
+                    } else {
+                        tile_survivors<VK, false, CH, true>(acc4, lane_hot, mk4, fa, fn, qs, ql, q_first + ql, ib, item0,
+                                                            [&] { return sc4; }, [&] { return ts4; }, A, slot, has_ts,
+                                                            need_compact, qcount, qkey, qql);
+                    }
                 }
             }
             if (pend_any) STAT_ADD(6, STAT_CLOCK() - t_slow);
@@ -1971,18 +1995,21 @@ static hipError_t coop_dispatch(int dtype, int vk, uint32_t ks, uint32_t m, uint
     return hipErrorInvalidDeviceFunction;
 }
 
-#define WIDE_CASE(VK, KS_, QW_)                                                                   \
-    if (dtype == LINR_I8 && vk == VK && ks == KS_ && m == 1 && qw == QW_)                         \
-        return scan_act(scan_kernel_wide<VK, KS_, QW_>, act);
+#define WIDE_CASE(DT, VK, KS_, QW_)                                                               \
+    if (dtype == DT && vk == VK && ks == KS_ && m == 1 && qw == QW_)                              \
+        return scan_act(scan_kernel_wide<DT, VK, KS_, QW_>, act);
 
 static hipError_t wide_dispatch(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qw, ScanAct& act)
 {
-    WIDE_CASE(LINR_VK_I8_SCALED, 1, 1) WIDE_CASE(LINR_VK_I8_SCALED, 1, 2)
-    WIDE_CASE(LINR_VK_I8_RAW, 1, 1)    WIDE_CASE(LINR_VK_I8_RAW, 1, 2)
-    WIDE_CASE(LINR_VK_I8_SCALED, 2, 1) WIDE_CASE(LINR_VK_I8_SCALED, 2, 2)
-    WIDE_CASE(LINR_VK_I8_RAW, 2, 1)    WIDE_CASE(LINR_VK_I8_RAW, 2, 2)
-    WIDE_CASE(LINR_VK_I8_SCALED, 4, 1) WIDE_CASE(LINR_VK_I8_SCALED, 4, 2)
-    WIDE_CASE(LINR_VK_I8_RAW, 4, 1)    WIDE_CASE(LINR_VK_I8_RAW, 4, 2)
+    WIDE_CASE(LINR_I8, LINR_VK_I8_SCALED, 1, 1) WIDE_CASE(LINR_I8, LINR_VK_I8_SCALED, 1, 2)
+    WIDE_CASE(LINR_I8, LINR_VK_I8_RAW, 1, 1)    WIDE_CASE(LINR_I8, LINR_VK_I8_RAW, 1, 2)
+    WIDE_CASE(LINR_I8, LINR_VK_I8_SCALED, 2, 1) WIDE_CASE(LINR_I8, LINR_VK_I8_SCALED, 2, 2)
+    WIDE_CASE(LINR_I8, LINR_VK_I8_RAW, 2, 1)    WIDE_CASE(LINR_I8, LINR_VK_I8_RAW, 2, 2)
+    WIDE_CASE(LINR_I8, LINR_VK_I8_SCALED, 4, 1) WIDE_CASE(LINR_I8, LINR_VK_I8_SCALED, 4, 2)
+    WIDE_CASE(LINR_I8, LINR_VK_I8_RAW, 4, 1)    WIDE_CASE(LINR_I8, LINR_VK_I8_RAW, 4, 2)
+    WIDE_CASE(LINR_BF16, LINR_VK_FLOAT, 1, 1)   WIDE_CASE(LINR_BF16, LINR_VK_FLOAT, 1, 2)
+    WIDE_CASE(LINR_BF16, LINR_VK_FLOAT, 2, 1)   WIDE_CASE(LINR_BF16, LINR_VK_FLOAT, 2, 2)
+    WIDE_CASE(LINR_BF16, LINR_VK_FLOAT, 4, 1)   WIDE_CASE(LINR_BF16, LINR_VK_FLOAT, 4, 2)
     return hipErrorInvalidDeviceFunction;
 }
 

@@ -143,8 +143,7 @@ def config1(device="cpu", n=100_000, B=16, k=100):
     return dict(dtype=F32, d=d, m=1, k=k, emb=emb, scale=None, mask=mask, ts=None, Q=Q, q_scale=None, filters=filt)
 
 
-def config2(device="cpu", n=10_000_000, B=256, k=1000, p=0.5, C=1000, sigma=0.3, chunk=4_000_000):
-    d = 128
+def config2(device="cpu", n=10_000_000, B=256, k=1000, p=0.5, C=1000, sigma=0.3, chunk=4_000_000, d=128):
     cen = unit_centres(C, d, device, _seed(2, 0))
     emb = torch.empty(n, d, dtype=torch.int16, device=device)
     for i, s in enumerate(range(0, n, chunk)):

@@ -248,6 +248,15 @@ def test_wide_tile_kernel_small_batch_and_compaction(oracle_mod):
     assert_exact(gpu, run_oracle(oracle_mod, w, k), "wide adversarial scaled")
 
 
+@pytest.mark.parametrize("d,B,n,k", [(128, 150, 60_000, 200), (64, 256, 45_001, 100), (32, 70, 30_000, 1000)])
+def test_wide_tile_kernel_bf16(oracle_mod, d, B, n, k):
+    """32x32-tile kernel on bf16 rows of 256, 128 and 64 bytes (cfg 2 generator with other shapes)"""
+    say(f"wide kernel bf16 d={d} B={B} n={n} k={k}")
+    w = S.config2(n=n, B=B, k=k, p=0.5, chunk=n, d=d)
+    gpu = run_gpu(to_cuda(w), tuning=dict(wide_min_batch=1))
+    assert_float_rule(oracle_mod, w, gpu, w["k"], label=f"wide bf16 d={d}")
+
+
 def test_coop_kernel_bf16_and_multi_embedding(oracle_mod):
     say("coop kernel: bf16 d=128 B=150; bf16 d=64 m=8 B=40")
     w = S.config2(n=60_000, B=150, k=200, p=0.5, chunk=60_000)
