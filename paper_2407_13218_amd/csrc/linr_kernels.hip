@@ -1658,7 +1658,7 @@ __global__ void init_kernel(u64* tau, uint32_t* ccnt, uint32_t* gcnt, uint32_t* 
 // the result.
 // ---------------------------------------------------------------------------
 #define MT 1024
-#define MERGE_LDS_KEYS 8192
+#define MERGE_LDS_KEYS 14336                    /* 112 KB of the 160 KB a workgroup may use */
 #define NPIECE (LINR_FLAT_REGIONS + 1)
 struct MergeLds {
     union {
@@ -1710,10 +1710,17 @@ __device__ __forceinline__ void for_each_candidate(const linr_merge_args& A, con
     }
 }
 
+// int32 dot product of two int8 rows (16-byte aligned, d a multiple of 16), 16 bytes per load
 __device__ __forceinline__ int dot_i8_row(const int8_t* q, const int8_t* x, uint32_t d)
 {
     int s = 0;
-    for (uint32_t j = 0; j < d; ++j) s += (int)q[j] * (int)x[j];
+    for (uint32_t j = 0; j < d; j += 16) {
+        const v4i a = *(const v4i*)(q + j), b = *(const v4i*)(x + j);
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+            for (int sh = 24; sh >= 0; sh -= 8) s += ((a[w] << sh) >> 24) * ((b[w] << sh) >> 24);
+    }
     return s;
 }
 
