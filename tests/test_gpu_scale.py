@@ -1,5 +1,6 @@
-"""Parity at the full benchmark size (config 5: 1e9 x d64 int8 resident in HBM, the launch configuration bench.py
-times).  The CPU oracle cannot hold 72 GB at once, so
+"""Parity at the full sizes of the five configurations.  Configs 2, 3 and 4 fit in host memory: the GPU answers the
+whole batch and the oracle scans the whole index for all (config 3) or every 16th query.  Config 5 (1e9 x d64 int8
+resident in HBM, the launch configuration bench.py times): the CPU oracle cannot hold 72 GB at once, so
   (a) every returned (query, id) pair of the whole batch is re-scored by the oracle one by one (rows gathered on the
       GPU, copied to the host): raw int32 dot, fp32 score bits, feasibility, ordering, uniqueness, counts;
   (b) for a few queries the oracle scans the entire index, streamed device->host in 16 M-item pieces; the per-piece
@@ -90,3 +91,46 @@ def test_config5_full_size_matches_oracle(oracle_mod):
         assert np.array_equal(best[j]["raw"], raw[b]) and best[j]["sc"].tobytes() == sc[b].tobytes()
         say(f"query {b} @ {sel}: top-{k} of {N_FULL:,} items identical to the oracle's")
     ix.close()
+
+
+def _full_size_case(oracle_mod, w, picks, label):
+    """GPU search on the whole batch; the oracle scans the whole (host-resident) index for the picked queries."""
+    from gpu_util import run_gpu, to_cuda, assert_exact, assert_float_rule
+    k = w["k"]
+    gpu = run_gpu(to_cuda(w), k=k)
+    say(f"{label}: GPU search done")
+    sub = dict(w)
+    sub["Q"] = w["Q"][picks]
+    sub["filters"] = w["filters"][picks]
+    sub["q_scale"] = None if w["q_scale"] is None else w["q_scale"][picks]
+    gpu_sub = tuple(None if a is None else a[picks] for a in gpu)
+    threads = max(1, min(16, os.cpu_count() or 1))
+    if w["dtype"] == S.I8:
+        h = S.to_numpy(sub)
+        ora = oracle_mod.search(S.I8, h["emb"], h["mask"], h["Q"], h["filters"], k, row_scale=h["scale"], ts=h["ts"],
+                                q_scale=h["q_scale"], nthreads=threads)
+        assert_exact(gpu_sub, ora, label)
+    else:
+        assert_float_rule(oracle_mod, sub, gpu_sub, k, label=label)
+    say(f"{label}: {len(picks)} queries identical to / within tolerance of the oracle's full scan")
+
+
+def test_config3_full_size(oracle_mod):
+    """5e7 x d64 int8 + timestamps, 16 queries, k = 1000: all queries against a full oracle scan, exact"""
+    say("generating config 3 at full size")
+    w = S.config3(device="cuda")
+    _full_size_case(oracle_mod, w, list(range(16)), "config 3 full size")
+
+
+def test_config2_full_size(oracle_mod):
+    """1e7 x d128 bf16, 256 queries, k = 1000: every 16th query against a full oracle scan (1e-3 rule)"""
+    say("generating config 2 at full size")
+    w = S.config2(device="cuda", p=0.5)
+    _full_size_case(oracle_mod, w, list(range(0, 256, 16)), "config 2 full size")
+
+
+def test_config4_full_size(oracle_mod):
+    """2e7 x d64 bf16, 128 queries x 8 embeddings, k = 500: eight queries against a full oracle scan (1e-3 rule)"""
+    say("generating config 4 at full size")
+    w = S.config4(device="cuda")
+    _full_size_case(oracle_mod, w, list(range(0, 128, 16)), "config 4 full size")
