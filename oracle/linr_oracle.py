@@ -20,16 +20,18 @@ FILTER_DTYPE = np.dtype([
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "linr_oracle.c")
+_SRC_BITS = os.path.join(_HERE, "linr_oracle_bits.c")
 _LIB = os.path.join(_HERE, "liblinr_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (no fast-math, no FMA contraction)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_BITS))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         tmp = _LIB + f".tmp{os.getpid()}"
         subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
-                               "-o", tmp, _SRC, "-lpthread", "-lm"])
+                               "-o", tmp, _SRC, _SRC_BITS, "-lpthread", "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -49,6 +51,12 @@ def _load():
         lib.linr_oracle_dot_f64.argtypes = [i32, vp, vp, u32]
         lib.linr_oracle_pass.restype = i32
         lib.linr_oracle_pass.argtypes = [vp, u32, i32, u32]
+        lib.linr_oracle_sign_oporp.restype = i32
+        lib.linr_oracle_sign_oporp.argtypes = [vp, u64, u32, vp, vp, u32, vp]
+        lib.linr_oracle_bit_matches.restype = u32
+        lib.linr_oracle_bit_matches.argtypes = [vp, vp, u32, u32]
+        lib.linr_oracle_bits_search.restype = i32
+        lib.linr_oracle_bits_search.argtypes = [vp, u32, u32, vp, vp, u64, u64, vp, u32, vp, u32, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -121,3 +129,74 @@ def passes(filt_record, mask, ts=None):
     lib = _load()
     f = np.ascontiguousarray(np.asarray(filt_record, dtype=FILTER_DTYPE).reshape(1))
     return bool(lib.linr_oracle_pass(_ptr(f), int(mask), 0 if ts is None else 1, 0 if ts is None else int(ts)))
+
+
+# ---------------------------------------------------------------------------
+# quantised search (Sec. 3.2): Sign-OPORP codes, bit matching, two-stage search
+# ---------------------------------------------------------------------------
+def widen(dtype, a):
+    """fp32 array or bf16 bit patterns (uint16) -> float64, exactly."""
+    a = np.ascontiguousarray(a)
+    if dtype == F32:
+        return a.astype(np.float64)
+    if dtype == BF16:
+        return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    raise TypeError("Sign-OPORP codes are built from fp32 or bf16 embeddings")
+
+
+def sign_oporp(dtype, x, perm, signs, k_bits):
+    """x [n, D] (fp32 or bf16 bit patterns) -> codes [n, ceil(k_bits/64)] uint64."""
+    lib = _load()
+    xd = np.ascontiguousarray(widen(dtype, x))
+    n, D = xd.shape
+    perm = _c(perm, np.uint32); signs = _c(signs, np.int8)
+    assert perm.shape == (D,) and signs.shape == (D,)
+    W = (k_bits + 63) // 64
+    out = np.zeros((n, W), np.uint64)
+    if lib.linr_oracle_sign_oporp(_ptr(xd), n, D, _ptr(perm), _ptr(signs), k_bits, _ptr(out)) != 0:
+        raise ValueError("D must be a positive multiple of k_bits")
+    return out
+
+
+def bit_matches(a, b, k_bits):
+    a = _c(a, np.uint64); b = _c(b, np.uint64)
+    return int(_load().linr_oracle_bit_matches(_ptr(a), _ptr(b), a.size, k_bits))
+
+
+def bits_search(bits, k_bits, mask, qbits, filters, T, ts=None, id_base=0):
+    """Filtered top-T by number of matching bits (desc), id (asc).  Returns ids [B,T], matches [B,T], counts [B]."""
+    lib = _load()
+    bits = _c(bits, np.uint64); qbits = _c(qbits, np.uint64)
+    n, W = bits.shape
+    B = qbits.shape[0]
+    mask = _c(mask, np.uint32); ts = _c(ts, np.uint32)
+    filters = np.ascontiguousarray(filters)
+    assert filters.dtype.itemsize == 40 and filters.shape == (B,)
+    ids = np.empty((B, T), np.uint32); mt = np.empty((B, T), np.int32); cnt = np.empty(B, np.uint32)
+    rc = lib.linr_oracle_bits_search(_ptr(bits), W, k_bits, _ptr(mask), _ptr(ts), n, id_base, _ptr(qbits), B, _ptr(filters), T,
+                                     _ptr(ids), _ptr(mt), _ptr(cnt))
+    if rc != 0:
+        raise MemoryError
+    return ids, mt, cnt
+
+
+def two_stage(dtype, emb, mask, Q, filters, perm, signs, k_bits, T, k, ts=None):
+    """Figure "KNN with Quantized Filtering": top-T by bit matching, then the exact scores of those T items, then
+    top-k by (score desc, id asc).  Q [B, d] or [B, 1, d].  Returns ids [B,k], scores [B,k] (float32), counts [B]."""
+    Q2 = Q.reshape(Q.shape[0], -1)
+    bits = sign_oporp(dtype, emb, perm, signs, k_bits)
+    qbits = sign_oporp(dtype, Q2, perm, signs, k_bits)
+    ids1, _, cnt1 = bits_search(bits, k_bits, mask, qbits, filters, T, ts=ts)
+    B = Q2.shape[0]
+    out_ids = np.full((B, k), NO_ID, np.uint32); out_sc = np.full((B, k), -np.inf, np.float32); out_cnt = np.zeros(B, np.uint32)
+    for b in range(B):
+        c = int(cnt1[b])
+        if c == 0:
+            continue
+        cand = ids1[b, :c].astype(np.uint64)
+        rank, _, feas = pairs(dtype, emb, mask, Q, filters, np.full(c, b, np.uint32), cand, ts=ts)
+        assert feas.all()
+        order = np.lexsort((cand, -rank))[:k]
+        kk = len(order)
+        out_ids[b, :kk] = cand[order].astype(np.uint32); out_sc[b, :kk] = rank[order].astype(np.float32); out_cnt[b] = kk
+    return out_ids, out_sc, out_cnt
