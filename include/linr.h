@@ -28,7 +28,8 @@ extern "C" {
 
 typedef struct linr_index linr_index;       /* opaque; created/destroyed by the library */
 
-enum { LINR_F32 = 0, LINR_BF16 = 1, LINR_I8 = 2 };          /* element type of the index */
+enum { LINR_F32 = 0, LINR_BF16 = 1, LINR_I8 = 2,            /* element type of the index */
+       LINR_BITS = 3 };                                      /* 1-bit codes only (see the quantised search below) */
 
 enum {
     LINR_OK = 0,
@@ -148,6 +149,49 @@ int linr_search_filtered(const linr_index*, const void* Q, const float* q_scale,
                          void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags);
 
 int linr_index_destroy(linr_index*);
+
+/*
+ * Quantised search (Sec. 3.2 "Quantized KNN" and the figure "KNN with Quantized
+ * Filtering").  An embedding is compressed to k_bits one-bit values by Sign-OPORP:
+ *     sketch[j] = sum_{t < L} signs[j*L+t] * x[perm[j*L+t]],  L = d / k_bits,
+ *     bit[j]    = sketch[j] > 0
+ * (perm: a permutation of 0..d-1; signs: +1 / -1; both drawn once by the caller and
+ * shared by items and queries; sums in double precision, t ascending).  Bit j is bit
+ * j%64 of 64-bit word j/64; a code is W = ceil(k_bits/64) words.  The similarity of two
+ * codes is their number of equal bits.  Limits: k_bits <= 256, d % k_bits == 0.
+ *
+ * linr_index_build_bits  derives the codes of every resident item of an fp32 / bf16
+ *     index (library-owned, n * W * 8 bytes); perm [d] and signs [d] are host arrays
+ *     (src == LINR_SRC_HOST) or device arrays (any other LINR_SRC_* value); copied.
+ * linr_index_load_bits   fills an index created with dtype LINR_BITS (d = k_bits) with
+ *     ready-made codes [n][W] plus mask / ts: a codes-only index (8 bytes per item at
+ *     64 bits) for when memory is the concern.  `src` as for the other loaders.
+ * linr_quantize_queries  codes of B query embeddings (device [B][d], index element
+ *     type) with the index's perm / signs -> device qbits [B][W].
+ * linr_search_bits       per query the T feasible items with the most matching bits,
+ *     ties to the lower id: out_ids / out_matches device [B][T] (padding LINR_NO_ID /
+ *     INT32_MIN), out_counts device [B] = min(T, #feasible).  qbits device [B][W],
+ *     16-byte aligned.  T <= LINR_MAX_K.  Exact with respect to the codes.
+ * linr_search_two_stage  quantises the queries, takes the top T by matching bits, scores
+ *     those T items with the full-precision embeddings (fp32 accumulation) and returns
+ *     the top k <= T by (score descending, id ascending): out_ids / out_scores device
+ *     [B][k], out_counts device [B] = min(k, T, #feasible).  m = 1.  An approximation of
+ *     linr_search_filtered whose recall grows with T; it equals it when T >= #feasible.
+ * Workspaces: device, 256-byte aligned, sizes from the *_workspace_bytes calls; filters,
+ * hip_stream and flags as for linr_search_filtered.  Errors as there, plus LINR_E_DTYPE
+ * (index kind does not fit the call) and LINR_E_NOT_LOADED (no codes built yet).
+ */
+int linr_index_build_bits(linr_index*, const uint32_t* perm, const int8_t* signs, uint32_t k_bits, int src);
+int linr_index_load_bits(linr_index*, const uint64_t* bits, const uint32_t* mask, const uint32_t* ts, uint64_t n, int src);
+int linr_quantize_queries(const linr_index*, const void* Q, uint32_t B, uint64_t* qbits, void* hip_stream);
+int linr_search_bits_workspace_bytes(const linr_index*, uint32_t B, uint32_t T, uint64_t* bytes);
+int linr_search_bits(const linr_index*, const uint64_t* qbits, uint32_t B, const linr_filter* filters, uint32_t T,
+                     uint32_t* out_ids, int32_t* out_matches, uint32_t* out_counts,
+                     void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags);
+int linr_search_two_stage_workspace_bytes(const linr_index*, uint32_t B, uint32_t T, uint32_t k, uint64_t* bytes);
+int linr_search_two_stage(const linr_index*, const void* Q, uint32_t B, const linr_filter* filters, uint32_t T, uint32_t k,
+                          uint32_t* out_ids, float* out_scores, uint32_t* out_counts,
+                          void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags);
 
 /* number of items currently resident / element type / dimensions */
 int linr_index_info(const linr_index*, uint64_t* n, uint32_t* d, int* dtype, int* has_ts, int* has_row_scale);

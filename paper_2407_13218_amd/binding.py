@@ -11,7 +11,7 @@ import ctypes as C
 import os
 import numpy as np
 
-F32, BF16, I8 = 0, 1, 2
+F32, BF16, I8, BITS = 0, 1, 2, 3
 NO_ID = 0xFFFFFFFF
 MAX_K = 2048
 MAX_M = 8
@@ -30,6 +30,8 @@ EXPORTS = [
     "linr_search_workspace_bytes", "linr_search_filtered", "linr_index_destroy", "linr_index_info",
     "linr_strerror", "linr_last_hip_error", "linr_set_tuning", "linr_search_filtered_timed",
     "linr_events_create", "linr_events_destroy", "linr_events_elapsed_ms",
+    "linr_index_build_bits", "linr_index_load_bits", "linr_quantize_queries", "linr_search_bits_workspace_bytes",
+    "linr_search_bits", "linr_search_two_stage_workspace_bytes", "linr_search_two_stage",
 ]
 
 
@@ -91,6 +93,20 @@ def load_library():
     lib.linr_events_destroy.argtypes = [vp, u32]
     lib.linr_events_elapsed_ms.restype = i32
     lib.linr_events_elapsed_ms.argtypes = [vp, u32, vp]
+    lib.linr_index_build_bits.restype = i32
+    lib.linr_index_build_bits.argtypes = [vp, vp, vp, u32, i32]
+    lib.linr_index_load_bits.restype = i32
+    lib.linr_index_load_bits.argtypes = [vp, vp, vp, vp, u64, i32]
+    lib.linr_quantize_queries.restype = i32
+    lib.linr_quantize_queries.argtypes = [vp, vp, u32, vp, vp]
+    lib.linr_search_bits_workspace_bytes.restype = i32
+    lib.linr_search_bits_workspace_bytes.argtypes = [vp, u32, u32, C.POINTER(u64)]
+    lib.linr_search_bits.restype = i32
+    lib.linr_search_bits.argtypes = [vp, vp, u32, vp, u32, vp, vp, vp, vp, u64, vp, u32]
+    lib.linr_search_two_stage_workspace_bytes.restype = i32
+    lib.linr_search_two_stage_workspace_bytes.argtypes = [vp, u32, u32, u32, C.POINTER(u64)]
+    lib.linr_search_two_stage.restype = i32
+    lib.linr_search_two_stage.argtypes = [vp, vp, u32, vp, u32, u32, vp, vp, vp, vp, u64, vp, u32]
     _lib = lib
     return lib
 
@@ -195,6 +211,44 @@ def events_elapsed_ms(ev, n_pairs: int):
     return [ms[i] for i in range(n_pairs)]
 
 
+def index_build_bits(ix, perm, signs, k_bits, src):
+    _check(load_library().linr_index_build_bits(ix, _ptr(perm), _ptr(signs), k_bits, src), "linr_index_build_bits")
+
+
+def index_load_bits(ix, bits, mask, ts, n, src):
+    _check(load_library().linr_index_load_bits(ix, _ptr(bits), _ptr(mask), _ptr(ts), n, src), "linr_index_load_bits")
+
+
+def quantize_queries(ix, Q, B, qbits, stream=0):
+    _check(load_library().linr_quantize_queries(ix, _ptr(Q), B, _ptr(qbits), stream), "linr_quantize_queries")
+
+
+def search_bits_workspace_bytes(ix, B, T) -> int:
+    out = C.c_uint64()
+    _check(load_library().linr_search_bits_workspace_bytes(ix, B, T, C.byref(out)), "linr_search_bits_workspace_bytes")
+    return out.value
+
+
+def search_bits(ix, qbits, B, filters, T, out_ids, out_matches, out_counts, workspace, workspace_bytes, stream=0,
+                flags=FILTERS_ON_DEVICE):
+    _check(load_library().linr_search_bits(ix, _ptr(qbits), B, _ptr(filters), T, _ptr(out_ids), _ptr(out_matches),
+                                           _ptr(out_counts), _ptr(workspace), workspace_bytes, stream, flags), "linr_search_bits")
+
+
+def search_two_stage_workspace_bytes(ix, B, T, k) -> int:
+    out = C.c_uint64()
+    _check(load_library().linr_search_two_stage_workspace_bytes(ix, B, T, k, C.byref(out)),
+           "linr_search_two_stage_workspace_bytes")
+    return out.value
+
+
+def search_two_stage(ix, Q, B, filters, T, k, out_ids, out_scores, out_counts, workspace, workspace_bytes, stream=0,
+                     flags=FILTERS_ON_DEVICE):
+    _check(load_library().linr_search_two_stage(ix, _ptr(Q), B, _ptr(filters), T, k, _ptr(out_ids), _ptr(out_scores),
+                                                _ptr(out_counts), _ptr(workspace), workspace_bytes, stream, flags),
+           "linr_search_two_stage")
+
+
 def set_tuning(**kw):
     """set_tuning() restores the defaults."""
     lib = load_library()
@@ -213,6 +267,7 @@ class Index:
     def __init__(self, capacity: int, d: int, dtype: int, device: int = 0):
         self.handle = index_create(capacity, d, dtype, device)
         self.dtype, self.d, self.device = dtype, d, device
+        self.k_bits = d if dtype == BITS else 0
         self._keep = None
 
     def load(self, emb, mask, ts=None, row_scale=None, src=None):
@@ -224,6 +279,8 @@ class Index:
             index_load_fp32(self.handle, emb, mask, ts, n, src)
         elif self.dtype == BF16:
             index_load_bf16(self.handle, emb, mask, ts, n, src)
+        elif self.dtype == BITS:
+            index_load_bits(self.handle, emb, mask, ts, n, src)              # `emb` = codes [n, W] (int64 bit patterns)
         else:
             index_load_int8(self.handle, emb, row_scale, mask, ts, n, src)
         self._keep = (emb, mask, ts, row_scale) if src == SRC_DEVICE_BORROW else None
@@ -261,6 +318,60 @@ class Index:
                         stream, flags)
         self._last_workspace = workspace
         return ids, scores, raw, counts
+
+    # ---- quantised search (Sec. 3.2) ----
+    def build_bits(self, perm, signs, k_bits):
+        """perm (uint32 [d]) and signs (int8 [d]): numpy (host) or device tensors"""
+        src = SRC_HOST if isinstance(perm, np.ndarray) else SRC_DEVICE_COPY
+        index_build_bits(self.handle, perm, signs, k_bits, src)
+        self.k_bits = k_bits
+        return self
+
+    def _filters(self, filters):
+        if isinstance(filters, np.ndarray):
+            return FILTERS_ON_HOST, np.ascontiguousarray(filters)
+        return FILTERS_ON_DEVICE, filters
+
+    def quantize(self, Q):
+        import torch
+        Q = Q.reshape(Q.shape[0], -1).contiguous()
+        W = (self.k_bits + 63) // 64
+        qbits = torch.empty((Q.shape[0], W), dtype=torch.int64, device=Q.device)
+        quantize_queries(self.handle, Q, Q.shape[0], qbits, torch.cuda.current_stream(Q.device).cuda_stream)
+        return qbits
+
+    def search_bits(self, qbits, filters, T):
+        """qbits: device int64 [B, W].  Returns device tensors ids, matches (int32), counts."""
+        import torch
+        qbits = qbits.contiguous()
+        B, dev = qbits.shape[0], qbits.device
+        ids = torch.empty((B, T), dtype=torch.int32, device=dev)
+        matches = torch.empty((B, T), dtype=torch.int32, device=dev)
+        counts = torch.empty((B,), dtype=torch.int32, device=dev)
+        if B == 0:
+            return ids, matches, counts
+        nbytes = search_bits_workspace_bytes(self.handle, B, T)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        flags, f = self._filters(filters)
+        search_bits(self.handle, qbits, B, f, T, ids, matches, counts, ws, nbytes, torch.cuda.current_stream(dev).cuda_stream, flags)
+        self._last_workspace = ws
+        return ids, matches, counts
+
+    def search_two_stage(self, Q, filters, T, k):
+        import torch
+        Q = Q.reshape(Q.shape[0], -1).contiguous()
+        B, dev = Q.shape[0], Q.device
+        ids = torch.empty((B, k), dtype=torch.int32, device=dev)
+        scores = torch.empty((B, k), dtype=torch.float32, device=dev)
+        counts = torch.empty((B,), dtype=torch.int32, device=dev)
+        if B == 0:
+            return ids, scores, counts
+        nbytes = search_two_stage_workspace_bytes(self.handle, B, T, k)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        flags, f = self._filters(filters)
+        search_two_stage(self.handle, Q, B, f, T, k, ids, scores, counts, ws, nbytes, torch.cuda.current_stream(dev).cuda_stream, flags)
+        self._last_workspace = ws
+        return ids, scores, counts
 
     def close(self):
         if self.handle:

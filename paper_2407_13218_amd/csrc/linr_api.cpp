@@ -49,10 +49,13 @@ extern "C" int linr_index_create(linr_index** out, uint64_t capacity, uint32_t d
 {
     if (!out) return LINR_E_NULL;
     *out = nullptr;
-    if (dtype != LINR_F32 && dtype != LINR_BF16 && dtype != LINR_I8) return LINR_E_DTYPE;
+    if (dtype != LINR_F32 && dtype != LINR_BF16 && dtype != LINR_I8 && dtype != LINR_BITS) return LINR_E_DTYPE;
     if (d == 0) return LINR_E_SHAPE;
     uint64_t rb = (uint64_t)d * elt_bytes(dtype);
-    if (rb % 16 != 0 || rb > 512) return LINR_E_SHAPE;
+    if (dtype == LINR_BITS) {                           // d = bits per code; a code is ceil(d / 64) words
+        if (d > 256) return LINR_E_SHAPE;
+        rb = (uint64_t)((d + 63) / 64) * 8;
+    } else if (rb % 16 != 0 || rb > 512) return LINR_E_SHAPE;
     if (capacity == 0 || capacity > 0xFFFFFFFEull) return LINR_E_CAPACITY;
     int ndev = 0;
     HIP_TRY(hipGetDeviceCount(&ndev));
@@ -64,6 +67,7 @@ extern "C" int linr_index_create(linr_index** out, uint64_t capacity, uint32_t d
     memset(ix, 0, sizeof(*ix));
     ix->device = device; ix->dtype = dtype; ix->d = d; ix->row_bytes = (uint32_t)rb;
     ix->capacity = capacity; ix->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+    if (dtype == LINR_BITS) { ix->k_bits = d; ix->bits_words = (d + 63) / 64; }
     *out = ix;
     return LINR_OK;
 }
@@ -76,6 +80,11 @@ static void release_columns(linr_index* ix)
         if (ix->mask) (void)hipFree((void*)ix->mask);
         if (ix->ts) (void)hipFree((void*)ix->ts);
     }
+    if (ix->bits && ix->dtype != LINR_BITS) (void)hipFree(ix->bits);     // (a codes-only index keeps its codes in `emb`)
+    if (ix->perm) (void)hipFree(ix->perm);
+    if (ix->signs) (void)hipFree(ix->signs);
+    ix->bits = nullptr; ix->perm = nullptr; ix->signs = nullptr;
+    if (ix->dtype != LINR_BITS) { ix->k_bits = 0; ix->bits_words = 0; }
     if (ix->scale_stats) (void)hipFree(ix->scale_stats);
     if (ix->scale_code) (void)hipFree(ix->scale_code);
     ix->scale_stats = nullptr; ix->scale_code = nullptr;
@@ -185,6 +194,12 @@ static int cached_blocks_per_cu(const linr_index* ix, const linr_plan& p, uint32
     (void)cache_dyn;
     const int ts = ix->ts != nullptr;
     if (p.generic) return linr_scan_blocks_per_cu(p, ix->dtype, Bp, m, ts);
+    if (p.bits) {
+        static int bits_cache[5][2];
+        int& bslot = bits_cache[p.ks <= 4 ? p.ks : 0][ts];
+        if (bslot == 0) { int v = linr_scan_blocks_per_cu(p, ix->dtype, Bp, m, ts); bslot = v > 0 ? v : -1; }
+        return bslot > 0 ? bslot : 0;
+    }
     int& slot = cache[ix->dtype][p.vk][0][p.wide ? 2 : p.coop ? 1 : 0][p.ks][p.qg][m][ts];
     if (slot == 0) {
         int v = linr_scan_blocks_per_cu(p, ix->dtype, Bp, m, ts);
@@ -199,7 +214,8 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
 {
     memset(p, 0, sizeof(*p));
     if (m == 0 || m > LINR_MAX_M) return LINR_E_SHAPE;
-    p->vk = ix->dtype == LINR_I8 ? (ix->row_scale ? LINR_VK_I8_SCALED : LINR_VK_I8_RAW) : LINR_VK_FLOAT;
+    const bool bits_mode = ix->dtype == LINR_BITS;
+    p->vk = (ix->dtype == LINR_I8 || bits_mode) ? (ix->row_scale ? LINR_VK_I8_SCALED : LINR_VK_I8_RAW) : LINR_VK_FLOAT;
     uint32_t ks = (ix->row_bytes + 63) / 64;
     p->ks = ks <= 1 ? 1 : ks <= 2 ? 2 : ks <= 4 ? 4 : 8;
     p->tpc = 8 / p->ks;
@@ -234,7 +250,17 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
             if (c * LINR_WAVES_PER_BLOCK * 32 >= B) break;
         }
     uint32_t Bp;
-    if (qw) {
+    if (bits_mode) {                                    // bit-matching kernel: every wave a chunk-slot, 64 queries per pass
+        if (m != 1) return LINR_E_SHAPE;
+        p->bits = 1;
+        p->ks = ix->bits_words;
+        p->qg = 4;
+        p->generic = 0;
+        p->chunk_items = 256;
+        p->max_batch = 64;
+        Bp = B < p->max_batch ? B : p->max_batch;
+        p->nsplit = 1;
+    } else if (qw) {
         p->qg = qw;
         p->coop = 1;
         p->wide = 1;
@@ -275,6 +301,7 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
         int occ = cached_blocks_per_cu(ix, *p, Bp, m);
         bpc = occ > 0 ? (uint32_t)occ : 2u;
         if (bpc > 8) bpc = 8;
+        if (p->bits && bpc > 4) bpc = 4;                // every wave is a chunk-slot: 256 CUs x 4 x 4 waves = LINR_MAX_SLOTS
     }
     p->n_chunks = (ix->n + p->chunk_items - 1) / p->chunk_items;
     uint64_t waves_wanted = p->n_chunks * p->nsplit;
@@ -421,7 +448,7 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
 
         linr_scan_args sa;
         memset(&sa, 0, sizeof(sa));
-        sa.emb = ix->emb; sa.row_scale = ix->row_scale; sa.mask = ix->mask; sa.ts = ix->ts; sa.scale_stats = ix->scale_stats; sa.scale_code = ix->scale_code;
+        sa.emb = ix->emb; sa.row_scale = ix->row_scale; sa.mask = ix->mask; sa.ts = ix->ts; sa.scale_stats = ix->scale_stats; sa.scale_code = ix->scale_code; sa.k_bits = ix->k_bits;
         sa.n = ix->n; sa.row_bytes = ix->row_bytes;
         sa.Q = (const char*)Q + (uint64_t)b0 * m * ix->row_bytes; sa.B = Bp; sa.m = m;
         sa.filters = use_filt; sa.tau = tau; sa.cnt = cnt; sa.seg = seg;
@@ -502,5 +529,154 @@ extern "C" int linr_events_elapsed_ms(void** events, uint32_t n_pairs, float* ms
     if (!events || !ms) return LINR_E_NULL;
     for (uint32_t i = 0; i < n_pairs; ++i)
         HIP_TRY(hipEventElapsedTime(&ms[i], (hipEvent_t)events[2 * i], (hipEvent_t)events[2 * i + 1]));
+    return LINR_OK;
+}
+
+// ---------------------------------------------------------------------------
+// quantised search (Sec. 3.2)
+// ---------------------------------------------------------------------------
+static int copy_small(void** dst, const void* src, uint64_t bytes, int from_host)
+{
+    void* p = nullptr;
+    HIP_TRY(hipMalloc(&p, bytes ? bytes : 16));
+    hipError_t e = hipMemcpy(p, src, bytes, from_host ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice);
+    if (e != hipSuccess) { (void)hipFree(p); g_last_hip = (int)e; return LINR_E_HIP; }
+    *dst = p;
+    return LINR_OK;
+}
+
+extern "C" int linr_index_build_bits(linr_index* ix, const uint32_t* perm, const int8_t* signs, uint32_t k_bits, int src)
+{
+    if (!ix || !perm || !signs) return LINR_E_NULL;
+    if (ix->dtype != LINR_F32 && ix->dtype != LINR_BF16) return LINR_E_DTYPE;
+    if (ix->n == 0 || !ix->emb) return LINR_E_NOT_LOADED;
+    if (k_bits == 0 || k_bits > 256 || ix->d % k_bits != 0) return LINR_E_SHAPE;
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipSetDevice(ix->device));
+    if (ix->bits) (void)hipFree(ix->bits);
+    if (ix->perm) (void)hipFree(ix->perm);
+    if (ix->signs) (void)hipFree(ix->signs);
+    ix->bits = nullptr; ix->perm = nullptr; ix->signs = nullptr;
+    ix->k_bits = k_bits; ix->bits_words = (k_bits + 63) / 64;
+    const int fh = src == LINR_SRC_HOST;
+    int rc = copy_small((void**)&ix->perm, perm, (uint64_t)ix->d * 4, fh);
+    if (rc == LINR_OK) rc = copy_small((void**)&ix->signs, signs, ix->d, fh);
+    if (rc == LINR_OK) {
+        hipError_t e = hipMalloc((void**)&ix->bits, ix->n * ix->bits_words * 8);
+        if (e == hipSuccess) e = linr_launch_sign_oporp(ix->dtype, ix->emb, ix->n, ix->d, ix->perm, ix->signs, k_bits, ix->bits, nullptr);
+        if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+        if (e != hipSuccess) { g_last_hip = (int)e; rc = LINR_E_HIP; }
+    }
+    (void)hipSetDevice(dev);
+    return rc;
+}
+
+extern "C" int linr_index_load_bits(linr_index* ix, const uint64_t* bits, const uint32_t* mask, const uint32_t* ts, uint64_t n,
+                                    int src)
+{
+    if (!ix) return LINR_E_NULL;
+    if (ix->dtype != LINR_BITS) return LINR_E_DTYPE;
+    int rc = load_common(ix, LINR_BITS, bits, nullptr, mask, ts, n, src);       // `emb` holds the codes
+    if (rc == LINR_OK) ix->bits = (uint64_t*)ix->emb;
+    return rc;
+}
+
+extern "C" int linr_quantize_queries(const linr_index* ix, const void* Q, uint32_t B, uint64_t* qbits, void* hip_stream)
+{
+    if (!ix || !Q || !qbits) return LINR_E_NULL;
+    if (ix->dtype != LINR_F32 && ix->dtype != LINR_BF16) return LINR_E_DTYPE;
+    if (!ix->bits || !ix->perm) return LINR_E_NOT_LOADED;
+    HIP_TRY(linr_launch_sign_oporp(ix->dtype, Q, B, ix->d, ix->perm, ix->signs, ix->k_bits, qbits, (hipStream_t)hip_stream));
+    return LINR_OK;
+}
+
+// a view of the index whose "embeddings" are the codes: the search machinery then ranks by matching bits
+static int bits_view(const linr_index* ix, linr_index* v)
+{
+    if (!ix) return LINR_E_NULL;
+    if (ix->n == 0 || !ix->bits) return LINR_E_NOT_LOADED;
+    *v = *ix;
+    v->dtype = LINR_BITS; v->emb = ix->bits; v->row_scale = nullptr; v->d = ix->k_bits; v->row_bytes = ix->bits_words * 8;
+    v->scale_stats = nullptr; v->scale_code = nullptr;
+    return LINR_OK;
+}
+
+extern "C" int linr_search_bits_workspace_bytes(const linr_index* ix, uint32_t B, uint32_t T, uint64_t* bytes)
+{
+    if (!bytes) return LINR_E_NULL;
+    linr_index v;
+    int rc = bits_view(ix, &v);
+    if (rc != LINR_OK) return rc;
+    uint64_t inner = 0;
+    rc = linr_search_workspace_bytes(&v, B, 1, T, &inner);
+    if (rc != LINR_OK) return rc;
+    *bytes = align_up(inner, 256) + align_up((uint64_t)B * T * 4, 256);       // + the float copy of the match counts
+    return LINR_OK;
+}
+
+extern "C" int linr_search_bits(const linr_index* ix, const uint64_t* qbits, uint32_t B, const linr_filter* filters, uint32_t T,
+                                uint32_t* out_ids, int32_t* out_matches, uint32_t* out_counts, void* workspace,
+                                uint64_t workspace_bytes, void* hip_stream, uint32_t flags)
+{
+    linr_index v;
+    int rc = bits_view(ix, &v);
+    if (rc != LINR_OK) return rc;
+    if (B == 0) return LINR_OK;
+    if (!out_matches) return LINR_E_NULL;
+    uint64_t inner = 0, total = 0;
+    rc = linr_search_workspace_bytes(&v, B, 1, T, &inner);
+    if (rc != LINR_OK) return rc;
+    rc = linr_search_bits_workspace_bytes(ix, B, T, &total);
+    if (rc != LINR_OK) return rc;
+    if (!workspace || (((uintptr_t)workspace) & 255u) || workspace_bytes < total) return LINR_E_WORKSPACE;
+    float* fscores = (float*)((char*)workspace + align_up(inner, 256));
+    return search_impl(&v, qbits, nullptr, B, 1, filters, T, out_ids, fscores, out_matches, out_counts, workspace, inner,
+                       hip_stream, flags, nullptr, nullptr, nullptr, nullptr);
+}
+
+extern "C" int linr_search_two_stage_workspace_bytes(const linr_index* ix, uint32_t B, uint32_t T, uint32_t k, uint64_t* bytes)
+{
+    if (!ix || !bytes) return LINR_E_NULL;
+    if (ix->dtype != LINR_F32 && ix->dtype != LINR_BF16) return LINR_E_DTYPE;
+    if (k == 0 || k > T) return LINR_E_K;
+    uint64_t s1 = 0;
+    int rc = linr_search_bits_workspace_bytes(ix, B, T, &s1);
+    if (rc != LINR_OK) return rc;
+    *bytes = align_up(s1, 256) + align_up((uint64_t)B * ix->bits_words * 8, 256) + 2 * align_up((uint64_t)B * T * 4, 256) +
+             align_up((uint64_t)B * 4, 256);
+    return LINR_OK;
+}
+
+extern "C" int linr_search_two_stage(const linr_index* ix, const void* Q, uint32_t B, const linr_filter* filters, uint32_t T,
+                                     uint32_t k, uint32_t* out_ids, float* out_scores, uint32_t* out_counts, void* workspace,
+                                     uint64_t workspace_bytes, void* hip_stream, uint32_t flags)
+{
+    if (!ix) return LINR_E_NULL;
+    if (ix->dtype != LINR_F32 && ix->dtype != LINR_BF16) return LINR_E_DTYPE;
+    if (k == 0 || k > T || T > LINR_MAX_K) return LINR_E_K;
+    if (ix->n == 0 || !ix->emb || !ix->bits) return LINR_E_NOT_LOADED;
+    if (B == 0) return LINR_OK;
+    if (!Q || !filters || !out_ids || !out_scores || !out_counts) return LINR_E_NULL;
+    uint64_t s1 = 0, total = 0;
+    int rc = linr_search_bits_workspace_bytes(ix, B, T, &s1);
+    if (rc != LINR_OK) return rc;
+    rc = linr_search_two_stage_workspace_bytes(ix, B, T, k, &total);
+    if (rc != LINR_OK) return rc;
+    if (!workspace || (((uintptr_t)workspace) & 255u) || workspace_bytes < total) return LINR_E_WORKSPACE;
+    char* w = (char*)workspace + align_up(s1, 256);
+    uint64_t* qbits = (uint64_t*)w;              w += align_up((uint64_t)B * ix->bits_words * 8, 256);
+    uint32_t* ids1 = (uint32_t*)w;               w += align_up((uint64_t)B * T * 4, 256);
+    int32_t* m1 = (int32_t*)w;                   w += align_up((uint64_t)B * T * 4, 256);
+    uint32_t* cnt1 = (uint32_t*)w;
+    rc = linr_quantize_queries(ix, Q, B, qbits, hip_stream);
+    if (rc != LINR_OK) return rc;
+    rc = linr_search_bits(ix, qbits, B, filters, T, ids1, m1, cnt1, workspace, s1, hip_stream, flags);
+    if (rc != LINR_OK) return rc;
+    linr_rescore_args ra;
+    memset(&ra, 0, sizeof(ra));
+    ra.dtype = ix->dtype; ra.emb = ix->emb; ra.d = ix->d; ra.row_bytes = ix->row_bytes; ra.Q = Q; ra.B = B; ra.T = T; ra.k = k;
+    ra.cand_ids = ids1; ra.cand_counts = cnt1; ra.out_ids = out_ids; ra.out_scores = out_scores; ra.out_counts = out_counts;
+    HIP_TRY(linr_launch_rescore(ra, (hipStream_t)hip_stream));
     return LINR_OK;
 }

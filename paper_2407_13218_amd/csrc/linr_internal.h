@@ -32,6 +32,11 @@ struct linr_index {
     int owned;                  // library allocated the four columns
     float* scale_stats;         // scaled int8: min of 1/scale, 127/span, span/127 (+ reduction scratch); always owned
     uint8_t* scale_code;        // scaled int8: E_i of every item, padded to a multiple of 256 items; always owned
+    // quantised search: Sign-OPORP codes [n][bits_words] (owned), k_bits, and the device copies of perm / signs
+    uint64_t* bits;
+    uint32_t k_bits, bits_words;
+    uint32_t* perm;
+    int8_t* signs;
     int num_cu;
 };
 
@@ -46,6 +51,7 @@ struct linr_plan {
     uint32_t generic;           // 1 = queries streamed from LDS
     uint32_t coop;              // 1 = the four waves of a workgroup share each chunk and split the query groups
     uint32_t wide;              // 1 = coop with 32x32 tiles; qg then counts 32-query groups per wave
+    uint32_t bits;              // 1 = bit-matching kernel over 1-bit codes (ks = 64-bit words per code)
     uint32_t grid;              // workgroups of LINR_WAVES_PER_BLOCK waves
     uint32_t nslots;            // chunk-slots = waves / nsplit
     uint32_t cap;               // entries per (slot, query) candidate segment
@@ -77,6 +83,7 @@ struct linr_scan_args {
     uint64_t n_dense;           // chunks this sweep visits
     uint32_t stride;            // chunk stride of this sweep
     uint32_t skip_mod;          // level indices that are multiples of this were visited by earlier sweeps (0: none)
+    uint32_t k_bits;            // bit-matching kernel: bits per code
 };
 
 struct linr_merge_args {
@@ -98,6 +105,15 @@ hipError_t linr_launch_init(unsigned long long* tau, uint32_t* ccnt, uint32_t* g
                             uint64_t n_cnt, uint32_t B, hipStream_t s);
 hipError_t linr_launch_scan(const linr_plan& p, int dtype, const linr_scan_args& a, hipStream_t s);
 hipError_t linr_launch_merge(const linr_merge_args& a, hipStream_t s);
+// quantised search helpers: codes of `n` rows (fp32 / bf16, row-major [n][d]); rescoring of T candidates per query
+hipError_t linr_launch_sign_oporp(int dtype, const void* x, uint64_t n, uint32_t d, const uint32_t* perm, const int8_t* signs,
+                                  uint32_t k_bits, uint64_t* out, hipStream_t s);
+struct linr_rescore_args {
+    int dtype; const void* emb; uint32_t d; uint32_t row_bytes; const void* Q; uint32_t B, T, k;
+    const uint32_t* cand_ids; const uint32_t* cand_counts;
+    uint32_t* out_ids; float* out_scores; uint32_t* out_counts;
+};
+hipError_t linr_launch_rescore(const linr_rescore_args& a, hipStream_t s);
 // 1 if a register-resident-query scan kernel exists for this shape
 int linr_fast_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg);
 int linr_coop_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg);

@@ -1522,6 +1522,222 @@ __global__ void __launch_bounds__(256) scale_code_kernel(const float* row_scale,
 }
 
 // ---------------------------------------------------------------------------
+// quantised search (LiNR Sec. 3.2): scan over 1-bit Sign-OPORP codes
+//   similarity = number of equal bits = k_bits - popcount(code ^ query code).
+// A wave is a chunk-slot of its own (no barrier); a lane holds 4 items of the 256-item
+// chunk (their W code words, mask, timestamp) in registers and walks over the batch's
+// queries, whose codes and bounds sit in LDS (uniform reads).  Per (item, query): W xor,
+// 2 W bit counts, one compare; the predicate and the key append run only for the lanes
+// that beat the query's bound.  The same candidate segments, bounds, sweeps and merges
+// as the exact scan are used, with the match count as an integer ranking value.
+// HBM-bound for a few queries (8 W + 4 bytes per item), vector-ALU-bound for many.
+// ---------------------------------------------------------------------------
+#define LINR_BITS_NQ 64            // queries per pass
+#define LINR_BITS_CH 256           // items per chunk
+
+template <int W>
+struct BitsRegs {
+    u64 x[4][W];
+    uint32_t mk[4], ts[4];
+};
+
+template <int W>
+__device__ __forceinline__ void issue_bits(BitsRegs<W>& R, const linr_scan_args& A, u64 lc, int lane, bool has_ts)
+{
+    const u64 item0 = lc * A.stride * LINR_BITS_CH;
+    const u64 last = A.n - 1;
+    const u64* bits = (const u64*)A.emb;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        u64 it = item0 + u * 64 + lane;
+        it = it < last ? it : last;
+#pragma unroll
+        for (int w = 0; w < W; ++w) R.x[u][w] = __builtin_nontemporal_load(bits + it * W + w);
+        R.mk[u] = __builtin_nontemporal_load(A.mask + it);
+        R.ts[u] = has_ts ? __builtin_nontemporal_load(A.ts + it) : 0u;
+    }
+}
+
+template <int W>
+__global__ void __launch_bounds__(64 * WPB, 4) scan_kernel_bits(linr_scan_args A)
+{
+    constexpr int NQ = LINR_BITS_NQ;
+    __shared__ WaveQ<NQ / 16> wq_all[WPB];
+    __shared__ uint32_t hist_all[WPB][256];
+    __shared__ u64 qcode[NQ][W];                         // the batch's codes (whole workgroup)
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    WaveQ<NQ / 16>& Wq = wq_all[wib];
+    const QSide qs = {Wq.cnt, Wq.thr_f, Wq.thr_i, Wq.fall, Wq.fnone, Wq.tsmin, Wq.tsmax, Wq.fflag};
+    const uint32_t slot = blockIdx.x * WPB + wib;
+    const bool has_ts = A.ts != nullptr;
+    const int kb = (int)A.k_bits;                        // bits per code
+    for (uint32_t t = threadIdx.x; t < (uint32_t)NQ * W; t += 64 * WPB) {
+        const uint32_t b = t / W;
+        qcode[b][t % W] = b < A.B ? ((const u64*)A.Q)[t] : 0ull;
+    }
+    for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) {
+        Wq.cnt[ql] = 0;
+        load_query_side(qs, ql, ql, A, true);
+    }
+    __syncthreads();
+    if (slot >= A.nslots) return;
+
+    BitsRegs<W> R, N;
+    uint32_t need_compact = 0u, since_refresh = 0u;
+    SweepWalk walk;
+    walk.init(slot, A);
+    u64 lc = walk.lc();
+    if (walk.valid()) issue_bits<W>(N, A, lc, lane, has_ts);
+    while (walk.valid()) {
+        const u64 item0 = lc * A.stride * LINR_BITS_CH;
+        R = N;
+        walk.advance();
+        const u64 nlc = walk.lc();
+        if (walk.valid()) issue_bits<W>(N, A, nlc, lane, has_ts);
+
+        bool live[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) live[u] = item0 + u * 64 + lane < A.n;
+#pragma unroll 1
+        for (uint32_t b = 0; b < A.B; ++b) {
+            // matches >= bound  <=>  differing bits <= k_bits - bound (no bound yet: everything qualifies)
+            const int thr = Wq.thr_i[b];
+            const int dmax = thr == INT_MIN ? INT_MAX : kb - thr;
+            u64 qw[W];
+#pragma unroll
+            for (int w = 0; w < W; ++w) qw[w] = qcode[b][w];
+            int diff[4];
+            bool hot = false;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                int dsum = 0;
+#pragma unroll
+                for (int w = 0; w < W; ++w) dsum += __popcll(R.x[u][w] ^ qw[w]);
+                diff[u] = dsum;
+                hot = hot | (dsum <= dmax);
+            }
+            if (!wave_any(hot)) continue;
+            // survivors: predicate, key, append (rare)
+            const linr_filter* F = A.filters + b;
+            const uint32_t fa = Wq.fall[b], fn = Wq.fnone[b];
+            const bool complex = (Wq.fflag[b] & 1u) != 0u;
+            u64* seg_p = A.seg + ((u64)slot * A.B + b) * A.cap;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int matches = kb - diff[u];
+                bool ok = live[u] & (diff[u] <= dmax) & ((R.mk[u] & fn) == fa);
+                if (has_ts) ok = ok & (R.ts[u] >= Wq.tsmin[b]) & (R.ts[u] <= Wq.tsmax[b]);
+                if (ok && complex) ok = filter_pass(*F, R.mk[u], has_ts, R.ts[u]);
+                if (ok) {
+                    const u64 item = item0 + u * 64 + lane;
+                    const u64 key = ((u64)ord_i32(matches) << 32) | (u64)(uint32_t)~(uint32_t)item;
+                    const uint32_t pos = atomicAdd(&Wq.cnt[b], 1u);
+                    if (pos < A.cap) seg_p[pos] = key;
+                    if (pos + 1 + LINR_BITS_CH > A.cap) need_compact = 1u;
+                }
+            }
+        }
+        bool refresh = ++since_refresh >= 16;
+        if (wave_any(need_compact != 0u)) {
+            compact_full_segments<LINR_BITS_CH>(A, qs, slot, 0, NQ, hist_all[wib], lane);
+            need_compact = 0u;
+            refresh = true;
+        }
+        if (refresh) {
+            for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) load_query_side(qs, ql, ql, A, false);
+            wave_sync();
+            since_refresh = 0;
+        }
+        lc = nlc;
+    }
+    own_stores_done();
+    flush_segments(A, qs, slot, 0, NQ, lane, hist_all[wib]);
+}
+
+// Sign-OPORP codes of n rows: thread (row, word) sums its 64 bins in double precision, t ascending, and
+// sets bit j%64 of word j/64 for a strictly positive bin sum (Sec. 3.2; construction in the header).
+__global__ void __launch_bounds__(256) sign_oporp_kernel(int dtype, const void* x, u64 n, uint32_t d, const uint32_t* perm,
+                                                         const int8_t* signs, uint32_t k_bits, u64* out)
+{
+    const uint32_t Wn = (k_bits + 63) / 64, L = d / k_bits;
+    const u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n * Wn) return;
+    const u64 row = t / Wn;
+    const uint32_t w = (uint32_t)(t % Wn);
+    u64 word = 0;
+    for (uint32_t jj = 0; jj < 64; ++jj) {
+        const uint32_t j = w * 64 + jj;
+        if (j >= k_bits) break;
+        double sum = 0.0;
+        for (uint32_t q = 0; q < L; ++q) {
+            const uint32_t col = perm[j * L + q];
+            double v;
+            if (dtype == LINR_F32) v = (double)((const float*)x)[row * d + col];
+            else v = (double)__uint_as_float((uint32_t)((const uint16_t*)x)[row * d + col] << 16);
+            sum = sum + (signs[j * L + q] > 0 ? v : -v);
+        }
+        if (sum > 0.0) word |= 1ull << jj;
+    }
+    out[t] = word;
+}
+
+// Second stage of the two-stage search: one workgroup per query scores its T candidates with the
+// full-precision embeddings (fp32 accumulation), sorts them by (score desc, id asc) and writes the first k.
+__global__ void __launch_bounds__(256) rescore_kernel(linr_rescore_args A)
+{
+    __shared__ u64 keys[LINR_MAX_K];
+    const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    uint32_t c = A.cand_counts[b];
+    if (c > A.T) c = A.T;
+    uint32_t P = 1;
+    while (P < c) P <<= 1;
+    for (uint32_t j = tid; j < P; j += 256) {
+        u64 key = 0ull;
+        if (j < c) {
+            const uint32_t id = A.cand_ids[(u64)b * A.T + j];
+            float s = 0.0f;
+            if (A.dtype == LINR_F32) {
+                const float* q = (const float*)A.Q + (u64)b * A.d;
+                const float* x = (const float*)A.emb + (u64)id * A.d;
+                for (uint32_t e = 0; e < A.d; ++e) s += q[e] * x[e];
+            } else {
+                const uint16_t* q = (const uint16_t*)A.Q + (u64)b * A.d;
+                const uint16_t* x = (const uint16_t*)A.emb + (u64)id * A.d;
+                for (uint32_t e = 0; e < A.d; ++e)
+                    s += __uint_as_float((uint32_t)q[e] << 16) * __uint_as_float((uint32_t)x[e] << 16);
+            }
+            key = ((u64)ord_f32(s) << 32) | (u64)(uint32_t)~id;
+        }
+        keys[j] = key;
+    }
+    __syncthreads();
+    for (uint32_t size = 2; size <= P; size <<= 1)
+        for (uint32_t str = size >> 1; str > 0; str >>= 1) {
+            for (uint32_t j = tid; j < P; j += 256) {
+                const uint32_t o = j ^ str;
+                if (o > j) {
+                    const u64 xk = keys[j], yk = keys[o];
+                    const bool desc = (j & size) == 0;
+                    if (desc ? (xk < yk) : (xk > yk)) { keys[j] = yk; keys[o] = xk; }
+                }
+            }
+            __syncthreads();
+        }
+    const uint32_t nout = c < A.k ? c : A.k;
+    for (uint32_t j = tid; j < A.k; j += 256) {
+        const u64 o = (u64)b * A.k + j;
+        if (j < nout) {
+            A.out_ids[o] = ~(uint32_t)keys[j];
+            A.out_scores[o] = unord_f32((uint32_t)(keys[j] >> 32));
+        } else {
+            A.out_ids[o] = LINR_NO_ID;
+            A.out_scores[o] = -INFINITY;
+        }
+    }
+    if (tid == 0) A.out_counts[b] = nout;
+}
+
+// ---------------------------------------------------------------------------
 // scan kernel, query fragments and query-side state streamed from LDS: any m, any
 // number of query groups (up to the LDS budget the host plans for); one chunk-slot per
 // wave.  Dynamic LDS: [n_frag][64] v4i fragments, 7 workgroup-shared arrays of nq16
@@ -1888,13 +2104,17 @@ __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
                     float rank = (A.vk == LINR_VK_I8_SCALED) ? (float)best * A.row_scale[id] : (float)best;
                     A.out_scores[o] = rank * qs;
                     if (A.out_raw) A.out_raw[o] = best;
+                } else if (A.dtype == LINR_BITS) {
+                    const int matches = unord_i32(hi);
+                    A.out_scores[o] = (float)matches;
+                    if (A.out_raw) A.out_raw[o] = matches;
                 } else {
                     A.out_scores[o] = unord_f32(hi);
                 }
             } else {
                 A.out_ids[o] = LINR_NO_ID;
                 A.out_scores[o] = -INFINITY;
-                if (A.out_raw && A.dtype == LINR_I8) A.out_raw[o] = INT_MIN;
+                if (A.out_raw && (A.dtype == LINR_I8 || A.dtype == LINR_BITS)) A.out_raw[o] = INT_MIN;
             }
         }
         if (tid == 0) A.out_counts[b] = nwin;
@@ -2073,8 +2293,35 @@ uint32_t linr_lds_scan_dynamic_bytes(uint32_t B, uint32_t m, uint32_t ks)
     return nsg * m * ks * 1024u + nsg * 16u * 4u * (7u + WPB);
 }
 
+static hipError_t bits_dispatch(uint32_t words, ScanAct& act)
+{
+    if (words == 1) return scan_act(scan_kernel_bits<1>, act);
+    if (words == 2) return scan_act(scan_kernel_bits<2>, act);
+    if (words == 3) return scan_act(scan_kernel_bits<3>, act);
+    if (words == 4) return scan_act(scan_kernel_bits<4>, act);
+    return hipErrorInvalidDeviceFunction;
+}
+
+hipError_t linr_launch_sign_oporp(int dtype, const void* x, uint64_t n, uint32_t d, const uint32_t* perm, const int8_t* signs,
+                                  uint32_t k_bits, uint64_t* out, hipStream_t s)
+{
+    const uint64_t threads = n * ((k_bits + 63) / 64);
+    if (threads == 0) return hipSuccess;
+    hipLaunchKernelGGL(sign_oporp_kernel, dim3((uint32_t)((threads + 255) / 256)), dim3(256), 0, s, dtype, x, (u64)n, d, perm, signs,
+                       k_bits, (u64*)out);
+    return hipGetLastError();
+}
+
+hipError_t linr_launch_rescore(const linr_rescore_args& a, hipStream_t s)
+{
+    if (a.T > LINR_MAX_K || a.k > a.T) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(rescore_kernel, dim3(a.B), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
 static hipError_t plan_dispatch(const linr_plan& p, int dtype, uint32_t B, uint32_t m, bool ts, ScanAct& act)
 {
+    if (p.bits) { act.dyn = 0; return bits_dispatch(p.ks, act); }
     if (p.generic) {
         act.dyn = linr_lds_scan_dynamic_bytes(B, m, p.ks);
         return lds_dispatch(dtype, p.vk, p.ks, act);

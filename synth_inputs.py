@@ -31,7 +31,7 @@ SEED0 = 20240713
 NOW = 1_720_000_000
 DAY = 86_400
 
-F32, BF16, I8 = 0, 1, 2
+F32, BF16, I8, BITS = 0, 1, 2, 3
 NO_ID = 0xFFFFFFFF
 MAX_ANY = 4
 
@@ -244,3 +244,22 @@ def to_numpy(w: dict) -> dict:
     out["scale"] = None if w["scale"] is None else w["scale"].cpu().numpy()
     out["q_scale"] = None if w["q_scale"] is None else w["q_scale"].cpu().numpy()
     return out
+
+
+def oporp_draw(d: int, seed: int = 0):
+    """The random inputs of Sign-OPORP (one permutation of the d coordinates, one +-1 vector), numpy, seeded.
+    They are inputs of the method on both sides; no part of the method is computed here."""
+    rng = np.random.default_rng(_seed(9, seed))
+    return rng.permutation(d).astype(np.uint32), rng.choice(np.array([-1, 1], np.int8), d)
+
+
+def random_codes(n: int, k_bits: int, seed: int = 0):
+    """n uniformly random codes of k_bits bits as [n, ceil(k_bits/64)] uint64 (unused high bits zero)."""
+    rng = np.random.default_rng(_seed(9, 100 + seed))
+    W = (k_bits + 63) // 64
+    hi = rng.integers(0, 2 ** 63, (n, W), dtype=np.uint64)
+    codes = hi * np.uint64(2) + rng.integers(0, 2, (n, W), dtype=np.uint64)
+    rem = k_bits - 64 * (W - 1)
+    if rem < 64:
+        codes[:, W - 1] &= np.uint64((1 << rem) - 1)
+    return codes

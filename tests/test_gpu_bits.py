@@ -1,0 +1,193 @@
+"""GPU parity of the quantised search (Sign-OPORP codes, bit matching, two-stage search) against the oracle.
+Codes, match counts, ids and counts are integers: bit-exact.  The second stage's fp32 scores follow the 1e-3 rule."""
+import time
+
+import numpy as np
+import pytest
+
+import synth_inputs as S
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(f"[{time.strftime('%H:%M:%S')}] {msg}", flush=True)
+
+
+def mixed_filters(B, rng, with_ts):
+    f = S.make_filters(B)
+    for b in range(B):
+        kind = b % 6
+        if kind == 1:
+            f["all_bits"][b] = 1 << rng.integers(0, 32)
+        elif kind == 2:
+            f["all_bits"][b] = (1 << rng.integers(0, 16)) | (1 << rng.integers(16, 32)); f["none_bits"][b] = 1 << rng.integers(0, 32)
+        elif kind == 3:
+            f["any_bits"][b][0] = 0x0000F00F; f["any_bits"][b][1] = 1 << rng.integers(0, 32); f["n_any"][b] = 2
+        elif kind == 4:
+            f["all_bits"][b] = 0xFFFFFFFF
+        elif kind == 5:
+            f["all_bits"][b] = sum(1 << int(x) for x in rng.choice(32, 6, replace=False))
+        if with_ts and b % 2 == 1:
+            f["ts_min"][b] = 200; f["ts_max"][b] = 800
+    return f
+
+
+def float_items(dtype, n, d, seed):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    x /= np.linalg.norm(x, axis=1, keepdims=True)
+    if dtype == S.BF16:
+        return S.to_bf16_bits_np(x) if hasattr(S, "to_bf16_bits_np") else (x.view(np.uint32) >> 16).astype(np.uint16)
+    return x
+
+
+@pytest.mark.parametrize("dtype,d,k_bits", [(S.F32, 64, 64), (S.F32, 128, 64), (S.BF16, 256, 128), (S.BF16, 64, 16),
+                                            (S.F32, 512 // 4, 128), (S.BF16, 192, 192)])
+def test_codes_match_the_oracle(oracle_mod, dtype, d, k_bits):
+    import torch
+    import paper_2407_13218_amd as L
+    say(f"codes dtype={dtype} d={d} k_bits={k_bits}")
+    n = 3001
+    x = float_items(dtype, n, d, d + k_bits)
+    x[7] = 0                                                                   # a zero row: all bin sums zero
+    perm, signs = S.oporp_draw(d, k_bits)
+    xt = torch.from_numpy(x.view(np.int16) if dtype == S.BF16 else x).cuda()
+    mask = torch.zeros(n, dtype=torch.int32, device="cuda")
+    ix = L.Index(n, d, dtype, 0)
+    ix.load(xt, mask)
+    ix.build_bits(perm, signs, k_bits)
+    got = ix.quantize(xt).cpu().numpy().view(np.uint64)
+    want = oracle_mod.sign_oporp(dtype, x, perm, signs, k_bits)
+    assert np.array_equal(got, want)
+    ix.close()
+
+
+def run_bits_case(oracle_mod, codes, k_bits, mask, ts, qbits, filt, T, label, host_filters=True):
+    import torch
+    import paper_2407_13218_amd as L
+    n = codes.shape[0]
+    ix = L.Index(n, k_bits, S.BITS, 0)
+    ix.load(torch.from_numpy(codes.view(np.int64)).cuda(), torch.from_numpy(mask.view(np.int32)).cuda(),
+            ts=None if ts is None else torch.from_numpy(ts.view(np.int32)).cuda())
+    f = filt if host_filters else torch.from_numpy(np.ascontiguousarray(filt).view(np.uint8).copy()).cuda()
+    ids, mt, cnt = ix.search_bits(torch.from_numpy(qbits.view(np.int64)).cuda(), f, T)
+    torch.cuda.synchronize()
+    ids = ids.cpu().numpy().view(np.uint32); mt = mt.cpu().numpy(); cnt = cnt.cpu().numpy().view(np.uint32)
+    oi, om, oc = oracle_mod.bits_search(codes, k_bits, mask, qbits, filt, T, ts=ts)
+    assert np.array_equal(cnt, oc), f"{label}: counts {cnt} vs {oc}"
+    assert np.array_equal(ids, oi), f"{label}: ids differ"
+    assert np.array_equal(mt, om), f"{label}: match counts differ"
+    ix.close()
+
+
+@pytest.mark.parametrize("n,k_bits,B,T,with_ts", [(1, 64, 1, 1, False), (255, 64, 3, 10, False), (100_003, 64, 17, 1000, True),
+                                                  (60_000, 128, 70, 500, False), (30_000, 256, 5, 2048, True),
+                                                  (50_000, 32, 9, 100, False), (20_000, 192, 130, 64, False)])
+def test_bits_search_exact(oracle_mod, n, k_bits, B, T, with_ts):
+    say(f"bits search n={n} k_bits={k_bits} B={B} T={T} ts={with_ts}")
+    rng = np.random.default_rng(n + B)
+    codes = S.random_codes(n, k_bits, seed=n)
+    qbits = S.random_codes(B, k_bits, seed=n + 1)
+    if n > 100:
+        codes[11] = qbits[0]; codes[3] = qbits[0]; codes[n - 1] = qbits[0]     # ties at the very top of query 0
+    mask = rng.integers(0, 2 ** 32, n, dtype=np.uint64).astype(np.uint32)
+    ts = rng.integers(0, 1000, n).astype(np.uint32) if with_ts else None
+    run_bits_case(oracle_mod, codes, k_bits, mask, ts, qbits, mixed_filters(B, rng, with_ts), T, f"n={n} k_bits={k_bits} B={B}")
+
+
+def test_bits_search_few_levels_many_ties(oracle_mod):
+    """16-bit codes: only 17 distinct match counts, so the T-th place is decided by ids among thousands of ties"""
+    say("bits search with 16-bit codes (massive ties), device filters, plan variants")
+    import paper_2407_13218_amd as L
+    rng = np.random.default_rng(3)
+    n, B, T = 80_000, 6, 300
+    codes = S.random_codes(n, 16, seed=5); qbits = S.random_codes(B, 16, seed=6)
+    mask = rng.integers(0, 2 ** 32, n, dtype=np.uint64).astype(np.uint32)
+    f = mixed_filters(B, rng, False)
+    run_bits_case(oracle_mod, codes, 16, mask, None, qbits, f, T, "16-bit codes", host_filters=False)
+    for tuning in (dict(max_levels=1, blocks_per_cu=1), dict(sample_ratio=2, min_sample=64)):
+        L.set_tuning(**tuning)
+        try:
+            run_bits_case(oracle_mod, codes, 16, mask, None, qbits, f, T, f"16-bit codes {tuning}")
+        finally:
+            L.set_tuning()
+
+
+@pytest.mark.parametrize("dtype,d,k_bits,T,k", [(S.F32, 64, 64, 400, 50), (S.BF16, 128, 64, 1000, 100), (S.F32, 64, 64, 2048, 2048)])
+def test_two_stage_against_the_oracle(oracle_mod, dtype, d, k_bits, T, k):
+    import torch
+    import paper_2407_13218_amd as L
+    say(f"two-stage dtype={dtype} d={d} k_bits={k_bits} T={T} k={k}")
+    n, B = 40_000, 9
+    rng = np.random.default_rng(T + k)
+    x = float_items(dtype, n, d, 77)
+    q = float_items(dtype, B, d, 78)
+    mask = rng.integers(0, 2 ** 32, n, dtype=np.uint64).astype(np.uint32)
+    f = mixed_filters(B, rng, False)
+    perm, signs = S.oporp_draw(d, 1)
+    as_t = (lambda a: torch.from_numpy(a.view(np.int16)).cuda()) if dtype == S.BF16 else (lambda a: torch.from_numpy(a).cuda())
+    ix = L.Index(n, d, dtype, 0)
+    ix.load(as_t(x), torch.from_numpy(mask.view(np.int32)).cuda())
+    ix.build_bits(perm, signs, k_bits)
+    ids, sc, cnt = ix.search_two_stage(as_t(q), f, T, k)
+    torch.cuda.synchronize()
+    ids = ids.cpu().numpy().view(np.uint32); sc = sc.cpu().numpy(); cnt = cnt.cpu().numpy().view(np.uint32)
+    # first stage, exactly: the candidate sets must be the oracle's
+    qb = ix.quantize(as_t(q)); i1, m1, c1 = ix.search_bits(qb, f, T)
+    torch.cuda.synchronize()
+    bits = oracle_mod.sign_oporp(dtype, x, perm, signs, k_bits); qbo = oracle_mod.sign_oporp(dtype, q, perm, signs, k_bits)
+    oi1, om1, oc1 = oracle_mod.bits_search(bits, k_bits, mask, qbo, f, T)
+    assert np.array_equal(i1.cpu().numpy().view(np.uint32), oi1) and np.array_equal(m1.cpu().numpy(), om1)
+    assert np.array_equal(c1.cpu().numpy().view(np.uint32), oc1)
+    # second stage: 1e-3 rule among the candidates
+    rtol, atol = 1e-3, 1e-6
+    for b in range(B):
+        c = int(oc1[b]); kk = min(k, c)
+        assert cnt[b] == kk, f"q{b}: count {cnt[b]} vs {kk}"
+        assert np.all(ids[b, kk:] == S.NO_ID) and np.all(np.isneginf(sc[b, kk:]))
+        if kk == 0:
+            continue
+        cand = oi1[b, :c].astype(np.uint64)
+        rank, _, feas = oracle_mod.pairs(dtype, x, mask, q[:, None, :], f, np.full(c, b, np.uint32), cand)
+        assert feas.all()
+        exact = dict(zip(cand.tolist(), rank.tolist()))
+        got = ids[b, :kk].tolist()
+        assert len(set(got)) == kk and set(got) <= set(cand.tolist()), f"q{b}: ids outside the candidate set"
+        err = np.abs(sc[b, :kk].astype(np.float64) - np.array([exact[i] for i in got]))
+        assert np.all(err <= rtol * np.abs(sc[b, :kk]) + atol), f"q{b}: score error {err.max()}"
+        assert np.all(np.diff(sc[b, :kk]) <= 0)
+        same = np.diff(sc[b, :kk]) == 0
+        assert np.all(np.diff(np.array(got, np.int64))[same] > 0)
+        order = np.lexsort((cand, -rank))
+        tau = rank[order][kk - 1]; band = rtol * abs(tau) + atol
+        must = set(cand[order][rank[order] > tau + band].tolist())
+        assert must <= set(got), f"q{b}: clearly better candidates missing"
+        assert all(exact[i] >= tau - band for i in got), f"q{b}: returned a candidate below the band"
+    ix.close()
+
+
+def test_quantised_argument_errors():
+    import torch
+    import paper_2407_13218_amd as L
+    say("argument errors of the quantised calls")
+    n, d = 1000, 64
+    perm, signs = S.oporp_draw(d, 0)
+    emb8 = torch.zeros((n, d), dtype=torch.int8, device="cuda"); mask = torch.zeros(n, dtype=torch.int32, device="cuda")
+    ix8 = L.Index(n, d, S.I8, 0); ix8.load(emb8, mask)
+    with pytest.raises(L.LinrError) as e:
+        ix8.build_bits(perm, signs, 64)
+    assert e.value.code == -3                                                  # element type mismatch
+    ixf = L.Index(n, d, S.F32, 0); ixf.load(torch.zeros((n, d), device="cuda"), mask)
+    with pytest.raises(L.LinrError) as e:
+        ixf.build_bits(perm, signs, 48)                                        # 64 % 48 != 0
+    assert e.value.code == -2
+    ixf.k_bits = 64
+    with pytest.raises(L.LinrError) as e:
+        ixf.search_bits(torch.zeros((1, 1), dtype=torch.int64, device="cuda"), S.make_filters(1), 10)
+    assert e.value.code == -6                                                  # no codes built yet
+    ixf.build_bits(perm, signs, 64)
+    with pytest.raises(L.LinrError) as e:
+        ixf.search_two_stage(torch.zeros((1, d), device="cuda"), S.make_filters(1), 10, 20)   # k > T
+    assert e.value.code == -4
+    ix8.close(); ixf.close()
