@@ -7,7 +7,9 @@ attribute mask resident in HBM (72 GB), clustered embeddings, top-1000, per-quer
 A "step" is one whole search (all threshold-seeding sweeps, the full sweep, every merge)
 of one query batch.  The headline is the small-batch, HBM-bound regime (B = 32, 5 % pass
 rate); a short sweep over B in {1, 32, 256, 1024} and pass rates {50 %, 5 %, 0.1 %} is
-reported in the same JSON line under "sweep".
+reported in the same JSON line under "sweep".  A second leg, reported under "quantised", runs the
+1-bit search of Sec. 3.2 (64-bit Sign-OPORP codes of the same items, the paper's billion-member
+setting of Sec. 5.3) for B in {1, 32}, with its own roofline and oracle timing.
 
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
@@ -30,6 +32,9 @@ BYTES_PER_ITEM = 64 + 4 + 4    # codes + mask + row scale: the algorithmic HBM b
 # scaled by what the same counter reads for a 4 GiB device copy (profiles/scan_kernel_cfg5_B32_pass5.md); keyed by
 # (N, B, pass rate, k).  30,767,340 KiB fetched x 2.000 + 10,461 KiB written x 1.000.
 MEASURED_TRAFFIC_BYTES = {(1_000_000_000, 32, "5%", 1000): 63_022_224_384}
+# the same for the largest sweep of the 1-bit search at B = 1, keyed by (N, code bits, pass rate, k):
+# 5,127,353 KiB fetched x 2.000 + 450 KiB written (profiles/scan_kernel_bits_1e9_B1.md)
+MEASURED_BITS_TRAFFIC_BYTES = {(1_000_000_000, 64, "5%", 1000): 10_501_279_181}
 
 
 def log(msg):
@@ -63,6 +68,95 @@ def timed_steps(L, ix, w, k, steps, warmup, workspace, out):
     return wall_ms, mean, kinds, items
 
 
+def quantised_leg(L, S, base, index_cols, N, k, args, dev):
+    """Search over 1-bit Sign-OPORP codes (Sec. 3.2) of the same N items: codes + mask resident (12 bytes per item at
+    64 bits), filtered top-k by matching bits, B in {1, 32} at the headline pass rate.  The codes are made by the
+    library (linr_quantize_queries over the de-quantised rows, chunk by chunk); the index is codes-only."""
+    import numpy as np
+    import torch
+    d, kb = 64, args.code_bits
+    W = (kb + 63) // 64
+    bpi = 8 * W + 4
+    perm, signs = S.oporp_draw(d, 0)
+    helper = L.Index(256, d, S.F32, 0)                       # holds the permutation and signs; quantises any rows
+    helper.load(torch.zeros((256, d), dtype=torch.float32, device=dev), torch.zeros(256, dtype=torch.int32, device=dev))
+    helper.build_bits(perm, signs, kb)
+    t0 = time.time()
+    codes = torch.empty((N, W), dtype=torch.int64, device=dev)
+    chunk = 16_000_000
+    for s0 in range(0, N, chunk):
+        e0 = min(N, s0 + chunk)
+        codes[s0:e0] = helper.quantize(index_cols[0][s0:e0].float() * index_cols[1][s0:e0, None])
+    torch.cuda.synchronize()
+    log(f"quantised: {N:,} codes of {kb} bits built in {time.time() - t0:.1f} s ({N * bpi / 1e9:.1f} GB with masks)")
+    qix = L.Index(N, kb, S.BITS, 0)
+    qix.load(codes, index_cols[2])
+    stream = torch.cuda.current_stream().cuda_stream
+    C = 10_000 if N >= 100_000_000 else max(10, N // 100_000)
+    res, keep = {}, None
+    for B in (1, 32):
+        w = S.config5(device=dev, n=N, B=B, k=k, selectivity=args.selectivity, index=index_cols, C=C)
+        Qf = (w["Q"].float() * w["q_scale"].reshape(B, 1, 1)).reshape(B, d).contiguous()
+        qbits = helper.quantize(Qf)
+        fdev = torch.from_numpy(np.ascontiguousarray(w["filters"]).view(np.uint8).copy()).to(dev)
+        nbytes = L.search_bits_workspace_bytes(qix.handle, B, k)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        ids = torch.empty((B, k), dtype=torch.int32, device=dev)
+        mt = torch.empty((B, k), dtype=torch.int32, device=dev)
+        cnt = torch.empty((B,), dtype=torch.int32, device=dev)
+        steps = args.steps
+        ev = [L.events_create(2 * L.MAX_STAGES) for _ in range(steps)]
+        for _ in range(args.warmup):
+            L.search_bits(qix.handle, qbits, B, fdev, k, ids, mt, cnt, ws, nbytes, stream, L.FILTERS_ON_DEVICE)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(steps):
+            kinds, items = L.search_bits_timed(qix.handle, qbits, B, fdev, k, ids, mt, cnt, ws, nbytes, stream,
+                                               L.FILTERS_ON_DEVICE, ev[s])
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        per = [L.events_elapsed_ms(e, len(kinds)) for e in ev]
+        for e in ev:
+            L.events_destroy(e)
+        mean = [sum(p[i] for p in per) / steps for i in range(len(kinds))]
+        scans = [i for i, kd in enumerate(kinds) if kd == 1]
+        big = max(scans, key=lambda i: items[i])
+        res[f"B{B}"] = dict(ms_per_step=wall, pairs_per_s=N * B / wall * 1e3, queries_per_s=B / wall * 1e3, sweeps=len(scans),
+                            largest_sweep_items=items[big], largest_sweep_ms=mean[big],
+                            all_sweeps_ms=sum(mean[i] for i in scans),
+                            merges_ms=sum(mean[i] for i, kd in enumerate(kinds) if kd == 2),
+                            hbm_GBs=items[big] * bpi / mean[big] / 1e6, hbm_frac=items[big] * bpi / mean[big] / 1e6 / HBM_PEAK_GBS,
+                            pairs_per_s_largest_sweep=items[big] * B / mean[big] * 1e3, min_count=int(cnt.min().item()))
+        r = res[f"B{B}"]
+        log(f"  quantised B={B:2d}: {wall:.3f} ms/step; largest sweep ({items[big]:,} items) {mean[big]:.3f} ms = "
+            f"{r['hbm_GBs']:.0f} GB/s ({100 * r['hbm_frac']:.1f} % of HBM peak), {r['pairs_per_s_largest_sweep']:.3e} pairs/s")
+        if B == 1:
+            keep = (qbits.cpu().numpy().view(np.uint64), w["filters"])
+        del ws
+    out = {"workload": f"{N} x {kb}-bit Sign-OPORP codes (of the config-5 items) + uint32 mask, pass rate {args.selectivity}, "
+                       f"top-{k} by matching bits", "bytes_per_item": bpi, **res,
+           "roofline": {"bound": "hbm", "achieved": res["B1"]["hbm_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": res["B1"]["hbm_frac"], "traffic": MEASURED_BITS_TRAFFIC_BYTES.get((N, kb, args.selectivity, k)),
+                        "kernel": "scan_kernel_bits, largest sweep of the B=1 search",
+                        "kernel_ms": res["B1"]["largest_sweep_ms"], "items_per_launch": res["B1"]["largest_sweep_items"],
+                        "algorithmic_bytes_per_launch": res["B1"]["largest_sweep_items"] * bpi}}
+    if not args.no_cpu:
+        import oracle
+        ns = min(N, 500_000_000)
+        codes_h = codes[:ns].cpu().numpy().view(np.uint64)
+        mk_h = index_cols[2][:ns].cpu().numpy().view(np.uint32)
+        t0 = time.perf_counter()
+        oracle.bits_search(codes_h, kb, mk_h, keep[0], keep[1], k)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = dict(value=ns / dt, unit="item-query pairs/s", cores=1, kind="oracle",
+                                   sample=f"first {ns} codes x 1 query of the same workload, {dt:.1f} s")
+        log(f"  quantised oracle: {ns / dt:.3e} pairs/s on 1 thread")
+    qix.close()
+    helper.close()
+    del codes
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -74,6 +168,8 @@ def main():
     ap.add_argument("--k", type=int, default=1000)
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-quantised", action="store_true", help="skip the 1-bit (Sign-OPORP) search leg")
+    ap.add_argument("--code-bits", type=int, default=64, help="bits per Sign-OPORP code of the quantised leg (divides 64)")
     ap.add_argument("--sweep-steps", type=int, default=5)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 4 GiB device copy (known traffic) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
@@ -158,10 +254,14 @@ def main():
                 log(f"  sweep B={B:4d} pass {sel:>4}: {r['ms_per_step']:.2f} ms/step  scans {r['all_sweeps_ms']:.2f} ms  "
                     f"{r['hbm_GBs']:.0f} GB/s  {r['int8_TOPs']:.0f} TOP/s  {r['queries_per_s']:.0f} QPS")
 
+    quant = None
+    if not args.no_quantised:
+        quant = quantised_leg(L, S, base, index_cols, N, k, args, dev)
+
     cpu = None
     if not args.no_cpu:
         import oracle
-        ns, Bs = min(N, 16_000_000), min(args.batch, 32)
+        ns, Bs = min(N, 48_000_000), min(args.batch, 32)
         log(f"cpu baseline: oracle on the first {ns:,} items x {Bs} queries ...")
         emb_h = base["emb"][:ns].cpu().numpy(); sc_h = base["scale"][:ns].cpu().numpy()
         mk_h = base["mask"][:ns].cpu().numpy().view(np.uint32)
@@ -196,6 +296,7 @@ def main():
         "cpu_baseline": cpu,
         "stage_ms": {"largest_sweep": head["largest_sweep_ms"], "all_sweeps": head["all_sweeps_ms"], "merges": head["merges_ms"]},
         "sweep": sweep,
+        "quantised": quant,
     }
     print(json.dumps(line), flush=True)
 

@@ -238,6 +238,11 @@ int linr_search_filtered_timed(const linr_index*, const void* Q, const float* q_
                          uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
                          void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags,
                          void** events, uint32_t* n_stages, uint32_t* kinds, uint64_t* stage_items);
+/* the same per-stage timing for linr_search_bits (Sec. 3.2) */
+int linr_search_bits_timed(const linr_index*, const uint64_t* qbits, uint32_t B, const linr_filter* filters, uint32_t T,
+                           uint32_t* out_ids, int32_t* out_matches, uint32_t* out_counts,
+                           void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags,
+                           void** events, uint32_t* n_stages, uint32_t* kinds, uint64_t* stage_items);
 /* hipEvent_t helpers for callers without direct access to the HIP runtime (host arrays) */
 int linr_events_create(void** events, uint32_t n);
 int linr_events_destroy(void** events, uint32_t n);

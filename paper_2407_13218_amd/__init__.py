@@ -8,5 +8,7 @@ from .binding import (  # noqa: F401
     index_create, index_load_fp32, index_load_bf16, index_load_int8, index_info, index_destroy,
     search_workspace_bytes, search_filtered, search_filtered_timed, set_tuning, strerror,
     events_create, events_destroy, events_elapsed_ms, MAX_STAGES, STAGE_NAMES,
+    index_build_bits, index_load_bits, quantize_queries, search_bits_workspace_bytes, search_bits, search_bits_timed,
+    search_two_stage_workspace_bytes, search_two_stage,
     Index,
 )

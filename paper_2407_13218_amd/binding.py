@@ -31,7 +31,7 @@ EXPORTS = [
     "linr_strerror", "linr_last_hip_error", "linr_set_tuning", "linr_search_filtered_timed",
     "linr_events_create", "linr_events_destroy", "linr_events_elapsed_ms",
     "linr_index_build_bits", "linr_index_load_bits", "linr_quantize_queries", "linr_search_bits_workspace_bytes",
-    "linr_search_bits", "linr_search_two_stage_workspace_bytes", "linr_search_two_stage",
+    "linr_search_bits", "linr_search_two_stage_workspace_bytes", "linr_search_two_stage", "linr_search_bits_timed",
 ]
 
 
@@ -103,6 +103,8 @@ def load_library():
     lib.linr_search_bits_workspace_bytes.argtypes = [vp, u32, u32, C.POINTER(u64)]
     lib.linr_search_bits.restype = i32
     lib.linr_search_bits.argtypes = [vp, vp, u32, vp, u32, vp, vp, vp, vp, u64, vp, u32]
+    lib.linr_search_bits_timed.restype = i32
+    lib.linr_search_bits_timed.argtypes = lib.linr_search_bits.argtypes + [vp, C.POINTER(u32), vp, vp]
     lib.linr_search_two_stage_workspace_bytes.restype = i32
     lib.linr_search_two_stage_workspace_bytes.argtypes = [vp, u32, u32, u32, C.POINTER(u64)]
     lib.linr_search_two_stage.restype = i32
@@ -233,6 +235,19 @@ def search_bits(ix, qbits, B, filters, T, out_ids, out_matches, out_counts, work
                 flags=FILTERS_ON_DEVICE):
     _check(load_library().linr_search_bits(ix, _ptr(qbits), B, _ptr(filters), T, _ptr(out_ids), _ptr(out_matches),
                                            _ptr(out_counts), _ptr(workspace), workspace_bytes, stream, flags), "linr_search_bits")
+
+
+def search_bits_timed(ix, qbits, B, filters, T, out_ids, out_matches, out_counts, workspace, workspace_bytes, stream, flags,
+                      events):
+    """As search_bits, recording `events` (2*MAX_STAGES hipEvent_t) around each launch.  Returns (kinds, items) per stage."""
+    ns = C.c_uint32()
+    kinds = (C.c_uint32 * MAX_STAGES)()
+    items = (C.c_uint64 * MAX_STAGES)()
+    _check(load_library().linr_search_bits_timed(ix, _ptr(qbits), B, _ptr(filters), T, _ptr(out_ids), _ptr(out_matches),
+                                                 _ptr(out_counts), _ptr(workspace), workspace_bytes, stream, flags,
+                                                 C.addressof(events), C.byref(ns), C.addressof(kinds), C.addressof(items)),
+           "linr_search_bits_timed")
+    return [kinds[i] for i in range(ns.value)], [items[i] for i in range(ns.value)]
 
 
 def search_two_stage_workspace_bytes(ix, B, T, k) -> int:

@@ -330,7 +330,10 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
     uint32_t max_levels = g_tuning.max_levels ? g_tuning.max_levels : LINR_MAX_LEVELS;
     if (max_levels > LINR_MAX_LEVELS) max_levels = LINR_MAX_LEVELS;
     // (kernels that already fold the predicate into their first test gain nothing from the finer split)
-    const bool top_split = !g_tuning.no_top_split && p->n_chunks >= 65536 && (p->coop || p->generic || p->qg > 2);
+    // (... nor does the bit-matching scan for a few queries: it is bound by HBM there, and a sweep over 7/8 of the
+    // chunks reads them in longer contiguous runs than the finer sweeps do)
+    const bool top_split = !g_tuning.no_top_split && p->n_chunks >= 65536 && (p->coop || p->generic || p->qg > 2) &&
+                           !(p->bits && B <= 8);
     static const uint32_t top_ratios[3] = {2, 4, 4};
     uint32_t strides[LINR_MAX_LEVELS];
     uint32_t nl = 0;
@@ -615,10 +618,12 @@ extern "C" int linr_search_bits_workspace_bytes(const linr_index* ix, uint32_t B
     return LINR_OK;
 }
 
-extern "C" int linr_search_bits(const linr_index* ix, const uint64_t* qbits, uint32_t B, const linr_filter* filters, uint32_t T,
-                                uint32_t* out_ids, int32_t* out_matches, uint32_t* out_counts, void* workspace,
-                                uint64_t workspace_bytes, void* hip_stream, uint32_t flags)
+static int search_bits_impl(const linr_index* ix, const uint64_t* qbits, uint32_t B, const linr_filter* filters, uint32_t T,
+                            uint32_t* out_ids, int32_t* out_matches, uint32_t* out_counts, void* workspace,
+                            uint64_t workspace_bytes, void* hip_stream, uint32_t flags, void** events, uint32_t* n_stages,
+                            uint32_t* kinds, uint64_t* stage_items)
 {
+    if (n_stages) *n_stages = 0;
     linr_index v;
     int rc = bits_view(ix, &v);
     if (rc != LINR_OK) return rc;
@@ -632,7 +637,24 @@ extern "C" int linr_search_bits(const linr_index* ix, const uint64_t* qbits, uin
     if (!workspace || (((uintptr_t)workspace) & 255u) || workspace_bytes < total) return LINR_E_WORKSPACE;
     float* fscores = (float*)((char*)workspace + align_up(inner, 256));
     return search_impl(&v, qbits, nullptr, B, 1, filters, T, out_ids, fscores, out_matches, out_counts, workspace, inner,
-                       hip_stream, flags, nullptr, nullptr, nullptr, nullptr);
+                       hip_stream, flags, events, n_stages, kinds, stage_items);
+}
+
+extern "C" int linr_search_bits(const linr_index* ix, const uint64_t* qbits, uint32_t B, const linr_filter* filters, uint32_t T,
+                                uint32_t* out_ids, int32_t* out_matches, uint32_t* out_counts, void* workspace,
+                                uint64_t workspace_bytes, void* hip_stream, uint32_t flags)
+{
+    return search_bits_impl(ix, qbits, B, filters, T, out_ids, out_matches, out_counts, workspace, workspace_bytes, hip_stream,
+                            flags, nullptr, nullptr, nullptr, nullptr);
+}
+
+extern "C" int linr_search_bits_timed(const linr_index* ix, const uint64_t* qbits, uint32_t B, const linr_filter* filters,
+                                      uint32_t T, uint32_t* out_ids, int32_t* out_matches, uint32_t* out_counts,
+                                      void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags,
+                                      void** events, uint32_t* n_stages, uint32_t* kinds, uint64_t* stage_items)
+{
+    return search_bits_impl(ix, qbits, B, filters, T, out_ids, out_matches, out_counts, workspace, workspace_bytes, hip_stream,
+                            flags, events, n_stages, kinds, stage_items);
 }
 
 extern "C" int linr_search_two_stage_workspace_bytes(const linr_index* ix, uint32_t B, uint32_t T, uint32_t k, uint64_t* bytes)

@@ -1558,84 +1558,130 @@ __device__ __forceinline__ void issue_bits(BitsRegs<W>& R, const linr_scan_args&
     }
 }
 
+// one query as the bit-matching loop reads it: its code and the offset that turns the bound test into a sign test
 template <int W>
-__global__ void __launch_bounds__(64 * WPB, 4) scan_kernel_bits(linr_scan_args A)
+struct __attribute__((aligned(8))) BitsQ {
+    u64 code[W];
+    uint32_t bias, pad;
+};
+
+// acc + number of set bits of x (one instruction; the accumulate operand carries the bound offset)
+__device__ __forceinline__ uint32_t bcnt_acc(uint32_t x, uint32_t acc)
+{
+    uint32_t r;
+    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(acc));
+    return r;
+}
+
+template <int W>
+__global__ void __launch_bounds__(64 * WPB, W <= 2 ? 4 : 2) scan_kernel_bits(linr_scan_args A)
 {
     constexpr int NQ = LINR_BITS_NQ;
     __shared__ WaveQ<NQ / 16> wq_all[WPB];
     __shared__ uint32_t hist_all[WPB][256];
-    __shared__ u64 qcode[NQ][W];                         // the batch's codes (whole workgroup)
+    __shared__ BitsQ<W> qrec_all[WPB][NQ + 2];           // per wave (the offsets follow the wave's own bounds); +2: read-ahead
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
     WaveQ<NQ / 16>& Wq = wq_all[wib];
+    BitsQ<W>* qrec = qrec_all[wib];
     const QSide qs = {Wq.cnt, Wq.thr_f, Wq.thr_i, Wq.fall, Wq.fnone, Wq.tsmin, Wq.tsmax, Wq.fflag};
     const uint32_t slot = blockIdx.x * WPB + wib;
     const bool has_ts = A.ts != nullptr;
     const int kb = (int)A.k_bits;                        // bits per code
-    for (uint32_t t = threadIdx.x; t < (uint32_t)NQ * W; t += 64 * WPB) {
-        const uint32_t b = t / W;
-        qcode[b][t % W] = b < A.B ? ((const u64*)A.Q)[t] : 0ull;
-    }
+    if (slot >= A.nslots) return;                        // no workgroup-wide barrier below
     for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) {
+#pragma unroll
+        for (int w = 0; w < W; ++w) qrec[ql].code[w] = ql < A.B ? ((const u64*)A.Q)[(u64)ql * W + w] : 0ull;
         Wq.cnt[ql] = 0;
         load_query_side(qs, ql, ql, A, true);
     }
-    __syncthreads();
-    if (slot >= A.nslots) return;
+    wave_sync();
+    // matches >= bound  <=>  differing bits - (k_bits - bound + 1) < 0: the bit counts accumulate onto that
+    // offset, so the sign of the sum is the test.  No bound yet (INT_MIN): the saturating add keeps INT_MIN,
+    // and every sum stays negative.
+    auto set_bias = [&]() {
+        for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64)
+            qrec[ql].bias = (uint32_t)__builtin_elementwise_add_sat(Wq.thr_i[ql], -(kb + 1));
+        wave_sync();
+    };
+    set_bias();
 
-    BitsRegs<W> R, N;
+    // The chunk being matched and the chunks in flight live in register sets whose roles rotate (no copies: a copy
+    // of a set with loads pending would wait for them).  64-bit codes keep two chunks in flight, wider codes one.
+    constexpr bool DEEP = W == 1;
     uint32_t need_compact = 0u, since_refresh = 0u;
     SweepWalk walk;
     walk.init(slot, A);
-    u64 lc = walk.lc();
-    if (walk.valid()) issue_bits<W>(N, A, lc, lane, has_ts);
-    while (walk.valid()) {
-        const u64 item0 = lc * A.stride * LINR_BITS_CH;
-        R = N;
+    u64 lcA = walk.lc(), lcB = 0;
+    bool vA = walk.valid(), vB = false;
+    BitsRegs<W> S0, S1, S2;
+    if (vA) issue_bits<W>(S0, A, lcA, lane, has_ts);
+    if constexpr (DEEP) {
         walk.advance();
-        const u64 nlc = walk.lc();
-        if (walk.valid()) issue_bits<W>(N, A, nlc, lane, has_ts);
+        lcB = walk.lc(); vB = walk.valid();
+        if (vB) issue_bits<W>(S1, A, lcB, lane, has_ts);
+    }
+    auto step = [&](BitsRegs<W>& cur, BitsRegs<W>& fre) -> bool {
+        if (!vA) return false;
+        const u64 item0 = lcA * A.stride * LINR_BITS_CH;
+        walk.advance();
+        const u64 lcC = walk.lc();
+        const bool vC = walk.valid();
+        if (vC) issue_bits<W>(fre, A, lcC, lane, has_ts);
 
         bool live[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) live[u] = item0 + u * 64 + lane < A.n;
-#pragma unroll 1
-        for (uint32_t b = 0; b < A.B; ++b) {
-            // matches >= bound  <=>  differing bits <= k_bits - bound (no bound yet: everything qualifies)
-            const int thr = Wq.thr_i[b];
-            const int dmax = thr == INT_MIN ? INT_MAX : kb - thr;
-            u64 qw[W];
-#pragma unroll
-            for (int w = 0; w < W; ++w) qw[w] = qcode[b][w];
-            int diff[4];
-            bool hot = false;
+        // survivors of one query: predicate, key, append (rare).  The query index goes through an opaque copy so
+        // that the addresses below are formed here and not carried as induction variables of the hot loop.
+        auto survivors = [&](uint32_t bq, const BitsQ<W>& q, const uint32_t (&r)[4]) {
+            asm volatile("" : "+s"(bq));
+            const linr_filter* F = A.filters + bq;
+            const uint32_t fa = Wq.fall[bq], fn = Wq.fnone[bq];
+            const bool complex = (Wq.fflag[bq] & 1u) != 0u;
+            u64* seg_p = A.seg + ((u64)slot * A.B + bq) * A.cap;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                int dsum = 0;
-#pragma unroll
-                for (int w = 0; w < W; ++w) dsum += __popcll(R.x[u][w] ^ qw[w]);
-                diff[u] = dsum;
-                hot = hot | (dsum <= dmax);
-            }
-            if (!wave_any(hot)) continue;
-            // survivors: predicate, key, append (rare)
-            const linr_filter* F = A.filters + b;
-            const uint32_t fa = Wq.fall[b], fn = Wq.fnone[b];
-            const bool complex = (Wq.fflag[b] & 1u) != 0u;
-            u64* seg_p = A.seg + ((u64)slot * A.B + b) * A.cap;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int matches = kb - diff[u];
-                bool ok = live[u] & (diff[u] <= dmax) & ((R.mk[u] & fn) == fa);
-                if (has_ts) ok = ok & (R.ts[u] >= Wq.tsmin[b]) & (R.ts[u] <= Wq.tsmax[b]);
-                if (ok && complex) ok = filter_pass(*F, R.mk[u], has_ts, R.ts[u]);
+                const int matches = kb - (int)(r[u] - q.bias);
+                bool ok = live[u] & ((int)r[u] < 0) & ((cur.mk[u] & fn) == fa);
+                if (has_ts) ok = ok & (cur.ts[u] >= Wq.tsmin[bq]) & (cur.ts[u] <= Wq.tsmax[bq]);
+                if (ok && complex) ok = filter_pass(*F, cur.mk[u], has_ts, cur.ts[u]);
                 if (ok) {
                     const u64 item = item0 + u * 64 + lane;
                     const u64 key = ((u64)ord_i32(matches) << 32) | (u64)(uint32_t)~(uint32_t)item;
-                    const uint32_t pos = atomicAdd(&Wq.cnt[b], 1u);
+                    const uint32_t pos = atomicAdd(&Wq.cnt[bq], 1u);
                     if (pos < A.cap) seg_p[pos] = key;
                     if (pos + 1 + LINR_BITS_CH > A.cap) need_compact = 1u;
                 }
             }
+        };
+        auto match4 = [&](const BitsQ<W>& q, uint32_t (&r)[4]) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                uint32_t acc = q.bias;
+#pragma unroll
+                for (int w = 0; w < W; ++w) {
+                    const u64 x = cur.x[u][w] ^ q.code[w];
+                    acc = bcnt_acc((uint32_t)x, acc);
+                    acc = bcnt_acc((uint32_t)(x >> 32), acc);
+                }
+                r[u] = acc;
+            }
+        };
+        // two queries per trip (the record after an odd batch's last query has a bound nothing reaches); the next
+        // two records are read ahead (entries up to NQ + 1 exist)
+        BitsQ<W> qn0 = qrec[0], qn1 = qrec[1];
+#pragma unroll 1
+        for (uint32_t b = 0; b < A.B; b += 2) {
+            const BitsQ<W> q0 = qn0, q1 = qn1;
+            qn0 = qrec[b + 2];
+            qn1 = qrec[b + 3];
+            uint32_t r0[4], r1[4];
+            match4(q0, r0);
+            match4(q1, r1);
+            const uint32_t h0 = r0[0] | r0[1] | r0[2] | r0[3], h1 = r1[0] | r1[1] | r1[2] | r1[3];
+            if (!wave_any((int)(h0 | h1) < 0)) continue;
+            if (wave_any((int)h0 < 0)) survivors(b, q0, r0);
+            if (wave_any((int)h1 < 0)) survivors(b + 1, q1, r1);
         }
         bool refresh = ++since_refresh >= 16;
         if (wave_any(need_compact != 0u)) {
@@ -1646,9 +1692,24 @@ __global__ void __launch_bounds__(64 * WPB, 4) scan_kernel_bits(linr_scan_args A
         if (refresh) {
             for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) load_query_side(qs, ql, ql, A, false);
             wave_sync();
+            set_bias();
             since_refresh = 0;
         }
-        lc = nlc;
+        if constexpr (DEEP) { lcA = lcB; vA = vB; lcB = lcC; vB = vC; }
+        else { lcA = lcC; vA = vC; }
+        return true;
+    };
+    if constexpr (DEEP) {
+        while (true) {
+            if (!step(S0, S2)) break;
+            if (!step(S1, S0)) break;
+            if (!step(S2, S1)) break;
+        }
+    } else {
+        while (true) {
+            if (!step(S0, S1)) break;
+            if (!step(S1, S0)) break;
+        }
     }
     own_stores_done();
     flush_segments(A, qs, slot, 0, NQ, lane, hist_all[wib]);
