@@ -140,6 +140,13 @@ def quantised_leg(L, S, base, index_cols, N, k, args, dev):
                         "kernel": "scan_kernel_bits, largest sweep of the B=1 search",
                         "kernel_ms": res["B1"]["largest_sweep_ms"], "items_per_launch": res["B1"]["largest_sweep_items"],
                         "algorithmic_bytes_per_launch": res["B1"]["largest_sweep_items"] * bpi}}
+    # many queries: bound by the vector ALUs.  One item-query pair costs at least 2 W xor + 2 W popcount lane-operations
+    # (32-bit each); 256 CUs x 64 lanes x 2.4 GHz lane-operations per second.
+    alu_peak = 256 * 64 * 2.4e9 / (4 * W)
+    out["roofline_B32"] = {"bound": "alu", "achieved": res["B32"]["pairs_per_s_largest_sweep"], "peak": alu_peak,
+                           "unit": "item-query pairs/s", "frac": res["B32"]["pairs_per_s_largest_sweep"] / alu_peak,
+                           "kernel": "scan_kernel_bits, largest sweep of the B=32 search",
+                           "kernel_ms": res["B32"]["largest_sweep_ms"], "items_per_launch": res["B32"]["largest_sweep_items"]}
     if not args.no_cpu:
         import oracle
         ns = min(N, 500_000_000)
