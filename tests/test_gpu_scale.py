@@ -1,4 +1,4 @@
-"""Parity at the full sizes of the five configurations.  Configs 2, 3 and 4 fit in host memory: the GPU answers the
+"""Parity at the full sizes of the five configurations (and of the quantised search over 1e9 codes, last test).  Configs 2, 3 and 4 fit in host memory: the GPU answers the
 whole batch and the oracle scans the whole index for all (config 3) or every 16th query.  Config 5 (1e9 x d64 int8
 resident in HBM, the launch configuration bench.py times): the CPU oracle cannot hold 72 GB at once, so
   (a) every returned (query, id) pair of the whole batch is re-scored by the oracle one by one (rows gathered on the
@@ -134,3 +134,94 @@ def test_config4_full_size(oracle_mod):
     say("generating config 4 at full size")
     w = S.config4(device="cuda")
     _full_size_case(oracle_mod, w, list(range(0, 128, 16)), "config 4 full size")
+
+
+def test_quantised_full_size(oracle_mod):
+    """1e9 x 64-bit Sign-OPORP codes + masks (the quantised leg bench.py times; Sec. 3.2 / 5.3), B = 1 and B = 32, T = 1000:
+      (a) the library's codes of 200 000 sampled items equal the oracle's codes of the same rows;
+      (b) every returned (query, id) pair: match count recomputed by the oracle, feasibility, order, uniqueness;
+      (c) the B = 1 query and two queries of the B = 32 batch against a full oracle scan streamed in pieces."""
+    import torch
+    import paper_2407_13218_amd as L
+
+    free, _ = torch.cuda.mem_get_info()
+    if free < N_FULL * 90:
+        pytest.skip("not enough free HBM for the full-size index")
+    T, d, kb = 1000, 64, 64
+    say(f"generating {N_FULL:,} items on the GPU")
+    base = S.config5(device="cuda", n=N_FULL, B=32, k=T, selectivity="5%")
+    cols = (base["emb"], base["scale"], base["mask"])
+    perm, signs = S.oporp_draw(d, 0)
+    helper = L.Index(256, d, S.F32, 0)
+    helper.load(torch.zeros((256, d), dtype=torch.float32, device="cuda"), torch.zeros(256, dtype=torch.int32, device="cuda"))
+    helper.build_bits(perm, signs, kb)
+    codes = torch.empty((N_FULL, 1), dtype=torch.int64, device="cuda")
+    for p0 in range(0, N_FULL, PIECE):
+        p1 = min(N_FULL, p0 + PIECE)
+        codes[p0:p1] = helper.quantize(base["emb"][p0:p1].float() * base["scale"][p0:p1, None])
+    torch.cuda.synchronize()
+    say("codes built by the library")
+
+    # (a) sampled codes
+    g = torch.Generator(device="cuda"); g.manual_seed(77)
+    pick = torch.randint(0, N_FULL, (200_000,), generator=g, device="cuda")
+    rows = (base["emb"].index_select(0, pick).float() * base["scale"].index_select(0, pick)[:, None]).cpu().numpy()
+    exp = oracle_mod.sign_oporp(S.F32, rows, perm, signs, kb)
+    assert np.array_equal(codes.index_select(0, pick).cpu().numpy().view(np.uint64), exp), "codes differ from the oracle's"
+    say("(a) 200000 sampled codes equal the oracle's")
+
+    ix = L.Index(N_FULL, kb, S.BITS, 0)
+    ix.load(codes, base["mask"])
+    runs = {}
+    for B in (1, 32):
+        w = S.config5(device="cuda", n=N_FULL, B=B, k=T, selectivity="5%", index=cols)
+        Qf = (w["Q"].float() * w["q_scale"].reshape(B, 1, 1)).reshape(B, d).contiguous()
+        qbits = helper.quantize(Qf)
+        assert np.array_equal(qbits.cpu().numpy().view(np.uint64), oracle_mod.sign_oporp(S.F32, Qf.cpu().numpy(), perm, signs, kb))
+        ids, mt, cnt = ix.search_bits(qbits, w["filters"], T)
+        torch.cuda.synchronize()
+        runs[B] = (w, qbits.cpu().numpy().view(np.uint64), ids.cpu().numpy().view(np.uint32), mt.cpu().numpy(),
+                   cnt.cpu().numpy().view(np.uint32))
+        say(f"GPU search done for B = {B}")
+
+    # (b) every returned pair
+    for B, (w, qb, ids, mt, cnt) in runs.items():
+        assert np.all(cnt == T), f"B={B}: counts {cnt}"
+        flat = torch.from_numpy(ids.astype(np.int64).reshape(-1)).cuda()
+        cd = codes.index_select(0, flat).cpu().numpy().view(np.uint64).reshape(B, T, 1)
+        mk = base["mask"].index_select(0, flat).cpu().numpy().view(np.uint32).reshape(B, T)
+        for b in range(B):
+            for j in range(T):
+                assert oracle_mod.bit_matches(cd[b, j], qb[b], kb) == mt[b, j], f"B={B} query {b} rank {j}: match count"
+                assert oracle_mod.passes(w["filters"][b], mk[b, j]), f"B={B} query {b} rank {j}: infeasible id"
+        m64 = mt.astype(np.int64)
+        assert np.all(np.diff(m64, axis=1) <= 0), f"B={B}: match counts increase"
+        same = np.diff(m64, axis=1) == 0
+        assert np.all(np.diff(ids.astype(np.int64), axis=1)[same] > 0), f"B={B}: equal counts not in ascending id"
+        assert all(len(set(ids[b].tolist())) == T for b in range(B)), f"B={B}: duplicate ids"
+        say(f"(b) B = {B}: all {B * T} returned pairs recomputed by the oracle: exact")
+
+    # (c) full oracle scans, streamed
+    picks = [(1, 0), (32, 5), (32, 26)]
+    qsel = np.stack([runs[B][1][b] for B, b in picks])
+    filt = np.stack([runs[B][0]["filters"][b] for B, b in picks]).astype(S.FILTER_DTYPE)
+    best = [dict(ids=np.zeros(0, np.uint32), mt=np.zeros(0, np.int32)) for _ in picks]
+    piece = 4 * PIECE
+    for p0 in range(0, N_FULL, piece):
+        p1 = min(N_FULL, p0 + piece)
+        c_h = codes[p0:p1].cpu().numpy().view(np.uint64)
+        mk_h = base["mask"][p0:p1].cpu().numpy().view(np.uint32)
+        oi, om, oc = oracle_mod.bits_search(c_h, kb, mk_h, qsel, filt, T, id_base=p0)
+        for j in range(len(picks)):
+            c = int(oc[j])
+            ids_j = np.concatenate([best[j]["ids"], oi[j, :c]]); mt_j = np.concatenate([best[j]["mt"], om[j, :c]])
+            order = np.lexsort((ids_j, -mt_j.astype(np.int64)))[:T]
+            best[j] = dict(ids=ids_j[order], mt=mt_j[order])
+        say(f"oracle streamed {p1:,} / {N_FULL:,} codes")
+    for j, (B, b) in enumerate(picks):
+        _, _, ids, mt, _ = runs[B]
+        assert np.array_equal(best[j]["ids"], ids[b]), f"B={B} query {b}: id list differs from the full oracle scan"
+        assert np.array_equal(best[j]["mt"], mt[b])
+        say(f"(c) B = {B} query {b}: top-{T} of {N_FULL:,} codes identical to the oracle's")
+    ix.close()
+    helper.close()
