@@ -41,7 +41,8 @@ enum {
     LINR_E_NOT_LOADED = -6,  /* search on an index that holds no items yet                 */
     LINR_E_WORKSPACE = -7,   /* workspace NULL, misaligned or smaller than required        */
     LINR_E_HIP = -8,         /* a HIP runtime call failed (see linr_last_hip_error)        */
-    LINR_E_FILTER = -9       /* malformed filter (host filters only are checked)           */
+    LINR_E_FILTER = -9,      /* malformed filter (host filters only are checked)           */
+    LINR_E_STATE = -10       /* the index is not in the state the call needs               */
 };
 
 /* where the loader's source arrays live and who owns the resident copy */
@@ -193,7 +194,55 @@ int linr_search_two_stage(const linr_index*, const void* Q, uint32_t B, const li
                           uint32_t* out_ids, float* out_scores, uint32_t* out_counts,
                           void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags);
 
-/* number of items currently resident / element type / dimensions */
+/*
+ * Live updates (Sec. 4 "Model Live Update": Upsert and Delete calls on columns that are
+ * pre-allocated larger than the initial index, a high-water mark for the working set, and
+ * updates that run next to searches; their cost for searches is the subject of Sec. 5.3,
+ * "Impact of Live Model Update on Inference").
+ *
+ * An item lives in a slot; the slot number is the id a search returns (the mapping from
+ * document keys to slots belongs to the caller's ingestor).  The index holds `capacity`
+ * slots (linr_index_create); slots [0, n) below the high-water mark n are scanned.
+ *
+ * linr_index_enable_updates  call once after a load.  From then on bit 31 of every item
+ *     mask belongs to the library (set = the slot holds no item) and 31 attribute bits
+ *     remain: LINR_E_FILTER if a resident mask carries bit 31.  A filter that requires
+ *     bit 31 matches nothing.  Library-owned columns already span the capacity; borrowed
+ *     columns (LINR_SRC_DEVICE_BORROW) must do so too -- updates write into them.
+ *     linr_search_workspace_bytes then answers for a full index.  A later load ends it.
+ * linr_index_upsert  writes `count` items into the given slots (host array, distinct,
+ *     each < capacity; LINR_E_CAPACITY / LINR_E_SHAPE otherwise): emb [count][d] (codes
+ *     [count][W] for LINR_BITS), mask, and row_scale / ts where the index has them, host
+ *     (src == LINR_SRC_HOST; copied before the call returns) or device (any other value;
+ *     read when the stream gets there).  Bit 31 of the new masks is ignored.  The slot may
+ *     be fresh, deleted or live.  The mark rises to max(slot) + 1; skipped slots below it
+ *     stay empty.  Codes made by linr_index_build_bits are refreshed for the new rows.
+ * linr_index_delete  marks the slots (host array, each below the mark) as empty; a slot
+ *     that is already empty stays so.
+ * linr_index_sync_updates  waits for every enqueued update and publishes the mark.
+ *
+ * Both calls only enqueue work on `hip_stream` (a copy from a pinned staging area and a
+ * few small kernels) and return; they wait only for the previous update, whose staging
+ * area they reuse.  Any number of host threads may search while one thread at a time
+ * updates (updaters are serialised by a lock; searches take a lock for a few loads only).
+ * Visibility: a search enqueued on the update's own stream sees it (stream order).  For
+ * searches on other streams a delete takes effect when its kernel runs (one atomic word
+ * per slot), and items upserted into slots at or above the published mark appear, whole,
+ * in searches enqueued after the update has finished on the device: the mark is published
+ * by the first call that finds the update's event complete.  Rewriting a slot below the
+ * published mark while searches on other streams are running is not atomic (such a search
+ * may pair the slot's new mask with its old row): give the new version a fresh slot and
+ * delete the old one instead.
+ * Errors: LINR_E_STATE (updates not enabled), LINR_E_NULL, LINR_E_CAPACITY, LINR_E_SHAPE,
+ * LINR_E_HIP.
+ */
+int linr_index_enable_updates(linr_index*);
+int linr_index_upsert(linr_index*, const uint32_t* slots, uint32_t count, const void* emb, const float* row_scale,
+                      const uint32_t* mask, const uint32_t* ts, int src, void* hip_stream);
+int linr_index_delete(linr_index*, const uint32_t* slots, uint32_t count, void* hip_stream);
+int linr_index_sync_updates(linr_index*);
+
+/* number of items currently resident (the published high-water mark) / element type / dimensions */
 int linr_index_info(const linr_index*, uint64_t* n, uint32_t* d, int* dtype, int* has_ts, int* has_row_scale);
 
 const char* linr_strerror(int code);

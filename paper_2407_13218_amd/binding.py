@@ -32,6 +32,7 @@ EXPORTS = [
     "linr_events_create", "linr_events_destroy", "linr_events_elapsed_ms",
     "linr_index_build_bits", "linr_index_load_bits", "linr_quantize_queries", "linr_search_bits_workspace_bytes",
     "linr_search_bits", "linr_search_two_stage_workspace_bytes", "linr_search_two_stage", "linr_search_bits_timed",
+    "linr_index_enable_updates", "linr_index_upsert", "linr_index_delete", "linr_index_sync_updates",
 ]
 
 
@@ -103,6 +104,14 @@ def load_library():
     lib.linr_search_bits_workspace_bytes.argtypes = [vp, u32, u32, C.POINTER(u64)]
     lib.linr_search_bits.restype = i32
     lib.linr_search_bits.argtypes = [vp, vp, u32, vp, u32, vp, vp, vp, vp, u64, vp, u32]
+    lib.linr_index_enable_updates.restype = i32
+    lib.linr_index_enable_updates.argtypes = [vp]
+    lib.linr_index_upsert.restype = i32
+    lib.linr_index_upsert.argtypes = [vp, vp, u32, vp, vp, vp, vp, i32, vp]
+    lib.linr_index_delete.restype = i32
+    lib.linr_index_delete.argtypes = [vp, vp, u32, vp]
+    lib.linr_index_sync_updates.restype = i32
+    lib.linr_index_sync_updates.argtypes = [vp]
     lib.linr_search_bits_timed.restype = i32
     lib.linr_search_bits_timed.argtypes = lib.linr_search_bits.argtypes + [vp, C.POINTER(u32), vp, vp]
     lib.linr_search_two_stage_workspace_bytes.restype = i32
@@ -264,6 +273,26 @@ def search_two_stage(ix, Q, B, filters, T, k, out_ids, out_scores, out_counts, w
            "linr_search_two_stage")
 
 
+def index_enable_updates(ix):
+    _check(load_library().linr_index_enable_updates(ix), "linr_index_enable_updates")
+
+
+def index_upsert(ix, slots, emb, row_scale, mask, ts, src, stream=0):
+    """slots: numpy uint32 (host).  emb / row_scale / mask / ts: numpy (src = SRC_HOST) or device tensors."""
+    slots = np.ascontiguousarray(slots, dtype=np.uint32)
+    _check(load_library().linr_index_upsert(ix, _ptr(slots), slots.size, _ptr(emb), _ptr(row_scale), _ptr(mask), _ptr(ts),
+                                            src, stream), "linr_index_upsert")
+
+
+def index_delete(ix, slots, stream=0):
+    slots = np.ascontiguousarray(slots, dtype=np.uint32)
+    _check(load_library().linr_index_delete(ix, _ptr(slots), slots.size, stream), "linr_index_delete")
+
+
+def index_sync_updates(ix):
+    _check(load_library().linr_index_sync_updates(ix), "linr_index_sync_updates")
+
+
 def set_tuning(**kw):
     """set_tuning() restores the defaults."""
     lib = load_library()
@@ -304,6 +333,33 @@ class Index:
 
     def workspace_bytes(self, B, m, k):
         return search_workspace_bytes(self.handle, B, m, k)
+
+    # live updates ------------------------------------------------------------------------------------------
+    def enable_updates(self):
+        index_enable_updates(self.handle)
+        return self
+
+    def upsert(self, slots, emb, mask, ts=None, row_scale=None, stream=None):
+        """slots: host integers; the rest numpy (copied before the call returns) or device tensors"""
+        import torch
+        host = isinstance(emb, np.ndarray)
+        if stream is None:
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+        index_upsert(self.handle, slots, emb, row_scale, mask, ts, SRC_HOST if host else SRC_DEVICE_COPY, stream)
+        if not host:
+            self._keep_update = (emb, mask, ts, row_scale)       # device sources are read when the stream gets there
+
+    def delete(self, slots, stream=None):
+        import torch
+        if stream is None:
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+        index_delete(self.handle, slots, stream)
+
+    def sync_updates(self):
+        index_sync_updates(self.handle)
+
+    def info(self):
+        return index_info(self.handle)
 
     def search(self, Q, filters, k, q_scale=None, workspace=None, want_raw=True):
         """Q: device tensor [B, m, d] (or [B, d]); filters: numpy records (host) or a device uint8/int32

@@ -3,9 +3,12 @@
 // (LiNR, arXiv 2407.13218: Sec. 4.2 -- the served model is the item embeddings plus
 // their filter attributes resident in GPU memory; Sec. 3.1 -- the search itself.)
 #include "linr_internal.h"
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
+#include <vector>
 
 static thread_local int g_last_hip = 0;
 static linr_tuning g_tuning = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -29,6 +32,7 @@ extern "C" const char* linr_strerror(int code)
     case LINR_E_WORKSPACE: return "workspace missing, misaligned or too small";
     case LINR_E_HIP: return "HIP runtime error";
     case LINR_E_FILTER: return "malformed filter";
+    case LINR_E_STATE: return "index is not in the state the call needs";
     default: return "unknown error";
     }
 }
@@ -72,8 +76,36 @@ extern "C" int linr_index_create(linr_index** out, uint64_t capacity, uint32_t d
     return LINR_OK;
 }
 
+// Host-side bookkeeping of live updates (Sec. 4 "Model Live Update").  `n` of the index is the published
+// high-water mark: searches on other streams use it, so it only rises once the update that wrote the new slots
+// has finished on the device; `n_pending` is the mark after the last enqueued update.
+struct linr_update_state {
+    std::mutex writer;          // one updater at a time (held for a whole upsert / delete call)
+    std::mutex mu;              // the fields below and linr_index::n (held for a few loads and stores)
+    uint64_t n_pending;
+    hipEvent_t done;            // recorded behind the last enqueued update
+    hipStream_t stream;         // ... on this stream
+    bool pending;
+    void* staging;              // device copy of an update batch (slots, and host-side rows / columns)
+    void* host_staging;         // its pinned host image (filled by the caller's thread, copied asynchronously)
+    uint64_t staging_bytes;
+};
+
+static void release_update_state(linr_index* ix)
+{
+    if (!ix->upd) return;
+    if (ix->upd->pending) (void)hipEventSynchronize(ix->upd->done);
+    (void)hipEventDestroy(ix->upd->done);
+    if (ix->upd->staging) (void)hipFree(ix->upd->staging);
+    if (ix->upd->host_staging) (void)hipHostFree(ix->upd->host_staging);
+    delete ix->upd;
+    ix->upd = nullptr;
+    ix->dead_bit = 0;
+}
+
 static void release_columns(linr_index* ix)
 {
+    release_update_state(ix);
     if (ix->owned) {
         if (ix->emb) (void)hipFree((void*)ix->emb);
         if (ix->row_scale) (void)hipFree((void*)ix->row_scale);
@@ -104,9 +136,30 @@ extern "C" int linr_index_destroy(linr_index* ix)
     return LINR_OK;
 }
 
+// The index as a search enqueued on stream `st` may see it.  Without live updates: the index itself.  With them:
+// a copy taken under the lock whose item count is the published high-water mark -- raised here if the last update
+// has finished, or taken from that update directly when the search runs on the update's own stream (stream order
+// then guarantees that the new slots are written before they are read; `same_stream_ok`).
+static const linr_index* view_for(const linr_index* ix, hipStream_t st, bool same_stream_ok, linr_index* snap)
+{
+    if (!ix || !ix->upd) return ix;
+    linr_index* mix = const_cast<linr_index*>(ix);      // index objects are heap objects of this library, never const
+    linr_update_state* u = ix->upd;
+    std::lock_guard<std::mutex> g(u->mu);
+    if (u->pending && hipEventQuery(u->done) == hipSuccess) {
+        mix->n = u->n_pending;
+        u->pending = false;
+    }
+    *snap = *mix;
+    if (u->pending && same_stream_ok && st == u->stream) snap->n = u->n_pending;
+    return snap;
+}
+
 extern "C" int linr_index_info(const linr_index* ix, uint64_t* n, uint32_t* d, int* dtype, int* has_ts, int* has_row_scale)
 {
     if (!ix) return LINR_E_NULL;
+    linr_index snap;
+    ix = view_for(ix, nullptr, false, &snap);
     if (n) *n = ix->n;
     if (d) *d = ix->d;
     if (dtype) *dtype = ix->dtype;
@@ -115,10 +168,13 @@ extern "C" int linr_index_info(const linr_index* ix, uint64_t* n, uint32_t* d, i
     return LINR_OK;
 }
 
-static int copy_column(const void** dst, const void* src, uint64_t bytes, int from_host)
+// library-owned columns are allocated for the whole capacity, so that live updates can add items in place
+// (Sec. 4: columns pre-allocated larger than the initial index)
+static int copy_column(const void** dst, const void* src, uint64_t bytes, uint64_t alloc_bytes, int from_host)
 {
     void* p = nullptr;
-    HIP_TRY(hipMalloc(&p, bytes ? bytes : 16));
+    if (alloc_bytes < bytes) alloc_bytes = bytes;
+    HIP_TRY(hipMalloc(&p, alloc_bytes ? alloc_bytes : 16));
     hipError_t e = hipMemcpy(p, src, bytes, from_host ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice);
     if (e != hipSuccess) { (void)hipFree(p); g_last_hip = (int)e; return LINR_E_HIP; }
     *dst = p;
@@ -146,10 +202,11 @@ static int load_common(linr_index* ix, int dtype, const void* emb, const float* 
     } else {
         int fh = src == LINR_SRC_HOST;
         ix->owned = 1;
-        rc = copy_column(&ix->emb, emb, n * ix->row_bytes, fh);
-        if (rc == LINR_OK) rc = copy_column((const void**)&ix->mask, mask, n * 4, fh);
-        if (rc == LINR_OK && ts) rc = copy_column((const void**)&ix->ts, ts, n * 4, fh);
-        if (rc == LINR_OK && row_scale) rc = copy_column((const void**)&ix->row_scale, row_scale, n * 4, fh);
+        const uint64_t cap = ix->capacity;
+        rc = copy_column(&ix->emb, emb, n * ix->row_bytes, cap * ix->row_bytes, fh);
+        if (rc == LINR_OK) rc = copy_column((const void**)&ix->mask, mask, n * 4, cap * 4, fh);
+        if (rc == LINR_OK && ts) rc = copy_column((const void**)&ix->ts, ts, n * 4, cap * 4, fh);
+        if (rc == LINR_OK && row_scale) rc = copy_column((const void**)&ix->row_scale, row_scale, n * 4, cap * 4, fh);
         if (rc != LINR_OK) release_columns(ix);
     }
     if (rc == LINR_OK && dtype == LINR_I8 && ix->row_scale) {
@@ -243,7 +300,7 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
     // the 16x16-tile kernels (its loop is bound by instruction issue, not by the matrix pipe).
     uint32_t qw = 0;
     if (!g_tuning.force_generic && !g_tuning.no_coop && g_tuning.wide_min_batch && B >= g_tuning.wide_min_batch &&
-        ix->row_bytes == p->ks * 64u)
+        ix->row_bytes == p->ks * 64u && !ix->dead_bit)  // (its per-item scale codes are not kept up to date by updates)
         for (uint32_t c = 1; c <= 4; c <<= 1) {
             if (!linr_wide_variant_exists(ix->dtype, p->vk, p->ks, m, c)) continue;
             qw = c;
@@ -376,6 +433,13 @@ extern "C" int linr_search_workspace_bytes(const linr_index* ix, uint32_t B, uin
     if (k == 0 || k > LINR_MAX_K) return LINR_E_K;
     if (ix->n == 0) return LINR_E_NOT_LOADED;
     if (B == 0) { *bytes = 256; return LINR_OK; }
+    linr_index full;
+    if (ix->dead_bit) {                                 // live updates: sized for a full index (the size grows with n)
+        full = *ix;
+        full.n = ix->capacity;
+        full.upd = nullptr;
+        ix = &full;
+    }
     linr_plan p;
     int rc = make_plan(ix, B, m, k, &p);
     if (rc != LINR_OK) return rc;
@@ -393,6 +457,8 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
 {
     if (n_stages) *n_stages = 0;
     if (!ix) return LINR_E_NULL;
+    linr_index snap;
+    ix = view_for(ix, (hipStream_t)hip_stream, true, &snap);
     if (k == 0 || k > LINR_MAX_K) return LINR_E_K;
     if (m == 0 || m > LINR_MAX_M) return LINR_E_SHAPE;
     if (ix->n == 0 || !ix->emb) return LINR_E_NOT_LOADED;
@@ -451,7 +517,7 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
 
         linr_scan_args sa;
         memset(&sa, 0, sizeof(sa));
-        sa.emb = ix->emb; sa.row_scale = ix->row_scale; sa.mask = ix->mask; sa.ts = ix->ts; sa.scale_stats = ix->scale_stats; sa.scale_code = ix->scale_code; sa.k_bits = ix->k_bits;
+        sa.emb = ix->emb; sa.row_scale = ix->row_scale; sa.mask = ix->mask; sa.ts = ix->ts; sa.scale_stats = ix->scale_stats; sa.scale_code = ix->scale_code; sa.k_bits = ix->k_bits; sa.dead_bit = ix->dead_bit;
         sa.n = ix->n; sa.row_bytes = ix->row_bytes;
         sa.Q = (const char*)Q + (uint64_t)b0 * m * ix->row_bytes; sa.B = Bp; sa.m = m;
         sa.filters = use_filt; sa.tau = tau; sa.cnt = cnt; sa.seg = seg;
@@ -566,7 +632,7 @@ extern "C" int linr_index_build_bits(linr_index* ix, const uint32_t* perm, const
     int rc = copy_small((void**)&ix->perm, perm, (uint64_t)ix->d * 4, fh);
     if (rc == LINR_OK) rc = copy_small((void**)&ix->signs, signs, ix->d, fh);
     if (rc == LINR_OK) {
-        hipError_t e = hipMalloc((void**)&ix->bits, ix->n * ix->bits_words * 8);
+        hipError_t e = hipMalloc((void**)&ix->bits, ix->capacity * ix->bits_words * 8);
         if (e == hipSuccess) e = linr_launch_sign_oporp(ix->dtype, ix->emb, ix->n, ix->d, ix->perm, ix->signs, k_bits, ix->bits, nullptr);
         if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
         if (e != hipSuccess) { g_last_hip = (int)e; rc = LINR_E_HIP; }
@@ -595,11 +661,14 @@ extern "C" int linr_quantize_queries(const linr_index* ix, const void* Q, uint32
 }
 
 // a view of the index whose "embeddings" are the codes: the search machinery then ranks by matching bits
-static int bits_view(const linr_index* ix, linr_index* v)
+static int bits_view(const linr_index* ix, hipStream_t st, linr_index* v)
 {
     if (!ix) return LINR_E_NULL;
+    linr_index snap;
+    ix = view_for(ix, st, true, &snap);
     if (ix->n == 0 || !ix->bits) return LINR_E_NOT_LOADED;
     *v = *ix;
+    v->upd = nullptr;                                   // the view is already the snapshot of this search
     v->dtype = LINR_BITS; v->emb = ix->bits; v->row_scale = nullptr; v->d = ix->k_bits; v->row_bytes = ix->bits_words * 8;
     v->scale_stats = nullptr; v->scale_code = nullptr;
     return LINR_OK;
@@ -609,7 +678,7 @@ extern "C" int linr_search_bits_workspace_bytes(const linr_index* ix, uint32_t B
 {
     if (!bytes) return LINR_E_NULL;
     linr_index v;
-    int rc = bits_view(ix, &v);
+    int rc = bits_view(ix, nullptr, &v);
     if (rc != LINR_OK) return rc;
     uint64_t inner = 0;
     rc = linr_search_workspace_bytes(&v, B, 1, T, &inner);
@@ -625,7 +694,7 @@ static int search_bits_impl(const linr_index* ix, const uint64_t* qbits, uint32_
 {
     if (n_stages) *n_stages = 0;
     linr_index v;
-    int rc = bits_view(ix, &v);
+    int rc = bits_view(ix, (hipStream_t)hip_stream, &v);
     if (rc != LINR_OK) return rc;
     if (B == 0) return LINR_OK;
     if (!out_matches) return LINR_E_NULL;
@@ -700,5 +769,172 @@ extern "C" int linr_search_two_stage(const linr_index* ix, const void* Q, uint32
     ra.dtype = ix->dtype; ra.emb = ix->emb; ra.d = ix->d; ra.row_bytes = ix->row_bytes; ra.Q = Q; ra.B = B; ra.T = T; ra.k = k;
     ra.cand_ids = ids1; ra.cand_counts = cnt1; ra.out_ids = out_ids; ra.out_scores = out_scores; ra.out_counts = out_counts;
     HIP_TRY(linr_launch_rescore(ra, (hipStream_t)hip_stream));
+    return LINR_OK;
+}
+
+// ---------------------------------------------------------------------------
+// live updates (Sec. 4 "Model Live Update"; their cost for concurrent searches: Sec. 5.3, Table 5)
+// ---------------------------------------------------------------------------
+#define LINR_DEAD_BIT 0x80000000u
+
+extern "C" int linr_index_enable_updates(linr_index* ix)
+{
+    if (!ix) return LINR_E_NULL;
+    if (ix->n == 0 || !ix->emb) return LINR_E_NOT_LOADED;
+    if (ix->upd) return LINR_OK;
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipSetDevice(ix->device));
+    int rc = LINR_OK;
+    // bit 31 of the masks becomes the library's "holds no item" mark: no resident item may carry it
+    uint32_t* acc = nullptr;
+    uint32_t host_acc = 0;
+    hipError_t e = hipMalloc((void**)&acc, 256);
+    if (e == hipSuccess) e = hipMemset(acc, 0, 4);
+    if (e == hipSuccess) e = linr_launch_mask_or(ix->mask, ix->n, acc, nullptr);
+    if (e == hipSuccess) e = hipMemcpy(&host_acc, acc, 4, hipMemcpyDeviceToHost);
+    if (acc) (void)hipFree(acc);
+    if (e != hipSuccess) { g_last_hip = (int)e; rc = LINR_E_HIP; }
+    else if (host_acc & LINR_DEAD_BIT) rc = LINR_E_FILTER;
+    if (rc == LINR_OK) {
+        linr_update_state* u = new (std::nothrow) linr_update_state();
+        if (!u) rc = LINR_E_HIP;
+        else {
+            u->n_pending = ix->n; u->stream = nullptr; u->pending = false; u->staging = nullptr; u->host_staging = nullptr; u->staging_bytes = 0;
+            e = hipEventCreateWithFlags(&u->done, hipEventDisableTiming);
+            if (e != hipSuccess) { g_last_hip = (int)e; rc = LINR_E_HIP; delete u; }
+            else { ix->upd = u; ix->dead_bit = LINR_DEAD_BIT; }
+        }
+    }
+    (void)hipSetDevice(dev);
+    return rc;
+}
+
+// room for `bytes` in the staging buffer; waits for the update that may still read the old contents
+static int staging_reserve(linr_update_state* u, uint64_t bytes)
+{
+    if (u->pending) HIP_TRY(hipEventSynchronize(u->done));
+    if (bytes > u->staging_bytes) {
+        if (u->staging) (void)hipFree(u->staging);
+        if (u->host_staging) (void)hipHostFree(u->host_staging);
+        u->staging = nullptr; u->host_staging = nullptr; u->staging_bytes = 0;
+        const uint64_t want = align_up(bytes < 65536 ? 65536 : bytes, 65536);
+        HIP_TRY(hipMalloc(&u->staging, want));
+        HIP_TRY(hipHostMalloc(&u->host_staging, want, hipHostMallocDefault));
+        u->staging_bytes = want;
+    }
+    return LINR_OK;
+}
+
+static int update_impl(linr_index* ix, const uint32_t* slots, uint32_t count, const void* emb, const float* row_scale,
+                       const uint32_t* mask, const uint32_t* ts, int src, hipStream_t st, bool is_delete)
+{
+    if (!ix) return LINR_E_NULL;
+    linr_update_state* u = ix->upd;
+    if (!u) return LINR_E_STATE;
+    if (count == 0) return LINR_OK;
+    if (!slots) return LINR_E_NULL;
+    if (!is_delete) {
+        if (!emb || !mask || (ix->row_scale && !row_scale) || (ix->ts && !ts)) return LINR_E_NULL;
+        if (src != LINR_SRC_HOST && src != LINR_SRC_DEVICE_COPY && src != LINR_SRC_DEVICE_BORROW) return LINR_E_SHAPE;
+    }
+    std::lock_guard<std::mutex> writer(u->writer);
+    uint64_t mark;
+    {
+        std::lock_guard<std::mutex> g(u->mu);
+        mark = u->pending ? u->n_pending : ix->n;
+    }
+    uint64_t top = 0;
+    for (uint32_t i = 0; i < count; ++i) {
+        if (slots[i] >= (is_delete ? mark : ix->capacity)) return LINR_E_CAPACITY;
+        if ((uint64_t)slots[i] + 1 > top) top = (uint64_t)slots[i] + 1;
+    }
+    if (!is_delete) {                                   // two writers of one slot in one launch would tear its row
+        std::vector<uint32_t> sorted(slots, slots + count);
+        std::sort(sorted.begin(), sorted.end());
+        if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end()) return LINR_E_SHAPE;
+    }
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipSetDevice(ix->device));
+    auto body = [&]() -> int {
+        const bool host_rows = !is_delete && src == LINR_SRC_HOST;
+        const uint64_t o_slots = 0;
+        const uint64_t o_emb = align_up((uint64_t)count * 4, 256);
+        const uint64_t o_mask = o_emb + (host_rows ? align_up((uint64_t)count * ix->row_bytes, 256) : 0);
+        const uint64_t o_scale = o_mask + (host_rows ? align_up((uint64_t)count * 4, 256) : 0);
+        const uint64_t o_ts = o_scale + (host_rows && ix->row_scale ? align_up((uint64_t)count * 4, 256) : 0);
+        const uint64_t total = o_ts + (host_rows && ix->ts ? align_up((uint64_t)count * 4, 256) : 0);
+        int rc = staging_reserve(u, total);
+        if (rc != LINR_OK) return rc;
+        char* sg = (char*)u->staging;
+        char* hs = (char*)u->host_staging;
+        memcpy(hs + o_slots, slots, (size_t)count * 4);
+        if (host_rows) {
+            memcpy(hs + o_emb, emb, (size_t)count * ix->row_bytes);
+            memcpy(hs + o_mask, mask, (size_t)count * 4);
+            if (ix->row_scale) memcpy(hs + o_scale, row_scale, (size_t)count * 4);
+            if (ix->ts) memcpy(hs + o_ts, ts, (size_t)count * 4);
+        }
+        HIP_TRY(hipMemcpyAsync(sg, hs, (size_t)total, hipMemcpyHostToDevice, st));
+        const uint32_t* d_slots = (const uint32_t*)(sg + o_slots);
+        if (is_delete) {
+            HIP_TRY(linr_launch_tombstone((uint32_t*)ix->mask, d_slots, count, ix->dead_bit, st));
+        } else {
+            linr_upsert_args a;
+            memset(&a, 0, sizeof(a));
+            a.slots = d_slots; a.count = count; a.row_bytes = ix->row_bytes; a.dead_bit = ix->dead_bit;
+            a.emb = (void*)ix->emb; a.row_scale = (float*)ix->row_scale; a.mask = (uint32_t*)ix->mask; a.ts = (uint32_t*)ix->ts;
+            if (host_rows) {
+                a.src_emb = sg + o_emb; a.src_mask = (const uint32_t*)(sg + o_mask);
+                a.src_scale = (const float*)(sg + o_scale); a.src_ts = (const uint32_t*)(sg + o_ts);
+            } else {
+                a.src_emb = emb; a.src_mask = mask; a.src_scale = row_scale; a.src_ts = ts;
+            }
+            // slots between the old mark and the new one that this batch does not write hold no item
+            if (top > mark) HIP_TRY(linr_launch_fill_u32((uint32_t*)ix->mask + mark, top - mark, ix->dead_bit, st));
+            HIP_TRY(linr_launch_upsert(a, st));
+            if (ix->bits && ix->dtype != LINR_BITS)     // the quantised search's codes follow the rows
+                HIP_TRY(linr_launch_sign_oporp_scatter(ix->dtype, a.src_emb, count, ix->d, ix->perm, ix->signs, ix->k_bits,
+                                                       ix->bits, d_slots, st));
+            HIP_TRY(linr_launch_upsert_masks(a, st));   // last: the mask makes the slot visible
+        }
+        HIP_TRY(hipEventRecord(u->done, st));
+        std::lock_guard<std::mutex> g(u->mu);
+        u->n_pending = top > mark ? top : mark;
+        u->stream = st;
+        u->pending = true;
+        return LINR_OK;
+    };
+    const int rc = body();
+    (void)hipSetDevice(dev);
+    return rc;
+}
+
+extern "C" int linr_index_upsert(linr_index* ix, const uint32_t* slots, uint32_t count, const void* emb, const float* row_scale,
+                                 const uint32_t* mask, const uint32_t* ts, int src, void* hip_stream)
+{
+    return update_impl(ix, slots, count, emb, row_scale, mask, ts, src, (hipStream_t)hip_stream, false);
+}
+
+extern "C" int linr_index_delete(linr_index* ix, const uint32_t* slots, uint32_t count, void* hip_stream)
+{
+    return update_impl(ix, slots, count, nullptr, nullptr, nullptr, nullptr, LINR_SRC_HOST, (hipStream_t)hip_stream, true);
+}
+
+extern "C" int linr_index_sync_updates(linr_index* ix)
+{
+    if (!ix) return LINR_E_NULL;
+    linr_update_state* u = ix->upd;
+    if (!u) return LINR_E_STATE;
+    std::lock_guard<std::mutex> writer(u->writer);
+    bool pending;
+    {
+        std::lock_guard<std::mutex> g(u->mu);
+        pending = u->pending;
+    }
+    if (pending) HIP_TRY(hipEventSynchronize(u->done));
+    std::lock_guard<std::mutex> g(u->mu);
+    if (u->pending) { ix->n = u->n_pending; u->pending = false; }
     return LINR_OK;
 }

@@ -38,6 +38,10 @@ struct linr_index {
     uint32_t* perm;
     int8_t* signs;
     int num_cu;
+    // live updates: the mask bit that marks a slot as holding no item (0 until updates are enabled) and the
+    // host-side bookkeeping of updates in flight (linr_api.cpp)
+    uint32_t dead_bit;
+    struct linr_update_state* upd;
 };
 
 // Launch plan of one search pass (at most max_batch queries).
@@ -84,6 +88,7 @@ struct linr_scan_args {
     uint32_t stride;            // chunk stride of this sweep
     uint32_t skip_mod;          // level indices that are multiples of this were visited by earlier sweeps (0: none)
     uint32_t k_bits;            // bit-matching kernel: bits per code
+    uint32_t dead_bit;          // mask bit no feasible item may carry (live updates), or 0
 };
 
 struct linr_merge_args {
@@ -108,6 +113,22 @@ hipError_t linr_launch_merge(const linr_merge_args& a, hipStream_t s);
 // quantised search helpers: codes of `n` rows (fp32 / bf16, row-major [n][d]); rescoring of T candidates per query
 hipError_t linr_launch_sign_oporp(int dtype, const void* x, uint64_t n, uint32_t d, const uint32_t* perm, const int8_t* signs,
                                   uint32_t k_bits, uint64_t* out, hipStream_t s);
+// codes of rows written by an update: row r of x goes to out[scatter[r]] (scatter == nullptr: out[r])
+hipError_t linr_launch_sign_oporp_scatter(int dtype, const void* x, uint64_t n, uint32_t d, const uint32_t* perm,
+                                          const int8_t* signs, uint32_t k_bits, uint64_t* out, const uint32_t* scatter,
+                                          hipStream_t s);
+// live updates: row / side-column scatter into slots, tombstones, mask fill, OR over all masks
+struct linr_upsert_args {
+    const uint32_t* slots; uint32_t count; uint32_t row_bytes;       // row_bytes: a multiple of 8
+    const void* src_emb; const float* src_scale; const uint32_t* src_mask; const uint32_t* src_ts;
+    void* emb; float* row_scale; uint32_t* mask; uint32_t* ts;
+    uint32_t dead_bit;
+};
+hipError_t linr_launch_upsert(const linr_upsert_args& a, hipStream_t s);          // rows, row scales, timestamps
+hipError_t linr_launch_upsert_masks(const linr_upsert_args& a, hipStream_t s);    // masks (launched last)
+hipError_t linr_launch_tombstone(uint32_t* mask, const uint32_t* slots, uint32_t count, uint32_t dead_bit, hipStream_t s);
+hipError_t linr_launch_fill_u32(uint32_t* dst, uint64_t n, uint32_t value, hipStream_t s);
+hipError_t linr_launch_mask_or(const uint32_t* mask, uint64_t n, uint32_t* out, hipStream_t s);   // *out |= OR of mask[0..n)
 struct linr_rescore_args {
     int dtype; const void* emb; uint32_t d; uint32_t row_bytes; const void* Q; uint32_t B, T, k;
     const uint32_t* cand_ids; const uint32_t* cand_counts;

@@ -382,9 +382,10 @@ __device__ __forceinline__ void load_query_side(const QSide& qs, uint32_t ql, ui
         linr_filter F;
         if (qi < A.B) F = A.filters[qi];
         else { F.all_bits = 0xFFFFFFFFu; F.none_bits = 0xFFFFFFFFu; F.n_any = 0; F.ts_min = 1; F.ts_max = 0; }
-        const bool impossible = (F.all_bits & F.none_bits) != 0u;       // a bit both required and forbidden
+        const uint32_t none = F.none_bits | A.dead_bit;                 // a slot marked as empty fails every filter
+        const bool impossible = (F.all_bits & none) != 0u;              // a bit both required and forbidden
         ((uint32_t*)qs.fall)[ql] = impossible ? 0xFFFFFFFFu : F.all_bits;
-        ((uint32_t*)qs.fnone)[ql] = impossible ? 0u : (F.all_bits | F.none_bits);
+        ((uint32_t*)qs.fnone)[ql] = impossible ? 0u : (F.all_bits | none);
         ((uint32_t*)qs.tsmin)[ql] = F.ts_min;
         ((uint32_t*)qs.tsmax)[ql] = F.ts_max;
         ((uint32_t*)qs.fflag)[ql] = F.n_any ? 1u : 0u;
@@ -1718,7 +1719,7 @@ __global__ void __launch_bounds__(64 * WPB, W <= 2 ? 4 : 2) scan_kernel_bits(lin
 // Sign-OPORP codes of n rows: thread (row, word) sums its 64 bins in double precision, t ascending, and
 // sets bit j%64 of word j/64 for a strictly positive bin sum (Sec. 3.2; construction in the header).
 __global__ void __launch_bounds__(256) sign_oporp_kernel(int dtype, const void* x, u64 n, uint32_t d, const uint32_t* perm,
-                                                         const int8_t* signs, uint32_t k_bits, u64* out)
+                                                         const int8_t* signs, uint32_t k_bits, u64* out, const uint32_t* scatter)
 {
     const uint32_t Wn = (k_bits + 63) / 64, L = d / k_bits;
     const u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1739,7 +1740,49 @@ __global__ void __launch_bounds__(256) sign_oporp_kernel(int dtype, const void* 
         }
         if (sum > 0.0) word |= 1ull << jj;
     }
-    out[t] = word;
+    out[scatter ? (u64)scatter[row] * Wn + w : t] = word;
+}
+
+// ---------------------------------------------------------------------------
+// live updates (LiNR Sec. 4 "Model Live Update"): rows and side columns of `count` slots, 8 bytes per thread
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) upsert_kernel(linr_upsert_args A)
+{
+    const uint32_t pieces = A.row_bytes / 8;
+    const u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (u64)A.count * pieces) return;
+    const uint32_t e = (uint32_t)(t / pieces), piece = (uint32_t)(t % pieces);
+    const u64 slot = A.slots[e];
+    ((u64*)A.emb)[slot * pieces + piece] = ((const u64*)A.src_emb)[(u64)e * pieces + piece];
+    if (piece == 0) {
+        if (A.row_scale) A.row_scale[slot] = A.src_scale[e];
+        if (A.ts) A.ts[slot] = A.src_ts[e];
+    }
+}
+
+// ... and, in a launch of its own behind the rows (and their codes), the masks: the word that makes a slot visible
+__global__ void __launch_bounds__(256) upsert_mask_kernel(linr_upsert_args A)
+{
+    const uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < A.count) A.mask[A.slots[e]] = A.src_mask[e] & ~A.dead_bit;
+}
+
+__global__ void __launch_bounds__(256) tombstone_kernel(uint32_t* mask, const uint32_t* slots, uint32_t count, uint32_t dead_bit)
+{
+    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < count) atomicOr(mask + slots[t], dead_bit);
+}
+
+__global__ void __launch_bounds__(256) fill_u32_kernel(uint32_t* dst, u64 n, uint32_t value)
+{
+    for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (u64)gridDim.x * blockDim.x) dst[i] = value;
+}
+
+__global__ void __launch_bounds__(256) mask_or_kernel(const uint32_t* mask, u64 n, uint32_t* out)
+{
+    uint32_t acc = 0;
+    for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (u64)gridDim.x * blockDim.x) acc |= mask[i];
+    if (acc) atomicOr(out, acc);
 }
 
 // Second stage of the two-stage search: one workgroup per query scores its T candidates with the
@@ -2363,13 +2406,59 @@ static hipError_t bits_dispatch(uint32_t words, ScanAct& act)
     return hipErrorInvalidDeviceFunction;
 }
 
-hipError_t linr_launch_sign_oporp(int dtype, const void* x, uint64_t n, uint32_t d, const uint32_t* perm, const int8_t* signs,
-                                  uint32_t k_bits, uint64_t* out, hipStream_t s)
+hipError_t linr_launch_sign_oporp_scatter(int dtype, const void* x, uint64_t n, uint32_t d, const uint32_t* perm,
+                                          const int8_t* signs, uint32_t k_bits, uint64_t* out, const uint32_t* scatter,
+                                          hipStream_t s)
 {
     const uint64_t threads = n * ((k_bits + 63) / 64);
     if (threads == 0) return hipSuccess;
     hipLaunchKernelGGL(sign_oporp_kernel, dim3((uint32_t)((threads + 255) / 256)), dim3(256), 0, s, dtype, x, (u64)n, d, perm, signs,
-                       k_bits, (u64*)out);
+                       k_bits, (u64*)out, scatter);
+    return hipGetLastError();
+}
+
+hipError_t linr_launch_sign_oporp(int dtype, const void* x, uint64_t n, uint32_t d, const uint32_t* perm, const int8_t* signs,
+                                  uint32_t k_bits, uint64_t* out, hipStream_t s)
+{
+    return linr_launch_sign_oporp_scatter(dtype, x, n, d, perm, signs, k_bits, out, nullptr, s);
+}
+
+hipError_t linr_launch_upsert(const linr_upsert_args& a, hipStream_t s)
+{
+    if (a.count == 0) return hipSuccess;
+    if (a.row_bytes == 0 || a.row_bytes % 8 != 0) return hipErrorInvalidValue;
+    const uint64_t threads = (uint64_t)a.count * (a.row_bytes / 8);
+    hipLaunchKernelGGL(upsert_kernel, dim3((uint32_t)((threads + 255) / 256)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t linr_launch_upsert_masks(const linr_upsert_args& a, hipStream_t s)
+{
+    if (a.count == 0) return hipSuccess;
+    hipLaunchKernelGGL(upsert_mask_kernel, dim3((a.count + 255) / 256), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t linr_launch_tombstone(uint32_t* mask, const uint32_t* slots, uint32_t count, uint32_t dead_bit, hipStream_t s)
+{
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(tombstone_kernel, dim3((count + 255) / 256), dim3(256), 0, s, mask, slots, count, dead_bit);
+    return hipGetLastError();
+}
+
+hipError_t linr_launch_fill_u32(uint32_t* dst, uint64_t n, uint32_t value, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    const uint64_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((uint32_t)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, s, dst, (u64)n, value);
+    return hipGetLastError();
+}
+
+hipError_t linr_launch_mask_or(const uint32_t* mask, uint64_t n, uint32_t* out, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    const uint64_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(mask_or_kernel, dim3((uint32_t)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, s, mask, (u64)n, out);
     return hipGetLastError();
 }
 
