@@ -9,7 +9,8 @@ of one query batch.  The headline is the small-batch, HBM-bound regime (B = 32, 
 rate); a short sweep over B in {1, 32, 256, 1024} and pass rates {50 %, 5 %, 0.1 %} is
 reported in the same JSON line under "sweep".  A second leg, reported under "quantised", runs the
 1-bit search of Sec. 3.2 (64-bit Sign-OPORP codes of the same items, the paper's billion-member
-setting of Sec. 5.3) for B in {1, 32}, with its own roofline and oracle timing.
+setting of Sec. 5.3) for B in {1, 32}, with its own roofline and oracle timing; a third, "live_update",
+measures search latency next to concurrent upserts and deletes (Sec. 5.3, Table 5).
 
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
@@ -164,6 +165,85 @@ def quantised_leg(L, S, base, index_cols, N, k, args, dev):
     return out
 
 
+def live_update_leg(L, S, args, dev):
+    """Search latency next to concurrent updates (Sec. 5.3 "Impact of Live Model Update on Inference", Table 5: requests
+    issued serially, batch 1 and 5, 0 / 300 / 600 updates per second; here also 20 000 per second in batches of 100).
+    Index: config 2 at full size (1e7 x d128 bf16, 25 % pass rate, k = 1000) with room for 400 000 more items.  An
+    update = one upsert into a fresh slot + one delete of an old slot, issued by a second host thread on its own stream."""
+    import threading
+    import numpy as np
+    import torch
+    w = S.config2(device=dev, p=0.5)
+    n, d, k = w["emb"].shape[0], 128, 1000
+    cap = n + 400_000
+    ix = L.Index(cap, d, S.BF16, 0)
+    ix.load(w["emb"], w["mask"] & 0x7FFFFFFF, src=L.SRC_DEVICE_COPY)      # bit 31 belongs to the library on such an index
+    w["filters"]["all_bits"] &= 0x7FFFFFFF
+    del w["emb"]
+    ix.enable_updates()
+    rng = np.random.default_rng(0)
+    pool = 4096                                            # update payloads, reused round-robin
+    rows = (rng.standard_normal((pool, d)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    masks = rng.integers(0, 1 << 31, pool, dtype=np.uint32)
+    side = torch.cuda.Stream()
+    stream = torch.cuda.current_stream().cuda_stream
+    state = {"mark": n}
+    out = []
+    for rate, per_call in ((0, 1), (300, 1), (600, 1), (20000, 100)):
+        for B in (1, 5):
+            Q = w["Q"][:B].contiguous()
+            filt = torch.from_numpy(np.ascontiguousarray(w["filters"][:B]).view(np.uint8).copy()).to(dev)
+            nbytes = ix.workspace_bytes(B, 1, k)
+            ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+            ids = torch.empty((B, k), dtype=torch.int32, device=dev); sc = torch.empty((B, k), dtype=torch.float32, device=dev)
+            cnt = torch.empty((B,), dtype=torch.int32, device=dev)
+            stop = threading.Event()
+            done = {"updates": 0}
+
+            def updater():
+                t0 = time.perf_counter()
+                while not stop.is_set():
+                    due = int((time.perf_counter() - t0) * rate)
+                    if done["updates"] + per_call > due or state["mark"] + per_call > cap:
+                        time.sleep(0.0005)
+                        continue
+                    j = done["updates"] % (pool - per_call)
+                    slots = np.arange(state["mark"], state["mark"] + per_call, dtype=np.uint32)
+                    ix.upsert(slots, rows[j:j + per_call], masks[j:j + per_call], stream=side.cuda_stream)
+                    ix.delete(rng.integers(0, n, per_call).astype(np.uint32), stream=side.cuda_stream)
+                    state["mark"] += per_call
+                    done["updates"] += per_call
+            th = threading.Thread(target=updater) if rate else None
+            for _ in range(5):
+                L.search_filtered(ix.handle, Q, None, B, 1, filt, k, ids, sc, None, cnt, ws, nbytes, stream, L.FILTERS_ON_DEVICE)
+            torch.cuda.synchronize()
+            if th:
+                th.start()
+            lat = []
+            t_end = time.perf_counter() + 1.5
+            while time.perf_counter() < t_end:
+                t0 = time.perf_counter()
+                L.search_filtered(ix.handle, Q, None, B, 1, filt, k, ids, sc, None, cnt, ws, nbytes, stream, L.FILTERS_ON_DEVICE)
+                torch.cuda.current_stream().synchronize()
+                lat.append((time.perf_counter() - t0) * 1e3)
+            stop.set()
+            if th:
+                th.join()
+            ix.sync_updates()
+            lat = np.array(lat)
+            r = dict(updates_per_s=rate, batch=B, qps=len(lat) / (lat.sum() / 1e3), avg_ms=float(lat.mean()),
+                     p95_ms=float(np.percentile(lat, 95)), searches=len(lat), updates_applied=done["updates"],
+                     items=ix.info()["n"])
+            out.append({key: (round(v, 4) if isinstance(v, float) else v) for key, v in r.items()})
+            log(f"  live update {rate:6d}/s batch {B}: {r['qps']:.0f} QPS, avg {r['avg_ms']:.3f} ms, p95 {r['p95_ms']:.3f} ms "
+                f"({done['updates']} updates applied)")
+            del ws
+    ix.close()
+    return {"workload": f"config 2 at full size: {n} x d128 bf16 + mask, 25 % pass rate, k = {k}; capacity {cap}; an update = "
+                        "upsert of a fresh slot + delete of an old one, from a second thread on its own stream; searches "
+                        "issued serially, host wall-clock latency per search", "rows": out}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -176,6 +256,7 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-quantised", action="store_true", help="skip the 1-bit (Sign-OPORP) search leg")
+    ap.add_argument("--no-live-update", action="store_true", help="skip the search-latency-under-updates leg")
     ap.add_argument("--code-bits", type=int, default=64, help="bits per Sign-OPORP code of the quantised leg (divides 64)")
     ap.add_argument("--sweep-steps", type=int, default=5)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -265,6 +346,11 @@ def main():
     if not args.no_quantised:
         quant = quantised_leg(L, S, base, index_cols, N, k, args, dev)
 
+    live = None
+    if not args.no_live_update:
+        log("live updates: search latency next to concurrent upserts / deletes")
+        live = live_update_leg(L, S, args, dev)
+
     cpu = None
     if not args.no_cpu:
         import oracle
@@ -304,6 +390,7 @@ def main():
         "stage_ms": {"largest_sweep": head["largest_sweep_ms"], "all_sweeps": head["all_sweeps_ms"], "merges": head["merges_ms"]},
         "sweep": sweep,
         "quantised": quant,
+        "live_update": live,
     }
     print(json.dumps(line), flush=True)
 
