@@ -21,17 +21,18 @@ FILTER_DTYPE = np.dtype([
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "linr_oracle.c")
 _SRC_BITS = os.path.join(_HERE, "linr_oracle_bits.c")
+_SRC_CLAUSES = os.path.join(_HERE, "linr_oracle_clauses.c")
 _LIB = os.path.join(_HERE, "liblinr_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (no fast-math, no FMA contraction)."""
-    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_BITS))
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_BITS), os.path.getmtime(_SRC_CLAUSES))
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         tmp = _LIB + f".tmp{os.getpid()}"
         subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
-                               "-o", tmp, _SRC, _SRC_BITS, "-lpthread", "-lm"])
+                               "-o", tmp, _SRC, _SRC_BITS, _SRC_CLAUSES, "-lpthread", "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -57,6 +58,8 @@ def _load():
         lib.linr_oracle_bit_matches.argtypes = [vp, vp, u32, u32]
         lib.linr_oracle_bits_search.restype = i32
         lib.linr_oracle_bits_search.argtypes = [vp, u32, u32, vp, vp, u64, u64, vp, u32, vp, u32, vp, vp, vp]
+        lib.linr_oracle_clause_feasible.restype = i32
+        lib.linr_oracle_clause_feasible.argtypes = [vp, u32, vp, u32, u64, vp, vp, u32, vp]
         _lib = lib
     return _lib
 
@@ -200,3 +203,40 @@ def two_stage(dtype, emb, mask, Q, filters, perm, signs, k_bits, T, k, ts=None):
         kk = len(order)
         out_ids[b, :kk] = cand[order].astype(np.uint32); out_sc[b, :kk] = rank[order].astype(np.float32); out_cnt[b] = kk
     return out_ids, out_sc, out_cnt
+
+
+# ---------------------------------------------------------------------------
+# attribute matching over clause lists (Sec. 3.1.1; the benchmark's representation, Sec. 5.3)
+# ---------------------------------------------------------------------------
+def clause_feasible(values, counts, q_values_row, q_counts_row, reverse):
+    """0/1 vector over the n items for ONE query.  values [n, row_width] u64, counts [n, C] u8 (lists back to back,
+    clause 0 first); the query's lists in the same layout; bit c of `reverse` marks clause c as a reverse clause."""
+    lib = _load()
+    values = _c(values, np.uint64); counts = _c(counts, np.uint8)
+    qv = _c(np.atleast_1d(q_values_row), np.uint64); qc = _c(q_counts_row, np.uint8)
+    n, row_width = values.shape
+    C = counts.shape[1]
+    assert counts.shape == (n, C) and qc.shape == (C,) and int(qc.sum()) <= qv.size
+    out = np.empty(n, np.uint8)
+    if lib.linr_oracle_clause_feasible(_ptr(values), row_width, _ptr(counts), C, n, _ptr(qv), _ptr(qc), int(reverse), _ptr(out)) != 0:
+        raise ValueError("an item's counts exceed the row width")
+    return out
+
+
+def clause_search(dtype, emb, values, counts, Q, q_values, q_counts, reverse, k, row_scale=None, q_scale=None, nthreads=1):
+    """Exhaustive top-k among the items that satisfy every clause of the query: for each query the feasibility vector
+    above, then the exhaustive oracle restricted to the feasible items (feasibility handed over as a one-bit mask)."""
+    if Q.ndim == 2:
+        Q = Q[:, None, :]
+    B = Q.shape[0]
+    ids = np.empty((B, k), np.uint32); sc = np.empty((B, k), np.float32)
+    raw = np.empty((B, k), np.int32); cnt = np.empty(B, np.uint32)
+    f = np.zeros(1, FILTER_DTYPE)
+    f["all_bits"] = 1
+    f["ts_max"] = 0xFFFFFFFF
+    for b in range(B):
+        feas = clause_feasible(values, counts, q_values[b], q_counts[b], reverse).astype(np.uint32)
+        i1, s1, r1, c1 = search(dtype, emb, feas, Q[b:b + 1], f, k, row_scale=row_scale,
+                                q_scale=None if q_scale is None else q_scale[b:b + 1], nthreads=nthreads)
+        ids[b], sc[b], raw[b], cnt[b] = i1[0], s1[0], r1[0], c1[0]
+    return ids, sc, raw, cnt
