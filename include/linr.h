@@ -195,6 +195,41 @@ int linr_search_two_stage(const linr_index*, const void* Q, uint32_t B, const li
                           void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags);
 
 /*
+ * Attribute matching over clause lists (Sec. 3.1.1 "KNN with Similarity Masking" and its
+ * figure; the datasets of Sec. 5.3 carry one 64-bit attribute per clause).  There are
+ * n_clauses clauses; item i lists counts[i][c] attributes (64-bit ids) for clause c, all
+ * lists of an item back to back, clause 0 first, in row i of values [n][row_width] (entries
+ * behind the last list are ignored; lists need not be sorted, the kernel stops at the
+ * first match anyway).  A query carries lists in the same layout.  A clause is satisfied
+ * when the two lists share an attribute -- a REVERSE clause (bit c of `reverse`) when they
+ * share none -- and an item is feasible when every clause is; a clause for which the query
+ * lists nothing places no constraint.  This predicate replaces the bitmask filter of
+ * linr_search_filtered; scoring, ranking, ties, outputs and errors are the same.
+ *
+ * linr_index_load_clauses  attaches clause columns to a loaded fp32 / bf16 / int8 index:
+ *     values [n][row_width] uint64, counts [n][n_clauses] uint8, host or device per `src`
+ *     (always copied); n must equal the number of resident items (LINR_E_CAPACITY).
+ *     Limits: n_clauses <= LINR_MAX_CLAUSES, row_width <= LINR_MAX_CLAUSE_ROW.
+ * linr_search_clauses  q_values device [B][q_width] uint64, q_counts device [B][n_clauses]
+ *     uint8, q_width <= LINR_MAX_QUERY_ROW.  Queries are answered in groups of 32: one pass
+ *     over the clause columns writes, per item, a word whose bit b says "feasible for query
+ *     b of the group", and the exhaustive search then runs with that bit as the predicate.
+ *     On an index with live updates, deleted slots are infeasible; items upserted after
+ *     linr_index_load_clauses have no lists: LINR_E_STATE until the columns are loaded again.
+ * Workspace from linr_search_clauses_workspace_bytes.  LINR_E_STATE without clause columns.
+ */
+#define LINR_MAX_CLAUSES 8
+#define LINR_MAX_CLAUSE_ROW 32
+#define LINR_MAX_QUERY_ROW 64
+int linr_index_load_clauses(linr_index*, const uint64_t* values, const uint8_t* counts, uint32_t n_clauses,
+                            uint32_t row_width, uint32_t reverse, uint64_t n, int src);
+int linr_search_clauses_workspace_bytes(const linr_index*, uint32_t B, uint32_t m, uint32_t k, uint64_t* bytes);
+int linr_search_clauses(const linr_index*, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                        const uint64_t* q_values, const uint8_t* q_counts, uint32_t q_width, uint32_t k,
+                        uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
+                        void* workspace, uint64_t workspace_bytes, void* hip_stream);
+
+/*
  * Live updates (Sec. 4 "Model Live Update": Upsert and Delete calls on columns that are
  * pre-allocated larger than the initial index, a high-water mark for the working set, and
  * updates that run next to searches; their cost for searches is the subject of Sec. 5.3,
@@ -281,7 +316,7 @@ int linr_set_tuning(const linr_tuning*);
  * and stage_items[s] the number of items a scan stage visits.
  */
 #define LINR_MAX_STAGES 64
-enum { LINR_STAGE_INIT = 0, LINR_STAGE_SCAN = 1, LINR_STAGE_MERGE = 2 };
+enum { LINR_STAGE_INIT = 0, LINR_STAGE_SCAN = 1, LINR_STAGE_MERGE = 2, LINR_STAGE_FILTER = 3 };
 int linr_search_filtered_timed(const linr_index*, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
                          const linr_filter* filters, uint32_t k,
                          uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
@@ -292,6 +327,12 @@ int linr_search_bits_timed(const linr_index*, const uint64_t* qbits, uint32_t B,
                            uint32_t* out_ids, int32_t* out_matches, uint32_t* out_counts,
                            void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags,
                            void** events, uint32_t* n_stages, uint32_t* kinds, uint64_t* stage_items);
+/* ... and for linr_search_clauses (LINR_STAGE_FILTER = the pass over the clause columns) */
+int linr_search_clauses_timed(const linr_index*, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                              const uint64_t* q_values, const uint8_t* q_counts, uint32_t q_width, uint32_t k,
+                              uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
+                              void* workspace, uint64_t workspace_bytes, void* hip_stream,
+                              void** events, uint32_t* n_stages, uint32_t* kinds, uint64_t* stage_items);
 /* hipEvent_t helpers for callers without direct access to the HIP runtime (host arrays) */
 int linr_events_create(void** events, uint32_t n);
 int linr_events_destroy(void** events, uint32_t n);

@@ -11,5 +11,6 @@ from .binding import (  # noqa: F401
     index_build_bits, index_load_bits, quantize_queries, search_bits_workspace_bytes, search_bits, search_bits_timed,
     search_two_stage_workspace_bytes, search_two_stage,
     index_enable_updates, index_upsert, index_delete, index_sync_updates,
+    index_load_clauses, search_clauses_workspace_bytes, search_clauses, search_clauses_timed,
     Index,
 )

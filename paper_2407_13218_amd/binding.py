@@ -18,7 +18,7 @@ MAX_M = 8
 SRC_HOST, SRC_DEVICE_COPY, SRC_DEVICE_BORROW = 0, 1, 2
 FILTERS_ON_DEVICE, FILTERS_ON_HOST = 0, 1
 MAX_STAGES = 64
-STAGE_NAMES = {0: "init", 1: "scan", 2: "merge"}
+STAGE_NAMES = {0: "init", 1: "scan", 2: "merge", 3: "filter"}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "liblinr.so")
@@ -33,6 +33,7 @@ EXPORTS = [
     "linr_index_build_bits", "linr_index_load_bits", "linr_quantize_queries", "linr_search_bits_workspace_bytes",
     "linr_search_bits", "linr_search_two_stage_workspace_bytes", "linr_search_two_stage", "linr_search_bits_timed",
     "linr_index_enable_updates", "linr_index_upsert", "linr_index_delete", "linr_index_sync_updates",
+    "linr_index_load_clauses", "linr_search_clauses_workspace_bytes", "linr_search_clauses", "linr_search_clauses_timed",
 ]
 
 
@@ -104,6 +105,14 @@ def load_library():
     lib.linr_search_bits_workspace_bytes.argtypes = [vp, u32, u32, C.POINTER(u64)]
     lib.linr_search_bits.restype = i32
     lib.linr_search_bits.argtypes = [vp, vp, u32, vp, u32, vp, vp, vp, vp, u64, vp, u32]
+    lib.linr_index_load_clauses.restype = i32
+    lib.linr_index_load_clauses.argtypes = [vp, vp, vp, u32, u32, u32, u64, i32]
+    lib.linr_search_clauses_workspace_bytes.restype = i32
+    lib.linr_search_clauses_workspace_bytes.argtypes = [vp, u32, u32, u32, C.POINTER(u64)]
+    lib.linr_search_clauses.restype = i32
+    lib.linr_search_clauses.argtypes = [vp, vp, vp, u32, u32, vp, vp, u32, u32, vp, vp, vp, vp, vp, u64, vp]
+    lib.linr_search_clauses_timed.restype = i32
+    lib.linr_search_clauses_timed.argtypes = lib.linr_search_clauses.argtypes + [vp, C.POINTER(u32), vp, vp]
     lib.linr_index_enable_updates.restype = i32
     lib.linr_index_enable_updates.argtypes = [vp]
     lib.linr_index_upsert.restype = i32
@@ -273,6 +282,38 @@ def search_two_stage(ix, Q, B, filters, T, k, out_ids, out_scores, out_counts, w
            "linr_search_two_stage")
 
 
+def index_load_clauses(ix, values, counts, n_clauses, row_width, reverse, n, src):
+    _check(load_library().linr_index_load_clauses(ix, _ptr(values), _ptr(counts), n_clauses, row_width, reverse, n, src),
+           "linr_index_load_clauses")
+
+
+def search_clauses_workspace_bytes(ix, B, m, k) -> int:
+    out = C.c_uint64()
+    _check(load_library().linr_search_clauses_workspace_bytes(ix, B, m, k, C.byref(out)), "linr_search_clauses_workspace_bytes")
+    return out.value
+
+
+def search_clauses(ix, Q, q_scale, B, m, q_values, q_counts, q_width, k, out_ids, out_scores, out_raw, out_counts,
+                   workspace, workspace_bytes, stream=0):
+    _check(load_library().linr_search_clauses(ix, _ptr(Q), _ptr(q_scale), B, m, _ptr(q_values), _ptr(q_counts), q_width, k,
+                                              _ptr(out_ids), _ptr(out_scores), _ptr(out_raw), _ptr(out_counts),
+                                              _ptr(workspace), workspace_bytes, stream), "linr_search_clauses")
+
+
+def search_clauses_timed(ix, Q, q_scale, B, m, q_values, q_counts, q_width, k, out_ids, out_scores, out_raw, out_counts,
+                         workspace, workspace_bytes, stream, events):
+    """As search_clauses, recording `events` around each launch.  Returns (kinds, items) per stage."""
+    ns = C.c_uint32()
+    kinds = (C.c_uint32 * MAX_STAGES)()
+    items = (C.c_uint64 * MAX_STAGES)()
+    _check(load_library().linr_search_clauses_timed(ix, _ptr(Q), _ptr(q_scale), B, m, _ptr(q_values), _ptr(q_counts), q_width,
+                                                    k, _ptr(out_ids), _ptr(out_scores), _ptr(out_raw), _ptr(out_counts),
+                                                    _ptr(workspace), workspace_bytes, stream, C.addressof(events),
+                                                    C.byref(ns), C.addressof(kinds), C.addressof(items)),
+           "linr_search_clauses_timed")
+    return [kinds[i] for i in range(ns.value)], [items[i] for i in range(ns.value)]
+
+
 def index_enable_updates(ix):
     _check(load_library().linr_index_enable_updates(ix), "linr_index_enable_updates")
 
@@ -333,6 +374,35 @@ class Index:
 
     def workspace_bytes(self, B, m, k):
         return search_workspace_bytes(self.handle, B, m, k)
+
+    # clause lists ------------------------------------------------------------------------------------------
+    def load_clauses(self, values, counts, reverse=0):
+        """values [n, row_width] (uint64 / int64 bit patterns), counts [n, n_clauses] uint8; numpy or device tensors"""
+        host = isinstance(values, np.ndarray)
+        n, width = values.shape
+        self.n_clauses = counts.shape[1]
+        index_load_clauses(self.handle, values, counts, self.n_clauses, width, reverse, n, SRC_HOST if host else SRC_DEVICE_COPY)
+        return self
+
+    def search_clauses(self, Q, q_values, q_counts, k, q_scale=None, want_raw=True):
+        """Q device [B, m, d]; q_values device [B, q_width] int64; q_counts device [B, n_clauses] uint8"""
+        import torch
+        if Q.dim() == 2:
+            Q = Q.unsqueeze(1)
+        Q = Q.contiguous()
+        B, m, dev = Q.shape[0], Q.shape[1], Q.device
+        ids = torch.empty((B, k), dtype=torch.int32, device=dev)
+        sc = torch.empty((B, k), dtype=torch.float32, device=dev)
+        raw = torch.empty((B, k), dtype=torch.int32, device=dev) if want_raw else None
+        cnt = torch.empty((B,), dtype=torch.int32, device=dev)
+        if B == 0:
+            return ids, sc, raw, cnt
+        nbytes = search_clauses_workspace_bytes(self.handle, B, m, k)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        search_clauses(self.handle, Q, q_scale, B, m, q_values.contiguous(), q_counts.contiguous(), q_values.shape[1], k,
+                       ids, sc, raw, cnt, ws, nbytes, torch.cuda.current_stream(dev).cuda_stream)
+        self._last_workspace = ws
+        return ids, sc, raw, cnt
 
     # live updates ------------------------------------------------------------------------------------------
     def enable_updates(self):

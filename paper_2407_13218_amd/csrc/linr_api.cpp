@@ -117,6 +117,9 @@ static void release_columns(linr_index* ix)
     if (ix->signs) (void)hipFree(ix->signs);
     ix->bits = nullptr; ix->perm = nullptr; ix->signs = nullptr;
     if (ix->dtype != LINR_BITS) { ix->k_bits = 0; ix->bits_words = 0; }
+    if (ix->clause_values) (void)hipFree(ix->clause_values);
+    if (ix->clause_counts) (void)hipFree(ix->clause_counts);
+    ix->clause_values = nullptr; ix->clause_counts = nullptr; ix->n_clauses = 0; ix->clause_n = 0;
     if (ix->scale_stats) (void)hipFree(ix->scale_stats);
     if (ix->scale_code) (void)hipFree(ix->scale_code);
     ix->scale_stats = nullptr; ix->scale_code = nullptr;
@@ -453,7 +456,8 @@ extern "C" int linr_search_workspace_bytes(const linr_index* ix, uint32_t B, uin
 static int search_impl(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
                        const linr_filter* filters, uint32_t k, uint32_t* out_ids, float* out_scores, int32_t* out_raw,
                        uint32_t* out_counts, void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags,
-                       void** events, uint32_t* n_stages, uint32_t* kinds, uint64_t* stage_items)
+                       void** events, uint32_t* n_stages, uint32_t* kinds, uint64_t* stage_items,
+                       uint32_t max_stages = LINR_MAX_STAGES)
 {
     if (n_stages) *n_stages = 0;
     if (!ix) return LINR_E_NULL;
@@ -479,7 +483,7 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
     char* ws = (char*)workspace;
     uint32_t stage = 0;
     auto ev = [&](int which, int kind, uint64_t items) -> hipError_t {
-        if (!events || stage >= LINR_MAX_STAGES) return hipSuccess;
+        if (!events || stage >= max_stages) return hipSuccess;
         hipError_t e = hipEventRecord((hipEvent_t)events[2 * stage + which], st);
         if (which == 1) {
             if (kinds) kinds[stage] = (uint32_t)kind;
@@ -937,4 +941,139 @@ extern "C" int linr_index_sync_updates(linr_index* ix)
     std::lock_guard<std::mutex> g(u->mu);
     if (u->pending) { ix->n = u->n_pending; u->pending = false; }
     return LINR_OK;
+}
+
+// ---------------------------------------------------------------------------
+// attribute matching over clause lists (Sec. 3.1.1; the representation the benchmark of Sec. 5.3 uses)
+// ---------------------------------------------------------------------------
+extern "C" int linr_index_load_clauses(linr_index* ix, const uint64_t* values, const uint8_t* counts, uint32_t n_clauses,
+                                       uint32_t row_width, uint32_t reverse, uint64_t n, int src)
+{
+    if (!ix || !values || !counts) return LINR_E_NULL;
+    if (ix->n == 0 || !ix->emb) return LINR_E_NOT_LOADED;
+    linr_index snap;
+    const linr_index* cur = view_for(ix, nullptr, false, &snap);
+    if (n != cur->n) return LINR_E_CAPACITY;
+    if (n_clauses == 0 || n_clauses > LINR_MAX_CLAUSES || row_width == 0 || row_width > LINR_MAX_CLAUSE_ROW) return LINR_E_SHAPE;
+    if (n_clauses < 32 && (reverse >> n_clauses) != 0) return LINR_E_SHAPE;
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipSetDevice(ix->device));
+    if (ix->clause_values) (void)hipFree(ix->clause_values);
+    if (ix->clause_counts) (void)hipFree(ix->clause_counts);
+    ix->clause_values = nullptr; ix->clause_counts = nullptr; ix->clause_n = 0;
+    const int fh = src == LINR_SRC_HOST;
+    int rc = copy_column((const void**)&ix->clause_values, values, n * row_width * 8, 0, fh);
+    if (rc == LINR_OK) rc = copy_column((const void**)&ix->clause_counts, counts, n * n_clauses, 0, fh);
+    if (rc == LINR_OK) { ix->n_clauses = n_clauses; ix->clause_width = row_width; ix->clause_reverse = reverse; ix->clause_n = n; }
+    (void)hipSetDevice(dev);
+    return rc;
+}
+
+// workspace of a clause search: the inner search of one group of <= 32 queries, then one word per item, then 32 filters
+static int clause_layout(const linr_index* v, uint32_t B, uint32_t m, uint32_t k, uint64_t* inner, uint64_t* off_words,
+                         uint64_t* off_filters, uint64_t* total)
+{
+    const uint32_t Bg = B < 32 ? B : 32;
+    int rc = linr_search_workspace_bytes(v, Bg, m, k, inner);
+    if (rc != LINR_OK) return rc;
+    const uint64_t items = v->dead_bit ? v->capacity : v->n;
+    *off_words = align_up(*inner, 256);
+    *off_filters = align_up(*off_words + items * 4, 256);
+    *total = align_up(*off_filters + 32 * sizeof(linr_filter), 256);
+    return LINR_OK;
+}
+
+extern "C" int linr_search_clauses_workspace_bytes(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, uint64_t* bytes)
+{
+    if (!ix || !bytes) return LINR_E_NULL;
+    if (!ix->clause_values) return LINR_E_STATE;
+    if (B == 0) { *bytes = 256; return LINR_OK; }
+    linr_index snap;
+    const linr_index* cur = view_for(ix, nullptr, false, &snap);
+    uint64_t inner, ow, of;
+    return clause_layout(cur, B, m, k, &inner, &ow, &of, bytes);
+}
+
+static int search_clauses_impl(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                               const uint64_t* q_values, const uint8_t* q_counts, uint32_t q_width, uint32_t k,
+                               uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts, void* workspace,
+                               uint64_t workspace_bytes, void* hip_stream, void** events, uint32_t* n_stages,
+                               uint32_t* kinds, uint64_t* stage_items)
+{
+    if (n_stages) *n_stages = 0;
+    if (!ix) return LINR_E_NULL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    linr_index v;
+    {
+        linr_index snap;
+        v = *view_for(ix, st, true, &snap);
+    }
+    if (v.n == 0 || !v.emb) return LINR_E_NOT_LOADED;
+    if (!v.clause_values || v.clause_n != v.n) return LINR_E_STATE;       // clause columns missing, or items added since
+    if (v.dtype == LINR_BITS) return LINR_E_DTYPE;
+    if (k == 0 || k > LINR_MAX_K) return LINR_E_K;
+    if (q_width == 0 || q_width > LINR_MAX_QUERY_ROW) return LINR_E_SHAPE;
+    if (B == 0) return LINR_OK;
+    if (!Q || !q_values || !q_counts || !out_ids || !out_scores || !out_counts) return LINR_E_NULL;
+    uint64_t inner, ow, of, total;
+    int rc = clause_layout(&v, B, m, k, &inner, &ow, &of, &total);
+    if (rc != LINR_OK) return rc;
+    if (!workspace || (((uintptr_t)workspace) & 255u) || workspace_bytes < total) return LINR_E_WORKSPACE;
+    uint32_t* words = (uint32_t*)((char*)workspace + ow);
+    linr_filter* filt = (linr_filter*)((char*)workspace + of);
+    // the inner search ranks over the word column: "bit b set" is query b's whole predicate
+    const uint32_t dead = v.dead_bit;
+    const uint32_t* item_mask = v.mask;
+    v.mask = words; v.ts = nullptr; v.dead_bit = 0; v.upd = nullptr;
+    HIP_TRY(linr_launch_bit_filters(filt, 32, st));
+    uint32_t stage = 0;
+    for (uint32_t b0 = 0; b0 < B; b0 += 32) {
+        const uint32_t Bg = (B - b0) < 32 ? (B - b0) : 32;
+        linr_clause_args ca;
+        memset(&ca, 0, sizeof(ca));
+        ca.values = v.clause_values; ca.counts = v.clause_counts; ca.n_clauses = v.n_clauses; ca.width = v.clause_width;
+        ca.reverse = v.clause_reverse; ca.n = v.n;
+        ca.q_values = q_values + (uint64_t)b0 * q_width; ca.q_counts = q_counts + (uint64_t)b0 * v.n_clauses;
+        ca.q_width = q_width; ca.nq = Bg; ca.mask = item_mask; ca.dead_bit = dead; ca.out = words;
+        const bool rec = events && stage < LINR_MAX_STAGES;
+        if (rec) HIP_TRY(hipEventRecord((hipEvent_t)events[2 * stage], st));
+        HIP_TRY(linr_launch_clause_words(ca, st));
+        if (rec) {
+            HIP_TRY(hipEventRecord((hipEvent_t)events[2 * stage + 1], st));
+            if (kinds) kinds[stage] = LINR_STAGE_FILTER;
+            if (stage_items) stage_items[stage] = v.n;
+            ++stage;
+        }
+        uint32_t ns = 0;
+        const bool more = events && stage < LINR_MAX_STAGES;
+        rc = search_impl(&v, (const char*)Q + (uint64_t)b0 * m * v.row_bytes, q_scale ? q_scale + b0 : nullptr, Bg, m, filt, k,
+                         out_ids + (uint64_t)b0 * k, out_scores + (uint64_t)b0 * k, out_raw ? out_raw + (uint64_t)b0 * k : nullptr,
+                         out_counts + b0, workspace, inner, hip_stream, LINR_FILTERS_ON_DEVICE, more ? events + 2 * stage : nullptr,
+                         more ? &ns : nullptr, more && kinds ? kinds + stage : nullptr, more && stage_items ? stage_items + stage : nullptr,
+                         more ? LINR_MAX_STAGES - stage : 0);
+        if (rc != LINR_OK) return rc;
+        stage += ns;
+    }
+    if (n_stages) *n_stages = stage;
+    return LINR_OK;
+}
+
+extern "C" int linr_search_clauses(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                                   const uint64_t* q_values, const uint8_t* q_counts, uint32_t q_width, uint32_t k,
+                                   uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts, void* workspace,
+                                   uint64_t workspace_bytes, void* hip_stream)
+{
+    return search_clauses_impl(ix, Q, q_scale, B, m, q_values, q_counts, q_width, k, out_ids, out_scores, out_raw, out_counts,
+                               workspace, workspace_bytes, hip_stream, nullptr, nullptr, nullptr, nullptr);
+}
+
+extern "C" int linr_search_clauses_timed(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                                         const uint64_t* q_values, const uint8_t* q_counts, uint32_t q_width, uint32_t k,
+                                         uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
+                                         void* workspace, uint64_t workspace_bytes, void* hip_stream, void** events,
+                                         uint32_t* n_stages, uint32_t* kinds, uint64_t* stage_items)
+{
+    return search_clauses_impl(ix, Q, q_scale, B, m, q_values, q_counts, q_width, k, out_ids, out_scores, out_raw, out_counts,
+                               workspace, workspace_bytes, hip_stream, events, n_stages, kinds, stage_items);
 }

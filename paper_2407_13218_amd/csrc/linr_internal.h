@@ -42,6 +42,11 @@ struct linr_index {
     // host-side bookkeeping of updates in flight (linr_api.cpp)
     uint32_t dead_bit;
     struct linr_update_state* upd;
+    // attribute matching over clause lists: values [clause_n][clause_width], counts [clause_n][n_clauses] (owned)
+    uint64_t* clause_values;
+    uint8_t* clause_counts;
+    uint32_t n_clauses, clause_width, clause_reverse;
+    uint64_t clause_n;
 };
 
 // Launch plan of one search pass (at most max_batch queries).
@@ -129,6 +134,16 @@ hipError_t linr_launch_upsert_masks(const linr_upsert_args& a, hipStream_t s);  
 hipError_t linr_launch_tombstone(uint32_t* mask, const uint32_t* slots, uint32_t count, uint32_t dead_bit, hipStream_t s);
 hipError_t linr_launch_fill_u32(uint32_t* dst, uint64_t n, uint32_t value, hipStream_t s);
 hipError_t linr_launch_mask_or(const uint32_t* mask, uint64_t n, uint32_t* out, hipStream_t s);   // *out |= OR of mask[0..n)
+// clause lists -> one word per item whose bit b says "item satisfies every clause of query b" (b < nq <= 32)
+struct linr_clause_args {
+    const uint64_t* values; const uint8_t* counts; uint32_t n_clauses, width, reverse; uint64_t n;
+    const uint64_t* q_values; const uint8_t* q_counts; uint32_t q_width, nq;
+    const uint32_t* mask; uint32_t dead_bit;           // live updates: slots whose mask carries dead_bit satisfy nothing
+    uint32_t* out;                                      // [n]
+};
+hipError_t linr_launch_clause_words(const linr_clause_args& a, hipStream_t s);
+// filters[b] = "bit b of the mask is set", b < nq
+hipError_t linr_launch_bit_filters(linr_filter* filters, uint32_t nq, hipStream_t s);
 struct linr_rescore_args {
     int dtype; const void* emb; uint32_t d; uint32_t row_bytes; const void* Q; uint32_t B, T, k;
     const uint32_t* cand_ids; const uint32_t* cand_counts;

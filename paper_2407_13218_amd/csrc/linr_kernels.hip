@@ -1744,6 +1744,74 @@ __global__ void __launch_bounds__(256) sign_oporp_kernel(int dtype, const void* 
 }
 
 // ---------------------------------------------------------------------------
+// attribute matching over clause lists (LiNR Sec. 3.1.1; 64-bit attributes as in the benchmark of Sec. 5.3)
+//   One thread per item.  The item's lists sit back to back in its row of the values matrix, their lengths in
+//   the count matrix; the lists of up to 32 queries are staged in LDS.  For every clause each attribute of the
+//   item is read once and compared with the clause's list of every query (uniform LDS reads); bit b of the
+//   result says that the item satisfies all clauses of query b.  A clause for which a query lists nothing does
+//   not constrain that query; a reverse clause is satisfied by "no attribute matches".
+// ---------------------------------------------------------------------------
+#define LINR_CLAUSE_MAX_C 8
+#define LINR_CLAUSE_MAX_QW 64
+__global__ void __launch_bounds__(256) clause_words_kernel(linr_clause_args A)
+{
+    __shared__ u64 qv[32][LINR_CLAUSE_MAX_QW];
+    __shared__ uint8_t qoff[32][LINR_CLAUSE_MAX_C], qlen[32][LINR_CLAUSE_MAX_C];
+    __shared__ uint32_t constrained[LINR_CLAUSE_MAX_C];       // bit b: query b lists something for this clause
+    const uint32_t C = A.n_clauses, nq = A.nq;
+    for (uint32_t t = threadIdx.x; t < nq * A.q_width; t += blockDim.x)
+        qv[t / A.q_width][t % A.q_width] = (u64)A.q_values[t];
+    if (threadIdx.x < C) constrained[threadIdx.x] = 0u;
+    __syncthreads();
+    if (threadIdx.x < nq) {
+        uint32_t off = 0;
+        for (uint32_t c = 0; c < C; ++c) {
+            uint32_t len = A.q_counts[threadIdx.x * C + c];
+            if (off + len > A.q_width) len = A.q_width - off;   // counts that overrun the query's row are cut
+            qoff[threadIdx.x][c] = (uint8_t)off;
+            qlen[threadIdx.x][c] = (uint8_t)len;
+            if (len) atomicOr(&constrained[c], 1u << threadIdx.x);
+            off += len;
+        }
+    }
+    __syncthreads();
+    const uint32_t all = nq >= 32 ? 0xFFFFFFFFu : ((1u << nq) - 1u);
+    for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < A.n; i += (u64)gridDim.x * blockDim.x) {
+        const u64* row = (const u64*)A.values + i * A.width;
+        const uint8_t* cnt = A.counts + i * C;
+        uint32_t ok = all, io = 0;
+        for (uint32_t c = 0; c < C; ++c) {
+            const uint32_t len = cnt[c];
+            uint32_t match = 0u;
+            for (uint32_t a = 0; a < len && io + a < A.width; ++a) {
+                const u64 v = row[io + a];
+                for (uint32_t b = 0; b < nq; ++b) {
+                    const uint32_t o = qoff[b][c], l = qlen[b][c];
+                    for (uint32_t t = 0; t < l; ++t)
+                        if (qv[b][o + t] == v) match |= 1u << b;
+                }
+            }
+            const uint32_t sat = ((A.reverse >> c) & 1u) ? ~match : match;
+            ok &= sat | ~constrained[c];
+            io += len;
+        }
+        if (A.dead_bit && (A.mask[i] & A.dead_bit)) ok = 0u;
+        A.out[i] = ok;
+    }
+}
+
+__global__ void __launch_bounds__(64) bit_filters_kernel(linr_filter* f, uint32_t nq)
+{
+    const uint32_t b = threadIdx.x;
+    if (b >= nq) return;
+    linr_filter F;
+    F.all_bits = 1u << b; F.none_bits = 0u;
+    for (int g = 0; g < LINR_MAX_ANY; ++g) F.any_bits[g] = 0u;
+    F.n_any = 0u; F.ts_min = 0u; F.ts_max = 0xFFFFFFFFu; F._pad = 0u;
+    f[b] = F;
+}
+
+// ---------------------------------------------------------------------------
 // live updates (LiNR Sec. 4 "Model Live Update"): rows and side columns of `count` slots, 8 bytes per thread
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) upsert_kernel(linr_upsert_args A)
@@ -2421,6 +2489,24 @@ hipError_t linr_launch_sign_oporp(int dtype, const void* x, uint64_t n, uint32_t
                                   uint32_t k_bits, uint64_t* out, hipStream_t s)
 {
     return linr_launch_sign_oporp_scatter(dtype, x, n, d, perm, signs, k_bits, out, nullptr, s);
+}
+
+hipError_t linr_launch_clause_words(const linr_clause_args& a, hipStream_t s)
+{
+    if (a.n == 0) return hipSuccess;
+    if (a.nq == 0 || a.nq > 32 || a.n_clauses == 0 || a.n_clauses > LINR_CLAUSE_MAX_C || a.q_width == 0 ||
+        a.q_width > LINR_CLAUSE_MAX_QW || a.width == 0)
+        return hipErrorInvalidValue;
+    const uint64_t blocks = (a.n + 255) / 256;
+    hipLaunchKernelGGL(clause_words_kernel, dim3((uint32_t)(blocks < 8192 ? blocks : 8192)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t linr_launch_bit_filters(linr_filter* filters, uint32_t nq, hipStream_t s)
+{
+    if (nq == 0 || nq > 32) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(bit_filters_kernel, dim3(1), dim3(64), 0, s, filters, nq);
+    return hipGetLastError();
 }
 
 hipError_t linr_launch_upsert(const linr_upsert_args& a, hipStream_t s)

@@ -263,3 +263,58 @@ def random_codes(n: int, k_bits: int, seed: int = 0):
     if rem < 64:
         codes[:, W - 1] &= np.uint64((1 << rem) - 1)
     return codes
+
+
+# ---------------------------------------------------------------------------
+# attribute clause lists (the representation of the paper's job-search benchmark, Sec. 5.3: geo-location match,
+# company-name reverse match, optionally job-title exact match; one 64-bit attribute per item / query and clause)
+# ---------------------------------------------------------------------------
+_ATTR_MULT = 0x9E3779B97F4A7C15          # spreads small category numbers over 64 bits (an id, not a hash of anything)
+
+
+def _zipf_draw(n, categories, s, device, seed):
+    """n category numbers in [0, categories) with P(c) proportional to 1 / (c + 1)^s"""
+    w = 1.0 / torch.arange(1, categories + 1, dtype=torch.float64, device=device) ** s
+    cdf = torch.cumsum(w / w.sum(), 0)
+    u = torch.rand(n, generator=_gen(device, seed), device=device, dtype=torch.float64)
+    return torch.searchsorted(cdf, u).clamp_(max=categories - 1)
+
+
+def _attr_ids(cat, clause):
+    """64-bit attribute ids (int64 bit patterns) of category numbers; different clauses never share an id"""
+    x = (cat.to(torch.int64) + 1 + clause * 1_000_003)
+    return x * torch.tensor(_ATTR_MULT - (1 << 64), dtype=torch.int64, device=cat.device)      # wraps modulo 2^64
+
+
+def job_clauses(device="cpu", n=15_500_000, B=16, low_pass=False, seed=0):
+    """values [n, C] int64, counts [n, C] uint8 (all ones), reverse mask, and the same for B queries.
+    Clause 0 geo (200 categories, Zipf 1.25: about 11 % of the items share a random query's geo), clause 1 company
+    (50 000 categories, uniform; REVERSE: items of the query's company are excluded), clause 2 (low_pass) job title
+    (20 000 categories, Zipf 1.0: a few titles match up to 9 % of the items, most a few thousand)."""
+    C = 3 if low_pass else 2
+    spec = [(200, 1.25), (50_000, 0.0), (20_000, 1.0)][:C]
+    vals = torch.empty((n, C), dtype=torch.int64, device=device)
+    qv = torch.empty((B, C), dtype=torch.int64, device=device)
+    for c, (cats, s) in enumerate(spec):
+        vals[:, c] = _attr_ids(_zipf_draw(n, cats, s, device, _seed(7, 10 * seed + c)), c)
+        qv[:, c] = _attr_ids(_zipf_draw(B, cats, s, device, _seed(7, 10 * seed + 5 + c)), c)
+    return dict(values=vals, counts=torch.ones((n, C), dtype=torch.uint8, device=device), reverse=0b10,
+                q_values=qv, q_counts=torch.ones((B, C), dtype=torch.uint8, device=device), n_clauses=C)
+
+
+def random_clause_lists(n, C, max_len, domain, seed, width=None):
+    """numpy: n rows of C lists with 0..max_len attributes each from [1, domain] (sorted inside each list), packed back to
+    back.  Returns values [n, width] uint64, counts [n, C] uint8."""
+    rng = np.random.default_rng(_seed(8, seed))
+    width = width or C * max_len
+    counts = rng.integers(0, max_len + 1, (n, C), dtype=np.uint8)
+    values = np.zeros((n, width), np.uint64)
+    draw = rng.integers(1, domain + 1, (n, C, max_len), dtype=np.uint64) * np.uint64(_ATTR_MULT)
+    draw.sort(axis=2)
+    off = np.zeros(n, np.int64)
+    for c in range(C):
+        for a in range(max_len):
+            sel = counts[:, c] > a
+            values[np.flatnonzero(sel), off[sel] + a] = draw[sel, c, a]
+        off += counts[:, c]
+    return values, counts

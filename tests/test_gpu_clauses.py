@@ -1,0 +1,178 @@
+"""GPU parity of the search with attribute matching over clause lists (LiNR Sec. 3.1.1; 64-bit attributes as in the
+benchmark of Sec. 5.3) against oracle.clause_search, through the C ABI.  int8 results are bit-exact; fp32 / bf16 cases
+use integer-valued embeddings, so their scores are exact too and are compared bit by bit."""
+import json
+import os
+import time
+
+import numpy as np
+import pytest
+
+import synth_inputs as S
+
+pytestmark = pytest.mark.gpu
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def say(msg):
+    print(f"[{time.strftime('%H:%M:%S')}] {msg}", flush=True)
+
+
+def dev(a):
+    import torch
+    if a is None:
+        return None
+    view = {np.dtype(np.uint16): np.int16, np.dtype(np.uint32): np.int32, np.dtype(np.uint64): np.int64}.get(a.dtype)
+    return torch.from_numpy(a.view(view) if view else a).cuda()
+
+
+def rows(rng, kind, n, d):
+    if kind == "f32":
+        return rng.integers(-4, 5, (n, d)).astype(np.float32), None
+    if kind == "bf16":
+        return (rng.integers(-4, 5, (n, d)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16), None
+    return rng.integers(-127, 128, (n, d), dtype=np.int8), rng.uniform(0.001, 0.02, n).astype(np.float32)
+
+
+DT = {"f32": S.F32, "bf16": S.BF16, "i8": S.I8}
+
+
+def run_case(oracle_mod, kind, d, n, B, k, values, counts, qv, qc, reverse, label, m=1):
+    import torch
+    import paper_2407_13218_amd as L
+    rng = np.random.default_rng(n + B)
+    emb, sc = rows(rng, kind, n, d)
+    Q, _ = rows(rng, kind, B * m, d)
+    Q = Q.reshape(B, m, d)
+    qs = np.ones(B, np.float32) if kind == "i8" else None
+    ix = L.Index(n, d, DT[kind], 0)
+    ix.load(emb, np.zeros(n, np.uint32), row_scale=sc)
+    ix.load_clauses(values, counts, reverse)
+    ids, scr, raw, cnt = ix.search_clauses(dev(Q), dev(qv), dev(qc), k, q_scale=dev(qs))
+    torch.cuda.synchronize()
+    got = (ids.cpu().numpy().view(np.uint32), scr.cpu().numpy(), raw.cpu().numpy(), cnt.cpu().numpy().view(np.uint32))
+    want = oracle_mod.clause_search(DT[kind], emb, values, counts, Q, qv, qc, reverse, k, row_scale=sc, q_scale=qs, nthreads=4)
+    assert np.array_equal(got[3], want[3]), f"{label}: counts {got[3][:8]} vs {want[3][:8]}"
+    bad = np.nonzero((got[0] != want[0]).any(axis=1))[0]
+    assert bad.size == 0, f"{label}: ids differ for queries {bad[:6]}: gpu {got[0][bad[0]][:8]} oracle {want[0][bad[0]][:8]}"
+    assert got[1].tobytes() == want[1].tobytes(), f"{label}: score bits differ"
+    if kind == "i8":
+        assert np.array_equal(got[2], want[2]), f"{label}: raw scores differ"
+    ix.close()
+    return want
+
+
+def test_hand_example_on_the_gpu(oracle_mod):
+    import torch
+    import paper_2407_13218_amd as L
+    from test_oracle_clauses_pins import pack
+    g = json.load(open(os.path.join(HERE, "golden", "clause_lists_example.json")))
+    v, c = pack(g["item_lists"], 2)
+    qv, qc = pack([g["query_lists"]], 2)
+    emb = np.zeros((5, 4), np.float32); emb[:, :2] = np.array(g["emb"], np.float32)
+    Q = np.zeros((1, 1, 4), np.float32); Q[0, 0, :2] = g["query"]
+    ix = L.Index(5, 4, S.F32, 0)
+    ix.load(emb, np.zeros(5, np.uint32))
+    ix.load_clauses(v, c, g["reverse"])
+    for k, key in ((1, "top1"), (3, "top3")):
+        ids, sc, _, cnt = ix.search_clauses(dev(Q), dev(qv), dev(qc), k)
+        torch.cuda.synchronize()
+        assert ids.cpu().numpy().view(np.uint32)[0].tolist() == g[key]["ids"] and sc.cpu().numpy()[0].tolist() == g[key]["scores"]
+    ids, sc, _, cnt = ix.search_clauses(dev(Q), dev(qv), dev(qc), 5)
+    assert int(cnt.cpu()[0]) == g["top5_count"]
+    none = np.zeros((1, 2), np.uint8)
+    ids, sc, _, _ = ix.search_clauses(dev(Q), dev(qv), dev(none), 1)
+    assert ids.cpu().numpy().view(np.uint32)[0].tolist() == g["no_clauses_top1"]["ids"]
+    ix.close()
+
+
+@pytest.mark.parametrize("kind,d,n,B,k,C,max_len,qlen,reverse", [
+    ("i8", 64, 20_000, 7, 50, 2, 1, 1, 0b10),         # the benchmark's shape: one attribute per clause, second clause reverse
+    ("i8", 64, 33_333, 40, 100, 3, 3, 4, 0b101),      # lists of 0..3 attributes, two groups of queries
+    ("f32", 32, 5_001, 70, 20, 5, 2, 2, 0b01010),     # three groups
+    ("bf16", 128, 9_000, 1, 300, 1, 4, 6, 0),         # one clause, long lists
+    ("i8", 64, 2_000, 33, 64, 8, 1, 2, 0xFF),         # eight reverse clauses
+    ("bf16", 64, 12_345, 16, 2000, 2, 2, 3, 0),       # k above the number of feasible items for most queries
+])
+def test_random_clause_lists(oracle_mod, kind, d, n, B, k, C, max_len, qlen, reverse):
+    domain = 6
+    values, counts = S.random_clause_lists(n, C, max_len, domain, seed=n)
+    qv, qc = S.random_clause_lists(B, C, qlen, domain, seed=n + 1)
+    want = run_case(oracle_mod, kind, d, n, B, k, values, counts, qv, qc, reverse, f"{kind} n={n} B={B} C={C}")
+    say(f"{kind} n={n} B={B} C={C}: feasible counts {want[3].min()}..{want[3].max()} (k = {k})")
+
+
+@pytest.mark.parametrize("low_pass", [False, True])
+def test_job_search_shape(oracle_mod, low_pass):
+    """the benchmark's clauses (geo match, company reverse match, optionally title match) at 300 000 items, top-2000"""
+    n, B = 300_000, 16
+    w = S.job_clauses(n=n, B=B, low_pass=low_pass)
+    values = w["values"].numpy().view(np.uint64); counts = w["counts"].numpy()
+    qv = w["q_values"].numpy().view(np.uint64); qc = w["q_counts"].numpy()
+    want = run_case(oracle_mod, "bf16", 128, n, B, 2000, values, counts, qv, qc, w["reverse"], f"job clauses low_pass={low_pass}")
+    say(f"job clauses low_pass={low_pass}: feasible per query {want[3].tolist()}")
+
+
+def test_multi_embedding_queries(oracle_mod):
+    values, counts = S.random_clause_lists(8_000, 2, 2, 5, seed=5)
+    qv, qc = S.random_clause_lists(9, 2, 2, 5, seed=6)
+    run_case(oracle_mod, "bf16", 64, 8_000, 9, 40, values, counts, qv, qc, 0b10, "m = 4", m=4)
+
+
+def test_with_live_updates(oracle_mod):
+    """deleted slots are infeasible for a clause search; items added after the clause columns were loaded make it an error"""
+    import torch
+    import paper_2407_13218_amd as L
+    rng = np.random.default_rng(2)
+    n, cap, d, B, k = 6_000, 7_000, 64, 5, 80
+    emb, sc = rows(rng, "i8", n, d)
+    Q, _ = rows(rng, "i8", B, d)
+    Q = Q.reshape(B, 1, d); qs = np.ones(B, np.float32)
+    values, counts = S.random_clause_lists(n, 2, 2, 4, seed=9)
+    qv, qc = S.random_clause_lists(B, 2, 2, 4, seed=10)
+    ix = L.Index(cap, d, S.I8, 0)
+    ix.load(emb, np.zeros(n, np.uint32), row_scale=sc)
+    ix.load_clauses(values, counts, 0)
+    ix.enable_updates()
+    gone = rng.choice(n, 2500, replace=False).astype(np.uint32)
+    ix.delete(gone)
+    ids, scr, raw, cnt = ix.search_clauses(dev(Q), dev(qv), dev(qc), k, q_scale=dev(qs))
+    torch.cuda.synchronize()
+    # the oracle's statement of "deleted": the item's lists are empty and the query constrains clause 0 ... simpler and
+    # independent of that: drop the deleted items, search, map the dense positions back to slots
+    keep = np.setdiff1d(np.arange(n), gone)
+    want = oracle_mod.clause_search(S.I8, emb[keep], values[keep], counts[keep], Q, qv, qc, 0, k, row_scale=sc[keep], q_scale=qs)
+    wid = np.where(want[0] == oracle_mod.NO_ID, oracle_mod.NO_ID, keep[np.minimum(want[0], len(keep) - 1)].astype(np.uint32))
+    assert np.array_equal(cnt.cpu().numpy().view(np.uint32), want[3])
+    assert np.array_equal(ids.cpu().numpy().view(np.uint32), wid)
+    assert scr.cpu().numpy().tobytes() == want[1].tobytes()
+    ix.upsert([n], emb[:1], np.zeros(1, np.uint32), row_scale=sc[:1])
+    ix.sync_updates()
+    with pytest.raises(L.LinrError) as e:
+        ix.search_clauses(dev(Q), dev(qv), dev(qc), k, q_scale=dev(qs))
+    assert e.value.code == -10
+    ix.close()
+
+
+def test_clause_argument_errors():
+    import paper_2407_13218_amd as L
+    rng = np.random.default_rng(1)
+    emb, sc = rows(rng, "i8", 100, 64)
+    ix = L.Index(100, 64, S.I8, 0)
+    ix.load(emb, np.zeros(100, np.uint32), row_scale=sc)
+    Q = dev(emb[:2].reshape(2, 1, 64))
+    qv = dev(np.zeros((2, 2), np.uint64)); qc = dev(np.zeros((2, 2), np.uint8))
+    with pytest.raises(L.LinrError) as e:
+        ix.search_clauses(Q, qv, qc, 5)                                   # no clause columns
+    assert e.value.code == -10
+    v = np.zeros((99, 2), np.uint64); c = np.zeros((99, 2), np.uint8)
+    with pytest.raises(L.LinrError) as e:
+        ix.load_clauses(v, c)                                             # not one row per item
+    assert e.value.code == -5
+    with pytest.raises(L.LinrError) as e:
+        ix.load_clauses(np.zeros((100, 9), np.uint64), np.zeros((100, 9), np.uint8))   # more clauses than supported
+    assert e.value.code == -2
+    with pytest.raises(L.LinrError) as e:
+        ix.load_clauses(np.zeros((100, 2), np.uint64), np.zeros((100, 2), np.uint8), reverse=0b100)   # reverse bit of no clause
+    assert e.value.code == -2
+    ix.close()
