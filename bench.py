@@ -10,7 +10,8 @@ rate); a short sweep over B in {1, 32, 256, 1024} and pass rates {50 %, 5 %, 0.1
 reported in the same JSON line under "sweep".  A second leg, reported under "quantised", runs the
 1-bit search of Sec. 3.2 (64-bit Sign-OPORP codes of the same items, the paper's billion-member
 setting of Sec. 5.3) for B in {1, 32}, with its own roofline and oracle timing; a third, "live_update",
-measures search latency next to concurrent upserts and deletes (Sec. 5.3, Table 5).
+measures search latency next to concurrent upserts and deletes (Sec. 5.3, Table 5); a fourth, "clause_lists",
+runs the paper's own benchmark shape (Sec. 5.3, Tables 3 and 4) with 64-bit clause lists as the filter.
 
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
@@ -165,6 +166,71 @@ def quantised_leg(L, S, base, index_cols, N, k, args, dev):
     return out
 
 
+def clause_leg(L, S, args, dev):
+    """The paper's own benchmark shape (Sec. 5.3, Tables 3 and 4): 15.5 M items x d128 (bf16 here, fp16 there), top-2000,
+    attribute matching over 64-bit clause lists -- high pass rate: geo match + company reverse match (about 11 % of the
+    items feasible); low pass rate: + title match (mostly thousands feasible) -- batch 1 and 16."""
+    import numpy as np
+    import torch
+    n, d, k = 15_500_000, 128, 2000
+    w = S.config2(device=dev, n=n, B=16, k=k, p=0.5)
+    ix = L.Index(n, d, S.BF16, 0)
+    ix.load(w["emb"], w["mask"])
+    stream = torch.cuda.current_stream().cuda_stream
+    rows, oracle_s = [], None
+    for low in (False, True):
+        cl = S.job_clauses(device=dev, n=n, B=16, low_pass=low)
+        C = cl["n_clauses"]
+        ix.load_clauses(cl["values"], cl["counts"], cl["reverse"])
+        for B in (1, 16):
+            Q = w["Q"][:B].contiguous(); qv = cl["q_values"][:B].contiguous(); qc = cl["q_counts"][:B].contiguous()
+            nbytes = L.search_clauses_workspace_bytes(ix.handle, B, 1, k)
+            ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+            ids = torch.empty((B, k), dtype=torch.int32, device=dev); sc = torch.empty((B, k), dtype=torch.float32, device=dev)
+            cnt = torch.empty((B,), dtype=torch.int32, device=dev)
+            steps = args.steps
+            ev = [L.events_create(2 * L.MAX_STAGES) for _ in range(steps)]
+            for _ in range(args.warmup):
+                L.search_clauses(ix.handle, Q, None, B, 1, qv, qc, C, k, ids, sc, None, cnt, ws, nbytes, stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for s_ in range(steps):
+                kinds, items = L.search_clauses_timed(ix.handle, Q, None, B, 1, qv, qc, C, k, ids, sc, None, cnt, ws, nbytes,
+                                                      stream, ev[s_])
+            torch.cuda.synchronize()
+            wall = (time.perf_counter() - t0) * 1e3 / steps
+            per = [L.events_elapsed_ms(e, len(kinds)) for e in ev]
+            for e in ev:
+                L.events_destroy(e)
+            mean = [sum(p[i] for p in per) / steps for i in range(len(kinds))]
+            filt_ms = sum(mean[i] for i, kd in enumerate(kinds) if kd == 3)
+            scan_ms = sum(mean[i] for i, kd in enumerate(kinds) if kd == 1)
+            fbytes = n * (8 * C + C + 4)                       # values + counts read, one word written
+            r = dict(pass_rate="low" if low else "high", clauses=C, batch=B, ms_per_search=wall, queries_per_s=B / wall * 1e3,
+                     clause_pass_ms=filt_ms, clause_pass_GBs=fbytes / filt_ms / 1e6, clause_pass_hbm_frac=fbytes / filt_ms / 1e6 / HBM_PEAK_GBS,
+                     sweeps_ms=scan_ms, sweeps_GBs=n * (2 * d + 4) / scan_ms / 1e6,
+                     merges_ms=sum(mean[i] for i, kd in enumerate(kinds) if kd == 2),
+                     feasible_min=int(cnt.min().item()), feasible_capped_mean=float(cnt.float().mean().item()))
+            rows.append({key: (round(v, 4) if isinstance(v, float) else v) for key, v in r.items()})
+            log(f"  clauses {r['pass_rate']:>4} pass, batch {B:2d}: {wall:.3f} ms/search (clause pass {filt_ms:.3f} ms = "
+                f"{r['clause_pass_GBs']:.0f} GB/s, sweeps {scan_ms:.3f} ms, merges {r['merges_ms']:.3f} ms)")
+            del ws
+        if low and not args.no_cpu:
+            import oracle
+            ns = 2_000_000
+            t0 = time.perf_counter()
+            oracle.clause_search(S.BF16, w["emb"][:ns].cpu().numpy().view(np.uint16), cl["values"][:ns].cpu().numpy().view(np.uint64),
+                                 cl["counts"][:ns].cpu().numpy(), w["Q"][:4].cpu().numpy().view(np.uint16),
+                                 cl["q_values"][:4].cpu().numpy().view(np.uint64), cl["q_counts"][:4].cpu().numpy(), cl["reverse"], k,
+                                 nthreads=max(1, min(16, os.cpu_count() or 1)))
+            dt = time.perf_counter() - t0
+            oracle_s = dict(value=ns * 4 / dt, unit="item-query pairs/s", cores=max(1, min(16, os.cpu_count() or 1)), kind="oracle",
+                            sample=f"first {ns} items x 4 queries of the low-pass workload, {dt:.1f} s")
+    ix.close()
+    return {"workload": f"{n} x d128 bf16, clustered; clause lists of one 64-bit attribute per clause (geo match, company "
+                        f"reverse match, + title match for the low pass rate), top-{k}", "rows": rows, "cpu_baseline": oracle_s}
+
+
 def live_update_leg(L, S, args, dev):
     """Search latency next to concurrent updates (Sec. 5.3 "Impact of Live Model Update on Inference", Table 5: requests
     issued serially, batch 1 and 5, 0 / 300 / 600 updates per second; here also 20 000 per second in batches of 100).
@@ -257,6 +323,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-quantised", action="store_true", help="skip the 1-bit (Sign-OPORP) search leg")
     ap.add_argument("--no-live-update", action="store_true", help="skip the search-latency-under-updates leg")
+    ap.add_argument("--no-clauses", action="store_true", help="skip the clause-list (job-search benchmark shape) leg")
     ap.add_argument("--code-bits", type=int, default=64, help="bits per Sign-OPORP code of the quantised leg (divides 64)")
     ap.add_argument("--sweep-steps", type=int, default=5)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -346,6 +413,11 @@ def main():
     if not args.no_quantised:
         quant = quantised_leg(L, S, base, index_cols, N, k, args, dev)
 
+    clauses = None
+    if not args.no_clauses:
+        log("clause lists: the paper's benchmark shape (15.5 M x d128, top-2000)")
+        clauses = clause_leg(L, S, args, dev)
+
     live = None
     if not args.no_live_update:
         log("live updates: search latency next to concurrent upserts / deletes")
@@ -391,6 +463,7 @@ def main():
         "sweep": sweep,
         "quantised": quant,
         "live_update": live,
+        "clause_lists": clauses,
     }
     print(json.dumps(line), flush=True)
 
