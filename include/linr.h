@@ -230,6 +230,23 @@ int linr_search_clauses(const linr_index*, const void* Q, const float* q_scale, 
                         void* workspace, uint64_t workspace_bytes, void* hip_stream);
 
 /*
+ * The same search by explicit pre-filtering (Sec. 3.1.2 "KNN with Explicit Pre-Filtering"):
+ * after the pass over the clause columns only the feasible (item, query) pairs are scored
+ * (rows gathered with 16-byte loads, one lane per pair) and one selection over their keys
+ * gives the top k -- the embeddings of infeasible items are never read.  Same arguments,
+ * workspace and results as linr_search_clauses (fp32 / bf16 scores within the usual
+ * tolerance of each other, int8 bit-identical).  Faster when few items are feasible,
+ * slower when many are (the caller chooses, as between the paper's two variants).  A query
+ * with more feasible items than the candidate arrays of the workspace hold (several
+ * million) is not answered: out_counts[b] = 0xFFFFFFFF, its other outputs are undefined.
+ */
+#define LINR_COUNT_OVERFLOW 0xFFFFFFFFu
+int linr_search_clauses_prefilter(const linr_index*, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                                  const uint64_t* q_values, const uint8_t* q_counts, uint32_t q_width, uint32_t k,
+                                  uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
+                                  void* workspace, uint64_t workspace_bytes, void* hip_stream);
+
+/*
  * Live updates (Sec. 4 "Model Live Update": Upsert and Delete calls on columns that are
  * pre-allocated larger than the initial index, a high-water mark for the working set, and
  * updates that run next to searches; their cost for searches is the subject of Sec. 5.3,

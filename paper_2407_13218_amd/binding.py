@@ -34,6 +34,7 @@ EXPORTS = [
     "linr_search_bits", "linr_search_two_stage_workspace_bytes", "linr_search_two_stage", "linr_search_bits_timed",
     "linr_index_enable_updates", "linr_index_upsert", "linr_index_delete", "linr_index_sync_updates",
     "linr_index_load_clauses", "linr_search_clauses_workspace_bytes", "linr_search_clauses", "linr_search_clauses_timed",
+    "linr_search_clauses_prefilter",
 ]
 
 
@@ -111,6 +112,8 @@ def load_library():
     lib.linr_search_clauses_workspace_bytes.argtypes = [vp, u32, u32, u32, C.POINTER(u64)]
     lib.linr_search_clauses.restype = i32
     lib.linr_search_clauses.argtypes = [vp, vp, vp, u32, u32, vp, vp, u32, u32, vp, vp, vp, vp, vp, u64, vp]
+    lib.linr_search_clauses_prefilter.restype = i32
+    lib.linr_search_clauses_prefilter.argtypes = lib.linr_search_clauses.argtypes
     lib.linr_search_clauses_timed.restype = i32
     lib.linr_search_clauses_timed.argtypes = lib.linr_search_clauses.argtypes + [vp, C.POINTER(u32), vp, vp]
     lib.linr_index_enable_updates.restype = i32
@@ -300,6 +303,13 @@ def search_clauses(ix, Q, q_scale, B, m, q_values, q_counts, q_width, k, out_ids
                                               _ptr(workspace), workspace_bytes, stream), "linr_search_clauses")
 
 
+def search_clauses_prefilter(ix, Q, q_scale, B, m, q_values, q_counts, q_width, k, out_ids, out_scores, out_raw, out_counts,
+                             workspace, workspace_bytes, stream=0):
+    _check(load_library().linr_search_clauses_prefilter(ix, _ptr(Q), _ptr(q_scale), B, m, _ptr(q_values), _ptr(q_counts), q_width,
+                                                        k, _ptr(out_ids), _ptr(out_scores), _ptr(out_raw), _ptr(out_counts),
+                                                        _ptr(workspace), workspace_bytes, stream), "linr_search_clauses_prefilter")
+
+
 def search_clauses_timed(ix, Q, q_scale, B, m, q_values, q_counts, q_width, k, out_ids, out_scores, out_raw, out_counts,
                          workspace, workspace_bytes, stream, events):
     """As search_clauses, recording `events` around each launch.  Returns (kinds, items) per stage."""
@@ -384,8 +394,9 @@ class Index:
         index_load_clauses(self.handle, values, counts, self.n_clauses, width, reverse, n, SRC_HOST if host else SRC_DEVICE_COPY)
         return self
 
-    def search_clauses(self, Q, q_values, q_counts, k, q_scale=None, want_raw=True):
-        """Q device [B, m, d]; q_values device [B, q_width] int64; q_counts device [B, n_clauses] uint8"""
+    def search_clauses(self, Q, q_values, q_counts, k, q_scale=None, want_raw=True, prefilter=False):
+        """Q device [B, m, d]; q_values device [B, q_width] int64; q_counts device [B, n_clauses] uint8;
+        prefilter=True: the explicit pre-filtering strategy (linr_search_clauses_prefilter)"""
         import torch
         if Q.dim() == 2:
             Q = Q.unsqueeze(1)
@@ -399,8 +410,9 @@ class Index:
             return ids, sc, raw, cnt
         nbytes = search_clauses_workspace_bytes(self.handle, B, m, k)
         ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-        search_clauses(self.handle, Q, q_scale, B, m, q_values.contiguous(), q_counts.contiguous(), q_values.shape[1], k,
-                       ids, sc, raw, cnt, ws, nbytes, torch.cuda.current_stream(dev).cuda_stream)
+        fn = search_clauses_prefilter if prefilter else search_clauses
+        fn(self.handle, Q, q_scale, B, m, q_values.contiguous(), q_counts.contiguous(), q_values.shape[1], k,
+           ids, sc, raw, cnt, ws, nbytes, torch.cuda.current_stream(dev).cuda_stream)
         self._last_workspace = ws
         return ids, sc, raw, cnt
 

@@ -980,7 +980,7 @@ static int clause_layout(const linr_index* v, uint32_t B, uint32_t m, uint32_t k
     const uint64_t items = v->dead_bit ? v->capacity : v->n;
     *off_words = align_up(*inner, 256);
     *off_filters = align_up(*off_words + items * 4, 256);
-    *total = align_up(*off_filters + 32 * sizeof(linr_filter), 256);
+    *total = align_up(*off_filters + 32 * sizeof(linr_filter) + 256, 256);     // + 32 counters of the pre-filtering strategy
     return LINR_OK;
 }
 
@@ -999,7 +999,7 @@ static int search_clauses_impl(const linr_index* ix, const void* Q, const float*
                                const uint64_t* q_values, const uint8_t* q_counts, uint32_t q_width, uint32_t k,
                                uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts, void* workspace,
                                uint64_t workspace_bytes, void* hip_stream, void** events, uint32_t* n_stages,
-                               uint32_t* kinds, uint64_t* stage_items)
+                               uint32_t* kinds, uint64_t* stage_items, bool prefilter = false)
 {
     if (n_stages) *n_stages = 0;
     if (!ix) return LINR_E_NULL;
@@ -1045,6 +1045,44 @@ static int search_clauses_impl(const linr_index* ix, const void* Q, const float*
             if (stage_items) stage_items[stage] = v.n;
             ++stage;
         }
+        if (prefilter) {
+            // explicit pre-filtering (Sec. 3.1.2): score the feasible items only, then one final merge
+            if (m == 0 || m > LINR_MAX_M) return LINR_E_SHAPE;
+            if (((uintptr_t)Q) & 15u) return LINR_E_SHAPE;
+            linr_plan pp;
+            rc = make_plan(&v, Bg, m, k, &pp);
+            if (rc != LINR_OK) return rc;
+            if (pp.total_bytes > inner) return LINR_E_WORKSPACE;
+            char* ws = (char*)workspace;
+            unsigned long long* tau = (unsigned long long*)(ws + pp.off_tau);
+            uint32_t* cnt = (uint32_t*)(ws + pp.off_cnt);
+            uint32_t* gcnt = (uint32_t*)(ws + pp.off_gcnt);
+            uint32_t* fvalid = (uint32_t*)(ws + pp.off_fvalid);
+            uint32_t* ccnt = (uint32_t*)(ws + pp.off_ccnt);
+            uint32_t* vcnt = (uint32_t*)(filt + 32);
+            HIP_TRY(linr_launch_init(tau, ccnt, gcnt, fvalid, cnt, (uint64_t)Bg * pp.nslots, Bg, st));
+            linr_prefilter_args pa;
+            memset(&pa, 0, sizeof(pa));
+            pa.words = words; pa.n = v.n; pa.nq = Bg; pa.dtype = v.dtype; pa.vk = pp.vk; pa.emb = v.emb; pa.row_scale = v.row_scale;
+            pa.row_bytes = v.row_bytes; pa.d = v.d; pa.Q = (const char*)Q + (uint64_t)b0 * m * v.row_bytes; pa.m = m;
+            pa.flat = (unsigned long long*)(ws + pp.off_flat); pa.flat_cap = pp.flat_cap;
+            pa.seg = (unsigned long long*)(ws + pp.off_seg); pa.nslots = pp.nslots; pa.cap = pp.cap; pa.B = Bg;
+            pa.vcnt = vcnt; pa.gcnt = gcnt; pa.fvalid = fvalid; pa.cnt = cnt;
+            HIP_TRY(linr_launch_prefilter(pa, st));
+            linr_merge_args ma;
+            memset(&ma, 0, sizeof(ma));
+            ma.tau = tau; ma.cnt = cnt; ma.seg = pa.seg; ma.nslots = pp.nslots; ma.cap = pp.cap; ma.B = Bg; ma.k = k;
+            ma.gcnt = gcnt; ma.fvalid = fvalid; ma.flat = pa.flat; ma.flat_cap = pp.flat_cap;
+            ma.carry = (unsigned long long*)(ws + pp.off_carry); ma.ccnt = ccnt;
+            ma.dtype = v.dtype; ma.vk = pp.vk; ma.emb = v.emb; ma.row_scale = v.row_scale; ma.row_bytes = v.row_bytes; ma.d = v.d;
+            ma.Q = pa.Q; ma.q_scale = q_scale ? q_scale + b0 : nullptr; ma.m = m;
+            ma.out_ids = out_ids + (uint64_t)b0 * k; ma.out_scores = out_scores + (uint64_t)b0 * k;
+            ma.out_raw = out_raw ? out_raw + (uint64_t)b0 * k : nullptr; ma.out_counts = out_counts + b0;
+            ma.final_level = 1;
+            HIP_TRY(linr_launch_merge(ma, st));
+            HIP_TRY(linr_launch_prefilter_overflow(vcnt, (uint64_t)pp.flat_cap + (uint64_t)pp.nslots * pp.cap, out_counts + b0, Bg, st));
+            continue;
+        }
         uint32_t ns = 0;
         const bool more = events && stage < LINR_MAX_STAGES;
         rc = search_impl(&v, (const char*)Q + (uint64_t)b0 * m * v.row_bytes, q_scale ? q_scale + b0 : nullptr, Bg, m, filt, k,
@@ -1076,4 +1114,13 @@ extern "C" int linr_search_clauses_timed(const linr_index* ix, const void* Q, co
 {
     return search_clauses_impl(ix, Q, q_scale, B, m, q_values, q_counts, q_width, k, out_ids, out_scores, out_raw, out_counts,
                                workspace, workspace_bytes, hip_stream, events, n_stages, kinds, stage_items);
+}
+
+extern "C" int linr_search_clauses_prefilter(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                                             const uint64_t* q_values, const uint8_t* q_counts, uint32_t q_width, uint32_t k,
+                                             uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
+                                             void* workspace, uint64_t workspace_bytes, void* hip_stream)
+{
+    return search_clauses_impl(ix, Q, q_scale, B, m, q_values, q_counts, q_width, k, out_ids, out_scores, out_raw, out_counts,
+                               workspace, workspace_bytes, hip_stream, nullptr, nullptr, nullptr, nullptr, true);
 }

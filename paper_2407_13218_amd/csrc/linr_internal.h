@@ -144,6 +144,18 @@ struct linr_clause_args {
 hipError_t linr_launch_clause_words(const linr_clause_args& a, hipStream_t s);
 // filters[b] = "bit b of the mask is set", b < nq
 hipError_t linr_launch_bit_filters(linr_filter* filters, uint32_t nq, hipStream_t s);
+// explicit pre-filtering (Sec. 3.1.2): score only the items whose feasibility word has a bit set, append their keys
+// to the query's flat candidate array (first flat_cap keys) and, beyond that, to the per-slot segments
+struct linr_prefilter_args {
+    const uint32_t* words; uint64_t n; uint32_t nq;
+    int dtype, vk; const void* emb; const float* row_scale; uint32_t row_bytes, d; const void* Q; uint32_t m;
+    unsigned long long* flat; uint32_t flat_cap; unsigned long long* seg; uint32_t nslots, cap, B;
+    uint32_t* vcnt;             // [nq] feasible items found per query (zeroed by the launcher's first kernel)
+    uint32_t* gcnt; uint32_t* fvalid; uint32_t* cnt;      // the merge's view of where the keys are (written by the second)
+};
+hipError_t linr_launch_prefilter(const linr_prefilter_args& a, hipStream_t s);
+// out_counts[b] = 0xFFFFFFFF where vcnt[b] > capacity (run behind the merge)
+hipError_t linr_launch_prefilter_overflow(const uint32_t* vcnt, uint64_t capacity, uint32_t* out_counts, uint32_t nq, hipStream_t s);
 struct linr_rescore_args {
     int dtype; const void* emb; uint32_t d; uint32_t row_bytes; const void* Q; uint32_t B, T, k;
     const uint32_t* cand_ids; const uint32_t* cand_counts;

@@ -1812,6 +1812,114 @@ __global__ void __launch_bounds__(64) bit_filters_kernel(linr_filter* f, uint32_
 }
 
 // ---------------------------------------------------------------------------
+// explicit pre-filtering (LiNR Sec. 3.1.2): the feasibility words are scanned, only feasible (item, query) pairs
+// are scored -- one lane per pair, rows read with 16-byte loads -- and their keys are appended where the merge
+// looks for candidates.  Pays off when few items are feasible; the scan kernels above serve the other case.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int dot_i8_row(const int8_t* q, const int8_t* x, uint32_t d);      // (defined with the merge)
+
+__device__ __forceinline__ float dot_f32_row(const float* q, const float* x, uint32_t d)
+{
+    float s = 0.0f;
+    for (uint32_t j = 0; j < d; j += 4) {
+        const float4 a = *(const float4*)(q + j), b = *(const float4*)(x + j);
+        s += a.x * b.x; s += a.y * b.y; s += a.z * b.z; s += a.w * b.w;
+    }
+    return s;
+}
+
+__device__ __forceinline__ float dot_bf16_row(const uint16_t* q, const uint16_t* x, uint32_t d)
+{
+    float s = 0.0f;
+    for (uint32_t j = 0; j < d; j += 8) {
+        const v4i a = *(const v4i*)(q + j), b = *(const v4i*)(x + j);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            s += __uint_as_float((uint32_t)a[w] << 16) * __uint_as_float((uint32_t)b[w] << 16);
+            s += __uint_as_float((uint32_t)a[w] & 0xFFFF0000u) * __uint_as_float((uint32_t)b[w] & 0xFFFF0000u);
+        }
+    }
+    return s;
+}
+
+__global__ void __launch_bounds__(64) prefilter_zero_kernel(uint32_t* vcnt) { if (threadIdx.x < 32) vcnt[threadIdx.x] = 0u; }
+
+__global__ void __launch_bounds__(256) prefilter_score_kernel(linr_prefilter_args A)
+{
+    const int lane = threadIdx.x & 63;
+    const u64 n_round = (A.n + 63) / 64 * 64;                     // whole waves stay together for the ballots
+    for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n_round; i += (u64)gridDim.x * blockDim.x) {
+        const uint32_t w = i < A.n ? A.words[i] : 0u;
+        if (!wave_any(w != 0u)) continue;
+        const char* x = (const char*)A.emb + i * A.row_bytes;
+        for (uint32_t b = 0; b < A.nq; ++b) {
+            const bool has = (w >> b) & 1u;
+            const u64 bal = wave_ballot(has);
+            if (bal == 0ull) continue;
+            uint32_t base = 0;
+            const int leader = __ffsll((long long)bal) - 1;
+            if (lane == leader) base = atomicAdd(&A.vcnt[b], (uint32_t)__popcll(bal));
+            base = __shfl(base, leader);
+            if (!has) continue;
+            const uint32_t pos = base + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+            uint32_t hi;
+            if (A.dtype == LINR_I8) {
+                int best = INT_MIN;
+                for (uint32_t e = 0; e < A.m; ++e) {
+                    const int r = dot_i8_row((const int8_t*)A.Q + ((u64)b * A.m + e) * A.row_bytes, (const int8_t*)x, A.d);
+                    best = r > best ? r : best;
+                }
+                hi = A.vk == LINR_VK_I8_SCALED ? ord_f32((float)best * A.row_scale[i]) : ord_i32(best);
+            } else {
+                float best = -INFINITY;
+                for (uint32_t e = 0; e < A.m; ++e) {
+                    const char* q = (const char*)A.Q + ((u64)b * A.m + e) * A.row_bytes;
+                    const float r = A.dtype == LINR_F32 ? dot_f32_row((const float*)q, (const float*)x, A.d)
+                                                        : dot_bf16_row((const uint16_t*)q, (const uint16_t*)x, A.d);
+                    best = fmaxf(best, r);
+                }
+                hi = ord_f32(best);
+            }
+            const u64 key = ((u64)hi << 32) | (u64)(uint32_t)~(uint32_t)i;
+            if (pos < A.flat_cap) {
+                const uint32_t rcap = A.flat_cap / LINR_FLAT_REGIONS;
+                A.flat[(u64)b * A.flat_cap + (u64)(pos % LINR_FLAT_REGIONS) * rcap + pos / LINR_FLAT_REGIONS] = key;
+            } else {
+                const u64 q2 = pos - A.flat_cap;
+                const u64 slot = q2 / A.cap;
+                if (slot < A.nslots) A.seg[(slot * A.B + b) * A.cap + q2 % A.cap] = key;
+            }
+        }
+    }
+}
+
+// tells the merge where the keys are: per flat region the number of keys, per slot the size of its segment
+__global__ void __launch_bounds__(256) prefilter_counts_kernel(linr_prefilter_args A)
+{
+    const uint32_t b = blockIdx.x;
+    const uint32_t total = A.vcnt[b];
+    const uint32_t in_flat = total < A.flat_cap ? total : A.flat_cap;
+    for (uint32_t r = threadIdx.x; r < LINR_FLAT_REGIONS; r += blockDim.x) {
+        const u64 ci = ((u64)b * LINR_FLAT_REGIONS + r) * LINR_COUNTER_STRIDE;
+        const uint32_t c = in_flat / LINR_FLAT_REGIONS + (r < in_flat % LINR_FLAT_REGIONS ? 1u : 0u);
+        A.gcnt[ci] = c;
+        A.fvalid[ci] = total > A.flat_cap ? c : 0xFFFFFFFFu;      // "look into the segments too"
+    }
+    const u64 rest = total - in_flat;
+    for (uint32_t s2 = threadIdx.x; s2 < A.nslots; s2 += blockDim.x) {
+        const u64 lo = (u64)s2 * A.cap;
+        A.cnt[(u64)b * A.nslots + s2] = rest > lo ? (uint32_t)(rest - lo < A.cap ? rest - lo : A.cap) : 0u;
+    }
+}
+
+// a query with more feasible items than the candidate arrays hold cannot be answered this way: say so in its count
+__global__ void __launch_bounds__(64) prefilter_overflow_kernel(const uint32_t* vcnt, uint64_t capacity, uint32_t* out_counts,
+                                                                uint32_t nq)
+{
+    if (threadIdx.x < nq && (uint64_t)vcnt[threadIdx.x] > capacity) out_counts[threadIdx.x] = 0xFFFFFFFFu;
+}
+
+// ---------------------------------------------------------------------------
 // live updates (LiNR Sec. 4 "Model Live Update"): rows and side columns of `count` slots, 8 bytes per thread
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) upsert_kernel(linr_upsert_args A)
@@ -2506,6 +2614,24 @@ hipError_t linr_launch_bit_filters(linr_filter* filters, uint32_t nq, hipStream_
 {
     if (nq == 0 || nq > 32) return hipErrorInvalidValue;
     hipLaunchKernelGGL(bit_filters_kernel, dim3(1), dim3(64), 0, s, filters, nq);
+    return hipGetLastError();
+}
+
+hipError_t linr_launch_prefilter(const linr_prefilter_args& a, hipStream_t s)
+{
+    if (a.nq == 0 || a.nq > 32 || a.nq > a.B || a.flat_cap % LINR_FLAT_REGIONS != 0 || a.cap == 0 || a.nslots == 0 ||
+        a.row_bytes % 16 != 0)
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(prefilter_zero_kernel, dim3(1), dim3(64), 0, s, a.vcnt);
+    const uint64_t blocks = (a.n + 255) / 256;
+    hipLaunchKernelGGL(prefilter_score_kernel, dim3((uint32_t)(blocks < 8192 ? blocks : 8192)), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(prefilter_counts_kernel, dim3(a.nq), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t linr_launch_prefilter_overflow(const uint32_t* vcnt, uint64_t capacity, uint32_t* out_counts, uint32_t nq, hipStream_t s)
+{
+    hipLaunchKernelGGL(prefilter_overflow_kernel, dim3(1), dim3(64), 0, s, vcnt, capacity, out_counts, nq);
     return hipGetLastError();
 }
 

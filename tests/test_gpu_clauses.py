@@ -48,16 +48,18 @@ def run_case(oracle_mod, kind, d, n, B, k, values, counts, qv, qc, reverse, labe
     ix = L.Index(n, d, DT[kind], 0)
     ix.load(emb, np.zeros(n, np.uint32), row_scale=sc)
     ix.load_clauses(values, counts, reverse)
-    ids, scr, raw, cnt = ix.search_clauses(dev(Q), dev(qv), dev(qc), k, q_scale=dev(qs))
-    torch.cuda.synchronize()
-    got = (ids.cpu().numpy().view(np.uint32), scr.cpu().numpy(), raw.cpu().numpy(), cnt.cpu().numpy().view(np.uint32))
     want = oracle_mod.clause_search(DT[kind], emb, values, counts, Q, qv, qc, reverse, k, row_scale=sc, q_scale=qs, nthreads=4)
-    assert np.array_equal(got[3], want[3]), f"{label}: counts {got[3][:8]} vs {want[3][:8]}"
-    bad = np.nonzero((got[0] != want[0]).any(axis=1))[0]
-    assert bad.size == 0, f"{label}: ids differ for queries {bad[:6]}: gpu {got[0][bad[0]][:8]} oracle {want[0][bad[0]][:8]}"
-    assert got[1].tobytes() == want[1].tobytes(), f"{label}: score bits differ"
-    if kind == "i8":
-        assert np.array_equal(got[2], want[2]), f"{label}: raw scores differ"
+    for prefilter in (False, True):                            # both strategies (Sec. 3.1.1 masking, Sec. 3.1.2 pre-filtering)
+        ids, scr, raw, cnt = ix.search_clauses(dev(Q), dev(qv), dev(qc), k, q_scale=dev(qs), prefilter=prefilter)
+        torch.cuda.synchronize()
+        got = (ids.cpu().numpy().view(np.uint32), scr.cpu().numpy(), raw.cpu().numpy(), cnt.cpu().numpy().view(np.uint32))
+        lab = f"{label} ({'pre-filtering' if prefilter else 'masking'})"
+        assert np.array_equal(got[3], want[3]), f"{lab}: counts {got[3][:8]} vs {want[3][:8]}"
+        bad = np.nonzero((got[0] != want[0]).any(axis=1))[0]
+        assert bad.size == 0, f"{lab}: ids differ for queries {bad[:6]}: gpu {got[0][bad[0]][:8]} oracle {want[0][bad[0]][:8]}"
+        assert got[1].tobytes() == want[1].tobytes(), f"{lab}: score bits differ"
+        if kind == "i8":
+            assert np.array_equal(got[2], want[2]), f"{lab}: raw scores differ"
     ix.close()
     return want
 
@@ -111,6 +113,37 @@ def test_job_search_shape(oracle_mod, low_pass):
     qv = w["q_values"].numpy().view(np.uint64); qc = w["q_counts"].numpy()
     want = run_case(oracle_mod, "bf16", 128, n, B, 2000, values, counts, qv, qc, w["reverse"], f"job clauses low_pass={low_pass}")
     say(f"job clauses low_pass={low_pass}: feasible per query {want[3].tolist()}")
+
+
+def test_prefilter_with_many_feasible_items(oracle_mod):
+    """queries without constraints: every item is feasible, the keys overflow the flat arrays into the segments"""
+    values, counts = S.random_clause_lists(50_000, 1, 1, 5, seed=2)
+    qv = np.zeros((3, 2), np.uint64); qc = np.zeros((3, 1), np.uint8)
+    qv[1, 0] = values[0, 0]; qc[1, 0] = 1                         # one query keeps a constraint
+    run_case(oracle_mod, "i8", 64, 50_000, 3, 10, values, counts, qv, qc, 0, "everything feasible")
+
+
+def test_prefilter_reports_overflow():
+    """more feasible items than the candidate arrays hold: the count says so (0xFFFFFFFF), other queries are answered"""
+    import torch
+    import paper_2407_13218_amd as L
+    n = 1_200_000
+    rng = np.random.default_rng(0)
+    emb = rng.integers(-127, 128, (n, 64), dtype=np.int8)
+    values = np.full((n, 1), 7, np.uint64); values[::1000, 0] = 9
+    counts = np.ones((n, 1), np.uint8)
+    ix = L.Index(n, 64, S.I8, 0)
+    ix.load(emb, np.zeros(n, np.uint32))
+    ix.load_clauses(values, counts, 0)
+    qv = np.array([[7], [9]], np.uint64); qc = np.ones((2, 1), np.uint8)
+    Q = dev(emb[:2].reshape(2, 1, 64))
+    ids, sc, raw, cnt = ix.search_clauses(Q, dev(qv), dev(qc), 5, prefilter=True)
+    torch.cuda.synchronize()
+    cnt = cnt.cpu().numpy().view(np.uint32)
+    assert cnt[0] == 0xFFFFFFFF and cnt[1] == 5
+    ids2, _, raw2, _ = ix.search_clauses(Q, dev(qv), dev(qc), 5)
+    assert np.array_equal(ids.cpu().numpy()[1], ids2.cpu().numpy()[1]) and np.array_equal(raw.cpu().numpy()[1], raw2.cpu().numpy()[1])
+    ix.close()
 
 
 def test_multi_embedding_queries(oracle_mod):
