@@ -980,7 +980,7 @@ static int clause_layout(const linr_index* v, uint32_t B, uint32_t m, uint32_t k
     const uint64_t items = v->dead_bit ? v->capacity : v->n;
     *off_words = align_up(*inner, 256);
     *off_filters = align_up(*off_words + items * 4, 256);
-    *total = align_up(*off_filters + 32 * sizeof(linr_filter) + 256, 256);     // + 32 counters of the pre-filtering strategy
+    *total = align_up(*off_filters + 32 * sizeof(linr_filter) + 4096, 256);    // + 32 counters (a 128-byte line each) of the pre-filtering strategy
     return LINR_OK;
 }
 
@@ -1068,7 +1068,6 @@ static int search_clauses_impl(const linr_index* ix, const void* Q, const float*
             pa.flat = (unsigned long long*)(ws + pp.off_flat); pa.flat_cap = pp.flat_cap;
             pa.seg = (unsigned long long*)(ws + pp.off_seg); pa.nslots = pp.nslots; pa.cap = pp.cap; pa.B = Bg;
             pa.vcnt = vcnt; pa.gcnt = gcnt; pa.fvalid = fvalid; pa.cnt = cnt;
-            HIP_TRY(linr_launch_prefilter(pa, st));
             linr_merge_args ma;
             memset(&ma, 0, sizeof(ma));
             ma.tau = tau; ma.cnt = cnt; ma.seg = pa.seg; ma.nslots = pp.nslots; ma.cap = pp.cap; ma.B = Bg; ma.k = k;
@@ -1078,6 +1077,14 @@ static int search_clauses_impl(const linr_index* ix, const void* Q, const float*
             ma.Q = pa.Q; ma.q_scale = q_scale ? q_scale + b0 : nullptr; ma.m = m;
             ma.out_ids = out_ids + (uint64_t)b0 * k; ma.out_scores = out_scores + (uint64_t)b0 * k;
             ma.out_raw = out_raw ? out_raw + (uint64_t)b0 * k : nullptr; ma.out_counts = out_counts + b0;
+            // phase 0: every 8th run of items, then a merge that publishes the k-th key found; phase 1: the rest,
+            // keeping only keys that are not below it; final merge (the scans' disjoint sweeps, on candidate lists)
+            pa.phase = 0; pa.tau = nullptr;
+            HIP_TRY(linr_launch_prefilter(pa, st));
+            ma.final_level = 0;
+            HIP_TRY(linr_launch_merge(ma, st));
+            pa.phase = 1; pa.tau = tau;
+            HIP_TRY(linr_launch_prefilter(pa, st));
             ma.final_level = 1;
             HIP_TRY(linr_launch_merge(ma, st));
             HIP_TRY(linr_launch_prefilter_overflow(vcnt, (uint64_t)pp.flat_cap + (uint64_t)pp.nslots * pp.cap, out_counts + b0, Bg, st));

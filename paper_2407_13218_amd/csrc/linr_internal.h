@@ -150,10 +150,14 @@ struct linr_prefilter_args {
     const uint32_t* words; uint64_t n; uint32_t nq;
     int dtype, vk; const void* emb; const float* row_scale; uint32_t row_bytes, d; const void* Q; uint32_t m;
     unsigned long long* flat; uint32_t flat_cap; unsigned long long* seg; uint32_t nslots, cap, B;
-    uint32_t* vcnt;             // [nq] feasible items found per query (zeroed by the launcher's first kernel)
-    uint32_t* gcnt; uint32_t* fvalid; uint32_t* cnt;      // the merge's view of where the keys are (written by the second)
+    uint32_t* vcnt;             // [32 x 32 words] per query, a 128-byte line each: word 0 keys appended in this phase,
+                                // word 1 sticky "the candidate arrays were too small"
+    uint32_t* gcnt; uint32_t* fvalid; uint32_t* cnt;      // the merge's view of where the keys are
+    // two phases, as the scans' sweeps: phase 0 scores every 8th run of items and a merge publishes the k-th key found
+    // (tau); phase 1 scores the other runs and keeps only keys that are not below it
+    uint32_t phase; const unsigned long long* tau;
 };
-hipError_t linr_launch_prefilter(const linr_prefilter_args& a, hipStream_t s);
+hipError_t linr_launch_prefilter(const linr_prefilter_args& a, hipStream_t s);   // one phase: zero, score, counts
 // out_counts[b] = 0xFFFFFFFF where vcnt[b] > capacity (run behind the merge)
 hipError_t linr_launch_prefilter_overflow(const uint32_t* vcnt, uint64_t capacity, uint32_t* out_counts, uint32_t nq, hipStream_t s);
 struct linr_rescore_args {

@@ -1842,53 +1842,119 @@ __device__ __forceinline__ float dot_bf16_row(const uint16_t* q, const uint16_t*
     return s;
 }
 
-__global__ void __launch_bounds__(64) prefilter_zero_kernel(uint32_t* vcnt) { if (threadIdx.x < 32) vcnt[threadIdx.x] = 0u; }
+#define LINR_VCNT_STRIDE 32            // words between two queries' counters (a 128-byte line each: no false sharing)
+#define LINR_PREFILTER_RUN 8           // 64-item groups a wave takes at a time (one counter update per query and run)
+
+#define LINR_PREFILTER_SAMPLE 8        // phase 0 takes every 8th run
+
+__global__ void __launch_bounds__(64) prefilter_zero_kernel(uint32_t* vcnt, uint32_t phase)
+{
+    if (threadIdx.x < 32) {
+        vcnt[threadIdx.x * LINR_VCNT_STRIDE] = 0u;
+        if (phase == 0) vcnt[threadIdx.x * LINR_VCNT_STRIDE + 1] = 0u;
+    }
+}
 
 __global__ void __launch_bounds__(256) prefilter_score_kernel(linr_prefilter_args A)
 {
+    constexpr int R = LINR_PREFILTER_RUN;
+    __shared__ uint32_t queue_all[256 / 64][64 * R];            // per wave: the run's feasible items of one query ...
+    __shared__ u64 keys_all[256 / 64][64 * R];                  // ... and their keys
     const int lane = threadIdx.x & 63;
-    const u64 n_round = (A.n + 63) / 64 * 64;                     // whole waves stay together for the ballots
-    for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n_round; i += (u64)gridDim.x * blockDim.x) {
-        const uint32_t w = i < A.n ? A.words[i] : 0u;
-        if (!wave_any(w != 0u)) continue;
-        const char* x = (const char*)A.emb + i * A.row_bytes;
+    uint32_t* queue = queue_all[threadIdx.x >> 6];
+    u64* keys = keys_all[threadIdx.x >> 6];
+    const u64 wave = ((u64)blockIdx.x * blockDim.x + threadIdx.x) >> 6, n_waves = ((u64)gridDim.x * blockDim.x) >> 6;
+    const u64 n_runs = (A.n + 64 * R - 1) / (64 * R);
+    for (u64 rr = wave; ; rr += n_waves) {
+        // phase 0: runs 0, 8, 16, ...; phase 1: the others
+        const u64 run = A.phase == 0 ? rr * LINR_PREFILTER_SAMPLE
+                                     : rr + rr / (LINR_PREFILTER_SAMPLE - 1) + 1;
+        if (run >= n_runs) break;
+        const u64 run0 = run * (64 * R);
+        uint32_t w[R];
+        uint32_t any = 0u;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const u64 i = run0 + (u64)r * 64 + lane;
+            w[r] = i < A.n ? A.words[i] : 0u;
+            any |= w[r];
+        }
+        if (!wave_any(any != 0u)) continue;
         for (uint32_t b = 0; b < A.nq; ++b) {
-            const bool has = (w >> b) & 1u;
-            const u64 bal = wave_ballot(has);
-            if (bal == 0ull) continue;
-            uint32_t base = 0;
-            const int leader = __ffsll((long long)bal) - 1;
-            if (lane == leader) base = atomicAdd(&A.vcnt[b], (uint32_t)__popcll(bal));
-            base = __shfl(base, leader);
-            if (!has) continue;
-            const uint32_t pos = base + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
-            uint32_t hi;
-            if (A.dtype == LINR_I8) {
-                int best = INT_MIN;
-                for (uint32_t e = 0; e < A.m; ++e) {
-                    const int r = dot_i8_row((const int8_t*)A.Q + ((u64)b * A.m + e) * A.row_bytes, (const int8_t*)x, A.d);
-                    best = r > best ? r : best;
-                }
-                hi = A.vk == LINR_VK_I8_SCALED ? ord_f32((float)best * A.row_scale[i]) : ord_i32(best);
-            } else {
-                float best = -INFINITY;
-                for (uint32_t e = 0; e < A.m; ++e) {
-                    const char* q = (const char*)A.Q + ((u64)b * A.m + e) * A.row_bytes;
-                    const float r = A.dtype == LINR_F32 ? dot_f32_row((const float*)q, (const float*)x, A.d)
-                                                        : dot_bf16_row((const uint16_t*)q, (const uint16_t*)x, A.d);
-                    best = fmaxf(best, r);
-                }
-                hi = ord_f32(best);
+            // the run's feasible items of query b, densely into the queue
+            uint32_t total = 0;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const bool has = (w[r] >> b) & 1u;
+                const u64 bal = wave_ballot(has);
+                if (has) queue[total + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull))] = (uint32_t)(r * 64 + lane);
+                total += (uint32_t)__popcll(bal);
             }
-            const u64 key = ((u64)hi << 32) | (u64)(uint32_t)~(uint32_t)i;
-            if (pos < A.flat_cap) {
-                const uint32_t rcap = A.flat_cap / LINR_FLAT_REGIONS;
-                A.flat[(u64)b * A.flat_cap + (u64)(pos % LINR_FLAT_REGIONS) * rcap + pos / LINR_FLAT_REGIONS] = key;
-            } else {
-                const u64 q2 = pos - A.flat_cap;
-                const u64 slot = q2 / A.cap;
-                if (slot < A.nslots) A.seg[(slot * A.B + b) * A.cap + q2 % A.cap] = key;
+            if (total == 0u) continue;
+            const u64 bound = A.tau ? A.tau[b] : 0ull;
+            wave_sync();
+            // sixteen lanes per feasible (item, query) pair: each reads 16 bytes of every 256-byte stretch of the row
+            // (one coalesced load per pair and stretch), the partial sums meet through four exchanges
+            const int grp = lane >> 4, sub = lane & 15;
+            for (uint32_t j0 = 0; j0 < total; j0 += 4) {
+                const uint32_t j = j0 + (uint32_t)grp;
+                const bool valid = j < total;
+                const u64 i = run0 + (valid ? queue[j] : 0u);
+                const char* x = (const char*)A.emb + i * A.row_bytes;
+                uint32_t hi;
+                if (A.dtype == LINR_I8) {
+                    int best = INT_MIN;
+                    for (uint32_t e = 0; e < A.m; ++e) {
+                        const char* q = (const char*)A.Q + ((u64)b * A.m + e) * A.row_bytes;
+                        int part = 0;
+                        if (valid)
+                            for (uint32_t off = (uint32_t)sub * 16; off < A.row_bytes; off += 256)
+                                part += dot_i8_row((const int8_t*)(q + off), (const int8_t*)(x + off), 16);
+                        part += __shfl_xor(part, 8); part += __shfl_xor(part, 4); part += __shfl_xor(part, 2); part += __shfl_xor(part, 1);
+                        best = part > best ? part : best;
+                    }
+                    hi = A.vk == LINR_VK_I8_SCALED ? ord_f32((float)best * (valid ? A.row_scale[i] : 0.0f)) : ord_i32(best);
+                } else {
+                    float best = -INFINITY;
+                    for (uint32_t e = 0; e < A.m; ++e) {
+                        const char* q = (const char*)A.Q + ((u64)b * A.m + e) * A.row_bytes;
+                        float part = 0.0f;
+                        if (valid)
+                            for (uint32_t off = (uint32_t)sub * 16; off < A.row_bytes; off += 256)
+                                part += A.dtype == LINR_F32 ? dot_f32_row((const float*)(q + off), (const float*)(x + off), 4)
+                                                            : dot_bf16_row((const uint16_t*)(q + off), (const uint16_t*)(x + off), 8);
+                        part += __shfl_xor(part, 8); part += __shfl_xor(part, 4); part += __shfl_xor(part, 2); part += __shfl_xor(part, 1);
+                        best = fmaxf(best, part);
+                    }
+                    hi = ord_f32(best);
+                }
+                if (valid && sub == 0) {
+                    const u64 key = ((u64)hi << 32) | (u64)(uint32_t)~(uint32_t)i;
+                    keys[j] = key < bound ? 0ull : key;        // below the k-th key found so far: cannot matter any more
+                }
             }
+            wave_sync();
+            // the surviving keys go where the merge looks for candidates; one counter update per query and run
+            for (uint32_t j0 = 0; j0 < total; j0 += 64) {
+                const uint32_t j = j0 + (uint32_t)lane;
+                const u64 key = j < total ? keys[j] : 0ull;
+                const u64 bal = wave_ballot(key != 0ull);
+                if (bal == 0ull) continue;
+                uint32_t base = 0;
+                if (lane == 0) base = atomicAdd(&A.vcnt[b * LINR_VCNT_STRIDE], (uint32_t)__popcll(bal));
+                base = __shfl(base, 0);
+                if (key == 0ull) continue;
+                const uint32_t pos = base + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+                if (pos < A.flat_cap) {
+                    const uint32_t rcap = A.flat_cap / LINR_FLAT_REGIONS;
+                    A.flat[(u64)b * A.flat_cap + (u64)(pos % LINR_FLAT_REGIONS) * rcap + pos / LINR_FLAT_REGIONS] = key;
+                } else {
+                    const u64 q2 = pos - A.flat_cap;
+                    const u64 slot = q2 / A.cap;
+                    if (slot < A.nslots) A.seg[(slot * A.B + b) * A.cap + q2 % A.cap] = key;
+                }
+            }
+            wave_sync();
         }
     }
 }
@@ -1897,7 +1963,8 @@ __global__ void __launch_bounds__(256) prefilter_score_kernel(linr_prefilter_arg
 __global__ void __launch_bounds__(256) prefilter_counts_kernel(linr_prefilter_args A)
 {
     const uint32_t b = blockIdx.x;
-    const uint32_t total = A.vcnt[b];
+    const uint32_t total = A.vcnt[b * LINR_VCNT_STRIDE];
+    if (threadIdx.x == 0 && (u64)total > (u64)A.flat_cap + (u64)A.nslots * A.cap) A.vcnt[b * LINR_VCNT_STRIDE + 1] = 1u;
     const uint32_t in_flat = total < A.flat_cap ? total : A.flat_cap;
     for (uint32_t r = threadIdx.x; r < LINR_FLAT_REGIONS; r += blockDim.x) {
         const u64 ci = ((u64)b * LINR_FLAT_REGIONS + r) * LINR_COUNTER_STRIDE;
@@ -1916,7 +1983,8 @@ __global__ void __launch_bounds__(256) prefilter_counts_kernel(linr_prefilter_ar
 __global__ void __launch_bounds__(64) prefilter_overflow_kernel(const uint32_t* vcnt, uint64_t capacity, uint32_t* out_counts,
                                                                 uint32_t nq)
 {
-    if (threadIdx.x < nq && (uint64_t)vcnt[threadIdx.x] > capacity) out_counts[threadIdx.x] = 0xFFFFFFFFu;
+    (void)capacity;
+    if (threadIdx.x < nq && vcnt[threadIdx.x * LINR_VCNT_STRIDE + 1] != 0u) out_counts[threadIdx.x] = 0xFFFFFFFFu;
 }
 
 // ---------------------------------------------------------------------------
@@ -2194,14 +2262,13 @@ __device__ __forceinline__ void for_each_candidate(const linr_merge_args& A, con
         const u64* src = piece_ptr(A, b, p);
         for (uint32_t j = lane; j < c; j += 64) f(src[j]);
     }
-    if (mode == MERGE_FROM_ALL) {
-        for (uint32_t g = tid; g < Mtot - m_flat; g += MT) {
-            uint32_t lo = 0, hi = A.nslots;
-            while (hi - lo > 1) {
-                uint32_t mid = (lo + hi) >> 1;
-                if (S.u.pre[mid] <= g) lo = mid; else hi = mid;
-            }
-            f(A.seg[((u64)lo * A.B + b) * A.cap + (g - S.u.pre[lo])]);
+    if (mode == MERGE_FROM_ALL) {                      // wave w walks the segments of slots w, w + 16, ...
+        const uint32_t* cnt = A.cnt + (u64)b * A.nslots;
+        for (uint32_t sl = wave; sl < A.nslots; sl += MT / 64) {
+            uint32_t c = cnt[sl];
+            if (c > A.cap) c = A.cap;
+            const u64* src = A.seg + ((u64)sl * A.B + b) * A.cap;
+            for (uint32_t j = lane; j < c; j += 64) f(src[j]);
         }
     }
 }
@@ -2622,8 +2689,8 @@ hipError_t linr_launch_prefilter(const linr_prefilter_args& a, hipStream_t s)
     if (a.nq == 0 || a.nq > 32 || a.nq > a.B || a.flat_cap % LINR_FLAT_REGIONS != 0 || a.cap == 0 || a.nslots == 0 ||
         a.row_bytes % 16 != 0)
         return hipErrorInvalidValue;
-    hipLaunchKernelGGL(prefilter_zero_kernel, dim3(1), dim3(64), 0, s, a.vcnt);
-    const uint64_t blocks = (a.n + 255) / 256;
+    hipLaunchKernelGGL(prefilter_zero_kernel, dim3(1), dim3(64), 0, s, a.vcnt, a.phase);
+    const uint64_t blocks = (a.n + 256 * LINR_PREFILTER_RUN - 1) / (256 * LINR_PREFILTER_RUN);
     hipLaunchKernelGGL(prefilter_score_kernel, dim3((uint32_t)(blocks < 8192 ? blocks : 8192)), dim3(256), 0, s, a);
     hipLaunchKernelGGL(prefilter_counts_kernel, dim3(a.nq), dim3(256), 0, s, a);
     return hipGetLastError();

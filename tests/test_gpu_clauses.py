@@ -123,11 +123,13 @@ def test_prefilter_with_many_feasible_items(oracle_mod):
     run_case(oracle_mod, "i8", 64, 50_000, 3, 10, values, counts, qv, qc, 0, "everything feasible")
 
 
-def test_prefilter_reports_overflow():
-    """more feasible items than the candidate arrays hold: the count says so (0xFFFFFFFF), other queries are answered"""
+def test_prefilter_with_a_million_feasible_items_and_overflow():
+    """1.2 M feasible items for one query: the two phases (a sample, then the rest against the bound the sample gave)
+    keep the candidate arrays small and both strategies agree; with a deliberately small workspace plan the sample
+    itself does not fit and the count says so (0xFFFFFFFF) while the other query is still answered"""
     import torch
     import paper_2407_13218_amd as L
-    n = 1_200_000
+    n = 2_000_000
     rng = np.random.default_rng(0)
     emb = rng.integers(-127, 128, (n, 64), dtype=np.int8)
     values = np.full((n, 1), 7, np.uint64); values[::1000, 0] = 9
@@ -137,11 +139,19 @@ def test_prefilter_reports_overflow():
     ix.load_clauses(values, counts, 0)
     qv = np.array([[7], [9]], np.uint64); qc = np.ones((2, 1), np.uint8)
     Q = dev(emb[:2].reshape(2, 1, 64))
+    ids2, _, raw2, cnt2 = ix.search_clauses(Q, dev(qv), dev(qc), 5)
     ids, sc, raw, cnt = ix.search_clauses(Q, dev(qv), dev(qc), 5, prefilter=True)
     torch.cuda.synchronize()
+    assert np.array_equal(cnt.cpu().numpy(), cnt2.cpu().numpy()) and np.array_equal(ids.cpu().numpy(), ids2.cpu().numpy())
+    assert np.array_equal(raw.cpu().numpy(), raw2.cpu().numpy())
+    L.set_tuning(blocks_per_cu=1)                             # 1024 slots x 192 keys + 4096: less than the 250 000 sampled keys
+    try:
+        ids, sc, raw, cnt = ix.search_clauses(Q, dev(qv), dev(qc), 5, prefilter=True)
+        torch.cuda.synchronize()
+    finally:
+        L.set_tuning()
     cnt = cnt.cpu().numpy().view(np.uint32)
     assert cnt[0] == 0xFFFFFFFF and cnt[1] == 5
-    ids2, _, raw2, _ = ix.search_clauses(Q, dev(qv), dev(qc), 5)
     assert np.array_equal(ids.cpu().numpy()[1], ids2.cpu().numpy()[1]) and np.array_equal(raw.cpu().numpy()[1], raw2.cpu().numpy()[1])
     ix.close()
 
