@@ -97,8 +97,10 @@ int linr_index_create(linr_index** out, uint64_t capacity, uint32_t d, int dtype
  * Make `n` items resident (Sec. 4.2: embeddings plus filter attributes form the
  * served model).  Row i of `emb` ([n][d], row-major, 16-byte aligned) becomes
  * item id i.  `mask` is [n]; `ts` is [n] or NULL (no timestamp column).
- * A later load replaces the previous contents.  `src` is a LINR_SRC_* value.
- * bf16 values are passed as their 16-bit patterns.
+ * A later load replaces the previous contents (and ends live updates, clause columns
+ * and 1-bit codes of the previous contents).  `src` is a LINR_SRC_* value; columns the
+ * library copies are allocated for the whole capacity, so that live updates can add
+ * items in place.  bf16 values are passed as their 16-bit patterns.
  * int8: symmetric codes with one positive fp32 scale per row; row_scale == NULL
  * selects raw ranking (see linr_search_filtered).  This quantised layout is this
  * library's memory-saving representation (the paper's own is the 1-bit code of
@@ -332,7 +334,7 @@ int linr_set_tuning(const linr_tuning*);
  * finished.  *n_stages receives the number of stages, kinds[s] a LINR_STAGE_* value
  * and stage_items[s] the number of items a scan stage visits.
  */
-#define LINR_MAX_STAGES 64
+#define LINR_MAX_STAGES 160
 enum { LINR_STAGE_INIT = 0, LINR_STAGE_SCAN = 1, LINR_STAGE_MERGE = 2, LINR_STAGE_FILTER = 3 };
 int linr_search_filtered_timed(const linr_index*, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
                          const linr_filter* filters, uint32_t k,

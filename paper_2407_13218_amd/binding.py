@@ -17,7 +17,7 @@ MAX_K = 2048
 MAX_M = 8
 SRC_HOST, SRC_DEVICE_COPY, SRC_DEVICE_BORROW = 0, 1, 2
 FILTERS_ON_DEVICE, FILTERS_ON_HOST = 0, 1
-MAX_STAGES = 64
+MAX_STAGES = 160
 STAGE_NAMES = {0: "init", 1: "scan", 2: "merge", 3: "filter"}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
