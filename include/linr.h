@@ -60,7 +60,7 @@ enum {
 };
 
 #define LINR_MAX_ANY 4
-#define LINR_MAX_K   2048
+#define LINR_MAX_K   8192
 #define LINR_MAX_M   8
 #define LINR_NO_ID   0xFFFFFFFFu
 

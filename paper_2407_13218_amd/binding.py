@@ -13,7 +13,7 @@ import numpy as np
 
 F32, BF16, I8, BITS = 0, 1, 2, 3
 NO_ID = 0xFFFFFFFF
-MAX_K = 2048
+MAX_K = 8192
 MAX_M = 8
 SRC_HOST, SRC_DEVICE_COPY, SRC_DEVICE_BORROW = 0, 1, 2
 FILTERS_ON_DEVICE, FILTERS_ON_HOST = 0, 1

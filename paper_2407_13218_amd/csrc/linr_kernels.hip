@@ -2222,14 +2222,17 @@ __global__ void init_kernel(u64* tau, uint32_t* ccnt, uint32_t* gcnt, uint32_t* 
 // the result.
 // ---------------------------------------------------------------------------
 #define MT 1024
-#define MERGE_LDS_KEYS 14336                    /* 112 KB of the 160 KB a workgroup may use */
 #define NPIECE (LINR_FLAT_REGIONS + 1)
-struct MergeLds {
+// LDS of a merge workgroup, for k up to KMAX: the winners (KMAX keys) and, when all candidates fit and nothing was
+// spilled, the candidates themselves -- 112 KB of the 160 KB a workgroup may use for k <= 2048, 80 KB above that
+template <int KMAX>
+struct MergeLdsT {
+    static constexpr uint32_t LDS_KEYS = KMAX <= 2048 ? 14336u : 10240u;
     union {
-        u64 keys[MERGE_LDS_KEYS];                 // all candidates, when they fit and nothing was spilled
+        u64 keys[LDS_KEYS];                       // all candidates, when they fit and nothing was spilled
         uint32_t pre[LINR_MAX_SLOTS + 1];         // exclusive prefix of segment counts (spilled case)
     } u;
-    u64 win[LINR_MAX_K];
+    u64 win[KMAX];
     uint32_t part[MT];
     uint32_t hist[256];
     uint32_t ppre[NPIECE + 1];                    // exclusive prefix over carry + flat regions
@@ -2248,8 +2251,8 @@ __device__ __forceinline__ const u64* piece_ptr(const linr_merge_args& A, uint32
 // Calls f(key) once for every candidate of the query, by the whole workgroup.  From LDS when they were
 // staged there; else wave w walks pieces w, w + 16, ... with consecutive lanes on consecutive keys; the
 // per-slot segments (spilled case only) are located through the prefix array.
-template <typename F>
-__device__ __forceinline__ void for_each_candidate(const linr_merge_args& A, const MergeLds& S, int mode, uint32_t m_flat,
+template <typename LDS, typename F>
+__device__ __forceinline__ void for_each_candidate(const linr_merge_args& A, const LDS& S, int mode, uint32_t m_flat,
                                                    uint32_t Mtot, uint32_t b, uint32_t tid, F f)
 {
     if (mode == MERGE_FROM_LDS) {
@@ -2287,9 +2290,10 @@ __device__ __forceinline__ int dot_i8_row(const int8_t* q, const int8_t* x, uint
     return s;
 }
 
+template <int KMAX>
 __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
 {
-    __shared__ MergeLds S;
+    __shared__ MergeLdsT<KMAX> S;
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
     const uint32_t ns = A.nslots;
     uint32_t* cnt = A.cnt + (u64)b * ns;
@@ -2346,7 +2350,7 @@ __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
         if (tid == MT - 1) S.u.pre[ns] = S.part[MT - 1];
         __syncthreads();
         Mtot += S.u.pre[ns];
-    } else if (m_flat <= MERGE_LDS_KEYS) {
+    } else if (m_flat <= MergeLdsT<KMAX>::LDS_KEYS) {
         // stage everything in LDS: wave w copies pieces w, w + 16, ...
         const uint32_t wave = tid >> 6, lane = tid & 63;
         for (uint32_t p = wave; p < NPIECE; p += MT / 64) {
@@ -2401,7 +2405,7 @@ __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
     for_each_candidate(A, S, mode, m_flat, Mtot, b, tid, [&](u64 key) {
         if (key >= kth) {
             uint32_t p = atomicAdd(&S.nwin, 1u);
-            if (p < LINR_MAX_K) S.win[p] = key;
+            if (p < (uint32_t)KMAX) S.win[p] = key;
         }
     });
     __syncthreads();
@@ -2488,7 +2492,8 @@ hipError_t linr_launch_init(unsigned long long* tau, uint32_t* ccnt, uint32_t* g
 hipError_t linr_launch_merge(const linr_merge_args& a, hipStream_t s)
 {
     if (a.nslots > LINR_MAX_SLOTS || a.k > LINR_MAX_K) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(merge_kernel, dim3(a.B), dim3(MT), 0, s, a);
+    if (a.k <= 2048) hipLaunchKernelGGL(merge_kernel<2048>, dim3(a.B), dim3(MT), 0, s, a);
+    else hipLaunchKernelGGL(merge_kernel<LINR_MAX_K>, dim3(a.B), dim3(MT), 0, s, a);
     return hipGetLastError();
 }
 

@@ -83,7 +83,8 @@ def run_bits_case(oracle_mod, codes, k_bits, mask, ts, qbits, filt, T, label, ho
 
 @pytest.mark.parametrize("n,k_bits,B,T,with_ts", [(1, 64, 1, 1, False), (255, 64, 3, 10, False), (100_003, 64, 17, 1000, True),
                                                   (60_000, 128, 70, 500, False), (30_000, 256, 5, 2048, True),
-                                                  (50_000, 32, 9, 100, False), (20_000, 192, 130, 64, False)])
+                                                  (50_000, 32, 9, 100, False), (20_000, 192, 130, 64, False),
+                                                  (400_000, 64, 3, 8192, False)])
 def test_bits_search_exact(oracle_mod, n, k_bits, B, T, with_ts):
     say(f"bits search n={n} k_bits={k_bits} B={B} T={T} ts={with_ts}")
     rng = np.random.default_rng(n + B)
@@ -114,7 +115,8 @@ def test_bits_search_few_levels_many_ties(oracle_mod):
             L.set_tuning()
 
 
-@pytest.mark.parametrize("dtype,d,k_bits,T,k", [(S.F32, 64, 64, 400, 50), (S.BF16, 128, 64, 1000, 100), (S.F32, 64, 64, 2048, 2048)])
+@pytest.mark.parametrize("dtype,d,k_bits,T,k", [(S.F32, 64, 64, 400, 50), (S.BF16, 128, 64, 1000, 100), (S.F32, 64, 64, 2048, 2048),
+                                                (S.BF16, 64, 64, 8192, 3000)])
 def test_two_stage_against_the_oracle(oracle_mod, dtype, d, k_bits, T, k):
     import torch
     import paper_2407_13218_amd as L

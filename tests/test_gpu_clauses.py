@@ -95,6 +95,7 @@ def test_hand_example_on_the_gpu(oracle_mod):
     ("bf16", 128, 9_000, 1, 300, 1, 4, 6, 0),         # one clause, long lists
     ("i8", 64, 2_000, 33, 64, 8, 1, 2, 0xFF),         # eight reverse clauses
     ("bf16", 64, 12_345, 16, 2000, 2, 2, 3, 0),       # k above the number of feasible items for most queries
+    ("i8", 64, 150_000, 3, 6000, 1, 1, 3, 0),         # k above 2048
 ])
 def test_random_clause_lists(oracle_mod, kind, d, n, B, k, C, max_len, qlen, reverse):
     domain = 6

@@ -59,7 +59,8 @@ def test_hand_example_on_gpu(dtype):
 
 @pytest.mark.parametrize("scaled", [True, False])
 @pytest.mark.parametrize("n,B,k", [(1, 1, 1), (63, 3, 2), (1000, 17, 100), (100_003, 16, 1000), (50_000, 40, 2048),
-                                   (300_000, 1, 1000), (20_000, 130, 500)])
+                                   (300_000, 1, 1000), (20_000, 130, 500), (200_000, 4, 5000), (1_000_000, 2, 8192),
+                                   (6_000, 33, 8192)])
 def test_int8_exact(oracle_mod, scaled, n, B, k):
     say(f"int8 exact scaled={scaled} n={n} B={B} k={k}")
     w = rand_int8_workload(100 + n % 97 + B, n, 64, B, scaled=scaled, with_ts=(B % 2 == 1))
@@ -86,6 +87,13 @@ def test_config2_shape_bf16(oracle_mod):
     w = S.config2(n=200_000, B=40, k=1000, p=0.5, chunk=100_000)
     gpu = run_gpu(to_cuda(w))
     assert_float_rule(oracle_mod, w, gpu, w["k"], label="cfg2")
+
+
+def test_config2_shape_bf16_large_k(oracle_mod):
+    say("config 2 shape (bf16 d=128), N=300k, B=6, k=7000")
+    w = S.config2(n=300_000, B=6, k=7000, p=0.9, chunk=100_000)
+    gpu = run_gpu(to_cuda(w))
+    assert_float_rule(oracle_mod, w, gpu, w["k"], label="cfg2 k=7000")
 
 
 def test_config3_shape_int8_ts(oracle_mod):
@@ -290,7 +298,7 @@ def test_argument_errors_on_device():
         L.index_load_int8(ix.handle, w["emb"], w["scale"], w["mask"], None, 1001, L.SRC_DEVICE_BORROW)
     assert e.value.code == -5
     ix.load(w["emb"], w["mask"], row_scale=w["scale"])
-    for k, code in ((0, -4), (2049, -4)):
+    for k, code in ((0, -4), (L.MAX_K + 1, -4)):
         with pytest.raises(L.LinrError) as e:
             ix.search(w["Q"], w["filters"], k)
         assert e.value.code == code
