@@ -242,6 +242,54 @@ def clause_leg(L, S, args, dev):
                         f"reverse match, + title match for the low pass rate), top-{k}", "rows": rows, "cpu_baseline": oracle_s}
 
 
+def two_stage_leg(L, S, args, dev):
+    """Latency / recall of the two-stage search (Sec. 3.2 and the trade-off figure of Sec. 5.3: 1-bit pre-selection of T
+    items, exact re-scoring, top-k) against the exact search on config 2 at full size (1e7 x d128 bf16, 25 % pass rate),
+    128-bit Sign-OPORP codes, k = 100, batch 16.  Recall = share of the exact top-k that the two-stage result contains."""
+    import numpy as np
+    import torch
+    B, k, kb = 16, 100, 128
+    w = S.config2(device=dev, B=B, k=k, p=0.5)
+    n, d = w["emb"].shape[0], 128
+    ix = L.Index(n, d, S.BF16, 0)
+    ix.load(w["emb"], w["mask"])
+    perm, signs = S.oporp_draw(d, 0)
+    ix.build_bits(perm, signs, kb)
+    filt = torch.from_numpy(np.ascontiguousarray(w["filters"]).view(np.uint8).copy()).to(dev)
+    Q = w["Q"].reshape(B, d).contiguous()
+    stream = torch.cuda.current_stream().cuda_stream
+    ids = torch.empty((B, k), dtype=torch.int32, device=dev); sc = torch.empty((B, k), dtype=torch.float32, device=dev)
+    cnt = torch.empty((B,), dtype=torch.int32, device=dev)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+    nb = ix.workspace_bytes(B, 1, k)
+    ws = torch.empty(nb, dtype=torch.uint8, device=dev)
+    exact_ms = timed(lambda: L.search_filtered(ix.handle, w["Q"], None, B, 1, filt, k, ids, sc, None, cnt, ws, nb, stream,
+                                               L.FILTERS_ON_DEVICE))
+    truth = [set(r.tolist()) for r in ids.cpu().numpy()]
+    rows = []
+    for T in (1000, 2000, 4000, 8192):
+        nb2 = L.search_two_stage_workspace_bytes(ix.handle, B, T, k)
+        ws2 = torch.empty(nb2, dtype=torch.uint8, device=dev)
+        ms = timed(lambda: L.search_two_stage(ix.handle, Q, B, filt, T, k, ids, sc, cnt, ws2, nb2, stream, L.FILTERS_ON_DEVICE))
+        got = ids.cpu().numpy()
+        recall = float(np.mean([len(truth[b] & set(got[b].tolist())) / k for b in range(B)]))
+        rows.append(dict(T=T, ms_per_search=round(ms, 4), recall_at_k=round(recall, 4)))
+        log(f"  two-stage T={T:5d}: {ms:.3f} ms/search, recall@{k} {recall:.3f} (exact search {exact_ms:.3f} ms)")
+        del ws2
+    ix.close()
+    return {"workload": f"config 2 at full size: {n} x d128 bf16, 25 % pass rate, B = {B}, k = {k}, {kb}-bit codes",
+            "exact_ms_per_search": round(exact_ms, 4), "rows": rows}
+
+
 def live_update_leg(L, S, args, dev):
     """Search latency next to concurrent updates (Sec. 5.3 "Impact of Live Model Update on Inference", Table 5: requests
     issued serially, batch 1 and 5, 0 / 300 / 600 updates per second; here also 20 000 per second in batches of 100).
@@ -424,6 +472,11 @@ def main():
     if not args.no_quantised:
         quant = quantised_leg(L, S, base, index_cols, N, k, args, dev)
 
+    two_stage = None
+    if not args.no_quantised:
+        log("two-stage search: latency and recall against the exact search")
+        two_stage = two_stage_leg(L, S, args, dev)
+
     clauses = None
     if not args.no_clauses:
         log("clause lists: the paper's benchmark shape (15.5 M x d128, top-2000)")
@@ -473,6 +526,7 @@ def main():
         "stage_ms": {"largest_sweep": head["largest_sweep_ms"], "all_sweeps": head["all_sweeps_ms"], "merges": head["merges_ms"]},
         "sweep": sweep,
         "quantised": quant,
+        "two_stage": two_stage,
         "live_update": live,
         "clause_lists": clauses,
     }
