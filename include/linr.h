@@ -216,15 +216,24 @@ int linr_search_two_stage(const linr_index*, const void* Q, uint32_t B, const li
  *     uint8, q_width <= LINR_MAX_QUERY_ROW.  Queries are answered in groups of 32: one pass
  *     over the clause columns writes, per item, a word whose bit b says "feasible for query
  *     b of the group", and the exhaustive search then runs with that bit as the predicate.
- *     On an index with live updates, deleted slots are infeasible; items upserted after
- *     linr_index_load_clauses have no lists: LINR_E_STATE until the columns are loaded again.
- * Workspace from linr_search_clauses_workspace_bytes.  LINR_E_STATE without clause columns.
+ *     On an index with live updates, deleted slots are infeasible.
+ * linr_index_upsert_clauses  (live updates) writes the lists of `count` slots (host array,
+ *     distinct, each < capacity): values [count][row_width], counts [count][n_clauses], host
+ *     (copied before the call returns) or device per `src`.  The clause columns span the
+ *     capacity; a slot that never received lists lists nothing (it fails every constrained
+ *     forward clause and satisfies every reverse clause).  For a new item call this before
+ *     linr_index_upsert on the same stream: the slot is not visible yet, so no search can
+ *     see the item with someone else's lists.  Enqueues only, like linr_index_upsert.
+ * Workspace from linr_search_clauses_workspace_bytes.  LINR_E_STATE without clause columns
+ * (and for linr_index_upsert_clauses without live updates).
  */
 #define LINR_MAX_CLAUSES 8
 #define LINR_MAX_CLAUSE_ROW 32
 #define LINR_MAX_QUERY_ROW 64
 int linr_index_load_clauses(linr_index*, const uint64_t* values, const uint8_t* counts, uint32_t n_clauses,
                             uint32_t row_width, uint32_t reverse, uint64_t n, int src);
+int linr_index_upsert_clauses(linr_index*, const uint32_t* slots, uint32_t count, const uint64_t* values,
+                              const uint8_t* counts, int src, void* hip_stream);
 int linr_search_clauses_workspace_bytes(const linr_index*, uint32_t B, uint32_t m, uint32_t k, uint64_t* bytes);
 int linr_search_clauses(const linr_index*, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
                         const uint64_t* q_values, const uint8_t* q_counts, uint32_t q_width, uint32_t k,

@@ -34,7 +34,7 @@ EXPORTS = [
     "linr_search_bits", "linr_search_two_stage_workspace_bytes", "linr_search_two_stage", "linr_search_bits_timed",
     "linr_index_enable_updates", "linr_index_upsert", "linr_index_delete", "linr_index_sync_updates",
     "linr_index_load_clauses", "linr_search_clauses_workspace_bytes", "linr_search_clauses", "linr_search_clauses_timed",
-    "linr_search_clauses_prefilter",
+    "linr_search_clauses_prefilter", "linr_index_upsert_clauses",
 ]
 
 
@@ -108,6 +108,8 @@ def load_library():
     lib.linr_search_bits.argtypes = [vp, vp, u32, vp, u32, vp, vp, vp, vp, u64, vp, u32]
     lib.linr_index_load_clauses.restype = i32
     lib.linr_index_load_clauses.argtypes = [vp, vp, vp, u32, u32, u32, u64, i32]
+    lib.linr_index_upsert_clauses.restype = i32
+    lib.linr_index_upsert_clauses.argtypes = [vp, vp, u32, vp, vp, i32, vp]
     lib.linr_search_clauses_workspace_bytes.restype = i32
     lib.linr_search_clauses_workspace_bytes.argtypes = [vp, u32, u32, u32, C.POINTER(u64)]
     lib.linr_search_clauses.restype = i32
@@ -290,6 +292,12 @@ def index_load_clauses(ix, values, counts, n_clauses, row_width, reverse, n, src
            "linr_index_load_clauses")
 
 
+def index_upsert_clauses(ix, slots, values, counts, src, stream=0):
+    slots = np.ascontiguousarray(slots, dtype=np.uint32)
+    _check(load_library().linr_index_upsert_clauses(ix, _ptr(slots), slots.size, _ptr(values), _ptr(counts), src, stream),
+           "linr_index_upsert_clauses")
+
+
 def search_clauses_workspace_bytes(ix, B, m, k) -> int:
     out = C.c_uint64()
     _check(load_library().linr_search_clauses_workspace_bytes(ix, B, m, k, C.byref(out)), "linr_search_clauses_workspace_bytes")
@@ -430,6 +438,15 @@ class Index:
         index_upsert(self.handle, slots, emb, row_scale, mask, ts, SRC_HOST if host else SRC_DEVICE_COPY, stream)
         if not host:
             self._keep_update = (emb, mask, ts, row_scale)       # device sources are read when the stream gets there
+
+    def upsert_clauses(self, slots, values, counts, stream=None):
+        import torch
+        host = isinstance(values, np.ndarray)
+        if stream is None:
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+        index_upsert_clauses(self.handle, slots, values, counts, SRC_HOST if host else SRC_DEVICE_COPY, stream)
+        if not host:
+            self._keep_clause_update = (values, counts)
 
     def delete(self, slots, stream=None):
         import torch

@@ -963,8 +963,14 @@ extern "C" int linr_index_load_clauses(linr_index* ix, const uint64_t* values, c
     if (ix->clause_counts) (void)hipFree(ix->clause_counts);
     ix->clause_values = nullptr; ix->clause_counts = nullptr; ix->clause_n = 0;
     const int fh = src == LINR_SRC_HOST;
-    int rc = copy_column((const void**)&ix->clause_values, values, n * row_width * 8, 0, fh);
-    if (rc == LINR_OK) rc = copy_column((const void**)&ix->clause_counts, counts, n * n_clauses, 0, fh);
+    // for the whole capacity, like the other library-owned columns; slots beyond n list nothing
+    const uint64_t cap = ix->capacity;
+    int rc = copy_column((const void**)&ix->clause_values, values, n * row_width * 8, cap * row_width * 8, fh);
+    if (rc == LINR_OK) rc = copy_column((const void**)&ix->clause_counts, counts, n * n_clauses, cap * n_clauses, fh);
+    if (rc == LINR_OK && cap > n) {
+        hipError_t e = hipMemset(ix->clause_counts + n * n_clauses, 0, (cap - n) * n_clauses);
+        if (e != hipSuccess) { g_last_hip = (int)e; rc = LINR_E_HIP; }
+    }
     if (rc == LINR_OK) { ix->n_clauses = n_clauses; ix->clause_width = row_width; ix->clause_reverse = reverse; ix->clause_n = n; }
     (void)hipSetDevice(dev);
     return rc;
@@ -1010,7 +1016,8 @@ static int search_clauses_impl(const linr_index* ix, const void* Q, const float*
         v = *view_for(ix, st, true, &snap);
     }
     if (v.n == 0 || !v.emb) return LINR_E_NOT_LOADED;
-    if (!v.clause_values || v.clause_n != v.n) return LINR_E_STATE;       // clause columns missing, or items added since
+    if (!v.clause_values) return LINR_E_STATE;                            // no clause columns
+    if (v.clause_n != v.n && !v.dead_bit) return LINR_E_STATE;            // (only live updates change the item count)
     if (v.dtype == LINR_BITS) return LINR_E_DTYPE;
     if (k == 0 || k > LINR_MAX_K) return LINR_E_K;
     if (q_width == 0 || q_width > LINR_MAX_QUERY_ROW) return LINR_E_SHAPE;
@@ -1130,4 +1137,56 @@ extern "C" int linr_search_clauses_prefilter(const linr_index* ix, const void* Q
 {
     return search_clauses_impl(ix, Q, q_scale, B, m, q_values, q_counts, q_width, k, out_ids, out_scores, out_raw, out_counts,
                                workspace, workspace_bytes, hip_stream, nullptr, nullptr, nullptr, nullptr, true);
+}
+
+extern "C" int linr_index_upsert_clauses(linr_index* ix, const uint32_t* slots, uint32_t count, const uint64_t* values,
+                                         const uint8_t* counts, int src, void* hip_stream)
+{
+    if (!ix) return LINR_E_NULL;
+    linr_update_state* u = ix->upd;
+    if (!u || !ix->clause_values) return LINR_E_STATE;
+    if (count == 0) return LINR_OK;
+    if (!slots || !values || !counts) return LINR_E_NULL;
+    if (src != LINR_SRC_HOST && src != LINR_SRC_DEVICE_COPY && src != LINR_SRC_DEVICE_BORROW) return LINR_E_SHAPE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    std::lock_guard<std::mutex> writer(u->writer);
+    for (uint32_t i = 0; i < count; ++i)
+        if (slots[i] >= ix->capacity) return LINR_E_CAPACITY;
+    {
+        std::vector<uint32_t> sorted(slots, slots + count);
+        std::sort(sorted.begin(), sorted.end());
+        if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end()) return LINR_E_SHAPE;
+    }
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipSetDevice(ix->device));
+    auto body = [&]() -> int {
+        const bool host_rows = src == LINR_SRC_HOST;
+        const uint32_t W = ix->clause_width, C = ix->n_clauses;
+        const uint64_t o_val = align_up((uint64_t)count * 4, 256);
+        const uint64_t o_cnt = o_val + (host_rows ? align_up((uint64_t)count * W * 8, 256) : 0);
+        const uint64_t total = o_cnt + (host_rows ? align_up((uint64_t)count * C, 256) : 0);
+        int rc = staging_reserve(u, total);
+        if (rc != LINR_OK) return rc;
+        char* sg = (char*)u->staging;
+        char* hs = (char*)u->host_staging;
+        memcpy(hs, slots, (size_t)count * 4);
+        if (host_rows) {
+            memcpy(hs + o_val, values, (size_t)count * W * 8);
+            memcpy(hs + o_cnt, counts, (size_t)count * C);
+        }
+        HIP_TRY(hipMemcpyAsync(sg, hs, (size_t)total, hipMemcpyHostToDevice, st));
+        HIP_TRY(linr_launch_upsert_clauses((const uint32_t*)sg, count, host_rows ? (const uint64_t*)(sg + o_val) : values,
+                                           host_rows ? (const uint8_t*)(sg + o_cnt) : counts, ix->clause_values, ix->clause_counts,
+                                           W, C, st));
+        HIP_TRY(hipEventRecord(u->done, st));
+        std::lock_guard<std::mutex> g(u->mu);
+        if (!u->pending) u->n_pending = ix->n;
+        u->stream = st;
+        u->pending = true;
+        return LINR_OK;
+    };
+    const int rc = body();
+    (void)hipSetDevice(dev);
+    return rc;
 }

@@ -131,6 +131,9 @@ struct linr_upsert_args {
 };
 hipError_t linr_launch_upsert(const linr_upsert_args& a, hipStream_t s);          // rows, row scales, timestamps
 hipError_t linr_launch_upsert_masks(const linr_upsert_args& a, hipStream_t s);    // masks (launched last)
+// clause lists of `count` slots: values rows of `width` words and counts rows of `n_clauses` bytes
+hipError_t linr_launch_upsert_clauses(const uint32_t* slots, uint32_t count, const uint64_t* src_values, const uint8_t* src_counts,
+                                      uint64_t* values, uint8_t* counts, uint32_t width, uint32_t n_clauses, hipStream_t s);
 hipError_t linr_launch_tombstone(uint32_t* mask, const uint32_t* slots, uint32_t count, uint32_t dead_bit, hipStream_t s);
 hipError_t linr_launch_fill_u32(uint32_t* dst, uint64_t n, uint32_t value, hipStream_t s);
 hipError_t linr_launch_mask_or(const uint32_t* mask, uint64_t n, uint32_t* out, hipStream_t s);   // *out |= OR of mask[0..n)

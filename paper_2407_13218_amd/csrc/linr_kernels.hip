@@ -2011,6 +2011,20 @@ __global__ void __launch_bounds__(256) upsert_mask_kernel(linr_upsert_args A)
     if (e < A.count) A.mask[A.slots[e]] = A.src_mask[e] & ~A.dead_bit;
 }
 
+__global__ void __launch_bounds__(256) upsert_clauses_kernel(const uint32_t* slots, uint32_t count, const u64* src_values,
+                                                             const uint8_t* src_counts, u64* values, uint8_t* counts, uint32_t width,
+                                                             uint32_t n_clauses)
+{
+    const u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (u64)count * width) return;
+    const uint32_t e = (uint32_t)(t / width), j = (uint32_t)(t % width);
+    const u64 slot = slots[e];
+    values[slot * width + j] = src_values[(u64)e * width + j];
+    if (j < n_clauses) counts[slot * n_clauses + j] = src_counts[(u64)e * n_clauses + j];
+    if (j == 0)
+        for (uint32_t c = width; c < n_clauses; ++c) counts[slot * n_clauses + c] = src_counts[(u64)e * n_clauses + c];
+}
+
 __global__ void __launch_bounds__(256) tombstone_kernel(uint32_t* mask, const uint32_t* slots, uint32_t count, uint32_t dead_bit)
 {
     const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
@@ -2720,6 +2734,16 @@ hipError_t linr_launch_upsert_masks(const linr_upsert_args& a, hipStream_t s)
 {
     if (a.count == 0) return hipSuccess;
     hipLaunchKernelGGL(upsert_mask_kernel, dim3((a.count + 255) / 256), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t linr_launch_upsert_clauses(const uint32_t* slots, uint32_t count, const uint64_t* src_values, const uint8_t* src_counts,
+                                      uint64_t* values, uint8_t* counts, uint32_t width, uint32_t n_clauses, hipStream_t s)
+{
+    if (count == 0) return hipSuccess;
+    const uint64_t threads = (uint64_t)count * width;
+    hipLaunchKernelGGL(upsert_clauses_kernel, dim3((uint32_t)((threads + 255) / 256)), dim3(256), 0, s, slots, count,
+                       (const u64*)src_values, src_counts, (u64*)values, counts, width, n_clauses);
     return hipGetLastError();
 }
 

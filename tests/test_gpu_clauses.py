@@ -164,37 +164,52 @@ def test_multi_embedding_queries(oracle_mod):
 
 
 def test_with_live_updates(oracle_mod):
-    """deleted slots are infeasible for a clause search; items added after the clause columns were loaded make it an error"""
+    """deleted slots are infeasible for a clause search; upserted items get their lists through linr_index_upsert_clauses
+    (without it they list nothing); both strategies against the oracle over the live items"""
     import torch
     import paper_2407_13218_amd as L
     rng = np.random.default_rng(2)
     n, cap, d, B, k = 6_000, 7_000, 64, 5, 80
-    emb, sc = rows(rng, "i8", n, d)
+    emb, sc = rows(rng, "i8", cap, d)
     Q, _ = rows(rng, "i8", B, d)
     Q = Q.reshape(B, 1, d); qs = np.ones(B, np.float32)
-    values, counts = S.random_clause_lists(n, 2, 2, 4, seed=9)
+    values, counts = S.random_clause_lists(cap, 2, 2, 4, seed=9)
     qv, qc = S.random_clause_lists(B, 2, 2, 4, seed=10)
+    qc[0] = 0                                                    # query 0 constrains nothing
     ix = L.Index(cap, d, S.I8, 0)
-    ix.load(emb, np.zeros(n, np.uint32), row_scale=sc)
-    ix.load_clauses(values, counts, 0)
+    ix.load(emb[:n], np.zeros(n, np.uint32), row_scale=sc[:n])
+    ix.load_clauses(values[:n], counts[:n], 0b10)
     ix.enable_updates()
+    live = np.zeros(cap, bool); live[:n] = True
+    have_lists = live.copy()
+
+    def check(label):
+        keep = np.flatnonzero(live)
+        cts = np.where(have_lists[keep, None], counts[keep], 0).astype(np.uint8)
+        want = oracle_mod.clause_search(S.I8, emb[keep], values[keep], cts, Q, qv, qc, 0b10, k, row_scale=sc[keep], q_scale=qs)
+        wid = np.where(want[0] == oracle_mod.NO_ID, oracle_mod.NO_ID, keep[np.minimum(want[0], len(keep) - 1)].astype(np.uint32))
+        for prefilter in (False, True):
+            ids, scr, raw, cnt = ix.search_clauses(dev(Q), dev(qv), dev(qc), k, q_scale=dev(qs), prefilter=prefilter)
+            torch.cuda.synchronize()
+            assert np.array_equal(cnt.cpu().numpy().view(np.uint32), want[3]), label
+            assert np.array_equal(ids.cpu().numpy().view(np.uint32), wid), label
+            assert scr.cpu().numpy().tobytes() == want[1].tobytes(), label
+
     gone = rng.choice(n, 2500, replace=False).astype(np.uint32)
-    ix.delete(gone)
-    ids, scr, raw, cnt = ix.search_clauses(dev(Q), dev(qv), dev(qc), k, q_scale=dev(qs))
-    torch.cuda.synchronize()
-    # the oracle's statement of "deleted": the item's lists are empty and the query constrains clause 0 ... simpler and
-    # independent of that: drop the deleted items, search, map the dense positions back to slots
-    keep = np.setdiff1d(np.arange(n), gone)
-    want = oracle_mod.clause_search(S.I8, emb[keep], values[keep], counts[keep], Q, qv, qc, 0, k, row_scale=sc[keep], q_scale=qs)
-    wid = np.where(want[0] == oracle_mod.NO_ID, oracle_mod.NO_ID, keep[np.minimum(want[0], len(keep) - 1)].astype(np.uint32))
-    assert np.array_equal(cnt.cpu().numpy().view(np.uint32), want[3])
-    assert np.array_equal(ids.cpu().numpy().view(np.uint32), wid)
-    assert scr.cpu().numpy().tobytes() == want[1].tobytes()
-    ix.upsert([n], emb[:1], np.zeros(1, np.uint32), row_scale=sc[:1])
-    ix.sync_updates()
-    with pytest.raises(L.LinrError) as e:
-        ix.search_clauses(dev(Q), dev(qv), dev(qc), k, q_scale=dev(qs))
-    assert e.value.code == -10
+    ix.delete(gone); live[gone] = False
+    check("after deletes")
+    fresh = np.arange(n, n + 400, dtype=np.uint32)
+    ix.upsert(fresh, emb[fresh], np.zeros(400, np.uint32), row_scale=sc[fresh]); live[fresh] = True
+    check("upserted items without lists")                        # they list nothing: only unconstrained / reverse clauses pass
+    ix.upsert_clauses(fresh[:300], values[fresh[:300]], counts[fresh[:300]]); have_lists[fresh[:300]] = True
+    check("lists for 300 of them (host source)")
+    ix.upsert_clauses(fresh[300:], dev(values[fresh[300:]]), dev(counts[fresh[300:]])); have_lists[fresh[300:]] = True
+    check("lists for the rest (device source)")
+    reuse = gone[:100]                                           # deleted slots come back with new rows and lists
+    ix.upsert_clauses(reuse, values[fresh[:100]], counts[fresh[:100]])
+    values[reuse] = values[fresh[:100]]; counts[reuse] = counts[fresh[:100]]
+    ix.upsert(reuse, emb[reuse], np.zeros(100, np.uint32), row_scale=sc[reuse]); live[reuse] = True
+    check("reused slots")
     ix.close()
 
 
