@@ -986,7 +986,8 @@ static int clause_layout(const linr_index* v, uint32_t B, uint32_t m, uint32_t k
     const uint64_t items = v->dead_bit ? v->capacity : v->n;
     *off_words = align_up(*inner, 256);
     *off_filters = align_up(*off_words + items * 4, 256);
-    *total = align_up(*off_filters + 32 * sizeof(linr_filter) + 4096, 256);    // + 32 counters (a 128-byte line each) of the pre-filtering strategy
+    // + 32 counters (a 128-byte line each) of the pre-filtering strategy + the group's lists regrouped by clause
+    *total = align_up(*off_filters + 32 * sizeof(linr_filter) + 4096 + linr_clause_entries_bytes(), 256);
     return LINR_OK;
 }
 
@@ -1043,6 +1044,7 @@ static int search_clauses_impl(const linr_index* ix, const void* Q, const float*
         ca.reverse = v.clause_reverse; ca.n = v.n;
         ca.q_values = q_values + (uint64_t)b0 * q_width; ca.q_counts = q_counts + (uint64_t)b0 * v.n_clauses;
         ca.q_width = q_width; ca.nq = Bg; ca.mask = item_mask; ca.dead_bit = dead; ca.out = words;
+        ca.entries = (char*)(filt + 32) + 4096;
         const bool rec = events && stage < LINR_MAX_STAGES;
         if (rec) HIP_TRY(hipEventRecord((hipEvent_t)events[2 * stage], st));
         HIP_TRY(linr_launch_clause_words(ca, st));

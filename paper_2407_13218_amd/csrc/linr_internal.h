@@ -143,8 +143,10 @@ struct linr_clause_args {
     const uint64_t* q_values; const uint8_t* q_counts; uint32_t q_width, nq;
     const uint32_t* mask; uint32_t dead_bit;           // live updates: slots whose mask carries dead_bit satisfy nothing
     uint32_t* out;                                      // [n]
+    void* entries;                                      // device scratch of linr_clause_entries_bytes(), 8-byte aligned
 };
 hipError_t linr_launch_clause_words(const linr_clause_args& a, hipStream_t s);
+uint32_t linr_clause_entries_bytes(void);
 // filters[b] = "bit b of the mask is set", b < nq
 hipError_t linr_launch_bit_filters(linr_filter* filters, uint32_t nq, hipStream_t s);
 // explicit pre-filtering (Sec. 3.1.2): score only the items whose feasibility word has a bit set, append their keys

@@ -1753,28 +1753,58 @@ __global__ void __launch_bounds__(256) sign_oporp_kernel(int dtype, const void* 
 // ---------------------------------------------------------------------------
 #define LINR_CLAUSE_MAX_C 8
 #define LINR_CLAUSE_MAX_QW 64
-__global__ void __launch_bounds__(256) clause_words_kernel(linr_clause_args A)
+#define LINR_CLAUSE_MAX_ENT (32 * LINR_CLAUSE_MAX_QW)
+
+// The group's query lists, regrouped by clause: entry e of clause c (start[c] <= e < start[c + 1]) is one attribute
+// some query lists for c, with that query's bit.  Written once per group by one small workgroup; the item pass then
+// walks a clause's entries with uniform (scalar) reads.
+struct ClauseEntries {
+    u64 val[LINR_CLAUSE_MAX_ENT];
+    uint32_t bit[LINR_CLAUSE_MAX_ENT];
+    uint32_t start[LINR_CLAUSE_MAX_C + 1];
+    uint32_t constrained[LINR_CLAUSE_MAX_C];          // bit b: query b lists something for this clause
+};
+
+__global__ void __launch_bounds__(256) clause_entries_kernel(linr_clause_args A, ClauseEntries* E)
 {
-    __shared__ u64 qv[32][LINR_CLAUSE_MAX_QW];
-    __shared__ uint8_t qoff[32][LINR_CLAUSE_MAX_C], qlen[32][LINR_CLAUSE_MAX_C];
-    __shared__ uint32_t constrained[LINR_CLAUSE_MAX_C];       // bit b: query b lists something for this clause
-    const uint32_t C = A.n_clauses, nq = A.nq;
-    for (uint32_t t = threadIdx.x; t < nq * A.q_width; t += blockDim.x)
-        qv[t / A.q_width][t % A.q_width] = (u64)A.q_values[t];
-    if (threadIdx.x < C) constrained[threadIdx.x] = 0u;
-    __syncthreads();
-    if (threadIdx.x < nq) {
+    __shared__ uint32_t len[32][LINR_CLAUSE_MAX_C], qoff[32][LINR_CLAUSE_MAX_C], tot[LINR_CLAUSE_MAX_C + 1];
+    const uint32_t C = A.n_clauses, nq = A.nq, t = threadIdx.x;
+    if (t < nq) {
         uint32_t off = 0;
         for (uint32_t c = 0; c < C; ++c) {
-            uint32_t len = A.q_counts[threadIdx.x * C + c];
-            if (off + len > A.q_width) len = A.q_width - off;   // counts that overrun the query's row are cut
-            qoff[threadIdx.x][c] = (uint8_t)off;
-            qlen[threadIdx.x][c] = (uint8_t)len;
-            if (len) atomicOr(&constrained[c], 1u << threadIdx.x);
-            off += len;
+            uint32_t l = A.q_counts[t * C + c];
+            if (off + l > A.q_width) l = A.q_width - off;       // counts that overrun the query's row are cut
+            len[t][c] = l; qoff[t][c] = off;
+            off += l;
         }
     }
     __syncthreads();
+    if (t == 0) {
+        uint32_t run = 0;
+        for (uint32_t c = 0; c < C; ++c) {
+            tot[c] = run;
+            uint32_t cons = 0;
+            for (uint32_t b = 0; b < nq; ++b) { run += len[b][c]; if (len[b][c]) cons |= 1u << b; }
+            E->constrained[c] = cons;
+        }
+        tot[C] = run;
+        for (uint32_t c = 0; c <= C; ++c) E->start[c] = tot[c];
+    }
+    __syncthreads();
+    if (t < nq * C) {
+        const uint32_t c = t / nq, b = t % nq;
+        uint32_t pos = tot[c];
+        for (uint32_t b2 = 0; b2 < b; ++b2) pos += len[b2][c];
+        for (uint32_t j = 0; j < len[b][c]; ++j) {
+            E->val[pos + j] = (u64)A.q_values[(u64)b * A.q_width + qoff[b][c] + j];
+            E->bit[pos + j] = 1u << b;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256) clause_words_kernel(linr_clause_args A, const ClauseEntries* __restrict__ E)
+{
+    const uint32_t C = A.n_clauses, nq = A.nq;
     const uint32_t all = nq >= 32 ? 0xFFFFFFFFu : ((1u << nq) - 1u);
     for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < A.n; i += (u64)gridDim.x * blockDim.x) {
         const u64* row = (const u64*)A.values + i * A.width;
@@ -1782,17 +1812,21 @@ __global__ void __launch_bounds__(256) clause_words_kernel(linr_clause_args A)
         uint32_t ok = all, io = 0;
         for (uint32_t c = 0; c < C; ++c) {
             const uint32_t len = cnt[c];
+            const uint32_t e0 = E->start[c], e1 = E->start[c + 1];
             uint32_t match = 0u;
             for (uint32_t a = 0; a < len && io + a < A.width; ++a) {
                 const u64 v = row[io + a];
-                for (uint32_t b = 0; b < nq; ++b) {
-                    const uint32_t o = qoff[b][c], l = qlen[b][c];
-                    for (uint32_t t = 0; t < l; ++t)
-                        if (qv[b][o + t] == v) match |= 1u << b;
+                uint32_t e = e0;
+                for (; e + 4 <= e1; e += 4) {                   // four entries per trip: their scalar reads overlap
+                    const u64 v0 = E->val[e], v1 = E->val[e + 1], v2 = E->val[e + 2], v3 = E->val[e + 3];
+                    const uint32_t b0 = E->bit[e], b1 = E->bit[e + 1], b2 = E->bit[e + 2], b3 = E->bit[e + 3];
+                    match |= (b0 & (0u - (uint32_t)(v0 == v))) | (b1 & (0u - (uint32_t)(v1 == v))) |
+                             (b2 & (0u - (uint32_t)(v2 == v))) | (b3 & (0u - (uint32_t)(v3 == v)));
                 }
+                for (; e < e1; ++e) match |= E->bit[e] & (0u - (uint32_t)(E->val[e] == v));
             }
             const uint32_t sat = ((A.reverse >> c) & 1u) ? ~match : match;
-            ok &= sat | ~constrained[c];
+            ok &= sat | ~E->constrained[c];
             io += len;
         }
         if (A.dead_bit && (A.mask[i] & A.dead_bit)) ok = 0u;
@@ -2689,12 +2723,16 @@ hipError_t linr_launch_clause_words(const linr_clause_args& a, hipStream_t s)
 {
     if (a.n == 0) return hipSuccess;
     if (a.nq == 0 || a.nq > 32 || a.n_clauses == 0 || a.n_clauses > LINR_CLAUSE_MAX_C || a.q_width == 0 ||
-        a.q_width > LINR_CLAUSE_MAX_QW || a.width == 0)
+        a.q_width > LINR_CLAUSE_MAX_QW || a.width == 0 || !a.entries || (((uintptr_t)a.entries) & 7u))
         return hipErrorInvalidValue;
+    ClauseEntries* E = (ClauseEntries*)a.entries;
+    hipLaunchKernelGGL(clause_entries_kernel, dim3(1), dim3(256), 0, s, a, E);
     const uint64_t blocks = (a.n + 255) / 256;
-    hipLaunchKernelGGL(clause_words_kernel, dim3((uint32_t)(blocks < 8192 ? blocks : 8192)), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(clause_words_kernel, dim3((uint32_t)(blocks < 8192 ? blocks : 8192)), dim3(256), 0, s, a, E);
     return hipGetLastError();
 }
+
+uint32_t linr_clause_entries_bytes(void) { return (uint32_t)sizeof(ClauseEntries); }
 
 hipError_t linr_launch_bit_filters(linr_filter* filters, uint32_t nq, hipStream_t s)
 {
