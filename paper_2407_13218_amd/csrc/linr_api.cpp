@@ -255,8 +255,8 @@ static int cached_blocks_per_cu(const linr_index* ix, const linr_plan& p, uint32
     const int ts = ix->ts != nullptr;
     if (p.generic) return linr_scan_blocks_per_cu(p, ix->dtype, Bp, m, ts);
     if (p.bits) {
-        static int bits_cache[5][2];
-        int& bslot = bits_cache[p.ks <= 4 ? p.ks : 0][ts];
+        static int bits_cache[3][5][9][2];
+        int& bslot = bits_cache[p.bits <= 2 ? p.bits : 0][p.ks <= 4 ? p.ks : 0][p.qg <= 8 ? p.qg : 0][ts];
         if (bslot == 0) { int v = linr_scan_blocks_per_cu(p, ix->dtype, Bp, m, ts); bslot = v > 0 ? v : -1; }
         return bslot > 0 ? bslot : 0;
     }
@@ -310,16 +310,35 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
             if (c * LINR_WAVES_PER_BLOCK * 32 >= B) break;
         }
     uint32_t Bp;
-    if (bits_mode) {                                    // bit-matching kernel: every wave a chunk-slot, 64 queries per pass
+    if (bits_mode) {
         if (m != 1) return LINR_E_SHAPE;
-        p->bits = 1;
         p->ks = ix->bits_words;
-        p->qg = 4;
         p->generic = 0;
-        p->chunk_items = 256;
-        p->max_batch = 64;
-        Bp = B < p->max_batch ? B : p->max_batch;
         p->nsplit = 1;
+        // two dozen queries or more: bit matching on the matrix cores (16 x 16 match counts per instruction; codes of
+        // up to 128 bits), 16 * qg queries per wave and pass (measured at 1e9 x 64 bits: 6.5 vs 7.1 ms at B = 32,
+        // 16.9 vs 25.2 ms at B = 128; at B = 16 the popcount kernel still wins, 4.3 vs 5.0 ms).  Fewer: the popcount
+        // kernel, which is bound by HBM for a few queries.
+        // (tests: no_coop = 1 forces the popcount kernel, force_generic = 1 the matrix-core kernel)
+        uint32_t mq = 0;
+        if ((B >= 24 || g_tuning.force_generic) && !g_tuning.no_coop)
+            for (uint32_t c = 1; c <= 8; c <<= 1) {
+                if (!linr_bits_mfma_variant_exists(p->ks, c)) continue;
+                mq = c;
+                if (c >= nsg) break;
+            }
+        if (mq) {
+            p->bits = 2;
+            p->qg = mq;
+            p->chunk_items = 128;
+            p->max_batch = mq * 16;
+        } else {                                        // every wave a chunk-slot, 64 queries per pass
+            p->bits = 1;
+            p->qg = 4;
+            p->chunk_items = 256;
+            p->max_batch = 64;
+        }
+        Bp = B < p->max_batch ? B : p->max_batch;
     } else if (qw) {
         p->qg = qw;
         p->coop = 1;
@@ -361,7 +380,7 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
         int occ = cached_blocks_per_cu(ix, *p, Bp, m);
         bpc = occ > 0 ? (uint32_t)occ : 2u;
         if (bpc > 8) bpc = 8;
-        if (p->bits && bpc > 4) bpc = 4;                // every wave is a chunk-slot: 256 CUs x 4 x 4 waves = LINR_MAX_SLOTS
+        if (p->bits == 1 && bpc > 4) bpc = 4;           // every wave is a chunk-slot: 256 CUs x 4 x 4 waves = LINR_MAX_SLOTS
     }
     p->n_chunks = (ix->n + p->chunk_items - 1) / p->chunk_items;
     uint64_t waves_wanted = p->n_chunks * p->nsplit;

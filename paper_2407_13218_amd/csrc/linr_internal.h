@@ -175,6 +175,7 @@ hipError_t linr_launch_rescore(const linr_rescore_args& a, hipStream_t s);
 int linr_fast_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg);
 int linr_coop_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg);
 int linr_wide_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qw);
+int linr_bits_mfma_variant_exists(uint32_t words, uint32_t qg);      // matrix-core bit matching (plan.bits == 2)
 // statistics of 1/row_scale of a scaled int8 index (out[3]; part: 3 * LINR_SCALE_STAT_BLOCKS floats of scratch) and the
 // per-item codes derived from them (codes: n_pad bytes)
 #define LINR_SCALE_STAT_BLOCKS 1024

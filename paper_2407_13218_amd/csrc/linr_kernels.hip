@@ -1716,6 +1716,179 @@ __global__ void __launch_bounds__(64 * WPB, W <= 2 ? 4 : 2) scan_kernel_bits(lin
     flush_segments(A, qs, slot, 0, NQ, lane, hist_all[wib]);
 }
 
+// ---------------------------------------------------------------------------
+// quantised search for many queries: bit matching on the matrix cores.
+//   With item bits a in {0, 1} and query bits q mapped to {-1, +1}, sum_j a_j q_j = (#bits both 1) - (#item 1, query 0)
+//   and the number of equal bits is that sum + (number of 0 bits in the query's code): a 16-item x 16-query tile of
+//   match counts is ONE int8 matrix instruction per 64 code bits whose accumulator starts at the query's constant.
+//   A lane expands its 16 bits of an item's code word to 16 bytes of 0 / 1 in registers (the code stays 8 bytes per
+//   item in HBM); the queries' +-1 bytes are built once per wave.  Everything after the product -- bound test,
+//   predicate, candidate segments, compaction, flush -- is the exact scan's (tile_survivors etc.) with the match
+//   count as a raw integer ranking value.  Waves are independent chunk-slots; a chunk is 128 items.
+// ---------------------------------------------------------------------------
+#define LINR_BITSM_CH 128
+
+// 16 bits -> 16 bytes of 0 / 1 (four registers; byte j of the result = bit j)
+__device__ __forceinline__ v4i expand16(uint32_t bits16)
+{
+    v4i r;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        r[j] = (int)((((bits16 >> (4 * j)) & 0xFu) * 0x00204081u) & 0x01010101u);
+    return r;
+}
+
+template <int W, int QG>
+__global__ void __launch_bounds__(64 * WPB, (QG * W <= 4 ? 3 : 2)) scan_kernel_bits_mfma(linr_scan_args A)
+{
+    constexpr int CH = LINR_BITSM_CH, TPC = 8, NQ = QG * 16;
+    // per-wave scratch: 256 words for the compaction's histogram; the final flush needs 2 * NQ + 1 words
+    constexpr int SCRATCH = 2 * NQ + 1 > 256 ? 2 * NQ + 8 : 256;
+    __shared__ WaveQ<QG> wq_all[WPB];
+    __shared__ uint32_t hist_all[WPB][SCRATCH];
+    __shared__ u64 stage_all[WPB][CH * W];
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    WaveQ<QG>& Wq = wq_all[wib];
+    const QSide qs = {Wq.cnt, Wq.thr_f, Wq.thr_i, Wq.fall, Wq.fnone, Wq.tsmin, Wq.tsmax, Wq.fflag};
+    const int row = lane & 15, g4 = lane >> 4;
+    const uint32_t gw = blockIdx.x * WPB + wib;
+    const uint32_t split = gw % A.nsplit, slot = gw / A.nsplit;
+    if (slot >= A.nslots) return;
+    const uint32_t q_first = split * NQ;
+    const bool has_ts = A.ts != nullptr;
+    const int sh = 16 * (g4 & 1);                        // this lane's 16 bits of a word: half g4 / 2, shifted by sh
+    const bool hi_half = g4 >= 2;
+
+    // ---- query operand: bits -> +1 / -1 bytes; accumulator start = number of 0 bits of the code
+    v4i q[QG][W];
+    v4i cinit[QG];
+#pragma unroll
+    for (int i = 0; i < QG; ++i) {
+        const uint32_t qi = q_first + i * 16 + row;
+        int zeros = 0;
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            const u64 code = qi < A.B ? ((const u64*)A.Q)[(u64)qi * W + w] : 0ull;
+            const uint32_t half = hi_half ? (uint32_t)(code >> 32) : (uint32_t)code;
+            const v4i e = expand16((half >> sh) & 0xFFFFu);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t ff = (uint32_t)e[j] * 255u;                 // 0xFF where the bit is 1
+                q[i][w][j] = qi < A.B ? (int)(0xFFFFFFFFu ^ (ff & 0xFEFEFEFEu)) : 0;   // 0x01 for 1, 0xFF (-1) for 0
+            }
+            zeros += 64 - __popcll(code);
+        }
+        zeros -= 64 * W - (int)A.k_bits;                                    // bits beyond k_bits are 0 in every code
+        cinit[i] = (v4i){zeros, zeros, zeros, zeros};
+    }
+
+    for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) {
+        Wq.cnt[ql] = 0;
+        load_query_side(qs, ql, q_first + ql, A, true);
+    }
+    wave_sync();
+    int thr_i[QG];
+    uint32_t f_all[QG], f_none[QG];
+#pragma unroll
+    for (int i = 0; i < QG; ++i) {
+        thr_i[i] = Wq.thr_i[i * 16 + row];
+        f_all[i] = Wq.fall[i * 16 + row]; f_none[i] = Wq.fnone[i * 16 + row];
+    }
+
+    // ---- items: a chunk's code words travel through registers (next chunk in flight, two items per lane) into the
+    // wave's LDS area, from which a lane picks the word of its tile row (keeps the tile loop rolled)
+    const u64* codes = (const u64*)A.emb;
+    const u64 last = A.n - 1;
+    u64* stage = stage_all[wib];
+    u64 nxt[2][W];
+    auto issue = [&](u64 lc) {
+        const u64 item0 = lc * A.stride * CH;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            u64 it = item0 + h * 64 + lane;
+            it = it < last ? it : last;
+#pragma unroll
+            for (int w = 0; w < W; ++w) nxt[h][w] = __builtin_nontemporal_load(codes + it * W + w);
+        }
+    };
+    uint32_t need_compact = 0u, since_refresh = 0u;
+    SweepWalk walk;
+    walk.init(slot, A);
+    u64 lc = walk.lc();
+    if (walk.valid()) issue(lc);
+    while (walk.valid()) {
+        const u64 item0 = lc * A.stride * CH;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int w = 0; w < W; ++w) stage[(h * 64 + lane) * W + w] = nxt[h][w];
+        wave_sync();
+        walk.advance();
+        const u64 nlc = walk.lc();
+        if (walk.valid()) issue(nlc);
+
+#pragma unroll 1
+        for (int t = 0; t < TPC; ++t) {
+            v4i a[W];
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+                const u64 code = stage[(t * 16 + row) * W + w];
+                const uint32_t half = hi_half ? (uint32_t)(code >> 32) : (uint32_t)code;
+                a[w] = expand16((half >> sh) & 0xFFFFu);
+            }
+            const int ib = t * 16 + 4 * g4;               // first of this lane's four items (output rows) in the chunk
+            v4i acc[QG];
+            u64 any_hot = 0;
+            u64 hot[QG];
+#pragma unroll
+            for (int i = 0; i < QG; ++i) {
+                v4i c = cinit[i];
+#pragma unroll
+                for (int w = 0; w < W; ++w) c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[w], q[i][w], c, 0, 0, 0);
+                acc[i] = c;
+                const int mx = max(max(c[0], c[1]), max(c[2], c[3]));
+                hot[i] = wave_ballot(mx >= thr_i[i]);
+                any_hot |= hot[i];
+            }
+            if (any_hot) {
+                // masks (and timestamps) of the lane's four items: read only now -- tiles without a survivor never ask
+                v4u mk4, ts4 = {0, 0, 0, 0};
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    u64 it = item0 + ib + r;
+                    it = it < last ? it : last;
+                    mk4[r] = A.mask[it];
+                    if (has_ts) ts4[r] = A.ts[it];
+                }
+#pragma unroll
+                for (int i = 0; i < QG; ++i)
+                    if (hot[i])
+                        tile_survivors<LINR_VK_I8_RAW, false, CH>(acc[i], (hot[i] >> lane) & 1ull, mk4, f_all[i], f_none[i], qs,
+                                                                  i * 16 + row, q_first + i * 16 + row, ib, item0,
+                                                                  [&] { return (v4f){0, 0, 0, 0}; }, [&] { return ts4; }, A, slot,
+                                                                  has_ts, need_compact);
+            }
+        }
+        wave_sync();
+        bool refresh = ++since_refresh >= 16;
+        if (wave_any(need_compact != 0u)) {
+            compact_full_segments<CH>(A, qs, slot, q_first, NQ, hist_all[wib], lane);
+            need_compact = 0u;
+            refresh = true;
+        }
+        if (refresh) {
+            for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) load_query_side(qs, ql, q_first + ql, A, false);
+            wave_sync();
+#pragma unroll
+            for (int i = 0; i < QG; ++i) thr_i[i] = Wq.thr_i[i * 16 + row];
+            since_refresh = 0;
+        }
+        lc = nlc;
+    }
+    own_stores_done();
+    flush_segments(A, qs, slot, q_first, NQ, lane, hist_all[wib]);
+}
+
 // Sign-OPORP codes of n rows: thread (row, word) sums its 64 bins in double precision, t ascending, and
 // sets bit j%64 of word j/64 for a strictly positive bin sum (Sec. 3.2; construction in the header).
 __global__ void __launch_bounds__(256) sign_oporp_kernel(int dtype, const void* x, u64 n, uint32_t d, const uint32_t* perm,
@@ -2693,6 +2866,19 @@ uint32_t linr_lds_scan_dynamic_bytes(uint32_t B, uint32_t m, uint32_t ks)
     return nsg * m * ks * 1024u + nsg * 16u * 4u * (7u + WPB);
 }
 
+#define BITSM_CASE(W_, QG_) if (words == W_ && qg == QG_) return scan_act(scan_kernel_bits_mfma<W_, QG_>, act);
+static hipError_t bits_mfma_dispatch(uint32_t words, uint32_t qg, ScanAct& act)
+{
+    BITSM_CASE(1, 1) BITSM_CASE(1, 2) BITSM_CASE(1, 4) BITSM_CASE(1, 8)
+    BITSM_CASE(2, 1) BITSM_CASE(2, 2) BITSM_CASE(2, 4) BITSM_CASE(2, 8)
+    return hipErrorInvalidDeviceFunction;
+}
+int linr_bits_mfma_variant_exists(uint32_t words, uint32_t qg)
+{
+    ScanAct act{}; act.what = ACT_EXISTS;
+    return bits_mfma_dispatch(words, qg, act) == hipSuccess;
+}
+
 static hipError_t bits_dispatch(uint32_t words, ScanAct& act)
 {
     if (words == 1) return scan_act(scan_kernel_bits<1>, act);
@@ -2817,6 +3003,7 @@ hipError_t linr_launch_rescore(const linr_rescore_args& a, hipStream_t s)
 
 static hipError_t plan_dispatch(const linr_plan& p, int dtype, uint32_t B, uint32_t m, bool ts, ScanAct& act)
 {
+    if (p.bits == 2) { act.dyn = 0; return bits_mfma_dispatch(p.ks, p.qg, act); }
     if (p.bits) { act.dyn = 0; return bits_dispatch(p.ks, act); }
     if (p.generic) {
         act.dyn = linr_lds_scan_dynamic_bytes(B, m, p.ks);

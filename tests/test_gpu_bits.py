@@ -97,6 +97,29 @@ def test_bits_search_exact(oracle_mod, n, k_bits, B, T, with_ts):
     run_bits_case(oracle_mod, codes, k_bits, mask, ts, qbits, mixed_filters(B, rng, with_ts), T, f"n={n} k_bits={k_bits} B={B}")
 
 
+@pytest.mark.parametrize("kernel", ["popcount", "matrix"])
+@pytest.mark.parametrize("n,k_bits,B,T,with_ts", [(300, 64, 2, 20, False), (70_001, 64, 37, 700, True), (40_000, 128, 129, 300, False),
+                                                  (25_000, 100, 16, 2500, True), (33_000, 17, 50, 90, False)])
+def test_both_bit_matching_kernels(oracle_mod, kernel, n, k_bits, B, T, with_ts):
+    """the same searches forced through the popcount kernel (vector ALU) and the matrix-core kernel (codes expanded to
+    0 / 1 bytes, queries to +-1 bytes, accumulators started at the query's zero count); ragged code widths included"""
+    import paper_2407_13218_amd as L
+    say(f"bits search via the {kernel} kernel: n={n} k_bits={k_bits} B={B} T={T}")
+    rng = np.random.default_rng(n + B + 1)
+    codes = S.random_codes(n, k_bits, seed=n + 7)
+    qbits = S.random_codes(B, k_bits, seed=n + 8)
+    codes[n // 2] = qbits[0]; codes[n - 1] = qbits[0]; codes[0] = ~qbits[B - 1] & codes.dtype.type((1 << min(64, k_bits)) - 1 if k_bits <= 64 else 0xFFFFFFFFFFFFFFFF)
+    if k_bits > 64 and k_bits % 64:
+        codes[0, -1] &= np.uint64((1 << (k_bits % 64)) - 1)
+    mask = rng.integers(0, 2 ** 32, n, dtype=np.uint64).astype(np.uint32)
+    ts = rng.integers(0, 1000, n).astype(np.uint32) if with_ts else None
+    L.set_tuning(**({"no_coop": 1} if kernel == "popcount" else {"force_generic": 1}))
+    try:
+        run_bits_case(oracle_mod, codes, k_bits, mask, ts, qbits, mixed_filters(B, rng, with_ts), T, f"{kernel} n={n} k_bits={k_bits} B={B}")
+    finally:
+        L.set_tuning()
+
+
 def test_bits_search_few_levels_many_ties(oracle_mod):
     """16-bit codes: only 17 distinct match counts, so the T-th place is decided by ids among thousands of ties"""
     say("bits search with 16-bit codes (massive ties), device filters, plan variants")
