@@ -9,7 +9,7 @@ of one query batch.  The headline is the small-batch, HBM-bound regime (B = 32, 
 rate); a short sweep over B in {1, 32, 256, 1024} and pass rates {50 %, 5 %, 0.1 %} is
 reported in the same JSON line under "sweep".  A second leg, reported under "quantised", runs the
 1-bit search of Sec. 3.2 (64-bit Sign-OPORP codes of the same items, the paper's billion-member
-setting of Sec. 5.3) for B in {1, 32}, with its own roofline and oracle timing; a third, "live_update",
+setting of Sec. 5.3) for B in {1, 32, 128}, with its own roofline and oracle timing; a third, "live_update",
 measures search latency next to concurrent upserts and deletes (Sec. 5.3, Table 5); a fourth, "clause_lists",
 runs the paper's own benchmark shape (Sec. 5.3, Tables 3 and 4) with 64-bit clause lists as the filter.
 
@@ -72,7 +72,7 @@ def timed_steps(L, ix, w, k, steps, warmup, workspace, out):
 
 def quantised_leg(L, S, base, index_cols, N, k, args, dev):
     """Search over 1-bit Sign-OPORP codes (Sec. 3.2) of the same N items: codes + mask resident (12 bytes per item at
-    64 bits), filtered top-k by matching bits, B in {1, 32} at the headline pass rate.  The codes are made by the
+    64 bits), filtered top-k by matching bits, B in {1, 32, 128} at the headline pass rate.  The codes are made by the
     library (linr_quantize_queries over the de-quantised rows, chunk by chunk); the index is codes-only."""
     import numpy as np
     import torch
@@ -96,7 +96,7 @@ def quantised_leg(L, S, base, index_cols, N, k, args, dev):
     stream = torch.cuda.current_stream().cuda_stream
     C = 10_000 if N >= 100_000_000 else max(10, N // 100_000)
     res, keep = {}, None
-    for B in (1, 32):
+    for B in (1, 32, 128):
         w = S.config5(device=dev, n=N, B=B, k=k, selectivity=args.selectivity, index=index_cols, C=C)
         Qf = (w["Q"].float() * w["q_scale"].reshape(B, 1, 1)).reshape(B, d).contiguous()
         qbits = helper.quantize(Qf)
@@ -142,13 +142,16 @@ def quantised_leg(L, S, base, index_cols, N, k, args, dev):
                         "kernel": "scan_kernel_bits, largest sweep of the B=1 search",
                         "kernel_ms": res["B1"]["largest_sweep_ms"], "items_per_launch": res["B1"]["largest_sweep_items"],
                         "algorithmic_bytes_per_launch": res["B1"]["largest_sweep_items"] * bpi}}
-    # many queries: bound by the vector ALUs.  One item-query pair costs at least 2 W xor + 2 W popcount lane-operations
-    # (32-bit each); 256 CUs x 64 lanes x 2.4 GHz lane-operations per second.
-    alu_peak = 256 * 64 * 2.4e9 / (4 * W)
-    out["roofline_B32"] = {"bound": "alu", "achieved": res["B32"]["pairs_per_s_largest_sweep"], "peak": alu_peak,
-                           "unit": "item-query pairs/s", "frac": res["B32"]["pairs_per_s_largest_sweep"] / alu_peak,
-                           "kernel": "scan_kernel_bits, largest sweep of the B=32 search",
-                           "kernel_ms": res["B32"]["largest_sweep_ms"], "items_per_launch": res["B32"]["largest_sweep_items"]}
+    # two dozen queries or more run on the matrix cores (one int8 16x16x64 instruction per 16 items x 16 queries x 64 code
+    # bits): 2 * 64 W operations per item-query pair against the dense int8 peak
+    for B in (32, 128):
+        tops = res[f"B{B}"]["pairs_per_s_largest_sweep"] * 2 * 64 * W / 1e12
+        out[f"roofline_B{B}"] = {"bound": "mfma", "achieved": tops, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                                 "frac": tops / INT8_PEAK_TOPS,
+                                 "kernel": f"scan_kernel_bits_mfma, largest sweep of the B={B} search",
+                                 "kernel_ms": res[f"B{B}"]["largest_sweep_ms"],
+                                 "items_per_launch": res[f"B{B}"]["largest_sweep_items"],
+                                 "pairs_per_s": res[f"B{B}"]["pairs_per_s_largest_sweep"]}
     if not args.no_cpu:
         import oracle
         ns = min(N, 500_000_000)
