@@ -1747,6 +1747,7 @@ __global__ void __launch_bounds__(64 * WPB, (QG * W <= 4 ? 3 : 2)) scan_kernel_b
     __shared__ WaveQ<QG> wq_all[WPB];
     __shared__ uint32_t hist_all[WPB][SCRATCH];
     __shared__ u64 stage_all[WPB][CH * W];
+    __shared__ __attribute__((aligned(16))) uint32_t stage_side[WPB][2][CH];     // masks, timestamps of the chunk
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
     WaveQ<QG>& Wq = wq_all[wib];
     const QSide qs = {Wq.cnt, Wq.thr_f, Wq.thr_i, Wq.fall, Wq.fnone, Wq.tsmin, Wq.tsmax, Wq.fflag};
@@ -1762,6 +1763,7 @@ __global__ void __launch_bounds__(64 * WPB, (QG * W <= 4 ? 3 : 2)) scan_kernel_b
     // ---- query operand: bits -> +1 / -1 bytes; accumulator start = number of 0 bits of the code
     v4i q[QG][W];
     v4i cinit[QG];
+    int zeros_q[QG];
 #pragma unroll
     for (int i = 0; i < QG; ++i) {
         const uint32_t qi = q_first + i * 16 + row;
@@ -1778,8 +1780,7 @@ __global__ void __launch_bounds__(64 * WPB, (QG * W <= 4 ? 3 : 2)) scan_kernel_b
             }
             zeros += 64 - __popcll(code);
         }
-        zeros -= 64 * W - (int)A.k_bits;                                    // bits beyond k_bits are 0 in every code
-        cinit[i] = (v4i){zeros, zeros, zeros, zeros};
+        zeros_q[i] = zeros - (64 * W - (int)A.k_bits);                      // bits beyond k_bits are 0 in every code
     }
 
     for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) {
@@ -1789,18 +1790,30 @@ __global__ void __launch_bounds__(64 * WPB, (QG * W <= 4 ? 3 : 2)) scan_kernel_b
     wave_sync();
     int thr_i[QG];
     uint32_t f_all[QG], f_none[QG];
+    // The accumulators start at (zero bits of the query) - (the query's bound), so that they hold matches - bound and
+    // "some item of the tile reaches some query's bound" is one running maximum over all groups against 0: two vector
+    // instructions per matrix instruction.  No bound yet: a start value that keeps everything non-negative.
+    auto set_start = [&]() {
 #pragma unroll
-    for (int i = 0; i < QG; ++i) {
-        thr_i[i] = Wq.thr_i[i * 16 + row];
-        f_all[i] = Wq.fall[i * 16 + row]; f_none[i] = Wq.fnone[i * 16 + row];
-    }
+        for (int i = 0; i < QG; ++i) {
+            thr_i[i] = Wq.thr_i[i * 16 + row];
+            const int c = zeros_q[i] + (thr_i[i] == INT_MIN ? (1 << 30) : -thr_i[i]);
+            cinit[i] = (v4i){c, c, c, c};
+        }
+    };
+    set_start();
+#pragma unroll
+    for (int i = 0; i < QG; ++i) { f_all[i] = Wq.fall[i * 16 + row]; f_none[i] = Wq.fnone[i * 16 + row]; }
 
     // ---- items: a chunk's code words travel through registers (next chunk in flight, two items per lane) into the
     // wave's LDS area, from which a lane picks the word of its tile row (keeps the tile loop rolled)
     const u64* codes = (const u64*)A.emb;
     const u64 last = A.n - 1;
     u64* stage = stage_all[wib];
+    uint32_t* stage_mk = stage_side[wib][0];
+    uint32_t* stage_ts = stage_side[wib][1];
     u64 nxt[2][W];
+    uint32_t nxt_mk[2], nxt_ts[2] = {0u, 0u};
     auto issue = [&](u64 lc) {
         const u64 item0 = lc * A.stride * CH;
 #pragma unroll
@@ -1809,6 +1822,8 @@ __global__ void __launch_bounds__(64 * WPB, (QG * W <= 4 ? 3 : 2)) scan_kernel_b
             it = it < last ? it : last;
 #pragma unroll
             for (int w = 0; w < W; ++w) nxt[h][w] = __builtin_nontemporal_load(codes + it * W + w);
+            nxt_mk[h] = __builtin_nontemporal_load(A.mask + it);
+            if (has_ts) nxt_ts[h] = __builtin_nontemporal_load(A.ts + it);
         }
     };
     uint32_t need_compact = 0u, since_refresh = 0u;
@@ -1822,44 +1837,50 @@ __global__ void __launch_bounds__(64 * WPB, (QG * W <= 4 ? 3 : 2)) scan_kernel_b
         for (int h = 0; h < 2; ++h)
 #pragma unroll
             for (int w = 0; w < W; ++w) stage[(h * 64 + lane) * W + w] = nxt[h][w];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) { stage_mk[h * 64 + lane] = nxt_mk[h]; stage_ts[h * 64 + lane] = nxt_ts[h]; }
         wave_sync();
         walk.advance();
         const u64 nlc = walk.lc();
         if (walk.valid()) issue(nlc);
 
+        u64 code_next[W];                                 // the next tile's words are read one tile ahead
+#pragma unroll
+        for (int w = 0; w < W; ++w) code_next[w] = stage[row * W + w];
 #pragma unroll 1
         for (int t = 0; t < TPC; ++t) {
             v4i a[W];
 #pragma unroll
             for (int w = 0; w < W; ++w) {
-                const u64 code = stage[(t * 16 + row) * W + w];
+                const u64 code = code_next[w];
+                code_next[w] = stage[(((t + 1) & (TPC - 1)) * 16 + row) * W + w];
                 const uint32_t half = hi_half ? (uint32_t)(code >> 32) : (uint32_t)code;
                 a[w] = expand16((half >> sh) & 0xFFFFu);
             }
             const int ib = t * 16 + 4 * g4;               // first of this lane's four items (output rows) in the chunk
             v4i acc[QG];
-            u64 any_hot = 0;
-            u64 hot[QG];
+            int best = INT_MIN;
 #pragma unroll
             for (int i = 0; i < QG; ++i) {
                 v4i c = cinit[i];
 #pragma unroll
                 for (int w = 0; w < W; ++w) c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[w], q[i][w], c, 0, 0, 0);
                 acc[i] = c;
-                const int mx = max(max(c[0], c[1]), max(c[2], c[3]));
-                hot[i] = wave_ballot(mx >= thr_i[i]);
-                any_hot |= hot[i];
+                best = max(max(best, c[0]), c[1]);
+                best = max(max(best, c[2]), c[3]);
             }
-            if (any_hot) {
-                // masks (and timestamps) of the lane's four items: read only now -- tiles without a survivor never ask
-                v4u mk4, ts4 = {0, 0, 0, 0};
+            if (wave_any(best >= 0)) {
+                u64 hot[QG];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    u64 it = item0 + ib + r;
-                    it = it < last ? it : last;
-                    mk4[r] = A.mask[it];
-                    if (has_ts) ts4[r] = A.ts[it];
+                for (int i = 0; i < QG; ++i) {
+                    hot[i] = wave_ballot(max(max(acc[i][0], acc[i][1]), max(acc[i][2], acc[i][3])) >= 0);
+                    const int back = thr_i[i] == INT_MIN ? -(1 << 30) : thr_i[i];      // back to match counts
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[i][r] += back;
                 }
+                // masks and timestamps of the lane's four items, staged with the codes
+                const v4u mk4 = *(const v4u*)&stage_mk[ib];
+                const v4u ts4 = *(const v4u*)&stage_ts[ib];
 #pragma unroll
                 for (int i = 0; i < QG; ++i)
                     if (hot[i])
@@ -1879,8 +1900,7 @@ __global__ void __launch_bounds__(64 * WPB, (QG * W <= 4 ? 3 : 2)) scan_kernel_b
         if (refresh) {
             for (uint32_t ql = lane; ql < (uint32_t)NQ; ql += 64) load_query_side(qs, ql, q_first + ql, A, false);
             wave_sync();
-#pragma unroll
-            for (int i = 0; i < QG; ++i) thr_i[i] = Wq.thr_i[i * 16 + row];
+            set_start();
             since_refresh = 0;
         }
         lc = nlc;
