@@ -319,10 +319,11 @@ int linr_last_hip_error(void);
  *   min_sample     : smallest first sweep, in items;
  *   blocks_per_cu  : persistent workgroups per compute unit for the scan;
  *   max_levels     : upper bound on the number of sweeps (1 = single full sweep);
- *   force_generic  : 1 = always use the kernel that streams queries from LDS;
+ *   force_generic  : 1 = always use the kernel that streams queries from LDS (searches over 1-bit codes: always
+ *                    the matrix-core bit-matching kernel);
  *   max_qg         : cap on the 16-query groups one wave keeps in registers (larger
  *                    batches are then split over several waves per chunk);
- *   no_coop        : 1 = never use the workgroup-cooperative scan kernel;
+ *   no_coop        : 1 = never use the workgroup-cooperative scan kernel (1-bit codes: always the popcount kernel);
  *   coop_min_groups: use that kernel for batches of more than this many 16-query groups;
  *   no_top_split   : 1 = do not split the last sweep into the finer 1/8, 3/8, 1/2 sweeps;
  *   wide_min_batch : use the 32x32-tile kernel (int8, m = 1, rows of 64 / 128 / 256 bytes) for batches of at
