@@ -2272,7 +2272,8 @@ __global__ void __launch_bounds__(256) mask_or_kernel(const uint32_t* mask, u64 
 
 // Second stage of the two-stage search: one workgroup per query scores its T candidates with the
 // full-precision embeddings (fp32 accumulation), sorts them by (score desc, id asc) and writes the first k.
-__global__ void __launch_bounds__(256) rescore_kernel(linr_rescore_args A)
+#define RESCORE_T 1024
+__global__ void __launch_bounds__(RESCORE_T) rescore_kernel(linr_rescore_args A)
 {
     __shared__ u64 keys[LINR_MAX_K];
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
@@ -2280,29 +2281,26 @@ __global__ void __launch_bounds__(256) rescore_kernel(linr_rescore_args A)
     if (c > A.T) c = A.T;
     uint32_t P = 1;
     while (P < c) P <<= 1;
-    for (uint32_t j = tid; j < P; j += 256) {
-        u64 key = 0ull;
-        if (j < c) {
-            const uint32_t id = A.cand_ids[(u64)b * A.T + j];
-            float s = 0.0f;
-            if (A.dtype == LINR_F32) {
-                const float* q = (const float*)A.Q + (u64)b * A.d;
-                const float* x = (const float*)A.emb + (u64)id * A.d;
-                for (uint32_t e = 0; e < A.d; ++e) s += q[e] * x[e];
-            } else {
-                const uint16_t* q = (const uint16_t*)A.Q + (u64)b * A.d;
-                const uint16_t* x = (const uint16_t*)A.emb + (u64)id * A.d;
-                for (uint32_t e = 0; e < A.d; ++e)
-                    s += __uint_as_float((uint32_t)q[e] << 16) * __uint_as_float((uint32_t)x[e] << 16);
-            }
-            key = ((u64)ord_f32(s) << 32) | (u64)(uint32_t)~id;
-        }
-        keys[j] = key;
+    // sixteen lanes per candidate: each reads 16 bytes of every 256-byte stretch of the row, four exchanges for the sum
+    const uint32_t grp = tid >> 4, sub = tid & 15;
+    const char* q = (const char*)A.Q + (u64)b * A.row_bytes;
+    for (uint32_t j0 = 0; j0 < P; j0 += RESCORE_T / 16) {
+        const uint32_t j = j0 + grp;
+        const bool valid = j < c;
+        const uint32_t id = valid ? A.cand_ids[(u64)b * A.T + j] : 0u;
+        const char* x = (const char*)A.emb + (u64)id * A.row_bytes;
+        float part = 0.0f;
+        if (valid)
+            for (uint32_t off = sub * 16; off < A.row_bytes; off += 256)
+                part += A.dtype == LINR_F32 ? dot_f32_row((const float*)(q + off), (const float*)(x + off), 4)
+                                            : dot_bf16_row((const uint16_t*)(q + off), (const uint16_t*)(x + off), 8);
+        part += __shfl_xor(part, 8); part += __shfl_xor(part, 4); part += __shfl_xor(part, 2); part += __shfl_xor(part, 1);
+        if (sub == 0 && j < P) keys[j] = valid ? (((u64)ord_f32(part) << 32) | (u64)(uint32_t)~id) : 0ull;
     }
     __syncthreads();
     for (uint32_t size = 2; size <= P; size <<= 1)
         for (uint32_t str = size >> 1; str > 0; str >>= 1) {
-            for (uint32_t j = tid; j < P; j += 256) {
+            for (uint32_t j = tid; j < P; j += RESCORE_T) {
                 const uint32_t o = j ^ str;
                 if (o > j) {
                     const u64 xk = keys[j], yk = keys[o];
@@ -2313,7 +2311,7 @@ __global__ void __launch_bounds__(256) rescore_kernel(linr_rescore_args A)
             __syncthreads();
         }
     const uint32_t nout = c < A.k ? c : A.k;
-    for (uint32_t j = tid; j < A.k; j += 256) {
+    for (uint32_t j = tid; j < A.k; j += RESCORE_T) {
         const u64 o = (u64)b * A.k + j;
         if (j < nout) {
             A.out_ids[o] = ~(uint32_t)keys[j];
@@ -3017,7 +3015,7 @@ hipError_t linr_launch_mask_or(const uint32_t* mask, uint64_t n, uint32_t* out, 
 hipError_t linr_launch_rescore(const linr_rescore_args& a, hipStream_t s)
 {
     if (a.T > LINR_MAX_K || a.k > a.T) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(rescore_kernel, dim3(a.B), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(rescore_kernel, dim3(a.B), dim3(RESCORE_T), 0, s, a);
     return hipGetLastError();
 }
 
