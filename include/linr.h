@@ -151,6 +151,26 @@ int linr_search_filtered(const linr_index*, const void* Q, const float* q_scale,
                          uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
                          void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags);
 
+/*
+ * The same search by explicit pre-filtering (Sec. 3.1.2 "KNN with Explicit Pre-Filtering"):
+ * one pass over the mask (and timestamp) column decides feasibility, only the feasible
+ * (item, query) pairs are scored -- their rows gathered with 16-byte loads -- and one
+ * selection over their keys gives the top k; the embeddings of infeasible items are never
+ * read.  Same arguments and results as linr_search_filtered (fp32 / bf16 scores within the
+ * usual tolerance of it, int8 bit-identical); workspace from
+ * linr_search_prefilter_workspace_bytes.  Queries are answered in groups of 32.  Faster
+ * when few items are feasible (1e9 items, 0.1 % feasible, one query: about a tenth of the
+ * time), slower when many are: the caller chooses, as between the paper's two variants.  A
+ * query with more feasible items than the candidate arrays of the workspace hold is not
+ * answered: out_counts[b] = LINR_COUNT_OVERFLOW, its other outputs are undefined.
+ */
+#define LINR_COUNT_OVERFLOW 0xFFFFFFFFu
+int linr_search_prefilter_workspace_bytes(const linr_index*, uint32_t B, uint32_t m, uint32_t k, uint64_t* bytes);
+int linr_search_filtered_prefilter(const linr_index*, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                                   const linr_filter* filters, uint32_t k,
+                                   uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
+                                   void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags);
+
 int linr_index_destroy(linr_index*);
 
 /*
@@ -249,9 +269,8 @@ int linr_search_clauses(const linr_index*, const void* Q, const float* q_scale, 
  * tolerance of each other, int8 bit-identical).  Faster when few items are feasible,
  * slower when many are (the caller chooses, as between the paper's two variants).  A query
  * with more feasible items than the candidate arrays of the workspace hold (several
- * million) is not answered: out_counts[b] = 0xFFFFFFFF, its other outputs are undefined.
+ * million) is not answered: out_counts[b] = LINR_COUNT_OVERFLOW, its other outputs are undefined.
  */
-#define LINR_COUNT_OVERFLOW 0xFFFFFFFFu
 int linr_search_clauses_prefilter(const linr_index*, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
                                   const uint64_t* q_values, const uint8_t* q_counts, uint32_t q_width, uint32_t k,
                                   uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,

@@ -12,6 +12,6 @@ from .binding import (  # noqa: F401
     search_two_stage_workspace_bytes, search_two_stage,
     index_enable_updates, index_upsert, index_delete, index_sync_updates,
     index_load_clauses, search_clauses_workspace_bytes, search_clauses, search_clauses_timed,
-    search_clauses_prefilter, index_upsert_clauses,
+    search_clauses_prefilter, index_upsert_clauses, search_prefilter_workspace_bytes, search_filtered_prefilter,
     Index,
 )

@@ -35,6 +35,7 @@ EXPORTS = [
     "linr_index_enable_updates", "linr_index_upsert", "linr_index_delete", "linr_index_sync_updates",
     "linr_index_load_clauses", "linr_search_clauses_workspace_bytes", "linr_search_clauses", "linr_search_clauses_timed",
     "linr_search_clauses_prefilter", "linr_index_upsert_clauses",
+    "linr_search_prefilter_workspace_bytes", "linr_search_filtered_prefilter",
 ]
 
 
@@ -78,6 +79,10 @@ def load_library():
     sargs = [vp, vp, vp, u32, u32, vp, u32, vp, vp, vp, vp, vp, u64, vp, u32]
     lib.linr_search_filtered.restype = i32
     lib.linr_search_filtered.argtypes = sargs
+    lib.linr_search_prefilter_workspace_bytes.restype = i32
+    lib.linr_search_prefilter_workspace_bytes.argtypes = [vp, u32, u32, u32, C.POINTER(u64)]
+    lib.linr_search_filtered_prefilter.restype = i32
+    lib.linr_search_filtered_prefilter.argtypes = sargs
     lib.linr_search_filtered_timed.restype = i32
     lib.linr_search_filtered_timed.argtypes = sargs + [vp, C.POINTER(u32), vp, vp]
     lib.linr_index_destroy.restype = i32
@@ -203,6 +208,19 @@ def search_filtered(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_r
     _check(load_library().linr_search_filtered(ix, _ptr(Q), _ptr(q_scale), B, m, _ptr(filters), k, _ptr(out_ids),
                                                _ptr(out_scores), _ptr(out_raw), _ptr(out_counts), _ptr(workspace),
                                                workspace_bytes, stream, flags), "linr_search_filtered")
+
+
+def search_prefilter_workspace_bytes(ix, B, m, k) -> int:
+    out = C.c_uint64()
+    _check(load_library().linr_search_prefilter_workspace_bytes(ix, B, m, k, C.byref(out)), "linr_search_prefilter_workspace_bytes")
+    return out.value
+
+
+def search_filtered_prefilter(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_raw, out_counts,
+                              workspace, workspace_bytes, stream=0, flags=FILTERS_ON_DEVICE):
+    _check(load_library().linr_search_filtered_prefilter(ix, _ptr(Q), _ptr(q_scale), B, m, _ptr(filters), k, _ptr(out_ids),
+                                                         _ptr(out_scores), _ptr(out_raw), _ptr(out_counts), _ptr(workspace),
+                                                         workspace_bytes, stream, flags), "linr_search_filtered_prefilter")
 
 
 def search_filtered_timed(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_raw, out_counts,
@@ -460,9 +478,10 @@ class Index:
     def info(self):
         return index_info(self.handle)
 
-    def search(self, Q, filters, k, q_scale=None, workspace=None, want_raw=True):
+    def search(self, Q, filters, k, q_scale=None, workspace=None, want_raw=True, prefilter=False):
         """Q: device tensor [B, m, d] (or [B, d]); filters: numpy records (host) or a device uint8/int32
-        tensor of B*40 bytes.  Returns device tensors ids (int32 bits of uint32), scores, raw, counts."""
+        tensor of B*40 bytes.  Returns device tensors ids (int32 bits of uint32), scores, raw, counts.
+        prefilter=True: the explicit pre-filtering strategy (linr_search_filtered_prefilter)."""
         import torch
         if Q.dim() == 2:
             Q = Q.unsqueeze(1)
@@ -476,7 +495,7 @@ class Index:
         counts = torch.empty((B,), dtype=torch.int32, device=dev)
         if B == 0:
             return ids, scores, raw, counts
-        nbytes = self.workspace_bytes(B, m, k)
+        nbytes = search_prefilter_workspace_bytes(self.handle, B, m, k) if prefilter else self.workspace_bytes(B, m, k)
         if workspace is None or workspace.numel() < nbytes:
             workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
         if isinstance(filters, np.ndarray):
@@ -484,8 +503,8 @@ class Index:
         else:
             flags, f = FILTERS_ON_DEVICE, filters
         stream = torch.cuda.current_stream(dev).cuda_stream
-        search_filtered(self.handle, Q, q_scale, B, m, f, k, ids, scores, raw, counts, workspace, workspace.numel(),
-                        stream, flags)
+        fn = search_filtered_prefilter if prefilter else search_filtered
+        fn(self.handle, Q, q_scale, B, m, f, k, ids, scores, raw, counts, workspace, workspace.numel(), stream, flags)
         self._last_workspace = workspace
         return ids, scores, raw, counts
 

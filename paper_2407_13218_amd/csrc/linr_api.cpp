@@ -1021,6 +1021,56 @@ extern "C" int linr_search_clauses_workspace_bytes(const linr_index* ix, uint32_
     return clause_layout(cur, B, m, k, &inner, &ow, &of, bytes);
 }
 
+// Explicit pre-filtering (Sec. 3.1.2) for one group of <= 32 queries: only feasible (item, query) pairs are scored --
+// feasibility from one word per item (`words`, clause searches) or from the bitmask / timestamp filters (`filters`,
+// device) -- in two phases (a sample of the items, a merge that publishes the k-th key found, the rest against that
+// bound), then the final merge.  `workspace` / `inner`: a search workspace for this group; vcnt: 4 KB of counters.
+static int prefilter_group(const linr_index& v, const uint32_t* words, const linr_filter* filters, const uint32_t* item_mask,
+                           const uint32_t* item_ts, uint32_t dead_bit, const void* Qg, const float* q_scale_g, uint32_t Bg,
+                           uint32_t m, uint32_t k, uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
+                           void* workspace, uint64_t inner, uint32_t* vcnt, hipStream_t st)
+{
+    if (m == 0 || m > LINR_MAX_M) return LINR_E_SHAPE;
+    if (((uintptr_t)Qg) & 15u) return LINR_E_SHAPE;
+    linr_plan pp;
+    int rc = make_plan(&v, Bg, m, k, &pp);
+    if (rc != LINR_OK) return rc;
+    if (pp.total_bytes > inner) return LINR_E_WORKSPACE;
+    char* ws = (char*)workspace;
+    unsigned long long* tau = (unsigned long long*)(ws + pp.off_tau);
+    uint32_t* cnt = (uint32_t*)(ws + pp.off_cnt);
+    uint32_t* gcnt = (uint32_t*)(ws + pp.off_gcnt);
+    uint32_t* fvalid = (uint32_t*)(ws + pp.off_fvalid);
+    uint32_t* ccnt = (uint32_t*)(ws + pp.off_ccnt);
+    HIP_TRY(linr_launch_init(tau, ccnt, gcnt, fvalid, cnt, (uint64_t)Bg * pp.nslots, Bg, st));
+    linr_prefilter_args pa;
+    memset(&pa, 0, sizeof(pa));
+    pa.words = words; pa.mask = item_mask; pa.ts = item_ts; pa.filters = filters; pa.dead_bit = dead_bit;
+    pa.n = v.n; pa.nq = Bg; pa.dtype = v.dtype; pa.vk = pp.vk; pa.emb = v.emb; pa.row_scale = v.row_scale;
+    pa.row_bytes = v.row_bytes; pa.d = v.d; pa.Q = Qg; pa.m = m;
+    pa.flat = (unsigned long long*)(ws + pp.off_flat); pa.flat_cap = pp.flat_cap;
+    pa.seg = (unsigned long long*)(ws + pp.off_seg); pa.nslots = pp.nslots; pa.cap = pp.cap; pa.B = Bg;
+    pa.vcnt = vcnt; pa.gcnt = gcnt; pa.fvalid = fvalid; pa.cnt = cnt;
+    linr_merge_args ma;
+    memset(&ma, 0, sizeof(ma));
+    ma.tau = tau; ma.cnt = cnt; ma.seg = pa.seg; ma.nslots = pp.nslots; ma.cap = pp.cap; ma.B = Bg; ma.k = k;
+    ma.gcnt = gcnt; ma.fvalid = fvalid; ma.flat = pa.flat; ma.flat_cap = pp.flat_cap;
+    ma.carry = (unsigned long long*)(ws + pp.off_carry); ma.ccnt = ccnt;
+    ma.dtype = v.dtype; ma.vk = pp.vk; ma.emb = v.emb; ma.row_scale = v.row_scale; ma.row_bytes = v.row_bytes; ma.d = v.d;
+    ma.Q = Qg; ma.q_scale = q_scale_g; ma.m = m;
+    ma.out_ids = out_ids; ma.out_scores = out_scores; ma.out_raw = out_raw; ma.out_counts = out_counts;
+    pa.phase = 0; pa.tau = nullptr;
+    HIP_TRY(linr_launch_prefilter(pa, st));
+    ma.final_level = 0;
+    HIP_TRY(linr_launch_merge(ma, st));
+    pa.phase = 1; pa.tau = tau;
+    HIP_TRY(linr_launch_prefilter(pa, st));
+    ma.final_level = 1;
+    HIP_TRY(linr_launch_merge(ma, st));
+    HIP_TRY(linr_launch_prefilter_overflow(vcnt, (uint64_t)pp.flat_cap + (uint64_t)pp.nslots * pp.cap, out_counts, Bg, st));
+    return LINR_OK;
+}
+
 static int search_clauses_impl(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
                                const uint64_t* q_values, const uint8_t* q_counts, uint32_t q_width, uint32_t k,
                                uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts, void* workspace,
@@ -1074,48 +1124,11 @@ static int search_clauses_impl(const linr_index* ix, const void* Q, const float*
             ++stage;
         }
         if (prefilter) {
-            // explicit pre-filtering (Sec. 3.1.2): score the feasible items only, then one final merge
-            if (m == 0 || m > LINR_MAX_M) return LINR_E_SHAPE;
-            if (((uintptr_t)Q) & 15u) return LINR_E_SHAPE;
-            linr_plan pp;
-            rc = make_plan(&v, Bg, m, k, &pp);
+            rc = prefilter_group(v, words, nullptr, nullptr, nullptr, 0, (const char*)Q + (uint64_t)b0 * m * v.row_bytes,
+                                 q_scale ? q_scale + b0 : nullptr, Bg, m, k, out_ids + (uint64_t)b0 * k,
+                                 out_scores + (uint64_t)b0 * k, out_raw ? out_raw + (uint64_t)b0 * k : nullptr, out_counts + b0,
+                                 workspace, inner, (uint32_t*)(filt + 32), st);
             if (rc != LINR_OK) return rc;
-            if (pp.total_bytes > inner) return LINR_E_WORKSPACE;
-            char* ws = (char*)workspace;
-            unsigned long long* tau = (unsigned long long*)(ws + pp.off_tau);
-            uint32_t* cnt = (uint32_t*)(ws + pp.off_cnt);
-            uint32_t* gcnt = (uint32_t*)(ws + pp.off_gcnt);
-            uint32_t* fvalid = (uint32_t*)(ws + pp.off_fvalid);
-            uint32_t* ccnt = (uint32_t*)(ws + pp.off_ccnt);
-            uint32_t* vcnt = (uint32_t*)(filt + 32);
-            HIP_TRY(linr_launch_init(tau, ccnt, gcnt, fvalid, cnt, (uint64_t)Bg * pp.nslots, Bg, st));
-            linr_prefilter_args pa;
-            memset(&pa, 0, sizeof(pa));
-            pa.words = words; pa.n = v.n; pa.nq = Bg; pa.dtype = v.dtype; pa.vk = pp.vk; pa.emb = v.emb; pa.row_scale = v.row_scale;
-            pa.row_bytes = v.row_bytes; pa.d = v.d; pa.Q = (const char*)Q + (uint64_t)b0 * m * v.row_bytes; pa.m = m;
-            pa.flat = (unsigned long long*)(ws + pp.off_flat); pa.flat_cap = pp.flat_cap;
-            pa.seg = (unsigned long long*)(ws + pp.off_seg); pa.nslots = pp.nslots; pa.cap = pp.cap; pa.B = Bg;
-            pa.vcnt = vcnt; pa.gcnt = gcnt; pa.fvalid = fvalid; pa.cnt = cnt;
-            linr_merge_args ma;
-            memset(&ma, 0, sizeof(ma));
-            ma.tau = tau; ma.cnt = cnt; ma.seg = pa.seg; ma.nslots = pp.nslots; ma.cap = pp.cap; ma.B = Bg; ma.k = k;
-            ma.gcnt = gcnt; ma.fvalid = fvalid; ma.flat = pa.flat; ma.flat_cap = pp.flat_cap;
-            ma.carry = (unsigned long long*)(ws + pp.off_carry); ma.ccnt = ccnt;
-            ma.dtype = v.dtype; ma.vk = pp.vk; ma.emb = v.emb; ma.row_scale = v.row_scale; ma.row_bytes = v.row_bytes; ma.d = v.d;
-            ma.Q = pa.Q; ma.q_scale = q_scale ? q_scale + b0 : nullptr; ma.m = m;
-            ma.out_ids = out_ids + (uint64_t)b0 * k; ma.out_scores = out_scores + (uint64_t)b0 * k;
-            ma.out_raw = out_raw ? out_raw + (uint64_t)b0 * k : nullptr; ma.out_counts = out_counts + b0;
-            // phase 0: every 8th run of items, then a merge that publishes the k-th key found; phase 1: the rest,
-            // keeping only keys that are not below it; final merge (the scans' disjoint sweeps, on candidate lists)
-            pa.phase = 0; pa.tau = nullptr;
-            HIP_TRY(linr_launch_prefilter(pa, st));
-            ma.final_level = 0;
-            HIP_TRY(linr_launch_merge(ma, st));
-            pa.phase = 1; pa.tau = tau;
-            HIP_TRY(linr_launch_prefilter(pa, st));
-            ma.final_level = 1;
-            HIP_TRY(linr_launch_merge(ma, st));
-            HIP_TRY(linr_launch_prefilter_overflow(vcnt, (uint64_t)pp.flat_cap + (uint64_t)pp.nslots * pp.cap, out_counts + b0, Bg, st));
             continue;
         }
         uint32_t ns = 0;
@@ -1210,4 +1223,68 @@ extern "C" int linr_index_upsert_clauses(linr_index* ix, const uint32_t* slots, 
     const int rc = body();
     (void)hipSetDevice(dev);
     return rc;
+}
+
+// ---------------------------------------------------------------------------
+// explicit pre-filtering for the bitmask / timestamp filters of linr_search_filtered
+// ---------------------------------------------------------------------------
+extern "C" int linr_search_prefilter_workspace_bytes(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, uint64_t* bytes)
+{
+    if (!ix || !bytes) return LINR_E_NULL;
+    if (B == 0) { *bytes = 256; return LINR_OK; }
+    uint64_t inner = 0;
+    int rc = linr_search_workspace_bytes(ix, B < 32 ? B : 32, m, k, &inner);
+    if (rc != LINR_OK) return rc;
+    *bytes = align_up(inner, 256) + 4096;
+    return LINR_OK;
+}
+
+extern "C" int linr_search_filtered_prefilter(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                                              const linr_filter* filters, uint32_t k, uint32_t* out_ids, float* out_scores,
+                                              int32_t* out_raw, uint32_t* out_counts, void* workspace, uint64_t workspace_bytes,
+                                              void* hip_stream, uint32_t flags)
+{
+    if (!ix) return LINR_E_NULL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    linr_index v;
+    {
+        linr_index snap;
+        v = *view_for(ix, st, true, &snap);
+    }
+    v.upd = nullptr;
+    if (k == 0 || k > LINR_MAX_K) return LINR_E_K;
+    if (m == 0 || m > LINR_MAX_M) return LINR_E_SHAPE;
+    if (v.n == 0 || !v.emb) return LINR_E_NOT_LOADED;
+    if (v.dtype == LINR_BITS) return LINR_E_DTYPE;
+    if (B == 0) return LINR_OK;
+    if (!Q || !filters || !out_ids || !out_scores || !out_counts) return LINR_E_NULL;
+    if (flags & LINR_FILTERS_ON_HOST)
+        for (uint32_t b = 0; b < B; ++b) {
+            if (filters[b].n_any > LINR_MAX_ANY) return LINR_E_FILTER;
+            if (filters[b].ts_min > filters[b].ts_max) return LINR_E_FILTER;
+        }
+    uint64_t inner = 0, total = 0;
+    int rc = linr_search_workspace_bytes(&v, B < 32 ? B : 32, m, k, &inner);
+    if (rc != LINR_OK) return rc;
+    rc = linr_search_prefilter_workspace_bytes(&v, B, m, k, &total);
+    if (rc != LINR_OK) return rc;
+    if (!workspace || (((uintptr_t)workspace) & 255u) || workspace_bytes < total) return LINR_E_WORKSPACE;
+    uint32_t* vcnt = (uint32_t*)((char*)workspace + align_up(inner, 256));
+    for (uint32_t b0 = 0; b0 < B; b0 += 32) {
+        const uint32_t Bg = (B - b0) < 32 ? (B - b0) : 32;
+        const linr_filter* use = filters + b0;
+        if (flags & LINR_FILTERS_ON_HOST) {
+            linr_plan pp;
+            rc = make_plan(&v, Bg, m, k, &pp);
+            if (rc != LINR_OK) return rc;
+            linr_filter* dfilt = (linr_filter*)((char*)workspace + pp.off_filters);
+            HIP_TRY(hipMemcpyAsync(dfilt, filters + b0, (size_t)Bg * sizeof(linr_filter), hipMemcpyHostToDevice, st));
+            use = dfilt;
+        }
+        rc = prefilter_group(v, nullptr, use, v.mask, v.ts, v.dead_bit, (const char*)Q + (uint64_t)b0 * m * v.row_bytes,
+                             q_scale ? q_scale + b0 : nullptr, Bg, m, k, out_ids + (uint64_t)b0 * k, out_scores + (uint64_t)b0 * k,
+                             out_raw ? out_raw + (uint64_t)b0 * k : nullptr, out_counts + b0, workspace, inner, vcnt, st);
+        if (rc != LINR_OK) return rc;
+    }
+    return LINR_OK;
 }

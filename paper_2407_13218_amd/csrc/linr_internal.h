@@ -152,7 +152,8 @@ hipError_t linr_launch_bit_filters(linr_filter* filters, uint32_t nq, hipStream_
 // explicit pre-filtering (Sec. 3.1.2): score only the items whose feasibility word has a bit set, append their keys
 // to the query's flat candidate array (first flat_cap keys) and, beyond that, to the per-slot segments
 struct linr_prefilter_args {
-    const uint32_t* words; uint64_t n; uint32_t nq;
+    const uint32_t* words; uint64_t n; uint32_t nq;   // words == nullptr: feasibility from the filters below instead
+    const uint32_t* mask; const uint32_t* ts; const linr_filter* filters; uint32_t dead_bit;
     int dtype, vk; const void* emb; const float* row_scale; uint32_t row_bytes, d; const void* Q; uint32_t m;
     unsigned long long* flat; uint32_t flat_cap; unsigned long long* seg; uint32_t nslots, cap, B;
     uint32_t* vcnt;             // [32 x 32 words] per query, a 128-byte line each: word 0 keys appended in this phase,

@@ -2092,6 +2092,25 @@ __global__ void __launch_bounds__(256) prefilter_score_kernel(linr_prefilter_arg
     u64* keys = keys_all[threadIdx.x >> 6];
     const u64 wave = ((u64)blockIdx.x * blockDim.x + threadIdx.x) >> 6, n_waves = ((u64)gridDim.x * blockDim.x) >> 6;
     const u64 n_runs = (A.n + 64 * R - 1) / (64 * R);
+    // bitmask / timestamp filters (no feasibility words given): the queries' filters in the compact form the scans use
+    __shared__ uint32_t f_must[32], f_care[32], f_t0[32], f_t1[32], f_any[32];
+    const bool from_filters = A.words == nullptr;
+    const bool has_ts = A.ts != nullptr;
+    if (from_filters) {
+        if (threadIdx.x < 32) {
+            const uint32_t b = threadIdx.x;
+            linr_filter F;
+            if (b < A.nq) F = A.filters[b];
+            else { F.all_bits = 0xFFFFFFFFu; F.none_bits = 0xFFFFFFFFu; F.n_any = 0; F.ts_min = 1; F.ts_max = 0; }
+            const uint32_t none = F.none_bits | A.dead_bit;
+            const bool impossible = (F.all_bits & none) != 0u || F.ts_min > F.ts_max;
+            f_must[b] = impossible ? 0xFFFFFFFFu : F.all_bits;
+            f_care[b] = impossible ? 0u : (F.all_bits | none);
+            f_t0[b] = F.ts_min; f_t1[b] = F.ts_max;
+            f_any[b] = F.n_any ? 1u : 0u;
+        }
+        __syncthreads();
+    }
     for (u64 rr = wave; ; rr += n_waves) {
         // phase 0: runs 0, 8, 16, ...; phase 1: the others
         const u64 run = A.phase == 0 ? rr * LINR_PREFILTER_SAMPLE
@@ -2103,8 +2122,22 @@ __global__ void __launch_bounds__(256) prefilter_score_kernel(linr_prefilter_arg
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const u64 i = run0 + (u64)r * 64 + lane;
-            w[r] = i < A.n ? A.words[i] : 0u;
-            any |= w[r];
+            uint32_t word = 0u;
+            if (i < A.n) {
+                if (!from_filters) word = A.words[i];
+                else {
+                    const uint32_t mk = __builtin_nontemporal_load(A.mask + i);
+                    const uint32_t t = has_ts ? __builtin_nontemporal_load(A.ts + i) : 0u;
+                    for (uint32_t b = 0; b < A.nq; ++b) {
+                        bool ok = (mk & f_care[b]) == f_must[b];
+                        if (has_ts) ok = ok && t >= f_t0[b] && t <= f_t1[b];
+                        if (ok && f_any[b]) ok = filter_pass(A.filters[b], mk, has_ts, t);
+                        word |= ok ? 1u << b : 0u;
+                    }
+                }
+            }
+            w[r] = word;
+            any |= word;
         }
         if (!wave_any(any != 0u)) continue;
         for (uint32_t b = 0; b < A.nq; ++b) {

@@ -5,7 +5,7 @@ import numpy as np
 import synth_inputs as S
 
 
-def run_gpu(w, k=None, tuning=None, want_raw=True, host_filters=True):
+def run_gpu(w, k=None, tuning=None, want_raw=True, host_filters=True, prefilter=False):
     """w: workload dict of torch tensors already on the GPU (see synth_inputs)."""
     import torch
     import paper_2407_13218_amd as L
@@ -18,7 +18,7 @@ def run_gpu(w, k=None, tuning=None, want_raw=True, host_filters=True):
         filt = w["filters"]
         if not host_filters:
             filt = torch.from_numpy(np.ascontiguousarray(filt).view(np.uint8).copy()).cuda()
-        ids, sc, raw, cnt = ix.search(w["Q"], filt, k, q_scale=w["q_scale"], want_raw=want_raw)
+        ids, sc, raw, cnt = ix.search(w["Q"], filt, k, q_scale=w["q_scale"], want_raw=want_raw, prefilter=prefilter)
         torch.cuda.synchronize()
         out = (ids.cpu().numpy().view(np.uint32), sc.cpu().numpy(),
                None if raw is None else raw.cpu().numpy(), cnt.cpu().numpy().view(np.uint32))
