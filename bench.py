@@ -471,6 +471,34 @@ def main():
                 log(f"  sweep B={B:4d} pass {sel:>4}: {r['ms_per_step']:.2f} ms/step  scans {r['all_sweeps_ms']:.2f} ms  "
                     f"{r['hbm_GBs']:.0f} GB/s  {r['int8_TOPs']:.0f} TOP/s  {r['queries_per_s']:.0f} QPS")
 
+    # explicit pre-filtering (Sec. 3.1.2) on the same index, at the pass rate where it pays off
+    pre = []
+    if not args.no_sweep:
+        for B in (1, 32):
+            wq = prepare(B, "0.1%")
+            nb = L.search_prefilter_workspace_bytes(ix.handle, B, 1, k)
+            ws = torch.empty(nb, dtype=torch.uint8, device=dev)
+            o = (torch.empty((B, k), dtype=torch.int32, device=dev), torch.empty((B, k), dtype=torch.float32, device=dev),
+                 torch.empty((B, k), dtype=torch.int32, device=dev), torch.empty((B,), dtype=torch.int32, device=dev))
+            stream = torch.cuda.current_stream().cuda_stream
+
+            def one():
+                L.search_filtered_prefilter(ix.handle, wq["Q"], wq["q_scale"], B, 1, wq["filters_dev"], k, o[0], o[1], o[2], o[3],
+                                            ws, nb, stream, L.FILTERS_ON_DEVICE)
+            for _ in range(2):
+                one()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.sweep_steps):
+                one()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / args.sweep_steps
+            masking = next(r["ms_per_step"] for r in sweep if r["B"] == B and r["selectivity"] == "0.1%")
+            pre.append(dict(B=B, selectivity="0.1%", prefilter_ms_per_step=round(ms, 4), masking_ms_per_step=masking,
+                            overflow=int((o[3] == -1).sum().item()), min_count=int(o[3].min().item())))
+            log(f"  pre-filtering B={B:2d} pass 0.1%: {ms:.3f} ms/step (masking {masking:.3f} ms/step)")
+            del ws
+
     quant = None
     if not args.no_quantised:
         quant = quantised_leg(L, S, base, index_cols, N, k, args, dev)
@@ -528,6 +556,7 @@ def main():
         "cpu_baseline": cpu,
         "stage_ms": {"largest_sweep": head["largest_sweep_ms"], "all_sweeps": head["all_sweeps_ms"], "merges": head["merges_ms"]},
         "sweep": sweep,
+        "prefilter": pre,
         "quantised": quant,
         "two_stage": two_stage,
         "live_update": live,

@@ -159,8 +159,9 @@ int linr_search_filtered(const linr_index*, const void* Q, const float* q_scale,
  * read.  Same arguments and results as linr_search_filtered (fp32 / bf16 scores within the
  * usual tolerance of it, int8 bit-identical); workspace from
  * linr_search_prefilter_workspace_bytes.  Queries are answered in groups of 32.  Faster
- * when few items are feasible (1e9 items, 0.1 % feasible, one query: about a tenth of the
- * time), slower when many are: the caller chooses, as between the paper's two variants.  A
+ * when few (item, query) pairs are feasible (1e9 items, 0.1 % feasible, one query: a third
+ * of the time), slower when many are: the caller chooses, as between the paper's two
+ * variants.  A
  * query with more feasible items than the candidate arrays of the workspace hold is not
  * answered: out_counts[b] = LINR_COUNT_OVERFLOW, its other outputs are undefined.
  */
