@@ -225,3 +225,65 @@ def test_quantised_full_size(oracle_mod):
         say(f"(c) B = {B} query {b}: top-{T} of {N_FULL:,} codes identical to the oracle's")
     ix.close()
     helper.close()
+
+
+def test_clause_lists_full_size(oracle_mod):
+    """The paper's benchmark shape as bench.py times it (15.5 M x d128 bf16, 64-bit clause lists, top-2000, batch 16;
+    high and low pass rate; both strategies):
+      (a) every returned (query, id): feasible under the clause rule (oracle, lists gathered from the GPU columns), score
+          within the float tolerance of the oracle's score of that pair, order, uniqueness, counts;
+      (b) four queries per pass rate against a full oracle scan (1e-3 rule on the k-th score band)."""
+    import torch
+    import paper_2407_13218_amd as L
+    n, d, k, B = 15_500_000, 128, 2000, 16
+    say("generating 15.5 M x d128 bf16 items")
+    w = S.config2(device="cuda", n=n, B=B, k=k, p=0.5)
+    ix = L.Index(n, d, S.BF16, 0)
+    ix.load(w["emb"], w["mask"])
+    emb_h = w["emb"].cpu().numpy().view(np.uint16)
+    Qh = w["Q"].cpu().numpy().view(np.uint16)
+    zero_mask = np.zeros(1, np.uint32)
+    pass_all = S.make_filters(B)
+    threads = max(1, min(16, os.cpu_count() or 1))
+    for low in (False, True):
+        cl = S.job_clauses(device="cuda", n=n, B=B, low_pass=low)
+        ix.load_clauses(cl["values"], cl["counts"], cl["reverse"])
+        vals_h = cl["values"].cpu().numpy().view(np.uint64); cnts_h = cl["counts"].cpu().numpy()
+        qv = cl["q_values"].cpu().numpy().view(np.uint64); qc = cl["q_counts"].cpu().numpy()
+        picks = [0, 5, 9, 15]
+        want = oracle_mod.clause_search(S.BF16, emb_h, vals_h, cnts_h, Qh[picks], qv[picks], qc[picks], cl["reverse"], k + 256,
+                                        nthreads=threads)
+        say(f"{'low' if low else 'high'} pass rate: oracle scans done (feasible, capped: {want[3].tolist()})")
+        for prefilter in (False, True):
+            label = f"{'low' if low else 'high'} pass, {'pre-filtering' if prefilter else 'masking'}"
+            ids, sc, _, cnt = ix.search_clauses(w["Q"], cl["q_values"], cl["q_counts"], k, prefilter=prefilter)
+            torch.cuda.synchronize()
+            ids = ids.cpu().numpy().view(np.uint32); sc = sc.cpu().numpy(); cnt = cnt.cpu().numpy().view(np.uint32)
+            for b in range(B):
+                c = int(cnt[b])
+                assert np.all(ids[b, c:] == S.NO_ID), f"{label} q{b}: padding"
+                if c == 0:
+                    continue
+                got = ids[b, :c].astype(np.int64)
+                assert len(set(got.tolist())) == c, f"{label} q{b}: duplicate ids"
+                feas = oracle_mod.clause_feasible(vals_h[got], cnts_h[got], qv[b], qc[b], cl["reverse"])
+                assert feas.all(), f"{label} q{b}: infeasible id returned"
+                rank, _, _ = oracle_mod.pairs(S.BF16, emb_h[got], np.zeros(c, np.uint32), Qh, pass_all, np.full(c, b), np.arange(c))
+                err = np.abs(sc[b, :c].astype(np.float64) - rank)
+                assert np.all(err <= 1e-3 * np.abs(rank) + 1e-6), f"{label} q{b}: score error {err.max()}"
+                dsc = np.diff(sc[b, :c])
+                assert np.all(dsc <= 0), f"{label} q{b}: scores increase"
+                assert np.all(np.diff(got)[dsc == 0] > 0), f"{label} q{b}: equal scores not in ascending id"
+            for j, b in enumerate(picks):
+                c = int(cnt[b])
+                assert c == min(k, int(want[3][j])), f"{label} q{b}: count {c} vs oracle {min(k, int(want[3][j]))}"
+                if c == 0:
+                    continue
+                tau = float(want[1][j, c - 1])
+                dt = 1e-3 * abs(tau) + 1e-6
+                must = want[0][j, :c][want[1][j, :c] > tau + dt]
+                missing = set(must.tolist()) - set(ids[b, :c].tolist())
+                assert not missing, f"{label} q{b}: {len(missing)} ids above the tolerance band are missing"
+                assert np.all(sc[b, :c] >= tau - dt), f"{label} q{b}: a score below the tolerance band"
+            say(f"{label}: all returned pairs checked, 4 queries against the full oracle scan")
+    ix.close()
