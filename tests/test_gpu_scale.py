@@ -287,3 +287,49 @@ def test_clause_lists_full_size(oracle_mod):
                 assert np.all(sc[b, :c] >= tau - dt), f"{label} q{b}: a score below the tolerance band"
             say(f"{label}: all returned pairs checked, 4 queries against the full oracle scan")
     ix.close()
+
+
+def test_live_updates_full_size(oracle_mod):
+    """config 2 at full size (1e7 x d128 bf16, the index of bench.py's live-update leg): 40 000 upserts into fresh slots and
+    30 000 deletes from a second stream, then the searches of the whole batch prefix against the oracle over the resulting
+    state (deleted slots carry an all-zero mask in the oracle's copy, which no filter of this configuration accepts)."""
+    import torch
+    import paper_2407_13218_amd as L
+    from gpu_util import assert_float_rule
+    say("generating config 2 at full size")
+    w = S.config2(device="cuda", p=0.5)
+    n, d, k, B = w["emb"].shape[0], 128, 1000, 8
+    cap = n + 50_000
+    ix = L.Index(cap, d, S.BF16, 0)
+    ix.load(w["emb"], w["mask"] & 0x7FFFFFFF, src=L.SRC_DEVICE_COPY)
+    ix.enable_updates()
+    filt = w["filters"][:B].copy()
+    filt["all_bits"] &= 0x7FFFFFFF
+    assert np.all(filt["all_bits"] != 0)
+    rng = np.random.default_rng(3)
+    emb_h = np.empty((cap, d), np.uint16); emb_h[:n] = w["emb"].cpu().numpy().view(np.uint16)
+    mask_h = np.zeros(cap, np.uint32); mask_h[:n] = w["mask"].cpu().numpy().view(np.uint32) & 0x7FFFFFFF
+    side = torch.cuda.Stream()
+    mark = n
+    for step in range(40):
+        slots = np.arange(mark, mark + 1000, dtype=np.uint32); mark += 1000
+        src = rng.integers(0, n, 1000)                               # new items: copies of old rows with new masks
+        rows = emb_h[src].copy(); masks = rng.integers(0, 1 << 31, 1000, dtype=np.uint32) | mask_h[src]
+        ix.upsert(slots, rows, masks, stream=side.cuda_stream)
+        emb_h[slots] = rows; mask_h[slots] = masks
+        if step < 30:
+            gone = rng.integers(0, n, 1000).astype(np.uint32)
+            ix.delete(gone, stream=side.cuda_stream)
+            mask_h[gone] = 0
+    ix.sync_updates()
+    assert ix.info()["n"] == mark
+    say("updates applied")
+    ids, sc, _, cnt = ix.search(w["Q"][:B], filt, k)
+    torch.cuda.synchronize()
+    gpu = (ids.cpu().numpy().view(np.uint32), sc.cpu().numpy(), None, cnt.cpu().numpy().view(np.uint32))
+    w2 = dict(w)
+    w2["emb"] = torch.from_numpy(emb_h[:mark].view(np.int16)); w2["mask"] = torch.from_numpy(mask_h[:mark].view(np.int32))
+    w2["Q"] = w["Q"][:B].cpu(); w2["filters"] = filt
+    assert_float_rule(oracle_mod, w2, gpu, k, label="live updates at full size")
+    say("8 queries within tolerance of the oracle's scan over the updated index")
+    ix.close()
