@@ -159,7 +159,7 @@ int linr_search_filtered(const linr_index*, const void* Q, const float* q_scale,
  * read.  Same arguments and results as linr_search_filtered (fp32 / bf16 scores within the
  * usual tolerance of it, int8 bit-identical); workspace from
  * linr_search_prefilter_workspace_bytes.  Queries are answered in groups of 32.  Faster
- * when few (item, query) pairs are feasible (1e9 items, 0.1 % feasible, one query: a third
+ * when few (item, query) pairs are feasible (1e9 items, 0.1 % feasible, one query: a sixth
  * of the time), slower when many are: the caller chooses, as between the paper's two
  * variants.  A
  * query with more feasible items than the candidate arrays of the workspace hold is not

@@ -2072,7 +2072,7 @@ __device__ __forceinline__ float dot_bf16_row(const uint16_t* q, const uint16_t*
 #define LINR_VCNT_STRIDE 32            // words between two queries' counters (a 128-byte line each: no false sharing)
 #define LINR_PREFILTER_RUN 8           // 64-item groups a wave takes at a time (one counter update per query and run)
 
-#define LINR_PREFILTER_SAMPLE 8        // phase 0 takes every 8th run
+#define LINR_PREFILTER_SAMPLE 16       // phase 0 takes every 16th run
 
 __global__ void __launch_bounds__(64) prefilter_zero_kernel(uint32_t* vcnt, uint32_t phase)
 {
@@ -2082,140 +2082,181 @@ __global__ void __launch_bounds__(64) prefilter_zero_kernel(uint32_t* vcnt, uint
     }
 }
 
+#define LINR_PREFILTER_QCAP 512        // (item, query) pairs a wave collects before it scores and places them
+
 __global__ void __launch_bounds__(256) prefilter_score_kernel(linr_prefilter_args A)
 {
-    constexpr int R = LINR_PREFILTER_RUN;
-    __shared__ uint32_t queue_all[256 / 64][64 * R];            // per wave: the run's feasible items of one query ...
-    __shared__ u64 keys_all[256 / 64][64 * R];                  // ... and their keys
-    const int lane = threadIdx.x & 63;
-    uint32_t* queue = queue_all[threadIdx.x >> 6];
-    u64* keys = keys_all[threadIdx.x >> 6];
-    const u64 wave = ((u64)blockIdx.x * blockDim.x + threadIdx.x) >> 6, n_waves = ((u64)gridDim.x * blockDim.x) >> 6;
-    const u64 n_runs = (A.n + 64 * R - 1) / (64 * R);
+    constexpr int R = LINR_PREFILTER_RUN, QCAP = LINR_PREFILTER_QCAP;
+    // per wave: the feasible (item, query) pairs of the current run(s) -- entry = query << 16 | item within the run's
+    // block of 65536 ... here: query << 24 | offset from `base_item` -- their keys, and per query a count / a position
+    __shared__ uint32_t queue_all[256 / 64][QCAP];
+    __shared__ u64 keys_all[256 / 64][QCAP];
+    __shared__ uint32_t hist_all[256 / 64][32], base_all[256 / 64][32];
+    __shared__ u64 bound_all[256 / 64][32];
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    uint32_t* queue = queue_all[wib];
+    u64* keys = keys_all[wib];
+    uint32_t* hist = hist_all[wib];
+    uint32_t* base = base_all[wib];
+    u64* bound = bound_all[wib];
+    // (run numbers fit 32 bits: item ids do)
+    const uint32_t wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, n_waves = (gridDim.x * blockDim.x) >> 6;
+    const uint32_t n_runs = (uint32_t)((A.n + 64 * R - 1) / (64 * R));
     // bitmask / timestamp filters (no feasibility words given): the queries' filters in the compact form the scans use
     __shared__ uint32_t f_must[32], f_care[32], f_t0[32], f_t1[32], f_any[32];
     const bool from_filters = A.words == nullptr;
     const bool has_ts = A.ts != nullptr;
-    if (from_filters) {
-        if (threadIdx.x < 32) {
-            const uint32_t b = threadIdx.x;
-            linr_filter F;
-            if (b < A.nq) F = A.filters[b];
-            else { F.all_bits = 0xFFFFFFFFu; F.none_bits = 0xFFFFFFFFu; F.n_any = 0; F.ts_min = 1; F.ts_max = 0; }
-            const uint32_t none = F.none_bits | A.dead_bit;
-            const bool impossible = (F.all_bits & none) != 0u || F.ts_min > F.ts_max;
-            f_must[b] = impossible ? 0xFFFFFFFFu : F.all_bits;
-            f_care[b] = impossible ? 0u : (F.all_bits | none);
-            f_t0[b] = F.ts_min; f_t1[b] = F.ts_max;
-            f_any[b] = F.n_any ? 1u : 0u;
-        }
-        __syncthreads();
+    if (from_filters && threadIdx.x < 32) {
+        const uint32_t b = threadIdx.x;
+        linr_filter F;
+        if (b < A.nq) F = A.filters[b];
+        else { F.all_bits = 0xFFFFFFFFu; F.none_bits = 0xFFFFFFFFu; F.n_any = 0; F.ts_min = 1; F.ts_max = 0; }
+        const uint32_t none = F.none_bits | A.dead_bit;
+        const bool impossible = (F.all_bits & none) != 0u || F.ts_min > F.ts_max;
+        f_must[b] = impossible ? 0xFFFFFFFFu : F.all_bits;
+        f_care[b] = impossible ? 0u : (F.all_bits | none);
+        f_t0[b] = F.ts_min; f_t1[b] = F.ts_max;
+        f_any[b] = F.n_any ? 1u : 0u;
     }
-    for (u64 rr = wave; ; rr += n_waves) {
-        // phase 0: runs 0, 8, 16, ...; phase 1: the others
-        const u64 run = A.phase == 0 ? rr * LINR_PREFILTER_SAMPLE
-                                     : rr + rr / (LINR_PREFILTER_SAMPLE - 1) + 1;
-        if (run >= n_runs) break;
-        const u64 run0 = run * (64 * R);
+    if (lane < 32) bound[lane] = (A.tau && (uint32_t)lane < A.nq) ? A.tau[lane] : 0ull;     // the phase's bounds do not move
+    __syncthreads();
+
+    // Scores the `qn` queued pairs (sixteen lanes per pair: each reads 16 bytes of every 256-byte stretch of the row, four
+    // exchanges for the sum; all loads of the loop are independent), drops keys below the query's bound, then places
+    // the rest: one LDS count per query, ONE round of counter updates (lane b for query b), one store per key.
+    auto flush = [&](u64 run0, uint32_t qn) {
+        const int grp = lane >> 4, sub = lane & 15;
+        for (uint32_t j0 = 0; j0 < qn; j0 += 4) {
+            const uint32_t j = j0 + (uint32_t)grp;
+            const bool valid = j < qn;
+            const uint32_t ent = valid ? queue[j] : 0u;
+            const uint32_t b = ent >> 24;
+            const u64 i = run0 + (ent & 0xFFFFFFu);
+            const char* x = (const char*)A.emb + i * A.row_bytes;
+            uint32_t hi;
+            if (A.dtype == LINR_I8) {
+                int best = INT_MIN;
+                for (uint32_t e = 0; e < A.m; ++e) {
+                    const char* q = (const char*)A.Q + ((u64)b * A.m + e) * A.row_bytes;
+                    int part = 0;
+                    if (valid)
+                        for (uint32_t off = (uint32_t)sub * 16; off < A.row_bytes; off += 256)
+                            part += dot_i8_row((const int8_t*)(q + off), (const int8_t*)(x + off), 16);
+                    part += __shfl_xor(part, 8); part += __shfl_xor(part, 4); part += __shfl_xor(part, 2); part += __shfl_xor(part, 1);
+                    best = part > best ? part : best;
+                }
+                hi = A.vk == LINR_VK_I8_SCALED ? ord_f32((float)best * (valid ? A.row_scale[i] : 0.0f)) : ord_i32(best);
+            } else {
+                float best = -INFINITY;
+                for (uint32_t e = 0; e < A.m; ++e) {
+                    const char* q = (const char*)A.Q + ((u64)b * A.m + e) * A.row_bytes;
+                    float part = 0.0f;
+                    if (valid)
+                        for (uint32_t off = (uint32_t)sub * 16; off < A.row_bytes; off += 256)
+                            part += A.dtype == LINR_F32 ? dot_f32_row((const float*)(q + off), (const float*)(x + off), 4)
+                                                        : dot_bf16_row((const uint16_t*)(q + off), (const uint16_t*)(x + off), 8);
+                    part += __shfl_xor(part, 8); part += __shfl_xor(part, 4); part += __shfl_xor(part, 2); part += __shfl_xor(part, 1);
+                    best = fmaxf(best, part);
+                }
+                hi = ord_f32(best);
+            }
+            if (valid && sub == 0) {
+                const u64 key = ((u64)hi << 32) | (u64)(uint32_t)~(uint32_t)i;
+                keys[j] = key < bound[b] ? 0ull : key;         // below the k-th key found so far: cannot matter any more
+            }
+        }
+        if (lane < 32) hist[lane] = 0u;
+        wave_sync();
+        uint32_t rank[QCAP / 64];
+#pragma unroll
+        for (int t = 0; t < QCAP / 64; ++t) {
+            const uint32_t j = (uint32_t)t * 64 + lane;
+            rank[t] = (j < qn && keys[j] != 0ull) ? atomicAdd(&hist[queue[j] >> 24], 1u) : 0xFFFFFFFFu;
+        }
+        wave_sync();
+        if (lane < 32) base[lane] = hist[lane] ? atomicAdd(&A.vcnt[lane * LINR_VCNT_STRIDE], hist[lane]) : 0u;
+        wave_sync();
+#pragma unroll
+        for (int t = 0; t < QCAP / 64; ++t) {
+            const uint32_t j = (uint32_t)t * 64 + lane;
+            if (rank[t] == 0xFFFFFFFFu) continue;
+            const uint32_t b = queue[j] >> 24;
+            const uint32_t pos = base[b] + rank[t];
+            const u64 key = keys[j];
+            if (pos < A.flat_cap) {
+                const uint32_t rcap = A.flat_cap / LINR_FLAT_REGIONS;
+                A.flat[(u64)b * A.flat_cap + (u64)(pos % LINR_FLAT_REGIONS) * rcap + pos / LINR_FLAT_REGIONS] = key;
+            } else {
+                const u64 q2 = pos - A.flat_cap;
+                const u64 slot = q2 / A.cap;
+                if (slot < A.nslots) A.seg[(slot * A.B + b) * A.cap + q2 % A.cap] = key;
+            }
+        }
+        wave_sync();
+    };
+
+    for (uint32_t rr = wave; ; rr += n_waves) {
+        // phase 0: runs 0, 16, 32, ...; phase 1: the others
+        const uint32_t run = A.phase == 0 ? rr * LINR_PREFILTER_SAMPLE
+                                          : rr + rr / (LINR_PREFILTER_SAMPLE - 1) + 1;
+        if (run >= n_runs || rr >= n_runs) break;
+        const u64 run0 = (u64)run * (64 * R);
         uint32_t w[R];
         uint32_t any = 0u;
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const u64 i = run0 + (u64)r * 64 + lane;
-            uint32_t word = 0u;
-            if (i < A.n) {
-                if (!from_filters) word = A.words[i];
-                else {
-                    const uint32_t mk = __builtin_nontemporal_load(A.mask + i);
-                    const uint32_t t = has_ts ? __builtin_nontemporal_load(A.ts + i) : 0u;
-                    for (uint32_t b = 0; b < A.nq; ++b) {
-                        bool ok = (mk & f_care[b]) == f_must[b];
-                        if (has_ts) ok = ok && t >= f_t0[b] && t <= f_t1[b];
-                        if (ok && f_any[b]) ok = filter_pass(A.filters[b], mk, has_ts, t);
-                        word |= ok ? 1u << b : 0u;
-                    }
-                }
-            }
-            w[r] = word;
-            any |= word;
-        }
-        if (!wave_any(any != 0u)) continue;
-        for (uint32_t b = 0; b < A.nq; ++b) {
-            // the run's feasible items of query b, densely into the queue
-            uint32_t total = 0;
+        if (!from_filters) {
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                const bool has = (w[r] >> b) & 1u;
-                const u64 bal = wave_ballot(has);
-                if (has) queue[total + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull))] = (uint32_t)(r * 64 + lane);
-                total += (uint32_t)__popcll(bal);
+                const u64 i = run0 + (u64)r * 64 + lane;
+                w[r] = i < A.n ? A.words[i] : 0u;
+                any |= w[r];
             }
-            if (total == 0u) continue;
-            const u64 bound = A.tau ? A.tau[b] : 0ull;
-            wave_sync();
-            // sixteen lanes per feasible (item, query) pair: each reads 16 bytes of every 256-byte stretch of the row
-            // (one coalesced load per pair and stretch), the partial sums meet through four exchanges
-            const int grp = lane >> 4, sub = lane & 15;
-            for (uint32_t j0 = 0; j0 < total; j0 += 4) {
-                const uint32_t j = j0 + (uint32_t)grp;
-                const bool valid = j < total;
-                const u64 i = run0 + (valid ? queue[j] : 0u);
-                const char* x = (const char*)A.emb + i * A.row_bytes;
-                uint32_t hi;
-                if (A.dtype == LINR_I8) {
-                    int best = INT_MIN;
-                    for (uint32_t e = 0; e < A.m; ++e) {
-                        const char* q = (const char*)A.Q + ((u64)b * A.m + e) * A.row_bytes;
-                        int part = 0;
-                        if (valid)
-                            for (uint32_t off = (uint32_t)sub * 16; off < A.row_bytes; off += 256)
-                                part += dot_i8_row((const int8_t*)(q + off), (const int8_t*)(x + off), 16);
-                        part += __shfl_xor(part, 8); part += __shfl_xor(part, 4); part += __shfl_xor(part, 2); part += __shfl_xor(part, 1);
-                        best = part > best ? part : best;
-                    }
-                    hi = A.vk == LINR_VK_I8_SCALED ? ord_f32((float)best * (valid ? A.row_scale[i] : 0.0f)) : ord_i32(best);
-                } else {
-                    float best = -INFINITY;
-                    for (uint32_t e = 0; e < A.m; ++e) {
-                        const char* q = (const char*)A.Q + ((u64)b * A.m + e) * A.row_bytes;
-                        float part = 0.0f;
-                        if (valid)
-                            for (uint32_t off = (uint32_t)sub * 16; off < A.row_bytes; off += 256)
-                                part += A.dtype == LINR_F32 ? dot_f32_row((const float*)(q + off), (const float*)(x + off), 4)
-                                                            : dot_bf16_row((const uint16_t*)(q + off), (const uint16_t*)(x + off), 8);
-                        part += __shfl_xor(part, 8); part += __shfl_xor(part, 4); part += __shfl_xor(part, 2); part += __shfl_xor(part, 1);
-                        best = fmaxf(best, part);
-                    }
-                    hi = ord_f32(best);
-                }
-                if (valid && sub == 0) {
-                    const u64 key = ((u64)hi << 32) | (u64)(uint32_t)~(uint32_t)i;
-                    keys[j] = key < bound ? 0ull : key;        // below the k-th key found so far: cannot matter any more
+        } else {
+            // all loads of the run first, then query by query (its filter constants are uniform) over the eight items
+            uint32_t mk[R], tv[R];
+            bool live[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const u64 i = run0 + (u64)r * 64 + lane;
+                live[r] = i < A.n;
+                const u64 ic = live[r] ? i : A.n - 1;
+                mk[r] = __builtin_nontemporal_load(A.mask + ic);
+                tv[r] = has_ts ? __builtin_nontemporal_load(A.ts + ic) : 0u;
+                w[r] = 0u;
+            }
+            for (uint32_t b = 0; b < A.nq; ++b) {
+                const uint32_t care = f_care[b], must = f_must[b], t0 = f_t0[b], span = f_t1[b] - f_t0[b];
+                const bool cx = f_any[b] != 0u;
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    bool ok = live[r] & ((mk[r] & care) == must);
+                    if (has_ts) ok = ok & (tv[r] - t0 <= span);              // t0 <= ts <= t1 (t0 <= t1 here)
+                    if (cx && ok) ok = filter_pass(A.filters[b], mk[r], has_ts, tv[r]);
+                    w[r] |= ok ? 1u << b : 0u;
                 }
             }
-            wave_sync();
-            // the surviving keys go where the merge looks for candidates; one counter update per query and run
-            for (uint32_t j0 = 0; j0 < total; j0 += 64) {
-                const uint32_t j = j0 + (uint32_t)lane;
-                const u64 key = j < total ? keys[j] : 0ull;
-                const u64 bal = wave_ballot(key != 0ull);
-                if (bal == 0ull) continue;
-                uint32_t base = 0;
-                if (lane == 0) base = atomicAdd(&A.vcnt[b * LINR_VCNT_STRIDE], (uint32_t)__popcll(bal));
-                base = __shfl(base, 0);
-                if (key == 0ull) continue;
-                const uint32_t pos = base + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
-                if (pos < A.flat_cap) {
-                    const uint32_t rcap = A.flat_cap / LINR_FLAT_REGIONS;
-                    A.flat[(u64)b * A.flat_cap + (u64)(pos % LINR_FLAT_REGIONS) * rcap + pos / LINR_FLAT_REGIONS] = key;
-                } else {
-                    const u64 q2 = pos - A.flat_cap;
-                    const u64 slot = q2 / A.cap;
-                    if (slot < A.nslots) A.seg[(slot * A.B + b) * A.cap + q2 % A.cap] = key;
-                }
-            }
-            wave_sync();
+#pragma unroll
+            for (int r = 0; r < R; ++r) any |= w[r];
         }
+        if (!wave_any(any != 0u)) continue;
+        // queue the run's feasible pairs: one pair per lane and trip, lowest query first; a full queue is flushed
+        uint32_t qn = 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            uint32_t word = w[r];
+            while (true) {
+                const u64 bal = wave_ballot(word != 0u);
+                if (bal == 0ull) break;
+                if (qn + 64 > (uint32_t)QCAP) { wave_sync(); flush(run0, qn); qn = 0; }
+                if (word) {
+                    const uint32_t b = (uint32_t)__builtin_ctz(word);
+                    word &= word - 1u;
+                    queue[qn + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull))] = (b << 24) | (uint32_t)(r * 64 + lane);
+                }
+                qn += (uint32_t)__popcll(bal);
+            }
+        }
+        wave_sync();
+        flush(run0, qn);
     }
 }
 

@@ -125,12 +125,12 @@ def test_prefilter_with_many_feasible_items(oracle_mod):
 
 
 def test_prefilter_with_a_million_feasible_items_and_overflow():
-    """1.2 M feasible items for one query: the two phases (a sample, then the rest against the bound the sample gave)
-    keep the candidate arrays small and both strategies agree; with a deliberately small workspace plan the sample
+    """four million feasible items for one query: the two phases (a sample, then the rest against the bound the sample
+    gave) keep the candidate arrays small and both strategies agree; with a deliberately small workspace plan the sample
     itself does not fit and the count says so (0xFFFFFFFF) while the other query is still answered"""
     import torch
     import paper_2407_13218_amd as L
-    n = 2_000_000
+    n = 4_000_000
     rng = np.random.default_rng(0)
     emb = rng.integers(-127, 128, (n, 64), dtype=np.int8)
     values = np.full((n, 1), 7, np.uint64); values[::1000, 0] = 9
@@ -145,7 +145,7 @@ def test_prefilter_with_a_million_feasible_items_and_overflow():
     torch.cuda.synchronize()
     assert np.array_equal(cnt.cpu().numpy(), cnt2.cpu().numpy()) and np.array_equal(ids.cpu().numpy(), ids2.cpu().numpy())
     assert np.array_equal(raw.cpu().numpy(), raw2.cpu().numpy())
-    L.set_tuning(blocks_per_cu=1)                             # 1024 slots x 192 keys + 4096: less than the 250 000 sampled keys
+    L.set_tuning(blocks_per_cu=1)                             # 1024 slots x 192 keys + 4096: less than the 250 000 sampled keys (n / 16)
     try:
         ids, sc, raw, cnt = ix.search_clauses(Q, dev(qv), dev(qc), 5, prefilter=True)
         torch.cuda.synchronize()
