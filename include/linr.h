@@ -346,12 +346,14 @@ int linr_last_hip_error(void);
  *   no_coop        : 1 = never use the workgroup-cooperative scan kernel (1-bit codes: always the popcount kernel);
  *   coop_min_groups: use that kernel for batches of more than this many 16-query groups;
  *   no_top_split   : 1 = do not split the last sweep into the finer 1/8, 3/8, 1/2 sweeps;
+ *   prefilter_phases: 2 or 3 = the explicit pre-filtering searches take that many phases (1/16 of the items, the
+ *                    rest; or 1/256, 15/256, the rest) whatever the index size; 0 = three from 2^26 items on;
  *   wide_min_batch : use the 32x32-tile kernel (int8, m = 1, rows of 64 / 128 / 256 bytes) for batches of at
  *                    least this many queries; 0 = never (the default: it does not beat the other kernels yet).
  */
 typedef struct {
     uint32_t sample_ratio, min_sample, blocks_per_cu, max_levels, force_generic, max_qg, no_coop, coop_min_groups;
-    uint32_t no_top_split, _r1, wide_min_batch, _r3;
+    uint32_t no_top_split, prefilter_phases, wide_min_batch, _r3;
 } linr_tuning;
 int linr_set_tuning(const linr_tuning*);
 

@@ -1023,8 +1023,9 @@ extern "C" int linr_search_clauses_workspace_bytes(const linr_index* ix, uint32_
 
 // Explicit pre-filtering (Sec. 3.1.2) for one group of <= 32 queries: only feasible (item, query) pairs are scored --
 // feasibility from one word per item (`words`, clause searches) or from the bitmask / timestamp filters (`filters`,
-// device) -- in two phases (a sample of the items, a merge that publishes the k-th key found, the rest against that
-// bound), then the final merge.  `workspace` / `inner`: a search workspace for this group; vcnt: 4 KB of counters.
+// device) -- in phases (a small sample of the items, a merge that publishes the k-th key found, the next part against
+// that bound, ...), the last merge being the final one.  `workspace` / `inner`: a search workspace for this group; vcnt: 4 KB of counters.
+#define LINR_PREFILTER_THREE_PHASES (64ull << 20)      // items from which a third, smaller first sample pays
 static int prefilter_group(const linr_index& v, const uint32_t* words, const linr_filter* filters, const uint32_t* item_mask,
                            const uint32_t* item_ts, uint32_t dead_bit, const void* Qg, const float* q_scale_g, uint32_t Bg,
                            uint32_t m, uint32_t k, uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
@@ -1059,14 +1060,18 @@ static int prefilter_group(const linr_index& v, const uint32_t* words, const lin
     ma.dtype = v.dtype; ma.vk = pp.vk; ma.emb = v.emb; ma.row_scale = v.row_scale; ma.row_bytes = v.row_bytes; ma.d = v.d;
     ma.Q = Qg; ma.q_scale = q_scale_g; ma.m = m;
     ma.out_ids = out_ids; ma.out_scores = out_scores; ma.out_raw = out_raw; ma.out_counts = out_counts;
-    pa.phase = 0; pa.tau = nullptr;
-    HIP_TRY(linr_launch_prefilter(pa, st));
-    ma.final_level = 0;
-    HIP_TRY(linr_launch_merge(ma, st));
-    pa.phase = 1; pa.tau = tau;
-    HIP_TRY(linr_launch_prefilter(pa, st));
-    ma.final_level = 1;
-    HIP_TRY(linr_launch_merge(ma, st));
+    // 1/256 of the runs, then 15/256, then the rest (small indexes: 1/16, then the rest)
+    static const uint32_t cuts3[4] = {0, 1, 16, 256}, cuts2[3] = {0, 1, 16};
+    const bool three = g_tuning.prefilter_phases ? g_tuning.prefilter_phases >= 3 : v.n >= LINR_PREFILTER_THREE_PHASES;
+    const uint32_t* cuts = three ? cuts3 : cuts2;
+    const int n_phases = three ? 3 : 2;
+    for (int ph = 0; ph < n_phases; ++ph) {
+        pa.mod = cuts[n_phases]; pa.lo = cuts[ph]; pa.hi = cuts[ph + 1];
+        pa.tau = ph ? tau : nullptr;
+        HIP_TRY(linr_launch_prefilter(pa, st));
+        ma.final_level = ph + 1 == n_phases ? 1 : 0;
+        HIP_TRY(linr_launch_merge(ma, st));
+    }
     HIP_TRY(linr_launch_prefilter_overflow(vcnt, (uint64_t)pp.flat_cap + (uint64_t)pp.nslots * pp.cap, out_counts, Bg, st));
     return LINR_OK;
 }

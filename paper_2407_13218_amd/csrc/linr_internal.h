@@ -159,9 +159,10 @@ struct linr_prefilter_args {
     uint32_t* vcnt;             // [32 x 32 words] per query, a 128-byte line each: word 0 keys appended in this phase,
                                 // word 1 sticky "the candidate arrays were too small"
     uint32_t* gcnt; uint32_t* fvalid; uint32_t* cnt;      // the merge's view of where the keys are
-    // two phases, as the scans' sweeps: phase 0 scores every 16th run of items and a merge publishes the k-th key found
-    // (tau); phase 1 scores the other runs and keeps only keys that are not below it
-    uint32_t phase; const unsigned long long* tau;
+    // phases, as the scans' sweeps: a phase scores the runs of 512 items whose number modulo `mod` lies in [lo, hi); the
+    // first (lo == 0) takes a small sample, a merge publishes the k-th key found (tau), and the later phases keep only
+    // keys that are not below it
+    uint32_t mod, lo, hi; const unsigned long long* tau;
 };
 hipError_t linr_launch_prefilter(const linr_prefilter_args& a, hipStream_t s);   // one phase: zero, score, counts
 // out_counts[b] = 0xFFFFFFFF where vcnt[b] > capacity (run behind the merge)

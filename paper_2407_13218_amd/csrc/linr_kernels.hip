@@ -2069,32 +2069,69 @@ __device__ __forceinline__ float dot_bf16_row(const uint16_t* q, const uint16_t*
     return s;
 }
 
+// sixteen bytes of a row against sixteen bytes of a query, already in registers
+__device__ __forceinline__ int dot16_i8(v4i a, v4i b)
+{
+    int s = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) s = __builtin_amdgcn_sdot4(a[w], b[w], s, false);
+    return s;
+}
+__device__ __forceinline__ float dot16_bf16(v4i a, v4i b)
+{
+    float s = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        s += __uint_as_float((uint32_t)a[w] << 16) * __uint_as_float((uint32_t)b[w] << 16);
+        s += __uint_as_float((uint32_t)a[w] & 0xFFFF0000u) * __uint_as_float((uint32_t)b[w] & 0xFFFF0000u);
+    }
+    return s;
+}
+__device__ __forceinline__ float dot16_f32(v4i a, v4i b)
+{
+    float s = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) s += __int_as_float(a[w]) * __int_as_float(b[w]);
+    return s;
+}
+
 #define LINR_VCNT_STRIDE 32            // words between two queries' counters (a 128-byte line each: no false sharing)
-#define LINR_PREFILTER_RUN 8           // 64-item groups a wave takes at a time (one counter update per query and run)
+#define LINR_PREFILTER_RUN 8           // 64-item groups a wave takes at a time: 512 items, a lane holds 2 x 4 neighbours
 
-#define LINR_PREFILTER_SAMPLE 16       // phase 0 takes every 16th run
-
-__global__ void __launch_bounds__(64) prefilter_zero_kernel(uint32_t* vcnt, uint32_t phase)
+// before the first phase: the counters and the sticky "too many" flags (later phases: the counts kernel re-zeroes)
+__global__ void __launch_bounds__(64) prefilter_zero_kernel(uint32_t* vcnt)
 {
     if (threadIdx.x < 32) {
         vcnt[threadIdx.x * LINR_VCNT_STRIDE] = 0u;
-        if (phase == 0) vcnt[threadIdx.x * LINR_VCNT_STRIDE + 1] = 0u;
+        vcnt[threadIdx.x * LINR_VCNT_STRIDE + 1] = 0u;
     }
 }
 
 #define LINR_PREFILTER_QCAP 512        // (item, query) pairs a wave collects before it scores and places them
 
-__global__ void __launch_bounds__(256) prefilter_score_kernel(linr_prefilter_args A)
+// w <- 2 w + (the lane's bit of `cond`): one instruction appends a query's verdict to the lane's feasibility word
+__device__ __forceinline__ uint32_t shift_in(uint32_t w, u64 cond)
+{
+    uint32_t r;
+    asm("v_addc_co_u32 %0, vcc, %1, %1, %2" : "=v"(r) : "v"(w), "s"(cond) : "vcc");
+    return r;
+}
+
+// MODE 0: one feasibility word per item is given; 1: bitmask filters; 2: bitmask filters and timestamp windows
+template <int MODE>
+__global__ void __launch_bounds__(256, 4) prefilter_score_kernel(linr_prefilter_args A)
 {
     constexpr int R = LINR_PREFILTER_RUN, QCAP = LINR_PREFILTER_QCAP;
-    // per wave: the feasible (item, query) pairs of the current run(s) -- entry = query << 16 | item within the run's
-    // block of 65536 ... here: query << 24 | offset from `base_item` -- their keys, and per query a count / a position
+    // per wave: the feasible (item, query) pairs found so far (item id, query), their keys, and per query a count / a
+    // position.  Pairs of many runs share one flush, so a sparse predicate costs few counter updates.
     __shared__ uint32_t queue_all[256 / 64][QCAP];
+    __shared__ uint8_t qb_all[256 / 64][QCAP];
     __shared__ u64 keys_all[256 / 64][QCAP];
     __shared__ uint32_t hist_all[256 / 64][32], base_all[256 / 64][32];
     __shared__ u64 bound_all[256 / 64][32];
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
     uint32_t* queue = queue_all[wib];
+    uint8_t* qb = qb_all[wib];
     u64* keys = keys_all[wib];
     uint32_t* hist = hist_all[wib];
     uint32_t* base = base_all[wib];
@@ -2102,10 +2139,16 @@ __global__ void __launch_bounds__(256) prefilter_score_kernel(linr_prefilter_arg
     // (run numbers fit 32 bits: item ids do)
     const uint32_t wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, n_waves = (gridDim.x * blockDim.x) >> 6;
     const uint32_t n_runs = (uint32_t)((A.n + 64 * R - 1) / (64 * R));
+    // this phase's runs: those whose number modulo `mod` lies in [lo, hi)
+    const uint32_t per = A.hi - A.lo, rem = n_runs % A.mod;
+    const uint32_t n_sel = (n_runs / A.mod) * per + (rem > A.lo ? (rem - A.lo < per ? rem - A.lo : per) : 0u);
     // bitmask / timestamp filters (no feasibility words given): the queries' filters in the compact form the scans use
-    __shared__ uint32_t f_must[32], f_care[32], f_t0[32], f_t1[32], f_any[32];
-    const bool from_filters = A.words == nullptr;
-    const bool has_ts = A.ts != nullptr;
+    __shared__ uint32_t f_must[32], f_care[32], f_t0[32], f_span[32];
+    __shared__ uint32_t f_any;                 // bit b: query b also has "any of" groups (checked apart, after the loop)
+    constexpr bool from_filters = MODE != 0;
+    constexpr bool has_ts = MODE == 2;
+    if (threadIdx.x == 0) f_any = 0u;
+    __syncthreads();
     if (from_filters && threadIdx.x < 32) {
         const uint32_t b = threadIdx.x;
         linr_filter F;
@@ -2115,23 +2158,68 @@ __global__ void __launch_bounds__(256) prefilter_score_kernel(linr_prefilter_arg
         const bool impossible = (F.all_bits & none) != 0u || F.ts_min > F.ts_max;
         f_must[b] = impossible ? 0xFFFFFFFFu : F.all_bits;
         f_care[b] = impossible ? 0u : (F.all_bits | none);
-        f_t0[b] = F.ts_min; f_t1[b] = F.ts_max;
-        f_any[b] = F.n_any ? 1u : 0u;
+        f_t0[b] = F.ts_min; f_span[b] = F.ts_max - F.ts_min;
+        if (F.n_any && !impossible) atomicOr(&f_any, 1u << b);
     }
     if (lane < 32) bound[lane] = (A.tau && (uint32_t)lane < A.nq) ? A.tau[lane] : 0ull;     // the phase's bounds do not move
     __syncthreads();
 
-    // Scores the `qn` queued pairs (sixteen lanes per pair: each reads 16 bytes of every 256-byte stretch of the row, four
-    // exchanges for the sum; all loads of the loop are independent), drops keys below the query's bound, then places
-    // the rest: one LDS count per query, ONE round of counter updates (lane b for query b), one store per key.
-    auto flush = [&](u64 run0, uint32_t qn) {
-        const int grp = lane >> 4, sub = lane & 15;
-        for (uint32_t j0 = 0; j0 < qn; j0 += 4) {
+    // Scores the `qn` queued pairs (4, 8 or 16 lanes per pair, by the length of a row: each reads 16 bytes of every
+    // stretch, two to four exchanges for the sum; all loads of the loop are independent), drops keys below the query's
+    // bound, then places the rest: one LDS count per query, ONE round of counter updates (lane b for query b), one
+    // store per key.
+    const int lpp_log = A.row_bytes >= 256 ? 4 : A.row_bytes >= 128 ? 3 : 2;
+    auto flush = [&](uint32_t qn) {
+        const int lpp = 1 << lpp_log, ppt = 64 >> lpp_log;
+        const int grp = lane >> lpp_log, sub = lane & (lpp - 1);
+        // rows of exactly one 16-byte piece per lane (64, 128 or 256 bytes), one embedding per query: two trips' loads
+        // are issued before the first product, so twice as many gathers are in flight
+        uint32_t j_from = 0;
+        if (A.m == 1 && A.row_bytes == (uint32_t)lpp * 16) {
+            constexpr int U = 2;
+            for (; j_from < qn; j_from += (uint32_t)(U * ppt)) {
+                v4i xv[U], qv[U];
+                float sc[U];
+                uint32_t jj[U], ii[U], bb[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    jj[u] = j_from + (uint32_t)(u * ppt + grp);
+                    const bool valid = jj[u] < qn;
+                    bb[u] = valid ? qb[jj[u]] : 0u;
+                    ii[u] = valid ? queue[jj[u]] : 0u;           // (item 0 exists: its row is read and dropped)
+                    xv[u] = *(const v4i*)((const char*)A.emb + (u64)ii[u] * A.row_bytes + sub * 16);
+                    sc[u] = A.vk == LINR_VK_I8_SCALED ? A.row_scale[ii[u]] : 1.0f;
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) qv[u] = *(const v4i*)((const char*)A.Q + (u64)bb[u] * A.row_bytes + sub * 16);
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    uint32_t hi;
+                    if (A.dtype == LINR_I8) {
+                        int part = dot16_i8(qv[u], xv[u]);
+                        if (lpp_log > 3) part += __shfl_xor(part, 8);
+                        if (lpp_log > 2) part += __shfl_xor(part, 4);
+                        part += __shfl_xor(part, 2); part += __shfl_xor(part, 1);
+                        hi = A.vk == LINR_VK_I8_SCALED ? ord_f32((float)part * sc[u]) : ord_i32(part);
+                    } else {
+                        float part = A.dtype == LINR_F32 ? dot16_f32(qv[u], xv[u]) : dot16_bf16(qv[u], xv[u]);
+                        if (lpp_log > 3) part += __shfl_xor(part, 8);
+                        if (lpp_log > 2) part += __shfl_xor(part, 4);
+                        part += __shfl_xor(part, 2); part += __shfl_xor(part, 1);
+                        hi = ord_f32(part);
+                    }
+                    if (jj[u] < qn && sub == 0) {
+                        const u64 key = ((u64)hi << 32) | (u64)(uint32_t)~ii[u];
+                        keys[jj[u]] = key < bound[bb[u]] ? 0ull : key;     // below the k-th key found so far: cannot matter
+                    }
+                }
+            }
+        }
+        for (uint32_t j0 = j_from; j0 < qn; j0 += (uint32_t)ppt) {
             const uint32_t j = j0 + (uint32_t)grp;
             const bool valid = j < qn;
-            const uint32_t ent = valid ? queue[j] : 0u;
-            const uint32_t b = ent >> 24;
-            const u64 i = run0 + (ent & 0xFFFFFFu);
+            const uint32_t b = valid ? qb[j] : 0u;
+            const u64 i = valid ? queue[j] : 0u;
             const char* x = (const char*)A.emb + i * A.row_bytes;
             uint32_t hi;
             if (A.dtype == LINR_I8) {
@@ -2140,9 +2228,11 @@ __global__ void __launch_bounds__(256) prefilter_score_kernel(linr_prefilter_arg
                     const char* q = (const char*)A.Q + ((u64)b * A.m + e) * A.row_bytes;
                     int part = 0;
                     if (valid)
-                        for (uint32_t off = (uint32_t)sub * 16; off < A.row_bytes; off += 256)
+                        for (uint32_t off = (uint32_t)sub * 16; off < A.row_bytes; off += (uint32_t)lpp * 16)
                             part += dot_i8_row((const int8_t*)(q + off), (const int8_t*)(x + off), 16);
-                    part += __shfl_xor(part, 8); part += __shfl_xor(part, 4); part += __shfl_xor(part, 2); part += __shfl_xor(part, 1);
+                    if (lpp_log > 3) part += __shfl_xor(part, 8);
+                    if (lpp_log > 2) part += __shfl_xor(part, 4);
+                    part += __shfl_xor(part, 2); part += __shfl_xor(part, 1);
                     best = part > best ? part : best;
                 }
                 hi = A.vk == LINR_VK_I8_SCALED ? ord_f32((float)best * (valid ? A.row_scale[i] : 0.0f)) : ord_i32(best);
@@ -2152,10 +2242,12 @@ __global__ void __launch_bounds__(256) prefilter_score_kernel(linr_prefilter_arg
                     const char* q = (const char*)A.Q + ((u64)b * A.m + e) * A.row_bytes;
                     float part = 0.0f;
                     if (valid)
-                        for (uint32_t off = (uint32_t)sub * 16; off < A.row_bytes; off += 256)
+                        for (uint32_t off = (uint32_t)sub * 16; off < A.row_bytes; off += (uint32_t)lpp * 16)
                             part += A.dtype == LINR_F32 ? dot_f32_row((const float*)(q + off), (const float*)(x + off), 4)
                                                         : dot_bf16_row((const uint16_t*)(q + off), (const uint16_t*)(x + off), 8);
-                    part += __shfl_xor(part, 8); part += __shfl_xor(part, 4); part += __shfl_xor(part, 2); part += __shfl_xor(part, 1);
+                    if (lpp_log > 3) part += __shfl_xor(part, 8);
+                    if (lpp_log > 2) part += __shfl_xor(part, 4);
+                    part += __shfl_xor(part, 2); part += __shfl_xor(part, 1);
                     best = fmaxf(best, part);
                 }
                 hi = ord_f32(best);
@@ -2171,7 +2263,7 @@ __global__ void __launch_bounds__(256) prefilter_score_kernel(linr_prefilter_arg
 #pragma unroll
         for (int t = 0; t < QCAP / 64; ++t) {
             const uint32_t j = (uint32_t)t * 64 + lane;
-            rank[t] = (j < qn && keys[j] != 0ull) ? atomicAdd(&hist[queue[j] >> 24], 1u) : 0xFFFFFFFFu;
+            rank[t] = (j < qn && keys[j] != 0ull) ? atomicAdd(&hist[qb[j]], 1u) : 0xFFFFFFFFu;
         }
         wave_sync();
         if (lane < 32) base[lane] = hist[lane] ? atomicAdd(&A.vcnt[lane * LINR_VCNT_STRIDE], hist[lane]) : 0u;
@@ -2180,7 +2272,7 @@ __global__ void __launch_bounds__(256) prefilter_score_kernel(linr_prefilter_arg
         for (int t = 0; t < QCAP / 64; ++t) {
             const uint32_t j = (uint32_t)t * 64 + lane;
             if (rank[t] == 0xFFFFFFFFu) continue;
-            const uint32_t b = queue[j] >> 24;
+            const uint32_t b = qb[j];
             const uint32_t pos = base[b] + rank[t];
             const u64 key = keys[j];
             if (pos < A.flat_cap) {
@@ -2195,69 +2287,106 @@ __global__ void __launch_bounds__(256) prefilter_score_kernel(linr_prefilter_arg
         wave_sync();
     };
 
-    for (uint32_t rr = wave; ; rr += n_waves) {
-        // phase 0: runs 0, 16, 32, ...; phase 1: the others
-        const uint32_t run = A.phase == 0 ? rr * LINR_PREFILTER_SAMPLE
-                                          : rr + rr / (LINR_PREFILTER_SAMPLE - 1) + 1;
-        if (run >= n_runs || rr >= n_runs) break;
-        const u64 run0 = (u64)run * (64 * R);
+    // word r = 4 h + c of a lane is item run0 + 256 h + 4 lane + c; `a` = feasibility words or masks, `t` = timestamps
+    auto run_of = [&](uint32_t rr) { return (rr / per) * A.mod + A.lo + rr % per; };
+    auto load_run = [&](uint32_t rr, uint32_t (&a)[R], uint32_t (&t)[R]) {
+        const u64 run0 = (u64)run_of(rr) * (64 * R);
+        const uint32_t* src = from_filters ? A.mask : A.words;
+        if (run0 + 64 * R <= A.n) {
+#pragma unroll
+            for (int h = 0; h < R / 4; ++h) {
+                const v4i x = __builtin_nontemporal_load((const v4i*)(src + run0 + 256 * h + 4 * lane));
+                a[4 * h] = (uint32_t)x[0]; a[4 * h + 1] = (uint32_t)x[1]; a[4 * h + 2] = (uint32_t)x[2]; a[4 * h + 3] = (uint32_t)x[3];
+                if (has_ts) {
+                    const v4i u = __builtin_nontemporal_load((const v4i*)(A.ts + run0 + 256 * h + 4 * lane));
+                    t[4 * h] = (uint32_t)u[0]; t[4 * h + 1] = (uint32_t)u[1]; t[4 * h + 2] = (uint32_t)u[2]; t[4 * h + 3] = (uint32_t)u[3];
+                }
+            }
+        } else {                                  // the index's last run: item by item (what lies beyond is dropped below)
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const u64 i = run0 + 256 * (r / 4) + 4 * lane + (r % 4);
+                const u64 ic = i < A.n ? i : A.n - 1;
+                a[r] = src[ic];
+                if (has_ts) t[r] = A.ts[ic];
+            }
+        }
+        if (!has_ts) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) t[r] = 0u;
+        }
+    };
+
+    uint32_t qn = 0;
+    uint32_t cur_a[R], cur_t[R];
+    if (wave < n_sel) load_run(wave, cur_a, cur_t);
+    for (uint32_t rr = wave; rr < n_sel; rr += n_waves) {
+        const u64 run0 = (u64)run_of(rr) * (64 * R);
+        const bool full = run0 + 64 * R <= A.n;
+        // the next run's words are on their way while this one is looked at
+        uint32_t nxt_a[R], nxt_t[R];
+        const bool more = rr + n_waves < n_sel && rr + n_waves > rr;
+        if (more) load_run(rr + n_waves, nxt_a, nxt_t);
         uint32_t w[R];
-        uint32_t any = 0u;
-        if (!from_filters) {
+        if constexpr (!from_filters) {
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const u64 i = run0 + (u64)r * 64 + lane;
-                w[r] = i < A.n ? A.words[i] : 0u;
-                any |= w[r];
-            }
+            for (int r = 0; r < R; ++r) w[r] = cur_a[r];
         } else {
-            // all loads of the run first, then query by query (its filter constants are uniform) over the eight items
-            uint32_t mk[R], tv[R];
-            bool live[R];
+            // query by query (its filter constants are uniform) over the eight items, last query first: each verdict is
+            // shifted into the word from below
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const u64 i = run0 + (u64)r * 64 + lane;
-                live[r] = i < A.n;
-                const u64 ic = live[r] ? i : A.n - 1;
-                mk[r] = __builtin_nontemporal_load(A.mask + ic);
-                tv[r] = has_ts ? __builtin_nontemporal_load(A.ts + ic) : 0u;
-                w[r] = 0u;
-            }
-            for (uint32_t b = 0; b < A.nq; ++b) {
-                const uint32_t care = f_care[b], must = f_must[b], t0 = f_t0[b], span = f_t1[b] - f_t0[b];
-                const bool cx = f_any[b] != 0u;
+            for (int r = 0; r < R; ++r) w[r] = 0u;
+            for (uint32_t b = A.nq; b-- > 0;) {
+                const uint32_t care = f_care[b], must = f_must[b], t0 = has_ts ? f_t0[b] : 0u, span = has_ts ? f_span[b] : 0u;
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
-                    bool ok = live[r] & ((mk[r] & care) == must);
-                    if (has_ts) ok = ok & (tv[r] - t0 <= span);              // t0 <= ts <= t1 (t0 <= t1 here)
-                    if (cx && ok) ok = filter_pass(A.filters[b], mk[r], has_ts, tv[r]);
-                    w[r] |= ok ? 1u << b : 0u;
+                    bool ok = (cur_a[r] & care) == must;
+                    if (has_ts) ok = ok & (cur_t[r] - t0 <= span);           // t0 <= ts <= t1 (t0 <= t1 here)
+                    w[r] = shift_in(w[r], wave_ballot(ok));
                 }
             }
+            for (uint32_t cx = f_any; cx != 0u; cx &= cx - 1u) {
+                const uint32_t b = (uint32_t)__builtin_ctz(cx);
 #pragma unroll
-            for (int r = 0; r < R; ++r) any |= w[r];
-        }
-        if (!wave_any(any != 0u)) continue;
-        // queue the run's feasible pairs: one pair per lane and trip, lowest query first; a full queue is flushed
-        uint32_t qn = 0;
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            uint32_t word = w[r];
-            while (true) {
-                const u64 bal = wave_ballot(word != 0u);
-                if (bal == 0ull) break;
-                if (qn + 64 > (uint32_t)QCAP) { wave_sync(); flush(run0, qn); qn = 0; }
-                if (word) {
-                    const uint32_t b = (uint32_t)__builtin_ctz(word);
-                    word &= word - 1u;
-                    queue[qn + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull))] = (b << 24) | (uint32_t)(r * 64 + lane);
-                }
-                qn += (uint32_t)__popcll(bal);
+                for (int r = 0; r < R; ++r)
+                    if (((w[r] >> b) & 1u) && !filter_pass(A.filters[b], cur_a[r], has_ts, cur_t[r])) w[r] &= ~(1u << b);
             }
         }
-        wave_sync();
-        flush(run0, qn);
+        if (!full) {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (run0 + 256 * (r / 4) + 4 * lane + (r % 4) >= A.n) w[r] = 0u;
+        }
+        uint32_t any = 0u;
+#pragma unroll
+        for (int r = 0; r < R; ++r) any |= w[r];
+        if (wave_any(any != 0u)) {
+            // queue the run's feasible pairs: one pair per lane and trip, lowest query first; a full queue is flushed
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                uint32_t word = w[r];
+                while (true) {
+                    const u64 bal = wave_ballot(word != 0u);
+                    if (bal == 0ull) break;
+                    if (qn + 64 > (uint32_t)QCAP) { wave_sync(); flush(qn); qn = 0; }
+                    if (word) {
+                        const uint32_t b = (uint32_t)__builtin_ctz(word);
+                        word &= word - 1u;
+                        const uint32_t at = qn + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+                        queue[at] = (uint32_t)run0 + (uint32_t)(256 * (r / 4) + 4 * lane + (r % 4));
+                        qb[at] = (uint8_t)b;
+                    }
+                    qn += (uint32_t)__popcll(bal);
+                }
+            }
+        }
+        if (more) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) { cur_a[r] = nxt_a[r]; cur_t[r] = nxt_t[r]; }
+        }
     }
+    wave_sync();
+    if (qn) flush(qn);
 }
 
 // tells the merge where the keys are: per flat region the number of keys, per slot the size of its segment
@@ -2265,7 +2394,11 @@ __global__ void __launch_bounds__(256) prefilter_counts_kernel(linr_prefilter_ar
 {
     const uint32_t b = blockIdx.x;
     const uint32_t total = A.vcnt[b * LINR_VCNT_STRIDE];
-    if (threadIdx.x == 0 && (u64)total > (u64)A.flat_cap + (u64)A.nslots * A.cap) A.vcnt[b * LINR_VCNT_STRIDE + 1] = 1u;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if ((u64)total > (u64)A.flat_cap + (u64)A.nslots * A.cap) A.vcnt[b * LINR_VCNT_STRIDE + 1] = 1u;
+        A.vcnt[b * LINR_VCNT_STRIDE] = 0u;                        // the next phase counts from zero
+    }
     const uint32_t in_flat = total < A.flat_cap ? total : A.flat_cap;
     for (uint32_t r = threadIdx.x; r < LINR_FLAT_REGIONS; r += blockDim.x) {
         const u64 ci = ((u64)b * LINR_FLAT_REGIONS + r) * LINR_COUNTER_STRIDE;
@@ -3022,11 +3155,27 @@ hipError_t linr_launch_bit_filters(linr_filter* filters, uint32_t nq, hipStream_
 hipError_t linr_launch_prefilter(const linr_prefilter_args& a, hipStream_t s)
 {
     if (a.nq == 0 || a.nq > 32 || a.nq > a.B || a.flat_cap % LINR_FLAT_REGIONS != 0 || a.cap == 0 || a.nslots == 0 ||
-        a.row_bytes % 16 != 0)
+        a.row_bytes % 16 != 0 || a.mod == 0 || a.lo >= a.hi || a.hi > a.mod)
         return hipErrorInvalidValue;
-    hipLaunchKernelGGL(prefilter_zero_kernel, dim3(1), dim3(64), 0, s, a.vcnt, a.phase);
-    const uint64_t blocks = (a.n + 256 * LINR_PREFILTER_RUN - 1) / (256 * LINR_PREFILTER_RUN);
-    hipLaunchKernelGGL(prefilter_score_kernel, dim3((uint32_t)(blocks < 8192 ? blocks : 8192)), dim3(256), 0, s, a);
+    // the kernel reads four neighbours' words with one 16-byte load
+    if ((((uintptr_t)a.words) | ((uintptr_t)a.mask) | ((uintptr_t)a.ts)) & 15u) return hipErrorInvalidValue;
+    static int per_cu = 0, cus = 0;
+    if (per_cu == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return hipGetLastError();
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, prefilter_score_kernel<2>, 256, 0) != hipSuccess || v <= 0) v = 4;
+        per_cu = v;
+    }
+    if (a.lo == 0) hipLaunchKernelGGL(prefilter_zero_kernel, dim3(1), dim3(64), 0, s, a.vcnt);
+    // as many workgroups as are resident at once; a wave keeps its queue across its runs
+    const uint64_t runs = (a.n + 64 * LINR_PREFILTER_RUN - 1) / (64 * LINR_PREFILTER_RUN);
+    const uint64_t sel = (runs / a.mod + 1) * (a.hi - a.lo);
+    const uint64_t blocks = (sel + 3) / 4, most = (uint64_t)cus * per_cu;
+    const dim3 grid((uint32_t)(blocks < most ? blocks : most));
+    if (a.words) hipLaunchKernelGGL(prefilter_score_kernel<0>, grid, dim3(256), 0, s, a);
+    else if (!a.ts) hipLaunchKernelGGL(prefilter_score_kernel<1>, grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(prefilter_score_kernel<2>, grid, dim3(256), 0, s, a);
     hipLaunchKernelGGL(prefilter_counts_kernel, dim3(a.nq), dim3(256), 0, s, a);
     return hipGetLastError();
 }

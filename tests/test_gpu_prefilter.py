@@ -27,6 +27,21 @@ def test_int8_exact_by_prefiltering(oracle_mod, scaled, n, B, k, host_filters):
     assert_exact(gpu, run_oracle(oracle_mod, w, k), f"pre-filtering int8 n={n} B={B} k={k}")
 
 
+@pytest.mark.parametrize("phases", [2, 3])
+@pytest.mark.parametrize("n,B,k", [(700_001, 5, 300), (2_000_000, 33, 1000), (513, 2, 10)])
+def test_phase_plans(oracle_mod, phases, n, B, k):
+    """the two- and the three-phase plan (the latter is the default only for very large indexes) on the same inputs"""
+    import paper_2407_13218_amd as L
+    say(f"pre-filtering in {phases} phases n={n} B={B} k={k}")
+    w = rand_int8_workload(40 + B, n, 64, B, scaled=True, with_ts=(B == 5))
+    L.set_tuning(prefilter_phases=phases)
+    try:
+        gpu = run_gpu(to_cuda(w), k=k, prefilter=True)
+    finally:
+        L.set_tuning()
+    assert_exact(gpu, run_oracle(oracle_mod, w, k), f"pre-filtering, {phases} phases, n={n} B={B} k={k}")
+
+
 def test_int8_multi_embedding_by_prefiltering(oracle_mod):
     w = rand_int8_workload(5, 30_000, 64, 9, m=3, scaled=True)
     gpu = run_gpu(to_cuda(w), k=200, prefilter=True)
