@@ -159,8 +159,8 @@ int linr_search_filtered(const linr_index*, const void* Q, const float* q_scale,
  * read.  Same arguments and results as linr_search_filtered (fp32 / bf16 scores within the
  * usual tolerance of it, int8 bit-identical); workspace from
  * linr_search_prefilter_workspace_bytes.  Queries are answered in groups of 32.  Faster
- * when few (item, query) pairs are feasible (1e9 items, 0.1 % feasible, one query: a sixth
- * of the time), slower when many are: the caller chooses, as between the paper's two
+ * when few (item, query) pairs are feasible (1e9 items, 0.1 % feasible, one query: a
+ * thirteenth of the time), slower when many are: the caller chooses, as between the paper's two
  * variants.  A
  * query with more feasible items than the candidate arrays of the workspace hold is not
  * answered: out_counts[b] = LINR_COUNT_OVERFLOW, its other outputs are undefined.
@@ -264,7 +264,7 @@ int linr_search_clauses(const linr_index*, const void* Q, const float* q_scale, 
 /*
  * The same search by explicit pre-filtering (Sec. 3.1.2 "KNN with Explicit Pre-Filtering"):
  * after the pass over the clause columns only the feasible (item, query) pairs are scored
- * (rows gathered with 16-byte loads, one lane per pair) and one selection over their keys
+ * (rows gathered with 16-byte loads, 4 to 16 lanes per pair) and one selection over their keys
  * gives the top k -- the embeddings of infeasible items are never read.  Same arguments,
  * workspace and results as linr_search_clauses (fp32 / bf16 scores within the usual
  * tolerance of each other, int8 bit-identical).  Faster when few items are feasible,
