@@ -98,7 +98,8 @@ int linr_index_create(linr_index** out, uint64_t capacity, uint32_t d, int dtype
  * served model).  Row i of `emb` ([n][d], row-major, 16-byte aligned) becomes
  * item id i.  `mask` is [n]; `ts` is [n] or NULL (no timestamp column).
  * A later load replaces the previous contents (and ends live updates, clause columns
- * and 1-bit codes of the previous contents).  `src` is a LINR_SRC_* value; columns the
+ * and 1-bit codes of the previous contents).  `src` is a LINR_SRC_* value (columns used in
+ * place, LINR_SRC_DEVICE_BORROW, must all be 16-byte aligned); columns the
  * library copies are allocated for the whole capacity, so that live updates can add
  * items in place.  bf16 values are passed as their 16-bit patterns.
  * int8: symmetric codes with one positive fp32 scale per row; row_scale == NULL

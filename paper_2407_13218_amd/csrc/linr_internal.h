@@ -163,6 +163,7 @@ struct linr_prefilter_args {
     // first (lo == 0) takes a small sample, a merge publishes the k-th key found (tau), and the later phases keep only
     // keys that are not below it
     uint32_t mod, lo, hi; const unsigned long long* tau;
+    uint32_t vec16;             // (set by the launcher) the word / mask / timestamp columns are 16-byte aligned
 };
 hipError_t linr_launch_prefilter(const linr_prefilter_args& a, hipStream_t s);   // one phase: zero, score, counts
 // out_counts[b] = 0xFFFFFFFF where vcnt[b] > capacity (run behind the merge)

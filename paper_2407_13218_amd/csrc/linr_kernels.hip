@@ -2292,7 +2292,7 @@ __global__ void __launch_bounds__(256, 4) prefilter_score_kernel(linr_prefilter_
     auto load_run = [&](uint32_t rr, uint32_t (&a)[R], uint32_t (&t)[R]) {
         const u64 run0 = (u64)run_of(rr) * (64 * R);
         const uint32_t* src = from_filters ? A.mask : A.words;
-        if (run0 + 64 * R <= A.n) {
+        if (run0 + 64 * R <= A.n && A.vec16) {
 #pragma unroll
             for (int h = 0; h < R / 4; ++h) {
                 const v4i x = __builtin_nontemporal_load((const v4i*)(src + run0 + 256 * h + 4 * lane));
@@ -2302,7 +2302,7 @@ __global__ void __launch_bounds__(256, 4) prefilter_score_kernel(linr_prefilter_
                     t[4 * h] = (uint32_t)u[0]; t[4 * h + 1] = (uint32_t)u[1]; t[4 * h + 2] = (uint32_t)u[2]; t[4 * h + 3] = (uint32_t)u[3];
                 }
             }
-        } else {                                  // the index's last run: item by item (what lies beyond is dropped below)
+        } else {                  // the index's last run, unaligned columns: item by item (what lies beyond is dropped below)
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const u64 i = run0 + 256 * (r / 4) + 4 * lane + (r % 4);
@@ -3152,13 +3152,14 @@ hipError_t linr_launch_bit_filters(linr_filter* filters, uint32_t nq, hipStream_
     return hipGetLastError();
 }
 
-hipError_t linr_launch_prefilter(const linr_prefilter_args& a, hipStream_t s)
+hipError_t linr_launch_prefilter(const linr_prefilter_args& a_in, hipStream_t s)
 {
+    linr_prefilter_args a = a_in;
     if (a.nq == 0 || a.nq > 32 || a.nq > a.B || a.flat_cap % LINR_FLAT_REGIONS != 0 || a.cap == 0 || a.nslots == 0 ||
         a.row_bytes % 16 != 0 || a.mod == 0 || a.lo >= a.hi || a.hi > a.mod)
         return hipErrorInvalidValue;
-    // the kernel reads four neighbours' words with one 16-byte load
-    if ((((uintptr_t)a.words) | ((uintptr_t)a.mask) | ((uintptr_t)a.ts)) & 15u) return hipErrorInvalidValue;
+    // four neighbours' words with one 16-byte load where the columns allow it (borrowed columns need not be aligned)
+    a.vec16 = ((((uintptr_t)a.words) | ((uintptr_t)a.mask) | ((uintptr_t)a.ts)) & 15u) == 0 ? 1u : 0u;
     static int per_cu = 0, cus = 0;
     if (per_cu == 0) {
         int dev = 0, v = 0;

@@ -42,6 +42,20 @@ def test_phase_plans(oracle_mod, phases, n, B, k):
     assert_exact(gpu, run_oracle(oracle_mod, w, k), f"pre-filtering, {phases} phases, n={n} B={B} k={k}")
 
 
+def test_borrowed_columns_must_be_aligned():
+    """columns used in place (LINR_SRC_DEVICE_BORROW) have to be 16-byte aligned: the loader says so"""
+    import torch
+    import paper_2407_13218_amd as L
+    w = rand_int8_workload(77, 4_000, 64, 2, scaled=True)
+    g = to_cuda(w)
+    big = torch.empty(g["mask"].numel() + 3, dtype=g["mask"].dtype, device="cuda")
+    big[3:] = g["mask"]
+    ix = L.Index(4_000, 64, S.I8, 0)
+    with pytest.raises(L.LinrError):
+        ix.load(g["emb"], big[3:], row_scale=g["scale"])
+    ix.close()
+
+
 def test_int8_multi_embedding_by_prefiltering(oracle_mod):
     w = rand_int8_workload(5, 30_000, 64, 9, m=3, scaled=True)
     gpu = run_gpu(to_cuda(w), k=200, prefilter=True)
