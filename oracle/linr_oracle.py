@@ -1,6 +1,11 @@
 """ctypes loader for oracle/linr_oracle.c (plain C, built with gcc).
 
 TEST INFRASTRUCTURE: the product path never calls into this module.
+
+Besides the loader, two functions are written here in numpy from their definitions: filter_passes (the Sec. 3.1.1
+rule for whole columns) and bits_select (large-K selection by bit matching, Sec. 3.2 / 5.3); both are pinned in
+tests/test_oracle_select_pins.py (hand-worked example, brute force with Python integers, the C ranking routine,
+characterising properties).
 """
 from __future__ import annotations
 
@@ -203,6 +208,49 @@ def two_stage(dtype, emb, mask, Q, filters, perm, signs, k_bits, T, k, ts=None):
         kk = len(order)
         out_ids[b, :kk] = cand[order].astype(np.uint32); out_sc[b, :kk] = rank[order].astype(np.float32); out_cnt[b] = kk
     return out_ids, out_sc, out_cnt
+
+
+def filter_passes(filt_record, mask, ts=None):
+    """Sec. 3.1.1 feasibility rule over the bitmask / timestamp attributes for whole columns at once (numpy): every
+    required bit present, no excluded bit present, at least one bit of every "any of" group, timestamp inside the
+    inclusive window.  Returns a bool array [n]."""
+    f = np.asarray(filt_record, dtype=FILTER_DTYPE).reshape(())
+    mask = np.asarray(mask, np.uint32)
+    ok = (mask & np.uint32(f["all_bits"])) == np.uint32(f["all_bits"])
+    ok &= (mask & np.uint32(f["none_bits"])) == 0
+    for g in range(min(int(f["n_any"]), 4)):
+        ok &= (mask & np.uint32(f["any_bits"][g])) != 0
+    if ts is not None:
+        ts = np.asarray(ts, np.uint32)
+        ok &= (ts >= np.uint32(f["ts_min"])) & (ts <= np.uint32(f["ts_max"]))
+    return ok
+
+
+def bits_select(bits, k_bits, mask, qbits, filters, K, ts=None, id_base=0):
+    """Large-K selection by bit matching (Sec. 3.2, the quantised module used on its own "when K is large"; the
+    notification use case of Sec. 5.3: the top 50 million of a billion members): per query the K feasible items with
+    the most matching bits, ties to the lower id -- i.e. the first K of the ranking by (matches desc, id asc) -- reported
+    as a set, in ascending id order.  Written as that definition: a stable sort by descending match count.
+    Returns (ids: list of B uint32 arrays, thresholds int32 [B] = fewest matching bits among the selected (-1: none),
+    counts uint64 [B] = min(K, #feasible))."""
+    bits = np.ascontiguousarray(bits, np.uint64); qbits = np.ascontiguousarray(qbits, np.uint64)
+    n, W = bits.shape
+    B = qbits.shape[0]
+    filters = np.ascontiguousarray(filters)
+    assert filters.shape == (B,) and K >= 1 and k_bits <= 64 * W
+    out, thr, cnt = [], np.full(B, -1, np.int32), np.zeros(B, np.uint64)
+    for b in range(B):
+        differing = np.zeros(n, np.uint16)
+        for w in range(W):
+            differing += np.bitwise_count(bits[:, w] ^ qbits[b, w]).astype(np.uint16)
+        feasible = np.flatnonzero(filter_passes(filters[b], mask, ts))
+        order = np.argsort(differing[feasible], kind="stable")          # fewest differing bits first, equal ones by id
+        chosen = feasible[order[:K]]
+        cnt[b] = chosen.size
+        if chosen.size:
+            thr[b] = k_bits - int(differing[chosen[-1]])
+        out.append((np.sort(chosen) + id_base).astype(np.uint32))
+    return out, thr, cnt
 
 
 # ---------------------------------------------------------------------------
