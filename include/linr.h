@@ -213,6 +213,25 @@ int linr_search_bits_workspace_bytes(const linr_index*, uint32_t B, uint32_t T, 
 int linr_search_bits(const linr_index*, const uint64_t* qbits, uint32_t B, const linr_filter* filters, uint32_t T,
                      uint32_t* out_ids, int32_t* out_matches, uint32_t* out_counts,
                      void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags);
+/*
+ * Large-K selection by bit matching (Sec. 3.2: the quantised module used without the
+ * full-precision stage "when K is large"; the notification use case of Sec. 5.3, the top
+ * 50 million of a billion members by 64-bit codes).  Per query the K feasible items with
+ * the most matching bits, ties to the lower id -- the first K of the ranking that
+ * linr_search_bits returns -- as a set: out_ids device [B][K], row b holding
+ * out_counts[b] = min(K, #feasible) ids in ascending order (the rest of the row is not
+ * written); out_thresholds[b] = the fewest matching bits among the selected (-1 if none).
+ * out_counts device uint64 [B], out_thresholds device int32 [B].  Any K >= 1 (K beyond
+ * the item count selects every feasible item).  qbits device [B][W], 16-byte aligned;
+ * filters / flags / hip_stream as for linr_search_filtered; B <= 65535.  Exact: a match
+ * count takes k_bits + 1 values only, so two streaming passes over the codes (counts per
+ * 65536-item segment, then the ids) replace a sort.  Works on a codes-only index and on
+ * the codes built for an fp32 / bf16 index, also next to live updates.
+ */
+int linr_select_bits_workspace_bytes(const linr_index*, uint32_t B, uint64_t* bytes);
+int linr_select_bits(const linr_index*, const uint64_t* qbits, uint32_t B, const linr_filter* filters, uint64_t K,
+                     uint32_t* out_ids, uint64_t* out_counts, int32_t* out_thresholds,
+                     void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags);
 int linr_search_two_stage_workspace_bytes(const linr_index*, uint32_t B, uint32_t T, uint32_t k, uint64_t* bytes);
 int linr_search_two_stage(const linr_index*, const void* Q, uint32_t B, const linr_filter* filters, uint32_t T, uint32_t k,
                           uint32_t* out_ids, float* out_scores, uint32_t* out_counts,

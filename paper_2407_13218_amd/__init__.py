@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     search_workspace_bytes, search_filtered, search_filtered_timed, set_tuning, strerror,
     events_create, events_destroy, events_elapsed_ms, MAX_STAGES, STAGE_NAMES,
     index_build_bits, index_load_bits, quantize_queries, search_bits_workspace_bytes, search_bits, search_bits_timed,
+    select_bits_workspace_bytes, select_bits,
     search_two_stage_workspace_bytes, search_two_stage,
     index_enable_updates, index_upsert, index_delete, index_sync_updates,
     index_load_clauses, search_clauses_workspace_bytes, search_clauses, search_clauses_timed,

@@ -31,7 +31,7 @@ EXPORTS = [
     "linr_strerror", "linr_last_hip_error", "linr_set_tuning", "linr_search_filtered_timed",
     "linr_events_create", "linr_events_destroy", "linr_events_elapsed_ms",
     "linr_index_build_bits", "linr_index_load_bits", "linr_quantize_queries", "linr_search_bits_workspace_bytes",
-    "linr_search_bits", "linr_search_two_stage_workspace_bytes", "linr_search_two_stage", "linr_search_bits_timed",
+    "linr_search_bits", "linr_select_bits_workspace_bytes", "linr_select_bits", "linr_search_two_stage_workspace_bytes", "linr_search_two_stage", "linr_search_bits_timed",
     "linr_index_enable_updates", "linr_index_upsert", "linr_index_delete", "linr_index_sync_updates",
     "linr_index_load_clauses", "linr_search_clauses_workspace_bytes", "linr_search_clauses", "linr_search_clauses_timed",
     "linr_search_clauses_prefilter", "linr_index_upsert_clauses",
@@ -111,6 +111,10 @@ def load_library():
     lib.linr_search_bits_workspace_bytes.argtypes = [vp, u32, u32, C.POINTER(u64)]
     lib.linr_search_bits.restype = i32
     lib.linr_search_bits.argtypes = [vp, vp, u32, vp, u32, vp, vp, vp, vp, u64, vp, u32]
+    lib.linr_select_bits_workspace_bytes.restype = i32
+    lib.linr_select_bits_workspace_bytes.argtypes = [vp, u32, C.POINTER(u64)]
+    lib.linr_select_bits.restype = i32
+    lib.linr_select_bits.argtypes = [vp, vp, u32, vp, u64, vp, vp, vp, vp, u64, vp, u32]
     lib.linr_index_load_clauses.restype = i32
     lib.linr_index_load_clauses.argtypes = [vp, vp, vp, u32, u32, u32, u64, i32]
     lib.linr_index_upsert_clauses.restype = i32
@@ -289,6 +293,19 @@ def search_bits_timed(ix, qbits, B, filters, T, out_ids, out_matches, out_counts
                                                  C.addressof(events), C.byref(ns), C.addressof(kinds), C.addressof(items)),
            "linr_search_bits_timed")
     return [kinds[i] for i in range(ns.value)], [items[i] for i in range(ns.value)]
+
+
+def select_bits_workspace_bytes(ix, B) -> int:
+    out = C.c_uint64()
+    _check(load_library().linr_select_bits_workspace_bytes(ix, B, C.byref(out)), "linr_select_bits_workspace_bytes")
+    return out.value
+
+
+def select_bits(ix, qbits, B, filters, K, out_ids, out_counts, out_thresholds, workspace, workspace_bytes, stream=0,
+                flags=FILTERS_ON_DEVICE):
+    _check(load_library().linr_select_bits(ix, _ptr(qbits), B, _ptr(filters), K, _ptr(out_ids), _ptr(out_counts),
+                                           _ptr(out_thresholds), _ptr(workspace), workspace_bytes, stream, flags),
+           "linr_select_bits")
 
 
 def search_two_stage_workspace_bytes(ix, B, T, k) -> int:
@@ -545,6 +562,24 @@ class Index:
         search_bits(self.handle, qbits, B, f, T, ids, matches, counts, ws, nbytes, torch.cuda.current_stream(dev).cuda_stream, flags)
         self._last_workspace = ws
         return ids, matches, counts
+
+    def select_bits(self, qbits, filters, K):
+        """Large-K selection: qbits device int64 [B, W].  Returns device tensors ids [B, K] (int32; row b holds
+        counts[b] ascending ids), counts (int64), thresholds (int32)."""
+        import torch
+        qbits = qbits.contiguous()
+        B, dev = qbits.shape[0], qbits.device
+        ids = torch.empty((B, K), dtype=torch.int32, device=dev)
+        counts = torch.empty((B,), dtype=torch.int64, device=dev)
+        thresholds = torch.empty((B,), dtype=torch.int32, device=dev)
+        if B == 0:
+            return ids, counts, thresholds
+        nbytes = select_bits_workspace_bytes(self.handle, B)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        flags, f = self._filters(filters)
+        select_bits(self.handle, qbits, B, f, K, ids, counts, thresholds, ws, nbytes, torch.cuda.current_stream(dev).cuda_stream, flags)
+        self._last_workspace = ws
+        return ids, counts, thresholds
 
     def search_two_stage(self, Q, filters, T, k):
         import torch

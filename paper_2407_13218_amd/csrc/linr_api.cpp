@@ -749,6 +749,77 @@ extern "C" int linr_search_bits_timed(const linr_index* ix, const uint64_t* qbit
                             flags, events, n_stages, kinds, stage_items);
 }
 
+// large-K selection by bit matching: workspace = counts [B][264] u64 | segment counts [B][n_seg][k_bits + 1] u32 |
+// two offset arrays [B][n_seg] u64 | cuts [B] | a copy of host-side filters
+struct select_layout { uint64_t off_hist, off_seg, off_gt, off_eq, off_cut, off_filters, total; uint32_t n_seg; };
+static void select_plan(const linr_index& v, uint32_t B, select_layout* L)
+{
+    L->n_seg = (uint32_t)((v.n + LINR_SELECT_SEGMENT - 1) / LINR_SELECT_SEGMENT);
+    uint64_t o = 0;
+    L->off_hist = o; o += align_up((uint64_t)B * LINR_SELECT_BINS * 8, 256);
+    L->off_seg = o; o += align_up((uint64_t)B * L->n_seg * (v.k_bits + 1) * 4, 256);
+    L->off_gt = o; o += align_up((uint64_t)B * L->n_seg * 8, 256);
+    L->off_eq = o; o += align_up((uint64_t)B * L->n_seg * 8, 256);
+    L->off_cut = o; o += align_up((uint64_t)B * sizeof(linr_select_cut), 256);
+    L->off_filters = o; o += align_up((uint64_t)B * sizeof(linr_filter), 256);
+    L->total = o;
+}
+
+extern "C" int linr_select_bits_workspace_bytes(const linr_index* ix, uint32_t B, uint64_t* bytes)
+{
+    if (!bytes) return LINR_E_NULL;
+    linr_index v;
+    int rc = bits_view(ix, nullptr, &v);
+    if (rc != LINR_OK) return rc;
+    if (B > 65535u) return LINR_E_SHAPE;
+    if (ix->dead_bit) v.n = ix->capacity;                    // live updates may add items up to the capacity
+    select_layout L;
+    select_plan(v, B ? B : 1, &L);
+    *bytes = L.total;
+    return LINR_OK;
+}
+
+extern "C" int linr_select_bits(const linr_index* ix, const uint64_t* qbits, uint32_t B, const linr_filter* filters, uint64_t K,
+                                uint32_t* out_ids, uint64_t* out_counts, int32_t* out_thresholds, void* workspace,
+                                uint64_t workspace_bytes, void* hip_stream, uint32_t flags)
+{
+    hipStream_t st = (hipStream_t)hip_stream;
+    linr_index v;
+    int rc = bits_view(ix, st, &v);
+    if (rc != LINR_OK) return rc;
+    if (K == 0) return LINR_E_K;
+    if (B > 65535u) return LINR_E_SHAPE;
+    if (B == 0) return LINR_OK;
+    if (!qbits || !filters || !out_ids || !out_counts || !out_thresholds) return LINR_E_NULL;
+    if (((uintptr_t)qbits) & 15u) return LINR_E_SHAPE;
+    if (flags & LINR_FILTERS_ON_HOST)
+        for (uint32_t b = 0; b < B; ++b) {
+            if (filters[b].n_any > LINR_MAX_ANY) return LINR_E_FILTER;
+            if (filters[b].ts_min > filters[b].ts_max) return LINR_E_FILTER;
+        }
+    select_layout L;
+    select_plan(v, B, &L);
+    if (!workspace || (((uintptr_t)workspace) & 255u) || workspace_bytes < L.total) return LINR_E_WORKSPACE;
+    char* ws = (char*)workspace;
+    const linr_filter* use = filters;
+    if (flags & LINR_FILTERS_ON_HOST) {
+        HIP_TRY(hipMemcpyAsync(ws + L.off_filters, filters, (size_t)B * sizeof(linr_filter), hipMemcpyHostToDevice, st));
+        use = (const linr_filter*)(ws + L.off_filters);
+    }
+    HIP_TRY(linr_launch_fill_u32((uint32_t*)(ws + L.off_hist), (uint64_t)B * LINR_SELECT_BINS * 2, 0u, st));
+    linr_select_args a;
+    memset(&a, 0, sizeof(a));
+    a.bits = (const unsigned long long*)v.bits; a.words = v.bits_words; a.k_bits = v.k_bits; a.mask = v.mask; a.ts = v.ts;
+    a.dead_bit = v.dead_bit; a.n = v.n; a.id_base = 0; a.n_seg = L.n_seg; a.B = B;
+    a.q_codes = (const unsigned long long*)qbits; a.filters = use; a.K = K;
+    a.hist = (unsigned long long*)(ws + L.off_hist); a.seg_hist = (uint32_t*)(ws + L.off_seg);
+    a.gt_base = (unsigned long long*)(ws + L.off_gt); a.eq_base = (unsigned long long*)(ws + L.off_eq);
+    a.cut = (linr_select_cut*)(ws + L.off_cut);
+    a.out_ids = out_ids; a.out_counts = (unsigned long long*)out_counts; a.out_thresholds = out_thresholds;
+    HIP_TRY(linr_launch_select(a, st));
+    return LINR_OK;
+}
+
 extern "C" int linr_search_two_stage_workspace_bytes(const linr_index* ix, uint32_t B, uint32_t T, uint32_t k, uint64_t* bytes)
 {
     if (!ix || !bytes) return LINR_E_NULL;
