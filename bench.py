@@ -152,6 +152,48 @@ def quantised_leg(L, S, base, index_cols, N, k, args, dev):
                                  "kernel_ms": res[f"B{B}"]["largest_sweep_ms"],
                                  "items_per_launch": res[f"B{B}"]["largest_sweep_items"],
                                  "pairs_per_s": res[f"B{B}"]["pairs_per_s_largest_sweep"]}
+    # large-K selection (Sec. 5.3, the notification use case: the top 5 % of the members by 64-bit codes, one query,
+    # no attribute filter): two streaming passes over codes + masks, the selected ids written in ascending order
+    K = max(1, N // 20)
+    f_all = torch.from_numpy(np.ascontiguousarray(S.make_filters(1)).view(np.uint8).copy()).to(dev)
+    q1 = torch.from_numpy(keep[0].view(np.int64)).to(dev)
+    nbytes = L.select_bits_workspace_bytes(qix.handle, 1)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    sel_ids = torch.empty((1, K), dtype=torch.int32, device=dev)
+    sel_cnt = torch.empty((1,), dtype=torch.int64, device=dev)
+    sel_thr = torch.empty((1,), dtype=torch.int32, device=dev)
+    for _ in range(args.warmup):
+        L.select_bits(qix.handle, q1, 1, f_all, K, sel_ids, sel_cnt, sel_thr, ws, nbytes, stream, L.FILTERS_ON_DEVICE)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        L.select_bits(qix.handle, q1, 1, f_all, K, sel_ids, sel_cnt, sel_thr, ws, nbytes, stream, L.FILTERS_ON_DEVICE)
+    e1.record()
+    torch.cuda.synchronize()
+    sel_ms = e0.elapsed_time(e1) / args.steps
+    sel_bytes = N * (bpi + 2) + 4 * K if kb <= 254 else 2 * N * bpi + 4 * K     # a byte per item kept between the passes
+    out["selection"] = dict(workload=f"top {K} of {N} items by matching bits ({kb}-bit codes), one query, pass-all filter",
+                            K=K, ms_per_step=sel_ms, items_per_s=N / sel_ms * 1e3, selected=int(sel_cnt.item()),
+                            threshold_bits=int(sel_thr.item()),
+                            roofline={"bound": "hbm", "achieved": sel_bytes / sel_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                      "frac": sel_bytes / sel_ms / 1e6 / HBM_PEAK_GBS, "traffic": None,
+                                      "kernel": "select_hist_kernel + select_write_kernel (the two passes of one call, with "
+                                                "the cut and scan kernels between them)",
+                                      "kernel_ms": sel_ms, "items_per_launch": N, "algorithmic_bytes_per_launch": sel_bytes})
+    log(f"  selection of the top {K:,}: {sel_ms:.3f} ms/step = {sel_bytes / sel_ms / 1e6:.0f} GB/s over both passes "
+        f"({100 * sel_bytes / sel_ms / 1e6 / HBM_PEAK_GBS:.1f} % of HBM peak); threshold {int(sel_thr.item())} matching bits")
+    del ws, sel_ids
+    if not args.no_cpu:
+        import oracle
+        ns = min(N, 20_000_000)
+        t0 = time.perf_counter()
+        oracle.bits_select(codes[:ns].cpu().numpy().view(np.uint64), kb, index_cols[2][:ns].cpu().numpy().view(np.uint32),
+                           keep[0], S.make_filters(1), max(1, ns // 20))
+        dt = time.perf_counter() - t0
+        out["selection"]["cpu_baseline"] = dict(value=ns / dt, unit="items/s", cores=1, kind="oracle",
+                                                sample=f"first {ns} codes, top {max(1, ns // 20)}, {dt:.1f} s")
+        log(f"  selection oracle: {ns / dt:.3e} items/s on 1 thread")
     if not args.no_cpu:
         import oracle
         ns = min(N, 500_000_000)

@@ -750,8 +750,8 @@ extern "C" int linr_search_bits_timed(const linr_index* ix, const uint64_t* qbit
 }
 
 // large-K selection by bit matching: workspace = counts [B][264] u64 | segment counts [B][n_seg][k_bits + 1] u32 |
-// two offset arrays [B][n_seg] u64 | cuts [B] | a copy of host-side filters
-struct select_layout { uint64_t off_hist, off_seg, off_gt, off_eq, off_cut, off_filters, total; uint32_t n_seg; };
+// two offset arrays [B][n_seg] u64 | cuts [B] | a copy of host-side filters | differing bits [B][n_seg * 65536] u8
+struct select_layout { uint64_t off_hist, off_seg, off_gt, off_eq, off_cut, off_filters, off_dcache, total; uint32_t n_seg; };
 static void select_plan(const linr_index& v, uint32_t B, select_layout* L)
 {
     L->n_seg = (uint32_t)((v.n + LINR_SELECT_SEGMENT - 1) / LINR_SELECT_SEGMENT);
@@ -762,6 +762,8 @@ static void select_plan(const linr_index& v, uint32_t B, select_layout* L)
     L->off_eq = o; o += align_up((uint64_t)B * L->n_seg * 8, 256);
     L->off_cut = o; o += align_up((uint64_t)B * sizeof(linr_select_cut), 256);
     L->off_filters = o; o += align_up((uint64_t)B * sizeof(linr_filter), 256);
+    // one byte per item and query: the differing bits, kept between the passes (codes of up to 254 bits)
+    L->off_dcache = o; if (v.k_bits <= 254) o += align_up((uint64_t)B * L->n_seg * LINR_SELECT_SEGMENT, 256);
     L->total = o;
 }
 
@@ -815,6 +817,7 @@ extern "C" int linr_select_bits(const linr_index* ix, const uint64_t* qbits, uin
     a.hist = (unsigned long long*)(ws + L.off_hist); a.seg_hist = (uint32_t*)(ws + L.off_seg);
     a.gt_base = (unsigned long long*)(ws + L.off_gt); a.eq_base = (unsigned long long*)(ws + L.off_eq);
     a.cut = (linr_select_cut*)(ws + L.off_cut);
+    a.dcache = v.k_bits <= 254 ? (uint8_t*)(ws + L.off_dcache) : nullptr;
     a.out_ids = out_ids; a.out_counts = (unsigned long long*)out_counts; a.out_thresholds = out_thresholds;
     HIP_TRY(linr_launch_select(a, st));
     return LINR_OK;

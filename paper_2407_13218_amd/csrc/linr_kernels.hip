@@ -2431,10 +2431,26 @@ __global__ void __launch_bounds__(64) prefilter_overflow_kernel(const uint32_t* 
 // ---------------------------------------------------------------------------
 #define LINR_SELECT_TILE 1024          // items per workgroup step: 256 lanes x 4 neighbours
 
+// one query's filter in the compact form the scans use: (mask & care) == must, an unsigned window test for the
+// timestamp, and a flag for "any of" groups (checked with the full rule, only where the rest passed)
+struct SelectFilter {
+    uint32_t care, must, t0, span; bool any;
+    __device__ __forceinline__ void set(const linr_filter& F, uint32_t dead_bit)
+    {
+        const uint32_t none = F.none_bits | dead_bit;
+        const bool impossible = (F.all_bits & none) != 0u || F.ts_min > F.ts_max;
+        must = impossible ? 0xFFFFFFFFu : F.all_bits;
+        care = impossible ? 0u : (F.all_bits | none);
+        t0 = F.ts_min; span = F.ts_max - F.ts_min;
+        any = F.n_any != 0u && !impossible;
+    }
+};
+
 template <int W, bool TS>
 struct SelectTile {
     uint32_t diff[4];                  // differing bits of the lane's four items; 0xFFFFFFFF = infeasible / beyond the end
-    __device__ __forceinline__ void load(const linr_select_args& A, const linr_filter& F, const u64* q, u64 i0)
+    __device__ __forceinline__ void load(const linr_select_args& A, const linr_filter& F, const SelectFilter& C, const u64* q,
+                                         u64 i0)
     {
         uint32_t mk[4], tv[4];
         u64 x[4][W];
@@ -2469,37 +2485,63 @@ struct SelectTile {
             uint32_t d = 0;
 #pragma unroll
             for (int w = 0; w < W; ++w) d += (uint32_t)__popcll(x[r][w] ^ q[w]);
-            const bool ok = i0 + r < A.n && (mk[r] & A.dead_bit) == 0u && filter_pass(F, mk[r], TS, TS ? tv[r] : 0u);
+            bool ok = (i0 + r < A.n) & ((mk[r] & C.care) == C.must);
+            if (TS) ok = ok & (tv[r] - C.t0 <= C.span);
             diff[r] = ok ? d : 0xFFFFFFFFu;
+        }
+        if (C.any) {                                          // (uniform)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (diff[r] != 0xFFFFFFFFu && !filter_pass(F, mk[r], TS, TS ? tv[r] : 0u)) diff[r] = 0xFFFFFFFFu;
         }
     }
 };
 
-// pass 1: grid (segments, queries).  seg_hist[b][segment][bins], hist[b][bins] (zeroed by the caller)
+// pass 1: grid (segments, queries).  seg_hist[b][segment][bins], hist[b][bins] (zeroed by the caller); with `dcache` the
+// count of differing bits of every item is kept, one byte each (0xFF = infeasible), so that pass 2 reads 1 byte per item
 template <int W, bool TS>
 __global__ void __launch_bounds__(256) select_hist_kernel(linr_select_args A)
 {
-    __shared__ uint32_t h[4][260];
+    // counts per (number of differing bits, lane): lane l of every wave adds into column l, so the lanes of one
+    // instruction never meet in a word (match counts cluster: a shared row would serialise them); two 16-bit counts
+    // per word -- a column sees at most 4 x 256 items of the segment
+    constexpr int HW = 32 * W + 1;
+    __shared__ uint32_t h[HW][64];
     const uint32_t b = blockIdx.y, seg = blockIdx.x, bins = A.k_bits + 1;
-    const int wib = threadIdx.x >> 6;
-    for (uint32_t j = threadIdx.x; j < 4 * 260; j += 256) (&h[0][0])[j] = 0u;
+    const int lane = threadIdx.x & 63;
+    for (uint32_t j = threadIdx.x; j < HW * 64; j += 256) (&h[0][0])[j] = 0u;
     __syncthreads();
     const linr_filter F = A.filters[b];
+    SelectFilter C;
+    C.set(F, A.dead_bit);
     u64 q[W];
 #pragma unroll
     for (int w = 0; w < W; ++w) q[w] = A.q_codes[(u64)b * W + w];
     const u64 lo = (u64)seg * LINR_SELECT_SEGMENT;
     const u64 hi = lo + LINR_SELECT_SEGMENT < A.n ? lo + LINR_SELECT_SEGMENT : A.n;
-    for (u64 t0 = lo; t0 < hi; t0 += LINR_SELECT_TILE) {
-        SelectTile<W, TS> T;
-        T.load(A, F, q, t0 + 4 * threadIdx.x);
+    uint8_t* dc = A.dcache ? A.dcache + (u64)b * A.n_seg * LINR_SELECT_SEGMENT : nullptr;
+    for (u64 t0 = lo; t0 < hi; t0 += 2 * LINR_SELECT_TILE) {            // two tiles' loads in flight
+        SelectTile<W, TS> T[2];
+        const bool two = t0 + LINR_SELECT_TILE < hi;
+        T[0].load(A, F, C, q, t0 + 4 * threadIdx.x);
+        if (two) T[1].load(A, F, C, q, t0 + LINR_SELECT_TILE + 4 * threadIdx.x);
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-            if (T.diff[r] != 0xFFFFFFFFu) atomicAdd(&h[wib][T.diff[r]], 1u);
+        for (int u = 0; u < 2; ++u) {
+            if (u == 1 && !two) break;
+            uint32_t packed = 0;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if (T[u].diff[r] != 0xFFFFFFFFu) atomicAdd(&h[T[u].diff[r] >> 1][lane], 1u << (16 * (T[u].diff[r] & 1u)));
+                packed |= (T[u].diff[r] & 0xFFu) << (8 * r);
+            }
+            // (the segments are padded to whole tiles)
+            if (dc) __builtin_nontemporal_store(packed, (uint32_t*)(dc + t0 + u * LINR_SELECT_TILE + 4 * threadIdx.x));
+        }
     }
     __syncthreads();
     for (uint32_t j = threadIdx.x; j < bins; j += 256) {
-        const uint32_t c = h[0][j] + h[1][j] + h[2][j] + h[3][j];
+        uint32_t c = 0;
+        for (int l = 0; l < 64; ++l) c += (h[j >> 1][(l + threadIdx.x) & 63] >> (16 * (j & 1u))) & 0xFFFFu;
         A.seg_hist[((u64)b * A.n_seg + seg) * bins + j] = c;
         if (c) atomicAdd(&A.hist[(u64)b * LINR_SELECT_BINS + j], (unsigned long long)c);
     }
@@ -2581,6 +2623,8 @@ __global__ void __launch_bounds__(256) select_write_kernel(linr_select_args A)
     if (cut.t_diff == 0xFFFFFFFFu) return;
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
     const linr_filter F = A.filters[b];
+    SelectFilter C;
+    C.set(F, A.dead_bit);
     u64 q[W];
 #pragma unroll
     for (int w = 0; w < W; ++w) q[w] = A.q_codes[(u64)b * W + w];
@@ -2592,7 +2636,7 @@ __global__ void __launch_bounds__(256) select_write_kernel(linr_select_args A)
     for (u64 t0 = lo; t0 < hi; t0 += LINR_SELECT_TILE) {
         SelectTile<W, TS> T;
         const u64 i0 = t0 + 4 * threadIdx.x;
-        T.load(A, F, q, i0);
+        T.load(A, F, C, q, i0);
         uint32_t cg = 0, ce = 0;
 #pragma unroll
         for (int r = 0; r < 4; ++r) { cg += T.diff[r] < cut.t_diff ? 1u : 0u; ce += T.diff[r] == cut.t_diff ? 1u : 0u; }
@@ -3388,6 +3432,58 @@ hipError_t linr_launch_prefilter_overflow(const uint32_t* vcnt, uint64_t capacit
     return hipGetLastError();
 }
 
+// pass 2 over the kept byte per item: 16 items per lane and step
+__global__ void __launch_bounds__(256) select_write_cached_kernel(linr_select_args A)
+{
+    __shared__ uint32_t wave_tot[4];
+    const uint32_t b = blockIdx.y, seg = blockIdx.x;
+    const linr_select_cut cut = A.cut[b];
+    if (cut.t_diff == 0xFFFFFFFFu) return;
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    u64 run_gt = A.gt_base[(u64)b * A.n_seg + seg], run_eq = A.eq_base[(u64)b * A.n_seg + seg];
+    const u64 need = cut.need_eq;
+    uint32_t* out = A.out_ids + (u64)b * A.K;
+    const uint8_t* dc = A.dcache + (u64)b * A.n_seg * LINR_SELECT_SEGMENT;
+    const u64 lo = (u64)seg * LINR_SELECT_SEGMENT;
+    const u64 hi = lo + LINR_SELECT_SEGMENT < A.n ? lo + LINR_SELECT_SEGMENT : A.n;
+    for (u64 t0 = lo; t0 < hi; t0 += 16 * 256) {
+        const u64 i0 = t0 + 16 * threadIdx.x;
+        v4i raw = {-1, -1, -1, -1};
+        if (i0 < hi) raw = __builtin_nontemporal_load((const v4i*)(dc + i0));
+        uint32_t better = 0, tie = 0;                 // one bit per item of the lane
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const uint32_t d = ((uint32_t)raw[r >> 2] >> (8 * (r & 3))) & 0xFFu;
+            const bool in = i0 + r < hi && d != 0xFFu;
+            better |= (in && d < cut.t_diff ? 1u : 0u) << r;
+            tie |= (in && d == cut.t_diff ? 1u : 0u) << r;
+        }
+        const uint32_t mine = ((uint32_t)__popc(tie) << 16) | (uint32_t)__popc(better);
+        uint32_t inc = mine;
+#pragma unroll
+        for (int st = 1; st < 64; st <<= 1) {
+            const uint32_t o = __shfl_up(inc, st);
+            if (lane >= st) inc += o;
+        }
+        if (lane == 63) wave_tot[wib] = inc;
+        __syncthreads();
+        uint32_t before = inc - mine, total = 0;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) { if (v < wib) before += wave_tot[v]; total += wave_tot[v]; }
+        __syncthreads();
+        u64 g_before = run_gt + (before & 0xFFFFu), e_before = run_eq + (before >> 16);
+        uint32_t todo = better | tie;
+        while (todo) {
+            const int r = __builtin_ctz(todo);
+            todo &= todo - 1u;
+            const uint32_t below = (1u << r) - 1u;
+            const u64 g = g_before + (uint32_t)__popc(better & below), e = e_before + (uint32_t)__popc(tie & below);
+            if (((better >> r) & 1u) || e < need) out[g + (e < need ? e : need)] = (uint32_t)(i0 + r) + A.id_base;
+        }
+        run_gt += total & 0xFFFFu; run_eq += total >> 16;
+    }
+}
+
 template <int W>
 static void select_launch(const linr_select_args& a, int pass, hipStream_t s)
 {
@@ -3395,6 +3491,8 @@ static void select_launch(const linr_select_args& a, int pass, hipStream_t s)
     if (pass == 0) {
         if (a.ts) hipLaunchKernelGGL((select_hist_kernel<W, true>), grid, block, 0, s, a);
         else hipLaunchKernelGGL((select_hist_kernel<W, false>), grid, block, 0, s, a);
+    } else if (a.dcache) {
+        hipLaunchKernelGGL(select_write_cached_kernel, grid, block, 0, s, a);
     } else {
         if (a.ts) hipLaunchKernelGGL((select_write_kernel<W, true>), grid, block, 0, s, a);
         else hipLaunchKernelGGL((select_write_kernel<W, false>), grid, block, 0, s, a);
@@ -3406,7 +3504,8 @@ hipError_t linr_launch_select(const linr_select_args& a, hipStream_t s)
 {
     if (a.B == 0 || a.B > 65535u || a.n == 0 || a.K == 0 || a.k_bits == 0 || a.k_bits + 1 > LINR_SELECT_BINS ||
         a.n_seg != (uint32_t)((a.n + LINR_SELECT_SEGMENT - 1) / LINR_SELECT_SEGMENT) ||
-        (a.words != 1 && a.words != 2 && a.words != 4) || a.k_bits > 64 * a.words)
+        (a.words != 1 && a.words != 2 && a.words != 4) || a.k_bits > 64 * a.words || (a.dcache && a.k_bits > 254) ||
+        (((uintptr_t)a.dcache) & 15u))
         return hipErrorInvalidValue;
     if ((((uintptr_t)a.bits) | ((uintptr_t)a.mask) | ((uintptr_t)a.ts)) & 15u) return hipErrorInvalidValue;
     for (int pass = 0; pass < 2; ++pass) {

@@ -333,3 +333,45 @@ def test_live_updates_full_size(oracle_mod):
     assert_float_rule(oracle_mod, w2, gpu, k, label="live updates at full size")
     say("8 queries within tolerance of the oracle's scan over the updated index")
     ix.close()
+
+
+def test_large_k_selection_full_size(oracle_mod):
+    """The selection leg bench.py times (Sec. 5.3, notification use case): the top 50 million of 1e9 items by 64-bit codes,
+    one query, no attribute filter -- every selected id, the count and the threshold against the oracle's stable sort of
+    all 1e9 match counts; then the same with the 5 % filter of the headline workload and K = 10 million."""
+    import torch
+    import paper_2407_13218_amd as L
+
+    free, _ = torch.cuda.mem_get_info()
+    if free < N_FULL * 30:
+        pytest.skip("not enough free HBM for the full-size code index")
+    kb = 64
+    g = torch.Generator(device="cuda"); g.manual_seed(4242)
+    codes = torch.empty((N_FULL, 1), dtype=torch.int64, device="cuda")
+    mask = torch.empty((N_FULL,), dtype=torch.int32, device="cuda")
+    for p0 in range(0, N_FULL, PIECE):                       # uniformly random codes and masks, piece by piece
+        p1 = min(N_FULL, p0 + PIECE)
+        codes[p0:p1] = torch.randint(-2 ** 63, 2 ** 63 - 1, (p1 - p0, 1), generator=g, device="cuda", dtype=torch.int64)
+        mask[p0:p1] = torch.randint(-2 ** 31, 2 ** 31 - 1, (p1 - p0,), generator=g, device="cuda", dtype=torch.int32)
+    ix = L.Index(N_FULL, kb, S.BITS, 0)
+    ix.load(codes, mask)
+    q = S.random_codes(1, kb, seed=31)
+    qd = torch.from_numpy(q.view(np.int64)).cuda()
+    f_all = S.make_filters(1)
+    f_5 = S.make_filters(1); f_5["all_bits"][0] = 0b1011; f_5["none_bits"][0] = 0b0100        # 1/16 of the items
+    codes_h = codes.cpu().numpy().view(np.uint64)
+    mask_h = mask.cpu().numpy().view(np.uint32)
+    say("codes and masks on the host")
+    for f, K in ((f_all, N_FULL // 20), (f_5, 10_000_000)):
+        ids, cnt, thr = ix.select_bits(qd, f, K)
+        torch.cuda.synchronize()
+        c = int(cnt.item())
+        got = ids[0, :c].cpu().numpy().view(np.uint32)
+        say(f"GPU selection of {K:,} done ({c:,} ids, threshold {int(thr.item())}); oracle sorting")
+        want_ids, want_thr, want_cnt = oracle_mod.bits_select(codes_h, kb, mask_h, q, f, K)
+        assert c == int(want_cnt[0]) == K
+        assert int(thr.item()) == int(want_thr[0])
+        assert np.array_equal(got, want_ids[0]), f"K={K}: selected ids differ from the oracle's"
+        say(f"top {K:,} of {N_FULL:,}: identical to the oracle's")
+        del ids, got, want_ids
+    ix.close()
