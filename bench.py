@@ -36,6 +36,8 @@ BYTES_PER_ITEM = 64 + 4 + 4    # codes + mask + row scale: the algorithmic HBM b
 MEASURED_TRAFFIC_BYTES = {(1_000_000_000, 32, "5%", 1000): 63_022_224_384}
 # the same for the largest sweep of the 1-bit search at B = 1, keyed by (N, code bits, pass rate, k):
 # 5,127,353 KiB fetched x 2.000 + 450 KiB written (profiles/scan_kernel_bits_1e9_B1.md)
+# FETCH_SIZE + WRITE_SIZE of the selection's kernels, (N, code bits, K) -> bytes per call (profiles/select_kernels_1e9_top50M.md)
+MEASURED_SELECT_TRAFFIC_BYTES = {(1_000_000_000, 64, 50_000_000): 14_783_381_504}
 MEASURED_BITS_TRAFFIC_BYTES = {(1_000_000_000, 64, "5%", 1000): 10_501_279_181}
 
 
@@ -176,8 +178,11 @@ def quantised_leg(L, S, base, index_cols, N, k, args, dev):
     out["selection"] = dict(workload=f"top {K} of {N} items by matching bits ({kb}-bit codes), one query, pass-all filter",
                             K=K, ms_per_step=sel_ms, items_per_s=N / sel_ms * 1e3, selected=int(sel_cnt.item()),
                             threshold_bits=int(sel_thr.item()),
+                            paper_context="Sec. 5.3: top 50 M of 1 B members, 64-bit codes, one query: 97.6 ms p95 on one A100 "
+                                          "(another machine: context, not a target)",
                             roofline={"bound": "hbm", "achieved": sel_bytes / sel_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                      "frac": sel_bytes / sel_ms / 1e6 / HBM_PEAK_GBS, "traffic": None,
+                                      "frac": sel_bytes / sel_ms / 1e6 / HBM_PEAK_GBS,
+                                      "traffic": MEASURED_SELECT_TRAFFIC_BYTES.get((N, kb, K)),
                                       "kernel": "select_hist_kernel + select_write_kernel (the two passes of one call, with "
                                                 "the cut and scan kernels between them)",
                                       "kernel_ms": sel_ms, "items_per_launch": N, "algorithmic_bytes_per_launch": sel_bytes})
