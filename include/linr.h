@@ -202,6 +202,10 @@ int linr_index_destroy(linr_index*);
  *     the top k <= T by (score descending, id ascending): out_ids / out_scores device
  *     [B][k], out_counts device [B] = min(k, T, #feasible).  m = 1.  An approximation of
  *     linr_search_filtered whose recall grows with T; it equals it when T >= #feasible.
+ *     T may exceed LINR_MAX_K (the paper's experiment keeps 1 % of the items): the
+ *     candidates then come from linr_select_bits and are scored by the gather pass of the
+ *     explicit pre-filtering; k <= LINR_MAX_K; a query whose sampled candidates overflow
+ *     the workspace's candidate arrays gets out_counts[b] = LINR_COUNT_OVERFLOW.
  * Workspaces: device, 256-byte aligned, sizes from the *_workspace_bytes calls; filters,
  * hip_stream and flags as for linr_search_filtered.  Errors as there, plus LINR_E_DTYPE
  * (index kind does not fit the call) and LINR_E_NOT_LOADED (no codes built yet).

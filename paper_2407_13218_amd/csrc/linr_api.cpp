@@ -823,11 +823,83 @@ extern "C" int linr_select_bits(const linr_index* ix, const uint64_t* qbits, uin
     return LINR_OK;
 }
 
+static int prefilter_group(const linr_index& v, const uint32_t* words, const linr_filter* filters, const uint32_t* item_mask,
+                           const uint32_t* item_ts, uint32_t dead_bit, const void* Qg, const float* q_scale_g, uint32_t Bg,
+                           uint32_t m, uint32_t k, uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
+                           void* workspace, uint64_t inner, uint32_t* vcnt, hipStream_t st, const uint32_t* cand,
+                           const unsigned long long* cand_counts, uint64_t cand_T);
+
+// Two-stage search with more candidates than a ranking holds (T > LINR_MAX_K; the paper's "keep 1 % of the items"):
+// the candidates come from the large-K selection, their exact scores from the gather-scoring pass of the explicit
+// pre-filtering (candidate lists in place of a predicate), the top k from its merges.
+// workspace: selection | query codes | candidates [B][T] | their counts [B] u64 | thresholds [B] | search workspace
+// of one group of <= 32 queries | 4 KB of counters
+struct two_stage_large_layout { uint64_t sel, off_q, off_cand, off_cnt, off_thr, off_inner, inner, off_vcnt, total; };
+static int two_stage_large_plan(const linr_index* ix, uint32_t B, uint64_t T, uint32_t k, two_stage_large_layout* L)
+{
+    if (k > LINR_MAX_K) return LINR_E_K;
+    int rc = linr_select_bits_workspace_bytes(ix, B, &L->sel);
+    if (rc != LINR_OK) return rc;
+    rc = linr_search_workspace_bytes(ix, B < 32 ? B : 32, 1, k, &L->inner);
+    if (rc != LINR_OK) return rc;
+    uint64_t o = align_up(L->sel, 256);
+    L->off_q = o; o += align_up((uint64_t)B * ix->bits_words * 8, 256);
+    L->off_cand = o; o += align_up((uint64_t)B * T * 4, 256);
+    L->off_cnt = o; o += align_up((uint64_t)B * 8, 256);
+    L->off_thr = o; o += align_up((uint64_t)B * 4, 256);
+    L->off_inner = o; o += align_up(L->inner, 256);
+    L->off_vcnt = o; o += 4096;
+    L->total = o;
+    return LINR_OK;
+}
+
+static int two_stage_large(const linr_index* ix, const void* Q, uint32_t B, const linr_filter* filters, uint64_t T, uint32_t k,
+                           uint32_t* out_ids, float* out_scores, uint32_t* out_counts, void* workspace, uint64_t workspace_bytes,
+                           void* hip_stream, uint32_t flags)
+{
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (T > ix->capacity) T = ix->capacity;
+    two_stage_large_layout L;
+    int rc = two_stage_large_plan(ix, B, T, k, &L);
+    if (rc != LINR_OK) return rc;
+    if (!workspace || (((uintptr_t)workspace) & 255u) || workspace_bytes < L.total) return LINR_E_WORKSPACE;
+    if (((uintptr_t)Q) & 15u) return LINR_E_SHAPE;
+    char* ws = (char*)workspace;
+    uint64_t* qbits = (uint64_t*)(ws + L.off_q);
+    uint32_t* cand = (uint32_t*)(ws + L.off_cand);
+    unsigned long long* ccnt = (unsigned long long*)(ws + L.off_cnt);
+    rc = linr_quantize_queries(ix, Q, B, qbits, hip_stream);
+    if (rc != LINR_OK) return rc;
+    rc = linr_select_bits(ix, qbits, B, filters, T, cand, (uint64_t*)ccnt, (int32_t*)(ws + L.off_thr), ws, L.sel, hip_stream, flags);
+    if (rc != LINR_OK) return rc;
+    linr_index v;
+    {
+        linr_index snap;
+        v = *view_for(ix, st, true, &snap);
+    }
+    v.upd = nullptr;
+    for (uint32_t b0 = 0; b0 < B; b0 += 32) {
+        const uint32_t Bg = (B - b0) < 32 ? (B - b0) : 32;
+        rc = prefilter_group(v, nullptr, nullptr, nullptr, nullptr, 0, (const char*)Q + (uint64_t)b0 * v.row_bytes, nullptr, Bg, 1, k,
+                             out_ids + (uint64_t)b0 * k, out_scores + (uint64_t)b0 * k, nullptr, out_counts + b0, ws + L.off_inner,
+                             L.inner, (uint32_t*)(ws + L.off_vcnt), st, cand + (uint64_t)b0 * T, ccnt + b0, T);
+        if (rc != LINR_OK) return rc;
+    }
+    return LINR_OK;
+}
+
 extern "C" int linr_search_two_stage_workspace_bytes(const linr_index* ix, uint32_t B, uint32_t T, uint32_t k, uint64_t* bytes)
 {
     if (!ix || !bytes) return LINR_E_NULL;
     if (ix->dtype != LINR_F32 && ix->dtype != LINR_BF16) return LINR_E_DTYPE;
     if (k == 0 || k > T) return LINR_E_K;
+    if (T > LINR_MAX_K) {
+        two_stage_large_layout L;
+        int rc2 = two_stage_large_plan(ix, B ? B : 1, T > ix->capacity ? ix->capacity : T, k, &L);
+        if (rc2 != LINR_OK) return rc2;
+        *bytes = L.total;
+        return LINR_OK;
+    }
     uint64_t s1 = 0;
     int rc = linr_search_bits_workspace_bytes(ix, B, T, &s1);
     if (rc != LINR_OK) return rc;
@@ -842,10 +914,13 @@ extern "C" int linr_search_two_stage(const linr_index* ix, const void* Q, uint32
 {
     if (!ix) return LINR_E_NULL;
     if (ix->dtype != LINR_F32 && ix->dtype != LINR_BF16) return LINR_E_DTYPE;
-    if (k == 0 || k > T || T > LINR_MAX_K) return LINR_E_K;
+    if (k == 0 || k > T) return LINR_E_K;
     if (ix->n == 0 || !ix->emb || !ix->bits) return LINR_E_NOT_LOADED;
     if (B == 0) return LINR_OK;
     if (!Q || !filters || !out_ids || !out_scores || !out_counts) return LINR_E_NULL;
+    if (T > LINR_MAX_K)
+        return two_stage_large(ix, Q, B, filters, T, k, out_ids, out_scores, out_counts, workspace, workspace_bytes, hip_stream,
+                               flags);
     uint64_t s1 = 0, total = 0;
     int rc = linr_search_bits_workspace_bytes(ix, B, T, &s1);
     if (rc != LINR_OK) return rc;
@@ -1103,7 +1178,8 @@ extern "C" int linr_search_clauses_workspace_bytes(const linr_index* ix, uint32_
 static int prefilter_group(const linr_index& v, const uint32_t* words, const linr_filter* filters, const uint32_t* item_mask,
                            const uint32_t* item_ts, uint32_t dead_bit, const void* Qg, const float* q_scale_g, uint32_t Bg,
                            uint32_t m, uint32_t k, uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
-                           void* workspace, uint64_t inner, uint32_t* vcnt, hipStream_t st)
+                           void* workspace, uint64_t inner, uint32_t* vcnt, hipStream_t st, const uint32_t* cand,
+                           const unsigned long long* cand_counts, uint64_t cand_T)
 {
     if (m == 0 || m > LINR_MAX_M) return LINR_E_SHAPE;
     if (((uintptr_t)Qg) & 15u) return LINR_E_SHAPE;
@@ -1126,6 +1202,7 @@ static int prefilter_group(const linr_index& v, const uint32_t* words, const lin
     pa.flat = (unsigned long long*)(ws + pp.off_flat); pa.flat_cap = pp.flat_cap;
     pa.seg = (unsigned long long*)(ws + pp.off_seg); pa.nslots = pp.nslots; pa.cap = pp.cap; pa.B = Bg;
     pa.vcnt = vcnt; pa.gcnt = gcnt; pa.fvalid = fvalid; pa.cnt = cnt;
+    pa.cand = cand; pa.cand_counts = cand_counts; pa.cand_T = cand_T;
     linr_merge_args ma;
     memset(&ma, 0, sizeof(ma));
     ma.tau = tau; ma.cnt = cnt; ma.seg = pa.seg; ma.nslots = pp.nslots; ma.cap = pp.cap; ma.B = Bg; ma.k = k;
@@ -1136,7 +1213,7 @@ static int prefilter_group(const linr_index& v, const uint32_t* words, const lin
     ma.out_ids = out_ids; ma.out_scores = out_scores; ma.out_raw = out_raw; ma.out_counts = out_counts;
     // 1/256 of the runs, then 15/256, then the rest (small indexes: 1/16, then the rest)
     static const uint32_t cuts3[4] = {0, 1, 16, 256}, cuts2[3] = {0, 1, 16};
-    const bool three = g_tuning.prefilter_phases ? g_tuning.prefilter_phases >= 3 : v.n >= LINR_PREFILTER_THREE_PHASES;
+    const bool three = !cand && (g_tuning.prefilter_phases ? g_tuning.prefilter_phases >= 3 : v.n >= LINR_PREFILTER_THREE_PHASES);
     const uint32_t* cuts = three ? cuts3 : cuts2;
     const int n_phases = three ? 3 : 2;
     for (int ph = 0; ph < n_phases; ++ph) {
@@ -1206,7 +1283,7 @@ static int search_clauses_impl(const linr_index* ix, const void* Q, const float*
             rc = prefilter_group(v, words, nullptr, nullptr, nullptr, 0, (const char*)Q + (uint64_t)b0 * m * v.row_bytes,
                                  q_scale ? q_scale + b0 : nullptr, Bg, m, k, out_ids + (uint64_t)b0 * k,
                                  out_scores + (uint64_t)b0 * k, out_raw ? out_raw + (uint64_t)b0 * k : nullptr, out_counts + b0,
-                                 workspace, inner, (uint32_t*)(filt + 32), st);
+                                 workspace, inner, (uint32_t*)(filt + 32), st, nullptr, nullptr, 0);
             if (rc != LINR_OK) return rc;
             continue;
         }
@@ -1362,7 +1439,7 @@ extern "C" int linr_search_filtered_prefilter(const linr_index* ix, const void* 
         }
         rc = prefilter_group(v, nullptr, use, v.mask, v.ts, v.dead_bit, (const char*)Q + (uint64_t)b0 * m * v.row_bytes,
                              q_scale ? q_scale + b0 : nullptr, Bg, m, k, out_ids + (uint64_t)b0 * k, out_scores + (uint64_t)b0 * k,
-                             out_raw ? out_raw + (uint64_t)b0 * k : nullptr, out_counts + b0, workspace, inner, vcnt, st);
+                             out_raw ? out_raw + (uint64_t)b0 * k : nullptr, out_counts + b0, workspace, inner, vcnt, st, nullptr, nullptr, 0);
         if (rc != LINR_OK) return rc;
     }
     return LINR_OK;

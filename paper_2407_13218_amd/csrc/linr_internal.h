@@ -163,6 +163,9 @@ struct linr_prefilter_args {
     // first (lo == 0) takes a small sample, a merge publishes the k-th key found (tau), and the later phases keep only
     // keys that are not below it
     uint32_t mod, lo, hi; const unsigned long long* tau;
+    // candidate lists instead of a predicate (two-stage search with many candidates): cand [nq][cand_T] item ids,
+    // cand_counts [nq] how many of each row are valid
+    const uint32_t* cand; const unsigned long long* cand_counts; uint64_t cand_T;
     uint32_t vec16;             // (set by the launcher) the word / mask / timestamp columns are 16-byte aligned
 };
 hipError_t linr_launch_prefilter(const linr_prefilter_args& a, hipStream_t s);   // one phase: zero, score, counts

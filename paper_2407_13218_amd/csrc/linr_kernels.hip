@@ -2117,11 +2117,15 @@ __device__ __forceinline__ uint32_t shift_in(uint32_t w, u64 cond)
     return r;
 }
 
-// MODE 0: one feasibility word per item is given; 1: bitmask filters; 2: bitmask filters and timestamp windows
+// MODE 0: one feasibility word per item is given; 1: bitmask filters; 2: bitmask filters and timestamp windows;
+// 3: a list of candidate ids per query is given (a "run" is then 512 slots of one query's list)
 template <int MODE>
 __global__ void __launch_bounds__(256, 4) prefilter_score_kernel(linr_prefilter_args A)
 {
     constexpr int R = LINR_PREFILTER_RUN, QCAP = LINR_PREFILTER_QCAP;
+    constexpr bool from_filters = MODE == 1 || MODE == 2;
+    constexpr bool has_ts = MODE == 2;
+    constexpr bool from_lists = MODE == 3;
     // per wave: the feasible (item, query) pairs found so far (item id, query), their keys, and per query a count / a
     // position.  Pairs of many runs share one flush, so a sparse predicate costs few counter updates.
     __shared__ uint32_t queue_all[256 / 64][QCAP];
@@ -2138,15 +2142,14 @@ __global__ void __launch_bounds__(256, 4) prefilter_score_kernel(linr_prefilter_
     u64* bound = bound_all[wib];
     // (run numbers fit 32 bits: item ids do)
     const uint32_t wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, n_waves = (gridDim.x * blockDim.x) >> 6;
-    const uint32_t n_runs = (uint32_t)((A.n + 64 * R - 1) / (64 * R));
+    const uint32_t rpq = from_lists ? (uint32_t)((A.cand_T + 64 * R - 1) / (64 * R)) : 1u;       // runs per query's list
+    const uint32_t n_runs = from_lists ? A.nq * rpq : (uint32_t)((A.n + 64 * R - 1) / (64 * R));
     // this phase's runs: those whose number modulo `mod` lies in [lo, hi)
     const uint32_t per = A.hi - A.lo, rem = n_runs % A.mod;
     const uint32_t n_sel = (n_runs / A.mod) * per + (rem > A.lo ? (rem - A.lo < per ? rem - A.lo : per) : 0u);
     // bitmask / timestamp filters (no feasibility words given): the queries' filters in the compact form the scans use
     __shared__ uint32_t f_must[32], f_care[32], f_t0[32], f_span[32];
     __shared__ uint32_t f_any;                 // bit b: query b also has "any of" groups (checked apart, after the loop)
-    constexpr bool from_filters = MODE != 0;
-    constexpr bool has_ts = MODE == 2;
     if (threadIdx.x == 0) f_any = 0u;
     __syncthreads();
     if (from_filters && threadIdx.x < 32) {
@@ -2290,6 +2293,17 @@ __global__ void __launch_bounds__(256, 4) prefilter_score_kernel(linr_prefilter_
     // word r = 4 h + c of a lane is item run0 + 256 h + 4 lane + c; `a` = feasibility words or masks, `t` = timestamps
     auto run_of = [&](uint32_t rr) { return (rr / per) * A.mod + A.lo + rr % per; };
     auto load_run = [&](uint32_t rr, uint32_t (&a)[R], uint32_t (&t)[R]) {
+        if constexpr (from_lists) {                   // a = candidate id (0xFFFFFFFF: beyond the list), t = its query
+            const uint32_t run = run_of(rr), b = run / rpq, c = run % rpq;
+            const u64 have = A.cand_counts[b] < A.cand_T ? A.cand_counts[b] : A.cand_T;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const u64 j = (u64)c * (64 * R) + 256 * (r / 4) + 4 * lane + (r % 4);
+                a[r] = j < have ? A.cand[(u64)b * A.cand_T + j] : 0xFFFFFFFFu;
+                t[r] = b;
+            }
+            return;
+        }
         const u64 run0 = (u64)run_of(rr) * (64 * R);
         const uint32_t* src = from_filters ? A.mask : A.words;
         if (run0 + 64 * R <= A.n && A.vec16) {
@@ -2322,13 +2336,16 @@ __global__ void __launch_bounds__(256, 4) prefilter_score_kernel(linr_prefilter_
     if (wave < n_sel) load_run(wave, cur_a, cur_t);
     for (uint32_t rr = wave; rr < n_sel; rr += n_waves) {
         const u64 run0 = (u64)run_of(rr) * (64 * R);
-        const bool full = run0 + 64 * R <= A.n;
+        const bool full = from_lists || run0 + 64 * R <= A.n;
         // the next run's words are on their way while this one is looked at
         uint32_t nxt_a[R], nxt_t[R];
         const bool more = rr + n_waves < n_sel && rr + n_waves > rr;
         if (more) load_run(rr + n_waves, nxt_a, nxt_t);
         uint32_t w[R];
-        if constexpr (!from_filters) {
+        if constexpr (from_lists) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) w[r] = cur_a[r] != 0xFFFFFFFFu ? 1u << cur_t[r] : 0u;
+        } else if constexpr (!from_filters) {
 #pragma unroll
             for (int r = 0; r < R; ++r) w[r] = cur_a[r];
         } else {
@@ -2373,7 +2390,7 @@ __global__ void __launch_bounds__(256, 4) prefilter_score_kernel(linr_prefilter_
                         const uint32_t b = (uint32_t)__builtin_ctz(word);
                         word &= word - 1u;
                         const uint32_t at = qn + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
-                        queue[at] = (uint32_t)run0 + (uint32_t)(256 * (r / 4) + 4 * lane + (r % 4));
+                        queue[at] = from_lists ? cur_a[r] : (uint32_t)run0 + (uint32_t)(256 * (r / 4) + 4 * lane + (r % 4));
                         qb[at] = (uint8_t)b;
                     }
                     qn += (uint32_t)__popcll(bal);
@@ -3415,11 +3432,13 @@ hipError_t linr_launch_prefilter(const linr_prefilter_args& a_in, hipStream_t s)
     }
     if (a.lo == 0) hipLaunchKernelGGL(prefilter_zero_kernel, dim3(1), dim3(64), 0, s, a.vcnt);
     // as many workgroups as are resident at once; a wave keeps its queue across its runs
-    const uint64_t runs = (a.n + 64 * LINR_PREFILTER_RUN - 1) / (64 * LINR_PREFILTER_RUN);
+    const uint64_t runs = a.cand ? (uint64_t)a.nq * ((a.cand_T + 64 * LINR_PREFILTER_RUN - 1) / (64 * LINR_PREFILTER_RUN))
+                                 : (a.n + 64 * LINR_PREFILTER_RUN - 1) / (64 * LINR_PREFILTER_RUN);
     const uint64_t sel = (runs / a.mod + 1) * (a.hi - a.lo);
     const uint64_t blocks = (sel + 3) / 4, most = (uint64_t)cus * per_cu;
     const dim3 grid((uint32_t)(blocks < most ? blocks : most));
-    if (a.words) hipLaunchKernelGGL(prefilter_score_kernel<0>, grid, dim3(256), 0, s, a);
+    if (a.cand) hipLaunchKernelGGL(prefilter_score_kernel<3>, grid, dim3(256), 0, s, a);
+    else if (a.words) hipLaunchKernelGGL(prefilter_score_kernel<0>, grid, dim3(256), 0, s, a);
     else if (!a.ts) hipLaunchKernelGGL(prefilter_score_kernel<1>, grid, dim3(256), 0, s, a);
     else hipLaunchKernelGGL(prefilter_score_kernel<2>, grid, dim3(256), 0, s, a);
     hipLaunchKernelGGL(prefilter_counts_kernel, dim3(a.nq), dim3(256), 0, s, a);

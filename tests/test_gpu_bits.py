@@ -139,7 +139,10 @@ def test_bits_search_few_levels_many_ties(oracle_mod):
 
 
 @pytest.mark.parametrize("dtype,d,k_bits,T,k", [(S.F32, 64, 64, 400, 50), (S.BF16, 128, 64, 1000, 100), (S.F32, 64, 64, 2048, 2048),
-                                                (S.BF16, 64, 64, 8192, 3000)])
+                                                (S.BF16, 64, 64, 8192, 3000),
+                                                # more candidates than a ranking holds: selection + candidate scoring
+                                                (S.F32, 64, 64, 8193, 100), (S.BF16, 128, 64, 30_000, 2000),
+                                                (S.F32, 64, 64, 40_000, 500), (S.BF16, 256, 128, 20_000, 8192)])
 def test_two_stage_against_the_oracle(oracle_mod, dtype, d, k_bits, T, k):
     import torch
     import paper_2407_13218_amd as L
@@ -159,12 +162,21 @@ def test_two_stage_against_the_oracle(oracle_mod, dtype, d, k_bits, T, k):
     torch.cuda.synchronize()
     ids = ids.cpu().numpy().view(np.uint32); sc = sc.cpu().numpy(); cnt = cnt.cpu().numpy().view(np.uint32)
     # first stage, exactly: the candidate sets must be the oracle's
-    qb = ix.quantize(as_t(q)); i1, m1, c1 = ix.search_bits(qb, f, T)
-    torch.cuda.synchronize()
+    qb = ix.quantize(as_t(q))
     bits = oracle_mod.sign_oporp(dtype, x, perm, signs, k_bits); qbo = oracle_mod.sign_oporp(dtype, q, perm, signs, k_bits)
     oi1, om1, oc1 = oracle_mod.bits_search(bits, k_bits, mask, qbo, f, T)
-    assert np.array_equal(i1.cpu().numpy().view(np.uint32), oi1) and np.array_equal(m1.cpu().numpy(), om1)
-    assert np.array_equal(c1.cpu().numpy().view(np.uint32), oc1)
+    if T <= L.MAX_K:
+        i1, m1, c1 = ix.search_bits(qb, f, T)
+        torch.cuda.synchronize()
+        assert np.array_equal(i1.cpu().numpy().view(np.uint32), oi1) and np.array_equal(m1.cpu().numpy(), om1)
+        assert np.array_equal(c1.cpu().numpy().view(np.uint32), oc1)
+    else:
+        i1, c1, _ = ix.select_bits(qb, f, T)
+        torch.cuda.synchronize()
+        i1 = i1.cpu().numpy().view(np.uint32); c1 = c1.cpu().numpy()
+        for b in range(B):
+            assert int(c1[b]) == int(oc1[b])
+            assert np.array_equal(i1[b, :int(c1[b])], np.sort(oi1[b, :int(oc1[b])]))
     # second stage: 1e-3 rule among the candidates
     rtol, atol = 1e-3, 1e-6
     for b in range(B):
