@@ -326,14 +326,14 @@ def two_stage_leg(L, S, args, dev):
                                                L.FILTERS_ON_DEVICE))
     truth = [set(r.tolist()) for r in ids.cpu().numpy()]
     rows = []
-    for T in (1000, 2000, 4000, 8192):
+    for T in (1000, 2000, 4000, 8192, n // 100):             # the last: "keep 1 % of the items" (Sec. 5.3)
         nb2 = L.search_two_stage_workspace_bytes(ix.handle, B, T, k)
         ws2 = torch.empty(nb2, dtype=torch.uint8, device=dev)
         ms = timed(lambda: L.search_two_stage(ix.handle, Q, B, filt, T, k, ids, sc, cnt, ws2, nb2, stream, L.FILTERS_ON_DEVICE))
         got = ids.cpu().numpy()
         recall = float(np.mean([len(truth[b] & set(got[b].tolist())) / k for b in range(B)]))
         rows.append(dict(T=T, ms_per_search=round(ms, 4), recall_at_k=round(recall, 4)))
-        log(f"  two-stage T={T:5d}: {ms:.3f} ms/search, recall@{k} {recall:.3f} (exact search {exact_ms:.3f} ms)")
+        log(f"  two-stage T={T:6d}: {ms:.3f} ms/search, recall@{k} {recall:.3f} (exact search {exact_ms:.3f} ms)")
         del ws2
     ix.close()
     return {"workload": f"config 2 at full size: {n} x d128 bf16, 25 % pass rate, B = {B}, k = {k}, {kb}-bit codes",
