@@ -202,10 +202,11 @@ int linr_index_destroy(linr_index*);
  *     the top k <= T by (score descending, id ascending): out_ids / out_scores device
  *     [B][k], out_counts device [B] = min(k, T, #feasible).  m = 1.  An approximation of
  *     linr_search_filtered whose recall grows with T; it equals it when T >= #feasible.
- *     T may exceed LINR_MAX_K (the paper's experiment keeps 1 % of the items): the
- *     candidates then come from linr_select_bits and are scored by the gather pass of the
- *     explicit pre-filtering; k <= LINR_MAX_K; a query whose sampled candidates overflow
- *     the workspace's candidate arrays gets out_counts[b] = LINR_COUNT_OVERFLOW.
+ *     T may exceed LINR_MAX_K (the paper's experiment keeps 1 % of the items): from
+ *     T = 2000 on the candidates come from linr_select_bits and are scored by the gather
+ *     pass of the explicit pre-filtering (faster than ranking them first; same results);
+ *     k <= LINR_MAX_K; a query whose sampled candidates overflow the workspace's
+ *     candidate arrays gets out_counts[b] = LINR_COUNT_OVERFLOW.
  * Workspaces: device, 256-byte aligned, sizes from the *_workspace_bytes calls; filters,
  * hip_stream and flags as for linr_search_filtered.  Errors as there, plus LINR_E_DTYPE
  * (index kind does not fit the call) and LINR_E_NOT_LOADED (no codes built yet).
@@ -228,8 +229,8 @@ int linr_search_bits(const linr_index*, const uint64_t* qbits, uint32_t B, const
  * out_counts device uint64 [B], out_thresholds device int32 [B].  Any K >= 1 (K beyond
  * the item count selects every feasible item).  qbits device [B][W], 16-byte aligned;
  * filters / flags / hip_stream as for linr_search_filtered; B <= 65535.  Exact: a match
- * count takes k_bits + 1 values only, so two streaming passes over the codes (counts per
- * 65536-item segment, then the ids) replace a sort.  Works on a codes-only index and on
+ * count takes k_bits + 1 values only, so two streaming passes (counts per segment of
+ * items, then the ids) replace a sort.  Works on a codes-only index and on
  * the codes built for an fp32 / bf16 index, also next to live updates.
  */
 int linr_select_bits_workspace_bytes(const linr_index*, uint32_t B, uint64_t* bytes);
@@ -372,12 +373,14 @@ int linr_last_hip_error(void);
  *   no_top_split   : 1 = do not split the last sweep into the finer 1/8, 3/8, 1/2 sweeps;
  *   prefilter_phases: 2 or 3 = the explicit pre-filtering searches take that many phases (1/16 of the items, the
  *                    rest; or 1/256, 15/256, the rest) whatever the index size; 0 = three from 2^26 items on;
+ *   two_stage_rank_max: linr_search_two_stage ranks its candidates (linr_search_bits + re-scoring kernel) up to this
+ *                    T and takes the selection path (linr_select_bits + gather scoring) above it; 0 = 1999;
  *   wide_min_batch : use the 32x32-tile kernel (int8, m = 1, rows of 64 / 128 / 256 bytes) for batches of at
  *                    least this many queries; 0 = never (the default: it does not beat the other kernels yet).
  */
 typedef struct {
     uint32_t sample_ratio, min_sample, blocks_per_cu, max_levels, force_generic, max_qg, no_coop, coop_min_groups;
-    uint32_t no_top_split, prefilter_phases, wide_min_batch, _r3;
+    uint32_t no_top_split, prefilter_phases, wide_min_batch, two_stage_rank_max;
 } linr_tuning;
 int linr_set_tuning(const linr_tuning*);
 

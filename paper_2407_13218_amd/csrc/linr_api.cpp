@@ -751,10 +751,13 @@ extern "C" int linr_search_bits_timed(const linr_index* ix, const uint64_t* qbit
 
 // large-K selection by bit matching: workspace = counts [B][264] u64 | segment counts [B][n_seg][k_bits + 1] u32 |
 // two offset arrays [B][n_seg] u64 | cuts [B] | a copy of host-side filters | differing bits [B][n_seg * 65536] u8
-struct select_layout { uint64_t off_hist, off_seg, off_gt, off_eq, off_cut, off_filters, off_dcache, total; uint32_t n_seg; };
+struct select_layout { uint64_t off_hist, off_seg, off_gt, off_eq, off_cut, off_filters, off_dcache, total; uint32_t n_seg, seg_items; };
 static void select_plan(const linr_index& v, uint32_t B, select_layout* L)
 {
-    L->n_seg = (uint32_t)((v.n + LINR_SELECT_SEGMENT - 1) / LINR_SELECT_SEGMENT);
+    // large segments when there are enough of them to fill the chip several times over, else smaller ones
+    // (decided by the capacity, so that the workspace size does not depend on the number of items resident right now)
+    L->seg_items = (v.capacity / 65536) * B >= 8192 ? 65536u : 16384u;
+    L->n_seg = (uint32_t)((v.n + L->seg_items - 1) / L->seg_items);
     uint64_t o = 0;
     L->off_hist = o; o += align_up((uint64_t)B * LINR_SELECT_BINS * 8, 256);
     L->off_seg = o; o += align_up((uint64_t)B * L->n_seg * (v.k_bits + 1) * 4, 256);
@@ -763,7 +766,7 @@ static void select_plan(const linr_index& v, uint32_t B, select_layout* L)
     L->off_cut = o; o += align_up((uint64_t)B * sizeof(linr_select_cut), 256);
     L->off_filters = o; o += align_up((uint64_t)B * sizeof(linr_filter), 256);
     // one byte per item and query: the differing bits, kept between the passes (codes of up to 254 bits)
-    L->off_dcache = o; if (v.k_bits <= 254) o += align_up((uint64_t)B * L->n_seg * LINR_SELECT_SEGMENT, 256);
+    L->off_dcache = o; if (v.k_bits <= 254) o += align_up((uint64_t)B * L->n_seg * L->seg_items, 256);
     L->total = o;
 }
 
@@ -812,7 +815,7 @@ extern "C" int linr_select_bits(const linr_index* ix, const uint64_t* qbits, uin
     linr_select_args a;
     memset(&a, 0, sizeof(a));
     a.bits = (const unsigned long long*)v.bits; a.words = v.bits_words; a.k_bits = v.k_bits; a.mask = v.mask; a.ts = v.ts;
-    a.dead_bit = v.dead_bit; a.n = v.n; a.id_base = 0; a.n_seg = L.n_seg; a.B = B;
+    a.dead_bit = v.dead_bit; a.n = v.n; a.id_base = 0; a.n_seg = L.n_seg; a.seg_items = L.seg_items; a.B = B;
     a.q_codes = (const unsigned long long*)qbits; a.filters = use; a.K = K;
     a.hist = (unsigned long long*)(ws + L.off_hist); a.seg_hist = (uint32_t*)(ws + L.off_seg);
     a.gt_base = (unsigned long long*)(ws + L.off_gt); a.eq_base = (unsigned long long*)(ws + L.off_eq);
@@ -851,6 +854,13 @@ static int two_stage_large_plan(const linr_index* ix, uint32_t B, uint64_t T, ui
     L->off_vcnt = o; o += 4096;
     L->total = o;
     return LINR_OK;
+}
+
+// candidates up to this T are ranked first (linr_search_bits + rescore kernel); above it: selection + gather scoring
+static uint32_t two_stage_rank_max()
+{
+    const uint32_t t = g_tuning.two_stage_rank_max ? g_tuning.two_stage_rank_max : 1999u;
+    return t < LINR_MAX_K ? t : LINR_MAX_K;
 }
 
 static int two_stage_large(const linr_index* ix, const void* Q, uint32_t B, const linr_filter* filters, uint64_t T, uint32_t k,
@@ -893,7 +903,7 @@ extern "C" int linr_search_two_stage_workspace_bytes(const linr_index* ix, uint3
     if (!ix || !bytes) return LINR_E_NULL;
     if (ix->dtype != LINR_F32 && ix->dtype != LINR_BF16) return LINR_E_DTYPE;
     if (k == 0 || k > T) return LINR_E_K;
-    if (T > LINR_MAX_K) {
+    if (T > two_stage_rank_max()) {
         two_stage_large_layout L;
         int rc2 = two_stage_large_plan(ix, B ? B : 1, T > ix->capacity ? ix->capacity : T, k, &L);
         if (rc2 != LINR_OK) return rc2;
@@ -918,7 +928,7 @@ extern "C" int linr_search_two_stage(const linr_index* ix, const void* Q, uint32
     if (ix->n == 0 || !ix->emb || !ix->bits) return LINR_E_NOT_LOADED;
     if (B == 0) return LINR_OK;
     if (!Q || !filters || !out_ids || !out_scores || !out_counts) return LINR_E_NULL;
-    if (T > LINR_MAX_K)
+    if (T > two_stage_rank_max())
         return two_stage_large(ix, Q, B, filters, T, k, out_ids, out_scores, out_counts, workspace, workspace_bytes, hip_stream,
                                flags);
     uint64_t s1 = 0, total = 0;

@@ -172,18 +172,19 @@ hipError_t linr_launch_prefilter(const linr_prefilter_args& a, hipStream_t s);  
 // out_counts[b] = 0xFFFFFFFF where vcnt[b] > capacity (run behind the merge)
 hipError_t linr_launch_prefilter_overflow(const uint32_t* vcnt, uint64_t capacity, uint32_t* out_counts, uint32_t nq, hipStream_t s);
 // large-K selection by bit matching (counting: the number of differing bits takes k_bits + 1 values)
-#define LINR_SELECT_SEGMENT 65536ull   // items whose counts are kept together (one workgroup per segment and query)
 #define LINR_SELECT_BINS 264           // row length of the global counts (k_bits <= 256 -> 257 values)
 struct linr_select_cut { uint32_t t_diff, pad_; uint64_t need_eq; };  // every item with fewer differing bits; the first need_eq with t_diff
 struct linr_select_args {
     const unsigned long long* bits; uint32_t words, k_bits; const uint32_t* mask; const uint32_t* ts; uint32_t dead_bit;
     uint64_t n; uint32_t id_base, n_seg, B;
+    uint32_t seg_items;                // items whose counts are kept together (one workgroup per segment and query):
+                                       // a multiple of 4096, at most 65536 (16-bit counts per lane in LDS)
     const unsigned long long* q_codes; const linr_filter* filters; uint64_t K;
     unsigned long long* hist;          // [B][LINR_SELECT_BINS], zero on entry
     uint32_t* seg_hist;                // [B][n_seg][k_bits + 1]
     unsigned long long* gt_base; unsigned long long* eq_base;     // [B][n_seg]
     linr_select_cut* cut;              // [B]
-    uint8_t* dcache;                   // [B][n_seg * 65536] differing bits per item (0xFF infeasible), or nullptr: recompute
+    uint8_t* dcache;                   // [B][n_seg * seg_items] differing bits per item (0xFF infeasible), or nullptr: recompute
     uint32_t* out_ids; unsigned long long* out_counts; int32_t* out_thresholds;
 };
 hipError_t linr_launch_select(const linr_select_args& a, hipStream_t s);

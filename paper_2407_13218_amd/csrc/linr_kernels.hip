@@ -2441,7 +2441,7 @@ __global__ void __launch_bounds__(64) prefilter_overflow_kernel(const uint32_t* 
 // ---------------------------------------------------------------------------
 // large-K selection by bit matching (LiNR Sec. 3.2: the quantised module on its own when K is large; the notification
 // use case of Sec. 5.3).  The number of differing bits takes k_bits + 1 values only, so the K best feasible items --
-// ties to the lower id -- follow from counting: pass 1 counts, per segment of 65536 items and per query, how many
+// ties to the lower id -- follow from counting: pass 1 counts, per segment of 16384 or 65536 items and per query, how many
 // feasible items differ in 0, 1, 2, ... bits; a small kernel finds the cut (every item below `t_diff` differing bits,
 // and the first `need_eq` items, by id, with exactly `t_diff`) and turns the segments' counts into output offsets;
 // pass 2 recomputes the counts of differing bits and writes the selected ids, in ascending id order.
@@ -2463,14 +2463,14 @@ struct SelectFilter {
     }
 };
 
+#define LINR_SELECT_QB 8               // queries one workgroup of the counting pass serves from one read of its items
+
 template <int W, bool TS>
 struct SelectTile {
-    uint32_t diff[4];                  // differing bits of the lane's four items; 0xFFFFFFFF = infeasible / beyond the end
-    __device__ __forceinline__ void load(const linr_select_args& A, const linr_filter& F, const SelectFilter& C, const u64* q,
-                                         u64 i0)
+    uint32_t mk[4], tv[4];             // the lane's four neighbouring items: masks, timestamps, codes
+    u64 x[4][W];
+    __device__ __forceinline__ void load(const linr_select_args& A, u64 i0)
     {
-        uint32_t mk[4], tv[4];
-        u64 x[4][W];
         if (i0 + 4 <= A.n) {
             const v4i m4 = __builtin_nontemporal_load((const v4i*)(A.mask + i0));
             mk[0] = (uint32_t)m4[0]; mk[1] = (uint32_t)m4[1]; mk[2] = (uint32_t)m4[2]; mk[3] = (uint32_t)m4[3];
@@ -2497,6 +2497,15 @@ struct SelectTile {
                 for (int w = 0; w < W; ++w) x[r][w] = A.bits[ic * W + w];
             }
         }
+        if (!TS) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) tv[r] = 0u;
+        }
+    }
+    // differing bits of the four items for one query; 0xFFFFFFFF = infeasible / beyond the end
+    __device__ __forceinline__ void eval(const linr_select_args& A, const linr_filter* F, const SelectFilter& C, const u64* q, u64 i0,
+                                         uint32_t (&diff)[4]) const
+    {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             uint32_t d = 0;
@@ -2507,60 +2516,64 @@ struct SelectTile {
             diff[r] = ok ? d : 0xFFFFFFFFu;
         }
         if (C.any) {                                          // (uniform)
+            const linr_filter f = *F;
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                if (diff[r] != 0xFFFFFFFFu && !filter_pass(F, mk[r], TS, TS ? tv[r] : 0u)) diff[r] = 0xFFFFFFFFu;
+                if (diff[r] != 0xFFFFFFFFu && !filter_pass(f, mk[r], TS, tv[r])) diff[r] = 0xFFFFFFFFu;
         }
     }
 };
 
-// pass 1: grid (segments, queries).  seg_hist[b][segment][bins], hist[b][bins] (zeroed by the caller); with `dcache` the
-// count of differing bits of every item is kept, one byte each (0xFF = infeasible), so that pass 2 reads 1 byte per item
+// pass 1: grid (segments, groups of up to 8 queries): every item of the segment is read once and compared with each
+// query of the group.  seg_hist[b][segment][bins], hist[b][bins] (zeroed by the caller); with `dcache` the count of
+// differing bits of every (query, item) is kept, one byte each (0xFF = infeasible), so that pass 2 reads 1 byte per item
 template <int W, bool TS>
 __global__ void __launch_bounds__(256) select_hist_kernel(linr_select_args A)
 {
-    // counts per (number of differing bits, lane): lane l of every wave adds into column l, so the lanes of one
-    // instruction never meet in a word (match counts cluster: a shared row would serialise them); two 16-bit counts
-    // per word -- a column sees at most 4 x 256 items of the segment
-    constexpr int HW = 32 * W + 1;
-    __shared__ uint32_t h[HW][64];
-    const uint32_t b = blockIdx.y, seg = blockIdx.x, bins = A.k_bits + 1;
-    const int lane = threadIdx.x & 63;
-    for (uint32_t j = threadIdx.x; j < HW * 64; j += 256) (&h[0][0])[j] = 0u;
+    constexpr int HB = 64 * W + 4;
+    __shared__ uint32_t h[LINR_SELECT_QB][4][HB];    // four copies per query (lane % 4): match counts cluster
+    __shared__ SelectFilter Cs[LINR_SELECT_QB];
+    __shared__ u64 qs[LINR_SELECT_QB][W];
+    const uint32_t b0 = blockIdx.y * LINR_SELECT_QB, seg = blockIdx.x, bins = A.k_bits + 1;
+    const uint32_t nqb = A.B - b0 < (uint32_t)LINR_SELECT_QB ? A.B - b0 : (uint32_t)LINR_SELECT_QB;
+    for (uint32_t j = threadIdx.x; j < LINR_SELECT_QB * 4 * HB; j += 256) (&h[0][0][0])[j] = 0u;
+    if (threadIdx.x < nqb) {
+        SelectFilter c;
+        c.set(A.filters[b0 + threadIdx.x], A.dead_bit);
+        Cs[threadIdx.x] = c;
+        for (int w = 0; w < W; ++w) qs[threadIdx.x][w] = A.q_codes[(u64)(b0 + threadIdx.x) * W + w];
+    }
     __syncthreads();
-    const linr_filter F = A.filters[b];
-    SelectFilter C;
-    C.set(F, A.dead_bit);
-    u64 q[W];
+    const u64 lo = (u64)seg * A.seg_items;
+    const u64 hi = lo + A.seg_items < A.n ? lo + A.seg_items : A.n;
+    const u64 row = (u64)A.n_seg * A.seg_items;                      // bytes of one query's kept counts
+    for (u64 t0 = lo; t0 < hi; t0 += LINR_SELECT_TILE) {
+        SelectTile<W, TS> T;
+        const u64 i0 = t0 + 4 * threadIdx.x;
+        T.load(A, i0);
+        for (uint32_t qi = 0; qi < nqb; ++qi) {
+            const SelectFilter C = Cs[qi];
+            u64 q[W];
 #pragma unroll
-    for (int w = 0; w < W; ++w) q[w] = A.q_codes[(u64)b * W + w];
-    const u64 lo = (u64)seg * LINR_SELECT_SEGMENT;
-    const u64 hi = lo + LINR_SELECT_SEGMENT < A.n ? lo + LINR_SELECT_SEGMENT : A.n;
-    uint8_t* dc = A.dcache ? A.dcache + (u64)b * A.n_seg * LINR_SELECT_SEGMENT : nullptr;
-    for (u64 t0 = lo; t0 < hi; t0 += 2 * LINR_SELECT_TILE) {            // two tiles' loads in flight
-        SelectTile<W, TS> T[2];
-        const bool two = t0 + LINR_SELECT_TILE < hi;
-        T[0].load(A, F, C, q, t0 + 4 * threadIdx.x);
-        if (two) T[1].load(A, F, C, q, t0 + LINR_SELECT_TILE + 4 * threadIdx.x);
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            if (u == 1 && !two) break;
+            for (int w = 0; w < W; ++w) q[w] = qs[qi][w];
+            uint32_t diff[4];
+            T.eval(A, A.filters + b0 + qi, C, q, i0, diff);
             uint32_t packed = 0;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                if (T[u].diff[r] != 0xFFFFFFFFu) atomicAdd(&h[T[u].diff[r] >> 1][lane], 1u << (16 * (T[u].diff[r] & 1u)));
-                packed |= (T[u].diff[r] & 0xFFu) << (8 * r);
+                if (diff[r] != 0xFFFFFFFFu) atomicAdd(&h[qi][threadIdx.x & 3][diff[r]], 1u);
+                packed |= (diff[r] & 0xFFu) << (8 * r);
             }
-            // (the segments are padded to whole tiles)
-            if (dc) __builtin_nontemporal_store(packed, (uint32_t*)(dc + t0 + u * LINR_SELECT_TILE + 4 * threadIdx.x));
+            // (the segments are whole tiles: the cache is padded to them)
+            if (A.dcache) __builtin_nontemporal_store(packed, (uint32_t*)(A.dcache + (u64)(b0 + qi) * row + i0));
         }
     }
     __syncthreads();
-    for (uint32_t j = threadIdx.x; j < bins; j += 256) {
-        uint32_t c = 0;
-        for (int l = 0; l < 64; ++l) c += (h[j >> 1][(l + threadIdx.x) & 63] >> (16 * (j & 1u))) & 0xFFFFu;
-        A.seg_hist[((u64)b * A.n_seg + seg) * bins + j] = c;
-        if (c) atomicAdd(&A.hist[(u64)b * LINR_SELECT_BINS + j], (unsigned long long)c);
+    for (uint32_t j = threadIdx.x; j < nqb * bins; j += 256) {
+        const uint32_t qi = j / bins, d = j % bins;
+        const uint32_t c = h[qi][0][d] + h[qi][1][d] + h[qi][2][d] + h[qi][3][d];
+        A.seg_hist[((u64)(b0 + qi) * A.n_seg + seg) * bins + d] = c;
+        if (c) atomicAdd(&A.hist[(u64)(b0 + qi) * LINR_SELECT_BINS + d], (unsigned long long)c);
     }
 }
 
@@ -2639,24 +2652,25 @@ __global__ void __launch_bounds__(256) select_write_kernel(linr_select_args A)
     const linr_select_cut cut = A.cut[b];
     if (cut.t_diff == 0xFFFFFFFFu) return;
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-    const linr_filter F = A.filters[b];
     SelectFilter C;
-    C.set(F, A.dead_bit);
+    C.set(A.filters[b], A.dead_bit);
     u64 q[W];
 #pragma unroll
     for (int w = 0; w < W; ++w) q[w] = A.q_codes[(u64)b * W + w];
     u64 run_gt = A.gt_base[(u64)b * A.n_seg + seg], run_eq = A.eq_base[(u64)b * A.n_seg + seg];
     const u64 need = cut.need_eq;
     uint32_t* out = A.out_ids + (u64)b * A.K;
-    const u64 lo = (u64)seg * LINR_SELECT_SEGMENT;
-    const u64 hi = lo + LINR_SELECT_SEGMENT < A.n ? lo + LINR_SELECT_SEGMENT : A.n;
+    const u64 lo = (u64)seg * A.seg_items;
+    const u64 hi = lo + A.seg_items < A.n ? lo + A.seg_items : A.n;
     for (u64 t0 = lo; t0 < hi; t0 += LINR_SELECT_TILE) {
         SelectTile<W, TS> T;
         const u64 i0 = t0 + 4 * threadIdx.x;
-        T.load(A, F, C, q, i0);
+        T.load(A, i0);
+        uint32_t diff[4];
+        T.eval(A, A.filters + b, C, q, i0, diff);
         uint32_t cg = 0, ce = 0;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) { cg += T.diff[r] < cut.t_diff ? 1u : 0u; ce += T.diff[r] == cut.t_diff ? 1u : 0u; }
+        for (int r = 0; r < 4; ++r) { cg += diff[r] < cut.t_diff ? 1u : 0u; ce += diff[r] == cut.t_diff ? 1u : 0u; }
         // exclusive scan over the 256 lanes of (ties << 16 | better): wave by shuffles, waves through LDS
         const uint32_t mine = (ce << 16) | cg;
         uint32_t inc = mine;
@@ -2674,7 +2688,7 @@ __global__ void __launch_bounds__(256) select_write_kernel(linr_select_args A)
         u64 g_before = run_gt + (before & 0xFFFFu), e_before = run_eq + (before >> 16);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const bool better = T.diff[r] < cut.t_diff, tie = T.diff[r] == cut.t_diff;
+            const bool better = diff[r] < cut.t_diff, tie = diff[r] == cut.t_diff;
             if (better || (tie && e_before < need))
                 out[g_before + (e_before < need ? e_before : need)] = (uint32_t)(i0 + r) + A.id_base;
             g_before += better ? 1u : 0u; e_before += tie ? 1u : 0u;
@@ -3462,9 +3476,9 @@ __global__ void __launch_bounds__(256) select_write_cached_kernel(linr_select_ar
     u64 run_gt = A.gt_base[(u64)b * A.n_seg + seg], run_eq = A.eq_base[(u64)b * A.n_seg + seg];
     const u64 need = cut.need_eq;
     uint32_t* out = A.out_ids + (u64)b * A.K;
-    const uint8_t* dc = A.dcache + (u64)b * A.n_seg * LINR_SELECT_SEGMENT;
-    const u64 lo = (u64)seg * LINR_SELECT_SEGMENT;
-    const u64 hi = lo + LINR_SELECT_SEGMENT < A.n ? lo + LINR_SELECT_SEGMENT : A.n;
+    const uint8_t* dc = A.dcache + (u64)b * A.n_seg * A.seg_items;
+    const u64 lo = (u64)seg * A.seg_items;
+    const u64 hi = lo + A.seg_items < A.n ? lo + A.seg_items : A.n;
     for (u64 t0 = lo; t0 < hi; t0 += 16 * 256) {
         const u64 i0 = t0 + 16 * threadIdx.x;
         v4i raw = {-1, -1, -1, -1};
@@ -3508,8 +3522,9 @@ static void select_launch(const linr_select_args& a, int pass, hipStream_t s)
 {
     const dim3 grid(a.n_seg, a.B), block(256);
     if (pass == 0) {
-        if (a.ts) hipLaunchKernelGGL((select_hist_kernel<W, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((select_hist_kernel<W, false>), grid, block, 0, s, a);
+        const dim3 grid1(a.n_seg, (a.B + LINR_SELECT_QB - 1) / LINR_SELECT_QB);
+        if (a.ts) hipLaunchKernelGGL((select_hist_kernel<W, true>), grid1, block, 0, s, a);
+        else hipLaunchKernelGGL((select_hist_kernel<W, false>), grid1, block, 0, s, a);
     } else if (a.dcache) {
         hipLaunchKernelGGL(select_write_cached_kernel, grid, block, 0, s, a);
     } else {
@@ -3522,7 +3537,8 @@ static void select_launch(const linr_select_args& a, int pass, hipStream_t s)
 hipError_t linr_launch_select(const linr_select_args& a, hipStream_t s)
 {
     if (a.B == 0 || a.B > 65535u || a.n == 0 || a.K == 0 || a.k_bits == 0 || a.k_bits + 1 > LINR_SELECT_BINS ||
-        a.n_seg != (uint32_t)((a.n + LINR_SELECT_SEGMENT - 1) / LINR_SELECT_SEGMENT) ||
+        a.seg_items == 0 || a.seg_items % 4096 != 0 || a.seg_items > 65536 ||
+        a.n_seg != (uint32_t)((a.n + a.seg_items - 1) / a.seg_items) ||
         (a.words != 1 && a.words != 2 && a.words != 4) || a.k_bits > 64 * a.words || (a.dcache && a.k_bits > 254) ||
         (((uintptr_t)a.dcache) & 15u))
         return hipErrorInvalidValue;

@@ -143,10 +143,15 @@ def test_bits_search_few_levels_many_ties(oracle_mod):
                                                 # more candidates than a ranking holds: selection + candidate scoring
                                                 (S.F32, 64, 64, 8193, 100), (S.BF16, 128, 64, 30_000, 2000),
                                                 (S.F32, 64, 64, 40_000, 500), (S.BF16, 256, 128, 20_000, 8192)])
-def test_two_stage_against_the_oracle(oracle_mod, dtype, d, k_bits, T, k):
+@pytest.mark.parametrize("rank_max", [0, 8192])
+def test_two_stage_against_the_oracle(oracle_mod, dtype, d, k_bits, T, k, rank_max):
+    """rank_max = 8192 forces the ranking path (candidates ranked by linr_search_bits, re-scoring kernel) for every
+    T it can serve; the default takes the selection path from T = 2000 on"""
     import torch
     import paper_2407_13218_amd as L
-    say(f"two-stage dtype={dtype} d={d} k_bits={k_bits} T={T} k={k}")
+    if rank_max and T > L.MAX_K:
+        pytest.skip("only the selection path serves this T")
+    say(f"two-stage dtype={dtype} d={d} k_bits={k_bits} T={T} k={k} rank_max={rank_max}")
     n, B = 40_000, 9
     rng = np.random.default_rng(T + k)
     x = float_items(dtype, n, d, 77)
@@ -158,8 +163,12 @@ def test_two_stage_against_the_oracle(oracle_mod, dtype, d, k_bits, T, k):
     ix = L.Index(n, d, dtype, 0)
     ix.load(as_t(x), torch.from_numpy(mask.view(np.int32)).cuda())
     ix.build_bits(perm, signs, k_bits)
-    ids, sc, cnt = ix.search_two_stage(as_t(q), f, T, k)
-    torch.cuda.synchronize()
+    L.set_tuning(two_stage_rank_max=rank_max)
+    try:
+        ids, sc, cnt = ix.search_two_stage(as_t(q), f, T, k)
+        torch.cuda.synchronize()
+    finally:
+        L.set_tuning()
     ids = ids.cpu().numpy().view(np.uint32); sc = sc.cpu().numpy(); cnt = cnt.cpu().numpy().view(np.uint32)
     # first stage, exactly: the candidate sets must be the oracle's
     qb = ix.quantize(as_t(q))
