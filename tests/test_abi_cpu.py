@@ -61,3 +61,23 @@ def test_missing_library_fails_loudly(tmp_path, monkeypatch):
     monkeypatch.setattr(Bd, "_LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(ImportError):
         Bd.load_library()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """every box has one GPU: bench.py --gpus N > 1 says so and exits without touching a device"""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=60)
+    assert res.returncode != 0 and "one GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_product_package_does_not_import_the_oracle():
+    """the oracle is test infrastructure: nothing under the package, and bench.py only in its baseline legs, names it"""
+    pkg = os.path.join(ROOT, "paper_2407_13218_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f), errors="replace").read()
+                assert "import oracle" not in text and "from oracle" not in text and "linr_oracle" not in text, f
+    assert "import oracle" not in open(os.path.join(ROOT, "synth_inputs.py")).read()
