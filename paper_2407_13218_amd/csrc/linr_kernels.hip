@@ -2547,10 +2547,12 @@ __global__ void __launch_bounds__(256) select_hist_kernel(linr_select_args A)
     const u64 lo = (u64)seg * A.seg_items;
     const u64 hi = lo + A.seg_items < A.n ? lo + A.seg_items : A.n;
     const u64 row = (u64)A.n_seg * A.seg_items;                      // bytes of one query's kept counts
+    SelectTile<W, TS> T, N;
+    if (lo < hi) T.load(A, lo + 4 * threadIdx.x);
     for (u64 t0 = lo; t0 < hi; t0 += LINR_SELECT_TILE) {
-        SelectTile<W, TS> T;
         const u64 i0 = t0 + 4 * threadIdx.x;
-        T.load(A, i0);
+        const bool more = t0 + LINR_SELECT_TILE < hi;
+        if (more) N.load(A, i0 + LINR_SELECT_TILE);              // the next tile's loads are in flight meanwhile
         for (uint32_t qi = 0; qi < nqb; ++qi) {
             const SelectFilter C = Cs[qi];
             u64 q[W];
@@ -2567,6 +2569,7 @@ __global__ void __launch_bounds__(256) select_hist_kernel(linr_select_args A)
             // (the segments are whole tiles: the cache is padded to them)
             if (A.dcache) __builtin_nontemporal_store(packed, (uint32_t*)(A.dcache + (u64)(b0 + qi) * row + i0));
         }
+        if (more) T = N;
     }
     __syncthreads();
     for (uint32_t j = threadIdx.x; j < nqb * bins; j += 256) {
