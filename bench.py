@@ -326,7 +326,7 @@ def two_stage_leg(L, S, args, dev):
                                                L.FILTERS_ON_DEVICE))
     truth = [set(r.tolist()) for r in ids.cpu().numpy()]
     rows = []
-    for T in (1000, 2000, 4000, 8192, n // 100):             # the last: "keep 1 % of the items" (Sec. 5.3)
+    for T in (500, 1000, 2000, 4000, 8192, n // 100):             # the last: "keep 1 % of the items" (Sec. 5.3)
         nb2 = L.search_two_stage_workspace_bytes(ix.handle, B, T, k)
         ws2 = torch.empty(nb2, dtype=torch.uint8, device=dev)
         ms = timed(lambda: L.search_two_stage(ix.handle, Q, B, filt, T, k, ids, sc, cnt, ws2, nb2, stream, L.FILTERS_ON_DEVICE))

@@ -203,7 +203,7 @@ int linr_index_destroy(linr_index*);
  *     [B][k], out_counts device [B] = min(k, T, #feasible).  m = 1.  An approximation of
  *     linr_search_filtered whose recall grows with T; it equals it when T >= #feasible.
  *     T may exceed LINR_MAX_K (the paper's experiment keeps 1 % of the items): from
- *     T = 2000 on the candidates come from linr_select_bits and are scored by the gather
+ *     T = 1000 on the candidates come from linr_select_bits and are scored by the gather
  *     pass of the explicit pre-filtering (faster than ranking them first; same results);
  *     k <= LINR_MAX_K; a query whose sampled candidates overflow the workspace's
  *     candidate arrays gets out_counts[b] = LINR_COUNT_OVERFLOW.
@@ -374,7 +374,7 @@ int linr_last_hip_error(void);
  *   prefilter_phases: 2 or 3 = the explicit pre-filtering searches take that many phases (1/16 of the items, the
  *                    rest; or 1/256, 15/256, the rest) whatever the index size; 0 = three from 2^26 items on;
  *   two_stage_rank_max: linr_search_two_stage ranks its candidates (linr_search_bits + re-scoring kernel) up to this
- *                    T and takes the selection path (linr_select_bits + gather scoring) above it; 0 = 1999;
+ *                    T and takes the selection path (linr_select_bits + gather scoring) above it; 0 = 999;
  *   wide_min_batch : use the 32x32-tile kernel (int8, m = 1, rows of 64 / 128 / 256 bytes) for batches of at
  *                    least this many queries; 0 = never (the default: it does not beat the other kernels yet).
  */

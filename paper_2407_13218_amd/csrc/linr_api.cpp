@@ -756,7 +756,8 @@ static void select_plan(const linr_index& v, uint32_t B, select_layout* L)
 {
     // large segments when there are enough of them to fill the chip several times over, else smaller ones
     // (decided by the capacity, so that the workspace size does not depend on the number of items resident right now)
-    L->seg_items = (v.capacity / 65536) * B >= 8192 ? 65536u : 16384u;
+    const uint64_t groups = (B + 7) / 8;                      // (the counting pass serves eight queries per workgroup)
+    L->seg_items = (v.capacity / 65536) * groups >= 8192 ? 65536u : (v.capacity / 16384) * groups >= 4096 ? 16384u : 4096u;
     L->n_seg = (uint32_t)((v.n + L->seg_items - 1) / L->seg_items);
     uint64_t o = 0;
     L->off_hist = o; o += align_up((uint64_t)B * LINR_SELECT_BINS * 8, 256);
@@ -859,7 +860,7 @@ static int two_stage_large_plan(const linr_index* ix, uint32_t B, uint64_t T, ui
 // candidates up to this T are ranked first (linr_search_bits + rescore kernel); above it: selection + gather scoring
 static uint32_t two_stage_rank_max()
 {
-    const uint32_t t = g_tuning.two_stage_rank_max ? g_tuning.two_stage_rank_max : 1999u;
+    const uint32_t t = g_tuning.two_stage_rank_max ? g_tuning.two_stage_rank_max : 999u;
     return t < LINR_MAX_K ? t : LINR_MAX_K;
 }
 

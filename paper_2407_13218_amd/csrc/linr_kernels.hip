@@ -2118,7 +2118,8 @@ __device__ __forceinline__ uint32_t shift_in(uint32_t w, u64 cond)
 }
 
 // MODE 0: one feasibility word per item is given; 1: bitmask filters; 2: bitmask filters and timestamp windows;
-// 3: a list of candidate ids per query is given (a "run" is then 512 slots of one query's list)
+// 3: a list of candidate ids per query is given (a "run" is then 64 slots of one query's list, one per lane: every
+// candidate costs a gather, so short runs spread them over many waves)
 template <int MODE>
 __global__ void __launch_bounds__(256, 4) prefilter_score_kernel(linr_prefilter_args A)
 {
@@ -2142,7 +2143,7 @@ __global__ void __launch_bounds__(256, 4) prefilter_score_kernel(linr_prefilter_
     u64* bound = bound_all[wib];
     // (run numbers fit 32 bits: item ids do)
     const uint32_t wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, n_waves = (gridDim.x * blockDim.x) >> 6;
-    const uint32_t rpq = from_lists ? (uint32_t)((A.cand_T + 64 * R - 1) / (64 * R)) : 1u;       // runs per query's list
+    const uint32_t rpq = from_lists ? (uint32_t)((A.cand_T + 63) / 64) : 1u;                    // runs per query's list
     const uint32_t n_runs = from_lists ? A.nq * rpq : (uint32_t)((A.n + 64 * R - 1) / (64 * R));
     // this phase's runs: those whose number modulo `mod` lies in [lo, hi)
     const uint32_t per = A.hi - A.lo, rem = n_runs % A.mod;
@@ -2296,12 +2297,10 @@ __global__ void __launch_bounds__(256, 4) prefilter_score_kernel(linr_prefilter_
         if constexpr (from_lists) {                   // a = candidate id (0xFFFFFFFF: beyond the list), t = its query
             const uint32_t run = run_of(rr), b = run / rpq, c = run % rpq;
             const u64 have = A.cand_counts[b] < A.cand_T ? A.cand_counts[b] : A.cand_T;
+            const u64 j = (u64)c * 64 + lane;
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const u64 j = (u64)c * (64 * R) + 256 * (r / 4) + 4 * lane + (r % 4);
-                a[r] = j < have ? A.cand[(u64)b * A.cand_T + j] : 0xFFFFFFFFu;
-                t[r] = b;
-            }
+            for (int r = 0; r < R; ++r) { a[r] = 0xFFFFFFFFu; t[r] = b; }
+            if (j < have) a[0] = A.cand[(u64)b * A.cand_T + j];
             return;
         }
         const u64 run0 = (u64)run_of(rr) * (64 * R);
@@ -3449,7 +3448,7 @@ hipError_t linr_launch_prefilter(const linr_prefilter_args& a_in, hipStream_t s)
     }
     if (a.lo == 0) hipLaunchKernelGGL(prefilter_zero_kernel, dim3(1), dim3(64), 0, s, a.vcnt);
     // as many workgroups as are resident at once; a wave keeps its queue across its runs
-    const uint64_t runs = a.cand ? (uint64_t)a.nq * ((a.cand_T + 64 * LINR_PREFILTER_RUN - 1) / (64 * LINR_PREFILTER_RUN))
+    const uint64_t runs = a.cand ? (uint64_t)a.nq * ((a.cand_T + 63) / 64)
                                  : (a.n + 64 * LINR_PREFILTER_RUN - 1) / (64 * LINR_PREFILTER_RUN);
     const uint64_t sel = (runs / a.mod + 1) * (a.hi - a.lo);
     const uint64_t blocks = (sel + 3) / 4, most = (uint64_t)cus * per_cu;

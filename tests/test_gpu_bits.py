@@ -146,7 +146,7 @@ def test_bits_search_few_levels_many_ties(oracle_mod):
 @pytest.mark.parametrize("rank_max", [0, 8192])
 def test_two_stage_against_the_oracle(oracle_mod, dtype, d, k_bits, T, k, rank_max):
     """rank_max = 8192 forces the ranking path (candidates ranked by linr_search_bits, re-scoring kernel) for every
-    T it can serve; the default takes the selection path from T = 2000 on"""
+    T it can serve; the default takes the selection path from T = 1000 on"""
     import torch
     import paper_2407_13218_amd as L
     if rank_max and T > L.MAX_K:
