@@ -67,6 +67,26 @@ def test_long_runs_of_ties_across_segments(oracle_mod):
         run_case(oracle_mod, codes, k_bits, mask, None, q, f, K, f"ties K={K}")
 
 
+@pytest.mark.parametrize("k_bits", [64, 254, 255, 256])
+def test_every_count_of_differing_bits(oracle_mod, k_bits):
+    """items that differ from the query in exactly 0, 1, ..., k_bits bits (the full range, up to the complement of the
+    query): 254 bits is the widest code whose counts are kept as bytes between the passes, 255 and 256 recompute them"""
+    W = (k_bits + 63) // 64
+    n = 3 * (k_bits + 1) + 2
+    q = S.random_codes(1, k_bits, seed=k_bits)
+    codes = np.repeat(q, n, axis=0).copy()
+    for i in range(n):
+        j = i % (k_bits + 1)                                      # flip the lowest j bits
+        for w in range(W):
+            nb = min(64, max(0, j - 64 * w))
+            if nb:
+                codes[i, w] ^= np.uint64((1 << nb) - 1)
+    mask = np.ones(n, np.uint32)
+    f = S.make_filters(1); f["all_bits"][0] = 1
+    for K in (1, 4, n // 2, n - 1, n, n + 10):
+        run_case(oracle_mod, codes, k_bits, mask, None, q, f, K, f"full range k_bits={k_bits} K={K}")
+
+
 def test_nothing_feasible_and_everything_selected(oracle_mod):
     n, k_bits = 70_000, 64
     codes = S.random_codes(n, k_bits, seed=1); q = S.random_codes(2, k_bits, seed=2)
