@@ -8,8 +8,9 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "liblinr.so")
-SOURCES = [os.path.join(HERE, "csrc", "linr_kernels.hip"), os.path.join(HERE, "csrc", "linr_api.cpp")]
-DEPS = SOURCES + [os.path.join(HERE, "csrc", "linr_internal.h"), os.path.join(ROOT, "include", "linr.h")]
+SOURCES = [os.path.join(HERE, "csrc", "linr_kernels.hip"), os.path.join(HERE, "csrc", "linr_kernels_select.hip"),
+           os.path.join(HERE, "csrc", "linr_api.cpp")]
+DEPS = SOURCES + [os.path.join(HERE, "csrc", "linr_internal.h"), os.path.join(HERE, "csrc", "linr_device.h"), os.path.join(ROOT, "include", "linr.h")]
 
 
 def build(force: bool = True, verbose: bool = False) -> str:

@@ -13,16 +13,7 @@
 //
 // Key of a candidate: (orderable(ranking value) << 32) | ~item_id, so that a larger
 // key means "better score, then lower id"; all keys of one query are distinct.
-#include "linr_internal.h"
-#include <limits.h>
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef unsigned v4u __attribute__((ext_vector_type(4)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-typedef unsigned long long u64;
-
-#define WPB LINR_WAVES_PER_BLOCK
+#include "linr_device.h"
 
 // Event counters for kernel studies; compiled in only with -DLINR_STATS (the shipped library has none).
 #ifdef LINR_STATS
@@ -39,63 +30,6 @@ extern "C" int linr_debug_stats(unsigned long long* out, int reset)
 #define STAT_ADD(i, v) do { } while (0)
 #define STAT_CLOCK() 0ll
 #endif
-
-// ---------------------------------------------------------------------------
-// small helpers
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ void wave_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-__device__ __forceinline__ u64 wave_ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
-__device__ __forceinline__ bool wave_any(bool p) { return wave_ballot(p) != 0ull; }
-
-// monotone map fp32 -> uint32 (−0.0 is first folded into +0.0 so that both compare equal)
-__device__ __forceinline__ uint32_t ord_f32(float s)
-{
-    s = s + 0.0f;
-    uint32_t u = __float_as_uint(s);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-__device__ __forceinline__ float unord_f32(uint32_t o)
-{
-    uint32_t u = (o & 0x80000000u) ? (o ^ 0x80000000u) : ~o;
-    return __uint_as_float(u);
-}
-__device__ __forceinline__ uint32_t ord_i32(int x) { return (uint32_t)x ^ 0x80000000u; }
-__device__ __forceinline__ int unord_i32(uint32_t o) { return (int)(o ^ 0x80000000u); }
-
-__device__ __forceinline__ u64 aload64(const u64* p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// read back what this wave itself stored earlier (same compute unit, same L2: no device-wide flush needed)
-__device__ __forceinline__ u64 own_load64(const u64* p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
-__device__ __forceinline__ void own_stores_done()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-}
-__device__ __forceinline__ uint32_t aload32(const uint32_t* p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Sec. 3.1.1 feasibility rule over the 32-bit attribute mask and the timestamp window
-__device__ __forceinline__ bool filter_pass(const linr_filter& f, uint32_t mask, bool has_ts, uint32_t ts)
-{
-    bool ok = ((mask & f.all_bits) == f.all_bits) && ((mask & f.none_bits) == 0u);
-#pragma unroll
-    for (uint32_t g = 0; g < (uint32_t)LINR_MAX_ANY; ++g)
-        ok = ok && (g >= f.n_any || (mask & f.any_bits[g]) != 0u);
-    if (has_ts) ok = ok && (ts >= f.ts_min) && (ts <= f.ts_max);
-    return ok;
-}
 
 template <int DT> struct AccOf { typedef v4f type; };
 template <> struct AccOf<LINR_I8> { typedef v4i type; };
@@ -2438,268 +2372,6 @@ __global__ void __launch_bounds__(64) prefilter_overflow_kernel(const uint32_t* 
 }
 
 // ---------------------------------------------------------------------------
-// large-K selection by bit matching (LiNR Sec. 3.2: the quantised module on its own when K is large; the notification
-// use case of Sec. 5.3).  The number of differing bits takes k_bits + 1 values only, so the K best feasible items --
-// ties to the lower id -- follow from counting: pass 1 counts, per segment of 16384 or 65536 items and per query, how many
-// feasible items differ in 0, 1, 2, ... bits; a small kernel finds the cut (every item below `t_diff` differing bits,
-// and the first `need_eq` items, by id, with exactly `t_diff`) and turns the segments' counts into output offsets;
-// pass 2 recomputes the counts of differing bits and writes the selected ids, in ascending id order.
-// ---------------------------------------------------------------------------
-#define LINR_SELECT_TILE 1024          // items per workgroup step: 256 lanes x 4 neighbours
-
-// one query's filter in the compact form the scans use: (mask & care) == must, an unsigned window test for the
-// timestamp, and a flag for "any of" groups (checked with the full rule, only where the rest passed)
-struct SelectFilter {
-    uint32_t care, must, t0, span; bool any;
-    __device__ __forceinline__ void set(const linr_filter& F, uint32_t dead_bit)
-    {
-        const uint32_t none = F.none_bits | dead_bit;
-        const bool impossible = (F.all_bits & none) != 0u || F.ts_min > F.ts_max;
-        must = impossible ? 0xFFFFFFFFu : F.all_bits;
-        care = impossible ? 0u : (F.all_bits | none);
-        t0 = F.ts_min; span = F.ts_max - F.ts_min;
-        any = F.n_any != 0u && !impossible;
-    }
-};
-
-#define LINR_SELECT_QB 8               // queries one workgroup of the counting pass serves from one read of its items
-
-template <int W, bool TS>
-struct SelectTile {
-    uint32_t mk[4], tv[4];             // the lane's four neighbouring items: masks, timestamps, codes
-    u64 x[4][W];
-    __device__ __forceinline__ void load(const linr_select_args& A, u64 i0)
-    {
-        if (i0 + 4 <= A.n) {
-            const v4i m4 = __builtin_nontemporal_load((const v4i*)(A.mask + i0));
-            mk[0] = (uint32_t)m4[0]; mk[1] = (uint32_t)m4[1]; mk[2] = (uint32_t)m4[2]; mk[3] = (uint32_t)m4[3];
-            if (TS) {
-                const v4i t4 = __builtin_nontemporal_load((const v4i*)(A.ts + i0));
-                tv[0] = (uint32_t)t4[0]; tv[1] = (uint32_t)t4[1]; tv[2] = (uint32_t)t4[2]; tv[3] = (uint32_t)t4[3];
-            }
-            const v4i* src = (const v4i*)(A.bits + i0 * W);
-#pragma unroll
-            for (int j = 0; j < 2 * W; ++j) {                 // 32 W contiguous bytes: two words per load
-                const v4i c = __builtin_nontemporal_load(src + j);
-                const u64 lo = (u64)(uint32_t)c[0] | ((u64)(uint32_t)c[1] << 32), hi = (u64)(uint32_t)c[2] | ((u64)(uint32_t)c[3] << 32);
-                x[(2 * j) / W][(2 * j) % W] = lo;
-                x[(2 * j + 1) / W][(2 * j + 1) % W] = hi;
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const bool in = i0 + r < A.n;
-                const u64 ic = in ? i0 + r : A.n - 1;
-                mk[r] = in ? A.mask[ic] : 0u;
-                tv[r] = TS ? A.ts[ic] : 0u;
-#pragma unroll
-                for (int w = 0; w < W; ++w) x[r][w] = A.bits[ic * W + w];
-            }
-        }
-        if (!TS) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) tv[r] = 0u;
-        }
-    }
-    // differing bits of the four items for one query; 0xFFFFFFFF = infeasible / beyond the end
-    __device__ __forceinline__ void eval(const linr_select_args& A, const linr_filter* F, const SelectFilter& C, const u64* q, u64 i0,
-                                         uint32_t (&diff)[4]) const
-    {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            uint32_t d = 0;
-#pragma unroll
-            for (int w = 0; w < W; ++w) d += (uint32_t)__popcll(x[r][w] ^ q[w]);
-            bool ok = (i0 + r < A.n) & ((mk[r] & C.care) == C.must);
-            if (TS) ok = ok & (tv[r] - C.t0 <= C.span);
-            diff[r] = ok ? d : 0xFFFFFFFFu;
-        }
-        if (C.any) {                                          // (uniform)
-            const linr_filter f = *F;
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (diff[r] != 0xFFFFFFFFu && !filter_pass(f, mk[r], TS, tv[r])) diff[r] = 0xFFFFFFFFu;
-        }
-    }
-};
-
-// pass 1: grid (segments, groups of up to 8 queries): every item of the segment is read once and compared with each
-// query of the group.  seg_hist[b][segment][bins], hist[b][bins] (zeroed by the caller); with `dcache` the count of
-// differing bits of every (query, item) is kept, one byte each (0xFF = infeasible), so that pass 2 reads 1 byte per item
-template <int W, bool TS>
-__global__ void __launch_bounds__(256) select_hist_kernel(linr_select_args A)
-{
-    constexpr int HB = 64 * W + 4;
-    __shared__ uint32_t h[LINR_SELECT_QB][4][HB];    // four copies per query (lane % 4): match counts cluster
-    __shared__ SelectFilter Cs[LINR_SELECT_QB];
-    __shared__ u64 qs[LINR_SELECT_QB][W];
-    const uint32_t b0 = blockIdx.y * LINR_SELECT_QB, seg = blockIdx.x, bins = A.k_bits + 1;
-    const uint32_t nqb = A.B - b0 < (uint32_t)LINR_SELECT_QB ? A.B - b0 : (uint32_t)LINR_SELECT_QB;
-    for (uint32_t j = threadIdx.x; j < LINR_SELECT_QB * 4 * HB; j += 256) (&h[0][0][0])[j] = 0u;
-    if (threadIdx.x < nqb) {
-        SelectFilter c;
-        c.set(A.filters[b0 + threadIdx.x], A.dead_bit);
-        Cs[threadIdx.x] = c;
-        for (int w = 0; w < W; ++w) qs[threadIdx.x][w] = A.q_codes[(u64)(b0 + threadIdx.x) * W + w];
-    }
-    __syncthreads();
-    const u64 lo = (u64)seg * A.seg_items;
-    const u64 hi = lo + A.seg_items < A.n ? lo + A.seg_items : A.n;
-    const u64 row = (u64)A.n_seg * A.seg_items;                      // bytes of one query's kept counts
-    SelectTile<W, TS> T, N;
-    if (lo < hi) T.load(A, lo + 4 * threadIdx.x);
-    for (u64 t0 = lo; t0 < hi; t0 += LINR_SELECT_TILE) {
-        const u64 i0 = t0 + 4 * threadIdx.x;
-        const bool more = t0 + LINR_SELECT_TILE < hi;
-        if (more) N.load(A, i0 + LINR_SELECT_TILE);              // the next tile's loads are in flight meanwhile
-        for (uint32_t qi = 0; qi < nqb; ++qi) {
-            const SelectFilter C = Cs[qi];
-            u64 q[W];
-#pragma unroll
-            for (int w = 0; w < W; ++w) q[w] = qs[qi][w];
-            uint32_t diff[4];
-            T.eval(A, A.filters + b0 + qi, C, q, i0, diff);
-            uint32_t packed = 0;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                if (diff[r] != 0xFFFFFFFFu) atomicAdd(&h[qi][threadIdx.x & 3][diff[r]], 1u);
-                packed |= (diff[r] & 0xFFu) << (8 * r);
-            }
-            // (the segments are whole tiles: the cache is padded to them)
-            if (A.dcache) __builtin_nontemporal_store(packed, (uint32_t*)(A.dcache + (u64)(b0 + qi) * row + i0));
-        }
-        if (more) T = N;
-    }
-    __syncthreads();
-    for (uint32_t j = threadIdx.x; j < nqb * bins; j += 256) {
-        const uint32_t qi = j / bins, d = j % bins;
-        const uint32_t c = h[qi][0][d] + h[qi][1][d] + h[qi][2][d] + h[qi][3][d];
-        A.seg_hist[((u64)(b0 + qi) * A.n_seg + seg) * bins + d] = c;
-        if (c) atomicAdd(&A.hist[(u64)(b0 + qi) * LINR_SELECT_BINS + d], (unsigned long long)c);
-    }
-}
-
-// the cut, and per segment the number of items below it and on it: grid (segments / 256, queries)
-__global__ void __launch_bounds__(256) select_cut_kernel(linr_select_args A)
-{
-    __shared__ uint32_t s_t;
-    const uint32_t b = blockIdx.y, bins = A.k_bits + 1;
-    if (threadIdx.x == 0) {
-        const unsigned long long* H = A.hist + (u64)b * LINR_SELECT_BINS;
-        u64 cum = 0, need = 0, n_gt = 0;
-        uint32_t t = 0xFFFFFFFFu, last = 0xFFFFFFFFu;
-        for (uint32_t d = 0; d < bins; ++d) {
-            if (H[d] == 0) continue;
-            last = d;
-            if (cum + H[d] >= A.K) { t = d; n_gt = cum; need = A.K - cum; break; }
-            cum += H[d];
-        }
-        if (t == 0xFFFFFFFFu && last != 0xFFFFFFFFu) {        // fewer than K feasible items: all of them
-            t = last; n_gt = cum - H[last]; need = H[last];
-        }
-        s_t = t;
-        if (blockIdx.x == 0) {
-            linr_select_cut c;
-            c.t_diff = t; c.need_eq = need;
-            A.cut[b] = c;
-            A.out_counts[b] = t == 0xFFFFFFFFu ? 0ull : n_gt + need;
-            A.out_thresholds[b] = t == 0xFFFFFFFFu ? -1 : (int32_t)(A.k_bits - t);
-        }
-    }
-    __syncthreads();
-    const uint32_t t = s_t, seg = blockIdx.x * 256 + threadIdx.x;
-    if (seg >= A.n_seg) return;
-    u64 g = 0, e = 0;
-    if (t != 0xFFFFFFFFu) {
-        const uint32_t* row = A.seg_hist + ((u64)b * A.n_seg + seg) * bins;
-        for (uint32_t d = 0; d < t; ++d) g += row[d];
-        e = row[t];
-    }
-    A.gt_base[(u64)b * A.n_seg + seg] = g; A.eq_base[(u64)b * A.n_seg + seg] = e;
-}
-
-// the segments' counts -> output offsets (exclusive prefix sums, in place): one workgroup of 1024 lanes per query
-__global__ void __launch_bounds__(1024) select_scan_kernel(linr_select_args A)
-{
-    __shared__ u64 part_gt[1024], part_eq[1024];
-    const uint32_t b = blockIdx.x;
-    unsigned long long* G = A.gt_base + (u64)b * A.n_seg;
-    unsigned long long* E = A.eq_base + (u64)b * A.n_seg;
-    const uint32_t per = (A.n_seg + 1023u) / 1024u;
-    const uint32_t s0 = threadIdx.x * per, s1 = s0 + per < A.n_seg ? s0 + per : A.n_seg;
-    u64 g = 0, e = 0;
-    for (uint32_t sgm = s0; sgm < s1; ++sgm) { g += G[sgm]; e += E[sgm]; }
-    part_gt[threadIdx.x] = g; part_eq[threadIdx.x] = e;
-    __syncthreads();
-    for (uint32_t st = 1; st < 1024; st <<= 1) {              // inclusive scan of the 1024 partial sums
-        const u64 ag = threadIdx.x >= st ? part_gt[threadIdx.x - st] : 0ull, ae = threadIdx.x >= st ? part_eq[threadIdx.x - st] : 0ull;
-        __syncthreads();
-        part_gt[threadIdx.x] += ag; part_eq[threadIdx.x] += ae;
-        __syncthreads();
-    }
-    u64 bg = part_gt[threadIdx.x] - g, be = part_eq[threadIdx.x] - e;      // exclusive
-    for (uint32_t sgm = s0; sgm < s1; ++sgm) {
-        const u64 cg = G[sgm], ce = E[sgm];
-        G[sgm] = bg; E[sgm] = be;
-        bg += cg; be += ce;
-    }
-}
-
-// pass 2: grid (segments, queries); ids of the selected items to out_ids[b][position], positions ascending with the id
-template <int W, bool TS>
-__global__ void __launch_bounds__(256) select_write_kernel(linr_select_args A)
-{
-    __shared__ uint32_t wave_tot[4];
-    const uint32_t b = blockIdx.y, seg = blockIdx.x;
-    const linr_select_cut cut = A.cut[b];
-    if (cut.t_diff == 0xFFFFFFFFu) return;
-    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-    SelectFilter C;
-    C.set(A.filters[b], A.dead_bit);
-    u64 q[W];
-#pragma unroll
-    for (int w = 0; w < W; ++w) q[w] = A.q_codes[(u64)b * W + w];
-    u64 run_gt = A.gt_base[(u64)b * A.n_seg + seg], run_eq = A.eq_base[(u64)b * A.n_seg + seg];
-    const u64 need = cut.need_eq;
-    uint32_t* out = A.out_ids + (u64)b * A.K;
-    const u64 lo = (u64)seg * A.seg_items;
-    const u64 hi = lo + A.seg_items < A.n ? lo + A.seg_items : A.n;
-    for (u64 t0 = lo; t0 < hi; t0 += LINR_SELECT_TILE) {
-        SelectTile<W, TS> T;
-        const u64 i0 = t0 + 4 * threadIdx.x;
-        T.load(A, i0);
-        uint32_t diff[4];
-        T.eval(A, A.filters + b, C, q, i0, diff);
-        uint32_t cg = 0, ce = 0;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) { cg += diff[r] < cut.t_diff ? 1u : 0u; ce += diff[r] == cut.t_diff ? 1u : 0u; }
-        // exclusive scan over the 256 lanes of (ties << 16 | better): wave by shuffles, waves through LDS
-        const uint32_t mine = (ce << 16) | cg;
-        uint32_t inc = mine;
-#pragma unroll
-        for (int st = 1; st < 64; st <<= 1) {
-            const uint32_t o = __shfl_up(inc, st);
-            if (lane >= st) inc += o;
-        }
-        if (lane == 63) wave_tot[wib] = inc;
-        __syncthreads();
-        uint32_t before = inc - mine, total = 0;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) { if (v < wib) before += wave_tot[v]; total += wave_tot[v]; }
-        __syncthreads();
-        u64 g_before = run_gt + (before & 0xFFFFu), e_before = run_eq + (before >> 16);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const bool better = diff[r] < cut.t_diff, tie = diff[r] == cut.t_diff;
-            if (better || (tie && e_before < need))
-                out[g_before + (e_before < need ? e_before : need)] = (uint32_t)(i0 + r) + A.id_base;
-            g_before += better ? 1u : 0u; e_before += tie ? 1u : 0u;
-        }
-        run_gt += total & 0xFFFFu; run_eq += total >> 16;
-    }
-}
-
-// ---------------------------------------------------------------------------
 // live updates (LiNR Sec. 4 "Model Live Update"): rows and side columns of `count` slots, 8 bytes per thread
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) upsert_kernel(linr_upsert_args A)
@@ -3464,96 +3136,6 @@ hipError_t linr_launch_prefilter(const linr_prefilter_args& a_in, hipStream_t s)
 hipError_t linr_launch_prefilter_overflow(const uint32_t* vcnt, uint64_t capacity, uint32_t* out_counts, uint32_t nq, hipStream_t s)
 {
     hipLaunchKernelGGL(prefilter_overflow_kernel, dim3(1), dim3(64), 0, s, vcnt, capacity, out_counts, nq);
-    return hipGetLastError();
-}
-
-// pass 2 over the kept byte per item: 16 items per lane and step
-__global__ void __launch_bounds__(256) select_write_cached_kernel(linr_select_args A)
-{
-    __shared__ uint32_t wave_tot[4];
-    const uint32_t b = blockIdx.y, seg = blockIdx.x;
-    const linr_select_cut cut = A.cut[b];
-    if (cut.t_diff == 0xFFFFFFFFu) return;
-    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-    u64 run_gt = A.gt_base[(u64)b * A.n_seg + seg], run_eq = A.eq_base[(u64)b * A.n_seg + seg];
-    const u64 need = cut.need_eq;
-    uint32_t* out = A.out_ids + (u64)b * A.K;
-    const uint8_t* dc = A.dcache + (u64)b * A.n_seg * A.seg_items;
-    const u64 lo = (u64)seg * A.seg_items;
-    const u64 hi = lo + A.seg_items < A.n ? lo + A.seg_items : A.n;
-    for (u64 t0 = lo; t0 < hi; t0 += 16 * 256) {
-        const u64 i0 = t0 + 16 * threadIdx.x;
-        v4i raw = {-1, -1, -1, -1};
-        if (i0 < hi) raw = __builtin_nontemporal_load((const v4i*)(dc + i0));
-        uint32_t better = 0, tie = 0;                 // one bit per item of the lane
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const uint32_t d = ((uint32_t)raw[r >> 2] >> (8 * (r & 3))) & 0xFFu;
-            const bool in = i0 + r < hi && d != 0xFFu;
-            better |= (in && d < cut.t_diff ? 1u : 0u) << r;
-            tie |= (in && d == cut.t_diff ? 1u : 0u) << r;
-        }
-        const uint32_t mine = ((uint32_t)__popc(tie) << 16) | (uint32_t)__popc(better);
-        uint32_t inc = mine;
-#pragma unroll
-        for (int st = 1; st < 64; st <<= 1) {
-            const uint32_t o = __shfl_up(inc, st);
-            if (lane >= st) inc += o;
-        }
-        if (lane == 63) wave_tot[wib] = inc;
-        __syncthreads();
-        uint32_t before = inc - mine, total = 0;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) { if (v < wib) before += wave_tot[v]; total += wave_tot[v]; }
-        __syncthreads();
-        u64 g_before = run_gt + (before & 0xFFFFu), e_before = run_eq + (before >> 16);
-        uint32_t todo = better | tie;
-        while (todo) {
-            const int r = __builtin_ctz(todo);
-            todo &= todo - 1u;
-            const uint32_t below = (1u << r) - 1u;
-            const u64 g = g_before + (uint32_t)__popc(better & below), e = e_before + (uint32_t)__popc(tie & below);
-            if (((better >> r) & 1u) || e < need) out[g + (e < need ? e : need)] = (uint32_t)(i0 + r) + A.id_base;
-        }
-        run_gt += total & 0xFFFFu; run_eq += total >> 16;
-    }
-}
-
-template <int W>
-static void select_launch(const linr_select_args& a, int pass, hipStream_t s)
-{
-    const dim3 grid(a.n_seg, a.B), block(256);
-    if (pass == 0) {
-        const dim3 grid1(a.n_seg, (a.B + LINR_SELECT_QB - 1) / LINR_SELECT_QB);
-        if (a.ts) hipLaunchKernelGGL((select_hist_kernel<W, true>), grid1, block, 0, s, a);
-        else hipLaunchKernelGGL((select_hist_kernel<W, false>), grid1, block, 0, s, a);
-    } else if (a.dcache) {
-        hipLaunchKernelGGL(select_write_cached_kernel, grid, block, 0, s, a);
-    } else {
-        if (a.ts) hipLaunchKernelGGL((select_write_kernel<W, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((select_write_kernel<W, false>), grid, block, 0, s, a);
-    }
-}
-
-// large-K selection: counts, cut, ids.  `hist` must be zero.
-hipError_t linr_launch_select(const linr_select_args& a, hipStream_t s)
-{
-    if (a.B == 0 || a.B > 65535u || a.n == 0 || a.K == 0 || a.k_bits == 0 || a.k_bits + 1 > LINR_SELECT_BINS ||
-        a.seg_items == 0 || a.seg_items % 4096 != 0 || a.seg_items > 65536 ||
-        a.n_seg != (uint32_t)((a.n + a.seg_items - 1) / a.seg_items) ||
-        (a.words != 1 && a.words != 2 && a.words != 4) || a.k_bits > 64 * a.words || (a.dcache && a.k_bits > 254) ||
-        (((uintptr_t)a.dcache) & 15u))
-        return hipErrorInvalidValue;
-    if ((((uintptr_t)a.bits) | ((uintptr_t)a.mask) | ((uintptr_t)a.ts)) & 15u) return hipErrorInvalidValue;
-    for (int pass = 0; pass < 2; ++pass) {
-        if (a.words == 1) select_launch<1>(a, pass, s);
-        else if (a.words == 2) select_launch<2>(a, pass, s);
-        else select_launch<4>(a, pass, s);
-        if (pass == 0) {
-            hipLaunchKernelGGL(select_cut_kernel, dim3((a.n_seg + 255) / 256, a.B), dim3(256), 0, s, a);
-            hipLaunchKernelGGL(select_scan_kernel, dim3(a.B), dim3(1024), 0, s, a);
-        }
-    }
     return hipGetLastError();
 }
 
