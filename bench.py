@@ -37,7 +37,7 @@ MEASURED_TRAFFIC_BYTES = {(1_000_000_000, 32, "5%", 1000): 63_022_224_384}
 # the same for the largest sweep of the 1-bit search at B = 1, keyed by (N, code bits, pass rate, k):
 # 5,127,353 KiB fetched x 2.000 + 450 KiB written (profiles/scan_kernel_bits_1e9_B1.md)
 # FETCH_SIZE + WRITE_SIZE of the selection's kernels, (N, code bits, K) -> bytes per call (profiles/select_kernels_1e9_top50M.md)
-MEASURED_SELECT_TRAFFIC_BYTES = {(1_000_000_000, 64, 50_000_000): 14_783_381_504}
+MEASURED_SELECT_TRAFFIC_BYTES = {(1_000_000_000, 64, 50_000_000): 10_244_115_456}
 MEASURED_BITS_TRAFFIC_BYTES = {(1_000_000_000, 64, "5%", 1000): 10_501_279_181}
 
 
@@ -174,7 +174,8 @@ def quantised_leg(L, S, base, index_cols, N, k, args, dev):
     e1.record()
     torch.cuda.synchronize()
     sel_ms = e0.elapsed_time(e1) / args.steps
-    sel_bytes = N * (bpi + 2) + 4 * K if kb <= 254 else 2 * N * bpi + 4 * K     # a byte per item kept between the passes
+    # a byte per item kept between the passes; a pass-all filter needs no mask column
+    sel_bytes = N * (8 * W + 2) + 4 * K if kb <= 254 else 2 * N * 8 * W + 4 * K
     out["selection"] = dict(workload=f"top {K} of {N} items by matching bits ({kb}-bit codes), one query, pass-all filter",
                             K=K, ms_per_step=sel_ms, items_per_s=N / sel_ms * 1e3, selected=int(sel_cnt.item()),
                             threshold_bits=int(sel_thr.item()),

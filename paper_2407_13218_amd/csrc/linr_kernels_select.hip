@@ -32,11 +32,15 @@ template <int W, bool TS>
 struct SelectTile {
     uint32_t mk[4], tv[4];             // the lane's four neighbouring items: masks, timestamps, codes
     u64 x[4][W];
-    __device__ __forceinline__ void load(const linr_select_args& A, u64 i0)
+    // with_mask == false (uniform): no query looks at the attributes, the mask column is not read
+    __device__ __forceinline__ void load(const linr_select_args& A, u64 i0, bool with_mask = true)
     {
         if (i0 + 4 <= A.n) {
-            const v4i m4 = __builtin_nontemporal_load((const v4i*)(A.mask + i0));
-            mk[0] = (uint32_t)m4[0]; mk[1] = (uint32_t)m4[1]; mk[2] = (uint32_t)m4[2]; mk[3] = (uint32_t)m4[3];
+            mk[0] = mk[1] = mk[2] = mk[3] = 0u;
+            if (with_mask) {
+                const v4i m4 = __builtin_nontemporal_load((const v4i*)(A.mask + i0));
+                mk[0] = (uint32_t)m4[0]; mk[1] = (uint32_t)m4[1]; mk[2] = (uint32_t)m4[2]; mk[3] = (uint32_t)m4[3];
+            }
             if (TS) {
                 const v4i t4 = __builtin_nontemporal_load((const v4i*)(A.ts + i0));
                 tv[0] = (uint32_t)t4[0]; tv[1] = (uint32_t)t4[1]; tv[2] = (uint32_t)t4[2]; tv[3] = (uint32_t)t4[3];
@@ -54,7 +58,7 @@ struct SelectTile {
             for (int r = 0; r < 4; ++r) {
                 const bool in = i0 + r < A.n;
                 const u64 ic = in ? i0 + r : A.n - 1;
-                mk[r] = in ? A.mask[ic] : 0u;
+                mk[r] = in && with_mask ? A.mask[ic] : 0u;
                 tv[r] = TS ? A.ts[ic] : 0u;
 #pragma unroll
                 for (int w = 0; w < W; ++w) x[r][w] = A.bits[ic * W + w];
@@ -97,25 +101,30 @@ __global__ void __launch_bounds__(256) select_hist_kernel(linr_select_args A)
     __shared__ uint32_t h[LINR_SELECT_QB][4][HB];    // four copies per query (lane % 4): match counts cluster
     __shared__ SelectFilter Cs[LINR_SELECT_QB];
     __shared__ u64 qs[LINR_SELECT_QB][W];
+    __shared__ uint32_t s_need_mask;
     const uint32_t b0 = blockIdx.y * LINR_SELECT_QB, seg = blockIdx.x, bins = A.k_bits + 1;
     const uint32_t nqb = A.B - b0 < (uint32_t)LINR_SELECT_QB ? A.B - b0 : (uint32_t)LINR_SELECT_QB;
     for (uint32_t j = threadIdx.x; j < LINR_SELECT_QB * 4 * HB; j += 256) (&h[0][0][0])[j] = 0u;
+    if (threadIdx.x == 0) s_need_mask = 0u;
+    __syncthreads();
     if (threadIdx.x < nqb) {
         SelectFilter c;
         c.set(A.filters[b0 + threadIdx.x], A.dead_bit);
         Cs[threadIdx.x] = c;
+        if (c.care != 0u || c.must != 0u || c.any) atomicOr(&s_need_mask, 1u);      // (must != 0 with care == 0: nothing passes)
         for (int w = 0; w < W; ++w) qs[threadIdx.x][w] = A.q_codes[(u64)(b0 + threadIdx.x) * W + w];
     }
     __syncthreads();
     const u64 lo = (u64)seg * A.seg_items;
     const u64 hi = lo + A.seg_items < A.n ? lo + A.seg_items : A.n;
     const u64 row = (u64)A.n_seg * A.seg_items;                      // bytes of one query's kept counts
+    const bool with_mask = s_need_mask != 0u;         // a pass-all group (the notification use case) reads the codes only
     SelectTile<W, TS> T, N;
-    if (lo < hi) T.load(A, lo + 4 * threadIdx.x);
+    if (lo < hi) T.load(A, lo + 4 * threadIdx.x, with_mask);
     for (u64 t0 = lo; t0 < hi; t0 += LINR_SELECT_TILE) {
         const u64 i0 = t0 + 4 * threadIdx.x;
         const bool more = t0 + LINR_SELECT_TILE < hi;
-        if (more) N.load(A, i0 + LINR_SELECT_TILE);              // the next tile's loads are in flight meanwhile
+        if (more) N.load(A, i0 + LINR_SELECT_TILE, with_mask);   // the next tile's loads are in flight meanwhile
         for (uint32_t qi = 0; qi < nqb; ++qi) {
             const SelectFilter C = Cs[qi];
             u64 q[W];
