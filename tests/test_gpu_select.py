@@ -37,7 +37,9 @@ def run_case(oracle_mod, codes, k_bits, mask, ts, qbits, filt, K, label, host_fi
 
 @pytest.mark.parametrize("n,k_bits,B,K,with_ts", [
     (1, 64, 1, 1, False), (5, 64, 2, 3, True),
-    (100_000, 64, 1, 33_333, False), (100_001, 128, 1, 5, True),          # one pass-all query: the mask column is skipped (1000, 64, 7, 100, False), (4099, 16, 3, 2000, True),
+    # one pass-all query: the mask column is skipped
+    (100_000, 64, 1, 33_333, False), (100_001, 128, 1, 5, True),
+    (1000, 64, 7, 100, False), (4099, 16, 3, 2000, True),
     (65_536, 64, 2, 30_000, False), (65_537, 64, 2, 65_537, False), (200_003, 128, 5, 77_777, True),
     (300_000, 256, 3, 150_000, False), (131_072, 200, 2, 1000, False), (1_000_000, 64, 13, 50_000, True)])
 def test_selection_matches_the_stable_sort(oracle_mod, n, k_bits, B, K, with_ts):
