@@ -138,6 +138,36 @@ def test_bits_search_few_levels_many_ties(oracle_mod):
             L.set_tuning()
 
 
+def verify_second_stage(oracle_mod, dtype, x, mask, q, f, oi1, oc1, k, ids, sc, cnt):
+    """ids / sc / cnt of a two-stage search against the oracle's candidates (oi1 [B, T], oc1 [B]): the 1e-3 rule among
+    the candidates, order, uniqueness, padding"""
+    B = q.shape[0]
+    # second stage: 1e-3 rule among the candidates
+    rtol, atol = 1e-3, 1e-6
+    for b in range(B):
+        c = int(oc1[b]); kk = min(k, c)
+        assert cnt[b] == kk, f"q{b}: count {cnt[b]} vs {kk}"
+        assert np.all(ids[b, kk:] == S.NO_ID) and np.all(np.isneginf(sc[b, kk:]))
+        if kk == 0:
+            continue
+        cand = oi1[b, :c].astype(np.uint64)
+        rank, _, feas = oracle_mod.pairs(dtype, x, mask, q[:, None, :], f, np.full(c, b, np.uint32), cand)
+        assert feas.all()
+        exact = dict(zip(cand.tolist(), rank.tolist()))
+        got = ids[b, :kk].tolist()
+        assert len(set(got)) == kk and set(got) <= set(cand.tolist()), f"q{b}: ids outside the candidate set"
+        err = np.abs(sc[b, :kk].astype(np.float64) - np.array([exact[i] for i in got]))
+        assert np.all(err <= rtol * np.abs(sc[b, :kk]) + atol), f"q{b}: score error {err.max()}"
+        assert np.all(np.diff(sc[b, :kk]) <= 0)
+        same = np.diff(sc[b, :kk]) == 0
+        assert np.all(np.diff(np.array(got, np.int64))[same] > 0)
+        order = np.lexsort((cand, -rank))
+        tau = rank[order][kk - 1]; band = rtol * abs(tau) + atol
+        must = set(cand[order][rank[order] > tau + band].tolist())
+        assert must <= set(got), f"q{b}: clearly better candidates missing"
+        assert all(exact[i] >= tau - band for i in got), f"q{b}: returned a candidate below the band"
+
+
 @pytest.mark.parametrize("dtype,d,k_bits,T,k", [(S.F32, 64, 64, 400, 50), (S.BF16, 128, 64, 1000, 100), (S.F32, 64, 64, 2048, 2048),
                                                 (S.BF16, 64, 64, 8192, 3000),
                                                 # more candidates than a ranking holds: selection + candidate scoring
@@ -186,30 +216,7 @@ def test_two_stage_against_the_oracle(oracle_mod, dtype, d, k_bits, T, k, rank_m
         for b in range(B):
             assert int(c1[b]) == int(oc1[b])
             assert np.array_equal(i1[b, :int(c1[b])], np.sort(oi1[b, :int(oc1[b])]))
-    # second stage: 1e-3 rule among the candidates
-    rtol, atol = 1e-3, 1e-6
-    for b in range(B):
-        c = int(oc1[b]); kk = min(k, c)
-        assert cnt[b] == kk, f"q{b}: count {cnt[b]} vs {kk}"
-        assert np.all(ids[b, kk:] == S.NO_ID) and np.all(np.isneginf(sc[b, kk:]))
-        if kk == 0:
-            continue
-        cand = oi1[b, :c].astype(np.uint64)
-        rank, _, feas = oracle_mod.pairs(dtype, x, mask, q[:, None, :], f, np.full(c, b, np.uint32), cand)
-        assert feas.all()
-        exact = dict(zip(cand.tolist(), rank.tolist()))
-        got = ids[b, :kk].tolist()
-        assert len(set(got)) == kk and set(got) <= set(cand.tolist()), f"q{b}: ids outside the candidate set"
-        err = np.abs(sc[b, :kk].astype(np.float64) - np.array([exact[i] for i in got]))
-        assert np.all(err <= rtol * np.abs(sc[b, :kk]) + atol), f"q{b}: score error {err.max()}"
-        assert np.all(np.diff(sc[b, :kk]) <= 0)
-        same = np.diff(sc[b, :kk]) == 0
-        assert np.all(np.diff(np.array(got, np.int64))[same] > 0)
-        order = np.lexsort((cand, -rank))
-        tau = rank[order][kk - 1]; band = rtol * abs(tau) + atol
-        must = set(cand[order][rank[order] > tau + band].tolist())
-        assert must <= set(got), f"q{b}: clearly better candidates missing"
-        assert all(exact[i] >= tau - band for i in got), f"q{b}: returned a candidate below the band"
+    verify_second_stage(oracle_mod, dtype, x, mask, q, f, oi1, oc1, k, ids, sc, cnt)
     ix.close()
 
 

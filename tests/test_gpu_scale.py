@@ -375,3 +375,35 @@ def test_large_k_selection_full_size(oracle_mod):
         say(f"top {K:,} of {N_FULL:,}: identical to the oracle's")
         del ids, got, want_ids
     ix.close()
+
+
+def test_two_stage_full_size(oracle_mod):
+    """The two-stage leg bench.py times (Sec. 3.2 / the trade-off figure of Sec. 5.3): config 2 at full size (1e7 x d128
+    bf16, 25 % pass rate), 128-bit codes, B = 16, k = 100, T = 4000 and T = 1 % of the items.  The oracle's codes of
+    all items (made piece by piece), its candidates, and the 1e-3 rule for the second stage among them."""
+    import torch
+    import paper_2407_13218_amd as L
+    from test_gpu_bits import verify_second_stage
+    B, k, kb, d = 16, 100, 128, 128
+    w = S.config2(device="cuda", B=B, k=k, p=0.5)
+    n = w["emb"].shape[0]
+    ix = L.Index(n, d, S.BF16, 0)
+    ix.load(w["emb"], w["mask"])
+    perm, signs = S.oporp_draw(d, 0)
+    ix.build_bits(perm, signs, kb)
+    Q = w["Q"].reshape(B, d).contiguous()
+    x_h = w["emb"].cpu().numpy().view(np.uint16)
+    mask_h = w["mask"].cpu().numpy().view(np.uint32)
+    q_h = Q.cpu().numpy().view(np.uint16)
+    f = w["filters"]
+    bits = np.concatenate([oracle_mod.sign_oporp(S.BF16, x_h[p0:p0 + 1_000_000], perm, signs, kb) for p0 in range(0, n, 1_000_000)])
+    qbits = oracle_mod.sign_oporp(S.BF16, q_h, perm, signs, kb)
+    say("oracle codes of all items built")
+    for T in (4000, n // 100):
+        ids, sc, cnt = ix.search_two_stage(Q, f, T, k)
+        torch.cuda.synchronize()
+        oi1, _, oc1 = oracle_mod.bits_search(bits, kb, mask_h, qbits, f, T)
+        verify_second_stage(oracle_mod, S.BF16, x_h, mask_h, q_h, f, oi1, oc1, k, ids.cpu().numpy().view(np.uint32),
+                            sc.cpu().numpy(), cnt.cpu().numpy().view(np.uint32))
+        say(f"two-stage T = {T}: candidates and second stage agree with the oracle")
+    ix.close()
