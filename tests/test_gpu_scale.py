@@ -43,6 +43,12 @@ def test_config5_full_size_matches_oracle(oracle_mod):
         torch.cuda.synchronize()
         runs[sel] = (w, ids.cpu().numpy().view(np.uint32), sc.cpu().numpy(), raw.cpu().numpy(), cnt.cpu().numpy().view(np.uint32))
         say(f"GPU search done for pass rate {sel}")
+        if sel == "0.1%":                       # the same batch by explicit pre-filtering (three phases at this size)
+            ids, sc, raw, cnt = ix.search(w["Q"], w["filters"], k, q_scale=w["q_scale"], prefilter=True)
+            torch.cuda.synchronize()
+            runs["0.1% by pre-filtering"] = (w, ids.cpu().numpy().view(np.uint32), sc.cpu().numpy(), raw.cpu().numpy(),
+                                             cnt.cpu().numpy().view(np.uint32))
+            say("GPU search by pre-filtering done")
 
     # (a) every returned pair, one by one
     for sel, (w, ids, sc, raw, cnt) in runs.items():
@@ -66,7 +72,7 @@ def test_config5_full_size_matches_oracle(oracle_mod):
         say(f"{sel}: all {B * k} returned pairs re-scored by the oracle: exact")
 
     # (b) full oracle scan for two queries of each batch, streamed
-    picks = [("5%", 0), ("5%", 17), ("0.1%", 3), ("0.1%", 30)]
+    picks = [("5%", 0), ("5%", 17), ("0.1%", 3), ("0.1%", 30), ("0.1% by pre-filtering", 3), ("0.1% by pre-filtering", 30)]
     Qs = np.stack([runs[s][0]["Q"][b].cpu().numpy() for s, b in picks])                  # [4, 1, 64]
     qsc = np.array([runs[s][0]["q_scale"][b].item() for s, b in picks], np.float32)
     filt = np.stack([runs[s][0]["filters"][b] for s, b in picks]).astype(S.FILTER_DTYPE)
