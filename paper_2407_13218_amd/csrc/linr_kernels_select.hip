@@ -291,13 +291,23 @@ __global__ void __launch_bounds__(256) select_write_cached_kernel(linr_select_ar
         const u64 i0 = t0 + 16 * threadIdx.x;
         v4i raw = {-1, -1, -1, -1};
         if (i0 < hi) raw = __builtin_nontemporal_load((const v4i*)(dc + i0));
-        uint32_t better = 0, tie = 0;                 // one bit per item of the lane
+        if (i0 < hi && i0 + 16 > hi) {                // the index's last bytes: what lies beyond counts as infeasible
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const uint32_t d = ((uint32_t)raw[r >> 2] >> (8 * (r & 3))) & 0xFFu;
-            const bool in = i0 + r < hi && d != 0xFFu;
-            better |= (in && d < cut.t_diff ? 1u : 0u) << r;
-            tie |= (in && d == cut.t_diff ? 1u : 0u) << r;
+            for (int r = 0; r < 16; ++r)
+                if (i0 + r >= hi) raw[r >> 2] |= (int)(0xFFu << (8 * (r & 3)));
+        }
+        // four bytes at a time: bit 7 of a byte of `lt` / `eq` says "fewer differing bits than the cut" / "as many"
+        // (0xFF, infeasible, is neither: the cut is at most 254); then one bit per item of the lane
+        uint32_t better = 0, tie = 0;
+        const uint32_t t4 = cut.t_diff * 0x01010101u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t w = (uint32_t)raw[j], x = w ^ t4;
+            const uint32_t eq = ((((x & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | x) & 0x80808080u) ^ 0x80808080u;
+            const uint32_t s7 = (w | 0x80808080u) - (t4 & 0x7F7F7F7Fu);
+            const uint32_t lt = ((~w & t4) | (~x & ~s7)) & 0x80808080u;
+            better |= ((((lt >> 7) & 0x01010101u) * 0x10204080u) >> 28) << (4 * j);
+            tie |= ((((eq >> 7) & 0x01010101u) * 0x10204080u) >> 28) << (4 * j);
         }
         const uint32_t mine = ((uint32_t)__popc(tie) << 16) | (uint32_t)__popc(better);
         uint32_t inc = mine;
