@@ -119,28 +119,38 @@ __global__ void __launch_bounds__(256) select_hist_kernel(linr_select_args A)
     const u64 hi = lo + A.seg_items < A.n ? lo + A.seg_items : A.n;
     const u64 row = (u64)A.n_seg * A.seg_items;                      // bytes of one query's kept counts
     const bool with_mask = s_need_mask != 0u;         // a pass-all group (the notification use case) reads the codes only
+    // one query's counts of a tile: infeasible items go to a spare slot behind the last bin, so that nothing branches
+    uint32_t* mine = &h[0][threadIdx.x & 3][0];
+    auto one_query = [&](const SelectTile<W, TS>& T, u64 i0, uint32_t qi, const SelectFilter& C, const u64* q) {
+        uint32_t diff[4];
+        T.eval(A, A.filters + b0 + qi, C, q, i0, diff);
+        uint32_t packed = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            atomicAdd(&mine[qi * 4 * HB + (diff[r] < (uint32_t)(HB - 1) ? diff[r] : (uint32_t)(HB - 1))], 1u);
+            packed |= (diff[r] & 0xFFu) << (8 * r);
+        }
+        // (the segments are whole tiles: the cache is padded to them)
+        if (A.dcache) __builtin_nontemporal_store(packed, (uint32_t*)(A.dcache + (u64)(b0 + qi) * row + i0));
+    };
+    const SelectFilter C0 = Cs[0];
+    u64 q0[W];
+#pragma unroll
+    for (int w = 0; w < W; ++w) q0[w] = qs[0][w];
     SelectTile<W, TS> T, N;
     if (lo < hi) T.load(A, lo + 4 * threadIdx.x, with_mask);
     for (u64 t0 = lo; t0 < hi; t0 += LINR_SELECT_TILE) {
         const u64 i0 = t0 + 4 * threadIdx.x;
         const bool more = t0 + LINR_SELECT_TILE < hi;
         if (more) N.load(A, i0 + LINR_SELECT_TILE, with_mask);   // the next tile's loads are in flight meanwhile
-        for (uint32_t qi = 0; qi < nqb; ++qi) {
-            const SelectFilter C = Cs[qi];
-            u64 q[W];
+        if (nqb == 1) one_query(T, i0, 0u, C0, q0);          // (its filter and code stay in registers)
+        else
+            for (uint32_t qi = 0; qi < nqb; ++qi) {
+                u64 q[W];
 #pragma unroll
-            for (int w = 0; w < W; ++w) q[w] = qs[qi][w];
-            uint32_t diff[4];
-            T.eval(A, A.filters + b0 + qi, C, q, i0, diff);
-            uint32_t packed = 0;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                if (diff[r] != 0xFFFFFFFFu) atomicAdd(&h[qi][threadIdx.x & 3][diff[r]], 1u);
-                packed |= (diff[r] & 0xFFu) << (8 * r);
+                for (int w = 0; w < W; ++w) q[w] = qs[qi][w];
+                one_query(T, i0, qi, Cs[qi], q);
             }
-            // (the segments are whole tiles: the cache is padded to them)
-            if (A.dcache) __builtin_nontemporal_store(packed, (uint32_t*)(A.dcache + (u64)(b0 + qi) * row + i0));
-        }
         if (more) T = N;
     }
     __syncthreads();
