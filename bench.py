@@ -519,11 +519,12 @@ def main():
                 log(f"  sweep B={B:4d} pass {sel:>4}: {r['ms_per_step']:.2f} ms/step  scans {r['all_sweeps_ms']:.2f} ms  "
                     f"{r['hbm_GBs']:.0f} GB/s  {r['int8_TOPs']:.0f} TOP/s  {r['queries_per_s']:.0f} QPS")
 
-    # explicit pre-filtering (Sec. 3.1.2) on the same index, at the pass rate where it pays off
+    # explicit pre-filtering (Sec. 3.1.2) against masking on the same index and queries: where it pays off (few feasible
+    # pairs) and where it does not (the V1-versus-V2 trade-off of Sec. 5.3)
     pre = []
     if not args.no_sweep:
-        for B in (1, 32):
-            wq = prepare(B, "0.1%")
+        for sel, B in (("0.1%", 1), ("0.1%", 32), ("5%", 1), ("5%", 32), ("50%", 1)):
+            wq = prepare(B, sel)
             nb = L.search_prefilter_workspace_bytes(ix.handle, B, 1, k)
             ws = torch.empty(nb, dtype=torch.uint8, device=dev)
             o = (torch.empty((B, k), dtype=torch.int32, device=dev), torch.empty((B, k), dtype=torch.float32, device=dev),
@@ -541,10 +542,10 @@ def main():
                 one()
             torch.cuda.synchronize()
             ms = (time.perf_counter() - t0) * 1e3 / args.sweep_steps
-            masking = next(r["ms_per_step"] for r in sweep if r["B"] == B and r["selectivity"] == "0.1%")
-            pre.append(dict(B=B, selectivity="0.1%", prefilter_ms_per_step=round(ms, 4), masking_ms_per_step=masking,
+            masking = next(r["ms_per_step"] for r in sweep if r["B"] == B and r["selectivity"] == sel)
+            pre.append(dict(B=B, selectivity=sel, prefilter_ms_per_step=round(ms, 4), masking_ms_per_step=masking,
                             overflow=int((o[3] == -1).sum().item()), min_count=int(o[3].min().item())))
-            log(f"  pre-filtering B={B:2d} pass 0.1%: {ms:.3f} ms/step (masking {masking:.3f} ms/step)")
+            log(f"  pre-filtering B={B:2d} pass {sel:>4}: {ms:.3f} ms/step (masking {masking:.3f} ms/step)")
             del ws
 
     quant = None

@@ -43,12 +43,16 @@ def test_config5_full_size_matches_oracle(oracle_mod):
         torch.cuda.synchronize()
         runs[sel] = (w, ids.cpu().numpy().view(np.uint32), sc.cpu().numpy(), raw.cpu().numpy(), cnt.cpu().numpy().view(np.uint32))
         say(f"GPU search done for pass rate {sel}")
-        if sel == "0.1%":                       # the same batch by explicit pre-filtering (three phases at this size)
-            ids, sc, raw, cnt = ix.search(w["Q"], w["filters"], k, q_scale=w["q_scale"], prefilter=True)
-            torch.cuda.synchronize()
-            runs["0.1% by pre-filtering"] = (w, ids.cpu().numpy().view(np.uint32), sc.cpu().numpy(), raw.cpu().numpy(),
-                                             cnt.cpu().numpy().view(np.uint32))
-            say("GPU search by pre-filtering done")
+        # the same batch by explicit pre-filtering (three phases at this size)
+        ids, sc, raw, cnt = ix.search(w["Q"], w["filters"], k, q_scale=w["q_scale"], prefilter=True)
+        torch.cuda.synchronize()
+        pre = (w, ids.cpu().numpy().view(np.uint32), sc.cpu().numpy(), raw.cpu().numpy(), cnt.cpu().numpy().view(np.uint32))
+        say(f"GPU search by pre-filtering done for pass rate {sel}")
+        if sel == "0.1%":
+            runs["0.1% by pre-filtering"] = pre                  # checked against the oracle like the others, below
+        else:                                                    # 1.6e9 feasible pairs: the masking result, which the
+            for a, b in zip(pre[1:], runs[sel][1:]):             # oracle checks below, must come out bit for bit
+                assert a.tobytes() == b.tobytes(), f"{sel}: pre-filtering and masking disagree"
 
     # (a) every returned pair, one by one
     for sel, (w, ids, sc, raw, cnt) in runs.items():
