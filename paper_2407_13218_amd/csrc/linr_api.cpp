@@ -836,21 +836,31 @@ static int prefilter_group(const linr_index& v, const uint32_t* words, const lin
 // Two-stage search with more candidates than a ranking holds (T > LINR_MAX_K; the paper's "keep 1 % of the items"):
 // the candidates come from the large-K selection, their exact scores from the gather-scoring pass of the explicit
 // pre-filtering (candidate lists in place of a predicate), the top k from its merges.
-// workspace: selection | query codes | candidates [B][T] | their counts [B] u64 | thresholds [B] | search workspace
-// of one group of <= 32 queries | 4 KB of counters
+// Queries are served in groups (the selection keeps a byte per item and query, so the group size bounds the
+// workspace): as many as fit 2 GiB of such bytes, at least 8, at most 32.
+// workspace: selection (8 queries) | query codes [B] | candidates [8][T] | their counts [8] u64 | thresholds [8] |
+// search workspace of one group | 4 KB of counters
+static uint32_t two_stage_group(const linr_index* ix, uint32_t B)
+{
+    uint64_t g = ((2ull << 30) / (ix->capacity ? ix->capacity : 1)) & ~7ull;
+    if (g < 8) g = 8;
+    if (g > 32) g = 32;
+    return B < g ? B : (uint32_t)g;
+}
 struct two_stage_large_layout { uint64_t sel, off_q, off_cand, off_cnt, off_thr, off_inner, inner, off_vcnt, total; };
 static int two_stage_large_plan(const linr_index* ix, uint32_t B, uint64_t T, uint32_t k, two_stage_large_layout* L)
 {
     if (k > LINR_MAX_K) return LINR_E_K;
-    int rc = linr_select_bits_workspace_bytes(ix, B, &L->sel);
+    const uint32_t G = two_stage_group(ix, B);
+    int rc = linr_select_bits_workspace_bytes(ix, G, &L->sel);
     if (rc != LINR_OK) return rc;
-    rc = linr_search_workspace_bytes(ix, B < 32 ? B : 32, 1, k, &L->inner);
+    rc = linr_search_workspace_bytes(ix, G, 1, k, &L->inner);
     if (rc != LINR_OK) return rc;
     uint64_t o = align_up(L->sel, 256);
     L->off_q = o; o += align_up((uint64_t)B * ix->bits_words * 8, 256);
-    L->off_cand = o; o += align_up((uint64_t)B * T * 4, 256);
-    L->off_cnt = o; o += align_up((uint64_t)B * 8, 256);
-    L->off_thr = o; o += align_up((uint64_t)B * 4, 256);
+    L->off_cand = o; o += align_up((uint64_t)G * T * 4, 256);
+    L->off_cnt = o; o += align_up((uint64_t)G * 8, 256);
+    L->off_thr = o; o += align_up((uint64_t)G * 4, 256);
     L->off_inner = o; o += align_up(L->inner, 256);
     L->off_vcnt = o; o += 4096;
     L->total = o;
@@ -881,19 +891,21 @@ static int two_stage_large(const linr_index* ix, const void* Q, uint32_t B, cons
     unsigned long long* ccnt = (unsigned long long*)(ws + L.off_cnt);
     rc = linr_quantize_queries(ix, Q, B, qbits, hip_stream);
     if (rc != LINR_OK) return rc;
-    rc = linr_select_bits(ix, qbits, B, filters, T, cand, (uint64_t*)ccnt, (int32_t*)(ws + L.off_thr), ws, L.sel, hip_stream, flags);
-    if (rc != LINR_OK) return rc;
     linr_index v;
     {
         linr_index snap;
         v = *view_for(ix, st, true, &snap);
     }
     v.upd = nullptr;
-    for (uint32_t b0 = 0; b0 < B; b0 += 32) {
-        const uint32_t Bg = (B - b0) < 32 ? (B - b0) : 32;
+    const uint32_t G = two_stage_group(ix, B);
+    for (uint32_t b0 = 0; b0 < B; b0 += G) {
+        const uint32_t Bg = (B - b0) < G ? (B - b0) : G;
+        rc = linr_select_bits(ix, qbits + (uint64_t)b0 * ix->bits_words, Bg, filters + b0, T, cand, (uint64_t*)ccnt,
+                              (int32_t*)(ws + L.off_thr), ws, L.sel, hip_stream, flags);
+        if (rc != LINR_OK) return rc;
         rc = prefilter_group(v, nullptr, nullptr, nullptr, nullptr, 0, (const char*)Q + (uint64_t)b0 * v.row_bytes, nullptr, Bg, 1, k,
                              out_ids + (uint64_t)b0 * k, out_scores + (uint64_t)b0 * k, nullptr, out_counts + b0, ws + L.off_inner,
-                             L.inner, (uint32_t*)(ws + L.off_vcnt), st, cand + (uint64_t)b0 * T, ccnt + b0, T);
+                             L.inner, (uint32_t*)(ws + L.off_vcnt), st, cand, ccnt, T);
         if (rc != LINR_OK) return rc;
     }
     return LINR_OK;

@@ -168,13 +168,15 @@ def verify_second_stage(oracle_mod, dtype, x, mask, q, f, oi1, oc1, k, ids, sc, 
         assert all(exact[i] >= tau - band for i in got), f"q{b}: returned a candidate below the band"
 
 
-@pytest.mark.parametrize("dtype,d,k_bits,T,k", [(S.F32, 64, 64, 400, 50), (S.BF16, 128, 64, 1000, 100), (S.F32, 64, 64, 2048, 2048),
-                                                (S.BF16, 64, 64, 8192, 3000),
-                                                # more candidates than a ranking holds: selection + candidate scoring
-                                                (S.F32, 64, 64, 8193, 100), (S.BF16, 128, 64, 30_000, 2000),
-                                                (S.F32, 64, 64, 40_000, 500), (S.BF16, 256, 128, 20_000, 8192)])
+@pytest.mark.parametrize("dtype,d,k_bits,T,k,B", [(S.F32, 64, 64, 400, 50, 9), (S.BF16, 128, 64, 1000, 100, 9),
+                                                  (S.F32, 64, 64, 2048, 2048, 9), (S.BF16, 64, 64, 8192, 3000, 9),
+                                                  # more candidates than a ranking holds: selection + candidate scoring
+                                                  (S.F32, 64, 64, 8193, 100, 9), (S.BF16, 128, 64, 30_000, 2000, 9),
+                                                  (S.F32, 64, 64, 40_000, 500, 9), (S.BF16, 256, 128, 20_000, 8192, 9),
+                                                  # more queries than one group of the selection path serves
+                                                  (S.F32, 64, 64, 3000, 60, 41)])
 @pytest.mark.parametrize("rank_max", [0, 8192])
-def test_two_stage_against_the_oracle(oracle_mod, dtype, d, k_bits, T, k, rank_max):
+def test_two_stage_against_the_oracle(oracle_mod, dtype, d, k_bits, T, k, B, rank_max):
     """rank_max = 8192 forces the ranking path (candidates ranked by linr_search_bits, re-scoring kernel) for every
     T it can serve; the default takes the selection path from T = 1000 on"""
     import torch
@@ -182,7 +184,7 @@ def test_two_stage_against_the_oracle(oracle_mod, dtype, d, k_bits, T, k, rank_m
     if rank_max and T > L.MAX_K:
         pytest.skip("only the selection path serves this T")
     say(f"two-stage dtype={dtype} d={d} k_bits={k_bits} T={T} k={k} rank_max={rank_max}")
-    n, B = 40_000, 9
+    n = 40_000
     rng = np.random.default_rng(T + k)
     x = float_items(dtype, n, d, 77)
     q = float_items(dtype, B, d, 78)
