@@ -162,13 +162,15 @@ __global__ void __launch_bounds__(256) select_hist_kernel(linr_select_args A)
     }
 }
 
-// the cut, and per segment the number of items below it and on it: grid (segments / 256, queries)
+// the cut, and per segment the number of items below it and on it: grid (segments / 64, queries)
 __global__ void __launch_bounds__(256) select_cut_kernel(linr_select_args A)
 {
     __shared__ uint32_t s_t;
+    __shared__ u64 H[LINR_SELECT_BINS];               // the query's counts, fetched by all lanes at once
     const uint32_t b = blockIdx.y, bins = A.k_bits + 1;
+    for (uint32_t j = threadIdx.x; j < bins; j += 256) H[j] = A.hist[(u64)b * LINR_SELECT_BINS + j];
+    __syncthreads();
     if (threadIdx.x == 0) {
-        const unsigned long long* H = A.hist + (u64)b * LINR_SELECT_BINS;
         u64 cum = 0, need = 0, n_gt = 0;
         uint32_t t = 0xFFFFFFFFu, last = 0xFFFFFFFFu;
         for (uint32_t d = 0; d < bins; ++d) {
@@ -190,15 +192,21 @@ __global__ void __launch_bounds__(256) select_cut_kernel(linr_select_args A)
         }
     }
     __syncthreads();
-    const uint32_t t = s_t, seg = blockIdx.x * 256 + threadIdx.x;
-    if (seg >= A.n_seg) return;
-    u64 g = 0, e = 0;
-    if (t != 0xFFFFFFFFu) {
-        const uint32_t* row = A.seg_hist + ((u64)b * A.n_seg + seg) * bins;
-        for (uint32_t d = 0; d < t; ++d) g += row[d];
-        e = row[t];
+    // a wave per segment: its lanes read the segment's counts side by side
+    const uint32_t t = s_t, lane = threadIdx.x & 63;
+    for (uint32_t seg = blockIdx.x * 64 + (threadIdx.x >> 6); seg < A.n_seg && seg < (blockIdx.x + 1) * 64; seg += 4) {
+        uint32_t g = 0, e = 0;
+        if (t != 0xFFFFFFFFu) {
+            const uint32_t* row = A.seg_hist + ((u64)b * A.n_seg + seg) * bins;
+            for (uint32_t d = lane; d <= t; d += 64) {
+                const uint32_t c = row[d];
+                if (d < t) g += c; else e = c;
+            }
+        }
+#pragma unroll
+        for (int st = 32; st >= 1; st >>= 1) { g += __shfl_xor(g, st); e += __shfl_xor(e, st); }
+        if (lane == 0) { A.gt_base[(u64)b * A.n_seg + seg] = g; A.eq_base[(u64)b * A.n_seg + seg] = e; }
     }
-    A.gt_base[(u64)b * A.n_seg + seg] = g; A.eq_base[(u64)b * A.n_seg + seg] = e;
 }
 
 // the segments' counts -> output offsets (exclusive prefix sums, in place): one workgroup of 1024 lanes per query
@@ -376,7 +384,7 @@ hipError_t linr_launch_select(const linr_select_args& a, hipStream_t s)
         else if (a.words == 2) select_launch<2>(a, pass, s);
         else select_launch<4>(a, pass, s);
         if (pass == 0) {
-            hipLaunchKernelGGL(select_cut_kernel, dim3((a.n_seg + 255) / 256, a.B), dim3(256), 0, s, a);
+            hipLaunchKernelGGL(select_cut_kernel, dim3((a.n_seg + 63) / 64, a.B), dim3(256), 0, s, a);
             hipLaunchKernelGGL(select_scan_kernel, dim3(a.B), dim3(1024), 0, s, a);
         }
     }
