@@ -231,7 +231,9 @@ int linr_search_bits(const linr_index*, const uint64_t* qbits, uint32_t B, const
  * filters / flags / hip_stream as for linr_search_filtered; B <= 65535.  Exact: a match
  * count takes k_bits + 1 values only, so two streaming passes (counts per segment of
  * items, then the ids) replace a sort.  Works on a codes-only index and on
- * the codes built for an fp32 / bf16 index, also next to live updates.
+ * the codes built for an fp32 / bf16 index, also next to live updates.  Workspace: about one
+ * byte per item (of the capacity) and query, plus a few MB of counts; a group of queries
+ * none of which looks at the attributes does not read the mask column.
  */
 int linr_select_bits_workspace_bytes(const linr_index*, uint32_t B, uint64_t* bytes);
 int linr_select_bits(const linr_index*, const uint64_t* qbits, uint32_t B, const linr_filter* filters, uint64_t K,
