@@ -449,6 +449,32 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
     return LINR_OK;
 }
 
+// The plans of one call: every pass but possibly the last serves max_batch queries with `first`; a ragged last
+// pass (B % max_batch queries) is planned for its own size, and that plan can need more workspace than the
+// first (fewer queries per wave means more chunk-slots, each with a segment per query).  Both are made -- and
+// checked against the caller's workspace -- before anything is enqueued.
+struct linr_call_plans {
+    linr_plan first, last;
+    bool ragged;
+    uint64_t bytes;             // workspace the call needs: the larger of the two plans
+};
+
+static int make_call_plans(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, linr_call_plans* cp)
+{
+    int rc = make_plan(ix, B, m, k, &cp->first);
+    if (rc != LINR_OK) return rc;
+    cp->ragged = false;
+    cp->bytes = cp->first.total_bytes;
+    const uint32_t rest = B > cp->first.max_batch ? B % cp->first.max_batch : 0u;
+    if (rest) {
+        rc = make_plan(ix, rest, m, k, &cp->last);
+        if (rc != LINR_OK) return rc;
+        cp->ragged = true;
+        if (cp->last.total_bytes > cp->bytes) cp->bytes = cp->last.total_bytes;
+    }
+    return LINR_OK;
+}
+
 extern "C" int linr_search_workspace_bytes(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, uint64_t* bytes)
 {
     if (!ix || !bytes) return LINR_E_NULL;
@@ -462,10 +488,25 @@ extern "C" int linr_search_workspace_bytes(const linr_index* ix, uint32_t B, uin
         full.upd = nullptr;
         ix = &full;
     }
-    linr_plan p;
-    int rc = make_plan(ix, B, m, k, &p);
+    linr_call_plans cp;
+    int rc = make_call_plans(ix, B, m, k, &cp);
     if (rc != LINR_OK) return rc;
-    *bytes = p.total_bytes;
+    *bytes = cp.bytes;
+    return LINR_OK;
+}
+
+// Workspace of a search that is issued in groups of at most G queries (clause lists, explicit pre-filtering): the
+// larger of what a full group and a ragged last group need.
+static int group_workspace_bytes(const linr_index* ix, uint32_t B, uint32_t G, uint32_t m, uint32_t k, uint64_t* bytes)
+{
+    int rc = linr_search_workspace_bytes(ix, B < G ? B : G, m, k, bytes);
+    if (rc != LINR_OK) return rc;
+    if (B > G && B % G) {
+        uint64_t rest = 0;
+        rc = linr_search_workspace_bytes(ix, B % G, m, k, &rest);
+        if (rc != LINR_OK) return rc;
+        if (rest > *bytes) *bytes = rest;
+    }
     return LINR_OK;
 }
 
@@ -488,10 +529,11 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
     if (B == 0) return LINR_OK;
     if (!Q || !filters || !out_ids || !out_scores || !out_counts) return LINR_E_NULL;
     if (((uintptr_t)Q) & 15u) return LINR_E_SHAPE;
-    linr_plan p;
-    int rc = make_plan(ix, B, m, k, &p);
+    linr_call_plans cp;
+    int rc = make_call_plans(ix, B, m, k, &cp);
     if (rc != LINR_OK) return rc;
-    if (!workspace || (((uintptr_t)workspace) & 255u) || workspace_bytes < p.total_bytes) return LINR_E_WORKSPACE;
+    const linr_plan& p = cp.first;
+    if (!workspace || (((uintptr_t)workspace) & 255u) || workspace_bytes < cp.bytes) return LINR_E_WORKSPACE;
     if (flags & LINR_FILTERS_ON_HOST) {
         for (uint32_t b = 0; b < B; ++b) {
             if (filters[b].n_any > LINR_MAX_ANY) return LINR_E_FILTER;
@@ -514,12 +556,7 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
 
     for (uint32_t b0 = 0; b0 < B; b0 += p.max_batch) {
         const uint32_t Bp = (B - b0) < p.max_batch ? (B - b0) : p.max_batch;
-        linr_plan pp = p;
-        if (Bp != (B < p.max_batch ? B : p.max_batch)) {      // ragged last pass: replan for its size
-            rc = make_plan(ix, Bp, m, k, &pp);
-            if (rc != LINR_OK) return rc;
-            if (pp.total_bytes > workspace_bytes) return LINR_E_WORKSPACE;
-        }
+        const linr_plan& pp = (cp.ragged && Bp != p.max_batch) ? cp.last : p;       // ragged last pass: its own plan
         unsigned long long* tau = (unsigned long long*)(ws + pp.off_tau);
         uint32_t* cnt = (uint32_t*)(ws + pp.off_cnt);
         uint32_t* gcnt = (uint32_t*)(ws + pp.off_gcnt);
@@ -854,7 +891,7 @@ static int two_stage_large_plan(const linr_index* ix, uint32_t B, uint64_t T, ui
     const uint32_t G = two_stage_group(ix, B);
     int rc = linr_select_bits_workspace_bytes(ix, G, &L->sel);
     if (rc != LINR_OK) return rc;
-    rc = linr_search_workspace_bytes(ix, G, 1, k, &L->inner);
+    rc = group_workspace_bytes(ix, B, G, 1, k, &L->inner);
     if (rc != LINR_OK) return rc;
     uint64_t o = align_up(L->sel, 256);
     L->off_q = o; o += align_up((uint64_t)B * ix->bits_words * 8, 256);
@@ -1171,8 +1208,7 @@ extern "C" int linr_index_load_clauses(linr_index* ix, const uint64_t* values, c
 static int clause_layout(const linr_index* v, uint32_t B, uint32_t m, uint32_t k, uint64_t* inner, uint64_t* off_words,
                          uint64_t* off_filters, uint64_t* total)
 {
-    const uint32_t Bg = B < 32 ? B : 32;
-    int rc = linr_search_workspace_bytes(v, Bg, m, k, inner);
+    int rc = group_workspace_bytes(v, B, 32, m, k, inner);
     if (rc != LINR_OK) return rc;
     const uint64_t items = v->dead_bit ? v->capacity : v->n;
     *off_words = align_up(*inner, 256);
@@ -1412,7 +1448,7 @@ extern "C" int linr_search_prefilter_workspace_bytes(const linr_index* ix, uint3
     if (!ix || !bytes) return LINR_E_NULL;
     if (B == 0) { *bytes = 256; return LINR_OK; }
     uint64_t inner = 0;
-    int rc = linr_search_workspace_bytes(ix, B < 32 ? B : 32, m, k, &inner);
+    int rc = group_workspace_bytes(ix, B, 32, m, k, &inner);
     if (rc != LINR_OK) return rc;
     *bytes = align_up(inner, 256) + 4096;
     return LINR_OK;
@@ -1443,7 +1479,7 @@ extern "C" int linr_search_filtered_prefilter(const linr_index* ix, const void* 
             if (filters[b].ts_min > filters[b].ts_max) return LINR_E_FILTER;
         }
     uint64_t inner = 0, total = 0;
-    int rc = linr_search_workspace_bytes(&v, B < 32 ? B : 32, m, k, &inner);
+    int rc = group_workspace_bytes(&v, B, 32, m, k, &inner);
     if (rc != LINR_OK) return rc;
     rc = linr_search_prefilter_workspace_bytes(&v, B, m, k, &total);
     if (rc != LINR_OK) return rc;

@@ -24,60 +24,73 @@ def say(msg):
 
 
 def test_config5_full_size_matches_oracle(oracle_mod):
+    """BASELINE config 5 at 1e9 items, every batch size it lists (1, 32, 256, 1024) at the 5 % pass rate, B = 32 also at
+    50 % and 0.1 % (by masking and by explicit pre-filtering): (a) and (b) of the module docstring for every run."""
     import torch
     import paper_2407_13218_amd as L
 
     free, _ = torch.cuda.mem_get_info()
     if free < N_FULL * 80:
         pytest.skip("not enough free HBM for the full-size index")
-    k, B = 1000, 32
+    k = 1000
     say(f"generating {N_FULL:,} items on the GPU")
-    base = S.config5(device="cuda", n=N_FULL, B=B, k=k, selectivity="5%")
+    base = S.config5(device="cuda", n=N_FULL, B=32, k=k, selectivity="5%")
     cols = (base["emb"], base["scale"], base["mask"])
     ix = L.Index(N_FULL, 64, S.I8, 0)
     ix.load(base["emb"], base["mask"], row_scale=base["scale"])
+
+    def host(ids, sc, raw, cnt):
+        return ids.cpu().numpy().view(np.uint32), sc.cpu().numpy(), raw.cpu().numpy(), cnt.cpu().numpy().view(np.uint32)
     runs = {}
-    for sel in ("5%", "0.1%"):
+    for sel, B in (("5%", 32), ("0.1%", 32), ("50%", 32), ("5%", 1), ("5%", 256), ("5%", 1024), ("0.1%", 256)):
         w = S.config5(device="cuda", n=N_FULL, B=B, k=k, selectivity=sel, index=cols)
         ids, sc, raw, cnt = ix.search(w["Q"], w["filters"], k, q_scale=w["q_scale"])
         torch.cuda.synchronize()
-        runs[sel] = (w, ids.cpu().numpy().view(np.uint32), sc.cpu().numpy(), raw.cpu().numpy(), cnt.cpu().numpy().view(np.uint32))
-        say(f"GPU search done for pass rate {sel}")
+        runs[f"{sel} B={B}"] = (w,) + host(ids, sc, raw, cnt)
+        say(f"GPU search done for pass rate {sel}, B = {B}")
+        if B != 32 or sel == "50%":
+            continue
         # the same batch by explicit pre-filtering (three phases at this size)
         ids, sc, raw, cnt = ix.search(w["Q"], w["filters"], k, q_scale=w["q_scale"], prefilter=True)
         torch.cuda.synchronize()
-        pre = (w, ids.cpu().numpy().view(np.uint32), sc.cpu().numpy(), raw.cpu().numpy(), cnt.cpu().numpy().view(np.uint32))
+        pre = (w,) + host(ids, sc, raw, cnt)
         say(f"GPU search by pre-filtering done for pass rate {sel}")
         if sel == "0.1%":
-            runs["0.1% by pre-filtering"] = pre                  # checked against the oracle like the others, below
+            runs["0.1% B=32 by pre-filtering"] = pre             # checked against the oracle like the others, below
         else:                                                    # 1.6e9 feasible pairs: the masking result, which the
-            for a, b in zip(pre[1:], runs[sel][1:]):             # oracle checks below, must come out bit for bit
+            for a, b in zip(pre[1:], runs[f"{sel} B={B}"][1:]):  # oracle checks below, must come out bit for bit
                 assert a.tobytes() == b.tobytes(), f"{sel}: pre-filtering and masking disagree"
 
     # (a) every returned pair, one by one
-    for sel, (w, ids, sc, raw, cnt) in runs.items():
-        assert np.all(cnt == k), f"{sel}: counts {cnt}"
-        flat = torch.from_numpy(ids.astype(np.int64).reshape(-1)).cuda()
-        rows = base["emb"].index_select(0, flat).cpu().numpy()
-        rs = base["scale"].index_select(0, flat).cpu().numpy()
-        mk = base["mask"].index_select(0, flat).cpu().numpy().view(np.uint32)
+    for label, (w, ids, sc, raw, cnt) in runs.items():
+        B = ids.shape[0]
+        assert np.all(cnt == k), f"{label}: counts {cnt}"
         Qh = w["Q"].cpu().numpy(); qs = w["q_scale"].cpu().numpy()
-        pb = np.repeat(np.arange(B, dtype=np.uint32), k)
-        rank, oraw, feas = oracle_mod.pairs(S.I8, rows, mk, Qh, w["filters"], pb, np.arange(B * k, dtype=np.uint64), row_scale=rs)
-        assert feas.all(), f"{sel}: infeasible ids returned"
-        assert np.array_equal(oraw.reshape(B, k), raw), f"{sel}: raw int32 scores differ"
-        exp = (rank.astype(np.float32).reshape(B, k) * qs[:, None]).astype(np.float32)
-        assert exp.tobytes() == sc.tobytes(), f"{sel}: fp32 score bits differ"
-        r2 = rank.reshape(B, k)
-        assert np.all(np.diff(r2, axis=1) <= 0), f"{sel}: ranking values increase"
-        same = np.diff(r2, axis=1) == 0
-        assert np.all(np.diff(ids.astype(np.int64), axis=1)[same] > 0), f"{sel}: equal ranks not in ascending id"
-        assert all(len(set(ids[b].tolist())) == k for b in range(B)), f"{sel}: duplicate ids"
-        say(f"{sel}: all {B * k} returned pairs re-scored by the oracle: exact")
+        for b0 in range(0, B, 256):                              # (gathers of at most 256 000 rows at a time)
+            b1 = min(B, b0 + 256)
+            flat = torch.from_numpy(ids[b0:b1].astype(np.int64).reshape(-1)).cuda()
+            rows = base["emb"].index_select(0, flat).cpu().numpy()
+            rs = base["scale"].index_select(0, flat).cpu().numpy()
+            mk = base["mask"].index_select(0, flat).cpu().numpy().view(np.uint32)
+            pb = np.repeat(np.arange(b0, b1, dtype=np.uint32), k)
+            rank, oraw, feas = oracle_mod.pairs(S.I8, rows, mk, Qh, w["filters"], pb, np.arange((b1 - b0) * k, dtype=np.uint64),
+                                                row_scale=rs)
+            assert feas.all(), f"{label}: infeasible ids returned"
+            assert np.array_equal(oraw.reshape(b1 - b0, k), raw[b0:b1]), f"{label}: raw int32 scores differ"
+            exp = (rank.astype(np.float32).reshape(b1 - b0, k) * qs[b0:b1, None]).astype(np.float32)
+            assert exp.tobytes() == sc[b0:b1].tobytes(), f"{label}: fp32 score bits differ"
+            r2 = rank.reshape(b1 - b0, k)
+            assert np.all(np.diff(r2, axis=1) <= 0), f"{label}: ranking values increase"
+            same = np.diff(r2, axis=1) == 0
+            assert np.all(np.diff(ids[b0:b1].astype(np.int64), axis=1)[same] > 0), f"{label}: equal ranks not in ascending id"
+        assert all(len(set(ids[b].tolist())) == k for b in range(B)), f"{label}: duplicate ids"
+        say(f"{label}: all {B * k} returned pairs re-scored by the oracle: exact")
 
-    # (b) full oracle scan for two queries of each batch, streamed
-    picks = [("5%", 0), ("5%", 17), ("0.1%", 3), ("0.1%", 30), ("0.1% by pre-filtering", 3), ("0.1% by pre-filtering", 30)]
-    Qs = np.stack([runs[s][0]["Q"][b].cpu().numpy() for s, b in picks])                  # [4, 1, 64]
+    # (b) full oracle scan for a few queries of each batch, streamed
+    picks = [("5% B=32", 0), ("5% B=32", 17), ("0.1% B=32", 3), ("0.1% B=32", 30), ("0.1% B=32 by pre-filtering", 3),
+             ("0.1% B=32 by pre-filtering", 30), ("50% B=32", 11), ("5% B=1", 0), ("5% B=256", 77), ("5% B=256", 255),
+             ("5% B=1024", 500), ("5% B=1024", 1023), ("0.1% B=256", 129)]
+    Qs = np.stack([runs[s][0]["Q"][b].cpu().numpy() for s, b in picks])                  # [picks, 1, 64]
     qsc = np.array([runs[s][0]["q_scale"][b].item() for s, b in picks], np.float32)
     filt = np.stack([runs[s][0]["filters"][b] for s, b in picks]).astype(S.FILTER_DTYPE)
     best = [dict(ids=np.zeros(0, np.uint32), sc=np.zeros(0, np.float32), raw=np.zeros(0, np.int32)) for _ in picks]
@@ -95,11 +108,57 @@ def test_config5_full_size_matches_oracle(oracle_mod):
             best[j] = dict(ids=ids_j[order], sc=sc_j[order], raw=raw_j[order])
         if (p0 // PIECE) % 8 == 0:
             say(f"oracle streamed {p1:,} / {N_FULL:,} items")
-    for j, (sel, b) in enumerate(picks):
-        _, ids, sc, raw, _ = runs[sel]
-        assert np.array_equal(best[j]["ids"], ids[b]), f"query {b} @ {sel}: id list differs from the full oracle scan"
+    for j, (label, b) in enumerate(picks):
+        _, ids, sc, raw, _ = runs[label]
+        assert np.array_equal(best[j]["ids"], ids[b]), f"query {b} @ {label}: id list differs from the full oracle scan"
         assert np.array_equal(best[j]["raw"], raw[b]) and best[j]["sc"].tobytes() == sc[b].tobytes()
-        say(f"query {b} @ {sel}: top-{k} of {N_FULL:,} items identical to the oracle's")
+        say(f"query {b} @ {label}: top-{k} of {N_FULL:,} items identical to the oracle's")
+    ix.close()
+
+
+def test_config5_mid_size_large_batches(oracle_mod):
+    """The config-5 recipe at 8.4 M items (more than 65 536 chunks, so the plan splits the last sweeps as it does at
+    full size; a ragged last chunk): B = 200 and B = 700, k = 1000, all three pass rates, every query against a full
+    oracle scan.  This is where the large-batch int8 kernels meet the full-size sweep plan in seconds."""
+    import torch
+    from gpu_util import run_gpu, assert_exact
+    n, k = 8_400_077, 1000
+    base = S.config5(device="cuda", n=n, B=1, k=k, selectivity="5%", C=100)
+    cols = (base["emb"], base["scale"], base["mask"])
+    emb_h = base["emb"].cpu().numpy(); rs_h = base["scale"].cpu().numpy(); mk_h = base["mask"].cpu().numpy().view(np.uint32)
+    threads = max(1, min(16, os.cpu_count() or 1))
+    for B, sel in ((200, "5%"), (200, "50%"), (200, "0.1%"), (700, "5%")):
+        w = S.config5(device="cuda", n=n, B=B, k=k, selectivity=sel, index=cols, C=100)
+        gpu = run_gpu(w, k=k)
+        say(f"mid size B={B} pass {sel}: GPU search done")
+        ora = oracle_mod.search(S.I8, emb_h, mk_h, w["Q"].cpu().numpy(), w["filters"], k, row_scale=rs_h,
+                                q_scale=w["q_scale"].cpu().numpy(), nthreads=threads)
+        assert_exact(gpu, ora, f"mid size B={B} pass {sel}")
+        say(f"mid size B={B} pass {sel}: all {B} queries identical to the oracle's full scan")
+
+
+@pytest.mark.parametrize("B", [320, 384, 1100])
+def test_ragged_last_pass_fits_the_stated_workspace(oracle_mod, B):
+    """A batch whose last pass is smaller than the others is planned for its own size; the workspace size the library
+    states for the batch must hold both plans (the search is given exactly that many bytes)."""
+    import torch
+    import paper_2407_13218_amd as L
+    from gpu_util import rand_int8_workload, run_oracle, assert_exact, to_cuda
+    n, k = 1_200_003, 1000
+    w = rand_int8_workload(900 + B, n, 64, B, scaled=True)
+    d = to_cuda(w)
+    ix = L.Index(n, 64, S.I8, 0)
+    ix.load(d["emb"], d["mask"], row_scale=d["scale"])
+    nbytes = ix.workspace_bytes(B, 1, k)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    ids = torch.empty((B, k), dtype=torch.int32, device="cuda"); sc = torch.empty((B, k), dtype=torch.float32, device="cuda")
+    raw = torch.empty((B, k), dtype=torch.int32, device="cuda"); cnt = torch.empty((B,), dtype=torch.int32, device="cuda")
+    filt = torch.from_numpy(np.ascontiguousarray(w["filters"]).view(np.uint8).copy()).cuda()
+    L.search_filtered(ix.handle, d["Q"], d["q_scale"], B, 1, filt, k, ids, sc, raw, cnt, ws, nbytes,
+                      torch.cuda.current_stream().cuda_stream, L.FILTERS_ON_DEVICE)
+    torch.cuda.synchronize()
+    gpu = (ids.cpu().numpy().view(np.uint32), sc.cpu().numpy(), raw.cpu().numpy(), cnt.cpu().numpy().view(np.uint32))
+    assert_exact(gpu, run_oracle(oracle_mod, w, k, nthreads=max(1, min(16, os.cpu_count() or 1))), f"ragged B={B}")
     ix.close()
 
 
@@ -147,10 +206,10 @@ def test_config4_full_size(oracle_mod):
 
 
 def test_quantised_full_size(oracle_mod):
-    """1e9 x 64-bit Sign-OPORP codes + masks (the quantised leg bench.py times; Sec. 3.2 / 5.3), B = 1 and B = 32, T = 1000:
+    """1e9 x 64-bit Sign-OPORP codes + masks (the quantised leg bench.py times; Sec. 3.2 / 5.3), B = 1, 32 and 128, T = 1000:
       (a) the library's codes of 200 000 sampled items equal the oracle's codes of the same rows;
       (b) every returned (query, id) pair: match count recomputed by the oracle, feasibility, order, uniqueness;
-      (c) the B = 1 query and two queries of the B = 32 batch against a full oracle scan streamed in pieces."""
+      (c) the B = 1 query, two queries of the B = 32 batch and one of the B = 128 batch against a full oracle scan streamed in pieces."""
     import torch
     import paper_2407_13218_amd as L
 
@@ -183,7 +242,7 @@ def test_quantised_full_size(oracle_mod):
     ix = L.Index(N_FULL, kb, S.BITS, 0)
     ix.load(codes, base["mask"])
     runs = {}
-    for B in (1, 32):
+    for B in (1, 32, 128):
         w = S.config5(device="cuda", n=N_FULL, B=B, k=T, selectivity="5%", index=cols)
         Qf = (w["Q"].float() * w["q_scale"].reshape(B, 1, 1)).reshape(B, d).contiguous()
         qbits = helper.quantize(Qf)
@@ -212,7 +271,7 @@ def test_quantised_full_size(oracle_mod):
         say(f"(b) B = {B}: all {B * T} returned pairs recomputed by the oracle: exact")
 
     # (c) full oracle scans, streamed
-    picks = [(1, 0), (32, 5), (32, 26)]
+    picks = [(1, 0), (32, 5), (32, 26), (128, 100)]
     qsel = np.stack([runs[B][1][b] for B, b in picks])
     filt = np.stack([runs[B][0]["filters"][b] for B, b in picks]).astype(S.FILTER_DTYPE)
     best = [dict(ids=np.zeros(0, np.uint32), mt=np.zeros(0, np.int32)) for _ in picks]
