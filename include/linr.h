@@ -42,7 +42,9 @@ enum {
     LINR_E_WORKSPACE = -7,   /* workspace NULL, misaligned or smaller than required        */
     LINR_E_HIP = -8,         /* a HIP runtime call failed (see linr_last_hip_error)        */
     LINR_E_FILTER = -9,      /* malformed filter (host filters only are checked)           */
-    LINR_E_STATE = -10       /* the index is not in the state the call needs               */
+    LINR_E_STATE = -10,      /* the index is not in the state the call needs               */
+    LINR_E_TOO_LARGE = -11   /* the search needs more scratch than the fixed array of
+                                linr_search_filtered_noalloc holds                         */
 };
 
 /* where the loader's source arrays live and who owns the resident copy */
@@ -151,6 +153,27 @@ int linr_search_filtered(const linr_index*, const void* Q, const float* q_scale,
                          const linr_filter* filters, uint32_t k,
                          uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
                          void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags);
+
+/*
+ * linr_search_filtered for callers that cannot allocate device memory or carry a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * (without the workspace), same kernels and bit-identical results; the scratch memory is a fixed
+ * array of LINR_NOALLOC_SCRATCH_BYTES inside the library, one copy per GPU, held from the time the
+ * library is loaded until the process ends.  The call allocates and frees nothing (the very first
+ * search of a process loads the kernels, as any first launch does: make one call before capturing).
+ * A search whose linr_search_workspace_bytes(B, m, k) exceeds LINR_NOALLOC_SCRATCH_BYTES is
+ * rejected with LINR_E_TOO_LARGE before anything is enqueued (one query with k <= 1000 fits at
+ * any index size; so does B = 4 with k <= 100).  All calls on one GPU share that GPU's array: two
+ * such searches that may overlap in time (different streams, different host threads) race -- keep
+ * them on one stream, or use linr_search_filtered with separate workspaces.  The array keeps the
+ * last call's contents; every counter a search relies on is reset by the search's own first
+ * kernel.  The index's device is made current for the duration of the call.
+ */
+#define LINR_NOALLOC_SCRATCH_BYTES (64u << 20)
+int linr_search_filtered_noalloc(const linr_index*, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                                 const linr_filter* filters, uint32_t k,
+                                 uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
+                                 void* hip_stream, uint32_t flags);
 
 /*
  * The same search by explicit pre-filtering (Sec. 3.1.2 "KNN with Explicit Pre-Filtering"):
@@ -287,6 +310,27 @@ int linr_search_clauses(const linr_index*, const void* Q, const float* q_scale, 
                         const uint64_t* q_values, const uint8_t* q_counts, uint32_t q_width, uint32_t k,
                         uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
                         void* workspace, uint64_t workspace_bytes, void* hip_stream);
+
+/*
+ * linr_search_filtered for callers that cannot allocate device memory or carry a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * (without the workspace), same kernels and bit-identical results; the scratch memory is a fixed
+ * array of LINR_NOALLOC_SCRATCH_BYTES inside the library, one copy per GPU, held from the time the
+ * library is loaded until the process ends.  The call allocates and frees nothing (the very first
+ * search of a process loads the kernels, as any first launch does: make one call before capturing).
+ * A search whose linr_search_workspace_bytes(B, m, k) exceeds LINR_NOALLOC_SCRATCH_BYTES is
+ * rejected with LINR_E_TOO_LARGE before anything is enqueued (one query with k <= 1000 fits at
+ * any index size; so does B = 4 with k <= 100).  All calls on one GPU share that GPU's array: two
+ * such searches that may overlap in time (different streams, different host threads) race -- keep
+ * them on one stream, or use linr_search_filtered with separate workspaces.  The array keeps the
+ * last call's contents; every counter a search relies on is reset by the search's own first
+ * kernel.  The index's device is made current for the duration of the call.
+ */
+#define LINR_NOALLOC_SCRATCH_BYTES (64u << 20)
+int linr_search_filtered_noalloc(const linr_index*, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                                 const linr_filter* filters, uint32_t k,
+                                 uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
+                                 void* hip_stream, uint32_t flags);
 
 /*
  * The same search by explicit pre-filtering (Sec. 3.1.2 "KNN with Explicit Pre-Filtering"):

@@ -14,5 +14,6 @@ from .binding import (  # noqa: F401
     index_enable_updates, index_upsert, index_delete, index_sync_updates,
     index_load_clauses, search_clauses_workspace_bytes, search_clauses, search_clauses_timed,
     search_clauses_prefilter, index_upsert_clauses, search_prefilter_workspace_bytes, search_filtered_prefilter,
+    search_filtered_noalloc, NOALLOC_SCRATCH_BYTES,
     Index,
 )

@@ -15,6 +15,7 @@ F32, BF16, I8, BITS = 0, 1, 2, 3
 NO_ID = 0xFFFFFFFF
 MAX_K = 8192
 MAX_M = 8
+NOALLOC_SCRATCH_BYTES = 64 << 20       # fixed scratch of linr_search_filtered_noalloc
 SRC_HOST, SRC_DEVICE_COPY, SRC_DEVICE_BORROW = 0, 1, 2
 FILTERS_ON_DEVICE, FILTERS_ON_HOST = 0, 1
 MAX_STAGES = 160
@@ -35,7 +36,7 @@ EXPORTS = [
     "linr_index_enable_updates", "linr_index_upsert", "linr_index_delete", "linr_index_sync_updates",
     "linr_index_load_clauses", "linr_search_clauses_workspace_bytes", "linr_search_clauses", "linr_search_clauses_timed",
     "linr_search_clauses_prefilter", "linr_index_upsert_clauses",
-    "linr_search_prefilter_workspace_bytes", "linr_search_filtered_prefilter",
+    "linr_search_prefilter_workspace_bytes", "linr_search_filtered_prefilter", "linr_search_filtered_noalloc",
 ]
 
 
@@ -83,6 +84,8 @@ def load_library():
     lib.linr_search_prefilter_workspace_bytes.argtypes = [vp, u32, u32, u32, C.POINTER(u64)]
     lib.linr_search_filtered_prefilter.restype = i32
     lib.linr_search_filtered_prefilter.argtypes = sargs
+    lib.linr_search_filtered_noalloc.restype = i32
+    lib.linr_search_filtered_noalloc.argtypes = sargs[:11] + sargs[13:]
     lib.linr_search_filtered_timed.restype = i32
     lib.linr_search_filtered_timed.argtypes = sargs + [vp, C.POINTER(u32), vp, vp]
     lib.linr_index_destroy.restype = i32
@@ -212,6 +215,14 @@ def search_filtered(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_r
     _check(load_library().linr_search_filtered(ix, _ptr(Q), _ptr(q_scale), B, m, _ptr(filters), k, _ptr(out_ids),
                                                _ptr(out_scores), _ptr(out_raw), _ptr(out_counts), _ptr(workspace),
                                                workspace_bytes, stream, flags), "linr_search_filtered")
+
+
+def search_filtered_noalloc(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_raw, out_counts, stream=0,
+                            flags=FILTERS_ON_DEVICE):
+    """linr_search_filtered without a workspace argument: the library's fixed scratch array serves (callers that cannot allocate)"""
+    _check(load_library().linr_search_filtered_noalloc(ix, _ptr(Q), _ptr(q_scale), B, m, _ptr(filters), k, _ptr(out_ids),
+                                                       _ptr(out_scores), _ptr(out_raw), _ptr(out_counts), stream, flags),
+           "linr_search_filtered_noalloc")
 
 
 def search_prefilter_workspace_bytes(ix, B, m, k) -> int:

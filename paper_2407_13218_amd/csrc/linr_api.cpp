@@ -33,6 +33,7 @@ extern "C" const char* linr_strerror(int code)
     case LINR_E_HIP: return "HIP runtime error";
     case LINR_E_FILTER: return "malformed filter";
     case LINR_E_STATE: return "index is not in the state the call needs";
+    case LINR_E_TOO_LARGE: return "search needs more scratch memory than the allocation-free entry point holds";
     default: return "unknown error";
     }
 }
@@ -620,6 +621,31 @@ extern "C" int linr_search_filtered(const linr_index* ix, const void* Q, const f
 {
     return search_impl(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_raw, out_counts, workspace,
                        workspace_bytes, hip_stream, flags, nullptr, nullptr, nullptr, nullptr);
+}
+
+// For callers that cannot allocate: the workspace is the library's fixed per-GPU array.  Nothing here allocates or
+// frees; sizes that do not fit are refused before any device work.
+extern "C" int linr_search_filtered_noalloc(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                                            const linr_filter* filters, uint32_t k, uint32_t* out_ids, float* out_scores,
+                                            int32_t* out_raw, uint32_t* out_counts, void* hip_stream, uint32_t flags)
+{
+    if (!ix) return LINR_E_NULL;
+    if (B == 0) return search_impl(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_raw, out_counts, nullptr, 0,
+                                   hip_stream, flags, nullptr, nullptr, nullptr, nullptr);
+    uint64_t need = 0;
+    int rc = linr_search_workspace_bytes(ix, B, m, k, &need);
+    if (rc != LINR_OK) return rc;
+    if (need > LINR_NOALLOC_SCRATCH_BYTES) return LINR_E_TOO_LARGE;
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev != ix->device) HIP_TRY(hipSetDevice(ix->device));
+    void* ws = nullptr;
+    hipError_t e = linr_static_scratch(ix->device, &ws);
+    if (e != hipSuccess) { g_last_hip = (int)e; rc = LINR_E_HIP; }
+    else rc = search_impl(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_raw, out_counts, ws,
+                          LINR_NOALLOC_SCRATCH_BYTES, hip_stream, flags, nullptr, nullptr, nullptr, nullptr);
+    if (dev != ix->device) (void)hipSetDevice(dev);
+    return rc;
 }
 
 extern "C" int linr_search_filtered_timed(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,

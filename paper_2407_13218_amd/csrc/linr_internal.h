@@ -194,6 +194,8 @@ struct linr_rescore_args {
     uint32_t* out_ids; float* out_scores; uint32_t* out_counts;
 };
 hipError_t linr_launch_rescore(const linr_rescore_args& a, hipStream_t s);
+// device address of the fixed scratch array (LINR_NOALLOC_SCRATCH_BYTES) of the GPU `device`, which must be current
+hipError_t linr_static_scratch(int device, void** ptr);
 // 1 if a register-resident-query scan kernel exists for this shape
 int linr_fast_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg);
 int linr_coop_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg);

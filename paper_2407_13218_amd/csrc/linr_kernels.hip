@@ -14,6 +14,7 @@
 // Key of a candidate: (orderable(ranking value) << 32) | ~item_id, so that a larger
 // key means "better score, then lower id"; all keys of one query are distinct.
 #include "linr_device.h"
+#include <mutex>
 
 // Event counters for kernel studies; compiled in only with -DLINR_STATS (the shipped library has none).
 #ifdef LINR_STATS
@@ -2871,6 +2872,35 @@ __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
         __syncthreads();
         for (uint32_t s = tid; s < ns; s += MT) cnt[s] = 0u;
     }
+}
+
+// ---------------------------------------------------------------------------
+// Fixed scratch memory of linr_search_filtered_noalloc: the search workspace of callers that cannot allocate.
+// Every GPU the library runs on holds its own copy of the array at its own address; in host code the name is
+// only a handle for hipGetSymbolAddress, never an address to hand to a kernel or a copy.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[LINR_NOALLOC_SCRATCH_BYTES];
+
+#define LINR_MAX_DEVICES 64
+hipError_t linr_static_scratch(int device, void** ptr)
+{
+    static std::mutex mu;
+    static void* per_device[LINR_MAX_DEVICES];          // device address of `scratch` on each GPU, looked up once
+    if (!ptr || device < 0 || device >= LINR_MAX_DEVICES) return hipErrorInvalidValue;
+    std::lock_guard<std::mutex> g(mu);
+    if (!per_device[device]) {
+        int cur = -1;
+        hipError_t e = hipGetDevice(&cur);
+        if (e != hipSuccess) return e;
+        if (cur != device) return hipErrorInvalidDevice;    // the symbol is resolved for the current GPU
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p || (((uintptr_t)p) & 255u)) return hipErrorInvalidSymbol;
+        per_device[device] = p;
+    }
+    *ptr = per_device[device];
+    return hipSuccess;
 }
 
 // ---------------------------------------------------------------------------
