@@ -422,11 +422,17 @@ int linr_last_hip_error(void);
  *   two_stage_rank_max: linr_search_two_stage ranks its candidates (linr_search_bits + re-scoring kernel) up to this
  *                    T and takes the selection path (linr_select_bits + gather scoring) above it; 0 = 999;
  *   wide_min_batch : use the 32x32-tile kernel (int8, m = 1, rows of 64 / 128 / 256 bytes) for batches of at
- *                    least this many queries; 0 = never (the default: it does not beat the other kernels yet).
+ *                    least this many queries; 0 = never (the default: it does not beat the other kernels yet);
+ *   no_dense       : 1 = never use the large-batch int8 kernel (rows of exactly 64 bytes, m = 1; the default for
+ *                    batches of 65 queries or more), so that the older kernels can still be exercised;
+ *   dense_min_batch: use that kernel from this batch size on; 0 = 65.
+ * The settings are process-wide and read by every search while it plans its launches: change them only while no
+ * other thread is inside a call of this library.
  */
 typedef struct {
     uint32_t sample_ratio, min_sample, blocks_per_cu, max_levels, force_generic, max_qg, no_coop, coop_min_groups;
     uint32_t no_top_split, prefilter_phases, wide_min_batch, two_stage_rank_max;
+    uint32_t no_dense, dense_min_batch;
 } linr_tuning;
 int linr_set_tuning(const linr_tuning*);
 

@@ -11,7 +11,7 @@
 #include <vector>
 
 static thread_local int g_last_hip = 0;
-static linr_tuning g_tuning = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+static linr_tuning g_tuning = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
 #define HIP_TRY(expr)                                   \
     do {                                                \
@@ -255,6 +255,12 @@ static int cached_blocks_per_cu(const linr_index* ix, const linr_plan& p, uint32
     (void)cache_dyn;
     const int ts = ix->ts != nullptr;
     if (p.generic) return linr_scan_blocks_per_cu(p, ix->dtype, Bp, m, ts);
+    if (p.dense) {
+        static int dense_cache[3][17][2];
+        int& dslot = dense_cache[p.vk][p.qg <= 16 ? p.qg : 0][ts];
+        if (dslot == 0) { int v = linr_scan_blocks_per_cu(p, ix->dtype, Bp, m, ts); dslot = v > 0 ? v : -1; }
+        return dslot > 0 ? dslot : 0;
+    }
     if (p.bits) {
         static int bits_cache[3][5][9][2];
         int& bslot = bits_cache[p.bits <= 2 ? p.bits : 0][p.ks <= 4 ? p.ks : 0][p.qg <= 8 ? p.qg : 0][ts];
@@ -310,8 +316,30 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
             qw = c;
             if (c * LINR_WAVES_PER_BLOCK * 32 >= B) break;
         }
+    // Large int8 batches on rows of exactly 64 bytes: queries as the row operand, bounds through the accumulator
+    // input, up to 1024 queries per stream of the index (linr_kernels_dense.hip).  Scaled ranking needs the largest
+    // row scale of the index to stay what it was at load time, which live updates do not guarantee.
+    uint32_t dg = 0;
+    // (a tuning that asks for one of the other kernel families is honoured)
+    const bool other_family = g_tuning.force_generic || g_tuning.no_coop || g_tuning.max_qg || g_tuning.coop_min_groups ||
+                              g_tuning.wide_min_batch;
+    if (!other_family && !g_tuning.no_dense && ix->dtype == LINR_I8 && !bits_mode && m == 1 && ix->row_bytes == 64 &&
+        B >= (g_tuning.dense_min_batch ? g_tuning.dense_min_batch : 65u) && !(ix->row_scale && ix->dead_bit) &&
+        !(ix->row_scale && !ix->scale_stats))
+        dg = B <= 64 ? 4u : B <= 128 ? 8u : 16u;
+    if (dg && linr_dense_dispatch(0, p->vk, dg, ix->ts != nullptr, 0, nullptr, nullptr, nullptr) != hipSuccess) dg = 0;
     uint32_t Bp;
-    if (bits_mode) {
+    if (dg) {
+        p->qg = dg;
+        p->dense = 1;
+        p->coop = 1;                                    // (a workgroup is one walker of the sweep, as in the cooperative kernels)
+        p->generic = 0;
+        p->chunk_items = 128;
+        p->max_batch = LINR_WAVES_PER_BLOCK * dg * 16;  // four query sets per workgroup
+        Bp = B < p->max_batch ? B : p->max_batch;
+        const uint32_t sets = (Bp + dg * 16 - 1) / (dg * 16);
+        p->nsplit = sets <= 1 ? 1u : sets <= 2 ? 2u : 4u;
+    } else if (bits_mode) {
         if (m != 1) return LINR_E_SHAPE;
         p->ks = ix->bits_words;
         p->generic = 0;
@@ -384,7 +412,7 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
         if (p->bits == 1 && bpc > 4) bpc = 4;           // every wave is a chunk-slot: 256 CUs x 4 x 4 waves = LINR_MAX_SLOTS
     }
     p->n_chunks = (ix->n + p->chunk_items - 1) / p->chunk_items;
-    uint64_t waves_wanted = p->n_chunks * p->nsplit;
+    uint64_t waves_wanted = p->n_chunks * (p->dense ? LINR_WAVES_PER_BLOCK : p->nsplit);   // (dense: a workgroup per chunk)
     uint64_t grid = (uint64_t)ix->num_cu * bpc;
     uint64_t grid_needed = (waves_wanted + LINR_WAVES_PER_BLOCK - 1) / LINR_WAVES_PER_BLOCK;
     if (grid > grid_needed) grid = grid_needed;
@@ -394,11 +422,15 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
         grid = (p->nsplit + LINR_WAVES_PER_BLOCK - 1) / LINR_WAVES_PER_BLOCK;
         nslots = 1;
     }
+    if (p->dense && nslots > LINR_MAX_SLOTS) {          // every wave of this kernel owns its slot: shrink the grid instead
+        grid = (uint64_t)LINR_MAX_SLOTS * p->nsplit / LINR_WAVES_PER_BLOCK;
+        nslots = grid * LINR_WAVES_PER_BLOCK / p->nsplit;
+    }
     if (nslots > LINR_MAX_SLOTS) nslots = LINR_MAX_SLOTS;
     p->grid = (uint32_t)grid;
     p->nslots = (uint32_t)nslots;
     // a segment must take what one append round can add on top of the k keys a compaction leaves
-    p->cap = (uint32_t)align_up((uint64_t)k + (p->wide ? (uint32_t)LINR_WIDE_QCAP : p->chunk_items), 64);
+    p->cap = (uint32_t)align_up((uint64_t)k + (p->dense ? (uint32_t)LINR_DENSE_SLACK : p->wide ? (uint32_t)LINR_WIDE_QCAP : p->chunk_items), 64);
 
     // Sweeps, coarse to fine.  Sweep l visits the chunks whose index is a multiple of stride[l] but not of
     // stride[l-1] (those were visited before), so every chunk is scored exactly once per search; the k best keys

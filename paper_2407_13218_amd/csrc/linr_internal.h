@@ -10,6 +10,7 @@
 #define LINR_MAX_SLOTS 4096          // merge kernel keeps one prefix entry per slot in LDS
 #define LINR_MAX_NSPLIT 16
 #define LINR_WIDE_QCAP 320            // keys a wave of the 32x32-tile kernel queues in LDS before writing them out
+#define LINR_DENSE_SLACK 320          // large-batch int8 kernel: a segment holds k keys + its wave's queue (192) + one chunk's appends (128)
 #define LINR_FLAT_REGIONS 64          // independently counted regions of a query's flat candidate array
 #define LINR_COUNTER_STRIDE 16        // words between two region counters (one 64-byte line each)
 
@@ -60,6 +61,8 @@ struct linr_plan {
     uint32_t generic;           // 1 = queries streamed from LDS
     uint32_t coop;              // 1 = the four waves of a workgroup share each chunk and split the query groups
     uint32_t wide;              // 1 = coop with 32x32 tiles; qg then counts 32-query groups per wave
+    uint32_t dense;             // 1 = large-batch int8 kernel (queries as the row operand, bounds through the accumulator
+                                //     input); qg groups per wave, nsplit query sets per workgroup, nslots = grid * 4 / nsplit
     uint32_t bits;              // 1 = bit-matching kernel over 1-bit codes (ks = 64-bit words per code)
     uint32_t grid;              // workgroups of LINR_WAVES_PER_BLOCK waves
     uint32_t nslots;            // chunk-slots = waves / nsplit
@@ -200,7 +203,11 @@ hipError_t linr_static_scratch(int device, void** ptr);
 int linr_fast_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg);
 int linr_coop_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qg);
 int linr_wide_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_t qw);
-int linr_bits_mfma_variant_exists(uint32_t words, uint32_t qg);      // matrix-core bit matching (plan.bits == 2)
+int linr_bits_mfma_variant_exists(uint32_t words, uint32_t qg);
+// large-batch int8 kernel (linr_kernels_dense.hip).  what: 0 = does the variant exist, 1 = workgroups per compute unit
+// (*blocks_per_cu), 2 = launch `grid` workgroups on stream s.  ng: 16-query groups per wave (4, 8 or 16).
+hipError_t linr_dense_dispatch(int what, int vk, uint32_t ng, bool ts, uint32_t grid, hipStream_t s, const linr_scan_args* a,
+                               int* blocks_per_cu);      // matrix-core bit matching (plan.bits == 2)
 // statistics of 1/row_scale of a scaled int8 index (out[3]; part: 3 * LINR_SCALE_STAT_BLOCKS floats of scratch) and the
 // per-item codes derived from them (codes: n_pad bytes)
 #define LINR_SCALE_STAT_BLOCKS 1024

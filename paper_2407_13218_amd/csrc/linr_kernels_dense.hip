@@ -1,0 +1,476 @@
+// Scan kernel for large int8 batches (rows of exactly 64 bytes, m = 1): the fused masked matrix product of
+// LiNR (arXiv 2407.13218) Sec. 6 "Custom filtering kernel" in the regime of Sec. 5.3.2 (batched queries, each
+// with its own filter), where the pass is bound by the matrix cores and by instruction issue, not by HBM.
+//
+// What limits such a pass on gfx950: a 16x16x64 int8 product occupies a SIMD for 16 cycles, and every vector
+// instruction issued next to it costs about 3.3 more (measured; matrix and vector instructions of one SIMD barely
+// overlap).  So the loop below spends the minimum of vector work per product:
+//   * queries are the ROW operand: after a product a lane holds 4 queries x ONE item.  Everything that belongs
+//     to the item (its scale, its mask) is then one value per lane, and the running maximum over all of a wave's
+//     queries is one register per lane;
+//   * the bound of each query enters through the accumulator input: acc = raw - T_q with T_q an integer lower
+//     bound of the raw dot product a candidate of query q needs.  "Some query wants this item" is then a sign /
+//     magnitude test of max_q(acc) that does not depend on q: two v_max3 per product, one compare per 64 queries;
+//   * per-row scales (ranking value raw * s_i): with s_ref >= every scale, T_q = floor(thr_q / s_ref) is valid
+//     for every item, and an item with a smaller scale needs raw >= T_q / (1 - e_i), e_i = 1 - s_i / s_ref, i.e.
+//     raw - T_q >= e_i * raw >= e_i * T_min.  The right side is per item and per wave only: the test
+//     "max_q(raw - T_q) >= e_i * T_min" never misses a candidate and is within about 1 % of exact;
+//   * a wave keeps 16 query groups (256 queries, 64 registers of fragments + 64 of bounds) and the four waves of
+//     a workgroup either split a batch of up to 1024 queries (every chunk is read from HBM once per search for
+//     ANY batch size up to 1024) or, for smaller batches, split the tiles of each chunk;
+//   * chunks arrive through direct global -> LDS loads into a ring of stages (no staging registers), consumed
+//     with hand-placed LDS reads; candidate keys are queued in LDS and written out in bulk.
+// A (tile, 64-query quarter) whose test fires still has its 16 accumulators per lane in registers: they are
+// narrowed to groups, then to (query, item) pairs by the exact predicate and ranking value, and the survivors'
+// keys go to the same per-(slot, query) segments, bounds, sweeps and merges as in the other scan kernels.
+#include "linr_scan_common.h"
+#include <type_traits>
+
+#define DENSE_CH 128                   // items per chunk (8 tiles of 16)
+#define DENSE_NST 4                    // ring stages: DENSE_NST - 1 chunks in flight per workgroup
+#define DENSE_DMA 4                    // direct loads every wave issues per chunk (always this many)
+#define DENSE_QCAP 192                 // keys a wave queues in LDS before writing them out
+#define DENSE_SLACK LINR_DENSE_SLACK   // room a segment must have beyond k: the queue's keys + what one chunk can add per query
+#define DENSE_SCRATCH_WORDS 516        // per wave: queue (keys, query numbers, count) / compaction histogram / flush prefix
+#define DENSE_BIG (1 << 30)
+
+// s_waitcnt immediate that waits for the vector-memory counter only (gfx9 encoding)
+#define DENSE_WAIT_VM(n) (((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+
+struct DenseStage {
+    v4i a[512];                        // 8 KB of rows: tile t (16 items) at a[64 t + lane], as the lanes fetched it
+    uint32_t mk[DENSE_CH];
+    float sc[DENSE_CH];
+    uint32_t ts[DENSE_CH];
+    uint32_t pad[DENSE_CH];            // target of the loads that only keep the per-wave load count uniform
+};
+
+__device__ __forceinline__ uint32_t dense_lds_addr(const void* p)
+{
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
+// The ring is read with hand-placed LDS instructions: for a read the compiler can see, it would wait until every
+// outstanding direct load has landed.  That a stage's loads have landed is established by the step protocol of
+// the kernel (counted wait + workgroup barrier).
+__device__ __forceinline__ v4i dense_read_b128(uint32_t addr)
+{
+    v4i r;
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(r) : "v"(addr) : "memory");
+    return r;
+}
+__device__ __forceinline__ void dense_read_tile(uint32_t addr_a, uint32_t addr_sc, v4i& a, float& sc)
+{
+    asm volatile("ds_read_b128 %0, %2\n\tds_read_b32 %1, %3\n\ts_waitcnt lgkmcnt(0)" : "=&v"(a), "=&v"(sc) : "v"(addr_a), "v"(addr_sc) : "memory");
+}
+__device__ __forceinline__ void dense_read_side(uint32_t addr_mk, uint32_t addr_sc, uint32_t addr_ts, uint32_t& mk, float& sc, uint32_t& ts)
+{
+    asm volatile("ds_read_b32 %0, %3\n\tds_read_b32 %1, %4\n\tds_read_b32 %2, %5\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(mk), "=&v"(sc), "=&v"(ts) : "v"(addr_mk), "v"(addr_sc), "v"(addr_ts) : "memory");
+}
+
+__device__ __forceinline__ int dense_floor_to_int(float x)      // floor(x) clamped to +-2^30 (x may be +-inf)
+{
+    return (int)fminf(fmaxf(floorf(x), -1073741824.0f), 1073741824.0f);
+}
+
+// running maximum over the four accumulators of a product (two v_max3_i32)
+__device__ __forceinline__ int dense_max_acc(int m, const v4i& a)
+{
+    m = max(max(m, a[0]), a[1]);
+    return max(max(m, a[2]), a[3]);
+}
+
+// Per-query state of a workgroup in LDS.  Bounds are kept per WAVE (a wave's accumulator inputs and the values its
+// survivor path adds back must be the same numbers, and waves refresh at different times); the filters, which never
+// change during a launch, per query set.
+template <int NQW, bool TS>
+struct DenseQ {
+    float thr[4 * NQW];                // [wave][query] lower bound of the ranking value (raw ranking: the int32 bound's bits; "none": -inf / INT_MIN)
+    int T[4 * NQW];                    // [wave][query] integer bound that enters the accumulators (see the header comment)
+    uint32_t fa[4 * NQW], fn[4 * NQW]; // compact filter: an item passes the all / none clauses iff (mask & fn) == fa
+    uint32_t t0[TS ? 4 * NQW : 1], t1[TS ? 4 * NQW : 1];   // timestamp window
+    uint8_t flag[4 * NQW];             // 1: the filter has any-of clauses (read the full record from global memory)
+};
+
+template <int VK, int NG, bool TS>
+__global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args A)
+{
+    constexpr int NQW = NG * 16;                         // queries per wave
+    constexpr int NQT = NG / 4;                          // 64-query quarters per wave
+    constexpr bool SCALED = (VK == LINR_VK_I8_SCALED);
+    constexpr int TPC = DENSE_CH / 16;
+    static_assert(NG % 4 == 0 && NG <= 16, "query groups per wave come in quarters of four");
+    static_assert(DENSE_SCRATCH_WORDS >= 2 * NQW + 1 + 3 && DENSE_SCRATCH_WORDS >= 2 * DENSE_QCAP + DENSE_QCAP / 4 + 4, "scratch");
+
+    __shared__ DenseStage ring[DENSE_NST];
+    __shared__ DenseQ<NQW, TS> QS;
+    __shared__ uint32_t cnt_all[WPB][NQW];
+    __shared__ __attribute__((aligned(8))) uint32_t scratch_all[WPB][DENSE_SCRATCH_WORDS];
+
+    const int lane = threadIdx.x & 63, wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int col = lane & 15, g4 = lane >> 4;
+    const uint32_t nsets = A.nsplit;                     // query sets per workgroup: 1, 2 or 4
+    const uint32_t wps = WPB / nsets;                    // waves that share a query set and split the tiles of a chunk
+    const uint32_t qset = (uint32_t)wib % nsets, tlane = (uint32_t)wib / nsets;
+    const uint32_t slot = blockIdx.x * wps + tlane;      // this wave's private candidate segments
+    const uint32_t q_first = qset * NQW;
+    const bool active = q_first < A.B;                   // waves past the batch still load and synchronise
+    const bool has_ts = TS && A.ts != nullptr;
+    uint32_t* const cnt = cnt_all[wib];
+    u64* const qkey = (u64*)&scratch_all[wib][0];
+    uint8_t* const qql = (uint8_t*)&scratch_all[wib][2 * DENSE_QCAP];
+    uint32_t* const qcount = &scratch_all[wib][DENSE_SCRATCH_WORDS - 1];
+    const QSide qs = {cnt, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};   // (the shared helpers use cnt only)
+    float* const s_thr = QS.thr + wib * NQW;
+    int* const s_T = QS.T + wib * NQW;
+    const uint32_t* const s_fa = QS.fa + q_first;
+    const uint32_t* const s_fn = QS.fn + q_first;
+    const uint8_t* const s_flag = QS.flag + q_first;
+    // quarters of this wave that hold queries of the batch
+    const uint32_t nq_mine = active ? (A.B - q_first < (uint32_t)NQW ? A.B - q_first : (uint32_t)NQW) : 0u;
+    const int nqt = (int)((nq_mine + 63) / 64);
+
+    float r_ref = 0.0f;                                  // lower bound of 1 / (largest row scale of the index)
+    if constexpr (SCALED) r_ref = A.scale_stats[0];
+
+    // ---- query fragments (row operand): lane l supplies bytes [16 (l/16), +16) of query row l%16 of each group
+    v4i q[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const uint32_t qi = q_first + g * 16 + col;
+        v4i z = {0, 0, 0, 0};
+        if (qi < A.B) z = *(const v4i*)((const char*)A.Q + (u64)qi * 64 + g4 * 16);
+        q[g] = z;
+    }
+    // ---- filters (once) and bounds (refreshed now and then); the first wave of each query set fills the set's arrays
+    if (tlane == 0) {
+        for (uint32_t ql = lane; ql < (uint32_t)NQW; ql += 64) {
+            const uint32_t qi = q_first + ql;
+            linr_filter F;
+            if (qi < A.B) F = A.filters[qi];
+            else { F.all_bits = 0xFFFFFFFFu; F.none_bits = 0xFFFFFFFFu; F.n_any = 0; F.ts_min = 1; F.ts_max = 0; }
+            const uint32_t none = F.none_bits | A.dead_bit;
+            const bool impossible = (F.all_bits & none) != 0u;
+            QS.fa[q_first + ql] = impossible ? 0xFFFFFFFFu : F.all_bits;
+            QS.fn[q_first + ql] = impossible ? 0u : (F.all_bits | none);
+            QS.flag[q_first + ql] = F.n_any ? 1 : 0;
+            if constexpr (TS) { QS.t0[q_first + ql] = F.ts_min; QS.t1[q_first + ql] = F.ts_max; }
+        }
+    }
+    for (uint32_t ql = lane; ql < (uint32_t)NQW; ql += 64) cnt[ql] = 0;
+    if (lane == 0) *qcount = 0;
+
+    v4i c[NG];                                           // accumulator inputs: -T of the lane's four queries of each group
+    float tmin_f = 0.0f;                                 // T_min of the wave's queries, lowered (0: no usable value)
+    // Bounds: every wave reads those of its queries into its own arrays and derives its accumulator inputs from them.
+    auto load_bounds = [&]() {
+        int tmin = DENSE_BIG;
+        for (uint32_t ql = lane; ql < (uint32_t)NQW; ql += 64) {
+            const uint32_t qi = q_first + ql;
+            float tf = SCALED ? INFINITY : __int_as_float(INT_MAX);
+            int T = DENSE_BIG;                           // past the batch: never a candidate
+            if (qi < A.B) {
+                const u64 t = aload64(A.tau + qi);
+                const uint32_t hi = (uint32_t)(t >> 32);
+                if constexpr (SCALED) {
+                    tf = t ? unord_f32(hi) : -INFINITY;
+                    // raw * s_i >= thr with s_i <= 1 / r_ref needs raw >= thr * r_ref (thr > 0)
+                    T = tf > 0.0f ? dense_floor_to_int(lowered(tf) * r_ref) : -DENSE_BIG;
+                } else {
+                    const int ti = t ? unord_i32(hi) : INT_MIN;
+                    tf = __int_as_float(ti);
+                    T = ti < -DENSE_BIG ? -DENSE_BIG : (ti > DENSE_BIG ? DENSE_BIG : ti);
+                }
+                tmin = min(tmin, T);
+            }
+            s_thr[ql] = tf;
+            s_T[ql] = T;
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) tmin = min(tmin, __shfl_xor(tmin, o));
+        // e_i * T_min with T_min lowered by 2^-11 relative; the test subtracts one more unit for the rounding of the product
+        tmin_f = (tmin > 0 && tmin < DENSE_BIG) ? (float)tmin * 0.99951f : 0.0f;
+        wave_sync();
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const v4i t4 = *(const v4i*)&s_T[g * 16 + 4 * g4];
+            c[g] = (v4i){-t4[0], -t4[1], -t4[2], -t4[3]};
+        }
+    };
+    __syncthreads();                                     // filters written
+    load_bounds();
+
+    uint32_t need_compact = 0u, direct = 0u;
+    uint32_t since_refresh = 0;
+    // Candidate keys wait in the wave's LDS queue and are written out in bulk.  Loads and stores may complete out of
+    // order with respect to each other, which would spoil the counting of outstanding direct loads, so every path
+    // that touches global memory ends by waiting for all of the wave's memory operations.
+    auto flush_queue = [&]() {
+        wave_sync();
+        uint32_t nqd = *qcount;
+        nqd = nqd < (uint32_t)DENSE_QCAP ? nqd : (uint32_t)DENSE_QCAP;     // (keys beyond the queue went straight to their segments)
+        for (uint32_t t = lane; t < nqd; t += 64) {
+            const u64 key = qkey[t];
+            const uint32_t ql = qql[t];
+            const uint32_t pos = atomicAdd(&cnt[ql], 1u);
+            if (pos < A.cap) A.seg[((u64)slot * A.B + q_first + ql) * A.cap + pos] = key;
+            if (pos + 1 + DENSE_SLACK > A.cap) need_compact = 1u;
+        }
+        wave_sync();
+        if (lane == 0) *qcount = 0;
+        wave_sync();
+        __builtin_amdgcn_s_waitcnt(DENSE_WAIT_VM(0));
+    };
+
+    // ---- the chunk ring
+    typedef const __attribute__((address_space(1))) void* gptr;
+    typedef __attribute__((address_space(3))) void* lptr;
+    SweepWalk ahead;
+    ahead.init_strided(blockIdx.x, gridDim.x, A);
+    const uint32_t n_dense32 = (uint32_t)A.n_dense;
+    const uint32_t n_mine = blockIdx.x < n_dense32 ? (n_dense32 - blockIdx.x + gridDim.x - 1) / gridDim.x : 0u;
+    u64 item0_q[DENSE_NST];
+    u64 item0_last = 0;
+    // byte offsets of what this lane fetches, relative to the start of a chunk's rows / side columns: they do not
+    // change from chunk to chunk, so a whole chunk costs no per-lane address arithmetic (uniform base + lane offset)
+    const uint32_t off_row0 = (uint32_t)(((wib * 2) * 16 + col) * 64 + g4 * 16), off_row1 = off_row0 + 16u * 64u;
+    const uint32_t off_side = (uint32_t)lane * 4u;
+    // Every wave issues the same four loads per chunk: two tiles of rows and two halves of a side column (wave 0 the
+    // masks, wave 1 the row scales, wave 2 the timestamps, wave 3 -- and the others where a column does not exist --
+    // the masks once more into a pad nobody reads).  Items past the end of the index repeat the last one; their
+    // candidates are discarded by the `item < n` test.
+    auto issue_next = [&](int rf) {
+        if (ahead.valid()) item0_last = ahead.lc() * A.stride * DENSE_CH;
+#pragma unroll
+        for (int t = 0; t < DENSE_NST; ++t)
+            if (t == rf) item0_q[t] = item0_last;
+        DenseStage& S = ring[rf];
+        const u64 item0 = item0_last;
+        const uint32_t* colp = A.mask;
+        uint32_t* dst = S.pad;
+        if (wib == 0) dst = S.mk;
+        if (SCALED && wib == 1) { colp = (const uint32_t*)A.row_scale; dst = (uint32_t*)S.sc; }
+        if (has_ts && wib == 2) { colp = A.ts; dst = S.ts; }
+        if (item0 + DENSE_CH <= A.n) {                   // uniform; all chunks but possibly the last one
+            const char* eb = (const char*)A.emb + item0 * 64;
+            const char* cb = (const char*)(colp + item0);
+            __builtin_amdgcn_global_load_lds((gptr)(eb + off_row0), (lptr)&S.a[(wib * 2) * 64], 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr)(eb + off_row1), (lptr)&S.a[(wib * 2 + 1) * 64], 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr)(cb + off_side), (lptr)dst, 4, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr)(cb + off_side + 256u), (lptr)(dst + 64), 4, 0, 0);
+        } else {                                         // ragged end: items past the last one repeat it
+            const u64 last = A.n - 1;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int t = wib * 2 + j;
+                u64 it = item0 + (u64)(t * 16 + col);
+                it = it < last ? it : last;
+                __builtin_amdgcn_global_load_lds((gptr)((const char*)A.emb + it * 64 + g4 * 16), (lptr)&S.a[t * 64], 16, 0, 0);
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                u64 it = item0 + (u64)(h * 64 + lane);
+                it = it < last ? it : last;
+                __builtin_amdgcn_global_load_lds((gptr)(colp + it), (lptr)(dst + h * 64), 4, 0, 0);
+            }
+        }
+        ahead.advance();
+    };
+
+    // ---- survivors of one (tile, group): hv = raw - T of the lane's four queries (rows 4 g4 + j of group g) for
+    //      its item (column col of the tile).  Exact predicate and ranking value, then the key goes to the queue.
+    auto survivors = [&](const v4i& hv, int g, float dtest, uint32_t it, u64 item0, const DenseStage& C) {
+        const uint32_t qb = (uint32_t)g * 16 + 4 * g4;   // first of the lane's four wave-local queries
+        uint32_t mk, tsv;
+        float sc;
+        dense_read_side(dense_lds_addr(&C.mk[it]), dense_lds_addr(&C.sc[it]), dense_lds_addr(&C.ts[it]), mk, sc, tsv);
+        const v4u fa4 = *(const v4u*)&s_fa[qb], fn4 = *(const v4u*)&s_fn[qb];
+        const v4i t4 = *(const v4i*)&s_T[qb];
+        const v4f thr4 = *(const v4f*)&s_thr[qb];
+        const u64 item = item0 + it;
+        uint32_t surv = 0;
+        uint32_t hi[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            bool ok = ((float)hv[j] >= dtest) & ((mk & fn4[j]) == fa4[j]) & (item < A.n) & (q_first + qb + j < A.B);
+            if constexpr (TS) {
+                if (has_ts) ok = ok & (tsv >= QS.t0[q_first + qb + j]) & (tsv <= QS.t1[q_first + qb + j]);
+            }
+            const int raw = hv[j] + t4[j];               // the accumulator input was -T exactly
+            if constexpr (SCALED) {
+                const float s = (float)raw * sc;
+                ok = ok & (s >= thr4[j]);
+                hi[j] = ord_f32(s);
+            } else {
+                ok = ok & (raw >= __float_as_int(thr4[j]));
+                hi[j] = ord_i32(raw);
+            }
+            if (ok) surv |= 1u << j;
+        }
+        if (!wave_any(surv != 0u)) return;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            bool ok = (surv >> j) & 1u;
+            if (!wave_any(ok)) continue;
+            if (ok && s_flag[qb + j]) ok = filter_pass(A.filters[q_first + qb + j], mk, has_ts, tsv);
+            if (ok) {
+                const u64 key = ((u64)hi[j] << 32) | (u64)(uint32_t)~(uint32_t)item;
+                const uint32_t pos = atomicAdd(qcount, 1u);
+                if (pos < (uint32_t)DENSE_QCAP) {
+                    qkey[pos] = key;
+                    qql[pos] = (uint8_t)(qb + j);
+                } else {                                  // queue full (rare): straight to the segment
+                    const uint32_t p2 = atomicAdd(&cnt[qb + j], 1u);
+                    if (p2 < A.cap) A.seg[((u64)slot * A.B + q_first + qb + j) * A.cap + p2] = key;
+                    if (p2 + 1 + DENSE_SLACK > A.cap) need_compact = 1u;
+                    direct = 1u;
+                }
+            }
+        }
+    };
+
+    // ---- a quarter (four groups, 64 queries) whose test fired: narrow to groups, then to pairs
+    auto quarter_hot = [&](const v4i (&acc)[4], int qt, float dtest, uint32_t it, u64 item0, const DenseStage& C) {
+        uint32_t pend = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            pend |= wave_any((float)dense_max_acc(INT_MIN, acc[i]) >= dtest) ? (1u << i) : 0u;
+        while (pend) {
+            const int i = __ffs((int)pend) - 1;
+            pend &= pend - 1;
+            v4i hv = acc[0];
+#pragma unroll
+            for (int s = 1; s < 4; ++s)
+                if (i == s) hv = acc[s];
+            survivors(hv, qt * 4 + i, dtest, it, item0, C);
+        }
+    };
+
+    auto consume = [&](int st) {
+        const DenseStage& C = ring[st];
+        u64 item0 = item0_q[0];
+#pragma unroll
+        for (int t = 1; t < DENSE_NST; ++t)
+            if (t == st) item0 = item0_q[t];
+        const uint32_t base_a = dense_lds_addr(&C.a[0]) + (uint32_t)lane * 16u;
+        const uint32_t base_sc = dense_lds_addr(&C.sc[0]) + (uint32_t)col * 4u;
+        // this wave's tiles of the chunk: tlane, tlane + wps, ...
+        v4i b;
+        float sc;
+        dense_read_tile(base_a + tlane * 1024u, base_sc + tlane * 64u, b, sc);
+        v4i X[4], Y[4];
+        // products of quarter QT (four groups) of the tile whose item fragments are `bb`
+        auto products = [&](v4i (&R)[4], auto QT, const v4i& bb) {
+            constexpr int qt = decltype(QT)::value;
+            if constexpr (qt < NQT) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) R[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q[4 * qt + i], bb, c[4 * qt + i], 0, 0, 0);
+            }
+        };
+        // can any of the quarter's 64 queries still want this lane's item?  16 accumulators -> 8 v_max3, one compare
+        auto test = [&](const v4i (&R)[4], auto QT, float dtest, uint32_t it) {
+            constexpr int qt = decltype(QT)::value;
+            if constexpr (qt < NQT) {
+                int m = INT_MIN;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) m = dense_max_acc(m, R[i]);
+                if (wave_any((float)m >= dtest)) quarter_hot(R, qt, dtest, it, item0, C);
+            }
+        };
+        using Q0 = std::integral_constant<int, 0>; using Q1 = std::integral_constant<int, 1>;
+        using Q2 = std::integral_constant<int, 2>; using Q3 = std::integral_constant<int, 3>;
+        products(X, Q0{}, b);
+#pragma unroll 1
+        for (uint32_t t = tlane; t < (uint32_t)TPC; t += wps) {
+            // the test value of this tile's items: e_i * T_min - 1 (raw ranking: -0.5, i.e. "max >= 0")
+            float dtest = -0.5f;
+            if constexpr (SCALED) dtest = __builtin_fmaf(__builtin_fmaf(-sc, r_ref, 1.0f), tmin_f, -1.0f);
+            const uint32_t it = t * 16 + col;
+            // operands of the next tile of this wave (the last one re-reads itself: its products are discarded)
+            const uint32_t tn = t + wps < (uint32_t)TPC ? t + wps : t;
+            v4i bn;
+            float scn;
+            dense_read_tile(base_a + tn * 1024u, base_sc + tn * 64u, bn, scn);
+            // the next quarter's products are issued before a quarter is tested, so the matrix pipe never waits for a test
+            if (nqt > 1) products(Y, Q1{}, b);
+            test(X, Q0{}, dtest, it);
+            if (nqt > 2) products(X, Q2{}, b);
+            if (nqt > 1) test(Y, Q1{}, dtest, it);
+            if (nqt > 3) products(Y, Q3{}, b);
+            if (nqt > 2) test(X, Q2{}, dtest, it);
+            products(X, Q0{}, bn);                       // first quarter of the next tile
+            if (nqt > 3) test(Y, Q3{}, dtest, it);
+            b = bn;
+            sc = scn;
+        }
+        // End of the chunk, the one place where this wave touches global memory besides its direct loads: write the
+        // queue out once it is half full, shrink segments that are nearly full, re-read the bounds now and then.  (An
+        // ordinary memory operation returns after all direct loads issued before it, so each of these empties the ring:
+        // they are kept rare.)
+        ++since_refresh;
+        if (wave_any(direct != 0u) || *qcount >= (uint32_t)(DENSE_QCAP / 2)) {
+            flush_queue();
+            direct = 0u;
+            if (wave_any(need_compact != 0u)) {
+                compact_full_segments<DENSE_SLACK>(A, qs, slot, q_first, NQW, scratch_all[wib], lane);
+                if (lane == 0) *qcount = 0;              // (the histogram shared the queue's memory)
+                wave_sync();
+                need_compact = 0u;
+                since_refresh = 1u << 30;                // bounds moved
+            }
+        }
+        if (since_refresh >= 256u) {
+            load_bounds();
+            since_refresh = 0;
+        }
+    };
+
+    // One step: wait until the chunk in stage `st` has landed for every wave, refill the stage consumed one step ago
+    // with the chunk DENSE_NST - 1 steps ahead, then consume `st`.  Every wave always issues DENSE_DMA loads per step
+    // (past the end of the sweep it reloads the last valid chunk), so "at most (DENSE_NST - 2) * DENSE_DMA loads
+    // outstanding" means: this wave's share of the chunk about to be consumed has landed.
+    if (n_mine) {
+        for (int st = 0; st < DENSE_NST - 1; ++st) issue_next(st);
+        int st = 0;
+        for (uint32_t ch = 0; ch < n_mine; ++ch) {
+            __builtin_amdgcn_s_waitcnt(DENSE_WAIT_VM((DENSE_NST - 2) * DENSE_DMA));
+            __builtin_amdgcn_s_barrier();
+            issue_next(st == 0 ? DENSE_NST - 1 : st - 1);
+            if (nqt > 0) consume(st);
+            st = st + 1 == DENSE_NST ? 0 : st + 1;
+        }
+        // nothing of this workgroup may still be on its way to LDS when its waves end
+        __builtin_amdgcn_s_waitcnt(DENSE_WAIT_VM(0));
+    }
+    if (active) {
+        flush_queue();
+        own_stores_done();
+        flush_segments(A, qs, slot, q_first, NQW, lane, scratch_all[wib]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side: which variants exist, their occupancy, their launch
+// ---------------------------------------------------------------------------
+template <typename K>
+static hipError_t dense_act(K kern, int what, uint32_t grid, hipStream_t s, const linr_scan_args* a, int* blocks_per_cu)
+{
+    if (what == 0) return hipSuccess;
+    if (what == 1) return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, kern, 64 * WPB, 0);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WPB), 0, s, *a);
+    return hipGetLastError();
+}
+
+#define DENSE_CASE(VK_, NG_)                                                                                    \
+    if (vk == VK_ && ng == NG_)                                                                                 \
+        return ts ? dense_act(scan_kernel_dense<VK_, NG_, true>, what, grid, s, a, blocks_per_cu)               \
+                  : dense_act(scan_kernel_dense<VK_, NG_, false>, what, grid, s, a, blocks_per_cu);
+
+// what: 0 = does the variant exist, 1 = workgroups per compute unit, 2 = launch
+hipError_t linr_dense_dispatch(int what, int vk, uint32_t ng, bool ts, uint32_t grid, hipStream_t s, const linr_scan_args* a,
+                               int* blocks_per_cu)
+{
+    DENSE_CASE(LINR_VK_I8_SCALED, 16) DENSE_CASE(LINR_VK_I8_SCALED, 8) DENSE_CASE(LINR_VK_I8_SCALED, 4)
+    DENSE_CASE(LINR_VK_I8_RAW, 16)    DENSE_CASE(LINR_VK_I8_RAW, 8)    DENSE_CASE(LINR_VK_I8_RAW, 4)
+    return hipErrorInvalidDeviceFunction;
+}
