@@ -317,14 +317,14 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
             if (c * LINR_WAVES_PER_BLOCK * 32 >= B) break;
         }
     // Large int8 batches on rows of exactly 64 bytes: queries as the row operand, bounds through the accumulator
-    // input, up to 1024 queries per stream of the index (linr_kernels_dense.hip).  Scaled ranking needs the largest
-    // row scale of the index to stay what it was at load time, which live updates do not guarantee.
+    // input, up to 1024 queries per stream of the index (linr_kernels_dense.hip).  (Its reference row scale, the mean
+    // at load time, only has to be positive to be valid, so live updates do not disturb it.)
     uint32_t dg = 0;
     // (a tuning that asks for one of the other kernel families is honoured)
     const bool other_family = g_tuning.force_generic || g_tuning.no_coop || g_tuning.max_qg || g_tuning.coop_min_groups ||
                               g_tuning.wide_min_batch;
     if (!other_family && !g_tuning.no_dense && ix->dtype == LINR_I8 && !bits_mode && m == 1 && ix->row_bytes == 64 &&
-        B >= (g_tuning.dense_min_batch ? g_tuning.dense_min_batch : 65u) && !(ix->row_scale && ix->dead_bit) &&
+        B >= (g_tuning.dense_min_batch ? g_tuning.dense_min_batch : 65u) &&
         !(ix->row_scale && !ix->scale_stats))
         dg = B <= 64 ? 4u : B <= 128 ? 8u : 16u;
     if (dg && linr_dense_dispatch(0, p->vk, dg, ix->ts != nullptr, 0, nullptr, nullptr, nullptr) != hipSuccess) dg = 0;

@@ -31,7 +31,7 @@ struct linr_index {
     const uint32_t* mask;
     const uint32_t* ts;
     int owned;                  // library allocated the four columns
-    float* scale_stats;         // scaled int8: min of 1/scale, 127/span, span/127 (+ reduction scratch); always owned
+    float* scale_stats;         // scaled int8: min of 1/scale, 127/span, span/127, mean of 1/scale (+ reduction scratch); always owned
     uint8_t* scale_code;        // scaled int8: E_i of every item, padded to a multiple of 256 items; always owned
     // quantised search: Sign-OPORP codes [n][bits_words] (owned), k_bits, and the device copies of perm / signs
     uint64_t* bits;

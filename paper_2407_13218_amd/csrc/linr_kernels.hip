@@ -894,7 +894,7 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A
 }
 
 // Index-wide statistics of r = 1 / row scale for the kernel above and the per-item codes E_i.
-// out[0] = min r; out[1] = 127 / span and out[2] = span / 127, both rounded down, where span =
+// out[3] = mean r (0 if unusable); out[0] = min r; out[1] = 127 / span and out[2] = span / 127, both rounded down, where span =
 // min(max r - min r, 2 (mean r - min r)) so that a few extreme rows do not cost the bulk its resolution
 // (rows beyond the span get E = 127, a valid if loose correction).  All zero if the scales are unusable.
 // Three launches: per-block partials, one block reduces them, then the codes.
@@ -942,6 +942,7 @@ __global__ void __launch_bounds__(256) scale_stats_final(const float* part, uint
         out[0] = ok ? mn : 0.0f;                               // 0: the bound degenerates to "everything may matter"
         out[1] = usable ? (127.0f / span) * 0.99999f : 0.0f;
         out[2] = usable ? (span / 127.0f) * 0.99999f : 0.0f;
+        out[3] = (ok && mean > 0.0f && mean < 3.0e38f) ? mean : 0.0f;   // a typical 1 / row scale (large-batch kernel's reference)
     }
 }
 

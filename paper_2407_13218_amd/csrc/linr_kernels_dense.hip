@@ -11,10 +11,12 @@
 //   * the bound of each query enters through the accumulator input: acc = raw - T_q with T_q an integer lower
 //     bound of the raw dot product a candidate of query q needs.  "Some query wants this item" is then a sign /
 //     magnitude test of max_q(acc) that does not depend on q: two v_max3 per product, one compare per 64 queries;
-//   * per-row scales (ranking value raw * s_i): with s_ref >= every scale, T_q = floor(thr_q / s_ref) is valid
-//     for every item, and an item with a smaller scale needs raw >= T_q / (1 - e_i), e_i = 1 - s_i / s_ref, i.e.
-//     raw - T_q >= e_i * raw >= e_i * T_min.  The right side is per item and per wave only: the test
-//     "max_q(raw - T_q) >= e_i * T_min" never misses a candidate and is within about 1 % of exact;
+//   * per-row scales (ranking value raw * s_i): with any reference scale s_ref = 1 / rho (the index's typical one)
+//     and T_q = floor(thr_q * rho), a candidate of query q at item i has raw >= thr_q / s_i >= T_q / u_i with
+//     u_i = s_i * rho, i.e. raw - T_q >= T_q * g_i, g_i = 1 / u_i - 1.  For g_i >= 0 the right side is at least
+//     T_min * g_i, for g_i < 0 at least T_max * g_i (T_min, T_max over the wave's queries): a value per item and
+//     per wave only.  "max_q(raw - T_q) >= that" never misses a candidate, is exact for scales equal to s_ref and
+//     loose only by (spread of the T_q) x |g_i|, a few per cent of the bound;
 //   * a wave keeps 16 query groups (256 queries, 64 registers of fragments + 64 of bounds) and the four waves of
 //     a workgroup either split a batch of up to 1024 queries (every chunk is read from HBM once per search for
 //     ANY batch size up to 1024) or, for smaller batches, split the tiles of each chunk;
@@ -52,22 +54,19 @@ __device__ __forceinline__ uint32_t dense_lds_addr(const void* p)
 // The ring is read with hand-placed LDS instructions: for a read the compiler can see, it would wait until every
 // outstanding direct load has landed.  That a stage's loads have landed is established by the step protocol of
 // the kernel (counted wait + workgroup barrier).
-__device__ __forceinline__ v4i dense_read_b128(uint32_t addr)
+// fragments of a tile for this lane plus its item's side columns (stage-relative layout: mk, sc, ts 512 bytes apart)
+template <bool TS>
+__device__ __forceinline__ void dense_read_tile(uint32_t addr_a, uint32_t addr_mk, v4i& a, uint32_t& mk, float& sc, uint32_t& ts)
 {
-    v4i r;
-    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(r) : "v"(addr) : "memory");
-    return r;
+    if constexpr (TS)
+        asm volatile("ds_read_b128 %0, %4\n\tds_read_b32 %1, %5\n\tds_read_b32 %2, %5 offset:512\n\tds_read_b32 %3, %5 offset:1024\n\t"
+                     "s_waitcnt lgkmcnt(0)" : "=&v"(a), "=&v"(mk), "=&v"(sc), "=&v"(ts) : "v"(addr_a), "v"(addr_mk) : "memory");
+    else {
+        asm volatile("ds_read_b128 %0, %3\n\tds_read_b32 %1, %4\n\tds_read_b32 %2, %4 offset:512\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&v"(a), "=&v"(mk), "=&v"(sc) : "v"(addr_a), "v"(addr_mk) : "memory");
+        ts = 0u;
+    }
 }
-__device__ __forceinline__ void dense_read_tile(uint32_t addr_a, uint32_t addr_sc, v4i& a, float& sc)
-{
-    asm volatile("ds_read_b128 %0, %2\n\tds_read_b32 %1, %3\n\ts_waitcnt lgkmcnt(0)" : "=&v"(a), "=&v"(sc) : "v"(addr_a), "v"(addr_sc) : "memory");
-}
-__device__ __forceinline__ void dense_read_side(uint32_t addr_mk, uint32_t addr_sc, uint32_t addr_ts, uint32_t& mk, float& sc, uint32_t& ts)
-{
-    asm volatile("ds_read_b32 %0, %3\n\tds_read_b32 %1, %4\n\tds_read_b32 %2, %5\n\ts_waitcnt lgkmcnt(0)"
-                 : "=&v"(mk), "=&v"(sc), "=&v"(ts) : "v"(addr_mk), "v"(addr_sc), "v"(addr_ts) : "memory");
-}
-
 __device__ __forceinline__ int dense_floor_to_int(float x)      // floor(x) clamped to +-2^30 (x may be +-inf)
 {
     return (int)fminf(fmaxf(floorf(x), -1073741824.0f), 1073741824.0f);
@@ -130,8 +129,11 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
     const uint32_t nq_mine = active ? (A.B - q_first < (uint32_t)NQW ? A.B - q_first : (uint32_t)NQW) : 0u;
     const int nqt = (int)((nq_mine + 63) / 64);
 
-    float r_ref = 0.0f;                                  // lower bound of 1 / (largest row scale of the index)
-    if constexpr (SCALED) r_ref = A.scale_stats[0];
+    float rho = 1.0f;                                    // 1 / (reference row scale): any positive number is valid, a typical one is tight
+    if constexpr (SCALED) {
+        const float mean_r = A.scale_stats[3];
+        if (mean_r > 0.0f && mean_r < 3.0e38f) rho = mean_r;
+    }
 
     // ---- query fragments (row operand): lane l supplies bytes [16 (l/16), +16) of query row l%16 of each group
     v4i q[NG];
@@ -142,6 +144,10 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
         if (qi < A.B) z = *(const v4i*)((const char*)A.Q + (u64)qi * 64 + g4 * 16);
         q[g] = z;
     }
+    // The fragments must have arrived before the chunk loop: a wait for them at their first use inside it would be
+    // repeated on every pass and, waiting for "all loads", would empty the ring of chunks in flight each time.
+#pragma unroll
+    for (int g = 0; g < NG; ++g) pin(q[g]);
     // ---- filters (once) and bounds (refreshed now and then); the first wave of each query set fills the set's arrays
     if (tlane == 0) {
         for (uint32_t ql = lane; ql < (uint32_t)NQW; ql += 64) {
@@ -161,10 +167,10 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
     if (lane == 0) *qcount = 0;
 
     v4i c[NG];                                           // accumulator inputs: -T of the lane's four queries of each group
-    float tmin_f = 0.0f;                                 // T_min of the wave's queries, lowered (0: no usable value)
+    float tmin_f = 0.0f, tmax_f = 0.0f;                  // T_min lowered / T_max raised over the wave's queries that have a bound
     // Bounds: every wave reads those of its queries into its own arrays and derives its accumulator inputs from them.
     auto load_bounds = [&]() {
-        int tmin = DENSE_BIG;
+        int tmin = DENSE_BIG, tmax = -DENSE_BIG;
         for (uint32_t ql = lane; ql < (uint32_t)NQW; ql += 64) {
             const uint32_t qi = q_first + ql;
             float tf = SCALED ? INFINITY : __int_as_float(INT_MAX);
@@ -174,22 +180,24 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
                 const uint32_t hi = (uint32_t)(t >> 32);
                 if constexpr (SCALED) {
                     tf = t ? unord_f32(hi) : -INFINITY;
-                    // raw * s_i >= thr with s_i <= 1 / r_ref needs raw >= thr * r_ref (thr > 0)
-                    T = tf > 0.0f ? dense_floor_to_int(lowered(tf) * r_ref) : -DENSE_BIG;
+                    T = tf > 0.0f ? dense_floor_to_int(lowered(tf) * rho) : -DENSE_BIG;     // (no usable bound: always a candidate)
                 } else {
                     const int ti = t ? unord_i32(hi) : INT_MIN;
                     tf = __int_as_float(ti);
                     T = ti < -DENSE_BIG ? -DENSE_BIG : (ti > DENSE_BIG ? DENSE_BIG : ti);
                 }
-                tmin = min(tmin, T);
+                if (T > -DENSE_BIG) { tmin = min(tmin, T); tmax = max(tmax, T); }   // (a query without a bound fires for every item by itself)
             }
             s_thr[ql] = tf;
             s_T[ql] = T;
         }
 #pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) tmin = min(tmin, __shfl_xor(tmin, o));
-        // e_i * T_min with T_min lowered by 2^-11 relative; the test subtracts one more unit for the rounding of the product
-        tmin_f = (tmin > 0 && tmin < DENSE_BIG) ? (float)tmin * 0.99951f : 0.0f;
+        for (int o = 32; o >= 1; o >>= 1) { tmin = min(tmin, __shfl_xor(tmin, o)); tmax = max(tmax, __shfl_xor(tmax, o)); }
+        // T_min lowered and T_max raised by 2^-11 relative (rounding of g_i and of the products), over the queries
+        // that have a bound (T >= 0)
+        const bool bounded = tmin <= tmax;
+        tmin_f = bounded ? (float)tmin * 0.99951f : 0.0f;
+        tmax_f = bounded ? (float)tmax * 1.00049f : 0.0f;
         wave_sync();
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
@@ -277,30 +285,34 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
         ahead.advance();
     };
 
-    // ---- survivors of one (tile, group): hv = raw - T of the lane's four queries (rows 4 g4 + j of group g) for
-    //      its item (column col of the tile).  Exact predicate and ranking value, then the key goes to the queue.
-    auto survivors = [&](const v4i& hv, int g, float dtest, uint32_t it, u64 item0, const DenseStage& C) {
+    // What the slow path knows about the tile it works on (one item per lane).
+    struct TileCtx {
+        int dtest;              // integer form of the first test: a pair can only matter if raw - T >= dtest
+        uint32_t mk, ts;        // the item's mask and timestamp
+        float sc;               // its row scale
+        u64 item;               // its id
+    };
+
+    // ---- survivors of one (tile, group): hv = raw - T of the lane's four queries (rows 4 g4 + j of group g) for its
+    //      item; bit j of `cand` says the pair passed the first test and the all / none clauses.  Timestamp window,
+    //      exact ranking value against the query's bound, any-of clauses; then the key goes to the queue.
+    auto survivors = [&](const v4i& hv, uint32_t cand, int g, const TileCtx& tc) {
         const uint32_t qb = (uint32_t)g * 16 + 4 * g4;   // first of the lane's four wave-local queries
-        uint32_t mk, tsv;
-        float sc;
-        dense_read_side(dense_lds_addr(&C.mk[it]), dense_lds_addr(&C.sc[it]), dense_lds_addr(&C.ts[it]), mk, sc, tsv);
-        const v4u fa4 = *(const v4u*)&s_fa[qb], fn4 = *(const v4u*)&s_fn[qb];
         const v4i t4 = *(const v4i*)&s_T[qb];
         const v4f thr4 = *(const v4f*)&s_thr[qb];
-        const u64 item = item0 + it;
         uint32_t surv = 0;
         uint32_t hi[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            bool ok = ((float)hv[j] >= dtest) & ((mk & fn4[j]) == fa4[j]) & (item < A.n) & (q_first + qb + j < A.B);
+            bool ok = ((cand >> j) & 1u) != 0u;
             if constexpr (TS) {
-                if (has_ts) ok = ok & (tsv >= QS.t0[q_first + qb + j]) & (tsv <= QS.t1[q_first + qb + j]);
+                if (has_ts) ok = ok & (tc.ts >= QS.t0[q_first + qb + j]) & (tc.ts <= QS.t1[q_first + qb + j]);
             }
             const int raw = hv[j] + t4[j];               // the accumulator input was -T exactly
             if constexpr (SCALED) {
-                const float s = (float)raw * sc;
-                ok = ok & (s >= thr4[j]);
-                hi[j] = ord_f32(s);
+                const float sv = (float)raw * tc.sc;
+                ok = ok & (sv >= thr4[j]);
+                hi[j] = ord_f32(sv);
             } else {
                 ok = ok & (raw >= __float_as_int(thr4[j]));
                 hi[j] = ord_i32(raw);
@@ -312,9 +324,9 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
         for (int j = 0; j < 4; ++j) {
             bool ok = (surv >> j) & 1u;
             if (!wave_any(ok)) continue;
-            if (ok && s_flag[qb + j]) ok = filter_pass(A.filters[q_first + qb + j], mk, has_ts, tsv);
+            if (ok && s_flag[qb + j]) ok = filter_pass(A.filters[q_first + qb + j], tc.mk, has_ts, tc.ts);
             if (ok) {
-                const u64 key = ((u64)hi[j] << 32) | (u64)(uint32_t)~(uint32_t)item;
+                const u64 key = ((u64)hi[j] << 32) | (u64)(uint32_t)~(uint32_t)tc.item;
                 const uint32_t pos = atomicAdd(qcount, 1u);
                 if (pos < (uint32_t)DENSE_QCAP) {
                     qkey[pos] = key;
@@ -329,20 +341,32 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
         }
     };
 
-    // ---- a quarter (four groups, 64 queries) whose test fired: narrow to groups, then to pairs
-    auto quarter_hot = [&](const v4i (&acc)[4], int qt, float dtest, uint32_t it, u64 item0, const DenseStage& C) {
+    // ---- a quarter (four groups, 64 queries) whose test fired: per group, which of the lane's four pairs pass the
+    //      first test AND the all / none clauses (at low pass rates nearly every firing ends here); the rest go on
+    auto quarter_hot = [&](const v4i (&acc)[4], int qt, const TileCtx& tc) {
         uint32_t pend = 0;
+        uint32_t bits[4];
+        const bool live = tc.item < A.n;                 // (items past the end of the index repeat the last one)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            pend |= wave_any((float)dense_max_acc(INT_MIN, acc[i]) >= dtest) ? (1u << i) : 0u;
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t qb = (uint32_t)(qt * 4 + i) * 16 + 4 * g4;
+            const v4u fa4 = *(const v4u*)&s_fa[qb], fn4 = *(const v4u*)&s_fn[qb];
+            uint32_t b = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                b |= ((acc[i][j] >= tc.dtest) & ((tc.mk & fn4[j]) == fa4[j]) & live) ? (1u << j) : 0u;
+            bits[i] = b;
+            pend |= wave_any(b != 0u) ? (1u << i) : 0u;
+        }
         while (pend) {
             const int i = __ffs((int)pend) - 1;
             pend &= pend - 1;
             v4i hv = acc[0];
+            uint32_t cand = bits[0];
 #pragma unroll
-            for (int s = 1; s < 4; ++s)
-                if (i == s) hv = acc[s];
-            survivors(hv, qt * 4 + i, dtest, it, item0, C);
+            for (int s2 = 1; s2 < 4; ++s2)
+                if (i == s2) { hv = acc[s2]; cand = bits[s2]; }
+            survivors(hv, cand, qt * 4 + i, tc);
         }
     };
 
@@ -353,13 +377,10 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
         for (int t = 1; t < DENSE_NST; ++t)
             if (t == st) item0 = item0_q[t];
         const uint32_t base_a = dense_lds_addr(&C.a[0]) + (uint32_t)lane * 16u;
-        const uint32_t base_sc = dense_lds_addr(&C.sc[0]) + (uint32_t)col * 4u;
-        // this wave's tiles of the chunk: tlane, tlane + wps, ...
-        v4i b;
-        float sc;
-        dense_read_tile(base_a + tlane * 1024u, base_sc + tlane * 64u, b, sc);
-        v4i X[4], Y[4];
-        // products of quarter QT (four groups) of the tile whose item fragments are `bb`
+        const uint32_t base_mk = dense_lds_addr(&C.mk[0]) + (uint32_t)col * 4u;
+        // this wave's tiles of the chunk: tlane, tlane + wps, ...  One set of accumulators serves the four quarters in
+        // turn; the second wave of the SIMD fills the matrix pipe while this one tests.
+        v4i X[4];
         auto products = [&](v4i (&R)[4], auto QT, const v4i& bb) {
             constexpr int qt = decltype(QT)::value;
             if constexpr (qt < NQT) {
@@ -368,40 +389,35 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
             }
         };
         // can any of the quarter's 64 queries still want this lane's item?  16 accumulators -> 8 v_max3, one compare
-        auto test = [&](const v4i (&R)[4], auto QT, float dtest, uint32_t it) {
+        auto test = [&](const v4i (&R)[4], auto QT, const TileCtx& tc) {
             constexpr int qt = decltype(QT)::value;
             if constexpr (qt < NQT) {
                 int m = INT_MIN;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) m = dense_max_acc(m, R[i]);
-                if (wave_any((float)m >= dtest)) quarter_hot(R, qt, dtest, it, item0, C);
+                if (wave_any(m >= tc.dtest)) quarter_hot(R, qt, tc);
             }
         };
         using Q0 = std::integral_constant<int, 0>; using Q1 = std::integral_constant<int, 1>;
         using Q2 = std::integral_constant<int, 2>; using Q3 = std::integral_constant<int, 3>;
-        products(X, Q0{}, b);
 #pragma unroll 1
         for (uint32_t t = tlane; t < (uint32_t)TPC; t += wps) {
-            // the test value of this tile's items: e_i * T_min - 1 (raw ranking: -0.5, i.e. "max >= 0")
-            float dtest = -0.5f;
-            if constexpr (SCALED) dtest = __builtin_fmaf(__builtin_fmaf(-sc, r_ref, 1.0f), tmin_f, -1.0f);
-            const uint32_t it = t * 16 + col;
-            // operands of the next tile of this wave (the last one re-reads itself: its products are discarded)
-            const uint32_t tn = t + wps < (uint32_t)TPC ? t + wps : t;
-            v4i bn;
-            float scn;
-            dense_read_tile(base_a + tn * 1024u, base_sc + tn * 64u, bn, scn);
-            // the next quarter's products are issued before a quarter is tested, so the matrix pipe never waits for a test
-            if (nqt > 1) products(Y, Q1{}, b);
-            test(X, Q0{}, dtest, it);
-            if (nqt > 2) products(X, Q2{}, b);
-            if (nqt > 1) test(Y, Q1{}, dtest, it);
-            if (nqt > 3) products(Y, Q3{}, b);
-            if (nqt > 2) test(X, Q2{}, dtest, it);
-            products(X, Q0{}, bn);                       // first quarter of the next tile
-            if (nqt > 3) test(Y, Q3{}, dtest, it);
-            b = bn;
-            sc = scn;
+            v4i b;
+            TileCtx tc;
+            dense_read_tile<TS>(base_a + t * 1024u, base_mk + t * 64u, b, tc.mk, tc.sc, tc.ts);
+            tc.item = item0 + t * 16 + col;
+            // the first test's right side for this lane's item (see the header comment); raw ranking: "max >= 0"
+            tc.dtest = 0;
+            if constexpr (SCALED) {
+                const float g = __builtin_amdgcn_rcpf(tc.sc * rho) - 1.0f;
+                const float d = g * (g >= 0.0f ? tmin_f : tmax_f);                     // (0 * inf = NaN for a zero scale: the minimum below drops it)
+                tc.dtest = (int)floorf(fminf(d, 536870912.0f) - 2.0f);
+            }
+            products(X, Q0{}, b);
+            test(X, Q0{}, tc);
+            if (nqt > 1) { products(X, Q1{}, b); test(X, Q1{}, tc); }
+            if (nqt > 2) { products(X, Q2{}, b); test(X, Q2{}, tc); }
+            if (nqt > 3) { products(X, Q3{}, b); test(X, Q3{}, tc); }
         }
         // End of the chunk, the one place where this wave touches global memory besides its direct loads: write the
         // queue out once it is half full, shrink segments that are nearly full, re-read the bounds now and then.  (An
