@@ -425,14 +425,15 @@ int linr_last_hip_error(void);
  *                    least this many queries; 0 = never (the default: it does not beat the other kernels yet);
  *   no_dense       : 1 = never use the large-batch int8 kernel (rows of exactly 64 bytes, m = 1; the default for
  *                    batches of 65 queries or more), so that the older kernels can still be exercised;
- *   dense_min_batch: use that kernel from this batch size on; 0 = 65.
+ *   dense_min_batch: use that kernel from this batch size on; 0 = 65;
+ *   dense_groups   : 16-query groups a wave of that kernel keeps in registers (4, 8 or 16); 0 = chosen by batch size.
  * The settings are process-wide and read by every search while it plans its launches: change them only while no
  * other thread is inside a call of this library.
  */
 typedef struct {
     uint32_t sample_ratio, min_sample, blocks_per_cu, max_levels, force_generic, max_qg, no_coop, coop_min_groups;
     uint32_t no_top_split, prefilter_phases, wide_min_batch, two_stage_rank_max;
-    uint32_t no_dense, dense_min_batch;
+    uint32_t no_dense, dense_min_batch, dense_groups;
 } linr_tuning;
 int linr_set_tuning(const linr_tuning*);
 

@@ -11,7 +11,7 @@
 #include <vector>
 
 static thread_local int g_last_hip = 0;
-static linr_tuning g_tuning = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+static linr_tuning g_tuning = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
 #define HIP_TRY(expr)                                   \
     do {                                                \
@@ -319,15 +319,27 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
     // Large int8 batches on rows of exactly 64 bytes: queries as the row operand, bounds through the accumulator
     // input, up to 1024 queries per stream of the index (linr_kernels_dense.hip).  (Its reference row scale, the mean
     // at load time, only has to be positive to be valid, so live updates do not disturb it.)
-    uint32_t dg = 0;
     // (a tuning that asks for one of the other kernel families is honoured)
     const bool other_family = g_tuning.force_generic || g_tuning.no_coop || g_tuning.max_qg || g_tuning.coop_min_groups ||
                               g_tuning.wide_min_batch;
-    if (!other_family && !g_tuning.no_dense && ix->dtype == LINR_I8 && !bits_mode && m == 1 && ix->row_bytes == 64 &&
-        B >= (g_tuning.dense_min_batch ? g_tuning.dense_min_batch : 65u) &&
-        !(ix->row_scale && !ix->scale_stats))
-        dg = B <= 64 ? 4u : B <= 128 ? 8u : 16u;
-    if (dg && linr_dense_dispatch(0, p->vk, dg, ix->ts != nullptr, 0, nullptr, nullptr, nullptr) != hipSuccess) dg = 0;
+    const bool dense_ok = !other_family && !g_tuning.no_dense && ix->dtype == LINR_I8 && !bits_mode && m == 1 && ix->row_bytes == 64 &&
+                          B >= (g_tuning.dense_min_batch ? g_tuning.dense_min_batch : 65u) && !(ix->row_scale && !ix->scale_stats);
+    uint32_t dg = 0, dsets = 1, dmax = 1024;
+    if (dense_ok) {
+        // up to four query sets per workgroup, each an equal run (a multiple of 64) of the batch's order; a wave keeps
+        // its set's queries in registers, 4 to 16 groups of 16
+        if (g_tuning.dense_groups) {
+            dg = g_tuning.dense_groups;
+            dmax = LINR_WAVES_PER_BLOCK * dg * 16;
+            const uint32_t b1 = B < dmax ? B : dmax, sets = (b1 + dg * 16 - 1) / (dg * 16);
+            dsets = sets <= 1 ? 1u : sets <= 2 ? 2u : 4u;
+        } else {
+            const uint32_t b1 = B < dmax ? B : dmax;
+            dsets = b1 <= 256 ? 1u : b1 <= 512 ? 2u : 4u;
+            dg = ((((b1 + dsets - 1) / dsets) + 63u) & ~63u) / 16;
+        }
+        if (linr_dense_dispatch(0, p->vk, dg, ix->ts != nullptr, 0, nullptr, nullptr, nullptr) != hipSuccess) dg = 0;
+    }
     uint32_t Bp;
     if (dg) {
         p->qg = dg;
@@ -335,10 +347,9 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
         p->coop = 1;                                    // (a workgroup is one walker of the sweep, as in the cooperative kernels)
         p->generic = 0;
         p->chunk_items = 128;
-        p->max_batch = LINR_WAVES_PER_BLOCK * dg * 16;  // four query sets per workgroup
+        p->max_batch = dmax;
         Bp = B < p->max_batch ? B : p->max_batch;
-        const uint32_t sets = (Bp + dg * 16 - 1) / (dg * 16);
-        p->nsplit = sets <= 1 ? 1u : sets <= 2 ? 2u : 4u;
+        p->nsplit = dsets;
     } else if (bits_mode) {
         if (m != 1) return LINR_E_SHAPE;
         p->ks = ix->bits_words;
@@ -476,6 +487,7 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
     p->off_fvalid = off;   off = align_up(off + (uint64_t)Bp * LINR_FLAT_REGIONS * LINR_COUNTER_STRIDE * 4, 256);
     p->off_cnt = off;      off = align_up(off + (uint64_t)Bp * p->nslots * 4, 256);
     p->off_filters = off;  off = align_up(off + (uint64_t)Bp * sizeof(linr_filter), 256);
+    p->off_order = off;    off = align_up(off + (uint64_t)Bp * 4, 256);
     p->off_flat = off;     off = align_up(off + (uint64_t)Bp * p->flat_cap * 8, 256);
     p->off_seg = off;      off = align_up(off + (uint64_t)p->nslots * Bp * p->cap * 8, 256);
     p->total_bytes = off;
@@ -634,6 +646,11 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
             uint64_t items = sa.n_dense * pp.chunk_items;
             if (items > ix->n) items = ix->n;
             HIP_TRY(ev(0, LINR_STAGE_SCAN, items));
+            if (pp.dense) {                             // its first test is tightest when neighbouring queries have similar bounds
+                uint32_t* order = (uint32_t*)(ws + pp.off_order);
+                HIP_TRY(linr_launch_dense_order(tau, Bp, order, st));
+                sa.qorder = order;
+            }
             HIP_TRY(linr_launch_scan(pp, ix->dtype, sa, st));
             HIP_TRY(ev(1, LINR_STAGE_SCAN, items));
             ma.final_level = (l + 1 == pp.nlevels);

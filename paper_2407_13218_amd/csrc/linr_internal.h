@@ -74,7 +74,7 @@ struct linr_plan {
     uint64_t n_chunks;
     // workspace layout (byte offsets)
     uint32_t flat_cap;          // keys per query in the flat candidate array
-    uint64_t off_tau, off_ccnt, off_carry, off_gcnt, off_fvalid, off_cnt, off_filters, off_flat, off_seg, total_bytes;
+    uint64_t off_tau, off_ccnt, off_carry, off_gcnt, off_fvalid, off_cnt, off_filters, off_order, off_flat, off_seg, total_bytes;
 };
 
 struct linr_scan_args {
@@ -97,6 +97,7 @@ struct linr_scan_args {
     uint32_t skip_mod;          // level indices that are multiples of this were visited by earlier sweeps (0: none)
     uint32_t k_bits;            // bit-matching kernel: bits per code
     uint32_t dead_bit;          // mask bit no feasible item may carry (live updates), or 0
+    const uint32_t* qorder;     // large-batch int8 kernel: the batch's queries in ascending order of their bounds, or nullptr
 };
 
 struct linr_merge_args {
@@ -206,6 +207,8 @@ int linr_wide_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_
 int linr_bits_mfma_variant_exists(uint32_t words, uint32_t qg);
 // large-batch int8 kernel (linr_kernels_dense.hip).  what: 0 = does the variant exist, 1 = workgroups per compute unit
 // (*blocks_per_cu), 2 = launch `grid` workgroups on stream s.  ng: 16-query groups per wave (4, 8 or 16).
+// order[0 .. B) = the queries of a pass (B <= 1024) in ascending order of their current bounds tau (none first)
+hipError_t linr_launch_dense_order(const unsigned long long* tau, uint32_t B, uint32_t* order, hipStream_t s);
 hipError_t linr_dense_dispatch(int what, int vk, uint32_t ng, bool ts, uint32_t grid, hipStream_t s, const linr_scan_args* a,
                                int* blocks_per_cu);      // matrix-core bit matching (plan.bits == 2)
 // statistics of 1/row_scale of a scaled int8 index (out[3]; part: 3 * LINR_SCALE_STAT_BLOCKS floats of scratch) and the

@@ -6,25 +6,29 @@
 // instruction issued next to it costs about 3.3 more (measured; matrix and vector instructions of one SIMD barely
 // overlap).  So the loop below spends the minimum of vector work per product:
 //   * queries are the ROW operand: after a product a lane holds 4 queries x ONE item.  Everything that belongs
-//     to the item (its scale, its mask) is then one value per lane, and the running maximum over all of a wave's
-//     queries is one register per lane;
+//     to the item (its scale, its mask) is then one value per lane, and the running maximum over a quarter of a
+//     wave's queries is one register per lane;
 //   * the bound of each query enters through the accumulator input: acc = raw - T_q with T_q an integer lower
-//     bound of the raw dot product a candidate of query q needs.  "Some query wants this item" is then a sign /
-//     magnitude test of max_q(acc) that does not depend on q: two v_max3 per product, one compare per 64 queries;
+//     bound of the raw dot product a candidate of query q needs.  "Some query wants this item" is then a test of
+//     max_q(acc) that does not depend on q: two v_max3 per product, one compare per 64 queries;
 //   * per-row scales (ranking value raw * s_i): with any reference scale s_ref = 1 / rho (the index's typical one)
 //     and T_q = floor(thr_q * rho), a candidate of query q at item i has raw >= thr_q / s_i >= T_q / u_i with
 //     u_i = s_i * rho, i.e. raw - T_q >= T_q * g_i, g_i = 1 / u_i - 1.  For g_i >= 0 the right side is at least
-//     T_min * g_i, for g_i < 0 at least T_max * g_i (T_min, T_max over the wave's queries): a value per item and
-//     per wave only.  "max_q(raw - T_q) >= that" never misses a candidate, is exact for scales equal to s_ref and
-//     loose only by (spread of the T_q) x |g_i|, a few per cent of the bound;
-//   * a wave keeps 16 query groups (256 queries, 64 registers of fragments + 64 of bounds) and the four waves of
-//     a workgroup either split a batch of up to 1024 queries (every chunk is read from HBM once per search for
-//     ANY batch size up to 1024) or, for smaller batches, split the tiles of each chunk;
+//     T_min * g_i, for g_i < 0 at least T_max * g_i (T_min, T_max over the 64 queries tested together): a value
+//     per item.  "max_q(raw - T_q) >= that" never misses a candidate, is exact for scales equal to s_ref and loose
+//     only by (spread of the T_q) x |g_i|.  That spread is kept small by ORDERING the batch: a tiny kernel sorts
+//     the queries by their current bounds before every sweep, a wave takes up to 256 neighbours of that order and
+//     tests them in quarters of 64 with the quarter's own T_min / T_max (data with dense clusters is unforgiving
+//     here: a test that is 10 % loose lets a query's whole cluster through);
+//   * a wave keeps up to 16 query groups (256 queries, 64 registers of fragments + 64 of bounds) and the four
+//     waves of a workgroup either split a batch of up to 1024 queries (every chunk is read from HBM once per
+//     search for ANY batch size up to 1024) or, for smaller batches, split the tiles of each chunk;
+//   * the loop over a tile is branch-free: products, maxima and compares of all quarters, then ONE branch.  A tile
+//     that fired recomputes the products of the quarters concerned (the fragments are still in registers) and
+//     narrows them to groups, then to (query, item) pairs by the exact predicate and ranking value;
 //   * chunks arrive through direct global -> LDS loads into a ring of stages (no staging registers), consumed
 //     with hand-placed LDS reads; candidate keys are queued in LDS and written out in bulk.
-// A (tile, 64-query quarter) whose test fires still has its 16 accumulators per lane in registers: they are
-// narrowed to groups, then to (query, item) pairs by the exact predicate and ranking value, and the survivors'
-// keys go to the same per-(slot, query) segments, bounds, sweeps and merges as in the other scan kernels.
+// The survivors' keys go to the same per-(slot, query) segments, bounds, sweeps and merges as in the other kernels.
 #include "linr_scan_common.h"
 #include <type_traits>
 
@@ -44,7 +48,6 @@ struct DenseStage {
     uint32_t mk[DENSE_CH];
     float sc[DENSE_CH];
     uint32_t ts[DENSE_CH];
-    uint32_t pad[DENSE_CH];            // target of the loads that only keep the per-wave load count uniform
 };
 
 __device__ __forceinline__ uint32_t dense_lds_addr(const void* p)
@@ -54,7 +57,7 @@ __device__ __forceinline__ uint32_t dense_lds_addr(const void* p)
 // The ring is read with hand-placed LDS instructions: for a read the compiler can see, it would wait until every
 // outstanding direct load has landed.  That a stage's loads have landed is established by the step protocol of
 // the kernel (counted wait + workgroup barrier).
-// fragments of a tile for this lane plus its item's side columns (stage-relative layout: mk, sc, ts 512 bytes apart)
+// Fragments of a tile for this lane plus its item's side columns (stage layout: mk, sc, ts 512 bytes apart).
 template <bool TS>
 __device__ __forceinline__ void dense_read_tile(uint32_t addr_a, uint32_t addr_mk, v4i& a, uint32_t& mk, float& sc, uint32_t& ts)
 {
@@ -67,6 +70,7 @@ __device__ __forceinline__ void dense_read_tile(uint32_t addr_a, uint32_t addr_m
         ts = 0u;
     }
 }
+
 __device__ __forceinline__ int dense_floor_to_int(float x)      // floor(x) clamped to +-2^30 (x may be +-inf)
 {
     return (int)fminf(fmaxf(floorf(x), -1073741824.0f), 1073741824.0f);
@@ -86,15 +90,16 @@ template <int NQW, bool TS>
 struct DenseQ {
     float thr[4 * NQW];                // [wave][query] lower bound of the ranking value (raw ranking: the int32 bound's bits; "none": -inf / INT_MIN)
     int T[4 * NQW];                    // [wave][query] integer bound that enters the accumulators (see the header comment)
-    uint32_t fa[4 * NQW], fn[4 * NQW]; // compact filter: an item passes the all / none clauses iff (mask & fn) == fa
+    uint32_t fa[4 * NQW], fn[4 * NQW]; // [set][query] compact filter: an item passes the all / none clauses iff (mask & fn) == fa
     uint32_t t0[TS ? 4 * NQW : 1], t1[TS ? 4 * NQW : 1];   // timestamp window
+    uint16_t qi[4 * NQW];              // [set][query] index of the query in the batch (0xFFFF: none)
     uint8_t flag[4 * NQW];             // 1: the filter has any-of clauses (read the full record from global memory)
 };
 
 template <int VK, int NG, bool TS>
 __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args A)
 {
-    constexpr int NQW = NG * 16;                         // queries per wave
+    constexpr int NQW = NG * 16;                         // query positions per wave
     constexpr int NQT = NG / 4;                          // 64-query quarters per wave
     constexpr bool SCALED = (VK == LINR_VK_I8_SCALED);
     constexpr int TPC = DENSE_CH / 16;
@@ -112,8 +117,11 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
     const uint32_t wps = WPB / nsets;                    // waves that share a query set and split the tiles of a chunk
     const uint32_t qset = (uint32_t)wib % nsets, tlane = (uint32_t)wib / nsets;
     const uint32_t slot = blockIdx.x * wps + tlane;      // this wave's private candidate segments
-    const uint32_t q_first = qset * NQW;
-    const bool active = q_first < A.B;                   // waves past the batch still load and synchronise
+    // The batch's order (ascending bounds) is dealt to the sets in equal runs of a multiple of 64 positions.
+    const uint32_t per_set = ((A.B + nsets - 1) / nsets + 63u) & ~63u;
+    const uint32_t pos_first = qset * per_set;           // first position of the order this wave serves
+    const uint32_t nq_mine = pos_first < A.B ? (A.B - pos_first < per_set ? A.B - pos_first : per_set) : 0u;
+    const int nqt = (int)((nq_mine + 63) / 64);          // quarters of this wave that hold queries
     const bool has_ts = TS && A.ts != nullptr;
     uint32_t* const cnt = cnt_all[wib];
     u64* const qkey = (u64*)&scratch_all[wib][0];
@@ -122,12 +130,11 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
     const QSide qs = {cnt, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};   // (the shared helpers use cnt only)
     float* const s_thr = QS.thr + wib * NQW;
     int* const s_T = QS.T + wib * NQW;
-    const uint32_t* const s_fa = QS.fa + q_first;
-    const uint32_t* const s_fn = QS.fn + q_first;
-    const uint8_t* const s_flag = QS.flag + q_first;
-    // quarters of this wave that hold queries of the batch
-    const uint32_t nq_mine = active ? (A.B - q_first < (uint32_t)NQW ? A.B - q_first : (uint32_t)NQW) : 0u;
-    const int nqt = (int)((nq_mine + 63) / 64);
+    const uint32_t set0 = qset * NQW;                    // this set's part of the per-set arrays
+    const uint32_t* const s_fa = QS.fa + set0;
+    const uint32_t* const s_fn = QS.fn + set0;
+    const uint8_t* const s_flag = QS.flag + set0;
+    const uint16_t* const s_qi = QS.qi + set0;           // wave-local query number -> query index of the batch
 
     float rho = 1.0f;                                    // 1 / (reference row scale): any positive number is valid, a typical one is tight
     if constexpr (SCALED) {
@@ -135,11 +142,31 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
         if (mean_r > 0.0f && mean_r < 3.0e38f) rho = mean_r;
     }
 
+    // ---- which queries: position p of the batch's order (the identity if no order is given) is wave-local query
+    //      p - pos_first of its set.  The first wave of each set fills the set's arrays.
+    if (tlane == 0) {
+        for (uint32_t ql = lane; ql < (uint32_t)NQW; ql += 64) {
+            const uint32_t pos = pos_first + ql;
+            uint32_t qi = 0xFFFFu;
+            if (ql < nq_mine) qi = A.qorder ? A.qorder[pos] : pos;
+            QS.qi[set0 + ql] = (uint16_t)qi;
+            linr_filter F;
+            if (qi < A.B) F = A.filters[qi];
+            else { F.all_bits = 0xFFFFFFFFu; F.none_bits = 0xFFFFFFFFu; F.n_any = 0; F.ts_min = 1; F.ts_max = 0; }
+            const uint32_t none = F.none_bits | A.dead_bit;
+            const bool impossible = (F.all_bits & none) != 0u;
+            QS.fa[set0 + ql] = impossible ? 0xFFFFFFFFu : F.all_bits;
+            QS.fn[set0 + ql] = impossible ? 0u : (F.all_bits | none);
+            QS.flag[set0 + ql] = F.n_any ? 1 : 0;
+            if constexpr (TS) { QS.t0[set0 + ql] = F.ts_min; QS.t1[set0 + ql] = F.ts_max; }
+        }
+    }
+    __syncthreads();
     // ---- query fragments (row operand): lane l supplies bytes [16 (l/16), +16) of query row l%16 of each group
     v4i q[NG];
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-        const uint32_t qi = q_first + g * 16 + col;
+        const uint32_t qi = s_qi[g * 16 + col];
         v4i z = {0, 0, 0, 0};
         if (qi < A.B) z = *(const v4i*)((const char*)A.Q + (u64)qi * 64 + g4 * 16);
         q[g] = z;
@@ -148,33 +175,20 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
     // repeated on every pass and, waiting for "all loads", would empty the ring of chunks in flight each time.
 #pragma unroll
     for (int g = 0; g < NG; ++g) pin(q[g]);
-    // ---- filters (once) and bounds (refreshed now and then); the first wave of each query set fills the set's arrays
-    if (tlane == 0) {
-        for (uint32_t ql = lane; ql < (uint32_t)NQW; ql += 64) {
-            const uint32_t qi = q_first + ql;
-            linr_filter F;
-            if (qi < A.B) F = A.filters[qi];
-            else { F.all_bits = 0xFFFFFFFFu; F.none_bits = 0xFFFFFFFFu; F.n_any = 0; F.ts_min = 1; F.ts_max = 0; }
-            const uint32_t none = F.none_bits | A.dead_bit;
-            const bool impossible = (F.all_bits & none) != 0u;
-            QS.fa[q_first + ql] = impossible ? 0xFFFFFFFFu : F.all_bits;
-            QS.fn[q_first + ql] = impossible ? 0u : (F.all_bits | none);
-            QS.flag[q_first + ql] = F.n_any ? 1 : 0;
-            if constexpr (TS) { QS.t0[q_first + ql] = F.ts_min; QS.t1[q_first + ql] = F.ts_max; }
-        }
-    }
     for (uint32_t ql = lane; ql < (uint32_t)NQW; ql += 64) cnt[ql] = 0;
     if (lane == 0) *qcount = 0;
 
     v4i c[NG];                                           // accumulator inputs: -T of the lane's four queries of each group
-    float tmin_f = 0.0f, tmax_f = 0.0f;                  // T_min lowered / T_max raised over the wave's queries that have a bound
+    float tmin_f[NQT], tmax_f[NQT];                      // per quarter: T_min lowered / T_max raised over its queries that have a bound
     // Bounds: every wave reads those of its queries into its own arrays and derives its accumulator inputs from them.
-    auto load_bounds = [&]() {
-        int tmin = DENSE_BIG, tmax = -DENSE_BIG;
-        for (uint32_t ql = lane; ql < (uint32_t)NQW; ql += 64) {
-            const uint32_t qi = q_first + ql;
+    auto load_bounds = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < NQT; ++r) {                  // iteration r of the lanes covers exactly quarter r
+            const uint32_t ql = (uint32_t)(r * 64 + lane);
+            const uint32_t qi = s_qi[ql];
             float tf = SCALED ? INFINITY : __int_as_float(INT_MAX);
-            int T = DENSE_BIG;                           // past the batch: never a candidate
+            int T = DENSE_BIG;                           // no query here: never a candidate
+            int tmin = DENSE_BIG, tmax = -DENSE_BIG;
             if (qi < A.B) {
                 const u64 t = aload64(A.tau + qi);
                 const uint32_t hi = (uint32_t)(t >> 32);
@@ -186,18 +200,17 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
                     tf = __int_as_float(ti);
                     T = ti < -DENSE_BIG ? -DENSE_BIG : (ti > DENSE_BIG ? DENSE_BIG : ti);
                 }
-                if (T > -DENSE_BIG) { tmin = min(tmin, T); tmax = max(tmax, T); }   // (a query without a bound fires for every item by itself)
+                if (T > -DENSE_BIG) { tmin = T; tmax = T; }     // (a query without a bound fires for every item by itself)
             }
             s_thr[ql] = tf;
             s_T[ql] = T;
-        }
 #pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) { tmin = min(tmin, __shfl_xor(tmin, o)); tmax = max(tmax, __shfl_xor(tmax, o)); }
-        // T_min lowered and T_max raised by 2^-11 relative (rounding of g_i and of the products), over the queries
-        // that have a bound (T >= 0)
-        const bool bounded = tmin <= tmax;
-        tmin_f = bounded ? (float)tmin * 0.99951f : 0.0f;
-        tmax_f = bounded ? (float)tmax * 1.00049f : 0.0f;
+            for (int o = 32; o >= 1; o >>= 1) { tmin = min(tmin, __shfl_xor(tmin, o)); tmax = max(tmax, __shfl_xor(tmax, o)); }
+            // lowered / raised by 2^-11 relative (rounding of g_i and of the products)
+            const bool bounded = tmin <= tmax;
+            tmin_f[r] = bounded ? (float)tmin * 0.99951f : 0.0f;
+            tmax_f[r] = bounded ? (float)tmax * 1.00049f : 0.0f;
+        }
         wave_sync();
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
@@ -205,15 +218,14 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
             c[g] = (v4i){-t4[0], -t4[1], -t4[2], -t4[3]};
         }
     };
-    __syncthreads();                                     // filters written
     load_bounds();
 
     uint32_t need_compact = 0u, direct = 0u;
     uint32_t since_refresh = 0;
-    // Candidate keys wait in the wave's LDS queue and are written out in bulk.  Loads and stores may complete out of
-    // order with respect to each other, which would spoil the counting of outstanding direct loads, so every path
-    // that touches global memory ends by waiting for all of the wave's memory operations.
-    auto flush_queue = [&]() {
+    uint32_t queued = 0;                                 // keys pushed to the queue since its last flush (uniform upper bound)
+    // Candidate keys wait in the wave's LDS queue and are written out in bulk (an ordinary memory operation returns
+    // after all direct loads issued before it, so whatever waits for one empties the ring of chunks in flight).
+    auto flush_queue = [&]() __attribute__((always_inline)) {
         wave_sync();
         uint32_t nqd = *qcount;
         nqd = nqd < (uint32_t)DENSE_QCAP ? nqd : (uint32_t)DENSE_QCAP;     // (keys beyond the queue went straight to their segments)
@@ -221,12 +233,13 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
             const u64 key = qkey[t];
             const uint32_t ql = qql[t];
             const uint32_t pos = atomicAdd(&cnt[ql], 1u);
-            if (pos < A.cap) A.seg[((u64)slot * A.B + q_first + ql) * A.cap + pos] = key;
+            if (pos < A.cap) A.seg[((u64)slot * A.B + s_qi[ql]) * A.cap + pos] = key;
             if (pos + 1 + DENSE_SLACK > A.cap) need_compact = 1u;
         }
         wave_sync();
         if (lane == 0) *qcount = 0;
         wave_sync();
+        queued = 0;
         __builtin_amdgcn_s_waitcnt(DENSE_WAIT_VM(0));
     };
 
@@ -237,31 +250,28 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
     ahead.init_strided(blockIdx.x, gridDim.x, A);
     const uint32_t n_dense32 = (uint32_t)A.n_dense;
     const uint32_t n_mine = blockIdx.x < n_dense32 ? (n_dense32 - blockIdx.x + gridDim.x - 1) / gridDim.x : 0u;
-    u64 item0_q[DENSE_NST];
     u64 item0_last = 0;
     // byte offsets of what this lane fetches, relative to the start of a chunk's rows / side columns: they do not
     // change from chunk to chunk, so a whole chunk costs no per-lane address arithmetic (uniform base + lane offset)
     const uint32_t off_row0 = (uint32_t)(((wib * 2) * 16 + col) * 64 + g4 * 16), off_row1 = off_row0 + 16u * 64u;
     const uint32_t off_side = (uint32_t)lane * 4u;
-    // Every wave issues the same four loads per chunk: two tiles of rows and two halves of a side column (wave 0 the
-    // masks, wave 1 the row scales, wave 2 the timestamps, wave 3 -- and the others where a column does not exist --
-    // the masks once more into a pad nobody reads).  Items past the end of the index repeat the last one; their
-    // candidates are discarded by the `item < n` test.
-    auto issue_next = [&](int rf) {
+    // which side column this wave fetches (wave 0 the masks, wave 1 the row scales, wave 2 the timestamps; wave 3 -- and
+    // the others where a column does not exist -- the masks once more, to the same place: the same bytes, only to keep
+    // the per-wave load count uniform) and where in a stage it goes
+    const uint32_t* side_col = A.mask;
+    uint32_t side_dst = (uint32_t)offsetof(DenseStage, mk);
+    if (SCALED && wib == 1) { side_col = (const uint32_t*)A.row_scale; side_dst = (uint32_t)offsetof(DenseStage, sc); }
+    if (has_ts && wib == 2) { side_col = A.ts; side_dst = (uint32_t)offsetof(DenseStage, ts); }
+    // Every wave issues the same four loads per chunk: two tiles of rows and the two halves of its side column.
+    // Items past the end of the index repeat the last one; their candidates are discarded by the `item < n` test.
+    // Returns the first item of the chunk it fetched (past the end of the sweep: the last valid chunk once more).
+    auto issue_next = [&](DenseStage& S) __attribute__((always_inline)) -> u64 {
         if (ahead.valid()) item0_last = ahead.lc() * A.stride * DENSE_CH;
-#pragma unroll
-        for (int t = 0; t < DENSE_NST; ++t)
-            if (t == rf) item0_q[t] = item0_last;
-        DenseStage& S = ring[rf];
         const u64 item0 = item0_last;
-        const uint32_t* colp = A.mask;
-        uint32_t* dst = S.pad;
-        if (wib == 0) dst = S.mk;
-        if (SCALED && wib == 1) { colp = (const uint32_t*)A.row_scale; dst = (uint32_t*)S.sc; }
-        if (has_ts && wib == 2) { colp = A.ts; dst = S.ts; }
+        uint32_t* dst = (uint32_t*)((char*)&S + side_dst);
         if (item0 + DENSE_CH <= A.n) {                   // uniform; all chunks but possibly the last one
             const char* eb = (const char*)A.emb + item0 * 64;
-            const char* cb = (const char*)(colp + item0);
+            const char* cb = (const char*)(side_col + item0);
             __builtin_amdgcn_global_load_lds((gptr)(eb + off_row0), (lptr)&S.a[(wib * 2) * 64], 16, 0, 0);
             __builtin_amdgcn_global_load_lds((gptr)(eb + off_row1), (lptr)&S.a[(wib * 2 + 1) * 64], 16, 0, 0);
             __builtin_amdgcn_global_load_lds((gptr)(cb + off_side), (lptr)dst, 4, 0, 0);
@@ -279,127 +289,116 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
             for (int h = 0; h < 2; ++h) {
                 u64 it = item0 + (u64)(h * 64 + lane);
                 it = it < last ? it : last;
-                __builtin_amdgcn_global_load_lds((gptr)(colp + it), (lptr)(dst + h * 64), 4, 0, 0);
+                __builtin_amdgcn_global_load_lds((gptr)(side_col + it), (lptr)(dst + h * 64), 4, 0, 0);
             }
         }
         ahead.advance();
+        return item0;
     };
 
     // What the slow path knows about the tile it works on (one item per lane).
     struct TileCtx {
-        int dtest;              // integer form of the first test: a pair can only matter if raw - T >= dtest
+        int dtest[NQT];         // per quarter, the integer right side of the first test: a pair can only matter if raw - T >= dtest
         uint32_t mk, ts;        // the item's mask and timestamp
         float sc;               // its row scale
         u64 item;               // its id
     };
 
-    // ---- survivors of one (tile, group): hv = raw - T of the lane's four queries (rows 4 g4 + j of group g) for its
-    //      item; bit j of `cand` says the pair passed the first test and the all / none clauses.  Timestamp window,
-    //      exact ranking value against the query's bound, any-of clauses; then the key goes to the queue.
-    auto survivors = [&](const v4i& hv, uint32_t cand, int g, const TileCtx& tc) {
-        const uint32_t qb = (uint32_t)g * 16 + 4 * g4;   // first of the lane's four wave-local queries
-        const v4i t4 = *(const v4i*)&s_T[qb];
-        const v4f thr4 = *(const v4f*)&s_thr[qb];
-        uint32_t surv = 0;
-        uint32_t hi[4];
+    // products of quarter QT (four groups) of the tile whose item fragments are `bb`
+    auto products = [&](v4i (&R)[4], auto QT, const v4i& bb) __attribute__((always_inline)) {
+        constexpr int qt = decltype(QT)::value;
+        if constexpr (qt < NQT) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            bool ok = ((cand >> j) & 1u) != 0u;
+            for (int i = 0; i < 4; ++i) R[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q[4 * qt + i], bb, c[4 * qt + i], 0, 0, 0);
+        }
+    };
+
+    // ---- One accumulator index a (0 .. 15: group a / 4 of the quarter, query row 4 g4 + a % 4) of a quarter that
+    //      fired: the lanes whose value hv = raw - T passed the first test finish their pair -- all / none clauses,
+    //      timestamp window, exact ranking value against the query's bound, any-of clauses -- and queue its key.
+    auto finish_pairs = [&](int hv, bool hot, int a, int qt, const TileCtx& tc) __attribute__((always_inline)) {
+        const uint32_t ql = (uint32_t)(qt * 4 + (a >> 2)) * 16 + 4 * g4 + (uint32_t)(a & 3);     // wave-local query of this lane's pair
+        bool ok = hot && tc.item < A.n;                  // (items past the end of the index repeat the last one)
+        uint32_t hi = 0;
+        if (ok) {
+            ok = (tc.mk & s_fn[ql]) == s_fa[ql];
             if constexpr (TS) {
-                if (has_ts) ok = ok & (tc.ts >= QS.t0[q_first + qb + j]) & (tc.ts <= QS.t1[q_first + qb + j]);
+                if (has_ts) ok = ok && tc.ts >= QS.t0[set0 + ql] && tc.ts <= QS.t1[set0 + ql];
             }
-            const int raw = hv[j] + t4[j];               // the accumulator input was -T exactly
+        }
+        if (ok) {
+            const int raw = hv + s_T[ql];                // the accumulator input was -T exactly
             if constexpr (SCALED) {
                 const float sv = (float)raw * tc.sc;
-                ok = ok & (sv >= thr4[j]);
-                hi[j] = ord_f32(sv);
+                ok = sv >= s_thr[ql];
+                hi = ord_f32(sv);
             } else {
-                ok = ok & (raw >= __float_as_int(thr4[j]));
-                hi[j] = ord_i32(raw);
+                ok = raw >= __float_as_int(s_thr[ql]);
+                hi = ord_i32(raw);
             }
-            if (ok) surv |= 1u << j;
         }
-        if (!wave_any(surv != 0u)) return;
+        if (ok && s_flag[ql]) ok = filter_pass(A.filters[s_qi[ql]], tc.mk, has_ts, tc.ts);
+        const u64 okm = wave_ballot(ok);
+        if (okm == 0ull) return;
+        if (ok) {
+            const u64 key = ((u64)hi << 32) | (u64)(uint32_t)~(uint32_t)tc.item;
+            const uint32_t pos = atomicAdd(qcount, 1u);
+            if (pos < (uint32_t)DENSE_QCAP) {
+                qkey[pos] = key;
+                qql[pos] = (uint8_t)ql;
+            } else {                                      // queue full (rare): straight to the segment
+                const uint32_t p2 = atomicAdd(&cnt[ql], 1u);
+                if (p2 < A.cap) A.seg[((u64)slot * A.B + s_qi[ql]) * A.cap + p2] = key;
+                if (p2 + 1 + DENSE_SLACK > A.cap) need_compact = 1u;
+                direct = 1u;
+            }
+        }
+        queued += (uint32_t)__popcll(okm);
+    };
+
+    // ---- a quarter (four groups, 64 queries) of a tile that fired: which of a lane's 16 values pass the first test
+    //      (one compare each, into wave masks), then the few accumulator indices that have any such lane
+    auto quarter_hot = [&](const v4i (&acc)[4], int qt, int dq, const TileCtx& tc) __attribute__((always_inline)) {
+        uint32_t pend = 0;                               // bit a: some lane's value a passed
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            bool ok = (surv >> j) & 1u;
-            if (!wave_any(ok)) continue;
-            if (ok && s_flag[qb + j]) ok = filter_pass(A.filters[q_first + qb + j], tc.mk, has_ts, tc.ts);
-            if (ok) {
-                const u64 key = ((u64)hi[j] << 32) | (u64)(uint32_t)~(uint32_t)tc.item;
-                const uint32_t pos = atomicAdd(qcount, 1u);
-                if (pos < (uint32_t)DENSE_QCAP) {
-                    qkey[pos] = key;
-                    qql[pos] = (uint8_t)(qb + j);
-                } else {                                  // queue full (rare): straight to the segment
-                    const uint32_t p2 = atomicAdd(&cnt[qb + j], 1u);
-                    if (p2 < A.cap) A.seg[((u64)slot * A.B + q_first + qb + j) * A.cap + p2] = key;
-                    if (p2 + 1 + DENSE_SLACK > A.cap) need_compact = 1u;
-                    direct = 1u;
+        for (int a = 0; a < 16; ++a)
+            pend |= wave_any(acc[a >> 2][a & 3] >= dq) ? (1u << a) : 0u;
+        while (pend) {
+            const int a = __ffs((int)pend) - 1;
+            pend &= pend - 1;
+            int hv = acc[0][0];
+#pragma unroll
+            for (int s2 = 1; s2 < 16; ++s2)
+                if (a == s2) hv = acc[s2 >> 2][s2 & 3];
+            finish_pairs(hv, hv >= dq, a, qt, tc);
+        }
+    };
+
+    using Q0 = std::integral_constant<int, 0>; using Q1 = std::integral_constant<int, 1>;
+    using Q2 = std::integral_constant<int, 2>; using Q3 = std::integral_constant<int, 3>;
+    // ---- a tile that fired: the products of each quarter are made again (the fragments are still in registers),
+    //      tested again, and the quarters that fired narrowed to pairs
+    auto tile_hot = [&](const v4i& b, const TileCtx& tc) __attribute__((always_inline)) {
+        v4i H[4];
+        auto one = [&](auto QT) __attribute__((always_inline)) {
+            constexpr int qt = decltype(QT)::value;
+            if constexpr (qt < NQT) {
+                if (qt < nqt) {
+                    products(H, QT, b);
+                    int m = INT_MIN;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) m = dense_max_acc(m, H[i]);
+                    if (wave_any(m >= tc.dtest[qt])) quarter_hot(H, qt, tc.dtest[qt], tc);
                 }
             }
-        }
+        };
+        one(Q0{}); one(Q1{}); one(Q2{}); one(Q3{});
     };
 
-    // ---- a quarter (four groups, 64 queries) whose test fired: per group, which of the lane's four pairs pass the
-    //      first test AND the all / none clauses (at low pass rates nearly every firing ends here); the rest go on
-    auto quarter_hot = [&](const v4i (&acc)[4], int qt, const TileCtx& tc) {
-        uint32_t pend = 0;
-        uint32_t bits[4];
-        const bool live = tc.item < A.n;                 // (items past the end of the index repeat the last one)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t qb = (uint32_t)(qt * 4 + i) * 16 + 4 * g4;
-            const v4u fa4 = *(const v4u*)&s_fa[qb], fn4 = *(const v4u*)&s_fn[qb];
-            uint32_t b = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                b |= ((acc[i][j] >= tc.dtest) & ((tc.mk & fn4[j]) == fa4[j]) & live) ? (1u << j) : 0u;
-            bits[i] = b;
-            pend |= wave_any(b != 0u) ? (1u << i) : 0u;
-        }
-        while (pend) {
-            const int i = __ffs((int)pend) - 1;
-            pend &= pend - 1;
-            v4i hv = acc[0];
-            uint32_t cand = bits[0];
-#pragma unroll
-            for (int s2 = 1; s2 < 4; ++s2)
-                if (i == s2) { hv = acc[s2]; cand = bits[s2]; }
-            survivors(hv, cand, qt * 4 + i, tc);
-        }
-    };
-
-    auto consume = [&](int st) {
-        const DenseStage& C = ring[st];
-        u64 item0 = item0_q[0];
-#pragma unroll
-        for (int t = 1; t < DENSE_NST; ++t)
-            if (t == st) item0 = item0_q[t];
+    auto consume = [&](const DenseStage& C, const u64 item0) __attribute__((always_inline)) {
         const uint32_t base_a = dense_lds_addr(&C.a[0]) + (uint32_t)lane * 16u;
         const uint32_t base_mk = dense_lds_addr(&C.mk[0]) + (uint32_t)col * 4u;
-        // this wave's tiles of the chunk: tlane, tlane + wps, ...  One set of accumulators serves the four quarters in
-        // turn; the second wave of the SIMD fills the matrix pipe while this one tests.
-        v4i X[4];
-        auto products = [&](v4i (&R)[4], auto QT, const v4i& bb) {
-            constexpr int qt = decltype(QT)::value;
-            if constexpr (qt < NQT) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) R[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q[4 * qt + i], bb, c[4 * qt + i], 0, 0, 0);
-            }
-        };
-        // can any of the quarter's 64 queries still want this lane's item?  16 accumulators -> 8 v_max3, one compare
-        auto test = [&](const v4i (&R)[4], auto QT, const TileCtx& tc) {
-            constexpr int qt = decltype(QT)::value;
-            if constexpr (qt < NQT) {
-                int m = INT_MIN;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) m = dense_max_acc(m, R[i]);
-                if (wave_any(m >= tc.dtest)) quarter_hot(R, qt, tc);
-            }
-        };
-        using Q0 = std::integral_constant<int, 0>; using Q1 = std::integral_constant<int, 1>;
-        using Q2 = std::integral_constant<int, 2>; using Q3 = std::integral_constant<int, 3>;
+        // this wave's tiles of the chunk: tlane, tlane + wps, ...
 #pragma unroll 1
         for (uint32_t t = tlane; t < (uint32_t)TPC; t += wps) {
             v4i b;
@@ -407,28 +406,47 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
             dense_read_tile<TS>(base_a + t * 1024u, base_mk + t * 64u, b, tc.mk, tc.sc, tc.ts);
             tc.item = item0 + t * 16 + col;
             // the first test's right side for this lane's item (see the header comment); raw ranking: "max >= 0"
-            tc.dtest = 0;
+#pragma unroll
+            for (int r = 0; r < NQT; ++r) tc.dtest[r] = 0;
             if constexpr (SCALED) {
                 const float g = __builtin_amdgcn_rcpf(tc.sc * rho) - 1.0f;
-                const float d = g * (g >= 0.0f ? tmin_f : tmax_f);                     // (0 * inf = NaN for a zero scale: the minimum below drops it)
-                tc.dtest = (int)floorf(fminf(d, 536870912.0f) - 2.0f);
+#pragma unroll
+                for (int r = 0; r < NQT; ++r) {
+                    // min(g T_min, g T_max) - 3: one of the two is the valid side (0 * inf = NaN for a zero scale is dropped
+                    // by the minimum); 2 of slack for the rounding of g and of the products, 1 because the conversion rounds
+                    // towards zero, which for a negative value is upwards by less than 1
+                    tc.dtest[r] = (int)fminf(fminf(__builtin_fmaf(g, tmin_f[r], -3.0f), __builtin_fmaf(g, tmax_f[r], -3.0f)), 536870912.0f);
+                }
             }
-            products(X, Q0{}, b);
-            test(X, Q0{}, tc);
-            if (nqt > 1) { products(X, Q1{}, b); test(X, Q1{}, tc); }
-            if (nqt > 2) { products(X, Q2{}, b); test(X, Q2{}, tc); }
-            if (nqt > 3) { products(X, Q3{}, b); test(X, Q3{}, tc); }
+            // Branch-free over the quarters: products, 8 v_max3 over the 16 accumulators, the excess over the quarter's
+            // test value folded into one running maximum; one compare and one branch per tile.
+            int excess = INT_MIN;
+            v4i X[4];
+            auto quarter = [&](auto QT) __attribute__((always_inline)) {
+                constexpr int qt = decltype(QT)::value;
+                if constexpr (qt < NQT) {
+                    products(X, QT, b);
+                    int m = INT_MIN;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) m = dense_max_acc(m, X[i]);
+                    excess = max(excess, m - tc.dtest[qt]);       // (|m|, |dtest| < 2^30 + 2^21: no overflow)
+                }
+            };
+            quarter(Q0{});
+            if constexpr (NQT > 1) { if (nqt > 1) quarter(Q1{}); }
+            if constexpr (NQT > 2) { if (nqt > 2) quarter(Q2{}); }
+            if constexpr (NQT > 3) { if (nqt > 3) quarter(Q3{}); }
+            if (__builtin_expect(wave_any(excess >= 0), 0)) tile_hot(b, tc);
         }
         // End of the chunk, the one place where this wave touches global memory besides its direct loads: write the
-        // queue out once it is half full, shrink segments that are nearly full, re-read the bounds now and then.  (An
-        // ordinary memory operation returns after all direct loads issued before it, so each of these empties the ring:
-        // they are kept rare.)
+        // queue out once it is half full, shrink segments that are nearly full, re-read the bounds now and then.  (Each
+        // of these empties the ring: they are kept rare.)
         ++since_refresh;
-        if (wave_any(direct != 0u) || *qcount >= (uint32_t)(DENSE_QCAP / 2)) {
+        if (queued >= (uint32_t)(DENSE_QCAP / 2) || wave_any(direct != 0u)) {
             flush_queue();
             direct = 0u;
             if (wave_any(need_compact != 0u)) {
-                compact_full_segments<DENSE_SLACK>(A, qs, slot, q_first, NQW, scratch_all[wib], lane);
+                compact_full_segments<DENSE_SLACK>(A, qs, slot, 0, NQW, scratch_all[wib], lane, s_qi);
                 if (lane == 0) *qcount = 0;              // (the histogram shared the queue's memory)
                 wave_sync();
                 need_compact = 0u;
@@ -441,28 +459,70 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
         }
     };
 
-    // One step: wait until the chunk in stage `st` has landed for every wave, refill the stage consumed one step ago
-    // with the chunk DENSE_NST - 1 steps ahead, then consume `st`.  Every wave always issues DENSE_DMA loads per step
+    // One step: wait until the chunk in stage ST has landed for every wave, refill the stage consumed one step ago with
+    // the chunk DENSE_NST - 1 steps ahead, then consume stage ST.  Every wave always issues DENSE_DMA loads per step
     // (past the end of the sweep it reloads the last valid chunk), so "at most (DENSE_NST - 2) * DENSE_DMA loads
-    // outstanding" means: this wave's share of the chunk about to be consumed has landed.
+    // outstanding" means: this wave's share of the chunk about to be consumed has landed.  The loop over the chunks is
+    // unrolled by the number of stages, so that stage numbers are constants and the chunks' first items stay in
+    // scalar registers.
+    u64 first_item[DENSE_NST];
+    auto step = [&](auto ST) __attribute__((always_inline)) {
+        constexpr int st = decltype(ST)::value;
+        constexpr int refill = st == 0 ? DENSE_NST - 1 : st - 1;
+        __builtin_amdgcn_s_waitcnt(DENSE_WAIT_VM((DENSE_NST - 2) * DENSE_DMA));
+        __builtin_amdgcn_s_barrier();
+        first_item[refill] = issue_next(ring[refill]);
+        if (nqt > 0) consume(ring[st], first_item[st]);
+    };
+    static_assert(DENSE_NST == 4, "the chunk loop is unrolled for four stages");
     if (n_mine) {
-        for (int st = 0; st < DENSE_NST - 1; ++st) issue_next(st);
-        int st = 0;
-        for (uint32_t ch = 0; ch < n_mine; ++ch) {
-            __builtin_amdgcn_s_waitcnt(DENSE_WAIT_VM((DENSE_NST - 2) * DENSE_DMA));
-            __builtin_amdgcn_s_barrier();
-            issue_next(st == 0 ? DENSE_NST - 1 : st - 1);
-            if (nqt > 0) consume(st);
-            st = st + 1 == DENSE_NST ? 0 : st + 1;
+        first_item[0] = issue_next(ring[0]);
+        first_item[1] = issue_next(ring[1]);
+        first_item[2] = issue_next(ring[2]);
+        for (uint32_t ch = 0; ch < n_mine; ch += DENSE_NST) {
+            step(std::integral_constant<int, 0>{});
+            if (ch + 1 < n_mine) step(std::integral_constant<int, 1>{});
+            if (ch + 2 < n_mine) step(std::integral_constant<int, 2>{});
+            if (ch + 3 < n_mine) step(std::integral_constant<int, 3>{});
         }
         // nothing of this workgroup may still be on its way to LDS when its waves end
         __builtin_amdgcn_s_waitcnt(DENSE_WAIT_VM(0));
     }
-    if (active) {
+    if (nqt > 0) {
         flush_queue();
         own_stores_done();
-        flush_segments(A, qs, slot, q_first, NQW, lane, scratch_all[wib]);
+        flush_segments(A, qs, slot, 0, NQW, lane, scratch_all[wib], s_qi);
     }
+}
+
+// ---------------------------------------------------------------------------
+// order[0 .. B) = the queries of a pass in ascending order of their current bounds (queries without one first), ties
+// by query index: one workgroup, bitonic sort of (bound, index) pairs in LDS.  B <= 1024.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024) dense_order_kernel(const u64* tau, uint32_t B, uint32_t* order)
+{
+    __shared__ u64 key[1024];
+    const uint32_t t = threadIdx.x;
+    key[t] = t < B ? (((aload64(tau + t) >> 32) << 32) | t) : ~0ull;
+    __syncthreads();
+    for (uint32_t size = 2; size <= 1024; size <<= 1)
+        for (uint32_t str = size >> 1; str > 0; str >>= 1) {
+            const uint32_t o = t ^ str;
+            if (o > t) {
+                const u64 x = key[t], y = key[o];
+                const bool asc = (t & size) == 0;
+                if (asc ? (x > y) : (x < y)) { key[t] = y; key[o] = x; }
+            }
+            __syncthreads();
+        }
+    if (t < B) order[t] = (uint32_t)key[t];
+}
+
+hipError_t linr_launch_dense_order(const unsigned long long* tau, uint32_t B, uint32_t* order, hipStream_t s)
+{
+    if (B == 0 || B > 1024) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(dense_order_kernel, dim3(1), dim3(1024), 0, s, (const u64*)tau, B, order);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
@@ -486,7 +546,7 @@ static hipError_t dense_act(K kern, int what, uint32_t grid, hipStream_t s, cons
 hipError_t linr_dense_dispatch(int what, int vk, uint32_t ng, bool ts, uint32_t grid, hipStream_t s, const linr_scan_args* a,
                                int* blocks_per_cu)
 {
-    DENSE_CASE(LINR_VK_I8_SCALED, 16) DENSE_CASE(LINR_VK_I8_SCALED, 8) DENSE_CASE(LINR_VK_I8_SCALED, 4)
-    DENSE_CASE(LINR_VK_I8_RAW, 16)    DENSE_CASE(LINR_VK_I8_RAW, 8)    DENSE_CASE(LINR_VK_I8_RAW, 4)
+    DENSE_CASE(LINR_VK_I8_SCALED, 16) DENSE_CASE(LINR_VK_I8_SCALED, 12) DENSE_CASE(LINR_VK_I8_SCALED, 8) DENSE_CASE(LINR_VK_I8_SCALED, 4)
+    DENSE_CASE(LINR_VK_I8_RAW, 16)    DENSE_CASE(LINR_VK_I8_RAW, 12)    DENSE_CASE(LINR_VK_I8_RAW, 8)    DENSE_CASE(LINR_VK_I8_RAW, 4)
     return hipErrorInvalidDeviceFunction;
 }

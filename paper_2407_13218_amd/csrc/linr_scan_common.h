@@ -436,20 +436,21 @@ __device__ __forceinline__ void tile_survivors(const acc_t& acc, bool lane_hot, 
 
 // Rare: some segment of this wave (wave-local queries 0 .. nq) is nearly full.
 template <int CH>
+// (qmap, if given, maps a wave-local query number to its query index; else query q_first + ql)
 __device__ __forceinline__ void compact_full_segments(const linr_scan_args& A, const QSide& qs, uint32_t slot, uint32_t q_first,
-                                                      uint32_t nq, uint32_t* hist, int lane)
+                                                      uint32_t nq, uint32_t* hist, int lane, const uint16_t* qmap = nullptr)
 {
     __threadfence();
     for (uint32_t q0 = 0; q0 < nq; q0 += 64) {
         uint32_t ql = q0 + lane;
         uint32_t c = 0;
-        if (ql < nq && q_first + ql < A.B) c = qs.cnt[ql];
+        if (ql < nq && (qmap ? (uint32_t)qmap[ql] : q_first + ql) < A.B) c = qs.cnt[ql];
         u64 todo = __ballot(c + CH > A.cap);
         while (todo) {
             int src = __ffsll((long long)todo) - 1;
             todo &= todo - 1;
             uint32_t lsel = q0 + src;
-            uint32_t qsel = q_first + lsel;
+            uint32_t qsel = qmap ? (uint32_t)qmap[lsel] : q_first + lsel;
             uint32_t csel = __shfl(c, src);
             if (csel > A.cap) csel = A.cap;
             wave_compact_segment(A.seg + ((u64)slot * A.B + qsel) * A.cap, &qs.cnt[lsel], A.tau + qsel, csel, A.k, hist, lane);
@@ -464,13 +465,13 @@ __device__ __forceinline__ void compact_full_segments(const linr_scan_args& A, c
 // does not fit, the wave records where the valid part of the flat array ends (fvalid) and leaves those
 // keys in the per-slot segment, whose count it publishes for the merge to pick up.
 __device__ __forceinline__ void flush_segments(const linr_scan_args& A, const QSide& qs, uint32_t slot, uint32_t q_first,
-                                               uint32_t nq, int lane, uint32_t* scratch)
+                                               uint32_t nq, int lane, uint32_t* scratch, const uint16_t* qmap = nullptr)
 {
     uint32_t* pre = scratch;               // [nq + 1] exclusive prefix of the sizes to copy
     uint32_t* dstb = scratch + nq + 1;     // [nq] start of the reserved range in the flat array
     uint32_t running = 0;
     for (uint32_t q0 = 0; q0 < nq; q0 += 64) {
-        const uint32_t ql = q0 + lane, qi = q_first + ql;
+        const uint32_t ql = q0 + lane, qi = (qmap && ql < nq) ? (uint32_t)qmap[ql] : q_first + ql;
         uint32_t c = (ql < nq && qi < A.B) ? qs.cnt[ql] : 0u;
         uint32_t base = 0;
         if (c) {
@@ -503,7 +504,7 @@ __device__ __forceinline__ void flush_segments(const linr_scan_args& A, const QS
             uint32_t mid = (lo + hi) >> 1;
             if (pre[mid] <= t) lo = mid; else hi = mid;
         }
-        const uint32_t j = t - pre[lo], qi = q_first + lo;
+        const uint32_t j = t - pre[lo], qi = qmap ? (uint32_t)qmap[lo] : q_first + lo;
         const u64 key = own_load64(A.seg + ((u64)slot * A.B + qi) * A.cap + j);
         A.flat[(u64)qi * A.flat_cap + dstb[lo] + j] = key;
     }

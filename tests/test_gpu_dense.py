@@ -38,6 +38,15 @@ def test_dense_group_counts_and_threshold(oracle_mod, min_batch, B):
     assert_exact(gpu, run_oracle(oracle_mod, w, 150, nthreads=THREADS), f"dense forced B={B}")
 
 
+@pytest.mark.parametrize("groups,B", [(4, 200), (8, 256), (8, 500), (12, 100), (16, 70), (4, 300)])
+def test_dense_forced_groups_per_wave(oracle_mod, groups, B):
+    """a given number of query groups per wave: the batch is then split into more (or fewer) query sets and passes"""
+    say(f"dense with {groups} groups per wave, B={B}")
+    w = rand_int8_workload(450 + B, 60_000, 64, B, scaled=True, with_ts=(groups == 8))
+    gpu = run_gpu(to_cuda(w), k=120, tuning=dict(dense_groups=groups))
+    assert_exact(gpu, run_oracle(oracle_mod, w, 120, nthreads=THREADS), f"dense groups={groups} B={B}")
+
+
 @pytest.mark.parametrize("tuning", [dict(max_levels=1), dict(max_levels=1, blocks_per_cu=1), dict(sample_ratio=2, min_sample=64),
                                     dict(min_sample=1, sample_ratio=64), dict(no_top_split=1), dict(no_dense=1)])
 def test_dense_degenerate_plans(oracle_mod, tuning):
