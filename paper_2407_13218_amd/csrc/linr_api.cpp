@@ -217,7 +217,7 @@ static int load_common(linr_index* ix, int dtype, const void* emb, const float* 
         // statistics of the row scales for the large-batch kernel's first test (Sec. 5.1: a quantised index
         // carries its scales); 4 floats of results followed by the reduction's scratch
         const uint64_t n_pad = align_up(n, 256);
-        hipError_t e = hipMalloc((void**)&ix->scale_stats, (4 + 3 * LINR_SCALE_STAT_BLOCKS) * sizeof(float));
+        hipError_t e = hipMalloc((void**)&ix->scale_stats, (4 + 4 * LINR_SCALE_STAT_BLOCKS) * sizeof(float));
         if (e == hipSuccess) e = hipMalloc((void**)&ix->scale_code, n_pad);
         if (e == hipSuccess)
             e = linr_launch_scale_stats(ix->row_scale, n, n_pad, ix->scale_stats + 4, ix->scale_stats, ix->scale_code, nullptr);

@@ -894,7 +894,7 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A
 }
 
 // Index-wide statistics of r = 1 / row scale for the kernel above and the per-item codes E_i.
-// out[3] = mean r (0 if unusable); out[0] = min r; out[1] = 127 / span and out[2] = span / 127, both rounded down, where span =
+// out[3] = 1 / (mean row scale) (0 if unusable); out[0] = min r; out[1] = 127 / span and out[2] = span / 127, both rounded down, where span =
 // min(max r - min r, 2 (mean r - min r)) so that a few extreme rows do not cost the bulk its resolution
 // (rows beyond the span get E = 127, a valid if loose correction).  All zero if the scales are unusable.
 // Three launches: per-block partials, one block reduces them, then the codes.
@@ -917,23 +917,27 @@ __device__ __forceinline__ float block_reduce(float v, float* sh, int op)    // 
 __global__ void __launch_bounds__(256) scale_stats_partial(const float* row_scale, u64 n, float* part)
 {
     __shared__ float sh[256];
-    float mn = INFINITY, mx = 0.0f, sum = 0.0f;
+    float mn = INFINITY, mx = 0.0f, sum = 0.0f, sum_s = 0.0f;
     for (u64 i = (u64)blockIdx.x * 256 + threadIdx.x; i < n; i += (u64)gridDim.x * 256) {
-        const float r = rcp_down(row_scale[i]);
+        const float sc = row_scale[i];
+        const float r = rcp_down(sc);
         if (r == r) { mn = fminf(mn, r); mx = fmaxf(mx, r); sum += fminf(r, 3.0e30f); }
+        if (sc > 0.0f) sum_s += fminf(sc, 3.0e30f);
     }
-    mn = block_reduce(mn, sh, 0); mx = block_reduce(mx, sh, 1); sum = block_reduce(sum, sh, 2);
-    if (threadIdx.x == 0) { part[3 * blockIdx.x] = mn; part[3 * blockIdx.x + 1] = mx; part[3 * blockIdx.x + 2] = sum; }
+    mn = block_reduce(mn, sh, 0); mx = block_reduce(mx, sh, 1); sum = block_reduce(sum, sh, 2); sum_s = block_reduce(sum_s, sh, 2);
+    if (threadIdx.x == 0) {
+        part[4 * blockIdx.x] = mn; part[4 * blockIdx.x + 1] = mx; part[4 * blockIdx.x + 2] = sum; part[4 * blockIdx.x + 3] = sum_s;
+    }
 }
 
 __global__ void __launch_bounds__(256) scale_stats_final(const float* part, uint32_t nparts, u64 n, float* out)
 {
     __shared__ float sh[256];
-    float mn = INFINITY, mx = 0.0f, sum = 0.0f;
+    float mn = INFINITY, mx = 0.0f, sum = 0.0f, sum_s = 0.0f;
     for (uint32_t i = threadIdx.x; i < nparts; i += 256) {
-        mn = fminf(mn, part[3 * i]); mx = fmaxf(mx, part[3 * i + 1]); sum += part[3 * i + 2];
+        mn = fminf(mn, part[4 * i]); mx = fmaxf(mx, part[4 * i + 1]); sum += part[4 * i + 2]; sum_s += part[4 * i + 3];
     }
-    mn = block_reduce(mn, sh, 0); mx = block_reduce(mx, sh, 1); sum = block_reduce(sum, sh, 2);
+    mn = block_reduce(mn, sh, 0); mx = block_reduce(mx, sh, 1); sum = block_reduce(sum, sh, 2); sum_s = block_reduce(sum_s, sh, 2);
     if (threadIdx.x == 0) {
         const float mean = sum / (float)n;
         float span = fminf(mx - mn, 2.0f * (mean - mn));
@@ -942,7 +946,10 @@ __global__ void __launch_bounds__(256) scale_stats_final(const float* part, uint
         out[0] = ok ? mn : 0.0f;                               // 0: the bound degenerates to "everything may matter"
         out[1] = usable ? (127.0f / span) * 0.99999f : 0.0f;
         out[2] = usable ? (span / 127.0f) * 0.99999f : 0.0f;
-        out[3] = (ok && mean > 0.0f && mean < 3.0e38f) ? mean : 0.0f;   // a typical 1 / row scale (large-batch kernel's reference)
+        // reference 1 / row scale of the large-batch kernel: 1 / (mean positive scale).  The mean scale is set by the
+        // rows with large scales, the ones whose scores reach the top; zero scales and outliers of 1 / scale do not move it.
+        const float ref = (float)n / sum_s;
+        out[3] = (sum_s > 0.0f && ref > 0.0f && ref < 3.0e38f) ? ref : 0.0f;
     }
 }
 

@@ -38,7 +38,9 @@
 #define DENSE_QCAP 192                 // keys a wave queues in LDS before writing them out
 #define DENSE_SLACK LINR_DENSE_SLACK   // room a segment must have beyond k: the queue's keys + what one chunk can add per query
 #define DENSE_SCRATCH_WORDS 516        // per wave: queue (keys, query numbers, count) / compaction histogram / flush prefix
-#define DENSE_BIG (1 << 30)
+// Stand-in for "no bound" (-) and "no query" (+) among the integer bounds T.  |raw| < 2^20, so raw - T stays within
+// +-(2^29 + 2^20) and its difference to a test value in [-2^29 (1 + 2^-11) - 3, 2^28] cannot overflow 32 bits.
+#define DENSE_BIG (1 << 29)
 
 // s_waitcnt immediate that waits for the vector-memory counter only (gfx9 encoding)
 #define DENSE_WAIT_VM(n) (((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
@@ -71,9 +73,9 @@ __device__ __forceinline__ void dense_read_tile(uint32_t addr_a, uint32_t addr_m
     }
 }
 
-__device__ __forceinline__ int dense_floor_to_int(float x)      // floor(x) clamped to +-2^30 (x may be +-inf)
+__device__ __forceinline__ int dense_floor_to_int(float x)      // floor(x) clamped to +-DENSE_BIG (x may be +-inf)
 {
-    return (int)fminf(fmaxf(floorf(x), -1073741824.0f), 1073741824.0f);
+    return (int)fminf(fmaxf(floorf(x), -(float)DENSE_BIG), (float)DENSE_BIG);
 }
 
 // running maximum over the four accumulators of a product (two v_max3_i32)
@@ -126,7 +128,6 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
     uint32_t* const cnt = cnt_all[wib];
     u64* const qkey = (u64*)&scratch_all[wib][0];
     uint8_t* const qql = (uint8_t*)&scratch_all[wib][2 * DENSE_QCAP];
-    uint32_t* const qcount = &scratch_all[wib][DENSE_SCRATCH_WORDS - 1];
     const QSide qs = {cnt, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};   // (the shared helpers use cnt only)
     float* const s_thr = QS.thr + wib * NQW;
     int* const s_T = QS.T + wib * NQW;
@@ -138,8 +139,8 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
 
     float rho = 1.0f;                                    // 1 / (reference row scale): any positive number is valid, a typical one is tight
     if constexpr (SCALED) {
-        const float mean_r = A.scale_stats[3];
-        if (mean_r > 0.0f && mean_r < 3.0e38f) rho = mean_r;
+        const float ref = A.scale_stats[3];              // 1 / (mean row scale) at load time
+        if (ref > 0.0f && ref < 3.0e38f) rho = ref;
     }
 
     // ---- which queries: position p of the batch's order (the identity if no order is given) is wave-local query
@@ -176,7 +177,6 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
 #pragma unroll
     for (int g = 0; g < NG; ++g) pin(q[g]);
     for (uint32_t ql = lane; ql < (uint32_t)NQW; ql += 64) cnt[ql] = 0;
-    if (lane == 0) *qcount = 0;
 
     v4i c[NG];                                           // accumulator inputs: -T of the lane's four queries of each group
     float tmin_f[NQT], tmax_f[NQT];                      // per quarter: T_min lowered / T_max raised over its queries that have a bound
@@ -222,13 +222,12 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
 
     uint32_t need_compact = 0u, direct = 0u;
     uint32_t since_refresh = 0;
-    uint32_t queued = 0;                                 // keys pushed to the queue since its last flush (uniform upper bound)
+    uint32_t queued = 0;                                 // keys in the queue (uniform)
     // Candidate keys wait in the wave's LDS queue and are written out in bulk (an ordinary memory operation returns
     // after all direct loads issued before it, so whatever waits for one empties the ring of chunks in flight).
     auto flush_queue = [&]() __attribute__((always_inline)) {
         wave_sync();
-        uint32_t nqd = *qcount;
-        nqd = nqd < (uint32_t)DENSE_QCAP ? nqd : (uint32_t)DENSE_QCAP;     // (keys beyond the queue went straight to their segments)
+        const uint32_t nqd = queued;                     // (keys that found the queue full went straight to their segments)
         for (uint32_t t = lane; t < nqd; t += 64) {
             const u64 key = qkey[t];
             const uint32_t ql = qql[t];
@@ -236,8 +235,6 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
             if (pos < A.cap) A.seg[((u64)slot * A.B + s_qi[ql]) * A.cap + pos] = key;
             if (pos + 1 + DENSE_SLACK > A.cap) need_compact = 1u;
         }
-        wave_sync();
-        if (lane == 0) *qcount = 0;
         wave_sync();
         queued = 0;
         __builtin_amdgcn_s_waitcnt(DENSE_WAIT_VM(0));
@@ -313,86 +310,100 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
         }
     };
 
-    // ---- One accumulator index a (0 .. 15: group a / 4 of the quarter, query row 4 g4 + a % 4) of a quarter that
-    //      fired: the lanes whose value hv = raw - T passed the first test finish their pair -- all / none clauses,
-    //      timestamp window, exact ranking value against the query's bound, any-of clauses -- and queue its key.
-    auto finish_pairs = [&](int hv, bool hot, int a, int qt, const TileCtx& tc) __attribute__((always_inline)) {
-        const uint32_t ql = (uint32_t)(qt * 4 + (a >> 2)) * 16 + 4 * g4 + (uint32_t)(a & 3);     // wave-local query of this lane's pair
-        bool ok = hot && tc.item < A.n;                  // (items past the end of the index repeat the last one)
-        uint32_t hi = 0;
-        if (ok) {
-            ok = (tc.mk & s_fn[ql]) == s_fa[ql];
-            if constexpr (TS) {
-                if (has_ts) ok = ok && tc.ts >= QS.t0[set0 + ql] && tc.ts <= QS.t1[set0 + ql];
-            }
-        }
-        if (ok) {
-            const int raw = hv + s_T[ql];                // the accumulator input was -T exactly
-            if constexpr (SCALED) {
-                const float sv = (float)raw * tc.sc;
-                ok = sv >= s_thr[ql];
-                hi = ord_f32(sv);
-            } else {
-                ok = raw >= __float_as_int(s_thr[ql]);
-                hi = ord_i32(raw);
-            }
-        }
-        if (ok && s_flag[ql]) ok = filter_pass(A.filters[s_qi[ql]], tc.mk, has_ts, tc.ts);
-        const u64 okm = wave_ballot(ok);
-        if (okm == 0ull) return;
-        if (ok) {
-            const u64 key = ((u64)hi << 32) | (u64)(uint32_t)~(uint32_t)tc.item;
-            const uint32_t pos = atomicAdd(qcount, 1u);
-            if (pos < (uint32_t)DENSE_QCAP) {
-                qkey[pos] = key;
-                qql[pos] = (uint8_t)ql;
-            } else {                                      // queue full (rare): straight to the segment
-                const uint32_t p2 = atomicAdd(&cnt[ql], 1u);
-                if (p2 < A.cap) A.seg[((u64)slot * A.B + s_qi[ql]) * A.cap + p2] = key;
-                if (p2 + 1 + DENSE_SLACK > A.cap) need_compact = 1u;
-                direct = 1u;
-            }
-        }
-        queued += (uint32_t)__popcll(okm);
-    };
-
-    // ---- a quarter (four groups, 64 queries) of a tile that fired: which of a lane's 16 values pass the first test
-    //      (one compare each, into wave masks), then the few accumulator indices that have any such lane
-    auto quarter_hot = [&](const v4i (&acc)[4], int qt, int dq, const TileCtx& tc) __attribute__((always_inline)) {
-        uint32_t pend = 0;                               // bit a: some lane's value a passed
-#pragma unroll
-        for (int a = 0; a < 16; ++a)
-            pend |= wave_any(acc[a >> 2][a & 3] >= dq) ? (1u << a) : 0u;
-        while (pend) {
-            const int a = __ffs((int)pend) - 1;
-            pend &= pend - 1;
-            int hv = acc[0][0];
-#pragma unroll
-            for (int s2 = 1; s2 < 16; ++s2)
-                if (a == s2) hv = acc[s2 >> 2][s2 & 3];
-            finish_pairs(hv, hv >= dq, a, qt, tc);
-        }
-    };
+    // LDS addresses of the per-query arrays this wave's slow path reads.  (It reads and writes LDS with hand-placed
+    // instructions for the same reason as the ring is: an LDS access the compiler can see waits for every direct
+    // load in flight, i.e. for the memory latency of the chunk requested last.)
+    const uint32_t lds_fa = dense_lds_addr(s_fa), lds_fn = dense_lds_addr(s_fn), lds_T = dense_lds_addr(s_T);
+    const uint32_t lds_thr = dense_lds_addr(s_thr), lds_flag = dense_lds_addr(s_flag);
+    const uint32_t lds_t0 = dense_lds_addr(QS.t0 + (TS ? set0 : 0)), lds_t1 = dense_lds_addr(QS.t1 + (TS ? set0 : 0));
+    const uint32_t lds_qkey = dense_lds_addr(qkey), lds_qql = dense_lds_addr(qql);
 
     using Q0 = std::integral_constant<int, 0>; using Q1 = std::integral_constant<int, 1>;
     using Q2 = std::integral_constant<int, 2>; using Q3 = std::integral_constant<int, 3>;
-    // ---- a tile that fired: the products of each quarter are made again (the fragments are still in registers),
-    //      tested again, and the quarters that fired narrowed to pairs
-    auto tile_hot = [&](const v4i& b, const TileCtx& tc) __attribute__((always_inline)) {
-        v4i H[4];
-        auto one = [&](auto QT) __attribute__((always_inline)) {
-            constexpr int qt = decltype(QT)::value;
-            if constexpr (qt < NQT) {
-                if (qt < nqt) {
-                    products(H, QT, b);
-                    int m = INT_MIN;
+    // ---- A tile that fired (rare).  For each quarter in `fired`: its products are made again (the fragments are
+    //      still in registers), every lane marks which of its 16 values raw - T pass the first test, and the lanes
+    //      that have any finish their (query, item) pairs one per round -- all / none clauses, timestamp window,
+    //      exact ranking value against the query's bound, any-of clauses -- and queue the keys of those that hold.
+    auto tile_hot = [&](const v4i& b, const TileCtx& tc, uint32_t fired) __attribute__((always_inline)) {
+        while (fired) {
+            const int qt = __ffs((int)fired) - 1;
+            fired &= fired - 1;
+            v4i H[4];
+            int dq = tc.dtest[0];
+            if (qt == 0) products(H, Q0{}, b);
+            if constexpr (NQT > 1) { if (qt == 1) { products(H, Q1{}, b); dq = tc.dtest[1]; } }
+            if constexpr (NQT > 2) { if (qt == 2) { products(H, Q2{}, b); dq = tc.dtest[2]; } }
+            if constexpr (NQT > 3) { if (qt == 3) { products(H, Q3{}, b); dq = tc.dtest[3]; } }
+            uint32_t lt = 0;                             // bit a: value a (group a / 4 of the quarter, query row 4 g4 + a % 4) is below the test
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) m = dense_max_acc(m, H[i]);
-                    if (wave_any(m >= tc.dtest[qt])) quarter_hot(H, qt, tc.dtest[qt], tc);
+            for (int a = 15; a >= 0; --a)
+                lt = __builtin_amdgcn_alignbit(lt, (uint32_t)(H[a >> 2][a & 3] - dq), 31);      // (lt << 1) | sign
+            uint32_t bm = ~lt & 0xFFFFu;
+            if (tc.item >= A.n) bm = 0u;                 // (items past the end of the index repeat the last one)
+            while (wave_any(bm != 0u)) {
+                const bool act = bm != 0u;
+                const uint32_t a = (uint32_t)(__ffs((int)bm) - 1) & 15u;
+                bm &= bm - 1u;
+                // the lane's value a: a binary tree of selects over the 16 registers
+                const bool a0 = (a & 1u) != 0u, a1 = (a & 2u) != 0u, a2 = (a & 4u) != 0u, a3 = (a & 8u) != 0u;
+                // (written out value by value and pinned: as an indexed array the compiler would place it in scratch memory)
+                int e0 = a0 ? H[0][1] : H[0][0], e1 = a0 ? H[0][3] : H[0][2], e2 = a0 ? H[1][1] : H[1][0], e3 = a0 ? H[1][3] : H[1][2];
+                int e4 = a0 ? H[2][1] : H[2][0], e5 = a0 ? H[2][3] : H[2][2], e6 = a0 ? H[3][1] : H[3][0], e7 = a0 ? H[3][3] : H[3][2];
+                pin(e0); pin(e1); pin(e2); pin(e3); pin(e4); pin(e5); pin(e6); pin(e7);
+                int f0 = a1 ? e1 : e0, f1 = a1 ? e3 : e2, f2 = a1 ? e5 : e4, f3 = a1 ? e7 : e6;
+                pin(f0); pin(f1); pin(f2); pin(f3);
+                const int hv = a3 ? (a2 ? f3 : f2) : (a2 ? f1 : f0);
+                const uint32_t ql = (uint32_t)(qt * 4) * 16u + (a >> 2) * 16u + 4u * (uint32_t)g4 + (a & 3u);   // wave-local query of the pair
+                uint32_t fa, fn, flag, t0 = 0u, t1 = 0xFFFFFFFFu;
+                int T;
+                float thr;
+                if constexpr (TS)
+                    asm volatile("ds_read_b32 %0, %7\n\tds_read_b32 %1, %8\n\tds_read_b32 %2, %9\n\tds_read_b32 %3, %10\n\t"
+                                 "ds_read_u8 %4, %11\n\tds_read_b32 %5, %12\n\tds_read_b32 %6, %13\n\ts_waitcnt lgkmcnt(0)"
+                                 : "=&v"(fa), "=&v"(fn), "=&v"(T), "=&v"(thr), "=&v"(flag), "=&v"(t0), "=&v"(t1)
+                                 : "v"(lds_fa + 4u * ql), "v"(lds_fn + 4u * ql), "v"(lds_T + 4u * ql), "v"(lds_thr + 4u * ql),
+                                   "v"(lds_flag + ql), "v"(lds_t0 + 4u * ql), "v"(lds_t1 + 4u * ql) : "memory");
+                else
+                    asm volatile("ds_read_b32 %0, %5\n\tds_read_b32 %1, %6\n\tds_read_b32 %2, %7\n\tds_read_b32 %3, %8\n\t"
+                                 "ds_read_u8 %4, %9\n\ts_waitcnt lgkmcnt(0)"
+                                 : "=&v"(fa), "=&v"(fn), "=&v"(T), "=&v"(thr), "=&v"(flag)
+                                 : "v"(lds_fa + 4u * ql), "v"(lds_fn + 4u * ql), "v"(lds_T + 4u * ql), "v"(lds_thr + 4u * ql),
+                                   "v"(lds_flag + ql) : "memory");
+                bool ok = act && (tc.mk & fn) == fa;
+                if constexpr (TS) {
+                    if (has_ts) ok = ok && tc.ts >= t0 && tc.ts <= t1;
+                }
+                const int raw = hv + T;                  // the accumulator input was -T exactly
+                uint32_t hi;
+                if constexpr (SCALED) {
+                    const float sv = (float)raw * tc.sc;
+                    ok = ok && sv >= thr;
+                    hi = ord_f32(sv);
+                } else {
+                    ok = ok && raw >= __float_as_int(thr);
+                    hi = ord_i32(raw);
+                }
+                if (ok && flag) ok = filter_pass(A.filters[s_qi[ql]], tc.mk, has_ts, tc.ts);
+                const u64 okm = wave_ballot(ok);
+                if (okm == 0ull) continue;
+                const uint32_t nok = (uint32_t)__popcll(okm);
+                const u64 key = ((u64)hi << 32) | (u64)(uint32_t)~(uint32_t)tc.item;
+                if (queued + nok <= (uint32_t)DENSE_QCAP) {
+                    const uint32_t pos = queued + __builtin_amdgcn_mbcnt_hi((uint32_t)(okm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)okm, 0u));
+                    if (ok)
+                        asm volatile("ds_write_b64 %0, %1\n\tds_write_b8 %2, %3"
+                                     :: "v"(lds_qkey + 8u * pos), "v"(key), "v"(lds_qql + pos), "v"(ql) : "memory");
+                    queued += nok;
+                } else {                                  // queue full (rare): straight to the segments
+                    if (ok) {
+                        const uint32_t p2 = atomicAdd(&cnt[ql], 1u);
+                        if (p2 < A.cap) A.seg[((u64)slot * A.B + s_qi[ql]) * A.cap + p2] = key;
+                        if (p2 + 1 + DENSE_SLACK > A.cap) need_compact = 1u;
+                    }
+                    direct = 1u;
                 }
             }
-        };
-        one(Q0{}); one(Q1{}); one(Q2{}); one(Q3{});
+        }
     };
 
     auto consume = [&](const DenseStage& C, const u64 item0) __attribute__((always_inline)) {
@@ -415,12 +426,12 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
                     // min(g T_min, g T_max) - 3: one of the two is the valid side (0 * inf = NaN for a zero scale is dropped
                     // by the minimum); 2 of slack for the rounding of g and of the products, 1 because the conversion rounds
                     // towards zero, which for a negative value is upwards by less than 1
-                    tc.dtest[r] = (int)fminf(fminf(__builtin_fmaf(g, tmin_f[r], -3.0f), __builtin_fmaf(g, tmax_f[r], -3.0f)), 536870912.0f);
+                    tc.dtest[r] = (int)fminf(fminf(__builtin_fmaf(g, tmin_f[r], -3.0f), __builtin_fmaf(g, tmax_f[r], -3.0f)), 268435456.0f);
                 }
             }
-            // Branch-free over the quarters: products, 8 v_max3 over the 16 accumulators, the excess over the quarter's
-            // test value folded into one running maximum; one compare and one branch per tile.
-            int excess = INT_MIN;
+            // Branch-free over the quarters: products, 8 v_max3 over the 16 accumulators, one compare into a scalar
+            // mask of the quarters that fired; one branch per tile.
+            uint32_t fired = 0;
             v4i X[4];
             auto quarter = [&](auto QT) __attribute__((always_inline)) {
                 constexpr int qt = decltype(QT)::value;
@@ -429,14 +440,14 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
                     int m = INT_MIN;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) m = dense_max_acc(m, X[i]);
-                    excess = max(excess, m - tc.dtest[qt]);       // (|m|, |dtest| < 2^30 + 2^21: no overflow)
+                    fired |= wave_any(m >= tc.dtest[qt]) ? (1u << qt) : 0u;
                 }
             };
             quarter(Q0{});
             if constexpr (NQT > 1) { if (nqt > 1) quarter(Q1{}); }
             if constexpr (NQT > 2) { if (nqt > 2) quarter(Q2{}); }
             if constexpr (NQT > 3) { if (nqt > 3) quarter(Q3{}); }
-            if (__builtin_expect(wave_any(excess >= 0), 0)) tile_hot(b, tc);
+            if (__builtin_expect(fired != 0u, 0)) tile_hot(b, tc, fired);
         }
         // End of the chunk, the one place where this wave touches global memory besides its direct loads: write the
         // queue out once it is half full, shrink segments that are nearly full, re-read the bounds now and then.  (Each
@@ -447,8 +458,6 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
             direct = 0u;
             if (wave_any(need_compact != 0u)) {
                 compact_full_segments<DENSE_SLACK>(A, qs, slot, 0, NQW, scratch_all[wib], lane, s_qi);
-                if (lane == 0) *qcount = 0;              // (the histogram shared the queue's memory)
-                wave_sync();
                 need_compact = 0u;
                 since_refresh = 1u << 30;                // bounds moved
             }

@@ -265,6 +265,7 @@ __device__ __forceinline__ float lowered_pos(float thr)      // same, and "no us
 // keep a loop-invariant value in its registers instead of re-materialising it every iteration
 __device__ __forceinline__ void pin(v4i& x) { asm volatile("" : "+v"(x)); }
 __device__ __forceinline__ void pin(v4f& x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ void pin(int& x) { asm volatile("" : "+v"(x)); }
 
 // Query-side state in LDS (pointers to arrays indexed by the wave-local query number).
 struct QSide {
