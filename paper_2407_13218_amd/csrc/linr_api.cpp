@@ -344,7 +344,7 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
     if (dg) {
         p->qg = dg;
         p->dense = 1;
-        p->coop = 1;                                    // (a workgroup is one walker of the sweep, as in the cooperative kernels)
+        p->coop = 1;                                    // (sweep schedule and slot count as for the cooperative kernels)
         p->generic = 0;
         p->chunk_items = 128;
         p->max_batch = dmax;
@@ -423,7 +423,7 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
         if (p->bits == 1 && bpc > 4) bpc = 4;           // every wave is a chunk-slot: 256 CUs x 4 x 4 waves = LINR_MAX_SLOTS
     }
     p->n_chunks = (ix->n + p->chunk_items - 1) / p->chunk_items;
-    uint64_t waves_wanted = p->n_chunks * (p->dense ? LINR_WAVES_PER_BLOCK : p->nsplit);   // (dense: a workgroup per chunk)
+    uint64_t waves_wanted = p->n_chunks * p->nsplit;
     uint64_t grid = (uint64_t)ix->num_cu * bpc;
     uint64_t grid_needed = (waves_wanted + LINR_WAVES_PER_BLOCK - 1) / LINR_WAVES_PER_BLOCK;
     if (grid > grid_needed) grid = grid_needed;

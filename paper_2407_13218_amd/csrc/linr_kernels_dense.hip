@@ -21,23 +21,24 @@
 //     tests them in quarters of 64 with the quarter's own T_min / T_max (data with dense clusters is unforgiving
 //     here: a test that is 10 % loose lets a query's whole cluster through);
 //   * a wave keeps up to 16 query groups (256 queries, 64 registers of fragments + 64 of bounds) and the four
-//     waves of a workgroup either split a batch of up to 1024 queries (every chunk is read from HBM once per
-//     search for ANY batch size up to 1024) or, for smaller batches, split the tiles of each chunk;
+//     waves of a workgroup either split a batch of up to 1024 queries between them (every item is read from HBM
+//     once per search for ANY batch size up to 1024; the other three waves find it in L2) or, for smaller
+//     batches, walk different chunks;
 //   * the loop over a tile is branch-free: products, maxima and compares of all quarters, then ONE branch.  A tile
 //     that fired recomputes the products of the quarters concerned (the fragments are still in registers) and
-//     narrows them to groups, then to (query, item) pairs by the exact predicate and ranking value;
-//   * chunks arrive through direct global -> LDS loads into a ring of stages (no staging registers), consumed
-//     with hand-placed LDS reads; candidate keys are queued in LDS and written out in bulk.
+//     narrows them to (query, item) pairs by the exact predicate and ranking value;
+//   * every wave is autonomous: its items arrive through direct global -> LDS loads into a private ring of
+//     steps (no staging registers, no workgroup barrier per step), consumed with hand-placed LDS reads; candidate
+//     keys are queued in LDS and written out in bulk.
 // The survivors' keys go to the same per-(slot, query) segments, bounds, sweeps and merges as in the other kernels.
 #include "linr_scan_common.h"
 #include <type_traits>
 
-#define DENSE_CH 128                   // items per chunk (8 tiles of 16)
-#define DENSE_NST 4                    // ring stages: DENSE_NST - 1 chunks in flight per workgroup
-#define DENSE_DMA 4                    // direct loads every wave issues per chunk (always this many)
+#define DENSE_CH 128                   // items per chunk, the unit of the sweep plan and of a wave's walk
+#define DENSE_SUB 32                   // items per step of a wave (two tiles of 16)
 #define DENSE_QCAP 192                 // keys a wave queues in LDS before writing them out
 #define DENSE_SLACK LINR_DENSE_SLACK   // room a segment must have beyond k: the queue's keys + what one chunk can add per query
-#define DENSE_SCRATCH_WORDS 516        // per wave: queue (keys, query numbers, count) / compaction histogram / flush prefix
+#define DENSE_SCRATCH_WORDS 516        // per wave: queue (keys, query numbers) / compaction histogram / flush prefix
 // Stand-in for "no bound" (-) and "no query" (+) among the integer bounds T.  |raw| < 2^20, so raw - T stays within
 // +-(2^29 + 2^20) and its difference to a test value in [-2^29 (1 + 2^-11) - 3, 2^28] cannot overflow 32 bits.
 #define DENSE_BIG (1 << 29)
@@ -45,32 +46,12 @@
 // s_waitcnt immediate that waits for the vector-memory counter only (gfx9 encoding)
 #define DENSE_WAIT_VM(n) (((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
 
-struct DenseStage {
-    v4i a[512];                        // 8 KB of rows: tile t (16 items) at a[64 t + lane], as the lanes fetched it
-    uint32_t mk[DENSE_CH];
-    float sc[DENSE_CH];
-    uint32_t ts[DENSE_CH];
-};
-
+// The ring and the per-query arrays are read with hand-placed LDS instructions: for an LDS access the compiler can
+// see, it would wait until every outstanding direct load has landed, i.e. for the memory latency of the step
+// requested last.  That a stage's loads have landed is established by the counted wait of the step loop.
 __device__ __forceinline__ uint32_t dense_lds_addr(const void* p)
 {
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
-}
-// The ring is read with hand-placed LDS instructions: for a read the compiler can see, it would wait until every
-// outstanding direct load has landed.  That a stage's loads have landed is established by the step protocol of
-// the kernel (counted wait + workgroup barrier).
-// Fragments of a tile for this lane plus its item's side columns (stage layout: mk, sc, ts 512 bytes apart).
-template <bool TS>
-__device__ __forceinline__ void dense_read_tile(uint32_t addr_a, uint32_t addr_mk, v4i& a, uint32_t& mk, float& sc, uint32_t& ts)
-{
-    if constexpr (TS)
-        asm volatile("ds_read_b128 %0, %4\n\tds_read_b32 %1, %5\n\tds_read_b32 %2, %5 offset:512\n\tds_read_b32 %3, %5 offset:1024\n\t"
-                     "s_waitcnt lgkmcnt(0)" : "=&v"(a), "=&v"(mk), "=&v"(sc), "=&v"(ts) : "v"(addr_a), "v"(addr_mk) : "memory");
-    else {
-        asm volatile("ds_read_b128 %0, %3\n\tds_read_b32 %1, %4\n\tds_read_b32 %2, %4 offset:512\n\ts_waitcnt lgkmcnt(0)"
-                     : "=&v"(a), "=&v"(mk), "=&v"(sc) : "v"(addr_a), "v"(addr_mk) : "memory");
-        ts = 0u;
-    }
 }
 
 __device__ __forceinline__ int dense_floor_to_int(float x)      // floor(x) clamped to +-DENSE_BIG (x may be +-inf)
@@ -104,11 +85,13 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
     constexpr int NQW = NG * 16;                         // query positions per wave
     constexpr int NQT = NG / 4;                          // 64-query quarters per wave
     constexpr bool SCALED = (VK == LINR_VK_I8_SCALED);
-    constexpr int TPC = DENSE_CH / 16;
+    constexpr int STG = 2048 + 256 + (TS ? 256 : 0);     // bytes of a ring stage: rows of two tiles, masks + scales, timestamps
+    constexpr int NST = TS ? 4 : 5;                      // ring stages per wave: NST - 1 steps in flight
+    constexpr int DMA = TS ? 4 : 3;                      // direct loads per step (always this many)
     static_assert(NG % 4 == 0 && NG <= 16, "query groups per wave come in quarters of four");
     static_assert(DENSE_SCRATCH_WORDS >= 2 * NQW + 1 + 3 && DENSE_SCRATCH_WORDS >= 2 * DENSE_QCAP + DENSE_QCAP / 4 + 4, "scratch");
 
-    __shared__ DenseStage ring[DENSE_NST];
+    __shared__ __attribute__((aligned(16))) unsigned char ring_all[WPB][NST * STG];
     __shared__ DenseQ<NQW, TS> QS;
     __shared__ uint32_t cnt_all[WPB][NQW];
     __shared__ __attribute__((aligned(8))) uint32_t scratch_all[WPB][DENSE_SCRATCH_WORDS];
@@ -180,8 +163,11 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
 
     v4i c[NG];                                           // accumulator inputs: -T of the lane's four queries of each group
     float tmin_f[NQT], tmax_f[NQT];                      // per quarter: T_min lowered / T_max raised over its queries that have a bound
+    float twmin = 0.0f, twmax = 0.0f;                    // the same over all quarters of the wave that hold queries
     // Bounds: every wave reads those of its queries into its own arrays and derives its accumulator inputs from them.
     auto load_bounds = [&]() __attribute__((always_inline)) {
+        twmin = 3.0e38f;
+        twmax = -3.0e38f;
 #pragma unroll
         for (int r = 0; r < NQT; ++r) {                  // iteration r of the lanes covers exactly quarter r
             const uint32_t ql = (uint32_t)(r * 64 + lane);
@@ -210,6 +196,7 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
             const bool bounded = tmin <= tmax;
             tmin_f[r] = bounded ? (float)tmin * 0.99951f : 0.0f;
             tmax_f[r] = bounded ? (float)tmax * 1.00049f : 0.0f;
+            if (wave_any(qi < A.B)) { twmin = fminf(twmin, tmin_f[r]); twmax = fmaxf(twmax, tmax_f[r]); }
         }
         wave_sync();
 #pragma unroll
@@ -240,57 +227,61 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
         __builtin_amdgcn_s_waitcnt(DENSE_WAIT_VM(0));
     };
 
-    // ---- the chunk ring
+    // ---- the wave's private ring of steps.  A step is DENSE_SUB = 32 items (two tiles): 2 KB of rows, their masks and
+    //      row scales (one load: lanes 0 .. 31 fetch masks, lanes 32 .. 63 scales) and, if the index has them, their
+    //      timestamps.  Nothing is shared between waves, so no workgroup barrier is needed per step: a wave waits on its
+    //      own load counter only.  Waves that serve different query sets of the same slot fetch the same items, each for
+    //      itself (the second to fourth fetch is an L2 hit; a barrier now and then keeps them close enough for that).
     typedef const __attribute__((address_space(1))) void* gptr;
     typedef __attribute__((address_space(3))) void* lptr;
+    unsigned char* const ring = ring_all[wib];
+    const uint32_t ring_lds = dense_lds_addr(ring);
+    const uint32_t nwalk = gridDim.x * wps;              // walkers of the sweep: one per slot
     SweepWalk ahead;
-    ahead.init_strided(blockIdx.x, gridDim.x, A);
-    const uint32_t n_dense32 = (uint32_t)A.n_dense;
-    const uint32_t n_mine = blockIdx.x < n_dense32 ? (n_dense32 - blockIdx.x + gridDim.x - 1) / gridDim.x : 0u;
-    u64 item0_last = 0;
-    // byte offsets of what this lane fetches, relative to the start of a chunk's rows / side columns: they do not
-    // change from chunk to chunk, so a whole chunk costs no per-lane address arithmetic (uniform base + lane offset)
-    const uint32_t off_row0 = (uint32_t)(((wib * 2) * 16 + col) * 64 + g4 * 16), off_row1 = off_row0 + 16u * 64u;
-    const uint32_t off_side = (uint32_t)lane * 4u;
-    // which side column this wave fetches (wave 0 the masks, wave 1 the row scales, wave 2 the timestamps; wave 3 -- and
-    // the others where a column does not exist -- the masks once more, to the same place: the same bytes, only to keep
-    // the per-wave load count uniform) and where in a stage it goes
-    const uint32_t* side_col = A.mask;
-    uint32_t side_dst = (uint32_t)offsetof(DenseStage, mk);
-    if (SCALED && wib == 1) { side_col = (const uint32_t*)A.row_scale; side_dst = (uint32_t)offsetof(DenseStage, sc); }
-    if (has_ts && wib == 2) { side_col = A.ts; side_dst = (uint32_t)offsetof(DenseStage, ts); }
-    // Every wave issues the same four loads per chunk: two tiles of rows and the two halves of its side column.
-    // Items past the end of the index repeat the last one; their candidates are discarded by the `item < n` test.
-    // Returns the first item of the chunk it fetched (past the end of the sweep: the last valid chunk once more).
-    auto issue_next = [&](DenseStage& S) __attribute__((always_inline)) -> u64 {
-        if (ahead.valid()) item0_last = ahead.lc() * A.stride * DENSE_CH;
-        const u64 item0 = item0_last;
-        uint32_t* dst = (uint32_t*)((char*)&S + side_dst);
-        if (item0 + DENSE_CH <= A.n) {                   // uniform; all chunks but possibly the last one
-            const char* eb = (const char*)A.emb + item0 * 64;
-            const char* cb = (const char*)(side_col + item0);
-            __builtin_amdgcn_global_load_lds((gptr)(eb + off_row0), (lptr)&S.a[(wib * 2) * 64], 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr)(eb + off_row1), (lptr)&S.a[(wib * 2 + 1) * 64], 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr)(cb + off_side), (lptr)dst, 4, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr)(cb + off_side + 256u), (lptr)(dst + 64), 4, 0, 0);
-        } else {                                         // ragged end: items past the last one repeat it
+    ahead.init_strided(slot, nwalk, A);
+    // every wave of a workgroup runs the step count of the workgroup's first slot (the largest); steps past the end of
+    // a wave's own walk fetch its last chunk once more and consume nothing
+    const uint32_t n_dense32 = (uint32_t)A.n_dense, slot_first = blockIdx.x * wps;
+    const uint32_t n_wg = slot_first < n_dense32 ? (n_dense32 - slot_first + nwalk - 1) / nwalk : 0u;
+    const uint32_t nsteps = n_wg * (DENSE_CH / DENSE_SUB);
+    // what this lane fetches, relative to the first item of a step (the same for every step)
+    const uint32_t off_row = (uint32_t)(col * 64 + g4 * 16);
+    const uint32_t side_lane = (uint32_t)lane & 31u;
+    const char* const side_base = (SCALED && lane >= 32) ? (const char*)(A.row_scale + side_lane) : (const char*)(A.mask + side_lane);
+    const char* const ts_base = has_ts ? (const char*)(A.ts + side_lane) : (const char*)(A.mask + side_lane);
+    u64 f_item = 0;                                      // first item of the chunk being fetched
+    uint32_t f_sub = 0;                                  // its next step
+    bool f_valid = false;                                // (false: past the end of this wave's walk)
+    uint32_t stage_info = 0;                             // lane s: first item / 32 of the step in stage s, bit 31: consume it
+    auto fetch = [&](uint32_t stage) __attribute__((always_inline)) {
+        if (f_sub == 0) {
+            f_valid = ahead.valid();
+            if (f_valid) f_item = ahead.lc() * A.stride * DENSE_CH;
+            ahead.advance();
+        }
+        const u64 item = f_item + f_sub * DENSE_SUB;
+        f_sub = (f_sub + 1) & (DENSE_CH / DENSE_SUB - 1);
+        if ((uint32_t)lane == stage) stage_info = (uint32_t)(item >> 5) | (f_valid ? 0x80000000u : 0u);
+        unsigned char* const dst = ring + stage * STG;
+        if (item + DENSE_SUB <= A.n) {                   // uniform; all steps but those at the end of the index
+            const char* eb = (const char*)A.emb + item * 64 + off_row;
+            __builtin_amdgcn_global_load_lds((gptr)eb, (lptr)dst, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr)(eb + 1024), (lptr)(dst + 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr)(side_base + item * 4), (lptr)(dst + 2048), 4, 0, 0);
+            if constexpr (TS) __builtin_amdgcn_global_load_lds((gptr)(ts_base + item * 4), (lptr)(dst + 2304), 4, 0, 0);
+        } else {                                         // items past the last one repeat it (discarded later by `item < n`)
             const u64 last = A.n - 1;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                const int t = wib * 2 + j;
-                u64 it = item0 + (u64)(t * 16 + col);
+                u64 it = item + (u64)(j * 16 + col);
                 it = it < last ? it : last;
-                __builtin_amdgcn_global_load_lds((gptr)((const char*)A.emb + it * 64 + g4 * 16), (lptr)&S.a[t * 64], 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gptr)((const char*)A.emb + it * 64 + g4 * 16), (lptr)(dst + j * 1024), 16, 0, 0);
             }
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                u64 it = item0 + (u64)(h * 64 + lane);
-                it = it < last ? it : last;
-                __builtin_amdgcn_global_load_lds((gptr)(side_col + it), (lptr)(dst + h * 64), 4, 0, 0);
-            }
+            u64 it = item + side_lane;
+            it = it < last ? it : last;
+            __builtin_amdgcn_global_load_lds((gptr)(side_base + (it - side_lane) * 4), (lptr)(dst + 2048), 4, 0, 0);
+            if constexpr (TS) __builtin_amdgcn_global_load_lds((gptr)(ts_base + (it - side_lane) * 4), (lptr)(dst + 2304), 4, 0, 0);
         }
-        ahead.advance();
-        return item0;
     };
 
     // What the slow path knows about the tile it works on (one item per lane).
@@ -406,52 +397,74 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
         }
     };
 
-    auto consume = [&](const DenseStage& C, const u64 item0) __attribute__((always_inline)) {
-        const uint32_t base_a = dense_lds_addr(&C.a[0]) + (uint32_t)lane * 16u;
-        const uint32_t base_mk = dense_lds_addr(&C.mk[0]) + (uint32_t)col * 4u;
-        // this wave's tiles of the chunk: tlane, tlane + wps, ...
-#pragma unroll 1
-        for (uint32_t t = tlane; t < (uint32_t)TPC; t += wps) {
-            v4i b;
-            TileCtx tc;
-            dense_read_tile<TS>(base_a + t * 1024u, base_mk + t * 64u, b, tc.mk, tc.sc, tc.ts);
-            tc.item = item0 + t * 16 + col;
-            // the first test's right side for this lane's item (see the header comment); raw ranking: "max >= 0"
-#pragma unroll
-            for (int r = 0; r < NQT; ++r) tc.dtest[r] = 0;
-            if constexpr (SCALED) {
-                const float g = __builtin_amdgcn_rcpf(tc.sc * rho) - 1.0f;
-#pragma unroll
-                for (int r = 0; r < NQT; ++r) {
-                    // min(g T_min, g T_max) - 3: one of the two is the valid side (0 * inf = NaN for a zero scale is dropped
-                    // by the minimum); 2 of slack for the rounding of g and of the products, 1 because the conversion rounds
-                    // towards zero, which for a negative value is upwards by less than 1
-                    tc.dtest[r] = (int)fminf(fminf(__builtin_fmaf(g, tmin_f[r], -3.0f), __builtin_fmaf(g, tmax_f[r], -3.0f)), 268435456.0f);
-                }
-            }
-            // Branch-free over the quarters: products, 8 v_max3 over the 16 accumulators, one compare into a scalar
-            // mask of the quarters that fired; one branch per tile.
-            uint32_t fired = 0;
-            v4i X[4];
-            auto quarter = [&](auto QT) __attribute__((always_inline)) {
-                constexpr int qt = decltype(QT)::value;
-                if constexpr (qt < NQT) {
-                    products(X, QT, b);
-                    int m = INT_MIN;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) m = dense_max_acc(m, X[i]);
-                    fired |= wave_any(m >= tc.dtest[qt]) ? (1u << qt) : 0u;
-                }
-            };
-            quarter(Q0{});
-            if constexpr (NQT > 1) { if (nqt > 1) quarter(Q1{}); }
-            if constexpr (NQT > 2) { if (nqt > 2) quarter(Q2{}); }
-            if constexpr (NQT > 3) { if (nqt > 3) quarter(Q3{}); }
-            if (__builtin_expect(fired != 0u, 0)) tile_hot(b, tc, fired);
+    // ---- one tile (16 items, one per lane and k-slice) against the wave's queries.  Branch-free over the quarters:
+    //      products, 8 v_max3 over the 16 accumulators of a quarter; then ONE compare of the maximum over all quarters
+    //      with the test value of the wave's whole range of bounds.  Only if that fires are the quarters' own (tighter)
+    //      test values made and compared, and the quarters that still fire handed to the slow path.
+    auto score_tile = [&](const v4i& b, uint32_t mk, float sc, uint32_t ts, u64 item) __attribute__((always_inline)) {
+        // right side of the first test for this lane's item (see the header comment): min(g T_min, g T_max) - 3.  One
+        // of the two is the valid side (0 * inf = NaN for a zero scale is dropped by the minimum); 2 of slack for the
+        // rounding of g and of the products, 1 because the conversion rounds towards zero, which for a negative
+        // value is upwards by less than 1.  Raw ranking: "max >= 0".
+        float g = 0.0f;
+        int dqw = 0;
+        if constexpr (SCALED) {
+            g = __builtin_amdgcn_rcpf(sc * rho) - 1.0f;
+            dqw = (int)fminf(fminf(__builtin_fmaf(g, twmin, -3.0f), __builtin_fmaf(g, twmax, -3.0f)), 268435456.0f);
         }
-        // End of the chunk, the one place where this wave touches global memory besides its direct loads: write the
-        // queue out once it is half full, shrink segments that are nearly full, re-read the bounds now and then.  (Each
-        // of these empties the ring: they are kept rare.)
+        int mq[4] = {INT_MIN, INT_MIN, INT_MIN, INT_MIN};
+        v4i X[4];
+        auto quarter = [&](auto QT) __attribute__((always_inline)) {
+            constexpr int qt = decltype(QT)::value;
+            if constexpr (qt < NQT) {
+                products(X, QT, b);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) mq[qt] = dense_max_acc(mq[qt], X[i]);
+            }
+        };
+        quarter(Q0{}); quarter(Q1{}); quarter(Q2{}); quarter(Q3{});
+        const int m = max(max(mq[0], mq[1]), max(mq[2], mq[3]));
+        if (__builtin_expect(wave_any(m >= dqw), 0)) {
+            TileCtx tc;
+            tc.mk = mk; tc.sc = sc; tc.ts = ts; tc.item = item;
+            uint32_t fired = 0;
+#pragma unroll
+            for (int r = 0; r < NQT; ++r) {
+                tc.dtest[r] = 0;
+                if constexpr (SCALED)
+                    tc.dtest[r] = (int)fminf(fminf(__builtin_fmaf(g, tmin_f[r], -3.0f), __builtin_fmaf(g, tmax_f[r], -3.0f)), 268435456.0f);
+                fired |= wave_any(mq[r] >= tc.dtest[r]) ? (1u << r) : 0u;
+            }
+            if (fired != 0u) tile_hot(b, tc, fired);
+        }
+    };
+
+    // ---- one step: both tiles' fragments and side values are read at once, then each tile is scored
+    auto consume = [&](uint32_t stage) __attribute__((always_inline)) {
+        const uint32_t info = __builtin_amdgcn_readlane(stage_info, stage);
+        if ((info >> 31) == 0u) return;
+        const u64 item0 = (u64)(info & 0x7FFFFFFFu) << 5;
+        const uint32_t addr_a = ring_lds + stage * STG + (uint32_t)lane * 16u;
+        const uint32_t addr_s = ring_lds + stage * STG + 2048u + (uint32_t)col * 4u;
+        v4i b0, b1;
+        uint32_t mk0, mk1, ts0 = 0u, ts1 = 0u;
+        float sc0, sc1;
+        if constexpr (TS)
+            asm volatile("ds_read_b128 %0, %8\n\tds_read_b128 %1, %8 offset:1024\n\tds_read_b32 %2, %9\n\tds_read_b32 %3, %9 offset:64\n\t"
+                         "ds_read_b32 %4, %9 offset:128\n\tds_read_b32 %5, %9 offset:192\n\tds_read_b32 %6, %9 offset:256\n\t"
+                         "ds_read_b32 %7, %9 offset:320\n\ts_waitcnt lgkmcnt(0)"
+                         : "=&v"(b0), "=&v"(b1), "=&v"(mk0), "=&v"(mk1), "=&v"(sc0), "=&v"(sc1), "=&v"(ts0), "=&v"(ts1)
+                         : "v"(addr_a), "v"(addr_s) : "memory");
+        else
+            asm volatile("ds_read_b128 %0, %6\n\tds_read_b128 %1, %6 offset:1024\n\tds_read_b32 %2, %7\n\tds_read_b32 %3, %7 offset:64\n\t"
+                         "ds_read_b32 %4, %7 offset:128\n\tds_read_b32 %5, %7 offset:192\n\ts_waitcnt lgkmcnt(0)"
+                         : "=&v"(b0), "=&v"(b1), "=&v"(mk0), "=&v"(mk1), "=&v"(sc0), "=&v"(sc1)
+                         : "v"(addr_a), "v"(addr_s) : "memory");
+        score_tile(b0, mk0, sc0, ts0, item0 + (uint32_t)col);
+        score_tile(b1, mk1, sc1, ts1, item0 + (uint32_t)(16 + col));
+        // The one place where this wave touches global memory besides its direct loads: write the queue out once it is
+        // half full, shrink segments that are nearly full, re-read the bounds now and then.  (Each of these waits for
+        // everything in flight: they are kept rare.)
         ++since_refresh;
         if (queued >= (uint32_t)(DENSE_QCAP / 2) || wave_any(direct != 0u)) {
             flush_queue();
@@ -460,41 +473,31 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
                 compact_full_segments<DENSE_SLACK>(A, qs, slot, 0, NQW, scratch_all[wib], lane, s_qi);
                 need_compact = 0u;
                 since_refresh = 1u << 30;                // bounds moved
+                __builtin_amdgcn_s_waitcnt(DENSE_WAIT_VM(0));
             }
         }
-        if (since_refresh >= 256u) {
+        if (since_refresh >= 1024u) {
             load_bounds();
             since_refresh = 0;
+            __builtin_amdgcn_s_waitcnt(DENSE_WAIT_VM(0));
         }
     };
 
-    // One step: wait until the chunk in stage ST has landed for every wave, refill the stage consumed one step ago with
-    // the chunk DENSE_NST - 1 steps ahead, then consume stage ST.  Every wave always issues DENSE_DMA loads per step
-    // (past the end of the sweep it reloads the last valid chunk), so "at most (DENSE_NST - 2) * DENSE_DMA loads
-    // outstanding" means: this wave's share of the chunk about to be consumed has landed.  The loop over the chunks is
-    // unrolled by the number of stages, so that stage numbers are constants and the chunks' first items stay in
-    // scalar registers.
-    u64 first_item[DENSE_NST];
-    auto step = [&](auto ST) __attribute__((always_inline)) {
-        constexpr int st = decltype(ST)::value;
-        constexpr int refill = st == 0 ? DENSE_NST - 1 : st - 1;
-        __builtin_amdgcn_s_waitcnt(DENSE_WAIT_VM((DENSE_NST - 2) * DENSE_DMA));
-        __builtin_amdgcn_s_barrier();
-        first_item[refill] = issue_next(ring[refill]);
-        if (nqt > 0) consume(ring[st], first_item[st]);
-    };
-    static_assert(DENSE_NST == 4, "the chunk loop is unrolled for four stages");
-    if (n_mine) {
-        first_item[0] = issue_next(ring[0]);
-        first_item[1] = issue_next(ring[1]);
-        first_item[2] = issue_next(ring[2]);
-        for (uint32_t ch = 0; ch < n_mine; ch += DENSE_NST) {
-            step(std::integral_constant<int, 0>{});
-            if (ch + 1 < n_mine) step(std::integral_constant<int, 1>{});
-            if (ch + 2 < n_mine) step(std::integral_constant<int, 2>{});
-            if (ch + 3 < n_mine) step(std::integral_constant<int, 3>{});
+    // The loop over the steps.  Steps 0 .. NST - 2 are fetched ahead; iteration i waits until at most the loads of the
+    // NST - 2 steps after it are outstanding (every step is exactly DMA loads and nothing else is in flight: whatever
+    // else touches memory ends with a wait for all of it), refills the stage consumed one iteration ago with the step
+    // NST - 1 ahead, and consumes its own stage.
+    if (nsteps) {
+        for (uint32_t sg = 0; sg + 1 < (uint32_t)NST; ++sg) fetch(sg);
+        uint32_t st = 0;
+        for (uint32_t i = 0; i < nsteps; ++i) {
+            __builtin_amdgcn_s_waitcnt(DENSE_WAIT_VM((NST - 2) * DMA));
+            fetch(st == 0 ? (uint32_t)NST - 1 : st - 1);
+            if (nqt > 0) consume(st);
+            st = st + 1 == (uint32_t)NST ? 0u : st + 1;
+            if (nsets > 1 && (i & 15u) == 15u) __builtin_amdgcn_s_barrier();
         }
-        // nothing of this workgroup may still be on its way to LDS when its waves end
+        // nothing of this wave may still be on its way to LDS when it ends
         __builtin_amdgcn_s_waitcnt(DENSE_WAIT_VM(0));
     }
     if (nqt > 0) {
