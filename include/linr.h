@@ -58,8 +58,13 @@ enum {
 /* flags of linr_search_filtered */
 enum {
     LINR_FILTERS_ON_DEVICE = 0,  /* default: `filters` is a device pointer                 */
-    LINR_FILTERS_ON_HOST = 1     /* `filters` is a host pointer: validated, then copied    */
+    LINR_FILTERS_ON_HOST = 1,    /* `filters` is a host pointer: validated, then copied    */
+    LINR_PLAN_MASKING = 2,       /* score every item, filter folded into the scan          */
+    LINR_PLAN_PREFILTER = 4      /* explicit pre-filtering (linr_search_filtered_prefilter) */
 };
+
+/* the two ways of answering a filtered search (Sec. 3.1.2) */
+enum { LINR_STRATEGY_MASKING = 0, LINR_STRATEGY_PREFILTER = 1 };
 
 #define LINR_MAX_ANY 4
 #define LINR_MAX_K   8192
@@ -148,11 +153,33 @@ int linr_search_workspace_bytes(const linr_index*, uint32_t B, uint32_t m, uint3
  * B == 0 is a no-op.  Errors: LINR_E_K, LINR_E_SHAPE (m == 0 or m > LINR_MAX_M),
  * LINR_E_NOT_LOADED, LINR_E_WORKSPACE, LINR_E_NULL, LINR_E_FILTER (host filters:
  * n_any > LINR_MAX_ANY, ts_min > ts_max), LINR_E_HIP.
+ *
+ * Strategy (Sec. 3.1.2; the trade-off of Sec. 5.3.1 - 5.3.2): the search either scores every
+ * item with the filter folded into the scan ("masking") or decides feasibility first and
+ * scores only the feasible (item, query) pairs (explicit pre-filtering, the path of
+ * linr_search_filtered_prefilter, whose notes on LINR_COUNT_OVERFLOW then apply).  Results
+ * are identical.  LINR_PLAN_MASKING / LINR_PLAN_PREFILTER force one.  With neither flag the
+ * library decides -- linr_plan_filtered's choice -- where it can read the filters
+ * (LINR_FILTERS_ON_HOST) and `workspace_bytes` also covers
+ * linr_search_prefilter_workspace_bytes; otherwise it masks.
  */
 int linr_search_filtered(const linr_index*, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
                          const linr_filter* filters, uint32_t k,
                          uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
                          void* workspace, uint64_t workspace_bytes, void* hip_stream, uint32_t flags);
+
+/*
+ * The planner behind linr_search_filtered.  From the share of items that carry each mask bit
+ * (sampled when the index was loaded; live updates do not refresh the sample) it estimates each
+ * filter's pass rate, taking attributes as independent and timestamp windows as open, and from
+ * that the cost of both strategies with constants fitted to measurements on an MI355X (a
+ * 1e9 x 64-byte index: pre-filtering wins below about 2.5e8 ... 5e8 feasible pairs for up to 32
+ * queries, below a pass rate of about 0.6 % for hundreds).  *strategy = LINR_STRATEGY_*;
+ * *est_pairs (may be NULL) = estimated feasible (item, query) pairs.  `host_filters` is a
+ * host pointer.  Nothing is launched.
+ */
+int linr_plan_filtered(const linr_index*, const linr_filter* host_filters, uint32_t B, uint32_t m, uint32_t k,
+                       int* strategy, double* est_pairs);
 
 /*
  * linr_search_filtered for callers that cannot allocate device memory or carry a workspace: code
@@ -310,27 +337,6 @@ int linr_search_clauses(const linr_index*, const void* Q, const float* q_scale, 
                         const uint64_t* q_values, const uint8_t* q_counts, uint32_t q_width, uint32_t k,
                         uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
                         void* workspace, uint64_t workspace_bytes, void* hip_stream);
-
-/*
- * linr_search_filtered for callers that cannot allocate device memory or carry a workspace: code
- * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
- * (without the workspace), same kernels and bit-identical results; the scratch memory is a fixed
- * array of LINR_NOALLOC_SCRATCH_BYTES inside the library, one copy per GPU, held from the time the
- * library is loaded until the process ends.  The call allocates and frees nothing (the very first
- * search of a process loads the kernels, as any first launch does: make one call before capturing).
- * A search whose linr_search_workspace_bytes(B, m, k) exceeds LINR_NOALLOC_SCRATCH_BYTES is
- * rejected with LINR_E_TOO_LARGE before anything is enqueued (one query with k <= 1000 fits at
- * any index size; so does B = 4 with k <= 100).  All calls on one GPU share that GPU's array: two
- * such searches that may overlap in time (different streams, different host threads) race -- keep
- * them on one stream, or use linr_search_filtered with separate workspaces.  The array keeps the
- * last call's contents; every counter a search relies on is reset by the search's own first
- * kernel.  The index's device is made current for the duration of the call.
- */
-#define LINR_NOALLOC_SCRATCH_BYTES (64u << 20)
-int linr_search_filtered_noalloc(const linr_index*, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
-                                 const linr_filter* filters, uint32_t k,
-                                 uint32_t* out_ids, float* out_scores, int32_t* out_raw, uint32_t* out_counts,
-                                 void* hip_stream, uint32_t flags);
 
 /*
  * The same search by explicit pre-filtering (Sec. 3.1.2 "KNN with Explicit Pre-Filtering"):

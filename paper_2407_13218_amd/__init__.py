@@ -3,7 +3,7 @@ LiNR, arXiv 2407.13218, Sec. 3.1): HIP kernels behind a C ABI, with a thin ctype
 binding.  Every step of a search runs in the HIP library; there is no CPU fallback."""
 from .binding import (  # noqa: F401
     F32, BF16, I8, BITS, NO_ID, MAX_K, MAX_M,
-    SRC_HOST, SRC_DEVICE_COPY, SRC_DEVICE_BORROW, FILTERS_ON_DEVICE, FILTERS_ON_HOST,
+    SRC_HOST, SRC_DEVICE_COPY, SRC_DEVICE_BORROW, FILTERS_ON_DEVICE, FILTERS_ON_HOST, PLAN_MASKING, PLAN_PREFILTER, STRATEGY_MASKING, STRATEGY_PREFILTER, plan_filtered,
     LinrError, lib_path, load_library,
     index_create, index_load_fp32, index_load_bf16, index_load_int8, index_info, index_destroy,
     search_workspace_bytes, search_filtered, search_filtered_timed, set_tuning, strerror,

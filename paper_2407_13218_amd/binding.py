@@ -18,6 +18,8 @@ MAX_M = 8
 NOALLOC_SCRATCH_BYTES = 64 << 20       # fixed scratch of linr_search_filtered_noalloc
 SRC_HOST, SRC_DEVICE_COPY, SRC_DEVICE_BORROW = 0, 1, 2
 FILTERS_ON_DEVICE, FILTERS_ON_HOST = 0, 1
+PLAN_MASKING, PLAN_PREFILTER = 2, 4          # flags of search_filtered: force a strategy
+STRATEGY_MASKING, STRATEGY_PREFILTER = 0, 1
 MAX_STAGES = 160
 STAGE_NAMES = {0: "init", 1: "scan", 2: "merge", 3: "filter"}
 
@@ -37,6 +39,7 @@ EXPORTS = [
     "linr_index_load_clauses", "linr_search_clauses_workspace_bytes", "linr_search_clauses", "linr_search_clauses_timed",
     "linr_search_clauses_prefilter", "linr_index_upsert_clauses",
     "linr_search_prefilter_workspace_bytes", "linr_search_filtered_prefilter", "linr_search_filtered_noalloc",
+    "linr_plan_filtered",
 ]
 
 
@@ -81,6 +84,8 @@ def load_library():
     sargs = [vp, vp, vp, u32, u32, vp, u32, vp, vp, vp, vp, vp, u64, vp, u32]
     lib.linr_search_filtered.restype = i32
     lib.linr_search_filtered.argtypes = sargs
+    lib.linr_plan_filtered.restype = i32
+    lib.linr_plan_filtered.argtypes = [vp, vp, u32, u32, u32, C.POINTER(C.c_int), C.POINTER(C.c_double)]
     lib.linr_search_prefilter_workspace_bytes.restype = i32
     lib.linr_search_prefilter_workspace_bytes.argtypes = [vp, u32, u32, u32, C.POINTER(u64)]
     lib.linr_search_filtered_prefilter.restype = i32
@@ -216,6 +221,14 @@ def search_filtered(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_r
     _check(load_library().linr_search_filtered(ix, _ptr(Q), _ptr(q_scale), B, m, _ptr(filters), k, _ptr(out_ids),
                                                _ptr(out_scores), _ptr(out_raw), _ptr(out_counts), _ptr(workspace),
                                                workspace_bytes, stream, flags), "linr_search_filtered")
+
+
+def plan_filtered(ix, host_filters, B, m, k):
+    """the planner's choice for these (host, numpy) filters: (STRATEGY_*, estimated feasible (item, query) pairs)"""
+    strategy = C.c_int()
+    pairs = C.c_double()
+    _check(load_library().linr_plan_filtered(ix, _ptr(host_filters), B, m, k, C.byref(strategy), C.byref(pairs)), "linr_plan_filtered")
+    return strategy.value, pairs.value
 
 
 def search_filtered_noalloc(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_raw, out_counts, stream=0,
@@ -440,6 +453,10 @@ class Index:
     def workspace_bytes(self, B, m, k):
         return search_workspace_bytes(self.handle, B, m, k)
 
+    def planned_workspace_bytes(self, B, m, k):
+        """enough for either strategy of search_filtered (masking or explicit pre-filtering)"""
+        return max(search_workspace_bytes(self.handle, B, m, k), search_prefilter_workspace_bytes(self.handle, B, m, k))
+
     # clause lists ------------------------------------------------------------------------------------------
     def load_clauses(self, values, counts, reverse=0):
         """values [n, row_width] (uint64 / int64 bit patterns), counts [n, n_clauses] uint8; numpy or device tensors"""
@@ -507,10 +524,11 @@ class Index:
     def info(self):
         return index_info(self.handle)
 
-    def search(self, Q, filters, k, q_scale=None, workspace=None, want_raw=True, prefilter=False):
+    def search(self, Q, filters, k, q_scale=None, workspace=None, want_raw=True, prefilter=False, strategy="auto"):
         """Q: device tensor [B, m, d] (or [B, d]); filters: numpy records (host) or a device uint8/int32
         tensor of B*40 bytes.  Returns device tensors ids (int32 bits of uint32), scores, raw, counts.
-        prefilter=True: the explicit pre-filtering strategy (linr_search_filtered_prefilter)."""
+        strategy: "auto" (the library's planner decides where it can: host filters), "masking" or "prefilter"
+        (forced through the flags of linr_search_filtered).  prefilter=True: call linr_search_filtered_prefilter itself."""
         import torch
         if Q.dim() == 2:
             Q = Q.unsqueeze(1)
@@ -524,7 +542,13 @@ class Index:
         counts = torch.empty((B,), dtype=torch.int32, device=dev)
         if B == 0:
             return ids, scores, raw, counts
-        nbytes = search_prefilter_workspace_bytes(self.handle, B, m, k) if prefilter else self.workspace_bytes(B, m, k)
+        plan_flag = {"auto": 0, "masking": PLAN_MASKING, "prefilter": PLAN_PREFILTER}[strategy]
+        if prefilter:
+            nbytes = search_prefilter_workspace_bytes(self.handle, B, m, k)
+        elif strategy == "masking":
+            nbytes = self.workspace_bytes(B, m, k)
+        else:
+            nbytes = self.planned_workspace_bytes(B, m, k)
         if workspace is None or workspace.numel() < nbytes:
             workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
         if isinstance(filters, np.ndarray):
@@ -532,8 +556,11 @@ class Index:
         else:
             flags, f = FILTERS_ON_DEVICE, filters
         stream = torch.cuda.current_stream(dev).cuda_stream
-        fn = search_filtered_prefilter if prefilter else search_filtered
-        fn(self.handle, Q, q_scale, B, m, f, k, ids, scores, raw, counts, workspace, workspace.numel(), stream, flags)
+        if prefilter:
+            search_filtered_prefilter(self.handle, Q, q_scale, B, m, f, k, ids, scores, raw, counts, workspace, workspace.numel(), stream, flags)
+        else:
+            search_filtered(self.handle, Q, q_scale, B, m, f, k, ids, scores, raw, counts, workspace, workspace.numel(), stream,
+                            flags | plan_flag)
         self._last_workspace = workspace
         return ids, scores, raw, counts
 

@@ -5,6 +5,7 @@
 #include "linr_internal.h"
 #include <algorithm>
 #include <cstdlib>
+#include <cmath>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -223,6 +224,23 @@ static int load_common(linr_index* ix, int dtype, const void* emb, const float* 
             e = linr_launch_scale_stats(ix->row_scale, n, n_pad, ix->scale_stats + 4, ix->scale_stats, ix->scale_code, nullptr);
         if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
         if (e != hipSuccess) { g_last_hip = (int)e; rc = LINR_E_HIP; release_columns(ix); }
+    }
+    ix->have_bit_freq = 0;
+    if (rc == LINR_OK) {
+        // how often each mask bit is set, from an evenly spaced sample of at most 2^24 items: what the planner of
+        // linr_search_filtered estimates a filter's pass rate from (Sec. 3.1.2: masking or explicit pre-filtering)
+        unsigned long long* dc = nullptr;
+        unsigned long long hc[33];
+        hipError_t e = hipMalloc((void**)&dc, sizeof(hc));
+        if (e == hipSuccess) e = hipMemsetAsync(dc, 0, sizeof(hc), nullptr);
+        if (e == hipSuccess) e = linr_launch_mask_bit_counts(ix->mask, n, (n + (1ull << 24) - 1) >> 24, dc, nullptr);
+        if (e == hipSuccess) e = hipMemcpy(hc, dc, sizeof(hc), hipMemcpyDeviceToHost);
+        if (dc) (void)hipFree(dc);
+        if (e != hipSuccess) { g_last_hip = (int)e; rc = LINR_E_HIP; release_columns(ix); }
+        else if (hc[32]) {
+            for (int b = 0; b < 32; ++b) ix->bit_freq[b] = (float)((double)hc[b] / (double)hc[32]);
+            ix->have_bit_freq = 1;
+        }
     }
     if (rc == LINR_OK) ix->n = n;
     (void)hipSetDevice(dev);
@@ -663,13 +681,109 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
     return LINR_OK;
 }
 
+// ---------------------------------------------------------------------------
+// masking or explicit pre-filtering (Sec. 3.1.2; the trade-off of Sec. 5.3.1 / 5.3.2, Tables 3 - 4)
+// ---------------------------------------------------------------------------
+static int prefilter_impl(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                          const linr_filter* filters, uint32_t k, uint32_t* out_ids, float* out_scores,
+                          int32_t* out_raw, uint32_t* out_counts, void* workspace, uint64_t workspace_bytes,
+                          void* hip_stream, uint32_t flags);
+
+// Share of the items a filter lets through if the attribute bits were independent (each with the frequency sampled
+// when the index was loaded).  The timestamp window is not estimated (taken as "all").
+static double filter_pass_estimate(const float* freq, const linr_filter& f)
+{
+    if (f.all_bits & f.none_bits) return 0.0;
+    double p = 1.0;
+    for (int b = 0; b < 32; ++b) {
+        if ((f.all_bits >> b) & 1u) p *= freq[b];
+        if ((f.none_bits >> b) & 1u) p *= 1.0 - freq[b];
+    }
+    for (uint32_t g = 0; g < f.n_any && g < LINR_MAX_ANY; ++g) {
+        double none_set = 1.0;
+        for (int b = 0; b < 32; ++b)
+            if ((f.any_bits[g] >> b) & 1u) none_set *= 1.0 - freq[b];
+        p *= 1.0 - none_set;
+    }
+    return p;
+}
+
+// Modelled cost of the two strategies, in milliseconds per 1e9 items (both grow in proportion to the index; only
+// their ratio matters).  The constants are fits to searches timed on an MI355X over a 1e9 x 64-byte int8 index with
+// per-row scales, k = 1000, B = 1 ... 1024, pass rates 0.1 % ... 50 %:
+//   pre-filtering, per group of Bg <= 32 queries: one pass over the mask column, 0.72 + 0.10 Bg, plus per feasible
+//     (item, query) pair 15 + 27 / Bg picoseconds per 64 bytes of row (gathered rows are shared by the group's queries);
+//   masking, up to 64 queries: bound by HBM, (row bytes + 8) / 6.3 TB/s whatever the pass rate;
+//   masking, larger batches (bound by instruction issue): per 256 queries 24 + 9.5 (log10(0.5 / pass rate))^2 on
+//     64-byte int8 rows -- the lower the pass rate, the later the bounds of the score test tighten; other row shapes
+//     in proportion to their bytes.
+// Returns 1 if explicit pre-filtering is modelled to be faster by a margin (masking cannot overflow: it is the default).
+static int plan_prefers_prefilter(const linr_index* ix, uint32_t B, uint32_t m, const double* pass, double* est_pairs)
+{
+    const double row64 = (double)((ix->row_bytes + 63) / 64) * m;
+    double t_pre = 0.0, sum_p = 0.0;
+    for (uint32_t b0 = 0; b0 < B; b0 += 32) {
+        const uint32_t Bg = (B - b0) < 32 ? (B - b0) : 32;
+        double pg = 0.0;
+        for (uint32_t b = 0; b < Bg; ++b) pg += pass[b0 + b];
+        t_pre += 0.72 + 0.10 * Bg + pg * 1.0e9 * (15.0 + 27.0 / Bg) * 1.0e-9 * row64;
+        sum_p += pg;
+    }
+    if (est_pairs) *est_pairs = sum_p * (double)ix->n;
+    double t_mask = ((double)ix->row_bytes + 8.0) * 1.0e9 / 6.3e12 * 1.0e3;
+    if (B > 64) {
+        double pm = sum_p / B;
+        pm = pm < 1.0e-4 ? 1.0e-4 : pm > 0.5 ? 0.5 : pm;
+        const double x = log10(0.5 / pm);
+        const double issue = (double)B / 256.0 * (24.0 + 9.5 * x * x) * row64;
+        if (issue > t_mask) t_mask = issue;
+    }
+    return t_pre < 0.85 * t_mask;
+}
+
+extern "C" int linr_plan_filtered(const linr_index* ix, const linr_filter* host_filters, uint32_t B, uint32_t m, uint32_t k,
+                                  int* strategy, double* est_pairs)
+{
+    (void)k;
+    if (!ix || !host_filters || !strategy) return LINR_E_NULL;
+    if (m == 0 || m > LINR_MAX_M) return LINR_E_SHAPE;
+    *strategy = LINR_STRATEGY_MASKING;
+    if (est_pairs) *est_pairs = 0.0;
+    if (B == 0 || ix->n == 0) return LINR_OK;
+    float ones[32];
+    for (int b = 0; b < 32; ++b) ones[b] = 0.5f;
+    const float* freq = ix->have_bit_freq ? ix->bit_freq : ones;
+    std::vector<double> pass(B);
+    for (uint32_t b = 0; b < B; ++b) {
+        pass[b] = filter_pass_estimate(freq, host_filters[b]);
+    }
+    const int pre = ix->have_bit_freq && ix->dtype != LINR_BITS && plan_prefers_prefilter(ix, B, m, pass.data(), est_pairs);
+    *strategy = pre ? LINR_STRATEGY_PREFILTER : LINR_STRATEGY_MASKING;
+    return LINR_OK;
+}
+
 extern "C" int linr_search_filtered(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
                                     const linr_filter* filters, uint32_t k, uint32_t* out_ids, float* out_scores,
                                     int32_t* out_raw, uint32_t* out_counts, void* workspace, uint64_t workspace_bytes,
                                     void* hip_stream, uint32_t flags)
 {
+    if ((flags & LINR_PLAN_MASKING) && (flags & LINR_PLAN_PREFILTER)) return LINR_E_SHAPE;
+    int strategy = LINR_STRATEGY_MASKING;
+    if (flags & LINR_PLAN_PREFILTER) strategy = LINR_STRATEGY_PREFILTER;
+    else if (!(flags & LINR_PLAN_MASKING) && (flags & LINR_FILTERS_ON_HOST) && ix && filters && B && k && k <= LINR_MAX_K) {
+        // the planner reads the filters, so it only runs where they are in host memory; and it only chooses the
+        // strategy that needs the larger workspace if the caller brought that much
+        uint64_t need = 0;
+        if (linr_plan_filtered(ix, filters, B, m, k, &strategy, nullptr) != LINR_OK ||
+            linr_search_prefilter_workspace_bytes(ix, B, m, k, &need) != LINR_OK || workspace_bytes < need)
+            strategy = LINR_STRATEGY_MASKING;
+    }
+    const uint32_t inner_flags = flags & ~(uint32_t)(LINR_PLAN_MASKING | LINR_PLAN_PREFILTER);
+    if (strategy == LINR_STRATEGY_PREFILTER)
+        return prefilter_impl(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_raw, out_counts, workspace,
+                              workspace_bytes, hip_stream, inner_flags);
     return search_impl(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_raw, out_counts, workspace,
-                       workspace_bytes, hip_stream, flags, nullptr, nullptr, nullptr, nullptr);
+                       workspace_bytes, hip_stream, inner_flags, nullptr, nullptr, nullptr, nullptr);
 }
 
 // For callers that cannot allocate: the workspace is the library's fixed per-GPU array.  Nothing here allocates or
@@ -1529,10 +1643,10 @@ extern "C" int linr_search_prefilter_workspace_bytes(const linr_index* ix, uint3
     return LINR_OK;
 }
 
-extern "C" int linr_search_filtered_prefilter(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
-                                              const linr_filter* filters, uint32_t k, uint32_t* out_ids, float* out_scores,
-                                              int32_t* out_raw, uint32_t* out_counts, void* workspace, uint64_t workspace_bytes,
-                                              void* hip_stream, uint32_t flags)
+static int prefilter_impl(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                          const linr_filter* filters, uint32_t k, uint32_t* out_ids, float* out_scores,
+                          int32_t* out_raw, uint32_t* out_counts, void* workspace, uint64_t workspace_bytes,
+                          void* hip_stream, uint32_t flags)
 {
     if (!ix) return LINR_E_NULL;
     hipStream_t st = (hipStream_t)hip_stream;
@@ -1577,4 +1691,13 @@ extern "C" int linr_search_filtered_prefilter(const linr_index* ix, const void* 
         if (rc != LINR_OK) return rc;
     }
     return LINR_OK;
+}
+
+extern "C" int linr_search_filtered_prefilter(const linr_index* ix, const void* Q, const float* q_scale, uint32_t B, uint32_t m,
+                                              const linr_filter* filters, uint32_t k, uint32_t* out_ids, float* out_scores,
+                                              int32_t* out_raw, uint32_t* out_counts, void* workspace, uint64_t workspace_bytes,
+                                              void* hip_stream, uint32_t flags)
+{
+    return prefilter_impl(ix, Q, q_scale, B, m, filters, k, out_ids, out_scores, out_raw, out_counts, workspace, workspace_bytes,
+                          hip_stream, flags);
 }

@@ -48,6 +48,10 @@ struct linr_index {
     uint8_t* clause_counts;
     uint32_t n_clauses, clause_width, clause_reverse;
     uint64_t clause_n;
+    // planner (masking or explicit pre-filtering): share of the items that have each mask bit set, from a sample
+    // taken when the columns were loaded (host copy; live updates do not refresh it)
+    float bit_freq[32];
+    int have_bit_freq;
 };
 
 // Launch plan of one search pass (at most max_batch queries).
@@ -214,6 +218,8 @@ hipError_t linr_dense_dispatch(int what, int vk, uint32_t ng, bool ts, uint32_t 
 // statistics of 1/row_scale of a scaled int8 index (out[3]; part: 4 * LINR_SCALE_STAT_BLOCKS floats of scratch) and the
 // per-item codes derived from them (codes: n_pad bytes)
 #define LINR_SCALE_STAT_BLOCKS 1024
+// out[b] += number of sampled items (every `step`-th of the n) whose mask has bit b, b < 32; out[32] += items sampled
+hipError_t linr_launch_mask_bit_counts(const uint32_t* mask, uint64_t n, uint64_t step, unsigned long long* out, hipStream_t s);
 hipError_t linr_launch_scale_stats(const float* row_scale, uint64_t n, uint64_t n_pad, float* part, float* out, uint8_t* codes,
                                    hipStream_t s);
 // workgroups of the planned scan kernel resident per compute unit (0 if unknown)

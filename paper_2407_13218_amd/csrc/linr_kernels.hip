@@ -2558,6 +2558,34 @@ int linr_wide_variant_exists(int dtype, int vk, uint32_t ks, uint32_t m, uint32_
     return wide_dispatch(dtype, vk, ks, m, qw, act) == hipSuccess;
 }
 
+// Per-bit population counts of the mask column over an evenly spaced sample (planner input: how selective is a filter).
+__global__ void __launch_bounds__(256) mask_bit_count_kernel(const uint32_t* mask, u64 n, u64 step, unsigned long long* out)
+{
+    const int lane = threadIdx.x & 63;
+    const u64 n_sample = (n + step - 1) / step;
+    uint32_t mine = 0;                                   // lane b < 32 accumulates bit b, lane 32 the number of items
+    for (u64 j0 = ((u64)blockIdx.x * 256 + (threadIdx.x & ~63u)); j0 < n_sample; j0 += (u64)gridDim.x * 256) {
+        const u64 j = j0 + lane;
+        const bool in = j < n_sample;
+        const uint32_t mk = in ? mask[j * step] : 0u;
+#pragma unroll
+        for (int b = 0; b < 32; ++b) {
+            const uint32_t c = (uint32_t)__popcll(wave_ballot(in && ((mk >> b) & 1u)));
+            if (lane == b) mine += c;
+        }
+        const uint32_t c = (uint32_t)__popcll(wave_ballot(in));
+        if (lane == 32) mine += c;
+    }
+    if (lane <= 32 && mine) atomicAdd(out + lane, (unsigned long long)mine);
+}
+
+hipError_t linr_launch_mask_bit_counts(const uint32_t* mask, uint64_t n, uint64_t step, unsigned long long* out, hipStream_t s)
+{
+    if (n == 0 || step == 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(mask_bit_count_kernel, dim3(1024), dim3(256), 0, s, mask, (u64)n, (u64)step, out);
+    return hipGetLastError();
+}
+
 hipError_t linr_launch_scale_stats(const float* row_scale, uint64_t n, uint64_t n_pad, float* part, float* out, uint8_t* codes,
                                    hipStream_t s)
 {

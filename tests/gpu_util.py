@@ -5,8 +5,9 @@ import numpy as np
 import synth_inputs as S
 
 
-def run_gpu(w, k=None, tuning=None, want_raw=True, host_filters=True, prefilter=False):
-    """w: workload dict of torch tensors already on the GPU (see synth_inputs)."""
+def run_gpu(w, k=None, tuning=None, want_raw=True, host_filters=True, prefilter=False, strategy="masking"):
+    """w: workload dict of torch tensors already on the GPU (see synth_inputs).  strategy: "masking" (the scan kernels,
+    what most tests are about), "prefilter" or "auto" (the planner of linr_search_filtered decides)."""
     import torch
     import paper_2407_13218_amd as L
     k = k or w["k"]
@@ -18,7 +19,7 @@ def run_gpu(w, k=None, tuning=None, want_raw=True, host_filters=True, prefilter=
         filt = w["filters"]
         if not host_filters:
             filt = torch.from_numpy(np.ascontiguousarray(filt).view(np.uint8).copy()).cuda()
-        ids, sc, raw, cnt = ix.search(w["Q"], filt, k, q_scale=w["q_scale"], want_raw=want_raw, prefilter=prefilter)
+        ids, sc, raw, cnt = ix.search(w["Q"], filt, k, q_scale=w["q_scale"], want_raw=want_raw, prefilter=prefilter, strategy=strategy)
         torch.cuda.synchronize()
         out = (ids.cpu().numpy().view(np.uint32), sc.cpu().numpy(),
                None if raw is None else raw.cpu().numpy(), cnt.cpu().numpy().view(np.uint32))

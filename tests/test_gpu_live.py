@@ -54,7 +54,7 @@ def gpu_search(ix, kind, Qd, filt, k, qs=None):
         ids, mt, cnt = ix.search_bits(Qd, filt, k)
         torch.cuda.synchronize()
         return ids.cpu().numpy().view(np.uint32), mt.cpu().numpy(), cnt.cpu().numpy().view(np.uint32)
-    ids, sc, raw, cnt = ix.search(Qd, filt, k, q_scale=qs)
+    ids, sc, raw, cnt = ix.search(Qd, filt, k, q_scale=qs, strategy="masking")
     torch.cuda.synchronize()
     return ids.cpu().numpy().view(np.uint32), sc.cpu().numpy(), raw.cpu().numpy() if raw is not None else None, \
         cnt.cpu().numpy().view(np.uint32)

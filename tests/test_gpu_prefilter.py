@@ -103,7 +103,7 @@ def test_with_live_updates_by_prefiltering(oracle_mod):
     li.upsert(fresh, emb[fresh], mask[fresh], scale=sc[fresh]); ix.upsert(fresh, emb[fresh], mask[fresh], row_scale=sc[fresh])
     want = li.search(Q, f, k, q_scale=qs)
     for prefilter in (True, False):
-        ids, scr, raw, cnt = ix.search(torch.from_numpy(Q).cuda(), f, k, q_scale=torch.from_numpy(qs).cuda(), prefilter=prefilter)
+        ids, scr, raw, cnt = ix.search(torch.from_numpy(Q).cuda(), f, k, q_scale=torch.from_numpy(qs).cuda(), prefilter=prefilter, strategy="masking")
         torch.cuda.synchronize()
         assert np.array_equal(cnt.cpu().numpy().view(np.uint32), want[3])
         assert np.array_equal(ids.cpu().numpy().view(np.uint32), want[0])

@@ -44,7 +44,7 @@ def test_config5_full_size_matches_oracle(oracle_mod):
     runs = {}
     for sel, B in (("5%", 32), ("0.1%", 32), ("50%", 32), ("5%", 1), ("5%", 256), ("5%", 1024), ("0.1%", 256)):
         w = S.config5(device="cuda", n=N_FULL, B=B, k=k, selectivity=sel, index=cols)
-        ids, sc, raw, cnt = ix.search(w["Q"], w["filters"], k, q_scale=w["q_scale"])
+        ids, sc, raw, cnt = ix.search(w["Q"], w["filters"], k, q_scale=w["q_scale"], strategy="masking")
         torch.cuda.synchronize()
         runs[f"{sel} B={B}"] = (w,) + host(ids, sc, raw, cnt)
         say(f"GPU search done for pass rate {sel}, B = {B}")
@@ -393,7 +393,7 @@ def test_live_updates_full_size(oracle_mod):
     ix.sync_updates()
     assert ix.info()["n"] == mark
     say("updates applied")
-    ids, sc, _, cnt = ix.search(w["Q"][:B], filt, k)
+    ids, sc, _, cnt = ix.search(w["Q"][:B], filt, k, strategy="masking")
     torch.cuda.synchronize()
     gpu = (ids.cpu().numpy().view(np.uint32), sc.cpu().numpy(), None, cnt.cpu().numpy().view(np.uint32))
     w2 = dict(w)
