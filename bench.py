@@ -7,7 +7,8 @@ attribute mask resident in HBM (72 GB), clustered embeddings, top-1000, per-quer
 A "step" is one whole search (all threshold-seeding sweeps, the full sweep, every merge)
 of one query batch.  The headline is the small-batch, HBM-bound regime (B = 32, 5 % pass
 rate); a short sweep over B in {1, 32, 256, 1024} and pass rates {50 %, 5 %, 0.1 %} is
-reported in the same JSON line under "sweep".  A second leg, reported under "quantised", runs the
+reported in the same JSON line under "sweep" -- each cell by masking and as the library's planner answers it -- with
+"roofline_B256" / "roofline_B1024" for the large batches; "configs" holds BASELINE configs 2, 3 and 4.  A second leg, reported under "quantised", runs the
 1-bit search of Sec. 3.2 (64-bit Sign-OPORP codes of the same items, the paper's billion-member
 setting of Sec. 5.3) for B in {1, 32, 128}, with its own roofline and oracle timing; a third, "live_update",
 measures search latency next to concurrent upserts and deletes (Sec. 5.3, Table 5); a fourth, "clause_lists",
@@ -29,11 +30,17 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 INT8_PEAK_TOPS = 5000.0        # MI355X dense int8 MFMA
+BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 BYTES_PER_ITEM = 64 + 4 + 4    # codes + mask + row scale: the algorithmic HBM bytes of one item
 # HBM bytes of the largest sweep's launch (7/8 of the items) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
 # scaled by what the same counter reads for a 4 GiB device copy (profiles/scan_kernel_cfg5_B32_pass5.md); keyed by
 # (N, B, pass rate, k).  30,767,340 KiB fetched x 2.000 + 10,461 KiB written x 1.000.
+# Measured at commit c2fe76c; scan_kernel<2, 1, 1, 1, 2, false> (the kernel of this cell) has not changed since.  To be
+# measured again (the two commands in that profile) whenever that kernel changes.
 MEASURED_TRAFFIC_BYTES = {(1_000_000_000, 32, "5%", 1000): 63_022_224_384}
+# the same for the largest sweep (500,000,000 items) of the large-batch kernel, scan_kernel_dense<1, 16, false>, at
+# B = 256 / 50 % and B = 1024 / 50 % (profiles/scan_kernel_dense_cfg5_B256.md); filled in with that profile
+MEASURED_DENSE_TRAFFIC_BYTES = {}
 # the same for the largest sweep of the 1-bit search at B = 1, keyed by (N, code bits, pass rate, k):
 # 5,127,353 KiB fetched x 2.000 + 450 KiB written (profiles/scan_kernel_bits_1e9_B1.md)
 # FETCH_SIZE + WRITE_SIZE of the selection's kernels, (N, code bits, K) -> bytes per call (profiles/select_kernels_1e9_top50M.md)
@@ -420,6 +427,83 @@ def live_update_leg(L, S, args, dev):
                         "issued serially, host wall-clock latency per search", "rows": out}
 
 
+def configs_leg(L, S, args, dev):
+    """BASELINE configs 2, 3 and 4 at full size (the paper's benchmark shapes, Sec. 5.3; multi-embedding queries, Sec. 3.1.1):
+    one search = one step, wall clock over `--sweep-steps` searches after 2 warm-up ones, inputs resident.  Rooflines are
+    for the whole search: algorithmic HBM bytes (every item's row and side columns once) and, for the batched
+    configurations, the dot products' operations against the dense matrix-core peak of the element type."""
+    import numpy as np
+    import torch
+    stream = torch.cuda.current_stream().cuda_stream
+    rows = []
+
+    def timed_search(ix, w, B, k, m):
+        Q = w["Q"][:B].contiguous()
+        qs = None if w["q_scale"] is None else w["q_scale"][:B].contiguous()
+        filt = torch.from_numpy(np.ascontiguousarray(w["filters"][:B]).view(np.uint8).copy()).to(dev)
+        nb = ix.workspace_bytes(B, m, k)
+        ws = torch.empty(nb, dtype=torch.uint8, device=dev)
+        ids = torch.empty((B, k), dtype=torch.int32, device=dev); sc = torch.empty((B, k), dtype=torch.float32, device=dev)
+        cnt = torch.empty((B,), dtype=torch.int32, device=dev)
+
+        def one():
+            L.search_filtered(ix.handle, Q, qs, B, m, filt, k, ids, sc, None, cnt, ws, nb, stream, L.FILTERS_ON_DEVICE)
+        for _ in range(2):
+            one()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.sweep_steps):
+            one()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.sweep_steps, int(cnt.min().item())
+
+    def row(name, workload, n, B, bytes_per_item, ops, peak, unit, ms, min_count):
+        gbs = n * bytes_per_item / ms / 1e6
+        r = dict(config=name, workload=workload, B=B, ms_per_search=round(ms, 4), queries_per_s=round(B / ms * 1e3, 1),
+                 pairs_per_s=n * B / ms * 1e3, min_count=min_count,
+                 roofline={"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                           "algorithmic_bytes_per_search": n * bytes_per_item})
+        if ops:
+            t = ops / ms / 1e9
+            r["roofline_mfma"] = {"bound": "mfma", "achieved": round(t, 1), "peak": peak, "unit": unit, "frac": round(t / peak, 4),
+                                  "ops_per_search": ops}
+        rows.append(r)
+        log(f"  {name} B={B}: {ms:.3f} ms/search = {gbs:.0f} GB/s ({100 * gbs / HBM_PEAK_GBS:.1f} % of HBM peak)"
+            + (f", {ops / ms / 1e9:.0f} {unit} ({100 * ops / ms / 1e9 / peak:.1f} % of the matrix-core peak)" if ops else ""))
+
+    # config 2: 1e7 x d128 bf16, 256 queries, two required bits of p = 0.5 (25 % pass), k = 1000
+    w = S.config2(device=dev, B=256, k=1000, p=0.5)
+    n = w["emb"].shape[0]
+    ix = L.Index(n, 128, S.BF16, 0)
+    ix.load(w["emb"], w["mask"])
+    ms, mc = timed_search(ix, w, 256, 1000, 1)
+    row("config 2", f"{n} x d128 bf16 + mask, 25 % pass rate, k = 1000", n, 256, 2 * 128 + 4, 2.0 * n * 256 * 128, BF16_PEAK_TFLOPS, "TFLOP/s", ms, mc)
+    ix.close()
+    del w
+    # config 3: 5e7 x d64 int8 + row scale + mask + timestamp, one required bit and a 7-day window (~7 % pass), k = 1000
+    w = S.config3(device=dev, B=512, k=1000)
+    n = w["emb"].shape[0]
+    ix = L.Index(n, 64, S.I8, 0)
+    ix.load(w["emb"], w["mask"], ts=w["ts"], row_scale=w["scale"])
+    for B in (1, 16, 64, 512):
+        ms, mc = timed_search(ix, w, B, 1000, 1)
+        row("config 3", f"{n} x d64 int8 + row scale + mask + timestamp, ~7 % pass rate, k = 1000", n, B, 64 + 4 + 4 + 4,
+            2.0 * n * B * 64 if B >= 64 else 0, INT8_PEAK_TOPS, "TOP/s", ms, mc)
+    ix.close()
+    del w
+    # config 4: 2e7 x d64 bf16, 128 queries of m = 8 embeddings (score = max over the 8 dot products), ~5 % pass, k = 500
+    w = S.config4(device=dev, B=128, k=500)
+    n = w["emb"].shape[0]
+    ix = L.Index(n, 64, S.BF16, 0)
+    ix.load(w["emb"], w["mask"])
+    ms, mc = timed_search(ix, w, 128, 500, 8)
+    row("config 4", f"{n} x d64 bf16 + mask, 128 queries x 8 embeddings, ~5 % pass rate, k = 500", n, 128, 2 * 64 + 4,
+        2.0 * n * 128 * 8 * 64, BF16_PEAK_TFLOPS, "TFLOP/s", ms, mc)
+    ix.close()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -434,6 +518,7 @@ def main():
     ap.add_argument("--no-quantised", action="store_true", help="skip the 1-bit (Sign-OPORP) search leg")
     ap.add_argument("--no-live-update", action="store_true", help="skip the search-latency-under-updates leg")
     ap.add_argument("--no-clauses", action="store_true", help="skip the clause-list (job-search benchmark shape) leg")
+    ap.add_argument("--no-configs", action="store_true", help="skip the leg over BASELINE configs 2, 3 and 4")
     ap.add_argument("--code-bits", type=int, default=64, help="bits per Sign-OPORP code of the quantised leg (divides 64)")
     ap.add_argument("--sweep-steps", type=int, default=5)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -501,9 +586,39 @@ def main():
                    hbm_GBs=big_items * BYTES_PER_ITEM / big_ms / 1e6, hbm_frac=big_items * BYTES_PER_ITEM / big_ms / 1e6 / HBM_PEAK_GBS,
                    hbm_GBs_all_sweeps=N * passes * BYTES_PER_ITEM / scans_ms / 1e6,
                    int8_TOPs=2.0 * N * B * 64 / scans_ms / 1e9, mfma_frac=2.0 * N * B * 64 / scans_ms / 1e9 / INT8_PEAK_TOPS,
+                   largest_sweep_TOPs=2.0 * big_items * (B / passes) * 64 / big_ms / 1e9,
+                   whole_search_hbm_frac=N * passes * BYTES_PER_ITEM / wall / 1e6 / HBM_PEAK_GBS,
+                   whole_search_TOPs=2.0 * N * B * 64 / wall / 1e9,
                    workspace_GB=nbytes / 1e9, min_count=int(out[3].min().item()))
         del ws
         return res, w, out
+
+    def run_planned(B, sel, steps, warmup):
+        """the same search as a caller would issue it: filters in host memory, a workspace that covers both strategies, no
+        strategy flag -- the library's planner picks masking or explicit pre-filtering (Sec. 3.1.2)"""
+        w = prepare(B, sel)
+        nbytes = ix.planned_workspace_bytes(B, 1, k)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        o = (torch.empty((B, k), dtype=torch.int32, device=dev), torch.empty((B, k), dtype=torch.float32, device=dev),
+             torch.empty((B, k), dtype=torch.int32, device=dev), torch.empty((B,), dtype=torch.int32, device=dev))
+        stream = torch.cuda.current_stream().cuda_stream
+        fh = np.ascontiguousarray(w["filters"])
+        strategy, pairs = L.plan_filtered(ix.handle, fh, B, 1, k)
+
+        def one():
+            L.search_filtered(ix.handle, w["Q"], w["q_scale"], B, 1, fh, k, o[0], o[1], o[2], o[3], ws, nbytes, stream, L.FILTERS_ON_HOST)
+        for _ in range(warmup):
+            one()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            one()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        del ws
+        return dict(planned_ms_per_step=ms, strategy="prefilter" if strategy == L.STRATEGY_PREFILTER else "masking",
+                    estimated_feasible_pairs=pairs, planned_min_count=int(o[3].min().item()),
+                    planned_overflow=int((o[3] == -1).sum().item()))
 
     log(f"headline: B={args.batch} pass rate {args.selectivity} k={k}: {args.warmup} warm-up + {args.steps} timed steps")
     head, w_head, out_head = run(args.batch, args.selectivity, args.steps, args.warmup)
@@ -515,9 +630,11 @@ def main():
         for sel in ("50%", "5%", "0.1%"):
             for B in (1, 32, 256, 1024):
                 r, _, _ = run(B, sel, args.sweep_steps, 2)
+                r.update(run_planned(B, sel, args.sweep_steps, 2))
                 sweep.append({key: (round(v, 4) if isinstance(v, float) else v) for key, v in r.items()})
-                log(f"  sweep B={B:4d} pass {sel:>4}: {r['ms_per_step']:.2f} ms/step  scans {r['all_sweeps_ms']:.2f} ms  "
-                    f"{r['hbm_GBs']:.0f} GB/s  {r['int8_TOPs']:.0f} TOP/s  {r['queries_per_s']:.0f} QPS")
+                log(f"  sweep B={B:4d} pass {sel:>4}: masking {r['ms_per_step']:.2f} ms/step  scans {r['all_sweeps_ms']:.2f} ms  "
+                    f"{r['hbm_GBs']:.0f} GB/s  {r['int8_TOPs']:.0f} TOP/s  {r['queries_per_s']:.0f} QPS; planner: {r['strategy']}, "
+                    f"{r['planned_ms_per_step']:.2f} ms/step")
 
     # explicit pre-filtering (Sec. 3.1.2) against masking on the same index and queries: where it pays off (few feasible
     # pairs) and where it does not (the V1-versus-V2 trade-off of Sec. 5.3)
@@ -562,6 +679,11 @@ def main():
         log("clause lists: the paper's benchmark shape (15.5 M x d128, top-2000)")
         clauses = clause_leg(L, S, args, dev)
 
+    configs = None
+    if not args.no_configs:
+        log("BASELINE configs 2, 3, 4 at full size")
+        configs = configs_leg(L, S, args, dev)
+
     live = None
     if not args.no_live_update:
         log("live updates: search latency next to concurrent upserts / deletes")
@@ -579,9 +701,29 @@ def main():
         t0 = time.perf_counter()
         oracle.search(S.I8, emb_h, mk_h, Qh, w_head["filters"][:Bs], k, row_scale=sc_h, q_scale=qs_h, nthreads=threads)
         dt = time.perf_counter() - t0
-        cpu = dict(value=ns * Bs / dt, unit="item-query pairs/s", cores=threads, kind="oracle",
+        cpu = dict(value=ns * Bs / dt, unit="item-query pairs/s", cores=os.cpu_count() or 1, threads=threads, kind="oracle",
                    sample=f"first {ns} items x {Bs} queries of the same workload, {dt:.1f} s")
         log(f"  oracle: {cpu['value']:.3e} pairs/s on {threads} threads")
+
+    # large batches (Sec. 5.3.2 / Sec. 6): bound by the matrix cores and instruction issue; the dense int8 peak is the yardstick
+    large_batch = {}
+    for B in (256, 1024):
+        cells = {r["selectivity"]: r for r in sweep if r["B"] == B}
+        if "50%" not in cells:
+            continue
+        c = cells["50%"]
+        large_batch[f"roofline_B{B}"] = {
+            "bound": "mfma", "achieved": c["whole_search_TOPs"], "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+            "frac": c["whole_search_TOPs"] / INT8_PEAK_TOPS, "hbm_frac": c["whole_search_hbm_frac"],
+            "traffic": MEASURED_DENSE_TRAFFIC_BYTES.get((N, B, "50%", k)),
+            "scope": f"whole search at B = {B}, 50 % pass rate: 2 x 64 x N x B operations / ms_per_step; masking strategy",
+            "ms_per_step": c["ms_per_step"], "passes": c["passes"],
+            "dominant_kernel": {"kernel": "scan_kernel_dense, largest sweep of the search", "achieved": c["largest_sweep_TOPs"],
+                                "frac": c["largest_sweep_TOPs"] / INT8_PEAK_TOPS, "hbm_frac": c["hbm_frac"],
+                                "kernel_ms": c["largest_sweep_ms"], "items_per_launch": c["largest_sweep_items"]},
+            "by_pass_rate": {sel: {"ms_per_step": r["ms_per_step"], "frac": r["whole_search_TOPs"] / INT8_PEAK_TOPS,
+                                   "planned_ms_per_step": r["planned_ms_per_step"], "strategy": r["strategy"]}
+                             for sel, r in cells.items()}}
 
     line = {
         "metric": "items scored/sec + queries/sec, filtered top-1000, 1B×d64 int8 index, 1 GPU",
@@ -596,16 +738,24 @@ def main():
         "config": {"workload": f"config 5: N={N} x d64 int8 per-row-scale + uint32 mask, clustered (10000 centres), "
                                f"B={args.batch}, pass rate {args.selectivity}, k={k}", "N": N, "d": 64, "B": args.batch,
                    "k": k, "selectivity": args.selectivity, "sweeps": head["sweeps_per_pass"], "workspace_GB": head["workspace_GB"]},
-        "roofline": {"bound": "hbm", "achieved": head["hbm_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": head["hbm_frac"], "traffic": MEASURED_TRAFFIC_BYTES.get((N, args.batch, args.selectivity, k)),
-                     "kernel": "scan_kernel, largest sweep of the search", "kernel_ms": head["largest_sweep_ms"],
-                     "items_per_launch": head["largest_sweep_items"],
-                     "algorithmic_bytes_per_launch": head["largest_sweep_items"] * BYTES_PER_ITEM,
+        # what a caller sees: the algorithmic bytes of the whole index once (72 B x N) over the whole search (all sweeps,
+        # merges, launch gaps); the dominant kernel -- the largest sweep, 7/8 of the items -- is kept beside it
+        "roofline": {"bound": "hbm", "achieved": N * BYTES_PER_ITEM / head["ms_per_step"] / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": N * BYTES_PER_ITEM / head["ms_per_step"] / 1e6 / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((N, args.batch, args.selectivity, k)),
+                     "scope": "whole search: 72 B x N / ms_per_step; `traffic` is the dominant kernel's launch",
+                     "algorithmic_bytes_per_search": N * BYTES_PER_ITEM,
+                     "dominant_kernel": {"kernel": "scan_kernel, largest sweep of the search", "achieved": head["hbm_GBs"],
+                                         "frac": head["hbm_frac"], "kernel_ms": head["largest_sweep_ms"],
+                                         "items_per_launch": head["largest_sweep_items"],
+                                         "algorithmic_bytes_per_launch": head["largest_sweep_items"] * BYTES_PER_ITEM},
                      "all_sweeps_GBs": head["hbm_GBs_all_sweeps"]},
         "cpu_baseline": cpu,
         "stage_ms": {"largest_sweep": head["largest_sweep_ms"], "all_sweeps": head["all_sweeps_ms"], "merges": head["merges_ms"]},
+        **large_batch,
         "sweep": sweep,
         "prefilter": pre,
+        "configs": configs,
         "quantised": quant,
         "two_stage": two_stage,
         "live_update": live,

@@ -13,7 +13,8 @@ CSRC = os.path.join(HERE, "csrc")
 SOURCES = [os.path.join(CSRC, f) for f in ("linr_kernels.hip", "linr_kernels_dense.hip", "linr_kernels_select.hip", "linr_api.cpp")]
 HEADERS = [os.path.join(CSRC, f) for f in ("linr_internal.h", "linr_device.h", "linr_scan_common.h")] + \
           [os.path.join(ROOT, "include", "linr.h")]
-DEPS = SOURCES + HEADERS
+DEPS = SOURCES + HEADERS + [os.path.join(CSRC, "mfma_issue_bench.hip")]
+ISSUE_BENCH = os.path.join(HERE, "mfma_issue_bench")  # executable (git-ignored, like the library)
 OBJDIR = os.path.join(HERE, "_build")          # object files (git-ignored); only the linked library ships
 
 
@@ -54,6 +55,11 @@ def build(force: bool = True, verbose: bool = False, defines=()) -> str:
         sys.stderr.write(res.stderr)
         raise RuntimeError("link failed")
     os.replace(tmp, LIB)
+    # stand-alone micro-benchmark of the matrix / vector issue model the large-batch kernel is designed around
+    res = subprocess.run([hipcc] + _flags() + [os.path.join(CSRC, "mfma_issue_bench.hip"), "-o", ISSUE_BENCH], capture_output=True, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stderr)
+        raise RuntimeError("hipcc failed on mfma_issue_bench.hip")
     return LIB
 
 
