@@ -35,12 +35,14 @@ BYTES_PER_ITEM = 64 + 4 + 4    # codes + mask + row scale: the algorithmic HBM b
 # HBM bytes of the largest sweep's launch (7/8 of the items) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
 # scaled by what the same counter reads for a 4 GiB device copy (profiles/scan_kernel_cfg5_B32_pass5.md); keyed by
 # (N, B, pass rate, k).  30,767,340 KiB fetched x 2.000 + 10,461 KiB written x 1.000.
-# Measured at commit c2fe76c; scan_kernel<2, 1, 1, 1, 2, false> (the kernel of this cell) has not changed since.  To be
-# measured again (the two commands in that profile) whenever that kernel changes.
-MEASURED_TRAFFIC_BYTES = {(1_000_000_000, 32, "5%", 1000): 63_022_224_384}
+# Measured at commit c2fe76c and again at 7d9ebd9 (30,767,378 KiB x 2.000 + 10,488 KiB: the same to 5 digits,
+# profiles/scan_kernel_dense_cfg5_B256.md); to be measured again -- the two commands in that profile -- whenever
+# scan_kernel<2, 1, 1, 1, 2, false>, the kernel of this cell, changes.
+MEASURED_TRAFFIC_BYTES = {(1_000_000_000, 32, "5%", 1000): 63_022_329_856}
 # the same for the largest sweep (500,000,000 items) of the large-batch kernel, scan_kernel_dense<1, 16, false>, at
-# B = 256 / 50 % and B = 1024 / 50 % (profiles/scan_kernel_dense_cfg5_B256.md); filled in with that profile
-MEASURED_DENSE_TRAFFIC_BYTES = {}
+# B = 256 / 50 % and B = 1024 / 50 % (profiles/scan_kernel_dense_cfg5_B256.md), measured at commit 7d9ebd9:
+# 17,591,260 KiB x 2.000 + 81,676 KiB and 17,608,586 KiB x 2.000 + 280,384 KiB
+MEASURED_DENSE_TRAFFIC_BYTES = {(1_000_000_000, 256, "50%", 1000): 36_110_536_704, (1_000_000_000, 1024, "50%", 1000): 36_349_497_344}
 # the same for the largest sweep of the 1-bit search at B = 1, keyed by (N, code bits, pass rate, k):
 # 5,127,353 KiB fetched x 2.000 + 450 KiB written (profiles/scan_kernel_bits_1e9_B1.md)
 # FETCH_SIZE + WRITE_SIZE of the selection's kernels, (N, code bits, K) -> bytes per call (profiles/select_kernels_1e9_top50M.md)
