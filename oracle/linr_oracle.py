@@ -59,6 +59,8 @@ def _load():
         lib.linr_oracle_pass.argtypes = [vp, u32, i32, u32]
         lib.linr_oracle_sign_oporp.restype = i32
         lib.linr_oracle_sign_oporp.argtypes = [vp, u64, u32, vp, vp, u32, vp]
+        lib.linr_oracle_sign_oporp_rep.restype = i32
+        lib.linr_oracle_sign_oporp_rep.argtypes = [vp, u64, u32, vp, vp, u32, u32, vp]
         lib.linr_oracle_bit_matches.restype = u32
         lib.linr_oracle_bit_matches.argtypes = [vp, vp, u32, u32]
         lib.linr_oracle_bits_search.restype = i32
@@ -153,14 +155,21 @@ def widen(dtype, a):
 
 
 def sign_oporp(dtype, x, perm, signs, k_bits):
-    """x [n, D] (fp32 or bf16 bit patterns) -> codes [n, ceil(k_bits/64)] uint64."""
+    """x [n, D] (fp32 or bf16 bit patterns) -> codes [n, ceil(k_bits/64)] uint64.  perm / signs of shape [D]: one draw;
+    of shape [R, D]: R independent draws, k_bits / R bits each, concatenated in draw order."""
     lib = _load()
     xd = np.ascontiguousarray(widen(dtype, x))
     n, D = xd.shape
     perm = _c(perm, np.uint32); signs = _c(signs, np.int8)
-    assert perm.shape == (D,) and signs.shape == (D,)
     W = (k_bits + 63) // 64
     out = np.zeros((n, W), np.uint64)
+    if perm.ndim == 2:
+        reps = perm.shape[0]
+        assert perm.shape == (reps, D) and signs.shape == (reps, D)
+        if lib.linr_oracle_sign_oporp_rep(_ptr(xd), n, D, _ptr(perm), _ptr(signs), k_bits, reps, _ptr(out)) != 0:
+            raise ValueError("k_bits must be a multiple of the draws and D a multiple of the bits per draw")
+        return out
+    assert perm.shape == (D,) and signs.shape == (D,)
     if lib.linr_oracle_sign_oporp(_ptr(xd), n, D, _ptr(perm), _ptr(signs), k_bits, _ptr(out)) != 0:
         raise ValueError("D must be a positive multiple of k_bits")
     return out

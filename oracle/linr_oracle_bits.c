@@ -13,6 +13,10 @@
  *      caller and shared by items and queries.  The sum runs in double precision, t
  *      ascending (the inputs are fp32 or bf16 values, exactly representable).  Bit j
  *      lives at position j%64 (least significant first) of 64-bit word j/64.
+ *      More bits than coordinates (Sec. 5.3.1 reports 512-bit codes of 128-dimensional
+ *      embeddings): the construction is repeated with R independent draws of (perm, signs),
+ *      each giving k_bits / R bits from bins of L = D * R / k_bits coordinates; the code is the
+ *      draws' codes one after the other, bit r * (k_bits / R) + j = bit j of draw r.
  *   2. Bit-wise matching: similarity of two codes = number of equal bits
  *      = k_bits - popcount(a XOR b).
  *   3. Quantised KNN with pre-filtering: among the items that satisfy the query's clauses
@@ -22,7 +26,9 @@
  *   is composed in oracle/linr_oracle.py from this file and the exact oracle's pair scorer.
  *
  * Readings (the paper is silent): bit = 1 for a strictly positive bin sum (a zero sum gives
- * 0); D must be a multiple of k_bits; ties by ascending id.
+ * 0); D must be a multiple of the bits per draw; ties by ascending id; codes longer than D bits
+ * come from repeating the construction with independent draws (the OPORP paper's repetition),
+ * concatenated in draw order.
  *
  * This file shares no code with the HIP library.  Every function is pinned by
  * tests/test_oracle_bits_pins.py (hand-worked example, projection-matrix form in numpy,
@@ -57,6 +63,36 @@ int linr_oracle_sign_oporp(const double* x, uint64_t n, uint32_t D, const uint32
                 s = s + (signs[j * L + t] > 0 ? v : -v);
             }
             if (s > 0.0) o[j / 64] |= (uint64_t)1 << (j % 64);
+        }
+    }
+    return 0;
+}
+
+/* The same with `reps` independent draws: perm and signs are [reps][D]; k_bits = reps * k1 with D a multiple of k1.
+   Returns 0, or -1 on a bad shape. */
+int linr_oracle_sign_oporp_rep(const double* x, uint64_t n, uint32_t D, const uint32_t* perm, const int8_t* signs,
+                               uint32_t k_bits, uint32_t reps, uint64_t* out)
+{
+    if (reps == 0 || k_bits == 0 || k_bits % reps != 0) return -1;
+    const uint32_t k1 = k_bits / reps;
+    if (D % k1 != 0) return -1;
+    const uint32_t L = D / k1, W = (k_bits + 63) / 64;
+    for (uint64_t i = 0; i < n; ++i) {
+        const double* row = x + (size_t)i * D;
+        uint64_t* o = out + (size_t)i * W;
+        for (uint32_t w = 0; w < W; ++w) o[w] = 0;
+        for (uint32_t r = 0; r < reps; ++r) {
+            const uint32_t* pr = perm + (size_t)r * D;
+            const int8_t* sr = signs + (size_t)r * D;
+            for (uint32_t j = 0; j < k1; ++j) {
+                double s = 0.0;
+                for (uint32_t t = 0; t < L; ++t) {
+                    double v = row[pr[j * L + t]];
+                    s = s + (sr[j * L + t] > 0 ? v : -v);
+                }
+                const uint32_t bit = r * k1 + j;
+                if (s > 0.0) o[bit / 64] |= (uint64_t)1 << (bit % 64);
+            }
         }
     }
     return 0;

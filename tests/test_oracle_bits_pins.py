@@ -37,6 +37,63 @@ def test_hand_example(oracle_mod):
         assert oracle_mod.bit_matches(codes[a], codes[b], g["k_bits"]) == want
 
 
+def test_hand_example_two_draws(oracle_mod):
+    g = json.load(open(os.path.join(HERE, "golden", "sign_oporp_two_draws_example.json")))
+    x = np.array(g["x"], np.float32)
+    codes = oracle_mod.sign_oporp(S.F32, x, np.array(g["perm"], np.uint32), np.array(g["signs"], np.int8), g["k_bits"])
+    assert codes.shape == (4, 1) and codes[:, 0].tolist() == g["codes"]
+    for key, want in g["matches"].items():
+        a, b = map(int, key.split(","))
+        assert oracle_mod.bit_matches(codes[a], codes[b], g["k_bits"]) == want
+
+
+@pytest.mark.parametrize("D,k_bits,reps", [(128, 512, 4), (128, 256, 2), (64, 384, 6), (128, 192, 3), (96, 64, 2)])
+def test_projection_matrix_form_with_repetitions(oracle_mod, D, k_bits, reps):
+    """R draws = one projection matrix of R stacked blocks, block r built from (perm_r, signs_r): sketch = P x"""
+    rng = np.random.default_rng(D + k_bits + reps)
+    perm = np.stack([rng.permutation(D) for _ in range(reps)]).astype(np.uint32)
+    signs = rng.choice(np.array([-1, 1], np.int8), (reps, D))
+    x = rng.standard_normal((200, D)).astype(np.float32)
+    k1 = k_bits // reps
+    L = D // k1
+    P = np.zeros((k_bits, D))
+    for r in range(reps):
+        for j in range(k1):
+            for t in range(L):
+                P[r * k1 + j, perm[r, j * L + t]] = signs[r, j * L + t]
+    sk = x.astype(np.float64) @ P.T
+    safe = np.abs(sk) > 1e-9
+    got = unpack(oracle_mod.sign_oporp(S.F32, x, perm, signs, k_bits), k_bits)
+    assert np.array_equal(got[safe], (sk > 0)[safe].astype(np.uint8))
+    assert safe.mean() > 0.999
+    # every coordinate enters each draw exactly once
+    assert np.all(np.abs(P).reshape(reps, k1, D).sum(axis=1) == 1)
+    with pytest.raises(ValueError):
+        oracle_mod.sign_oporp(S.F32, x, perm, signs, k_bits + reps * 7)      # bits per draw must divide D
+
+
+def test_angle_law_holds_for_repeated_draws(oracle_mod):
+    """each draw obeys 1 - angle/pi, so does their concatenation; independent draws make the estimate tighter than one
+    draw of the same bins would (the reason for repeating): the spread of the match fraction over pairs shrinks"""
+    D, reps, k1, pairs_n = 1024, 4, 32, 1200
+    rng = np.random.default_rng(77)
+    perm = np.stack([rng.permutation(D) for _ in range(reps)]).astype(np.uint32)
+    signs = rng.choice(np.array([-1, 1], np.int8), (reps, D))
+    rho = 0.6
+    a = rng.standard_normal((pairs_n, D))
+    b = rho * a + math.sqrt(1 - rho * rho) * rng.standard_normal((pairs_n, D))
+    want = 1.0 - math.acos(rho) / math.pi
+    kb = reps * k1
+    ca = oracle_mod.sign_oporp(S.F32, a.astype(np.float32), perm, signs, kb)
+    cb = oracle_mod.sign_oporp(S.F32, b.astype(np.float32), perm, signs, kb)
+    fr = np.array([oracle_mod.bit_matches(ca[i], cb[i], kb) for i in range(pairs_n)]) / kb
+    assert abs(fr.mean() - want) < 4.0 * 0.5 / math.sqrt(pairs_n * kb) + 3e-3
+    c1a = oracle_mod.sign_oporp(S.F32, a.astype(np.float32), perm[0], signs[0], k1)
+    c1b = oracle_mod.sign_oporp(S.F32, b.astype(np.float32), perm[0], signs[0], k1)
+    fr1 = np.array([oracle_mod.bit_matches(c1a[i], c1b[i], k1) for i in range(pairs_n)]) / k1
+    assert fr.std() < 0.62 * fr1.std()                       # 4 x the bits: about half the spread
+
+
 @pytest.mark.parametrize("D,k_bits", [(64, 64), (128, 64), (256, 128), (96, 32), (64, 16), (512, 256)])
 def test_projection_matrix_form(oracle_mod, D, k_bits):
     """sketch = P x with P[j, perm[jL+t]] = signs[jL+t]: "one random projection" written as a matrix"""
