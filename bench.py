@@ -303,18 +303,18 @@ def clause_leg(L, S, args, dev):
 
 
 def two_stage_leg(L, S, args, dev):
-    """Latency / recall of the two-stage search (Sec. 3.2 and the trade-off figure of Sec. 5.3: 1-bit pre-selection of T
-    items, exact re-scoring, top-k) against the exact search on config 2 at full size (1e7 x d128 bf16, 25 % pass rate),
-    128-bit Sign-OPORP codes, k = 100, batch 16.  Recall = share of the exact top-k that the two-stage result contains."""
+    """Latency / recall of the two-stage search (Sec. 3.2 and the trade-off figure of Sec. 5.3.1: 1-bit pre-selection of T
+    items, exact re-scoring, top-k) against the exact search, on the paper's benchmark shape (15.5 M x d128, here bf16,
+    25 % pass rate) with 512-bit Sign-OPORP codes (four independent draws of 128 bits, as the paper's 512-bit codes of
+    128-dimensional embeddings need) and, for comparison, one draw of 128 bits; k = 100, batch 16.
+    Recall = share of the exact top-k that the two-stage result contains."""
     import numpy as np
     import torch
-    B, k, kb = 16, 100, 128
-    w = S.config2(device=dev, B=B, k=k, p=0.5)
-    n, d = w["emb"].shape[0], 128
+    B, k, n = 16, 100, 15_500_000
+    w = S.config2(device=dev, n=n, B=B, k=k, p=0.5)
+    d = 128
     ix = L.Index(n, d, S.BF16, 0)
     ix.load(w["emb"], w["mask"])
-    perm, signs = S.oporp_draw(d, 0)
-    ix.build_bits(perm, signs, kb)
     filt = torch.from_numpy(np.ascontiguousarray(w["filters"]).view(np.uint8).copy()).to(dev)
     Q = w["Q"].reshape(B, d).contiguous()
     stream = torch.cuda.current_stream().cuda_stream
@@ -336,18 +336,21 @@ def two_stage_leg(L, S, args, dev):
                                                L.FILTERS_ON_DEVICE))
     truth = [set(r.tolist()) for r in ids.cpu().numpy()]
     rows = []
-    for T in (500, 1000, 2000, 4000, 8192, n // 100):             # the last: "keep 1 % of the items" (Sec. 5.3)
-        nb2 = L.search_two_stage_workspace_bytes(ix.handle, B, T, k)
-        ws2 = torch.empty(nb2, dtype=torch.uint8, device=dev)
-        ms = timed(lambda: L.search_two_stage(ix.handle, Q, B, filt, T, k, ids, sc, cnt, ws2, nb2, stream, L.FILTERS_ON_DEVICE))
-        got = ids.cpu().numpy()
-        recall = float(np.mean([len(truth[b] & set(got[b].tolist())) / k for b in range(B)]))
-        rows.append(dict(T=T, ms_per_search=round(ms, 4), recall_at_k=round(recall, 4)))
-        log(f"  two-stage T={T:6d}: {ms:.3f} ms/search, recall@{k} {recall:.3f} (exact search {exact_ms:.3f} ms)")
-        del ws2
+    for kb, reps in ((512, 4), (128, 1)):
+        perm, signs = S.oporp_draws(d, reps, 0) if reps > 1 else S.oporp_draw(d, 0)
+        ix.build_bits(perm, signs, kb)
+        for T in (500, 1000, 2000, 4000, 8192, n // 100):         # the last: "keep 1 % of the items" (Sec. 5.3.1)
+            nb2 = L.search_two_stage_workspace_bytes(ix.handle, B, T, k)
+            ws2 = torch.empty(nb2, dtype=torch.uint8, device=dev)
+            ms = timed(lambda: L.search_two_stage(ix.handle, Q, B, filt, T, k, ids, sc, cnt, ws2, nb2, stream, L.FILTERS_ON_DEVICE))
+            got = ids.cpu().numpy()
+            recall = float(np.mean([len(truth[b] & set(got[b].tolist())) / k for b in range(B)]))
+            rows.append(dict(code_bits=kb, draws=reps, T=T, ms_per_search=round(ms, 4), recall_at_k=round(recall, 4)))
+            log(f"  two-stage {kb}-bit codes T={T:6d}: {ms:.3f} ms/search, recall@{k} {recall:.3f} (exact search {exact_ms:.3f} ms)")
+            del ws2
     ix.close()
-    return {"workload": f"config 2 at full size: {n} x d128 bf16, 25 % pass rate, B = {B}, k = {k}, {kb}-bit codes",
-            "exact_ms_per_search": round(exact_ms, 4), "rows": rows}
+    return {"workload": f"{n} x d128 bf16 (the paper's benchmark shape), 25 % pass rate, B = {B}, k = {k}; 512-bit codes = 4 draws "
+                        "of 128 bits, 128-bit codes = 1 draw", "exact_ms_per_search": round(exact_ms, 4), "rows": rows}
 
 
 def live_update_leg(L, S, args, dev):

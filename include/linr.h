@@ -233,11 +233,16 @@ int linr_index_destroy(linr_index*);
  * (perm: a permutation of 0..d-1; signs: +1 / -1; both drawn once by the caller and
  * shared by items and queries; sums in double precision, t ascending).  Bit j is bit
  * j%64 of 64-bit word j/64; a code is W = ceil(k_bits/64) words.  The similarity of two
- * codes is their number of equal bits.  Limits: k_bits <= 256, d % k_bits == 0.
+ * codes is their number of equal bits.  Codes longer than one pass over the coordinates
+ * gives (Sec. 5.3.1 uses 512 bits for d = 128) are R independent draws of (perm, signs),
+ * k_bits / R bits each with L = d * R / k_bits, one after the other: bit r * (k_bits / R) + j
+ * is bit j of draw r.  Limits: k_bits <= 512 with W in {1, 2, 3, 4, 6, 8}; k_bits % R == 0;
+ * d % (k_bits / R) == 0; R <= 64.
  *
  * linr_index_build_bits  derives the codes of every resident item of an fp32 / bf16
  *     index (library-owned, n * W * 8 bytes); perm [d] and signs [d] are host arrays
  *     (src == LINR_SRC_HOST) or device arrays (any other LINR_SRC_* value); copied.
+ * linr_index_build_bits_rep  the same with `reps` = R draws: perm [R][d], signs [R][d].
  * linr_index_load_bits   fills an index created with dtype LINR_BITS (d = k_bits) with
  *     ready-made codes [n][W] plus mask / ts: a codes-only index (8 bytes per item at
  *     64 bits) for when memory is the concern.  `src` as for the other loaders.
@@ -262,6 +267,7 @@ int linr_index_destroy(linr_index*);
  * (index kind does not fit the call) and LINR_E_NOT_LOADED (no codes built yet).
  */
 int linr_index_build_bits(linr_index*, const uint32_t* perm, const int8_t* signs, uint32_t k_bits, int src);
+int linr_index_build_bits_rep(linr_index*, const uint32_t* perm, const int8_t* signs, uint32_t k_bits, uint32_t reps, int src);
 int linr_index_load_bits(linr_index*, const uint64_t* bits, const uint32_t* mask, const uint32_t* ts, uint64_t n, int src);
 int linr_quantize_queries(const linr_index*, const void* Q, uint32_t B, uint64_t* qbits, void* hip_stream);
 int linr_search_bits_workspace_bytes(const linr_index*, uint32_t B, uint32_t T, uint64_t* bytes);

@@ -39,7 +39,7 @@ EXPORTS = [
     "linr_index_load_clauses", "linr_search_clauses_workspace_bytes", "linr_search_clauses", "linr_search_clauses_timed",
     "linr_search_clauses_prefilter", "linr_index_upsert_clauses",
     "linr_search_prefilter_workspace_bytes", "linr_search_filtered_prefilter", "linr_search_filtered_noalloc",
-    "linr_plan_filtered",
+    "linr_plan_filtered", "linr_index_build_bits_rep",
 ]
 
 
@@ -112,6 +112,8 @@ def load_library():
     lib.linr_events_elapsed_ms.argtypes = [vp, u32, vp]
     lib.linr_index_build_bits.restype = i32
     lib.linr_index_build_bits.argtypes = [vp, vp, vp, u32, i32]
+    lib.linr_index_build_bits_rep.restype = i32
+    lib.linr_index_build_bits_rep.argtypes = [vp, vp, vp, u32, u32, i32]
     lib.linr_index_load_bits.restype = i32
     lib.linr_index_load_bits.argtypes = [vp, vp, vp, vp, u64, i32]
     lib.linr_quantize_queries.restype = i32
@@ -283,8 +285,11 @@ def events_elapsed_ms(ev, n_pairs: int):
     return [ms[i] for i in range(n_pairs)]
 
 
-def index_build_bits(ix, perm, signs, k_bits, src):
-    _check(load_library().linr_index_build_bits(ix, _ptr(perm), _ptr(signs), k_bits, src), "linr_index_build_bits")
+def index_build_bits(ix, perm, signs, k_bits, src, reps=1):
+    if reps == 1:
+        _check(load_library().linr_index_build_bits(ix, _ptr(perm), _ptr(signs), k_bits, src), "linr_index_build_bits")
+    else:
+        _check(load_library().linr_index_build_bits_rep(ix, _ptr(perm), _ptr(signs), k_bits, reps, src), "linr_index_build_bits_rep")
 
 
 def index_load_bits(ix, bits, mask, ts, n, src):
@@ -566,9 +571,15 @@ class Index:
 
     # ---- quantised search (Sec. 3.2) ----
     def build_bits(self, perm, signs, k_bits):
-        """perm (uint32 [d]) and signs (int8 [d]): numpy (host) or device tensors"""
+        """perm (uint32 [d]) and signs (int8 [d]): numpy (host) or device tensors; [R, d] each for R independent draws
+        (codes of k_bits / R bits per draw, concatenated)"""
         src = SRC_HOST if isinstance(perm, np.ndarray) else SRC_DEVICE_COPY
-        index_build_bits(self.handle, perm, signs, k_bits, src)
+        reps = int(perm.shape[0]) if len(perm.shape) == 2 else 1
+        if isinstance(perm, np.ndarray):
+            perm, signs = np.ascontiguousarray(perm), np.ascontiguousarray(signs)
+        else:
+            perm, signs = perm.contiguous(), signs.contiguous()
+        index_build_bits(self.handle, perm, signs, k_bits, src, reps)
         self.k_bits = k_bits
         return self
 

@@ -51,6 +51,13 @@ extern "C" int linr_set_tuning(const linr_tuning* t)
 static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 static uint32_t elt_bytes(int dtype) { return dtype == LINR_F32 ? 4u : dtype == LINR_BF16 ? 2u : 1u; }
 
+// code lengths the bit-matching kernels exist for: 1, 2, 3, 4, 6 or 8 words of 64 bits (up to 512 bits)
+static bool bits_words_supported(uint32_t k_bits)
+{
+    const uint32_t w = (k_bits + 63) / 64;
+    return k_bits != 0 && (w <= 4 || w == 6 || w == 8);
+}
+
 extern "C" int linr_index_create(linr_index** out, uint64_t capacity, uint32_t d, int dtype, int device)
 {
     if (!out) return LINR_E_NULL;
@@ -59,7 +66,7 @@ extern "C" int linr_index_create(linr_index** out, uint64_t capacity, uint32_t d
     if (d == 0) return LINR_E_SHAPE;
     uint64_t rb = (uint64_t)d * elt_bytes(dtype);
     if (dtype == LINR_BITS) {                           // d = bits per code; a code is ceil(d / 64) words
-        if (d > 256) return LINR_E_SHAPE;
+        if (!bits_words_supported(d)) return LINR_E_SHAPE;
         rb = (uint64_t)((d + 63) / 64) * 8;
     } else if (rb % 16 != 0 || rb > 512) return LINR_E_SHAPE;
     if (capacity == 0 || capacity > 0xFFFFFFFEull) return LINR_E_CAPACITY;
@@ -865,10 +872,17 @@ static int copy_small(void** dst, const void* src, uint64_t bytes, int from_host
 
 extern "C" int linr_index_build_bits(linr_index* ix, const uint32_t* perm, const int8_t* signs, uint32_t k_bits, int src)
 {
+    return linr_index_build_bits_rep(ix, perm, signs, k_bits, 1, src);
+}
+
+extern "C" int linr_index_build_bits_rep(linr_index* ix, const uint32_t* perm, const int8_t* signs, uint32_t k_bits, uint32_t reps,
+                                         int src)
+{
     if (!ix || !perm || !signs) return LINR_E_NULL;
     if (ix->dtype != LINR_F32 && ix->dtype != LINR_BF16) return LINR_E_DTYPE;
     if (ix->n == 0 || !ix->emb) return LINR_E_NOT_LOADED;
-    if (k_bits == 0 || k_bits > 256 || ix->d % k_bits != 0) return LINR_E_SHAPE;
+    if (reps == 0 || reps > 64 || k_bits == 0 || k_bits % reps != 0 || ix->d % (k_bits / reps) != 0 || !bits_words_supported(k_bits))
+        return LINR_E_SHAPE;
     int dev = 0;
     HIP_TRY(hipGetDevice(&dev));
     HIP_TRY(hipSetDevice(ix->device));
@@ -876,13 +890,13 @@ extern "C" int linr_index_build_bits(linr_index* ix, const uint32_t* perm, const
     if (ix->perm) (void)hipFree(ix->perm);
     if (ix->signs) (void)hipFree(ix->signs);
     ix->bits = nullptr; ix->perm = nullptr; ix->signs = nullptr;
-    ix->k_bits = k_bits; ix->bits_words = (k_bits + 63) / 64;
+    ix->k_bits = k_bits; ix->bits_words = (k_bits + 63) / 64; ix->bits_reps = reps;
     const int fh = src == LINR_SRC_HOST;
-    int rc = copy_small((void**)&ix->perm, perm, (uint64_t)ix->d * 4, fh);
-    if (rc == LINR_OK) rc = copy_small((void**)&ix->signs, signs, ix->d, fh);
+    int rc = copy_small((void**)&ix->perm, perm, (uint64_t)reps * ix->d * 4, fh);
+    if (rc == LINR_OK) rc = copy_small((void**)&ix->signs, signs, (uint64_t)reps * ix->d, fh);
     if (rc == LINR_OK) {
         hipError_t e = hipMalloc((void**)&ix->bits, ix->capacity * ix->bits_words * 8);
-        if (e == hipSuccess) e = linr_launch_sign_oporp(ix->dtype, ix->emb, ix->n, ix->d, ix->perm, ix->signs, k_bits, ix->bits, nullptr);
+        if (e == hipSuccess) e = linr_launch_sign_oporp(ix->dtype, ix->emb, ix->n, ix->d, ix->perm, ix->signs, k_bits, reps, ix->bits, nullptr);
         if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
         if (e != hipSuccess) { g_last_hip = (int)e; rc = LINR_E_HIP; }
     }
@@ -905,7 +919,7 @@ extern "C" int linr_quantize_queries(const linr_index* ix, const void* Q, uint32
     if (!ix || !Q || !qbits) return LINR_E_NULL;
     if (ix->dtype != LINR_F32 && ix->dtype != LINR_BF16) return LINR_E_DTYPE;
     if (!ix->bits || !ix->perm) return LINR_E_NOT_LOADED;
-    HIP_TRY(linr_launch_sign_oporp(ix->dtype, Q, B, ix->d, ix->perm, ix->signs, ix->k_bits, qbits, (hipStream_t)hip_stream));
+    HIP_TRY(linr_launch_sign_oporp(ix->dtype, Q, B, ix->d, ix->perm, ix->signs, ix->k_bits, ix->bits_reps, qbits, (hipStream_t)hip_stream));
     return LINR_OK;
 }
 
@@ -1317,7 +1331,7 @@ static int update_impl(linr_index* ix, const uint32_t* slots, uint32_t count, co
             HIP_TRY(linr_launch_upsert(a, st));
             if (ix->bits && ix->dtype != LINR_BITS)     // the quantised search's codes follow the rows
                 HIP_TRY(linr_launch_sign_oporp_scatter(ix->dtype, a.src_emb, count, ix->d, ix->perm, ix->signs, ix->k_bits,
-                                                       ix->bits, d_slots, st));
+                                                       ix->bits_reps, ix->bits, d_slots, st));
             HIP_TRY(linr_launch_upsert_masks(a, st));   // last: the mask makes the slot visible
         }
         HIP_TRY(hipEventRecord(u->done, st));

@@ -36,6 +36,7 @@ struct linr_index {
     // quantised search: Sign-OPORP codes [n][bits_words] (owned), k_bits, and the device copies of perm / signs
     uint64_t* bits;
     uint32_t k_bits, bits_words;
+    uint32_t bits_reps;         // independent (permutation, signs) draws the code is made of: perm / signs are [bits_reps][d]
     uint32_t* perm;
     int8_t* signs;
     int num_cu;
@@ -125,11 +126,11 @@ hipError_t linr_launch_scan(const linr_plan& p, int dtype, const linr_scan_args&
 hipError_t linr_launch_merge(const linr_merge_args& a, hipStream_t s);
 // quantised search helpers: codes of `n` rows (fp32 / bf16, row-major [n][d]); rescoring of T candidates per query
 hipError_t linr_launch_sign_oporp(int dtype, const void* x, uint64_t n, uint32_t d, const uint32_t* perm, const int8_t* signs,
-                                  uint32_t k_bits, uint64_t* out, hipStream_t s);
+                                  uint32_t k_bits, uint32_t reps, uint64_t* out, hipStream_t s);
 // codes of rows written by an update: row r of x goes to out[scatter[r]] (scatter == nullptr: out[r])
 hipError_t linr_launch_sign_oporp_scatter(int dtype, const void* x, uint64_t n, uint32_t d, const uint32_t* perm,
-                                          const int8_t* signs, uint32_t k_bits, uint64_t* out, const uint32_t* scatter,
-                                          hipStream_t s);
+                                          const int8_t* signs, uint32_t k_bits, uint32_t reps, uint64_t* out,
+                                          const uint32_t* scatter, hipStream_t s);
 // live updates: row / side-column scatter into slots, tombstones, mask fill, OR over all masks
 struct linr_upsert_args {
     const uint32_t* slots; uint32_t count; uint32_t row_bytes;       // row_bytes: a multiple of 8
@@ -180,7 +181,7 @@ hipError_t linr_launch_prefilter(const linr_prefilter_args& a, hipStream_t s);  
 // out_counts[b] = 0xFFFFFFFF where vcnt[b] > capacity (run behind the merge)
 hipError_t linr_launch_prefilter_overflow(const uint32_t* vcnt, uint64_t capacity, uint32_t* out_counts, uint32_t nq, hipStream_t s);
 // large-K selection by bit matching (counting: the number of differing bits takes k_bits + 1 values)
-#define LINR_SELECT_BINS 264           // row length of the global counts (k_bits <= 256 -> 257 values)
+#define LINR_SELECT_BINS 520           // row length of the global counts (k_bits <= 512 -> 513 values)
 struct linr_select_cut { uint32_t t_diff, pad_; uint64_t need_eq; };  // every item with fewer differing bits; the first need_eq with t_diff
 struct linr_select_args {
     const unsigned long long* bits; uint32_t words, k_bits; const uint32_t* mask; const uint32_t* ts; uint32_t dead_bit;

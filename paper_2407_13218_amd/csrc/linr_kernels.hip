@@ -1351,11 +1351,14 @@ __global__ void __launch_bounds__(64 * WPB, (QG * W <= 4 ? 3 : 2)) scan_kernel_b
 }
 
 // Sign-OPORP codes of n rows: thread (row, word) sums its 64 bins in double precision, t ascending, and
-// sets bit j%64 of word j/64 for a strictly positive bin sum (Sec. 3.2; construction in the header).
+// sets bit j%64 of word j/64 for a strictly positive bin sum (Sec. 3.2; construction in the header).  Codes of
+// more bits than one pass over the coordinates gives (Sec. 5.3.1: 512 bits for d = 128) are `reps` independent
+// draws one after the other: bit r * k1 + j comes from bin j of draw r (perm / signs are [reps][d], k1 = k_bits / reps).
 __global__ void __launch_bounds__(256) sign_oporp_kernel(int dtype, const void* x, u64 n, uint32_t d, const uint32_t* perm,
-                                                         const int8_t* signs, uint32_t k_bits, u64* out, const uint32_t* scatter)
+                                                         const int8_t* signs, uint32_t k_bits, uint32_t reps, u64* out,
+                                                         const uint32_t* scatter)
 {
-    const uint32_t Wn = (k_bits + 63) / 64, L = d / k_bits;
+    const uint32_t Wn = (k_bits + 63) / 64, k1 = k_bits / reps, L = d / k1;
     const u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= n * Wn) return;
     const u64 row = t / Wn;
@@ -1364,13 +1367,14 @@ __global__ void __launch_bounds__(256) sign_oporp_kernel(int dtype, const void* 
     for (uint32_t jj = 0; jj < 64; ++jj) {
         const uint32_t j = w * 64 + jj;
         if (j >= k_bits) break;
+        const uint32_t base = (j / k1) * d + (j % k1) * L;       // draw j / k1, bin j % k1
         double sum = 0.0;
         for (uint32_t q = 0; q < L; ++q) {
-            const uint32_t col = perm[j * L + q];
+            const uint32_t col = perm[base + q];
             double v;
             if (dtype == LINR_F32) v = (double)((const float*)x)[row * d + col];
             else v = (double)__uint_as_float((uint32_t)((const uint16_t*)x)[row * d + col] << 16);
-            sum = sum + (signs[j * L + q] > 0 ? v : -v);
+            sum = sum + (signs[base + q] > 0 ? v : -v);
         }
         if (sum > 0.0) word |= 1ull << jj;
     }
@@ -2624,24 +2628,27 @@ static hipError_t bits_dispatch(uint32_t words, ScanAct& act)
     if (words == 2) return scan_act(scan_kernel_bits<2>, act);
     if (words == 3) return scan_act(scan_kernel_bits<3>, act);
     if (words == 4) return scan_act(scan_kernel_bits<4>, act);
+    if (words == 6) return scan_act(scan_kernel_bits<6>, act);
+    if (words == 8) return scan_act(scan_kernel_bits<8>, act);
     return hipErrorInvalidDeviceFunction;
 }
 
 hipError_t linr_launch_sign_oporp_scatter(int dtype, const void* x, uint64_t n, uint32_t d, const uint32_t* perm,
-                                          const int8_t* signs, uint32_t k_bits, uint64_t* out, const uint32_t* scatter,
-                                          hipStream_t s)
+                                          const int8_t* signs, uint32_t k_bits, uint32_t reps, uint64_t* out,
+                                          const uint32_t* scatter, hipStream_t s)
 {
+    if (reps == 0 || k_bits == 0 || k_bits % reps != 0 || d % (k_bits / reps) != 0) return hipErrorInvalidValue;
     const uint64_t threads = n * ((k_bits + 63) / 64);
     if (threads == 0) return hipSuccess;
     hipLaunchKernelGGL(sign_oporp_kernel, dim3((uint32_t)((threads + 255) / 256)), dim3(256), 0, s, dtype, x, (u64)n, d, perm, signs,
-                       k_bits, (u64*)out, scatter);
+                       k_bits, reps, (u64*)out, scatter);
     return hipGetLastError();
 }
 
 hipError_t linr_launch_sign_oporp(int dtype, const void* x, uint64_t n, uint32_t d, const uint32_t* perm, const int8_t* signs,
-                                  uint32_t k_bits, uint64_t* out, hipStream_t s)
+                                  uint32_t k_bits, uint32_t reps, uint64_t* out, hipStream_t s)
 {
-    return linr_launch_sign_oporp_scatter(dtype, x, n, d, perm, signs, k_bits, out, nullptr, s);
+    return linr_launch_sign_oporp_scatter(dtype, x, n, d, perm, signs, k_bits, reps, out, nullptr, s);
 }
 
 hipError_t linr_launch_clause_words(const linr_clause_args& a, hipStream_t s)

@@ -375,14 +375,17 @@ hipError_t linr_launch_select(const linr_select_args& a, hipStream_t s)
     if (a.B == 0 || a.B > 65535u || a.n == 0 || a.K == 0 || a.k_bits == 0 || a.k_bits + 1 > LINR_SELECT_BINS ||
         a.seg_items == 0 || a.seg_items % 4096 != 0 || a.seg_items > 65536 ||
         a.n_seg != (uint32_t)((a.n + a.seg_items - 1) / a.seg_items) ||
-        (a.words != 1 && a.words != 2 && a.words != 4) || a.k_bits > 64 * a.words || (a.dcache && a.k_bits > 254) ||
+        (a.words != 1 && a.words != 2 && a.words != 3 && a.words != 4 && a.words != 6 && a.words != 8) || a.k_bits > 64 * a.words || (a.dcache && a.k_bits > 254) ||
         (((uintptr_t)a.dcache) & 15u))
         return hipErrorInvalidValue;
     if ((((uintptr_t)a.bits) | ((uintptr_t)a.mask) | ((uintptr_t)a.ts)) & 15u) return hipErrorInvalidValue;
     for (int pass = 0; pass < 2; ++pass) {
         if (a.words == 1) select_launch<1>(a, pass, s);
         else if (a.words == 2) select_launch<2>(a, pass, s);
-        else select_launch<4>(a, pass, s);
+        else if (a.words == 3) select_launch<3>(a, pass, s);
+        else if (a.words == 4) select_launch<4>(a, pass, s);
+        else if (a.words == 6) select_launch<6>(a, pass, s);
+        else select_launch<8>(a, pass, s);
         if (pass == 0) {
             hipLaunchKernelGGL(select_cut_kernel, dim3((a.n_seg + 63) / 64, a.B), dim3(256), 0, s, a);
             hipLaunchKernelGGL(select_scan_kernel, dim3(a.B), dim3(1024), 0, s, a);

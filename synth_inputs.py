@@ -253,6 +253,13 @@ def oporp_draw(d: int, seed: int = 0):
     return rng.permutation(d).astype(np.uint32), rng.choice(np.array([-1, 1], np.int8), d)
 
 
+def oporp_draws(d: int, reps: int, seed: int = 0):
+    """`reps` independent draws of the random inputs of Sign-OPORP, as [reps, d] arrays (codes longer than d bits)."""
+    rng = np.random.default_rng(_seed(9, 50 + seed))
+    perm = np.stack([rng.permutation(d) for _ in range(reps)]).astype(np.uint32)
+    return perm, rng.choice(np.array([-1, 1], np.int8), (reps, d))
+
+
 def random_codes(n: int, k_bits: int, seed: int = 0):
     """n uniformly random codes of k_bits bits as [n, ceil(k_bits/64)] uint64 (unused high bits zero)."""
     rng = np.random.default_rng(_seed(9, 100 + seed))

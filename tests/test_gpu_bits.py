@@ -42,16 +42,19 @@ def float_items(dtype, n, d, seed):
     return x
 
 
-@pytest.mark.parametrize("dtype,d,k_bits", [(S.F32, 64, 64), (S.F32, 128, 64), (S.BF16, 256, 128), (S.BF16, 64, 16),
-                                            (S.F32, 512 // 4, 128), (S.BF16, 192, 192)])
-def test_codes_match_the_oracle(oracle_mod, dtype, d, k_bits):
+@pytest.mark.parametrize("dtype,d,k_bits,reps", [(S.F32, 64, 64, 1), (S.F32, 128, 64, 1), (S.BF16, 256, 128, 1), (S.BF16, 64, 16, 1),
+                                                 (S.F32, 512 // 4, 128, 1), (S.BF16, 192, 192, 1),
+                                                 # codes longer than the embedding: independent draws, concatenated
+                                                 (S.F32, 128, 512, 4), (S.BF16, 128, 512, 8), (S.BF16, 128, 384, 3), (S.F32, 64, 192, 3),
+                                                 (S.BF16, 128, 256, 2), (S.F32, 64, 64, 2)])
+def test_codes_match_the_oracle(oracle_mod, dtype, d, k_bits, reps):
     import torch
     import paper_2407_13218_amd as L
-    say(f"codes dtype={dtype} d={d} k_bits={k_bits}")
+    say(f"codes dtype={dtype} d={d} k_bits={k_bits} draws={reps}")
     n = 3001
     x = float_items(dtype, n, d, d + k_bits)
     x[7] = 0                                                                   # a zero row: all bin sums zero
-    perm, signs = S.oporp_draw(d, k_bits)
+    perm, signs = S.oporp_draw(d, k_bits) if reps == 1 else S.oporp_draws(d, reps, k_bits)
     xt = torch.from_numpy(x.view(np.int16) if dtype == S.BF16 else x).cuda()
     mask = torch.zeros(n, dtype=torch.int32, device="cuda")
     ix = L.Index(n, d, dtype, 0)
@@ -84,7 +87,8 @@ def run_bits_case(oracle_mod, codes, k_bits, mask, ts, qbits, filt, T, label, ho
 @pytest.mark.parametrize("n,k_bits,B,T,with_ts", [(1, 64, 1, 1, False), (255, 64, 3, 10, False), (100_003, 64, 17, 1000, True),
                                                   (60_000, 128, 70, 500, False), (30_000, 256, 5, 2048, True),
                                                   (50_000, 32, 9, 100, False), (20_000, 192, 130, 64, False),
-                                                  (400_000, 64, 3, 8192, False)])
+                                                  (400_000, 64, 3, 8192, False),
+                                                  (40_000, 512, 9, 300, True), (30_000, 384, 70, 100, False), (25_000, 500, 3, 1000, False)])
 def test_bits_search_exact(oracle_mod, n, k_bits, B, T, with_ts):
     say(f"bits search n={n} k_bits={k_bits} B={B} T={T} ts={with_ts}")
     rng = np.random.default_rng(n + B)
@@ -174,7 +178,10 @@ def verify_second_stage(oracle_mod, dtype, x, mask, q, f, oi1, oc1, k, ids, sc, 
                                                   (S.F32, 64, 64, 8193, 100, 9), (S.BF16, 128, 64, 30_000, 2000, 9),
                                                   (S.F32, 64, 64, 40_000, 500, 9), (S.BF16, 256, 128, 20_000, 8192, 9),
                                                   # more queries than one group of the selection path serves
-                                                  (S.F32, 64, 64, 3000, 60, 41)])
+                                                  (S.F32, 64, 64, 3000, 60, 41),
+                                                  # 512-bit codes of 128-dimensional embeddings (four draws), both paths
+                                                  (S.BF16, 128, 512, 600, 100, 9), (S.BF16, 128, 512, 12_000, 1000, 9),
+                                                  (S.F32, 64, 384, 2000, 200, 5)])
 @pytest.mark.parametrize("rank_max", [0, 8192])
 def test_two_stage_against_the_oracle(oracle_mod, dtype, d, k_bits, T, k, B, rank_max):
     """rank_max = 8192 forces the ranking path (candidates ranked by linr_search_bits, re-scoring kernel) for every
@@ -190,7 +197,7 @@ def test_two_stage_against_the_oracle(oracle_mod, dtype, d, k_bits, T, k, B, ran
     q = float_items(dtype, B, d, 78)
     mask = rng.integers(0, 2 ** 32, n, dtype=np.uint64).astype(np.uint32)
     f = mixed_filters(B, rng, False)
-    perm, signs = S.oporp_draw(d, 1)
+    perm, signs = S.oporp_draw(d, 1) if k_bits <= d else S.oporp_draws(d, k_bits // min(d, 128), 1)
     as_t = (lambda a: torch.from_numpy(a.view(np.int16)).cuda()) if dtype == S.BF16 else (lambda a: torch.from_numpy(a).cuda())
     ix = L.Index(n, d, dtype, 0)
     ix.load(as_t(x), torch.from_numpy(mask.view(np.int32)).cuda())
@@ -236,6 +243,13 @@ def test_quantised_argument_errors():
     ixf = L.Index(n, d, S.F32, 0); ixf.load(torch.zeros((n, d), device="cuda"), mask)
     with pytest.raises(L.LinrError) as e:
         ixf.build_bits(perm, signs, 48)                                        # 64 % 48 != 0
+    assert e.value.code == -2
+    p4, s4 = S.oporp_draws(d, 5, 0)
+    with pytest.raises(L.LinrError) as e:
+        ixf.build_bits(p4, s4, 320)                                            # 5 words: no kernel for that length
+    assert e.value.code == -2
+    with pytest.raises(L.LinrError) as e:
+        ixf.build_bits(p4, s4, 128)                                            # 128 bits do not split into 5 draws
     assert e.value.code == -2
     ixf.k_bits = 64
     with pytest.raises(L.LinrError) as e:
