@@ -396,9 +396,12 @@ int linr_search_clauses_prefilter(const linr_index*, const void* Q, const float*
  * per slot), and items upserted into slots at or above the published mark appear, whole,
  * in searches enqueued after the update has finished on the device: the mark is published
  * by the first call that finds the update's event complete.  Rewriting a slot below the
- * published mark while searches on other streams are running is not atomic (such a search
- * may pair the slot's new mask with its old row): give the new version a fresh slot and
- * delete the old one instead.
+ * published mark -- a live one, or a DELETED one that is being recycled -- while searches on
+ * other streams are running is not atomic: the writer stores the row first and the mask
+ * last, but nothing orders a reader's loads of the two against them across streams, so
+ * such a search may pair the slot's new mask with its old row.  Give new versions fresh slots (at or above the mark) and
+ * delete the old ones; recycle deleted slots from the searches' own stream, or while no
+ * search is in flight.
  * Errors: LINR_E_STATE (updates not enabled), LINR_E_NULL, LINR_E_CAPACITY, LINR_E_SHAPE,
  * LINR_E_HIP.
  */

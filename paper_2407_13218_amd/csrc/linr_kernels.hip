@@ -104,7 +104,8 @@ scan_kernel(linr_scan_args A)
     for (int i = 0; i < QG; ++i) {
         f_all[i] = W.fall[i * 16 + row]; f_none[i] = W.fnone[i * 16 + row];
         f_t0[i] = W.tsmin[i * 16 + row]; f_t1[i] = W.tsmax[i * 16 + row] - f_t0[i];     // window as (start, length)
-        if (W.tsmax[i * 16 + row] < W.tsmin[i * 16 + row]) { f_all[i] = 0xFFFFFFFFu; f_none[i] = 0u; }   // empty window
+        // an empty window matches nothing -- where there is a timestamp column (without one, windows are not evaluated)
+        if (A.ts != nullptr && W.tsmax[i * 16 + row] < W.tsmin[i * 16 + row]) { f_all[i] = 0xFFFFFFFFu; f_none[i] = 0u; }
     }
 
     ChunkRegs<VK, KS> R;
@@ -1604,7 +1605,7 @@ __global__ void __launch_bounds__(256, 4) prefilter_score_kernel(linr_prefilter_
         if (b < A.nq) F = A.filters[b];
         else { F.all_bits = 0xFFFFFFFFu; F.none_bits = 0xFFFFFFFFu; F.n_any = 0; F.ts_min = 1; F.ts_max = 0; }
         const uint32_t none = F.none_bits | A.dead_bit;
-        const bool impossible = (F.all_bits & none) != 0u || F.ts_min > F.ts_max;
+        const bool impossible = (F.all_bits & none) != 0u || (A.ts != nullptr && F.ts_min > F.ts_max);   // (windows count only with a timestamp column)
         f_must[b] = impossible ? 0xFFFFFFFFu : F.all_bits;
         f_care[b] = impossible ? 0u : (F.all_bits | none);
         f_t0[b] = F.ts_min; f_span[b] = F.ts_max - F.ts_min;

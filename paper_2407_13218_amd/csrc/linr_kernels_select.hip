@@ -15,10 +15,11 @@
 // timestamp, and a flag for "any of" groups (checked with the full rule, only where the rest passed)
 struct SelectFilter {
     uint32_t care, must, t0, span; bool any;
-    __device__ __forceinline__ void set(const linr_filter& F, uint32_t dead_bit)
+    // has_ts: the index has a timestamp column (without one, windows are not evaluated, not even empty ones)
+    __device__ __forceinline__ void set(const linr_filter& F, uint32_t dead_bit, bool has_ts)
     {
         const uint32_t none = F.none_bits | dead_bit;
-        const bool impossible = (F.all_bits & none) != 0u || F.ts_min > F.ts_max;
+        const bool impossible = (F.all_bits & none) != 0u || (has_ts && F.ts_min > F.ts_max);
         must = impossible ? 0xFFFFFFFFu : F.all_bits;
         care = impossible ? 0u : (F.all_bits | none);
         t0 = F.ts_min; span = F.ts_max - F.ts_min;
@@ -109,7 +110,7 @@ __global__ void __launch_bounds__(256) select_hist_kernel(linr_select_args A)
     __syncthreads();
     if (threadIdx.x < nqb) {
         SelectFilter c;
-        c.set(A.filters[b0 + threadIdx.x], A.dead_bit);
+        c.set(A.filters[b0 + threadIdx.x], A.dead_bit, TS);
         Cs[threadIdx.x] = c;
         if (c.care != 0u || c.must != 0u || c.any) atomicOr(&s_need_mask, 1u);      // (must != 0 with care == 0: nothing passes)
         for (int w = 0; w < W; ++w) qs[threadIdx.x][w] = A.q_codes[(u64)(b0 + threadIdx.x) * W + w];
@@ -246,7 +247,7 @@ __global__ void __launch_bounds__(256) select_write_kernel(linr_select_args A)
     if (cut.t_diff == 0xFFFFFFFFu) return;
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
     SelectFilter C;
-    C.set(A.filters[b], A.dead_bit);
+    C.set(A.filters[b], A.dead_bit, TS);
     u64 q[W];
 #pragma unroll
     for (int w = 0; w < W; ++w) q[w] = A.q_codes[(u64)b * W + w];

@@ -328,3 +328,19 @@ def test_argument_errors_on_device():
     assert all(torch.equal(x, y) for x, y in zip(a, b) if x is not None)
     assert L.index_info(ix2.handle) == dict(n=1000, d=64, dtype=S.I8, has_ts=False, has_row_scale=True)
     ix.close(); ix2.close()
+
+
+@pytest.mark.parametrize("tuning", [None, {"no_coop": 1}, {"max_qg": 2}, {"max_qg": 1}, {"force_generic": 1}, {"no_dense": 1}])
+@pytest.mark.parametrize("B", [5, 40, 100])
+def test_empty_ts_window_without_a_ts_column_is_ignored_by_every_kernel(oracle_mod, tuning, B):
+    """filters in device memory are not validated; a window with ts_min > ts_max must then mean the same in every kernel
+    the planner can pick: nothing, where the index has timestamps -- and no constraint at all where it has none"""
+    from gpu_util import rand_int8_workload
+    w = rand_int8_workload(4242 + B, 50_000, 64, B, scaled=True, with_ts=False)
+    w["filters"]["ts_min"][::2] = 900
+    w["filters"]["ts_max"][::2] = 100
+    ora = run_oracle(oracle_mod, w, 30)
+    dev = to_cuda(w)
+    for strategy in ("masking", "prefilter"):
+        assert_exact(run_gpu(dev, k=30, tuning=tuning, host_filters=False, strategy=strategy), ora,
+                     f"empty window, no ts column, B={B}, {tuning}, {strategy}")

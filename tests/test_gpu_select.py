@@ -158,3 +158,18 @@ def test_errors():
     with pytest.raises(L.LinrError):
         fx.select_bits(q, S.make_filters(1), 5)
     fx.close()
+
+
+def test_empty_ts_window_without_a_ts_column_is_no_constraint(oracle_mod):
+    """device filters are not validated: ts_min > ts_max matches nothing where the index has timestamps, and is not
+    looked at where it has none -- as in the searches"""
+    say("select: empty window without a ts column")
+    n, k_bits, B = 50_000, 64, 4
+    rng = np.random.default_rng(3)
+    codes = S.random_codes(n, k_bits, seed=3)
+    q = S.random_codes(B, k_bits, seed=4)
+    mask = rng.integers(0, 2 ** 32, n, dtype=np.uint64).astype(np.uint32)
+    f = mixed_filters(B, rng, False)
+    f["ts_min"][:] = 900
+    f["ts_max"][:] = 100
+    run_case(oracle_mod, codes, k_bits, mask, None, q, f, 5000, "empty window, no ts", host_filters=False)
