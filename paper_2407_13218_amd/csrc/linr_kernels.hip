@@ -16,21 +16,6 @@
 #include "linr_device.h"
 #include <mutex>
 
-// Event counters for kernel studies; compiled in only with -DLINR_STATS (the shipped library has none).
-#ifdef LINR_STATS
-__device__ unsigned long long linr_stats[16];
-#define STAT_ADD(i, v) do { if ((threadIdx.x & 63) == 0) atomicAdd(&linr_stats[i], (unsigned long long)(v)); } while (0)
-#define STAT_CLOCK() clock64()
-extern "C" int linr_debug_stats(unsigned long long* out, int reset)
-{
-    if (out && hipMemcpyFromSymbol(out, HIP_SYMBOL(linr_stats), sizeof(unsigned long long) * 16) != hipSuccess) return -1;
-    if (reset) { unsigned long long z[16] = {0}; if (hipMemcpyToSymbol(HIP_SYMBOL(linr_stats), z, sizeof(z)) != hipSuccess) return -1; }
-    return 0;
-}
-#else
-#define STAT_ADD(i, v) do { } while (0)
-#define STAT_CLOCK() 0ll
-#endif
 
 #include "linr_scan_common.h"
 
@@ -726,8 +711,6 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A
     auto flush_queue = [&]() {
         wave_sync();
         const uint32_t nqd = *qcount;
-        STAT_ADD(4, 1);
-        STAT_ADD(5, nqd);
         for (uint32_t t = lane; t < nqd; t += 64) {
             const u64 key = qkey[t];
             const uint32_t ql = qql[t];
@@ -793,11 +776,6 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A
             uint32_t pend = 0;                       // groups of this tile whose test fired (uniform)
 #pragma unroll
             for (int i = 0; i < QW; ++i) pend |= wave_any(max16(acc[i]) >= bound[i]) ? (1u << i) : 0u;
-            STAT_ADD(0, QW);
-            const long long t_slow = pend ? STAT_CLOCK() : 0ll;
-            (void)t_slow;
-            if (pend) STAT_ADD(1, __popc(pend));
-            const uint32_t pend_any = pend;
             while (pend) {
                 const int i = __ffs((int)pend) - 1;
                 pend &= pend - 1;
@@ -820,8 +798,6 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A
                     v4i acc4 = {hv[4 * j], hv[4 * j + 1], hv[4 * j + 2], hv[4 * j + 3]};
                     const bool lane_hot = max(max(acc4[0], acc4[1]), max(acc4[2], acc4[3])) >= bi;
                     if (!wave_any(lane_hot)) continue;
-                    STAT_ADD(2, 1);
-                    STAT_ADD(3, __popcll(wave_ballot(lane_hot)));
                     v4u mk4, ts4;
                     v4f sc4;
                     uint32_t e4;
@@ -852,8 +828,6 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A
                     }
                 }
             }
-            if (pend_any) STAT_ADD(6, STAT_CLOCK() - t_slow);
-            (void)pend_any;
         }
         // (an ordinary load returns after all direct loads issued before it, so each refresh empties the ring: keep it rare)
         const bool refresh = ++since_refresh >= 64;
@@ -867,8 +841,6 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A
 
     // One step: wait until the chunk in stage `cur` has landed for every wave, refill the stage consumed one
     // step ago with the chunk NST - 1 steps ahead, then consume `cur`.
-    const long long t_begin = STAT_CLOCK();
-    (void)t_begin;
     if (n_mine) {
         // prologue: NST - 1 chunks in flight
         for (int st = 0; st < NST - 1; ++st) issue_next(st);
@@ -885,8 +857,6 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_wide(linr_scan_args A
         // nothing of this workgroup may still be on its way to LDS when its waves end
         __builtin_amdgcn_s_waitcnt(LINR_WAIT_VM(0));
     }
-    STAT_ADD(7, STAT_CLOCK() - t_begin);
-    STAT_ADD(8, 1);
     if (active) {
         flush_queue();
         own_stores_done();
