@@ -236,7 +236,8 @@ int linr_index_destroy(linr_index*);
  * codes is their number of equal bits.  Codes longer than one pass over the coordinates
  * gives (Sec. 5.3.1 uses 512 bits for d = 128) are R independent draws of (perm, signs),
  * k_bits / R bits each with L = d * R / k_bits, one after the other: bit r * (k_bits / R) + j
- * is bit j of draw r.  Limits: k_bits <= 512 with W in {1, 2, 3, 4, 6, 8}; k_bits % R == 0;
+ * is bit j of draw r (draws add information only with bins of two or more coordinates:
+ * with L = 1 every draw is the same sign quantisation).  Limits: k_bits <= 512 with W in {1, 2, 3, 4, 6, 8}; k_bits % R == 0;
  * d % (k_bits / R) == 0; R <= 64.
  *
  * linr_index_build_bits  derives the codes of every resident item of an fp32 / bf16

@@ -1006,8 +1006,8 @@ static void select_plan(const linr_index& v, uint32_t B, select_layout* L)
     L->off_eq = o; o += align_up((uint64_t)B * L->n_seg * 8, 256);
     L->off_cut = o; o += align_up((uint64_t)B * sizeof(linr_select_cut), 256);
     L->off_filters = o; o += align_up((uint64_t)B * sizeof(linr_filter), 256);
-    // one byte per item and query: the differing bits, kept between the passes (codes of up to 254 bits)
-    L->off_dcache = o; if (v.k_bits <= 254) o += align_up((uint64_t)B * L->n_seg * L->seg_items, 256);
+    // one byte per item and query: the differing bits, kept between the passes (saturating at 255 for longer codes)
+    L->off_dcache = o; o += align_up((uint64_t)B * L->n_seg * L->seg_items, 256);
     L->total = o;
 }
 
@@ -1061,7 +1061,7 @@ extern "C" int linr_select_bits(const linr_index* ix, const uint64_t* qbits, uin
     a.hist = (unsigned long long*)(ws + L.off_hist); a.seg_hist = (uint32_t*)(ws + L.off_seg);
     a.gt_base = (unsigned long long*)(ws + L.off_gt); a.eq_base = (unsigned long long*)(ws + L.off_eq);
     a.cut = (linr_select_cut*)(ws + L.off_cut);
-    a.dcache = v.k_bits <= 254 ? (uint8_t*)(ws + L.off_dcache) : nullptr;
+    a.dcache = (uint8_t*)(ws + L.off_dcache);
     a.out_ids = out_ids; a.out_counts = (unsigned long long*)out_counts; a.out_thresholds = out_thresholds;
     HIP_TRY(linr_launch_select(a, st));
     return LINR_OK;

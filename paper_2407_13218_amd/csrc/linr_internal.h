@@ -193,7 +193,7 @@ struct linr_select_args {
     uint32_t* seg_hist;                // [B][n_seg][k_bits + 1]
     unsigned long long* gt_base; unsigned long long* eq_base;     // [B][n_seg]
     linr_select_cut* cut;              // [B]
-    uint8_t* dcache;                   // [B][n_seg * seg_items] differing bits per item (0xFF infeasible), or nullptr: recompute
+    uint8_t* dcache;                   // [B][n_seg * seg_items] differing bits per item (255: infeasible, or 255 and more), or nullptr: recompute
     uint32_t* out_ids; unsigned long long* out_counts; int32_t* out_thresholds;
 };
 hipError_t linr_launch_select(const linr_select_args& a, hipStream_t s);

@@ -94,7 +94,7 @@ struct SelectTile {
 
 // pass 1: grid (segments, groups of up to 8 queries): every item of the segment is read once and compared with each
 // query of the group.  seg_hist[b][segment][bins], hist[b][bins] (zeroed by the caller); with `dcache` the count of
-// differing bits of every (query, item) is kept, one byte each (0xFF = infeasible), so that pass 2 reads 1 byte per item
+// differing bits of every (query, item) is kept, one byte each (255 = infeasible, or 255 bits and more), so that pass 2 reads 1 byte per item
 template <int W, bool TS>
 __global__ void __launch_bounds__(256) select_hist_kernel(linr_select_args A)
 {
@@ -129,7 +129,7 @@ __global__ void __launch_bounds__(256) select_hist_kernel(linr_select_args A)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             atomicAdd(&mine[qi * 4 * HB + (diff[r] < (uint32_t)(HB - 1) ? diff[r] : (uint32_t)(HB - 1))], 1u);
-            packed |= (diff[r] & 0xFFu) << (8 * r);
+            packed |= (diff[r] < 255u ? diff[r] : 255u) << (8 * r);      // 255: infeasible, or (codes of more than 254 bits) 255 bits or more
         }
         // (the segments are whole tiles: the cache is padded to them)
         if (A.dcache) __builtin_nontemporal_store(packed, (uint32_t*)(A.dcache + (u64)(b0 + qi) * row + i0));
@@ -245,6 +245,7 @@ __global__ void __launch_bounds__(256) select_write_kernel(linr_select_args A)
     const uint32_t b = blockIdx.y, seg = blockIdx.x;
     const linr_select_cut cut = A.cut[b];
     if (cut.t_diff == 0xFFFFFFFFu) return;
+    if (A.dcache && cut.t_diff <= 254u) return;       // this query's cut is decided by the kept bytes (the other pass-2 kernel)
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
     SelectFilter C;
     C.set(A.filters[b], A.dead_bit, TS);
@@ -299,6 +300,7 @@ __global__ void __launch_bounds__(256) select_write_cached_kernel(linr_select_ar
     const uint32_t b = blockIdx.y, seg = blockIdx.x;
     const linr_select_cut cut = A.cut[b];
     if (cut.t_diff == 0xFFFFFFFFu) return;
+    if (cut.t_diff > 254u) return;                    // (long codes) the kept bytes saturate at 255: the recomputing kernel serves this query
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
     u64 run_gt = A.gt_base[(u64)b * A.n_seg + seg], run_eq = A.eq_base[(u64)b * A.n_seg + seg];
     const u64 need = cut.need_eq;
@@ -362,11 +364,15 @@ static void select_launch(const linr_select_args& a, int pass, hipStream_t s)
         const dim3 grid1(a.n_seg, (a.B + LINR_SELECT_QB - 1) / LINR_SELECT_QB);
         if (a.ts) hipLaunchKernelGGL((select_hist_kernel<W, true>), grid1, block, 0, s, a);
         else hipLaunchKernelGGL((select_hist_kernel<W, false>), grid1, block, 0, s, a);
-    } else if (a.dcache) {
-        hipLaunchKernelGGL(select_write_cached_kernel, grid, block, 0, s, a);
     } else {
-        if (a.ts) hipLaunchKernelGGL((select_write_kernel<W, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((select_write_kernel<W, false>), grid, block, 0, s, a);
+        // with the kept byte per (query, item): one pass over those bytes.  Codes of more than 254 bits: a query whose cut
+        // lies at 255 differing bits or beyond (rare: it keeps most of the items) is served by the recomputing kernel,
+        // whose workgroups leave at once for every other query.
+        if (a.dcache) hipLaunchKernelGGL(select_write_cached_kernel, grid, block, 0, s, a);
+        if (!a.dcache || a.k_bits > 254) {
+            if (a.ts) hipLaunchKernelGGL((select_write_kernel<W, true>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((select_write_kernel<W, false>), grid, block, 0, s, a);
+        }
     }
 }
 
@@ -376,7 +382,7 @@ hipError_t linr_launch_select(const linr_select_args& a, hipStream_t s)
     if (a.B == 0 || a.B > 65535u || a.n == 0 || a.K == 0 || a.k_bits == 0 || a.k_bits + 1 > LINR_SELECT_BINS ||
         a.seg_items == 0 || a.seg_items % 4096 != 0 || a.seg_items > 65536 ||
         a.n_seg != (uint32_t)((a.n + a.seg_items - 1) / a.seg_items) ||
-        (a.words != 1 && a.words != 2 && a.words != 3 && a.words != 4 && a.words != 6 && a.words != 8) || a.k_bits > 64 * a.words || (a.dcache && a.k_bits > 254) ||
+        (a.words != 1 && a.words != 2 && a.words != 3 && a.words != 4 && a.words != 6 && a.words != 8) || a.k_bits > 64 * a.words ||
         (((uintptr_t)a.dcache) & 15u))
         return hipErrorInvalidValue;
     if ((((uintptr_t)a.bits) | ((uintptr_t)a.mask) | ((uintptr_t)a.ts)) & 15u) return hipErrorInvalidValue;

@@ -43,7 +43,9 @@ def run_case(oracle_mod, codes, k_bits, mask, ts, qbits, filt, K, label, host_fi
     (65_536, 64, 2, 30_000, False), (65_537, 64, 2, 65_537, False), (200_003, 128, 5, 77_777, True),
     (300_000, 256, 3, 150_000, False), (131_072, 200, 2, 1000, False), (1_000_000, 64, 13, 50_000, True),
     # three, six and eight words per code
-    (120_000, 192, 2, 5000, False), (100_000, 384, 2, 999, True), (150_000, 512, 3, 40_000, False), (70_000, 450, 9, 35_000, True)])
+    (120_000, 192, 2, 5000, False), (100_000, 384, 2, 999, True), (150_000, 512, 3, 40_000, False), (70_000, 450, 9, 35_000, True),
+    # long codes whose cut lies beyond what the kept byte per item resolves (255 differing bits or more)
+    (60_000, 512, 2, 55_000, False), (80_000, 384, 3, 79_000, True)])
 def test_selection_matches_the_stable_sort(oracle_mod, n, k_bits, B, K, with_ts):
     say(f"select n={n} k_bits={k_bits} B={B} K={K} ts={with_ts}")
     rng = np.random.default_rng(n % 1000 + k_bits + B)
