@@ -10,8 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "liblinr.so")
 CSRC = os.path.join(HERE, "csrc")
-SOURCES = [os.path.join(CSRC, f) for f in ("linr_kernels.hip", "linr_kernels_dense.hip", "linr_kernels_select.hip", "linr_api.cpp")]
-HEADERS = [os.path.join(CSRC, f) for f in ("linr_internal.h", "linr_device.h", "linr_scan_common.h")] + \
+SOURCES = [os.path.join(CSRC, f) for f in ("linr_kernels.hip", "linr_kernels_dense.hip", "linr_kernels_dense_bf16.hip", "linr_kernels_select.hip", "linr_api.cpp")]
+HEADERS = [os.path.join(CSRC, f) for f in ("linr_internal.h", "linr_device.h", "linr_scan_common.h", "linr_dense.h")] + \
           [os.path.join(ROOT, "include", "linr.h")]
 DEPS = SOURCES + HEADERS + [os.path.join(CSRC, "mfma_issue_bench.hip")]
 ISSUE_BENCH = os.path.join(HERE, "mfma_issue_bench")  # executable (git-ignored, like the library)
@@ -43,7 +43,7 @@ def build(force: bool = True, verbose: bool = False, defines=()) -> str:
             raise RuntimeError(f"hipcc failed on {os.path.basename(src)}")
         return obj, res.stderr
 
-    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as pool:
+    with ThreadPoolExecutor(max_workers=min(5, len(SOURCES))) as pool:
         results = list(pool.map(compile_one, SOURCES))
     if verbose:
         for _, err in results:

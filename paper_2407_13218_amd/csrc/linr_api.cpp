@@ -347,8 +347,11 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
     // (a tuning that asks for one of the other kernel families is honoured)
     const bool other_family = g_tuning.force_generic || g_tuning.no_coop || g_tuning.max_qg || g_tuning.coop_min_groups ||
                               g_tuning.wide_min_batch;
-    const bool dense_ok = !other_family && !g_tuning.no_dense && ix->dtype == LINR_I8 && !bits_mode && m == 1 && ix->row_bytes == 64 &&
-                          B >= (g_tuning.dense_min_batch ? g_tuning.dense_min_batch : 65u) && !(ix->row_scale && !ix->scale_stats);
+    const bool dense_common = !other_family && !g_tuning.no_dense && !bits_mode && m == 1 &&
+                              B >= (g_tuning.dense_min_batch ? g_tuning.dense_min_batch : 65u);
+    const bool dense_ok = dense_common && ix->dtype == LINR_I8 && ix->row_bytes == 64 && !(ix->row_scale && !ix->scale_stats);
+    // the same design for bf16 rows of 256 bytes (linr_kernels_dense_bf16.hip): up to 8 groups per wave, 512 queries per stream
+    const bool dense_bf16_ok = dense_common && ix->dtype == LINR_BF16 && ix->row_bytes == 256;
     uint32_t dg = 0, dsets = 1, dmax = 1024;
     if (dense_ok) {
         // up to four query sets per workgroup, each an equal run (a multiple of 64) of the batch's order; a wave keeps
@@ -364,6 +367,18 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
             dg = ((((b1 + dsets - 1) / dsets) + 63u) & ~63u) / 16;
         }
         if (linr_dense_dispatch(0, p->vk, dg, ix->ts != nullptr, 0, nullptr, nullptr, nullptr) != hipSuccess) dg = 0;
+    } else if (dense_bf16_ok) {
+        dmax = 512;
+        const uint32_t b1 = B < dmax ? B : dmax;
+        dsets = b1 <= 128 ? 1u : b1 <= 256 ? 2u : 4u;
+        dg = ((((b1 + dsets - 1) / dsets) + 63u) & ~63u) / 16;
+        if (g_tuning.dense_groups == 4 || g_tuning.dense_groups == 8) {
+            dg = g_tuning.dense_groups;
+            dmax = LINR_WAVES_PER_BLOCK * dg * 16;
+            const uint32_t b2 = B < dmax ? B : dmax, sets = (b2 + dg * 16 - 1) / (dg * 16);
+            dsets = sets <= 1 ? 1u : sets <= 2 ? 2u : 4u;
+        }
+        if (linr_dense_bf16_dispatch(0, p->ks, dg, ix->ts != nullptr, 0, nullptr, nullptr, nullptr) != hipSuccess) dg = 0;
     }
     uint32_t Bp;
     if (dg) {

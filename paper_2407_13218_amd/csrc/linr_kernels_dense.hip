@@ -31,53 +31,7 @@
 //     steps (no staging registers, no workgroup barrier per step), consumed with hand-placed LDS reads; candidate
 //     keys are queued in LDS and written out in bulk.
 // The survivors' keys go to the same per-(slot, query) segments, bounds, sweeps and merges as in the other kernels.
-#include "linr_scan_common.h"
-#include <type_traits>
-
-#define DENSE_CH 128                   // items per chunk, the unit of the sweep plan and of a wave's walk
-#define DENSE_SUB 32                   // items per step of a wave (two tiles of 16)
-#define DENSE_QCAP 192                 // keys a wave queues in LDS before writing them out
-#define DENSE_SLACK LINR_DENSE_SLACK   // room a segment must have beyond k: the queue's keys + what one chunk can add per query
-#define DENSE_SCRATCH_WORDS 516        // per wave: queue (keys, query numbers) / compaction histogram / flush prefix
-// Stand-in for "no bound" (-) and "no query" (+) among the integer bounds T.  |raw| < 2^20, so raw - T stays within
-// +-(2^29 + 2^20) and its difference to a test value in [-2^29 (1 + 2^-11) - 3, 2^28] cannot overflow 32 bits.
-#define DENSE_BIG (1 << 29)
-
-// s_waitcnt immediate that waits for the vector-memory counter only (gfx9 encoding)
-#define DENSE_WAIT_VM(n) (((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
-
-// The ring and the per-query arrays are read with hand-placed LDS instructions: for an LDS access the compiler can
-// see, it would wait until every outstanding direct load has landed, i.e. for the memory latency of the step
-// requested last.  That a stage's loads have landed is established by the counted wait of the step loop.
-__device__ __forceinline__ uint32_t dense_lds_addr(const void* p)
-{
-    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
-}
-
-__device__ __forceinline__ int dense_floor_to_int(float x)      // floor(x) clamped to +-DENSE_BIG (x may be +-inf)
-{
-    return (int)fminf(fmaxf(floorf(x), -(float)DENSE_BIG), (float)DENSE_BIG);
-}
-
-// running maximum over the four accumulators of a product (two v_max3_i32)
-__device__ __forceinline__ int dense_max_acc(int m, const v4i& a)
-{
-    m = max(max(m, a[0]), a[1]);
-    return max(max(m, a[2]), a[3]);
-}
-
-// Per-query state of a workgroup in LDS.  Bounds are kept per WAVE (a wave's accumulator inputs and the values its
-// survivor path adds back must be the same numbers, and waves refresh at different times); the filters, which never
-// change during a launch, per query set.
-template <int NQW, bool TS>
-struct DenseQ {
-    float thr[4 * NQW];                // [wave][query] lower bound of the ranking value (raw ranking: the int32 bound's bits; "none": -inf / INT_MIN)
-    int T[4 * NQW];                    // [wave][query] integer bound that enters the accumulators (see the header comment)
-    uint32_t fa[4 * NQW], fn[4 * NQW]; // [set][query] compact filter: an item passes the all / none clauses iff (mask & fn) == fa
-    uint32_t t0[TS ? 4 * NQW : 1], t1[TS ? 4 * NQW : 1];   // timestamp window
-    uint16_t qi[4 * NQW];              // [set][query] index of the query in the batch (0xFFFF: none)
-    uint8_t flag[4 * NQW];             // 1: the filter has any-of clauses (read the full record from global memory)
-};
+#include "linr_dense.h"
 
 template <int VK, int NG, bool TS>
 __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args A)
@@ -237,13 +191,21 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
     unsigned char* const ring = ring_all[wib];
     const uint32_t ring_lds = dense_lds_addr(ring);
     const uint32_t nwalk = gridDim.x * wps;              // walkers of the sweep: one per slot
+    // A sweep with fewer chunks than slots (the first, small sweeps, where bounds are missing or weak and most pairs go
+    // through the slow path) is dealt out by steps instead of chunks: SPC neighbouring slots share a walker and each
+    // takes one step of every chunk it visits, so SPC times as many waves have work.
+    constexpr uint32_t SPC = DENSE_CH / DENSE_SUB;       // steps per chunk
+    const uint32_t n_dense32 = (uint32_t)A.n_dense, slot_first = blockIdx.x * wps;
+    const bool fine = nwalk % SPC == 0u && n_dense32 < nwalk;
+    const uint32_t walker = fine ? slot / SPC : slot, walker_first = fine ? slot_first / SPC : slot_first;
+    const uint32_t nwalkers = fine ? nwalk / SPC : nwalk;
+    const uint32_t sub_fixed = fine ? slot % SPC : 0u;
     SweepWalk ahead;
-    ahead.init_strided(slot, nwalk, A);
+    ahead.init_strided(walker, nwalkers, A);
     // every wave of a workgroup runs the step count of the workgroup's first slot (the largest); steps past the end of
     // a wave's own walk fetch its last chunk once more and consume nothing
-    const uint32_t n_dense32 = (uint32_t)A.n_dense, slot_first = blockIdx.x * wps;
-    const uint32_t n_wg = slot_first < n_dense32 ? (n_dense32 - slot_first + nwalk - 1) / nwalk : 0u;
-    const uint32_t nsteps = n_wg * (DENSE_CH / DENSE_SUB);
+    const uint32_t n_wg = walker_first < n_dense32 ? (n_dense32 - walker_first + nwalkers - 1) / nwalkers : 0u;
+    const uint32_t nsteps = fine ? n_wg : n_wg * SPC;
     // what this lane fetches, relative to the first item of a step (the same for every step)
     const uint32_t off_row = (uint32_t)(col * 64 + g4 * 16);
     const uint32_t side_lane = (uint32_t)lane & 31u;
@@ -256,11 +218,11 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
     auto fetch = [&](uint32_t stage) __attribute__((always_inline)) {
         if (f_sub == 0) {
             f_valid = ahead.valid();
-            if (f_valid) f_item = ahead.lc() * A.stride * DENSE_CH;
+            if (f_valid) f_item = ahead.lc() * A.stride * DENSE_CH + sub_fixed * DENSE_SUB;
             ahead.advance();
         }
         const u64 item = f_item + f_sub * DENSE_SUB;
-        f_sub = (f_sub + 1) & (DENSE_CH / DENSE_SUB - 1);
+        f_sub = fine ? 0u : (f_sub + 1) & (SPC - 1);
         if ((uint32_t)lane == stage) stage_info = (uint32_t)(item >> 5) | (f_valid ? 0x80000000u : 0u);
         unsigned char* const dst = ring + stage * STG;
         if (item + DENSE_SUB <= A.n) {                   // uniform; all steps but those at the end of the index
