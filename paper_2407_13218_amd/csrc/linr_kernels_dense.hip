@@ -297,15 +297,6 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
                 const bool act = bm != 0u;
                 const uint32_t a = (uint32_t)(__ffs((int)bm) - 1) & 15u;
                 bm &= bm - 1u;
-                // the lane's value a: a binary tree of selects over the 16 registers
-                const bool a0 = (a & 1u) != 0u, a1 = (a & 2u) != 0u, a2 = (a & 4u) != 0u, a3 = (a & 8u) != 0u;
-                // (written out value by value and pinned: as an indexed array the compiler would place it in scratch memory)
-                int e0 = a0 ? H[0][1] : H[0][0], e1 = a0 ? H[0][3] : H[0][2], e2 = a0 ? H[1][1] : H[1][0], e3 = a0 ? H[1][3] : H[1][2];
-                int e4 = a0 ? H[2][1] : H[2][0], e5 = a0 ? H[2][3] : H[2][2], e6 = a0 ? H[3][1] : H[3][0], e7 = a0 ? H[3][3] : H[3][2];
-                pin(e0); pin(e1); pin(e2); pin(e3); pin(e4); pin(e5); pin(e6); pin(e7);
-                int f0 = a1 ? e1 : e0, f1 = a1 ? e3 : e2, f2 = a1 ? e5 : e4, f3 = a1 ? e7 : e6;
-                pin(f0); pin(f1); pin(f2); pin(f3);
-                const int hv = a3 ? (a2 ? f3 : f2) : (a2 ? f1 : f0);
                 const uint32_t ql = (uint32_t)(qt * 4) * 16u + (a >> 2) * 16u + 4u * (uint32_t)g4 + (a & 3u);   // wave-local query of the pair
                 uint32_t fa, fn, flag, t0 = 0u, t1 = 0xFFFFFFFFu;
                 int T;
@@ -326,6 +317,18 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense(linr_scan_args 
                 if constexpr (TS) {
                     if (has_ts) ok = ok && tc.ts >= t0 && tc.ts <= t1;
                 }
+                // most pairs that beat their bound fail their filter when the pass rate is low: a round without any
+                // survivor of the filter ends here, before the value is selected and scored
+                if (!wave_any(ok)) continue;
+                // the lane's value a: a binary tree of selects over the 16 registers
+                const bool a0 = (a & 1u) != 0u, a1 = (a & 2u) != 0u, a2 = (a & 4u) != 0u, a3 = (a & 8u) != 0u;
+                // (written out value by value and pinned: as an indexed array the compiler would place it in scratch memory)
+                int e0 = a0 ? H[0][1] : H[0][0], e1 = a0 ? H[0][3] : H[0][2], e2 = a0 ? H[1][1] : H[1][0], e3 = a0 ? H[1][3] : H[1][2];
+                int e4 = a0 ? H[2][1] : H[2][0], e5 = a0 ? H[2][3] : H[2][2], e6 = a0 ? H[3][1] : H[3][0], e7 = a0 ? H[3][3] : H[3][2];
+                pin(e0); pin(e1); pin(e2); pin(e3); pin(e4); pin(e5); pin(e6); pin(e7);
+                int f0 = a1 ? e1 : e0, f1 = a1 ? e3 : e2, f2 = a1 ? e5 : e4, f3 = a1 ? e7 : e6;
+                pin(f0); pin(f1); pin(f2); pin(f3);
+                const int hv = a3 ? (a2 ? f3 : f2) : (a2 ? f1 : f0);
                 const int raw = hv + T;                  // the accumulator input was -T exactly
                 uint32_t hi;
                 if constexpr (SCALED) {

@@ -233,25 +233,6 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense_bf16(linr_scan_
                 const bool act = bm != 0u;
                 const uint32_t a = (uint32_t)(__ffs((int)bm) - 1) & 15u;
                 bm &= bm - 1u;
-                const bool a0 = (a & 1u) != 0u, a1 = (a & 2u) != 0u, a2 = (a & 4u) != 0u, a3 = (a & 8u) != 0u;
-                // (the group first, then the row; every select written out and pinned -- as an indexed array the
-                // compiler would place the accumulators in scratch memory, whose loads wait for the whole ring)
-                int t0v, t1v, t2v, t3v;
-                {
-                    int lo0 = __float_as_int(a2 ? H[1][0] : H[0][0]), hi0 = __float_as_int(a2 ? H[3][0] : H[2][0]);
-                    pin(lo0); pin(hi0);
-                    t0v = a3 ? hi0 : lo0; pin(t0v);
-                    int lo1 = __float_as_int(a2 ? H[1][1] : H[0][1]), hi1 = __float_as_int(a2 ? H[3][1] : H[2][1]);
-                    pin(lo1); pin(hi1);
-                    t1v = a3 ? hi1 : lo1; pin(t1v);
-                    int lo2 = __float_as_int(a2 ? H[1][2] : H[0][2]), hi2 = __float_as_int(a2 ? H[3][2] : H[2][2]);
-                    pin(lo2); pin(hi2);
-                    t2v = a3 ? hi2 : lo2; pin(t2v);
-                    int lo3 = __float_as_int(a2 ? H[1][3] : H[0][3]), hi3 = __float_as_int(a2 ? H[3][3] : H[2][3]);
-                    pin(lo3); pin(hi3);
-                    t3v = a3 ? hi3 : lo3; pin(t3v);
-                }
-                const float hv = __int_as_float(a1 ? (a0 ? t3v : t2v) : (a0 ? t1v : t0v));
                 const uint32_t ql = (uint32_t)(qt * 4) * 16u + (a >> 2) * 16u + 4u * (uint32_t)g4 + (a & 3u);
                 uint32_t fa, fn, flag, t0 = 0u, t1 = 0xFFFFFFFFu;
                 float low, thr;
@@ -271,6 +252,27 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense_bf16(linr_scan_
                 if constexpr (TS) {
                     if (has_ts) ok = ok && ts >= t0 && ts <= t1;
                 }
+                // (a round without any survivor of the filter ends here, before the value is selected and scored)
+                if (!wave_any(ok)) continue;
+                const bool a0 = (a & 1u) != 0u, a1 = (a & 2u) != 0u, a2 = (a & 4u) != 0u, a3 = (a & 8u) != 0u;
+                // (the group first, then the row; every select written out and pinned -- as an indexed array the
+                // compiler would place the accumulators in scratch memory, whose loads wait for the whole ring)
+                int t0v, t1v, t2v, t3v;
+                {
+                    int lo0 = __float_as_int(a2 ? H[1][0] : H[0][0]), hi0 = __float_as_int(a2 ? H[3][0] : H[2][0]);
+                    pin(lo0); pin(hi0);
+                    t0v = a3 ? hi0 : lo0; pin(t0v);
+                    int lo1 = __float_as_int(a2 ? H[1][1] : H[0][1]), hi1 = __float_as_int(a2 ? H[3][1] : H[2][1]);
+                    pin(lo1); pin(hi1);
+                    t1v = a3 ? hi1 : lo1; pin(t1v);
+                    int lo2 = __float_as_int(a2 ? H[1][2] : H[0][2]), hi2 = __float_as_int(a2 ? H[3][2] : H[2][2]);
+                    pin(lo2); pin(hi2);
+                    t2v = a3 ? hi2 : lo2; pin(t2v);
+                    int lo3 = __float_as_int(a2 ? H[1][3] : H[0][3]), hi3 = __float_as_int(a2 ? H[3][3] : H[2][3]);
+                    pin(lo3); pin(hi3);
+                    t3v = a3 ? hi3 : lo3; pin(t3v);
+                }
+                const float hv = __int_as_float(a1 ? (a0 ? t3v : t2v) : (a0 ? t1v : t0v));
                 const float sv = hv + low;               // ranking value: the accumulator plus what it started from
                 ok = ok && sv >= thr;
                 if (ok && flag) ok = filter_pass(A.filters[s_qi[ql]], mk, has_ts, ts);
