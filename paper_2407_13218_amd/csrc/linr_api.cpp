@@ -736,7 +736,7 @@ static double filter_pass_estimate(const float* freq, const linr_filter& f)
 //   pre-filtering, per group of Bg <= 32 queries: one pass over the mask column, 0.72 + 0.10 Bg, plus per feasible
 //     (item, query) pair 15 + 27 / Bg picoseconds per 64 bytes of row (gathered rows are shared by the group's queries);
 //   masking, up to 64 queries: bound by HBM, (row bytes + 8) / 6.3 TB/s whatever the pass rate;
-//   masking, larger batches (bound by instruction issue): per 256 queries 24 + 9.5 (log10(0.5 / pass rate))^2 on
+//   masking, larger batches (bound by instruction issue): per 256 queries 24 + 7.8 (log10(0.5 / pass rate))^2 on
 //     64-byte int8 rows -- the lower the pass rate, the later the bounds of the score test tighten; other row shapes
 //     in proportion to their bytes.
 // Returns 1 if explicit pre-filtering is modelled to be faster by a margin (masking cannot overflow: it is the default).
@@ -757,7 +757,7 @@ static int plan_prefers_prefilter(const linr_index* ix, uint32_t B, uint32_t m, 
         double pm = sum_p / B;
         pm = pm < 1.0e-4 ? 1.0e-4 : pm > 0.5 ? 0.5 : pm;
         const double x = log10(0.5 / pm);
-        const double issue = (double)B / 256.0 * (24.0 + 9.5 * x * x) * row64;
+        const double issue = (double)B / 256.0 * (24.0 + 7.8 * x * x) * row64;
         if (issue > t_mask) t_mask = issue;
     }
     return t_pre < 0.85 * t_mask;
