@@ -487,7 +487,8 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
     // stride[l-1] (those were visited before), so every chunk is scored exactly once per search; the k best keys
     // found so far are carried from merge to merge and the k-th of them bounds the next sweep.  A sweep that
     // multiplies the number of visited items by r lets about k * (r - 1) / pass_rate items per query through
-    // its score test, so the last, largest sweeps use small factors (2, 4, 4) and the early, tiny ones a big one.
+    // its score test, so the last, largest sweeps use small factors (2, 4, 4 by default) and the early, tiny ones a
+    // big one.
     uint32_t ratio = g_tuning.sample_ratio ? g_tuning.sample_ratio : 8;
     uint64_t min_sample = g_tuning.min_sample ? g_tuning.min_sample : (uint64_t)4 * k;
     uint32_t max_levels = g_tuning.max_levels ? g_tuning.max_levels : LINR_MAX_LEVELS;
@@ -497,13 +498,21 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
     // chunks reads them in longer contiguous runs than the finer sweeps do)
     const bool top_split = !g_tuning.no_top_split && p->n_chunks >= 65536 && (p->coop || p->generic || p->qg > 2) &&
                            !(p->bits && B <= 8);
-    static const uint32_t top_ratios[3] = {2, 4, 4};
+    // (the large-batch kernels pay for every pair that beats its query's bound, and a sweep that multiplies the visited
+    // items by r lets k * (r - 1) / pass_rate of them through per query: they halve all the way down to sweeps of a few
+    // million items -- measured at 1e9 x 64 B, B = 256: 23.0 / 29.0 ms at 50 / 5 % pass against 23.9 / 31.5 with {2, 4, 4})
+    const uint32_t top_code = g_tuning.top_ratios ? g_tuning.top_ratios
+                              : p->dense ? (ix->n >= (1ull << 28) ? 0x2222222u : 0x44222u) : 0x442u;
     uint32_t strides[LINR_MAX_LEVELS];
     uint32_t nl = 0;
     uint64_t s = 1;
     strides[nl++] = 1;
     while (nl < max_levels) {
-        uint32_t r = (top_split && nl - 1 < 3) ? top_ratios[nl - 1] : ratio;
+        uint32_t r = ratio;
+        if (top_split && nl - 1 < 8) {
+            const uint32_t digit = (top_code >> (4 * (nl - 1))) & 15u;
+            if (digit == 2 || digit == 4 || digit == 8) r = digit;
+        }
         uint64_t s2 = s * r;
         uint64_t items = (p->n_chunks / s2) * p->chunk_items;
         if (s2 > 0x40000000ull || items < min_sample) break;
@@ -736,7 +745,7 @@ static double filter_pass_estimate(const float* freq, const linr_filter& f)
 //   pre-filtering, per group of Bg <= 32 queries: one pass over the mask column, 0.72 + 0.10 Bg, plus per feasible
 //     (item, query) pair 15 + 27 / Bg picoseconds per 64 bytes of row (gathered rows are shared by the group's queries);
 //   masking, up to 64 queries: bound by HBM, (row bytes + 8) / 6.3 TB/s whatever the pass rate;
-//   masking, larger batches (bound by instruction issue): per 256 queries 24 + 7.8 (log10(0.5 / pass rate))^2 on
+//   masking, larger batches (bound by instruction issue): per 256 queries 23 + 7.6 (log10(0.5 / pass rate))^2 on
 //     64-byte int8 rows -- the lower the pass rate, the later the bounds of the score test tighten; other row shapes
 //     in proportion to their bytes.
 // Returns 1 if explicit pre-filtering is modelled to be faster by a margin (masking cannot overflow: it is the default).
@@ -757,7 +766,7 @@ static int plan_prefers_prefilter(const linr_index* ix, uint32_t B, uint32_t m, 
         double pm = sum_p / B;
         pm = pm < 1.0e-4 ? 1.0e-4 : pm > 0.5 ? 0.5 : pm;
         const double x = log10(0.5 / pm);
-        const double issue = (double)B / 256.0 * (24.0 + 7.8 * x * x) * row64;
+        const double issue = (double)B / 256.0 * (23.0 + 7.6 * x * x) * row64;
         if (issue > t_mask) t_mask = issue;
     }
     return t_pre < 0.85 * t_mask;
