@@ -439,9 +439,10 @@ int linr_last_hip_error(void);
  *                    T and takes the selection path (linr_select_bits + gather scoring) above it; 0 = 999;
  *   wide_min_batch : use the 32x32-tile kernel (int8, m = 1, rows of 64 / 128 / 256 bytes) for batches of at
  *                    least this many queries; 0 = never (the default: it does not beat the other kernels yet);
- *   no_dense       : 1 = never use the large-batch int8 kernel (rows of exactly 64 bytes, m = 1; the default for
- *                    batches of 65 queries or more), so that the older kernels can still be exercised;
- *   dense_min_batch: use that kernel from this batch size on; 0 = 65;
+ *   no_dense       : 1 = never use the large-batch kernels (int8 rows of exactly 64 bytes or bf16 rows of 256 bytes with
+ *                    m = 1: the default for batches of 65 queries or more; bf16 rows of 128 bytes with m = 8: from 24
+ *                    queries on), so that the older kernels can still be exercised;
+ *   dense_min_batch: use those kernels from this batch size on; 0 = 65 (m = 8: 24);
  *   dense_groups   : 16-query groups a wave of that kernel keeps in registers (4, 8 or 16); 0 = chosen by batch size.
  *   top_ratios     : factors of the last sweeps when they are split, one hexadecimal digit each (2, 4 or 8), the
  *                    last sweep's in the lowest digit: 0x442 = the last sweep visits 1/2 of the chunks, the one before

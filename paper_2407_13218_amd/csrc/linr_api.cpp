@@ -352,6 +352,9 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
     const bool dense_ok = dense_common && ix->dtype == LINR_I8 && ix->row_bytes == 64 && !(ix->row_scale && !ix->scale_stats);
     // the same design for bf16 rows of 256 bytes (linr_kernels_dense_bf16.hip): up to 8 groups per wave, 512 queries per stream
     const bool dense_bf16_ok = dense_common && ix->dtype == LINR_BF16 && ix->row_bytes == 256;
+    // ... and for bf16 rows of 128 bytes with eight embeddings per query: 32 queries per wave, 128 per stream
+    const bool dense_bf16_m8_ok = !other_family && !g_tuning.no_dense && m == 8 && ix->dtype == LINR_BF16 && ix->row_bytes == 128 &&
+                                  B >= (g_tuning.dense_min_batch ? g_tuning.dense_min_batch : 24u);
     uint32_t dg = 0, dsets = 1, dmax = 1024;
     if (dense_ok) {
         // up to four query sets per workgroup, each an equal run (a multiple of 64) of the batch's order; a wave keeps
@@ -378,7 +381,13 @@ static int make_plan(const linr_index* ix, uint32_t B, uint32_t m, uint32_t k, l
             const uint32_t b2 = B < dmax ? B : dmax, sets = (b2 + dg * 16 - 1) / (dg * 16);
             dsets = sets <= 1 ? 1u : sets <= 2 ? 2u : 4u;
         }
-        if (linr_dense_bf16_dispatch(0, p->ks, dg, ix->ts != nullptr, 0, nullptr, nullptr, nullptr) != hipSuccess) dg = 0;
+        if (linr_dense_bf16_dispatch(0, p->ks, dg, 1, ix->ts != nullptr, 0, nullptr, nullptr, nullptr) != hipSuccess) dg = 0;
+    } else if (dense_bf16_m8_ok) {
+        dmax = 128;
+        const uint32_t b1 = B < dmax ? B : dmax;
+        dsets = b1 <= 32 ? 1u : b1 <= 64 ? 2u : 4u;
+        dg = 16;
+        if (linr_dense_bf16_dispatch(0, p->ks, dg, 8, ix->ts != nullptr, 0, nullptr, nullptr, nullptr) != hipSuccess) dg = 0;
     }
     uint32_t Bp;
     if (dg) {

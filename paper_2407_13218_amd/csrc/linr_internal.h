@@ -216,8 +216,8 @@ int linr_bits_mfma_variant_exists(uint32_t words, uint32_t qg);
 hipError_t linr_launch_dense_order(const unsigned long long* tau, uint32_t B, uint32_t* order, hipStream_t s);
 hipError_t linr_dense_dispatch(int what, int vk, uint32_t ng, bool ts, uint32_t grid, hipStream_t s, const linr_scan_args* a,
                                int* blocks_per_cu);
-hipError_t linr_dense_bf16_dispatch(int what, uint32_t ks, uint32_t ng, bool ts, uint32_t grid, hipStream_t s, const linr_scan_args* a,
-                                    int* blocks_per_cu);      // matrix-core bit matching (plan.bits == 2)
+hipError_t linr_dense_bf16_dispatch(int what, uint32_t ks, uint32_t ng, uint32_t m, bool ts, uint32_t grid, hipStream_t s,
+                                    const linr_scan_args* a, int* blocks_per_cu);      // matrix-core bit matching (plan.bits == 2)
 // statistics of 1/row_scale of a scaled int8 index (out[3]; part: 4 * LINR_SCALE_STAT_BLOCKS floats of scratch) and the
 // per-item codes derived from them (codes: n_pad bytes)
 #define LINR_SCALE_STAT_BLOCKS 1024

@@ -2747,7 +2747,7 @@ static hipError_t plan_dispatch(const linr_plan& p, int dtype, uint32_t B, uint3
     }
     act.dyn = 0;
     if (p.dense && dtype == LINR_BF16)
-        return linr_dense_bf16_dispatch(act.what == ACT_EXISTS ? 0 : act.what == ACT_OCCUPANCY ? 1 : 2, p.ks, p.qg, ts, act.grid, act.s,
+        return linr_dense_bf16_dispatch(act.what == ACT_EXISTS ? 0 : act.what == ACT_OCCUPANCY ? 1 : 2, p.ks, p.qg, m, ts, act.grid, act.s,
                                         act.a, &act.blocks_per_cu);
     if (p.dense)
         return linr_dense_dispatch(act.what == ACT_EXISTS ? 0 : act.what == ACT_OCCUPANCY ? 1 : 2, p.vk, p.qg, ts, act.grid, act.s,

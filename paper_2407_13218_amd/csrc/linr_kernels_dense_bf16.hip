@@ -1,5 +1,6 @@
 // Scan kernel for large bf16 batches (rows of 256 bytes: d = 128, the shape of the benchmark in LiNR, arXiv 2407.13218,
-// Sec. 5.3; m = 1): the large-batch design of linr_kernels_dense.hip for a float ranking value.
+// Sec. 5.3, m = 1; and rows of 128 bytes with m = 8 embeddings per query, the multi-embedding score of Sec. 3.1.1):
+// the large-batch design of linr_kernels_dense.hip for a float ranking value.
 //
 // Same ideas, simpler arithmetic (no row scales):
 //   * queries are the ROW operand, so after the products of a group a lane holds 4 queries x ONE item;
@@ -14,17 +15,24 @@
 //   * every wave is autonomous: a private ring of steps of ONE tile (16 items: 4 KB of rows + masks), direct global ->
 //     LDS loads, a counted wait per step, hand-placed LDS reads, no workgroup barrier per step;
 //   * a wave keeps up to 8 query groups (128 queries: 128 registers of fragments + 32 of bounds); the four waves of a
-//     workgroup hold up to four query sets (512 queries per stream of the index) or walk different chunks.
+//     workgroup hold up to four query sets (512 queries per stream of the index) or walk different chunks;
+//   * m = 8: the eight embeddings of a query are the rows 4 (l / 16) .. + 3 of two neighbouring groups, so that ONE lane
+//     holds all eight values of a (query, item) pair; they share the query's bound as accumulator input, the tile's test
+//     is the same maximum, and the pair's ranking value is the maximum of the lane's eight accumulators.  A wave keeps
+//     16 groups = 32 queries, a workgroup up to 128.
 // Matrix work dominates here (32 products of 16 clocks per tile against 16 + a few vector instructions).
 #include "linr_dense.h"
 
 #define DENSEF_STEP 16                 // items per step of a wave: one tile
 
-template <int KS, int NG, bool TS>
+template <int KS, int NG, int M, bool TS>
 __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense_bf16(linr_scan_args A)
 {
-    constexpr int NQW = NG * 16;                         // query positions per wave
-    constexpr int NQT = NG / 4;                          // 64-query quarters per wave
+    static_assert(M == 1 || M == 8, "one embedding per query, or eight");
+    constexpr int NQW = NG * 16 / M;                     // query positions per wave
+    constexpr int NQT = NG / 4;                          // quarters (four groups: 64 / M queries) per wave
+    constexpr int QPQ = 64 / M;                          // queries per quarter
+    constexpr int NC = M == 8 ? NG / 2 : NG;             // accumulator inputs kept per lane (m = 8: one per pair of groups)
     constexpr int RB = KS * 64;                          // bytes per row
     constexpr int ROWS = KS * 1024;                      // bytes of a tile's rows
     constexpr int STG = ROWS + 256 + (TS ? 256 : 0);     // bytes of a ring stage: rows, masks, timestamps
@@ -45,10 +53,10 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense_bf16(linr_scan_
     const uint32_t wps = WPB / nsets;                    // waves per query set; each walks its own chunks
     const uint32_t qset = (uint32_t)wib % nsets, tlane = (uint32_t)wib / nsets;
     const uint32_t slot = blockIdx.x * wps + tlane;      // this wave's private candidate segments
-    const uint32_t per_set = ((A.B + nsets - 1) / nsets + 63u) & ~63u;
+    const uint32_t per_set = ((A.B + nsets - 1) / nsets + (uint32_t)QPQ - 1u) / (uint32_t)QPQ * (uint32_t)QPQ;
     const uint32_t pos_first = qset * per_set;           // first position of the batch's order this wave serves
     const uint32_t nq_mine = pos_first < A.B ? (A.B - pos_first < per_set ? A.B - pos_first : per_set) : 0u;
-    const int nqt = (int)((nq_mine + 63) / 64);
+    const int nqt = (int)((nq_mine + QPQ - 1) / QPQ);
     const bool has_ts = TS && A.ts != nullptr;
     uint32_t* const cnt = cnt_all[wib];
     u64* const qkey = (u64*)&scratch_all[wib][0];
@@ -80,15 +88,18 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense_bf16(linr_scan_
         }
     }
     __syncthreads();
-    // ---- query fragments (row operand): for each 64-byte K-step, lane l supplies bytes [16 (l/16), +16) of query row l%16
+    // ---- query fragments (row operand): for each 64-byte K-step, lane l supplies bytes [16 (l/16), +16) of row l%16.
+    //      m = 1: row r of group g is query position 16 g + r; m = 8: embedding 4 (g % 2) + r % 4 of position 4 (g / 2) + r / 4
     v4i q[NG][KS];
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-        const uint32_t qi = s_qi[g * 16 + col];
+        const uint32_t qpos = M == 8 ? (uint32_t)(4 * (g / 2) + col / 4) : (uint32_t)(g * 16 + col);
+        const uint32_t emb_e = M == 8 ? (uint32_t)(4 * (g % 2) + (col & 3)) : 0u;
+        const uint32_t qi = s_qi[qpos];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             v4i z = {0, 0, 0, 0};
-            if (qi < A.B) z = *(const v4i*)((const char*)A.Q + (u64)qi * RB + ks * 64 + g4 * 16);
+            if (qi < A.B) z = *(const v4i*)((const char*)A.Q + ((u64)qi * M + emb_e) * RB + ks * 64 + g4 * 16);
             q[g][ks] = z;
         }
     }
@@ -99,7 +110,7 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense_bf16(linr_scan_
         for (int ks = 0; ks < KS; ++ks) pin(q[g][ks]);
     for (uint32_t ql = lane; ql < (uint32_t)NQW; ql += 64) cnt[ql] = 0;
 
-    v4f c[NG];                                           // accumulator inputs: -(lowered bound) of the lane's four queries of each group
+    v4f c[NC];                                           // accumulator inputs: -(lowered bound) of the lane's four queries of each group
     bool any_free = false;                               // (uniform) some query of this wave has no bound yet: every tile matters
     auto load_bounds = [&]() __attribute__((always_inline)) {
         bool fr = false;
@@ -118,10 +129,18 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense_bf16(linr_scan_
         }
         any_free = wave_any(fr);
         wave_sync();
+        if constexpr (M == 8) {                          // (all eight rows of a pair of groups belong to one query per lane)
 #pragma unroll
-        for (int g = 0; g < NG; ++g) {
-            const v4f t4 = *(const v4f*)&s_low[g * 16 + 4 * g4];
-            c[g] = (v4f){-t4[0], -t4[1], -t4[2], -t4[3]};
+            for (int j = 0; j < NC; ++j) {
+                const float t = -s_low[4 * j + g4];
+                c[j] = (v4f){t, t, t, t};
+            }
+        } else {
+#pragma unroll
+            for (int g = 0; g < NC; ++g) {
+                const v4f t4 = *(const v4f*)&s_low[g * 16 + 4 * g4];
+                c[g] = (v4f){-t4[0], -t4[1], -t4[2], -t4[3]};
+            }
         }
     };
     load_bounds();
@@ -202,7 +221,7 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense_bf16(linr_scan_
         constexpr int qt = decltype(QT)::value;
         if constexpr (qt < NQT) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) R[i] = mfma_kstep<LINR_BF16>(q[4 * qt + i][0], bb[0], c[4 * qt + i]);
+            for (int i = 0; i < 4; ++i) R[i] = mfma_kstep<LINR_BF16>(q[4 * qt + i][0], bb[0], c[M == 8 ? (4 * qt + i) / 2 : 4 * qt + i]);
 #pragma unroll
             for (int ks = 1; ks < KS; ++ks)
 #pragma unroll
@@ -217,23 +236,35 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense_bf16(linr_scan_
 
     using Q0 = std::integral_constant<int, 0>; using Q1 = std::integral_constant<int, 1>;
     using Q2 = std::integral_constant<int, 2>; using Q3 = std::integral_constant<int, 3>;
-    // ---- a quarter (64 queries) of a tile that fired, its accumulators H still in registers: the lane's 16 values that
-    //      are >= 0 are marked (their sign bits, one instruction each), and the lanes that have any finish their
-    //      (query, item) pairs one per round
+    // ---- a quarter (four groups) of a tile that fired, its accumulators H still in registers: the lane's values that
+    //      are >= 0 are marked (m = 1: the sign bits of its 16 values, one instruction each; m = 8: the maxima of its two
+    //      queries' eight values), and the lanes that have any finish their (query, item) pairs one per round
     auto quarter_hot = [&](const v4f (&H)[4], int qt, uint32_t mk, uint32_t ts, u64 item) __attribute__((always_inline)) {
         {
-            uint32_t lt = 0;                             // bit a: value a (group a / 4 of the quarter, query row 4 g4 + a % 4) is negative
+            uint32_t bm;
+            float v0 = 0.0f, v1 = 0.0f;                  // m = 8: the values of the lane's two queries of this quarter
+            if constexpr (M == 8) {
+                v0 = fmaxf(fmaxf(H[0][0], H[0][1]), fmaxf(H[0][2], H[0][3]));
+                v0 = fmaxf(fmaxf(v0, H[1][0]), H[1][1]); v0 = fmaxf(fmaxf(v0, H[1][2]), H[1][3]);
+                v1 = fmaxf(fmaxf(H[2][0], H[2][1]), fmaxf(H[2][2], H[2][3]));
+                v1 = fmaxf(fmaxf(v1, H[3][0]), H[3][1]); v1 = fmaxf(fmaxf(v1, H[3][2]), H[3][3]);
+                bm = (v0 >= 0.0f ? 1u : 0u) | (v1 >= 0.0f ? 2u : 0u);
+                if (any_free) bm = 3u;
+            } else {
+                uint32_t lt = 0;                         // bit a: value a (group a / 4 of the quarter, query row 4 g4 + a % 4) is negative
 #pragma unroll
-            for (int a = 15; a >= 0; --a)
-                lt = __builtin_amdgcn_alignbit(lt, (uint32_t)__float_as_int(H[a >> 2][a & 3]), 31);      // (lt << 1) | sign
-            uint32_t bm = ~lt & 0xFFFFu;
-            if (any_free) bm = 0xFFFFu;                  // queries without a bound take every item: all pairs are looked at
+                for (int a = 15; a >= 0; --a)
+                    lt = __builtin_amdgcn_alignbit(lt, (uint32_t)__float_as_int(H[a >> 2][a & 3]), 31);  // (lt << 1) | sign
+                bm = ~lt & 0xFFFFu;
+                if (any_free) bm = 0xFFFFu;              // queries without a bound take every item: all pairs are looked at
+            }
             if (item >= A.n) bm = 0u;                    // (items past the end of the index repeat the last one)
             while (wave_any(bm != 0u)) {
                 const bool act = bm != 0u;
                 const uint32_t a = (uint32_t)(__ffs((int)bm) - 1) & 15u;
                 bm &= bm - 1u;
-                const uint32_t ql = (uint32_t)(qt * 4) * 16u + (a >> 2) * 16u + 4u * (uint32_t)g4 + (a & 3u);
+                const uint32_t ql = M == 8 ? (uint32_t)(qt * 8) + (a & 1u) * 4u + (uint32_t)g4
+                                           : (uint32_t)(qt * 4) * 16u + (a >> 2) * 16u + 4u * (uint32_t)g4 + (a & 3u);
                 uint32_t fa, fn, flag, t0 = 0u, t1 = 0xFFFFFFFFu;
                 float low, thr;
                 if constexpr (TS)
@@ -257,8 +288,8 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense_bf16(linr_scan_
                 const bool a0 = (a & 1u) != 0u, a1 = (a & 2u) != 0u, a2 = (a & 4u) != 0u, a3 = (a & 8u) != 0u;
                 // (the group first, then the row; every select written out and pinned -- as an indexed array the
                 // compiler would place the accumulators in scratch memory, whose loads wait for the whole ring)
-                int t0v, t1v, t2v, t3v;
-                {
+                int t0v = 0, t1v = 0, t2v = 0, t3v = 0;
+                if constexpr (M == 1) {
                     int lo0 = __float_as_int(a2 ? H[1][0] : H[0][0]), hi0 = __float_as_int(a2 ? H[3][0] : H[2][0]);
                     pin(lo0); pin(hi0);
                     t0v = a3 ? hi0 : lo0; pin(t0v);
@@ -272,7 +303,7 @@ __global__ void __launch_bounds__(64 * WPB, 2) scan_kernel_dense_bf16(linr_scan_
                     pin(lo3); pin(hi3);
                     t3v = a3 ? hi3 : lo3; pin(t3v);
                 }
-                const float hv = __int_as_float(a1 ? (a0 ? t3v : t2v) : (a0 ? t1v : t0v));
+                const float hv = M == 8 ? (a0 ? v1 : v0) : __int_as_float(a1 ? (a0 ? t3v : t2v) : (a0 ? t1v : t0v));
                 const float sv = hv + low;               // ranking value: the accumulator plus what it started from
                 ok = ok && sv >= thr;
                 if (ok && flag) ok = filter_pass(A.filters[s_qi[ql]], mk, has_ts, ts);
@@ -397,15 +428,15 @@ static hipError_t densef_act(K kern, int what, uint32_t grid, hipStream_t s, con
     return hipGetLastError();
 }
 
-#define DENSEF_CASE(KS_, NG_)                                                                                      \
-    if (ks == KS_ && ng == NG_)                                                                                    \
-        return ts ? densef_act(scan_kernel_dense_bf16<KS_, NG_, true>, what, grid, s, a, blocks_per_cu)            \
-                  : densef_act(scan_kernel_dense_bf16<KS_, NG_, false>, what, grid, s, a, blocks_per_cu);
+#define DENSEF_CASE(KS_, NG_, M_)                                                                                  \
+    if (ks == KS_ && ng == NG_ && m == M_)                                                                         \
+        return ts ? densef_act(scan_kernel_dense_bf16<KS_, NG_, M_, true>, what, grid, s, a, blocks_per_cu)        \
+                  : densef_act(scan_kernel_dense_bf16<KS_, NG_, M_, false>, what, grid, s, a, blocks_per_cu);
 
 // what: 0 = does the variant exist, 1 = workgroups per compute unit, 2 = launch
-hipError_t linr_dense_bf16_dispatch(int what, uint32_t ks, uint32_t ng, bool ts, uint32_t grid, hipStream_t s, const linr_scan_args* a,
-                                    int* blocks_per_cu)
+hipError_t linr_dense_bf16_dispatch(int what, uint32_t ks, uint32_t ng, uint32_t m, bool ts, uint32_t grid, hipStream_t s,
+                                    const linr_scan_args* a, int* blocks_per_cu)
 {
-    DENSEF_CASE(4, 8) DENSEF_CASE(4, 4)
+    DENSEF_CASE(4, 8, 1) DENSEF_CASE(4, 4, 1) DENSEF_CASE(2, 16, 8)
     return hipErrorInvalidDeviceFunction;
 }
