@@ -2126,9 +2126,40 @@ __device__ __forceinline__ const u64* piece_ptr(const linr_merge_args& A, uint32
     return A.flat + (u64)b * A.flat_cap + (u64)(p - 1) * (A.flat_cap / LINR_FLAT_REGIONS);
 }
 
+// f(key, j) for keys j = first, first + step, ... < c of src, U loads in flight at a time (a merge workgroup is
+// alone on its compute unit and waits for every load it depends on: the latency of a walk is what its time is)
+template <int U, typename F>
+__device__ __forceinline__ void walk_keys(const u64* src, uint32_t c, uint32_t first, uint32_t step, F f)
+{
+    for (uint32_t j0 = first; j0 < c; j0 += step * U) {
+        u64 kk[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t j = j0 + (uint32_t)u * step;
+            kk[u] = j < c ? src[j] : 0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t j = j0 + (uint32_t)u * step;
+            if (j < c) f(kk[u], j);
+        }
+    }
+}
+
+// The keys of the carry and of the flat regions of query b, f(key, piece, j) once each: the carried keys by all 1024
+// lanes, region r by the 16 lanes 16 r .. 16 r + 15 (a region holds at most flat_cap / 64 keys, usually far fewer).
+template <typename LDS, typename F>
+__device__ __forceinline__ void walk_flat(const linr_merge_args& A, const LDS& S, uint32_t b, uint32_t tid, F f)
+{
+    walk_keys<4>(piece_ptr(A, b, 0), S.ppre[1] - S.ppre[0], tid, MT, [&](u64 key, uint32_t j) { f(key, 0u, j); });
+    static_assert(MT / 16 == LINR_FLAT_REGIONS, "sixteen lanes per region");
+    const uint32_t p = 1u + (tid >> 4);
+    walk_keys<8>(piece_ptr(A, b, p), S.ppre[p + 1] - S.ppre[p], tid & 15u, 16u, [&](u64 key, uint32_t j) { f(key, p, j); });
+}
+
 // Calls f(key) once for every candidate of the query, by the whole workgroup.  From LDS when they were
-// staged there; else wave w walks pieces w, w + 16, ... with consecutive lanes on consecutive keys; the
-// per-slot segments (spilled case only) are located through the prefix array.
+// staged there; else from the carry and the flat regions; the per-slot segments (spilled case only) are
+// located through the prefix array.
 template <typename LDS, typename F>
 __device__ __forceinline__ void for_each_candidate(const linr_merge_args& A, const LDS& S, int mode, uint32_t m_flat,
                                                    uint32_t Mtot, uint32_t b, uint32_t tid, F f)
@@ -2138,11 +2169,7 @@ __device__ __forceinline__ void for_each_candidate(const linr_merge_args& A, con
         return;
     }
     const uint32_t wave = tid >> 6, lane = tid & 63;
-    for (uint32_t p = wave; p < NPIECE; p += MT / 64) {
-        const uint32_t c = S.ppre[p + 1] - S.ppre[p];
-        const u64* src = piece_ptr(A, b, p);
-        for (uint32_t j = lane; j < c; j += 64) f(src[j]);
-    }
+    walk_flat(A, S, b, tid, [&](u64 key, uint32_t, uint32_t) { f(key); });
     if (mode == MERGE_FROM_ALL) {                      // wave w walks the segments of slots w, w + 16, ...
         const uint32_t* cnt = A.cnt + (u64)b * A.nslots;
         for (uint32_t sl = wave; sl < A.nslots; sl += MT / 64) {
@@ -2154,16 +2181,15 @@ __device__ __forceinline__ void for_each_candidate(const linr_merge_args& A, con
     }
 }
 
-// int32 dot product of two int8 rows (16-byte aligned, d a multiple of 16), 16 bytes per load
+// int32 dot product of two int8 rows (16-byte aligned, d a multiple of 16), 16 bytes per load, four bytes per
+// instruction (v_dot4_i32_i8: exact, like the matrix instruction's integer accumulation)
 __device__ __forceinline__ int dot_i8_row(const int8_t* q, const int8_t* x, uint32_t d)
 {
     int s = 0;
     for (uint32_t j = 0; j < d; j += 16) {
         const v4i a = *(const v4i*)(q + j), b = *(const v4i*)(x + j);
 #pragma unroll
-        for (int w = 0; w < 4; ++w)
-#pragma unroll
-            for (int sh = 24; sh >= 0; sh -= 8) s += ((a[w] << sh) >> 24) * ((b[w] << sh) >> 24);
+        for (int w = 0; w < 4; ++w) s = __builtin_amdgcn_sdot4(a[w], b[w], s, false);
     }
     return s;
 }
@@ -2229,13 +2255,8 @@ __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
         __syncthreads();
         Mtot += S.u.pre[ns];
     } else if (m_flat <= MergeLdsT<KMAX>::LDS_KEYS) {
-        // stage everything in LDS: wave w copies pieces w, w + 16, ...
-        const uint32_t wave = tid >> 6, lane = tid & 63;
-        for (uint32_t p = wave; p < NPIECE; p += MT / 64) {
-            const uint32_t o = S.ppre[p], c = S.ppre[p + 1] - o;
-            const u64* src = piece_ptr(A, b, p);
-            for (uint32_t j = lane; j < c; j += 64) S.u.keys[o + j] = src[j];
-        }
+        // stage everything in LDS
+        walk_flat(A, S, b, tid, [&](u64 key, uint32_t p, uint32_t j) { S.u.keys[S.ppre[p] + j] = key; });
         mode = MERGE_FROM_LDS;
         __syncthreads();
     } else {
@@ -2298,23 +2319,70 @@ __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
             A.gcnt[ci] = 0; A.fvalid[ci] = 0xFFFFFFFFu;
         }
     } else {
-        // sort them, write the outputs
-        uint32_t P = 1;
+        // sort them (descending), write the outputs.  Bitonic network over P = 1024 E keys, key e * 1024 + tid in register
+        // e of lane tid: partners less than 64 apart are exchanged by lane shuffles, those 1024 or more apart sit in
+        // the same lane, and only the strides 64 .. 512 go through LDS and the workgroup barrier.
+        constexpr int EMAX = KMAX / MT;
+        uint32_t P = MT;
         while (P < nwin) P <<= 1;
-        for (uint32_t j = nwin + tid; j < P; j += MT) S.win[j] = 0ull;
+        const int E = (int)(P / MT);
+        u64 key_e[EMAX];
+#pragma unroll
+        for (int e = 0; e < EMAX; ++e) {
+            const uint32_t idx = (uint32_t)e * MT + tid;
+            key_e[e] = (e < E && idx < nwin) ? S.win[idx] : 0ull;
+        }
         __syncthreads();
         for (uint32_t size = 2; size <= P; size <<= 1)
             for (uint32_t str = size >> 1; str > 0; str >>= 1) {
-                for (uint32_t j = tid; j < P; j += MT) {
-                    uint32_t o = j ^ str;
-                    if (o > j) {
-                        u64 x = S.win[j], y = S.win[o];
-                        bool desc = (j & size) == 0;
-                        if (desc ? (x < y) : (x > y)) { S.win[j] = y; S.win[o] = x; }
+                if (str >= MT) {                           // partner in the same lane
+                    const int se = (int)(str / MT);
+#pragma unroll
+                    for (int e = 0; e < EMAX; ++e) {
+                        if (e < E && (e & se) == 0) {
+                            const uint32_t idx = (uint32_t)e * MT + tid;
+                            const bool desc = (idx & size) == 0;
+#pragma unroll
+                            for (int e2 = 0; e2 < EMAX; ++e2)
+                                if (e2 == (e | se)) {
+                                    const u64 x = key_e[e], y = key_e[e2];
+                                    if (desc ? (x < y) : (x > y)) { key_e[e] = y; key_e[e2] = x; }
+                                }
+                        }
                     }
+                } else if (str >= 64) {                    // through LDS
+#pragma unroll
+                    for (int e = 0; e < EMAX; ++e)
+                        if (e < E) S.win[(uint32_t)e * MT + tid] = key_e[e];
+                    __syncthreads();
+#pragma unroll
+                    for (int e = 0; e < EMAX; ++e)
+                        if (e < E) {
+                            const uint32_t idx = (uint32_t)e * MT + tid;
+                            const u64 y = S.win[idx ^ str];
+                            const bool keep_max = ((idx & str) == 0) == ((idx & size) == 0);
+                            const u64 x = key_e[e];
+                            key_e[e] = keep_max ? (x > y ? x : y) : (x < y ? x : y);
+                        }
+                    __syncthreads();
+                } else {                                   // inside the wave
+#pragma unroll
+                    for (int e = 0; e < EMAX; ++e)
+                        if (e < E) {
+                            const uint32_t idx = (uint32_t)e * MT + tid;
+                            const u64 x = key_e[e];
+                            const uint32_t ylo = (uint32_t)__shfl_xor((int)(uint32_t)x, (int)str);
+                            const uint32_t yhi = (uint32_t)__shfl_xor((int)(uint32_t)(x >> 32), (int)str);
+                            const u64 y = ((u64)yhi << 32) | ylo;
+                            const bool keep_max = ((idx & str) == 0) == ((idx & size) == 0);
+                            key_e[e] = keep_max ? (x > y ? x : y) : (x < y ? x : y);
+                        }
                 }
-                __syncthreads();
             }
+#pragma unroll
+        for (int e = 0; e < EMAX; ++e)
+            if (e < E) S.win[(uint32_t)e * MT + tid] = key_e[e];
+        __syncthreads();
         for (uint32_t j = tid; j < A.k; j += MT) {
             u64 o = (u64)b * A.k + j;
             if (j < nwin) {
