@@ -447,13 +447,16 @@ int linr_last_hip_error(void);
  *   top_ratios     : factors of the last sweeps when they are split, one hexadecimal digit each (2, 4 or 8), the
  *                    last sweep's in the lowest digit: 0x442 = the last sweep visits 1/2 of the chunks, the one before
  *                    3/8, the one before that 3/32; 0 = chosen by batch size.
+ *   prefilter_table_min: the explicit pre-filtering searches evaluate the all / none clauses of a group of queries by
+ *                    table look-up (one AND of four entries per item, whatever the number of queries) from this many
+ *                    queries per group on, query by query below; 0 = 6, 33 or more = never.
  * The settings are process-wide and read by every search while it plans its launches: change them only while no
  * other thread is inside a call of this library.
  */
 typedef struct {
     uint32_t sample_ratio, min_sample, blocks_per_cu, max_levels, force_generic, max_qg, no_coop, coop_min_groups;
     uint32_t no_top_split, prefilter_phases, wide_min_batch, two_stage_rank_max;
-    uint32_t no_dense, dense_min_batch, dense_groups, top_ratios;
+    uint32_t no_dense, dense_min_batch, dense_groups, top_ratios, prefilter_table_min;
 } linr_tuning;
 int linr_set_tuning(const linr_tuning*);
 

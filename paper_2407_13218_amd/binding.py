@@ -56,7 +56,8 @@ class Tuning(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in ("sample_ratio", "min_sample", "blocks_per_cu", "max_levels",
                                           "force_generic", "max_qg", "no_coop", "coop_min_groups",
                                           "no_top_split", "prefilter_phases", "wide_min_batch", "two_stage_rank_max",
-                                          "no_dense", "dense_min_batch", "dense_groups", "top_ratios")]
+                                          "no_dense", "dense_min_batch", "dense_groups", "top_ratios",
+                                          "prefilter_table_min")]
 
 
 def lib_path() -> str:

@@ -751,7 +751,8 @@ static double filter_pass_estimate(const float* freq, const linr_filter& f)
 // Modelled cost of the two strategies, in milliseconds per 1e9 items (both grow in proportion to the index; only
 // their ratio matters).  The constants are fits to searches timed on an MI355X over a 1e9 x 64-byte int8 index with
 // per-row scales, k = 1000, B = 1 ... 1024, pass rates 0.1 % ... 50 %:
-//   pre-filtering, per group of Bg <= 32 queries: one pass over the mask column, 0.72 + 0.10 Bg, plus per feasible
+//   pre-filtering, per group of Bg <= 32 queries: one pass over the mask column, 0.72 + 0.10 Bg with the clauses tested
+//     query by query, 1.2 + 0.01 Bg with the byte table (the default from 6 queries on), plus per feasible
 //     (item, query) pair 15 + 27 / Bg picoseconds per 64 bytes of row (gathered rows are shared by the group's queries);
 //   masking, up to 64 queries: bound by HBM, (row bytes + 8) / 6.3 TB/s whatever the pass rate;
 //   masking, larger batches (bound by instruction issue): per 256 queries 23 + 7.6 (log10(0.5 / pass rate))^2 on
@@ -766,7 +767,8 @@ static int plan_prefers_prefilter(const linr_index* ix, uint32_t B, uint32_t m, 
         const uint32_t Bg = (B - b0) < 32 ? (B - b0) : 32;
         double pg = 0.0;
         for (uint32_t b = 0; b < Bg; ++b) pg += pass[b0 + b];
-        t_pre += 0.72 + 0.10 * Bg + pg * 1.0e9 * (15.0 + 27.0 / Bg) * 1.0e-9 * row64;
+        const uint32_t table_min = g_tuning.prefilter_table_min ? g_tuning.prefilter_table_min : LINR_PREFILTER_TABLE_MIN;
+        t_pre += (Bg >= table_min ? 1.2 + 0.01 * Bg : 0.72 + 0.10 * Bg) + pg * 1.0e9 * (15.0 + 27.0 / Bg) * 1.0e-9 * row64;
         sum_p += pg;
     }
     if (est_pairs) *est_pairs = sum_p * (double)ix->n;
@@ -1498,6 +1500,7 @@ static int prefilter_group(const linr_index& v, const uint32_t* words, const lin
     pa.seg = (unsigned long long*)(ws + pp.off_seg); pa.nslots = pp.nslots; pa.cap = pp.cap; pa.B = Bg;
     pa.vcnt = vcnt; pa.gcnt = gcnt; pa.fvalid = fvalid; pa.cnt = cnt;
     pa.cand = cand; pa.cand_counts = cand_counts; pa.cand_T = cand_T;
+    pa.table_min = g_tuning.prefilter_table_min ? g_tuning.prefilter_table_min : LINR_PREFILTER_TABLE_MIN;
     linr_merge_args ma;
     memset(&ma, 0, sizeof(ma));
     ma.tau = tau; ma.cnt = cnt; ma.seg = pa.seg; ma.nslots = pp.nslots; ma.cap = pp.cap; ma.B = Bg; ma.k = k;

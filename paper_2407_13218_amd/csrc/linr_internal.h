@@ -160,6 +160,7 @@ uint32_t linr_clause_entries_bytes(void);
 hipError_t linr_launch_bit_filters(linr_filter* filters, uint32_t nq, hipStream_t s);
 // explicit pre-filtering (Sec. 3.1.2): score only the items whose feasibility word has a bit set, append their keys
 // to the query's flat candidate array (first flat_cap keys) and, beyond that, to the per-slot segments
+#define LINR_PREFILTER_TABLE_MIN 6     // queries per group from which the clause table beats the query-by-query test (measured at 1e9 items)
 struct linr_prefilter_args {
     const uint32_t* words; uint64_t n; uint32_t nq;   // words == nullptr: feasibility from the filters below instead
     const uint32_t* mask; const uint32_t* ts; const linr_filter* filters; uint32_t dead_bit;
@@ -176,6 +177,7 @@ struct linr_prefilter_args {
     // cand_counts [nq] how many of each row are valid
     const uint32_t* cand; const unsigned long long* cand_counts; uint64_t cand_T;
     uint32_t vec16;             // (set by the launcher) the word / mask / timestamp columns are 16-byte aligned
+    uint32_t table_min;         // bitmask filters are looked up byte by byte in a table from this many queries on (0: never)
 };
 hipError_t linr_launch_prefilter(const linr_prefilter_args& a, hipStream_t s);   // one phase: zero, score, counts
 // out_counts[b] = 0xFFFFFFFF where vcnt[b] > capacity (run behind the merge)

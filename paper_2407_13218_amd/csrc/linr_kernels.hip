@@ -1583,6 +1583,23 @@ __global__ void __launch_bounds__(256, 4) prefilter_score_kernel(linr_prefilter_
     }
     if (lane < 32) bound[lane] = (A.tau && (uint32_t)lane < A.nq) ? A.tau[lane] : 0ull;     // the phase's bounds do not move
     __syncthreads();
+    // Many queries: the all / none clauses of ALL of them at once.  (mask & care) == must holds iff it holds byte by byte,
+    // so table[p][v] keeps, for byte p of a mask having the value v, the queries whose clauses on that byte are met: an
+    // item's feasibility word is the AND of four table entries, whatever the number of queries (three vector
+    // instructions per item and QUERY otherwise).  Timestamp windows and any-of groups are checked afterwards, only
+    // for the queries that are still feasible somewhere in the run.
+    __shared__ uint32_t table[4][256];
+    const bool use_table = from_filters && A.table_min != 0u && A.nq >= A.table_min;
+    if (use_table) {
+        for (uint32_t e = threadIdx.x; e < 1024u; e += blockDim.x) {
+            const uint32_t p8 = 8u * (e >> 8), v = e & 255u;
+            uint32_t bits = 0u;
+            for (uint32_t b = 0; b < 32u; ++b)
+                if ((v & ((f_care[b] >> p8) & 255u)) == ((f_must[b] >> p8) & 255u)) bits |= 1u << b;
+            table[e >> 8][v] = bits;
+        }
+        __syncthreads();
+    }
 
     // Scores the `qn` queued pairs (4, 8 or 16 lanes per pair, by the length of a row: each reads 16 bytes of every
     // stretch, two to four exchanges for the sum; all loads of the loop are independent), drops keys below the query's
@@ -1766,15 +1783,35 @@ __global__ void __launch_bounds__(256, 4) prefilter_score_kernel(linr_prefilter_
         } else {
             // query by query (its filter constants are uniform) over the eight items, last query first: each verdict is
             // shifted into the word from below
+            if (use_table) {
 #pragma unroll
-            for (int r = 0; r < R; ++r) w[r] = 0u;
-            for (uint32_t b = A.nq; b-- > 0;) {
-                const uint32_t care = f_care[b], must = f_must[b], t0 = has_ts ? f_t0[b] : 0u, span = has_ts ? f_span[b] : 0u;
+                for (int r = 0; r < R; ++r)
+                    w[r] = table[0][cur_a[r] & 255u] & table[1][(cur_a[r] >> 8) & 255u] & table[2][(cur_a[r] >> 16) & 255u] &
+                           table[3][cur_a[r] >> 24];
+                if (has_ts) {                              // windows: only the queries some item of the run still passes for
+                    uint32_t live = 0u;
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    bool ok = (cur_a[r] & care) == must;
-                    if (has_ts) ok = ok & (cur_t[r] - t0 <= span);           // t0 <= ts <= t1 (t0 <= t1 here)
-                    w[r] = shift_in(w[r], wave_ballot(ok));
+                    for (int r = 0; r < R; ++r) live |= w[r];
+#pragma unroll
+                    for (int o = 32; o > 0; o >>= 1) live |= (uint32_t)__shfl_xor((int)live, o);
+                    for (uint32_t cx = (uint32_t)__builtin_amdgcn_readfirstlane((int)live); cx != 0u; cx &= cx - 1u) {
+                        const uint32_t b = (uint32_t)__builtin_ctz(cx), t0 = f_t0[b], span = f_span[b];
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+                            if (cur_t[r] - t0 > span) w[r] &= ~(1u << b);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < R; ++r) w[r] = 0u;
+                for (uint32_t b = A.nq; b-- > 0;) {
+                    const uint32_t care = f_care[b], must = f_must[b], t0 = has_ts ? f_t0[b] : 0u, span = has_ts ? f_span[b] : 0u;
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        bool ok = (cur_a[r] & care) == must;
+                        if (has_ts) ok = ok & (cur_t[r] - t0 <= span);       // t0 <= ts <= t1 (t0 <= t1 here)
+                        w[r] = shift_in(w[r], wave_ballot(ok));
+                    }
                 }
             }
             for (uint32_t cx = f_any; cx != 0u; cx &= cx - 1u) {

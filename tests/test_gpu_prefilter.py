@@ -42,6 +42,24 @@ def test_phase_plans(oracle_mod, phases, n, B, k):
     assert_exact(gpu, run_oracle(oracle_mod, w, k), f"pre-filtering, {phases} phases, n={n} B={B} k={k}")
 
 
+@pytest.mark.parametrize("table_min", [1, 64])
+@pytest.mark.parametrize("n,B,k,with_ts", [(200_003, 1, 100, True), (150_000, 7, 300, False), (90_001, 32, 1000, True),
+                                           (60_000, 45, 64, False), (511, 33, 20, True)])
+def test_clause_table_and_query_loop(oracle_mod, table_min, n, B, k, with_ts):
+    """the all / none clauses of a group looked up in the byte table (forced from one query on) and tested query by query
+    (table switched off): mixed filters incl. any-of groups, impossible ones and pass-all, timestamp windows, a ragged
+    last group"""
+    import paper_2407_13218_amd as L
+    say(f"pre-filtering table_min={table_min} n={n} B={B} k={k} ts={with_ts}")
+    w = rand_int8_workload(70 + B, n, 64, B, scaled=True, with_ts=with_ts)
+    L.set_tuning(prefilter_table_min=table_min)
+    try:
+        gpu = run_gpu(to_cuda(w), k=k, prefilter=True)
+    finally:
+        L.set_tuning()
+    assert_exact(gpu, run_oracle(oracle_mod, w, k), f"pre-filtering table_min={table_min} n={n} B={B}")
+
+
 def test_borrowed_columns_must_be_aligned():
     """columns used in place (LINR_SRC_DEVICE_BORROW) have to be 16-byte aligned: the loader says so"""
     import torch
