@@ -12,7 +12,7 @@
 #include <vector>
 
 static thread_local int g_last_hip = 0;
-static linr_tuning g_tuning = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+static linr_tuning g_tuning = {};                       // all zero: library defaults
 
 #define HIP_TRY(expr)                                   \
     do {                                                \

@@ -2199,7 +2199,7 @@ __device__ __forceinline__ void walk_flat(const linr_merge_args& A, const LDS& S
 // located through the prefix array.
 template <typename LDS, typename F>
 __device__ __forceinline__ void for_each_candidate(const linr_merge_args& A, const LDS& S, int mode, uint32_t m_flat,
-                                                   uint32_t Mtot, uint32_t b, uint32_t tid, F f)
+                                                   uint32_t b, uint32_t tid, F f)
 {
     if (mode == MERGE_FROM_LDS) {
         for (uint32_t i = tid; i < m_flat; i += MT) f(S.u.keys[i]);
@@ -2311,7 +2311,7 @@ __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
             if (tid < 256) S.hist[tid] = 0;
             __syncthreads();
             const u64 want = shift == 56 ? 0ull : (prefix >> (shift + 8));
-            for_each_candidate(A, S, mode, m_flat, Mtot, b, tid, [&](u64 key) {
+            for_each_candidate(A, S, mode, m_flat, b, tid, [&](u64 key) {
                 const bool match = (shift == 56) || ((key >> (shift + 8)) == want);
                 if (match) atomicAdd(&S.hist[(uint32_t)(key >> shift) & 255u], 1u);
             });
@@ -2338,7 +2338,7 @@ __global__ void __launch_bounds__(MT) merge_kernel(linr_merge_args A)
     // 3. gather the winners (all candidates when there are fewer than k)
     if (tid == 0) S.nwin = 0;
     __syncthreads();
-    for_each_candidate(A, S, mode, m_flat, Mtot, b, tid, [&](u64 key) {
+    for_each_candidate(A, S, mode, m_flat, b, tid, [&](u64 key) {
         if (key >= kth) {
             uint32_t p = atomicAdd(&S.nwin, 1u);
             if (p < (uint32_t)KMAX) S.win[p] = key;
