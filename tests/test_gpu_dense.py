@@ -56,15 +56,18 @@ def test_dense_degenerate_plans(oracle_mod, tuning):
     assert_exact(gpu, run_oracle(oracle_mod, w, 300, nthreads=THREADS), f"dense tuning {tuning}")
 
 
-@pytest.mark.parametrize("code", [0, 0x442, 0x22222222, 0x84, 0x248])
-def test_dense_split_schedules_of_the_last_sweeps(oracle_mod, code):
+def test_dense_split_schedules_of_the_last_sweeps(oracle_mod):
     """from 65 536 chunks on the last sweeps are split by their own factors (halving by default for this kernel): the
-    default and forced factor lists, on the smallest index that has the split, with a ragged end"""
+    default and forced factor lists, on the smallest index that has the split, with a ragged end (one workload, one
+    oracle run, every list against it)"""
     n, B, k = 65_536 * 128 + 77, 72, 200
-    say(f"dense split schedule {code:#x} n={n} B={B}")
     w = rand_int8_workload(520, n, 64, B, scaled=True)
-    gpu = run_gpu(to_cuda(w), k=k, tuning=dict(top_ratios=code) if code else None)
-    assert_exact(gpu, run_oracle(oracle_mod, w, k, nthreads=THREADS), f"dense split schedule {code:#x}")
+    want = run_oracle(oracle_mod, w, k, nthreads=THREADS)
+    dev = to_cuda(w)
+    for code in (0, 0x442, 0x22222222, 0x84, 0x248):
+        say(f"dense split schedule {code:#x} n={n} B={B}")
+        gpu = run_gpu(dev, k=k, tuning=dict(top_ratios=code) if code else None)
+        assert_exact(gpu, want, f"dense split schedule {code:#x}")
 
 
 def test_dense_adversarial_order_forces_compaction(oracle_mod):
