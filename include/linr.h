@@ -450,13 +450,15 @@ int linr_last_hip_error(void);
  *   prefilter_table_min: the explicit pre-filtering searches evaluate the all / none clauses of a group of queries by
  *                    table look-up (one AND of four entries per item, whatever the number of queries) from this many
  *                    queries per group on, query by query below; 0 = 6, 33 or more = never.
+ *   select_seg_items: items per segment of the large-K selection (4096, 16384 or 65536; one workgroup counts a segment
+ *                    for up to eight queries); 0 = chosen from the capacity, the batch and the code length.
  * The settings are process-wide and read by every search while it plans its launches: change them only while no
  * other thread is inside a call of this library.
  */
 typedef struct {
     uint32_t sample_ratio, min_sample, blocks_per_cu, max_levels, force_generic, max_qg, no_coop, coop_min_groups;
     uint32_t no_top_split, prefilter_phases, wide_min_batch, two_stage_rank_max;
-    uint32_t no_dense, dense_min_batch, dense_groups, top_ratios, prefilter_table_min;
+    uint32_t no_dense, dense_min_batch, dense_groups, top_ratios, prefilter_table_min, select_seg_items;
 } linr_tuning;
 int linr_set_tuning(const linr_tuning*);
 

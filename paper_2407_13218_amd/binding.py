@@ -57,7 +57,7 @@ class Tuning(C.Structure):
                                           "force_generic", "max_qg", "no_coop", "coop_min_groups",
                                           "no_top_split", "prefilter_phases", "wide_min_batch", "two_stage_rank_max",
                                           "no_dense", "dense_min_batch", "dense_groups", "top_ratios",
-                                          "prefilter_table_min")]
+                                          "prefilter_table_min", "select_seg_items")]
 
 
 def lib_path() -> str:

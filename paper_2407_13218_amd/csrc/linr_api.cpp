@@ -1032,7 +1032,13 @@ static void select_plan(const linr_index& v, uint32_t B, select_layout* L)
     // large segments when there are enough of them to fill the chip several times over, else smaller ones
     // (decided by the capacity, so that the workspace size does not depend on the number of items resident right now)
     const uint64_t groups = (B + 7) / 8;                      // (the counting pass serves eight queries per workgroup)
-    L->seg_items = (v.capacity / 65536) * groups >= 8192 ? 65536u : (v.capacity / 16384) * groups >= 4096 ? 16384u : 4096u;
+    // (a workgroup's fixed work -- clearing and adding up its counts -- grows with the code length, so long codes take
+    // the large segments already when they fill the chip once; measured on 15.5 M codes of 128 and 512 bits, B = 16)
+    const uint32_t words = (v.k_bits + 63) / 64;
+    L->seg_items = (v.capacity / 65536) * groups >= (words >= 4 ? 256u : 8192u) ? 65536u
+                   : (v.capacity / 16384) * groups >= 1024 ? 16384u : 4096u;
+    if (g_tuning.select_seg_items == 4096 || g_tuning.select_seg_items == 16384 || g_tuning.select_seg_items == 65536)
+        L->seg_items = g_tuning.select_seg_items;
     L->n_seg = (uint32_t)((v.n + L->seg_items - 1) / L->seg_items);
     uint64_t o = 0;
     L->off_hist = o; o += align_up((uint64_t)B * LINR_SELECT_BINS * 8, 256);

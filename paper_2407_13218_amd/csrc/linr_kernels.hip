@@ -1352,6 +1352,35 @@ __global__ void __launch_bounds__(256) sign_oporp_kernel(int dtype, const void* 
     out[scatter ? (u64)scatter[row] * Wn + w : t] = word;
 }
 
+// The same codes for a FEW rows (the queries of a search): one wave per (row, word), lane jj sums bin 64 w + jj in the
+// same order and precision, the word is the ballot of the signs.  A thread per word would walk its 64 bins one after
+// the other, which for a batch of 16 queries of 512 bits is 60 us of latency in front of every search.
+__global__ void __launch_bounds__(256) sign_oporp_rows_kernel(int dtype, const void* x, u64 n, uint32_t d, const uint32_t* perm,
+                                                              const int8_t* signs, uint32_t k_bits, uint32_t reps, u64* out,
+                                                              const uint32_t* scatter)
+{
+    const uint32_t Wn = (k_bits + 63) / 64, k1 = k_bits / reps, L = d / k1;
+    const u64 t = ((u64)blockIdx.x * blockDim.x + threadIdx.x) >> 6;       // (uniform over the wave)
+    if (t >= n * Wn) return;
+    const u64 row = t / Wn;
+    const uint32_t w = (uint32_t)(t % Wn), j = w * 64 + (threadIdx.x & 63u);
+    bool on = false;
+    if (j < k_bits) {
+        const uint32_t base = (j / k1) * d + (j % k1) * L;
+        double sum = 0.0;
+        for (uint32_t q = 0; q < L; ++q) {
+            const uint32_t col = perm[base + q];
+            double v;
+            if (dtype == LINR_F32) v = (double)((const float*)x)[row * d + col];
+            else v = (double)__uint_as_float((uint32_t)((const uint16_t*)x)[row * d + col] << 16);
+            sum = sum + (signs[base + q] > 0 ? v : -v);
+        }
+        on = sum > 0.0;
+    }
+    const u64 word = wave_ballot(on);
+    if ((threadIdx.x & 63u) == 0u) out[scatter ? (u64)scatter[row] * Wn + w : t] = word;
+}
+
 // ---------------------------------------------------------------------------
 // attribute matching over clause lists (LiNR Sec. 3.1.1; 64-bit attributes as in the benchmark of Sec. 5.3)
 //   One thread per item.  The item's lists sit back to back in its row of the values matrix, their lengths in
@@ -2716,8 +2745,12 @@ hipError_t linr_launch_sign_oporp_scatter(int dtype, const void* x, uint64_t n, 
     if (reps == 0 || k_bits == 0 || k_bits % reps != 0 || d % (k_bits / reps) != 0) return hipErrorInvalidValue;
     const uint64_t threads = n * ((k_bits + 63) / 64);
     if (threads == 0) return hipSuccess;
-    hipLaunchKernelGGL(sign_oporp_kernel, dim3((uint32_t)((threads + 255) / 256)), dim3(256), 0, s, dtype, x, (u64)n, d, perm, signs,
-                       k_bits, reps, (u64*)out, scatter);
+    if (threads <= 16384)                               // few rows (queries): a wave per word
+        hipLaunchKernelGGL(sign_oporp_rows_kernel, dim3((uint32_t)((threads + 3) / 4)), dim3(256), 0, s, dtype, x, (u64)n, d, perm,
+                           signs, k_bits, reps, (u64*)out, scatter);
+    else
+        hipLaunchKernelGGL(sign_oporp_kernel, dim3((uint32_t)((threads + 255) / 256)), dim3(256), 0, s, dtype, x, (u64)n, d, perm, signs,
+                           k_bits, reps, (u64*)out, scatter);
     return hipGetLastError();
 }
 
