@@ -965,7 +965,9 @@ __device__ __forceinline__ void issue_bits(BitsRegs<W>& R, const linr_scan_args&
         u64 it = item0 + u * 64 + lane;
         it = it < last ? it : last;
 #pragma unroll
-        for (int w = 0; w < W; ++w) R.x[u][w] = __builtin_nontemporal_load(bits + it * W + w);
+        // (codes of several words: a lane's loads touch each 64-byte sector several times in a row; only an allocating
+        // load lets the first-level cache serve the repeats)
+        for (int w = 0; w < W; ++w) R.x[u][w] = W >= 2 ? bits[it * W + w] : __builtin_nontemporal_load(bits + it * W + w);
         R.mk[u] = __builtin_nontemporal_load(A.mask + it);
         R.ts[u] = has_ts ? __builtin_nontemporal_load(A.ts + it) : 0u;
     }
