@@ -289,8 +289,10 @@ __global__ void __launch_bounds__(256) select_write_kernel(linr_select_args A)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const bool better = diff[r] < cut.t_diff, tie = diff[r] == cut.t_diff;
-            if (better || (tie && e_before < need))
-                out[g_before + (e_before < need ? e_before : need)] = (uint32_t)(i0 + r) + A.id_base;
+            // (pos < K always when the codes are what the counting pass saw; an update that lands between the two passes
+            // can break that, and must cost a wrong id at most, not a write past the output)
+            const u64 pos = g_before + (e_before < need ? e_before : need);
+            if ((better || (tie && e_before < need)) && pos < A.K) out[pos] = (uint32_t)(i0 + r) + A.id_base;
             g_before += better ? 1u : 0u; e_before += tie ? 1u : 0u;
         }
         run_gt += total & 0xFFFFu; run_eq += total >> 16;
@@ -355,7 +357,8 @@ __global__ void __launch_bounds__(256) select_write_cached_kernel(linr_select_ar
             todo &= todo - 1u;
             const uint32_t below = (1u << r) - 1u;
             const u64 g = g_before + (uint32_t)__popc(better & below), e = e_before + (uint32_t)__popc(tie & below);
-            if (((better >> r) & 1u) || e < need) out[g + (e < need ? e : need)] = (uint32_t)(i0 + r) + A.id_base;
+            const u64 pos = g + (e < need ? e : need);
+            if ((((better >> r) & 1u) || e < need) && pos < A.K) out[pos] = (uint32_t)(i0 + r) + A.id_base;   // (pos < K: see the other write pass)
         }
         run_gt += total & 0xFFFFu; run_eq += total >> 16;
     }
