@@ -704,7 +704,9 @@ static int search_impl(const linr_index* ix, const void* Q, const float* q_scale
             uint64_t items = sa.n_dense * pp.chunk_items;
             if (items > ix->n) items = ix->n;
             HIP_TRY(ev(0, LINR_STAGE_SCAN, items));
-            if (pp.dense) {                             // its first test is tightest when neighbouring queries have similar bounds
+            // (int8: the first test works from the smallest and largest bound of a group of queries, and is tightest when
+            // neighbouring queries have similar bounds; the bf16 kernel carries every query's own bound in its accumulator)
+            if (pp.dense && ix->dtype == LINR_I8) {
                 uint32_t* order = (uint32_t*)(ws + pp.off_order);
                 HIP_TRY(linr_launch_dense_order(tau, Bp, order, st));
                 sa.qorder = order;
