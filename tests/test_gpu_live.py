@@ -114,12 +114,15 @@ def test_hand_sequence_on_the_gpu(oracle_mod):
     ("bits", 64, 4000, 7000, 9, 200),
     ("bits", 192, 1500, 3000, 3, 40),
     ("i8", 64, 300, 100_000, 130, 300),       # mostly empty capacity, k close to the number of live items
+    ("bf16x8", 64, 3000, 5000, 40, 80),       # eight embeddings per query: the large-batch bf16 kernel for that shape
 ])
 def test_random_updates_match_the_model(oracle_mod, kind, d, n0, cap, B, k):
     """upserts (fresh slots, reused slots, in-place; host and device sources) and deletes on the search stream, a search
     after every step compared with the reference model"""
     import paper_2407_13218_amd as L
     rng = np.random.default_rng(n0 + d)
+    m = 8 if kind == "bf16x8" else 1
+    kind = "bf16" if kind == "bf16x8" else kind
     with_ts = kind in ("i8", "bits")
     dtype = {"f32": S.F32, "bf16": S.BF16, "i8": S.I8, "bits": S.BITS}[kind]
     emb, sc = gen_rows(rng, kind, n0, d)
@@ -133,8 +136,8 @@ def test_random_updates_match_the_model(oracle_mod, kind, d, n0, cap, B, k):
     ix = L.Index(cap, d, dtype, 0)
     ix.load(emb, mask, ts=ts, row_scale=sc)                    # host arrays: library-owned columns of `cap` slots
     ix.enable_updates()
-    Q, _ = gen_rows(rng, kind, B, d)
-    Qd = dev(Q) if kind == "bits" else dev(Q.reshape(B, 1, d))
+    Q, _ = gen_rows(rng, kind, B * m, d)
+    Qd = dev(Q) if kind == "bits" else dev(Q.reshape(B, m, d))
     qs = np.ones(B, np.float32) if kind == "i8" else None
     qsd = dev(qs)
     filt = S.make_filters(B)
@@ -151,7 +154,7 @@ def test_random_updates_match_the_model(oracle_mod, kind, d, n0, cap, B, k):
         if kind == "bits":
             ora = li.bits_search(d, Q, filt, k)
         else:
-            ora = li.search(Q.reshape(B, 1, d), filt, k, q_scale=qs, nthreads=4)
+            ora = li.search(Q.reshape(B, m, d), filt, k, q_scale=qs, nthreads=4)
         compare(kind, gpu_search(ix, kind, Qd, filt, k, qsd), ora, label)
 
     check("after load")
@@ -162,13 +165,13 @@ def test_random_updates_match_the_model(oracle_mod, kind, d, n0, cap, B, k):
             hi = min(cap, li.mark + (u if r != 4 else 3 * u))
             slots = rng.choice(hi, min(u, hi), replace=False).astype(np.uint32)
             e, s = gen_rows(rng, kind, len(slots), d)
-            m = rng.integers(0, 1 << 32, len(slots), dtype=np.uint32) & rng.integers(0, 1 << 32, len(slots), dtype=np.uint32)
+            mk = rng.integers(0, 1 << 32, len(slots), dtype=np.uint32) & rng.integers(0, 1 << 32, len(slots), dtype=np.uint32)
             t = rng.integers(0, 1000, len(slots), dtype=np.uint32) if with_ts else None
-            li.upsert(slots, e, m, ts=t, scale=s)
+            li.upsert(slots, e, mk, ts=t, scale=s)
             if step % 2 == 0:
-                ix.upsert(slots, e, m, ts=t, row_scale=s)
+                ix.upsert(slots, e, mk, ts=t, row_scale=s)
             else:
-                ix.upsert(slots, dev(e), dev(m), ts=dev(t), row_scale=dev(s))
+                ix.upsert(slots, dev(e), dev(mk), ts=dev(t), row_scale=dev(s))
             label = f"step {step}: upsert of {len(slots)} slots (mark {li.mark})"
         elif r in (2, 5):                                     # delete live and already empty slots
             cand = rng.choice(li.mark, min(li.mark, int(rng.integers(1, 600))), replace=False).astype(np.uint32)
@@ -176,7 +179,7 @@ def test_random_updates_match_the_model(oracle_mod, kind, d, n0, cap, B, k):
             ix.delete(cand)
             label = f"step {step}: delete of {len(cand)} slots"
         elif r == 3:                                          # the current best answers of query 0 disappear
-            first = li.bits_search(d, Q, filt, k)[0][0] if kind == "bits" else li.search(Q.reshape(B, 1, d), filt, k, q_scale=qs)[0][0]
+            first = li.bits_search(d, Q, filt, k)[0][0] if kind == "bits" else li.search(Q.reshape(B, m, d), filt, k, q_scale=qs)[0][0]
             victims = first[first != S.NO_ID][:10]
             if len(victims):
                 li.delete(victims); ix.delete(victims)
@@ -184,9 +187,9 @@ def test_random_updates_match_the_model(oracle_mod, kind, d, n0, cap, B, k):
         else:                                                 # one slot far above the mark: the slots between stay empty
             slot = np.array([min(cap - 1, li.mark + 1000)], np.uint32)
             e, s = gen_rows(rng, kind, 1, d)
-            m = np.array([0], np.uint32); t = np.array([500], np.uint32) if with_ts else None
-            li.upsert(slot, e, m, ts=t, scale=s)
-            ix.upsert(slot, e, m, ts=t, row_scale=s)
+            mk = np.array([0], np.uint32); t = np.array([500], np.uint32) if with_ts else None
+            li.upsert(slot, e, mk, ts=t, scale=s)
+            ix.upsert(slot, e, mk, ts=t, row_scale=s)
             label = f"step {step}: upsert far above the mark (mark {li.mark})"
         check(label)
     ix.sync_updates()
